@@ -1,0 +1,569 @@
+/*
+ * CPU oracle for farthest point sampling, minimum-distance-prediction sampling
+ * (MDPS) and ball query -- FastPoint, arXiv 2507.23480.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, single-threaded
+ * statement of what the GPU library must compute.  Nothing in the product path
+ * may include, link or call it; it shares no code, header, table or helper
+ * with the HIP sources.  Only the tests, the smoke check and the benchmark's
+ * "cpu_baseline" leg load it.
+ *
+ * Arithmetic conventions (fixed so that index results can be compared
+ * bit-for-bit):
+ *   - "distance" in Algorithm 1 / Algorithm 2 is the SQUARED Euclidean
+ *     distance in IEEE binary32, evaluated as ((dx*dx) + (dy*dy)) + (dz*dz)
+ *     with every operation rounded separately (build with -ffp-contract=off,
+ *     never -ffast-math).  Squaring keeps every comparison and argmax of the
+ *     paper's algorithms, which only ever compare distances.
+ *   - argmax and "find any available point" take the LOWEST index among
+ *     equals / candidates (the paper leaves both open: Alg. 1 line 8,
+ *     Alg. 2 line 33).
+ *   - the curve estimator works in binary64 and rounds each threshold once
+ *     to binary32.
+ *
+ * Parity pins: every function below is pinned by tests/test_oracle_*.py
+ * against brute-force restatements, closed-form cases and hand-worked examples
+ * (tests/golden/).  The one thing no test can pin to the paper is the CHOICE of
+ * estimator constants (exponent, bias, fit window): the paper fits them on data
+ * sets that are not available ("parity unpinned" for those constants only; the
+ * arithmetic that uses them is pinned by closed forms).
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define REF_MAX_SEG 16
+
+/* squared distance, the one rounding order used everywhere */
+static float ref_dist2(const float *a, const float *b)
+{
+    float dx = a[0] - b[0];
+    float dy = a[1] - b[1];
+    float dz = a[2] - b[2];
+    float t = dx * dx;
+    t = t + dy * dy;
+    t = t + dz * dz;
+    return t;
+}
+
+/* Alg. 1 lines 4-7: fold one sample into the running min-distance array */
+static void ref_fold(const float *xyz, int32_t N, int32_t s, float *dists)
+{
+    const float *c = xyz + 3 * (size_t)s;
+    for (int32_t j = 0; j < N; ++j) {
+        float d = ref_dist2(c, xyz + 3 * (size_t)j);
+        if (dists[j] > d)
+            dists[j] = d;
+    }
+}
+
+/* Alg. 1 line 8: index of the maximum, lowest index among equal maxima */
+static int32_t ref_argmax(const float *dists, int32_t N)
+{
+    int32_t best = 0;
+    for (int32_t j = 1; j < N; ++j)
+        if (dists[j] > dists[best])
+            best = j;
+    return best;
+}
+
+/*
+ * Exact farthest point sampling -- Algorithm 1 (Section 3.3).
+ *   xyz      [N][3] points
+ *   start    seed index (Alg. 1 line 1; the paper draws it at random)
+ *   out_idx  [n]  sampled indices, out_idx[0] = start
+ *   out_mdc  [n]  or NULL: out_mdc[i] = max(min_dists) at the moment sample i
+ *            was picked (the "minimum distance curve", Section 4 and Alg. 2
+ *            line 11), squared; out_mdc[0] = +inf.
+ * Returns 0, or -1 on bad arguments.
+ */
+int ref_fps_exact(const float *xyz, int32_t N, int32_t n, int32_t start,
+                  int32_t *out_idx, float *out_mdc)
+{
+    if (!xyz || !out_idx || N < 1 || n < 1 || n > N || start < 0 || start >= N)
+        return -1;
+    float *dists = (float *)malloc(sizeof(float) * (size_t)N);
+    if (!dists)
+        return -1;
+    for (int32_t j = 0; j < N; ++j)
+        dists[j] = INFINITY;
+    out_idx[0] = start;
+    if (out_mdc)
+        out_mdc[0] = INFINITY;
+    for (int32_t i = 1; i < n; ++i) {
+        ref_fold(xyz, N, out_idx[i - 1], dists);
+        int32_t best = ref_argmax(dists, N);
+        out_idx[i] = best;
+        if (out_mdc)
+            out_mdc[i] = dists[best];
+    }
+    free(dists);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ MDPS -- */
+
+typedef struct {
+    float p;              /* prefix ratio of exact FPS iterations (Sec. 4.1: 0.1)    */
+    int32_t nseg;         /* number of curve segments (Sec. 5.3 default 6), 1..16    */
+    double exponent;      /* e of the power-law curve C(x) = a / x^e (App. A.3),
+                             in SQUARED-distance space, x = sample index            */
+    float bias;           /* multiplies the predicted DISTANCE (so bias^2 on d^2)    */
+    int32_t fit_window;   /* W: number of trailing prefix points that determine a    */
+    int32_t m_min;        /* lower limit of prefix iterations                        */
+    int32_t use_override; /* nonzero: take thresholds from thr_override (tests)      */
+    float thr_override[REF_MAX_SEG];
+} ref_mdps_params;
+
+typedef struct {
+    int32_t m;                          /* prefix iterations actually run             */
+    int32_t et_index;                   /* first sample index filled by the remainder
+                                           FPS (early termination), n if none         */
+    int32_t level_start[REF_MAX_SEG];   /* sample index at which level l+1 became
+                                           current, -1 if it never did                */
+    int32_t level_exhausted[REF_MAX_SEG]; /* 1 if level l+1 ran out of available points */
+    float thr2[REF_MAX_SEG];            /* squared thresholds R_l^2 used              */
+} ref_mdps_info;
+
+/* number of prefix iterations: floor(p*n), at least m_min; the caller treats
+ * m >= n-1 as "everything is exact FPS" */
+int32_t ref_mdps_prefix_len(const ref_mdps_params *prm, int32_t n)
+{
+    int32_t m = (int32_t)floor((double)prm->p * (double)n);
+    if (m < prm->m_min)
+        m = prm->m_min;
+    return m;
+}
+
+/*
+ * Curve estimator and segment thresholds (Section 4.1 step 1, Eq. 1, with the
+ * power-function estimator of Appendix A.3; Section 4.1 step 2 and Alg. 2 line
+ * 20 for the thresholds).
+ *   mdc[0..m]  measured curve of the prefix (mdc[0] unused)
+ *   C(x) = a / x^e ; a = mean over the last W prefix points of mdc[i] * i^e
+ *   R_l^2 = curve value at the END of segment l, index b_l = floor(n*l/nseg)
+ *           clamped to [1, n-1]: the measured value if b_l <= m, else the
+ *           prediction times bias^2.  R_l serves as the lower bound of the
+ *           spacing inside segment l (Section 4.1 step 3), hence the end.
+ *   thresholds are kept >= FLT_MIN and non-increasing.
+ */
+int ref_mdps_thresholds(const float *mdc, int32_t n, int32_t m,
+                        const ref_mdps_params *prm, float *thr2)
+{
+    if (!mdc || !prm || !thr2 || prm->nseg < 1 || prm->nseg > REF_MAX_SEG || m < 1 || m >= n)
+        return -1;
+    if (prm->use_override) {
+        for (int32_t l = 0; l < prm->nseg; ++l)
+            thr2[l] = prm->thr_override[l];
+        return 0;
+    }
+    int32_t W = prm->fit_window < m ? prm->fit_window : m;
+    if (W < 1)
+        return -1;
+    double e = prm->exponent;
+    double a = 0.0;
+    for (int32_t i = m - W + 1; i <= m; ++i)
+        a += (double)mdc[i] * pow((double)i, e);
+    a = a / (double)W;
+    double bias2 = (double)prm->bias * (double)prm->bias;
+    for (int32_t l = 1; l <= prm->nseg; ++l) {
+        int64_t b = ((int64_t)n * l) / prm->nseg;
+        if (b < 1)
+            b = 1;
+        if (b > n - 1)
+            b = n - 1;
+        float r;
+        if (b <= m)
+            r = mdc[b];
+        else
+            r = (float)(bias2 * a / pow((double)b, e));
+        if (!(r >= FLT_MIN))
+            r = FLT_MIN;
+        if (l >= 2 && r > thr2[l - 2])
+            r = thr2[l - 2];
+        thr2[l - 1] = r;
+    }
+    return 0;
+}
+
+static void ref_info_init(ref_mdps_info *info, int32_t n)
+{
+    memset(info, 0, sizeof(*info));
+    info->et_index = n;
+    for (int l = 0; l < REF_MAX_SEG; ++l)
+        info->level_start[l] = -1;
+}
+
+/* quota rule of Alg. 2 line 22: the segment that sample index i belongs to */
+static int32_t ref_quota_level(int32_t i, int32_t n, int32_t nseg)
+{
+    return 1 + (int32_t)(((int64_t)i * nseg) / n);
+}
+
+/*
+ * MDPS -- Algorithm 2 (Appendix A.1), running-min-distance form.
+ *
+ * Availability of point j at level l is kept implicitly: the bitmap bit of
+ * Alg. 2 is 0 exactly when some already chosen sample lies closer than R_l,
+ * i.e. when dists[j] < R_l^2 where dists is the same running min-distance
+ * array exact FPS keeps.  ref_mdps_literal() below builds the exclusion lists
+ * and bitmaps explicitly and must return the same indices.
+ *
+ * Steps:
+ *  S1  exact FPS for i = 1..m recording mdc (Alg. 2 lines 3-11); the prefix
+ *      samples stay in the output and sampling continues at i = m+1.
+ *  S2  thresholds from the estimated curve (line 13, lines 15-22).
+ *  S3  threshold sampling (lines 24-37): level = max(level, quota level of i);
+ *      pick the lowest-index available point at the current level; if none,
+ *      move to the next level without consuming a sample slot.
+ *  S4  early termination (lines 39-53): once the last level is exhausted the
+ *      remaining samples come from exact FPS on the (already current) dists.
+ */
+int ref_mdps_sample(const float *xyz, int32_t N, int32_t n, int32_t start,
+                    const ref_mdps_params *prm, int32_t *out_idx, ref_mdps_info *info_out)
+{
+    if (!xyz || !out_idx || !prm || N < 1 || n < 1 || n > N || start < 0 || start >= N ||
+        prm->nseg < 1 || prm->nseg > REF_MAX_SEG)
+        return -1;
+    ref_mdps_info info;
+    ref_info_init(&info, n);
+    int32_t m = ref_mdps_prefix_len(prm, n);
+    if (m >= n - 1) {               /* nothing left to predict: all exact FPS */
+        info.m = n - 1;
+        info.et_index = n;
+        if (info_out)
+            *info_out = info;
+        return ref_fps_exact(xyz, N, n, start, out_idx, NULL);
+    }
+    info.m = m;
+    float *dists = (float *)malloc(sizeof(float) * (size_t)N);
+    float *mdc = (float *)malloc(sizeof(float) * (size_t)(m + 1));
+    if (!dists || !mdc) {
+        free(dists);
+        free(mdc);
+        return -1;
+    }
+    /* S1 */
+    for (int32_t j = 0; j < N; ++j)
+        dists[j] = INFINITY;
+    out_idx[0] = start;
+    mdc[0] = INFINITY;
+    for (int32_t i = 1; i <= m; ++i) {
+        ref_fold(xyz, N, out_idx[i - 1], dists);
+        int32_t best = ref_argmax(dists, N);
+        out_idx[i] = best;
+        mdc[i] = dists[best];
+    }
+    /* S2 */
+    if (ref_mdps_thresholds(mdc, n, m, prm, info.thr2) != 0) {
+        free(dists);
+        free(mdc);
+        return -1;
+    }
+    /* S3 */
+    int32_t seg = 0;
+    int32_t i = m + 1;
+    int32_t applied = m - 1;        /* last sample index folded into dists */
+    while (i < n) {
+        int32_t q = ref_quota_level(i, n, prm->nseg);
+        if (q > seg) {
+            seg = q;
+            if (seg <= prm->nseg && info.level_start[seg - 1] < 0)
+                info.level_start[seg - 1] = i;
+        }
+        if (seg > prm->nseg)
+            break;
+        while (applied < i - 1) {
+            ++applied;
+            ref_fold(xyz, N, out_idx[applied], dists);
+        }
+        float r2 = info.thr2[seg - 1];
+        int32_t pick = -1;
+        for (int32_t j = 0; j < N; ++j)
+            if (dists[j] >= r2) {
+                pick = j;
+                break;
+            }
+        if (pick < 0) {             /* level exhausted */
+            info.level_exhausted[seg - 1] = 1;
+            ++seg;
+            if (seg <= prm->nseg && info.level_start[seg - 1] < 0)
+                info.level_start[seg - 1] = i;
+            continue;
+        }
+        out_idx[i] = pick;
+        ++i;
+    }
+    /* S4 */
+    if (i < n) {
+        info.et_index = i;
+        while (applied < i - 1) {
+            ++applied;
+            ref_fold(xyz, N, out_idx[applied], dists);
+        }
+        /* remainder FPS in the order of Alg. 2 lines 48-53 (the first fold
+         * repeats sample i-1, which is already in dists: a no-op) */
+        for (; i < n; ++i) {
+            ref_fold(xyz, N, out_idx[i - 1], dists);
+            out_idx[i] = ref_argmax(dists, N);
+        }
+    }
+    if (info_out)
+        *info_out = info;
+    free(dists);
+    free(mdc);
+    return 0;
+}
+
+/* growable index list */
+typedef struct {
+    int32_t *v;
+    int32_t len, cap;
+} ref_list;
+
+static int ref_list_push(ref_list *l, int32_t x)
+{
+    if (l->len == l->cap) {
+        int32_t nc = l->cap ? 2 * l->cap : 8;
+        int32_t *nv = (int32_t *)realloc(l->v, sizeof(int32_t) * (size_t)nc);
+        if (!nv)
+            return -1;
+        l->v = nv;
+        l->cap = nc;
+    }
+    l->v[l->len++] = x;
+    return 0;
+}
+
+/*
+ * MDPS with the data structures of Algorithm 2 written out: per-level
+ * exclusion lists for every point (lines 15-22, one distance per pair), one
+ * availability bitmap per level (line 24), bitmap clearing from the lists of
+ * the most recent sample for the current and all later levels (lines 29-32),
+ * findAnyOne = lowest set bit (line 33), and the early-termination rebuild of
+ * dists from the level-1 lists restricted to sampled points (lines 41-46)
+ * followed by the remainder FPS (lines 48-53).  O(N^2) time and memory: tiny
+ * clouds only.  The bitmaps start from all ones and then have the prefix
+ * samples' lists cleared, because the prefix samples stay part of the output.
+ */
+int ref_mdps_literal(const float *xyz, int32_t N, int32_t n, int32_t start,
+                     const ref_mdps_params *prm, int32_t *out_idx, ref_mdps_info *info_out)
+{
+    if (!xyz || !out_idx || !prm || N < 1 || n < 1 || n > N || start < 0 || start >= N ||
+        prm->nseg < 1 || prm->nseg > REF_MAX_SEG)
+        return -1;
+    ref_mdps_info info;
+    ref_info_init(&info, n);
+    int32_t m = ref_mdps_prefix_len(prm, n);
+    if (m >= n - 1) {
+        info.m = n - 1;
+        if (info_out)
+            *info_out = info;
+        return ref_fps_exact(xyz, N, n, start, out_idx, NULL);
+    }
+    info.m = m;
+    const int32_t nseg = prm->nseg;
+    float *dists = (float *)malloc(sizeof(float) * (size_t)N);
+    float *mdc = (float *)malloc(sizeof(float) * (size_t)(m + 1));
+    ref_list *excl = (ref_list *)calloc((size_t)nseg * (size_t)N, sizeof(ref_list));
+    uint8_t *bitmap = (uint8_t *)malloc((size_t)nseg * (size_t)N);
+    uint8_t *is_sampled = (uint8_t *)calloc((size_t)N, 1);
+    int rc = -1;
+    if (!dists || !mdc || !excl || !bitmap || !is_sampled)
+        goto done;
+
+    /* 1-1: prefix FPS, curve capture */
+    for (int32_t j = 0; j < N; ++j)
+        dists[j] = INFINITY;
+    out_idx[0] = start;
+    mdc[0] = INFINITY;
+    for (int32_t i = 1; i <= m; ++i) {
+        ref_fold(xyz, N, out_idx[i - 1], dists);
+        int32_t best = ref_argmax(dists, N);
+        out_idx[i] = best;
+        mdc[i] = dists[best];
+    }
+    /* 1-2: estimation */
+    if (ref_mdps_thresholds(mdc, n, m, prm, info.thr2) != 0)
+        goto done;
+    /* 2: exclusion lists, one distance per pair */
+    for (int32_t a = 0; a < N; ++a)
+        for (int32_t b = 0; b < N; ++b) {
+            float d = ref_dist2(xyz + 3 * (size_t)a, xyz + 3 * (size_t)b);
+            for (int32_t l = 0; l < nseg; ++l)
+                if (d < info.thr2[l])
+                    if (ref_list_push(&excl[(size_t)l * N + a], b) != 0)
+                        goto done;
+        }
+    /* 3: bitmaps */
+    memset(bitmap, 1, (size_t)nseg * (size_t)N);
+    for (int32_t s = 0; s < m; ++s)          /* prefix samples 0..m-1 */
+        for (int32_t l = 0; l < nseg; ++l) {
+            ref_list *li = &excl[(size_t)l * N + out_idx[s]];
+            for (int32_t t = 0; t < li->len; ++t)
+                bitmap[(size_t)l * N + li->v[t]] = 0;
+        }
+    int32_t seg = 0;
+    int32_t i = m + 1;
+    while (i < n) {
+        int32_t q = ref_quota_level(i, n, nseg);
+        if (q > seg) {
+            seg = q;
+            if (seg <= nseg && info.level_start[seg - 1] < 0)
+                info.level_start[seg - 1] = i;
+        }
+        if (seg > nseg)
+            break;
+        for (int32_t l = seg - 1; l < nseg; ++l) {
+            ref_list *li = &excl[(size_t)l * N + out_idx[i - 1]];
+            for (int32_t t = 0; t < li->len; ++t)
+                bitmap[(size_t)l * N + li->v[t]] = 0;
+        }
+        int32_t pick = -1;
+        for (int32_t j = 0; j < N; ++j)
+            if (bitmap[(size_t)(seg - 1) * N + j]) {
+                pick = j;
+                break;
+            }
+        if (pick < 0) {
+            info.level_exhausted[seg - 1] = 1;
+            ++seg;
+            if (seg <= nseg && info.level_start[seg - 1] < 0)
+                info.level_start[seg - 1] = i;
+            continue;
+        }
+        out_idx[i] = pick;
+        ++i;
+    }
+    /* 4: early termination */
+    if (i < n) {
+        info.et_index = i;
+        for (int32_t s = 0; s < i; ++s)
+            is_sampled[out_idx[s]] = 1;
+        /* 4-1: dists still holds the prefix state (samples 0..m-1) */
+        for (int32_t a = 0; a < N; ++a) {
+            ref_list *li = &excl[(size_t)0 * N + a];
+            for (int32_t t = 0; t < li->len; ++t)
+                if (is_sampled[li->v[t]]) {
+                    float d = ref_dist2(xyz + 3 * (size_t)a, xyz + 3 * (size_t)li->v[t]);
+                    if (dists[a] > d)
+                        dists[a] = d;
+                }
+        }
+        /* 4-2: remainder FPS */
+        for (; i < n; ++i) {
+            ref_fold(xyz, N, out_idx[i - 1], dists);
+            out_idx[i] = ref_argmax(dists, N);
+        }
+    }
+    if (info_out)
+        *info_out = info;
+    rc = 0;
+done:
+    if (excl)
+        for (size_t t = 0; t < (size_t)nseg * (size_t)N; ++t)
+            free(excl[t].v);
+    free(excl);
+    free(bitmap);
+    free(is_sampled);
+    free(dists);
+    free(mdc);
+    return rc;
+}
+
+/* ------------------------------------------------------------ ball query -- */
+/*
+ * Ball query (Section 3.1 step 2): for each centre (a point of the same
+ * cloud, given by index) the neighbours closer than `radius`.  The paper
+ * fixes neither k, the order nor the padding; this build takes the first k
+ * hits in ascending index order, strict "<" on squared binary32 distances
+ * (the comparison of Alg. 2 line 20), and pads unused slots with the first
+ * hit.  out_cnt[q] = min(hits, k) >= 1 because a centre always hits itself.
+ *   out_idx [M][k], out_cnt [M] or NULL
+ */
+int ref_ball_query(const float *xyz, int32_t N, const int32_t *center_idx, int32_t M,
+                   float radius, int32_t k, int32_t *out_idx, int32_t *out_cnt)
+{
+    if (!xyz || !center_idx || !out_idx || N < 1 || M < 0 || k < 1 || !(radius > 0.0f) ||
+        !isfinite(radius))
+        return -1;
+    float r2 = radius * radius;
+    for (int32_t q = 0; q < M; ++q) {
+        int32_t c = center_idx[q];
+        if (c < 0 || c >= N)
+            return -1;
+        int32_t cnt = 0;
+        int32_t *row = out_idx + (size_t)q * k;
+        for (int32_t j = 0; j < N && cnt < k; ++j)
+            if (ref_dist2(xyz + 3 * (size_t)c, xyz + 3 * (size_t)j) < r2)
+                row[cnt++] = j;
+        for (int32_t t = cnt; t < k; ++t)
+            row[t] = cnt > 0 ? row[0] : -1;
+        if (out_cnt)
+            out_cnt[q] = cnt;
+    }
+    return 0;
+}
+
+/* gather of sampled coordinates (input of the next stage of a hierarchy) */
+int ref_gather_xyz(const float *xyz, int32_t N, const int32_t *idx, int32_t M, float *out_xyz)
+{
+    if (!xyz || !idx || !out_xyz)
+        return -1;
+    for (int32_t q = 0; q < M; ++q) {
+        if (idx[q] < 0 || idx[q] >= N)
+            return -1;
+        memcpy(out_xyz + 3 * (size_t)q, xyz + 3 * (size_t)idx[q], 3 * sizeof(float));
+    }
+    return 0;
+}
+
+/* --------------------------------------------------------- quality metrics -- */
+/* binary64 Euclidean distance from the binary32 inputs */
+static double ref_dist_f64(const float *a, const float *b)
+{
+    double dx = (double)a[0] - (double)b[0];
+    double dy = (double)a[1] - (double)b[1];
+    double dz = (double)a[2] - (double)b[2];
+    return sqrt(dx * dx + dy * dy + dz * dz);
+}
+
+/* coverage radius: max over points of the distance to the nearest sample */
+double ref_coverage_radius(const float *xyz, int32_t N, const int32_t *idx, int32_t n)
+{
+    double worst = 0.0;
+    for (int32_t j = 0; j < N; ++j) {
+        double best = INFINITY;
+        for (int32_t s = 0; s < n; ++s) {
+            double d = ref_dist_f64(xyz + 3 * (size_t)j, xyz + 3 * (size_t)idx[s]);
+            if (d < best)
+                best = d;
+        }
+        if (best > worst)
+            worst = best;
+    }
+    return worst;
+}
+
+/* the paper's sampling-quality metric (Section 5.2, Table 1): mean over samples
+ * of the distance to the nearest other sample */
+double ref_mean_spacing(const float *xyz, const int32_t *idx, int32_t n)
+{
+    if (n < 2)
+        return 0.0;
+    double sum = 0.0;
+    for (int32_t s = 0; s < n; ++s) {
+        double best = INFINITY;
+        for (int32_t t = 0; t < n; ++t) {
+            if (t == s)
+                continue;
+            double d = ref_dist_f64(xyz + 3 * (size_t)idx[s], xyz + 3 * (size_t)idx[t]);
+            if (d < best)
+                best = d;
+        }
+        sum += best;
+    }
+    return sum / (double)n;
+}

@@ -1,0 +1,189 @@
+"""ctypes access to the CPU oracle (oracle/fastpoint_ref.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product package never imports this module.
+Every function takes and returns numpy arrays on the host; batches are plain
+Python loops over clouds.
+"""
+from __future__ import annotations
+
+import ctypes
+import dataclasses
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+MAX_SEG = 16
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [("p", ctypes.c_float), ("nseg", ctypes.c_int32), ("exponent", ctypes.c_double),
+                ("bias", ctypes.c_float), ("fit_window", ctypes.c_int32), ("m_min", ctypes.c_int32),
+                ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG)]
+
+
+class _Info(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_int32), ("et_index", ctypes.c_int32),
+                ("level_start", ctypes.c_int32 * MAX_SEG),
+                ("level_exhausted", ctypes.c_int32 * MAX_SEG),
+                ("thr2", ctypes.c_float * MAX_SEG)]
+
+
+@dataclasses.dataclass
+class MdpsParams:
+    p: float = 0.1
+    nseg: int = 6
+    exponent: float = 1.0
+    bias: float = 1.0
+    fit_window: int = 32
+    m_min: int = 8
+    thr_override: Optional[Sequence[float]] = None
+
+    def to_c(self) -> _Params:
+        c = _Params()
+        c.p, c.nseg, c.exponent, c.bias = self.p, self.nseg, self.exponent, self.bias
+        c.fit_window, c.m_min = self.fit_window, self.m_min
+        c.use_override = 0
+        if self.thr_override is not None:
+            assert len(self.thr_override) == self.nseg
+            c.use_override = 1
+            for i, v in enumerate(self.thr_override):
+                c.thr_override[i] = v
+        return c
+
+
+@dataclasses.dataclass
+class MdpsInfo:
+    m: int
+    et_index: int
+    level_start: np.ndarray
+    level_exhausted: np.ndarray
+    thr2: np.ndarray
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(_build.build())
+        fp = ctypes.POINTER(ctypes.c_float)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        i32 = ctypes.c_int32
+        _lib.ref_fps_exact.argtypes = [fp, i32, i32, i32, ip, fp]
+        _lib.ref_mdps_prefix_len.argtypes = [ctypes.POINTER(_Params), i32]
+        _lib.ref_mdps_thresholds.argtypes = [fp, i32, i32, ctypes.POINTER(_Params), fp]
+        _lib.ref_mdps_sample.argtypes = [fp, i32, i32, i32, ctypes.POINTER(_Params), ip,
+                                         ctypes.POINTER(_Info)]
+        _lib.ref_mdps_literal.argtypes = _lib.ref_mdps_sample.argtypes
+        _lib.ref_ball_query.argtypes = [fp, i32, ip, i32, ctypes.c_float, i32, ip, ip]
+        _lib.ref_gather_xyz.argtypes = [fp, i32, ip, i32, fp]
+        _lib.ref_coverage_radius.argtypes = [fp, i32, ip, i32]
+        _lib.ref_coverage_radius.restype = ctypes.c_double
+        _lib.ref_mean_spacing.argtypes = [fp, ip, i32]
+        _lib.ref_mean_spacing.restype = ctypes.c_double
+    return _lib
+
+
+def _f(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _i(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _cloud(xyz) -> np.ndarray:
+    a = np.ascontiguousarray(xyz, dtype=np.float32)
+    assert a.ndim == 2 and a.shape[1] == 3
+    return a
+
+
+def fps_exact(xyz, n: int, start: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+    """Algorithm 1 on one cloud: (idx[n] int32, mdc[n] float32 squared)."""
+    a = _cloud(xyz)
+    idx = np.empty(n, dtype=np.int32)
+    mdc = np.empty(n, dtype=np.float32)
+    rc = lib().ref_fps_exact(_f(a), a.shape[0], n, start, _i(idx), _f(mdc))
+    if rc != 0:
+        raise ValueError("ref_fps_exact rejected its arguments")
+    return idx, mdc
+
+
+def mdps_prefix_len(prm: MdpsParams, n: int) -> int:
+    c = prm.to_c()
+    return int(lib().ref_mdps_prefix_len(ctypes.byref(c), n))
+
+
+def mdps_thresholds(mdc, n: int, m: int, prm: MdpsParams) -> np.ndarray:
+    a = np.ascontiguousarray(mdc, dtype=np.float32)
+    assert a.shape[0] >= m + 1
+    out = np.empty(prm.nseg, dtype=np.float32)
+    c = prm.to_c()
+    rc = lib().ref_mdps_thresholds(_f(a), n, m, ctypes.byref(c), _f(out))
+    if rc != 0:
+        raise ValueError("ref_mdps_thresholds rejected its arguments")
+    return out
+
+
+def _mdps(fn, xyz, n, start, prm) -> Tuple[np.ndarray, MdpsInfo]:
+    a = _cloud(xyz)
+    idx = np.empty(n, dtype=np.int32)
+    c = prm.to_c()
+    info = _Info()
+    rc = fn(_f(a), a.shape[0], n, start, ctypes.byref(c), _i(idx), ctypes.byref(info))
+    if rc != 0:
+        raise ValueError("oracle MDPS rejected its arguments")
+    return idx, MdpsInfo(int(info.m), int(info.et_index),
+                         np.array(info.level_start[:prm.nseg], dtype=np.int32),
+                         np.array(info.level_exhausted[:prm.nseg], dtype=np.int32),
+                         np.array(info.thr2[:prm.nseg], dtype=np.float32))
+
+
+def mdps_sample(xyz, n: int, prm: MdpsParams, start: int = 0) -> Tuple[np.ndarray, MdpsInfo]:
+    """Algorithm 2, running-min-distance form, one cloud."""
+    return _mdps(lib().ref_mdps_sample, xyz, n, start, prm)
+
+
+def mdps_literal(xyz, n: int, prm: MdpsParams, start: int = 0) -> Tuple[np.ndarray, MdpsInfo]:
+    """Algorithm 2 with explicit exclusion lists and bitmaps (O(N^2); tiny clouds)."""
+    return _mdps(lib().ref_mdps_literal, xyz, n, start, prm)
+
+
+def ball_query(xyz, centers, radius: float, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """(idx[M][k] int32, cnt[M] int32) for one cloud."""
+    a = _cloud(xyz)
+    c = np.ascontiguousarray(centers, dtype=np.int32)
+    M = c.shape[0]
+    idx = np.empty((M, k), dtype=np.int32)
+    cnt = np.empty(M, dtype=np.int32)
+    rc = lib().ref_ball_query(_f(a), a.shape[0], _i(c), M, np.float32(radius), k, _i(idx), _i(cnt))
+    if rc != 0:
+        raise ValueError("ref_ball_query rejected its arguments")
+    return idx, cnt
+
+
+def gather_xyz(xyz, idx) -> np.ndarray:
+    a = _cloud(xyz)
+    c = np.ascontiguousarray(idx, dtype=np.int32)
+    out = np.empty((c.shape[0], 3), dtype=np.float32)
+    rc = lib().ref_gather_xyz(_f(a), a.shape[0], _i(c), c.shape[0], _f(out))
+    if rc != 0:
+        raise ValueError("ref_gather_xyz rejected its arguments")
+    return out
+
+
+def coverage_radius(xyz, idx) -> float:
+    a = _cloud(xyz)
+    c = np.ascontiguousarray(idx, dtype=np.int32)
+    return float(lib().ref_coverage_radius(_f(a), a.shape[0], _i(c), c.shape[0]))
+
+
+def mean_spacing(xyz, idx) -> float:
+    a = _cloud(xyz)
+    c = np.ascontiguousarray(idx, dtype=np.int32)
+    return float(lib().ref_mean_spacing(_f(a), _i(c), c.shape[0]))
