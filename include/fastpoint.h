@@ -1,0 +1,162 @@
+/*
+ * fastpoint.h -- C ABI of the MI355X (gfx950) library for farthest point
+ * sampling, minimum-distance-prediction sampling (MDPS) and ball query
+ * (FastPoint, arXiv 2507.23480).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller (contiguous,
+ *     row-major), unless a parameter says "host".  The library never frees or
+ *     keeps them and allocates no device memory itself: scratch comes from the
+ *     caller's workspace (fp_workspace_bytes) and the optional ball-query cache
+ *     (fp_bq_cache_bytes).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising.
+ *   - Arguments are validated on the host before anything is enqueued; a
+ *     negative status means nothing was launched.
+ *   - Arithmetic: squared Euclidean distance in IEEE binary32 evaluated as
+ *     ((dx*dx)+(dy*dy))+(dz*dz), each operation rounded separately (no FMA);
+ *     argmax and "any available point" resolve to the lowest index.  Index
+ *     results are therefore reproducible bit for bit.
+ *   - Inputs must be finite with |coordinate| < 1e18.
+ *   - Calls that share a workspace or a cache must not overlap in time.
+ */
+#ifndef FASTPOINT_H_
+#define FASTPOINT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t fp_status;
+enum {
+    FP_OK = 0,
+    FP_ERR_NULL = -1,      /* a required pointer is NULL                         */
+    FP_ERR_SHAPE = -2,     /* B, N, n, M or k out of range / cloud too large     */
+    FP_ERR_PARAM = -3,     /* radius or an MDPS parameter out of range           */
+    FP_ERR_WORKSPACE = -4, /* workspace or cache missing, misaligned or too small */
+    FP_ERR_DEVICE = -5     /* a HIP runtime call failed                          */
+};
+
+#define FP_MAX_SEG 16
+
+/* MDPS hyper-parameters (Section 4.1; Appendix A.3 for the estimator). Host struct. */
+typedef struct fp_mdps_params {
+    float   p;            /* ratio of exact FPS iterations run first (paper: 0.1), 0 < p < 1   */
+    int32_t nseg;         /* segments of the distance curve (paper default 6), 1..FP_MAX_SEG   */
+    double  exponent;     /* e of the power-function estimator C(x) = a / x^e, in squared-
+                             distance space, x = sample position; fitted offline per workload */
+    float   bias;         /* factor on the predicted DISTANCE (bias^2 on the squared value), > 0 */
+    int32_t fit_window;   /* trailing prefix points that determine a (1..64)                   */
+    int32_t m_min;        /* lower limit of the prefix length                                  */
+    int32_t use_override; /* nonzero: skip the estimator, use thr_override                     */
+    float   thr_override[FP_MAX_SEG]; /* squared thresholds R_l^2, l = 1..nseg, non-increasing */
+} fp_mdps_params;
+
+/* Per-cloud record written by the sampler kernels (device memory, [B], optional). */
+typedef struct fp_mdps_info {
+    int32_t m;                          /* exact FPS iterations run first                         */
+    int32_t et_index;                   /* first sample position filled by the remainder FPS
+                                           (early termination, Section 4.1 step 4); n if none     */
+    int32_t level_start[FP_MAX_SEG];    /* sample position at which level l+1 became current, or -1 */
+    int32_t level_exhausted[FP_MAX_SEG];/* 1 if level l+1 ran out of available points             */
+    float   thr2[FP_MAX_SEG];           /* squared thresholds used                                */
+    int32_t rounds;                     /* candidate rounds of the threshold phase                */
+    int32_t status;                     /* 0 ok; 1 start index out of range; 2 a bounded wait
+                                           between workgroups expired (output invalid)            */
+} fp_mdps_info;
+
+/* Bytes of workspace fp_fps_exact / fp_mdps_sample need for B clouds of N points
+ * (0 is returned for shapes the library rejects). Alignment: 256 bytes. */
+size_t fp_workspace_bytes(int32_t B, int32_t N);
+
+/* Bytes of the ball-query cache for B clouds of N points and n samples each.
+ * The cache stores, for every sample, one bit per point: "closer than the
+ * radius" -- the extra exclusion list at the ball-query radius of Section 4.2,
+ * kept as bitmap rows.  Alignment: 256 bytes. */
+size_t fp_bq_cache_bytes(int32_t B, int32_t N, int32_t n);
+
+/*
+ * Exact farthest point sampling, Algorithm 1 (Section 3.3).
+ *   xyz        [B][N][3] float32
+ *   start_idx  [B] int32 seed index per cloud, or NULL for 0
+ *   out_idx    [B][n] int32; out_idx[b][0] = seed
+ *   out_mdc    [B][n] float32 or NULL: squared min-distance of each pick at pick
+ *              time (the minimum distance curve of Section 4; +inf for the seed)
+ *   info       [B] or NULL (only m, et_index = n and status are meaningful)
+ *   bq_cache   NULL, or a buffer of fp_bq_cache_bytes(B,N,n) that receives the
+ *              radius test of every (sample, point) pair as a by-product of the
+ *              distance updates (Section 4.2); bq_radius is then required > 0
+ * A seed index outside [0,N) makes that cloud's out_idx all -1 (info.status 1).
+ */
+fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n,
+                       const int32_t* start_idx, int32_t* out_idx, float* out_mdc,
+                       fp_mdps_info* info, void* bq_cache, float bq_radius,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Minimum Distance Prediction Sampling, Algorithm 2 (Section 4.1, Appendix A.1):
+ * m = max(floor(p*n), m_min) exact FPS iterations that record the distance
+ * curve, thresholds R_l from the estimated curve at the segment ends,
+ * threshold-guided picks (lowest available index; level advances on quota or
+ * on exhaustion), and exact FPS for whatever remains once the last level is
+ * exhausted.  If m >= n-1 the call is exact FPS.  Arguments as fp_fps_exact;
+ * prm is a HOST pointer.
+ */
+fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n,
+                         const int32_t* start_idx, const fp_mdps_params* prm,
+                         int32_t* out_idx, fp_mdps_info* info,
+                         void* bq_cache, float bq_radius,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Ball query (Section 3.1 step 2): for centre q of cloud b (a point of that
+ * cloud, center_idx[b][q]) the indices j with dist^2(centre, P[j]) < radius^2
+ * (strict, binary32), ascending, first k kept; unused slots repeat the first
+ * hit; out_cnt = min(hits, k).
+ *   center_idx [B][M] int32, out_idx [B][M][k] int32, out_cnt [B][M] int32 or NULL
+ *   bq_cache   NULL = brute force over all N points.  Otherwise a cache filled
+ *              by fp_fps_exact / fp_mdps_sample on the same xyz: centres that
+ *              are the cached samples (same position q, same radius) are read
+ *              from the cache with no distance evaluation (redundancy-free ball
+ *              query, Section 4.2); any other centre falls back to the brute-
+ *              force test inside the same kernel.  Results are identical.
+ * A centre index outside [0,N) yields a row of -1 and count 0.
+ */
+fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N,
+                        const int32_t* center_idx, int32_t M, float radius, int32_t k,
+                        int32_t* out_idx, int32_t* out_cnt,
+                        const void* bq_cache, void* stream);
+
+/* out_xyz[b][q] = xyz[b][idx[b][q]] -- input of the next stage of a hierarchy
+ * (Section 3.1).  Indices outside [0,N) give NaN coordinates. */
+fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N,
+                        const int32_t* idx, int32_t M, float* out_xyz, void* stream);
+
+/* Sampling-quality helper: out_cov2[b] = max_j min_q dist^2(P[j], S[q]) in
+ * binary32, the squared coverage radius of the sample set.
+ *   sample_xyz [B][n][3] (e.g. from fp_gather_xyz), out_cov2 [B] float32 */
+fp_status fp_coverage(const float* xyz, int32_t B, int32_t N,
+                      const float* sample_xyz, int32_t n, float* out_cov2, void* stream);
+
+/* How the sampler splits one cloud: workgroups per cloud, threads per
+ * workgroup, points per thread.  Returns FP_ERR_SHAPE if the cloud does not fit. */
+fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
+                  int32_t* points_per_thread);
+
+/* Tuning hook for benchmarks: force workgroups per cloud (0 = automatic).
+ * Process-wide; not meant for concurrent use. */
+void fp_set_wg_per_cloud(int32_t wg_per_cloud);
+
+/* Upper limit, in microseconds, of any wait of one workgroup on another
+ * (default 2 000 000).  A wait that expires ends the kernel with info.status 2. */
+void fp_set_wait_limit_us(int64_t microseconds);
+
+const char* fp_status_string(fp_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTPOINT_H_ */

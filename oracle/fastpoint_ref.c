@@ -138,6 +138,43 @@ int32_t ref_mdps_prefix_len(const ref_mdps_params *prm, int32_t n)
 }
 
 /*
+ * x^e for an integer x >= 1, binary64.  The estimator needs a power function
+ * whose result does not depend on the math library at hand (the thresholds
+ * derived from it decide integer picks), so it is spelled out with + - * /
+ * only, each of which IEEE 754 rounds the same way everywhere:
+ *   x = f * 2^k with f in [sqrt(1/2), sqrt(2));  ln f = 2 atanh((f-1)/(f+1))
+ *   by its series (13 terms, |s| < 0.172);  y = e * (k ln2 + ln f);
+ *   y = q ln2 + r with q = round(y / ln2);  exp r by its Taylor series
+ *   (20 terms, |r| < 0.35);  result = exp(r) * 2^q.
+ * Relative error stays below 2e-14 (ln 2 is itself rounded); tests pin it against libm pow.
+ */
+double ref_pow_int_base(int64_t x, double e)
+{
+    const double LN2 = 0.6931471805599453;
+    int k = 0;
+    while (((int64_t)1 << (k + 1)) <= x)
+        ++k;
+    double f = (double)x / (double)((int64_t)1 << k);   /* exact, in [1,2) */
+    if (f > 1.4142135623730951) {
+        f = f * 0.5;
+        k = k + 1;
+    }
+    double s = (f - 1.0) / (f + 1.0);
+    double s2 = s * s;
+    double sum = 0.0;
+    for (int t = 12; t >= 0; --t)
+        sum = sum * s2 + 1.0 / (double)(2 * t + 1);
+    double lnx = ((double)k * LN2) + ((2.0 * s) * sum);
+    double y = e * lnx;
+    double q = floor(y / LN2 + 0.5);
+    double r = y - q * LN2;
+    double acc = 1.0;
+    for (int t = 20; t >= 1; --t)
+        acc = 1.0 + acc * (r / (double)t);
+    return ldexp(acc, (int)q);                           /* exact scaling */
+}
+
+/*
  * Curve estimator and segment thresholds (Section 4.1 step 1, Eq. 1, with the
  * power-function estimator of Appendix A.3; Section 4.1 step 2 and Alg. 2 line
  * 20 for the thresholds).
@@ -165,7 +202,7 @@ int ref_mdps_thresholds(const float *mdc, int32_t n, int32_t m,
     double e = prm->exponent;
     double a = 0.0;
     for (int32_t i = m - W + 1; i <= m; ++i)
-        a += (double)mdc[i] * pow((double)i, e);
+        a += (double)mdc[i] * ref_pow_int_base(i, e);
     a = a / (double)W;
     double bias2 = (double)prm->bias * (double)prm->bias;
     for (int32_t l = 1; l <= prm->nseg; ++l) {
@@ -178,7 +215,7 @@ int ref_mdps_thresholds(const float *mdc, int32_t n, int32_t m,
         if (b <= m)
             r = mdc[b];
         else
-            r = (float)(bias2 * a / pow((double)b, e));
+            r = (float)((bias2 * a) / ref_pow_int_base(b, e));
         if (!(r >= FLT_MIN))
             r = FLT_MIN;
         if (l >= 2 && r > thr2[l - 2])

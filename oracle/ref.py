@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         ip = ctypes.POINTER(ctypes.c_int32)
         i32 = ctypes.c_int32
         _lib.ref_fps_exact.argtypes = [fp, i32, i32, i32, ip, fp]
+        _lib.ref_pow_int_base.argtypes = [ctypes.c_int64, ctypes.c_double]
+        _lib.ref_pow_int_base.restype = ctypes.c_double
         _lib.ref_mdps_prefix_len.argtypes = [ctypes.POINTER(_Params), i32]
         _lib.ref_mdps_thresholds.argtypes = [fp, i32, i32, ctypes.POINTER(_Params), fp]
         _lib.ref_mdps_sample.argtypes = [fp, i32, i32, i32, ctypes.POINTER(_Params), ip,
@@ -112,6 +114,11 @@ def fps_exact(xyz, n: int, start: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     if rc != 0:
         raise ValueError("ref_fps_exact rejected its arguments")
     return idx, mdc
+
+
+def pow_int_base(x: int, e: float) -> float:
+    """x^e for an integer x >= 1 by the oracle's fixed-order series."""
+    return float(lib().ref_pow_int_base(int(x), float(e)))
 
 
 def mdps_prefix_len(prm: MdpsParams, n: int) -> int:

@@ -1,0 +1,303 @@
+// Host side of the C ABI declared in include/fastpoint.h: argument checks,
+// launch planning and kernel launches.  No device memory is allocated here.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <atomic>
+#include <mutex>
+
+#include "kernels.h"
+
+namespace fastpoint {
+namespace {
+
+std::atomic<int> g_force_wg_per_cloud{0};
+std::atomic<int64_t> g_wait_limit_us{2000000};
+
+struct DeviceInfo {
+    bool ok = false;
+    int cus = 0;
+    int64_t wall_khz = 100000;
+};
+
+constexpr int kMaxDevices = 64;
+DeviceInfo g_dev[kMaxDevices];
+std::mutex g_dev_mutex;
+
+bool device_info(DeviceInfo* out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (!g_dev[dev].ok) {
+        int cus = 0, khz = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return false;
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
+            khz = 100000;
+        g_dev[dev].cus = cus;
+        g_dev[dev].wall_khz = khz;
+        g_dev[dev].ok = cus > 0;
+    }
+    *out = g_dev[dev];
+    return out->ok;
+}
+
+// capacities (threads, points per thread) the sampler kernel is built for
+struct Shape {
+    int T, P;
+};
+constexpr Shape kShapes[] = {{256, 2}, {256, 4}, {256, 8}, {256, 16}, {256, 32}};
+constexpr int kNumShapes = (int)(sizeof(kShapes) / sizeof(kShapes[0]));
+constexpr int kTargetPointsPerWg = 4096;
+
+bool shape_for(int64_t points_per_wg, Shape* s)
+{
+    for (int i = 0; i < kNumShapes; ++i)
+        if ((int64_t)kShapes[i].T * kShapes[i].P >= points_per_wg) {
+            *s = kShapes[i];
+            return true;
+        }
+    return false;
+}
+
+// Splits B clouds of N points over at most `cus` resident workgroups.
+bool make_plan(int B, int N, int cus, Plan* plan)
+{
+    if (B < 1 || N < 1 || cus < 1) return false;
+    const int clouds_at_once = B < cus ? B : cus;
+    int gmax = cus / clouds_at_once;
+    if (gmax > kMaxGroup) gmax = kMaxGroup;
+    if (gmax < 1) gmax = 1;
+    int G = (int)(((int64_t)N + kTargetPointsPerWg - 1) / kTargetPointsPerWg);
+    const int forced = g_force_wg_per_cloud.load();
+    if (forced > 0) G = forced;
+    if (G > gmax) G = gmax;
+    if (G < 1) G = 1;
+    Shape s;
+    while (!shape_for(((int64_t)N + G - 1) / G, &s)) {
+        if (G >= gmax) return false;
+        ++G;
+    }
+    plan->G = G;
+    plan->T = s.T;
+    plan->P = s.P;
+    int groups = cus / G;
+    if (groups > B) groups = B;
+    plan->groups = groups;
+    return true;
+}
+
+inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+int64_t bq_row_words(int N) { return align_up(((int64_t)N + 63) / 64, 8); }
+
+constexpr int64_t kLlPkWords = (int64_t)2 * kMaxGroup * kLlSlotWords;             // all groups together
+constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandPerRound * 4;
+
+fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
+                      const fp_mdps_params* prm, int32_t* out_idx, float* out_mdc, fp_mdps_info* info,
+                      void* bq_cache, float bq_radius, void* workspace, size_t workspace_bytes,
+                      void* stream_v)
+{
+    if (!xyz || !out_idx) return FP_ERR_NULL;
+    if (B < 1 || N < 1 || n < 1 || n > N) return FP_ERR_SHAPE;
+    if ((int64_t)B * N > (int64_t)1 << 40) return FP_ERR_SHAPE;
+    DeviceInfo di;
+    if (!device_info(&di)) return FP_ERR_DEVICE;
+    Plan plan;
+    if (!make_plan(B, N, di.cus < 256 ? di.cus : 256, &plan)) return FP_ERR_SHAPE;
+    if (bq_cache) {
+        if (!(bq_radius > 0.0f) || !isfinite(bq_radius)) return FP_ERR_PARAM;
+        if ((reinterpret_cast<uintptr_t>(bq_cache) & 255u) != 0) return FP_ERR_WORKSPACE;
+    }
+    if (!workspace || workspace_bytes < fp_workspace_bytes(B, N) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return FP_ERR_WORKSPACE;
+
+    SamplerArgs a;
+    memset(&a, 0, sizeof(a));
+    a.xyz = xyz;
+    a.start_idx = start_idx;
+    a.out_idx = out_idx;
+    a.out_mdc = out_mdc;
+    a.info = info;
+    a.B = B;
+    a.N = N;
+    a.n = n;
+    a.G = plan.G;
+    a.m = n - 1;
+    a.nseg = 1;
+    if (prm) {
+        if (!(prm->p > 0.0f) || !(prm->p < 1.0f)) return FP_ERR_PARAM;
+        if (prm->nseg < 1 || prm->nseg > FP_MAX_SEG) return FP_ERR_PARAM;
+        if (prm->m_min < 1) return FP_ERR_PARAM;
+        if (prm->use_override) {
+            for (int l = 0; l < prm->nseg; ++l) {
+                if (!(prm->thr_override[l] > 0.0f)) return FP_ERR_PARAM;
+                if (l > 0 && prm->thr_override[l] > prm->thr_override[l - 1]) return FP_ERR_PARAM;
+                a.thr_override[l] = prm->thr_override[l];
+            }
+        } else {
+            if (!(prm->bias > 0.0f) || !isfinite(prm->bias) || !isfinite(prm->exponent))
+                return FP_ERR_PARAM;
+            if (prm->fit_window < 1 || prm->fit_window > 64) return FP_ERR_PARAM;
+        }
+        int64_t m = (int64_t)floor((double)prm->p * (double)n);
+        if (m < prm->m_min) m = prm->m_min;
+        if (m > n - 1) m = n - 1;
+        a.m = (int32_t)m;
+        a.nseg = prm->nseg;
+        a.fit_window = prm->fit_window;
+        a.use_override = prm->use_override ? 1 : 0;
+        a.exponent = prm->exponent;
+        a.bias2 = (double)prm->bias * (double)prm->bias;
+    }
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
+    a.ll_pk = reinterpret_cast<uint64_t*>(workspace);
+    a.ll_cd = a.ll_pk + kLlPkWords;
+    a.wait_ticks = g_wait_limit_us.load() * di.wall_khz / 1000;
+
+    const bool bq = bq_cache != nullptr;
+    if (bq) {
+        BqHeader h;
+        memset(&h, 0, sizeof(h));
+        h.magic = kBqMagic;
+        h.B = B;
+        h.N = N;
+        h.n = n;
+        h.row_words = bq_row_words(N);
+        const float r2 = bq_radius * bq_radius;
+        memcpy(&h.r2_bits, &r2, sizeof(r2));
+        h.valid = 1;
+        h.idx_offset = 256;
+        h.bits_offset = 256 + align_up((int64_t)B * n * 4, 256);
+        unsigned char* base = reinterpret_cast<unsigned char*>(bq_cache);
+        a.bq_idx = reinterpret_cast<int32_t*>(base + h.idx_offset);
+        a.bq_bits = reinterpret_cast<uint64_t*>(base + h.bits_offset);
+        a.bq_r2 = r2;
+        a.bq_row_words = h.row_words;
+        if (launch_bq_header(bq_cache, h, stream) != hipSuccess) return FP_ERR_DEVICE;
+    }
+
+    const void* fn = sampler_kernel_for(plan.T, plan.P, bq);
+    if (!fn) return FP_ERR_SHAPE;
+    const unsigned grid = (unsigned)(plan.groups * plan.G);
+    void* kargs[] = {&a};
+    hipError_t err;
+    if (plan.G > 1) {
+        // workgroups of a cloud wait on each other: stamps start from zeroed words and the
+        // whole grid has to be resident
+        if (launch_zero_words(a.ll_pk, kLlPkWords + kLlCdWords, stream) != hipSuccess)
+            return FP_ERR_DEVICE;
+        err = hipLaunchCooperativeKernel(fn, dim3(grid), dim3((unsigned)plan.T), kargs, 0, stream);
+    } else {
+        err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)plan.T), kargs, 0, stream);
+    }
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
+}  // namespace
+}  // namespace fastpoint
+
+using namespace fastpoint;
+
+extern "C" {
+
+size_t fp_workspace_bytes(int32_t B, int32_t N)
+{
+    if (B < 1 || N < 1) return 0;
+    return (size_t)((kLlPkWords + kLlCdWords) * 8);
+}
+
+size_t fp_bq_cache_bytes(int32_t B, int32_t N, int32_t n)
+{
+    if (B < 1 || N < 1 || n < 1 || n > N) return 0;
+    return (size_t)(256 + align_up((int64_t)B * n * 4, 256) + (int64_t)B * n * bq_row_words(N) * 8);
+}
+
+fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
+                       int32_t* out_idx, float* out_mdc, fp_mdps_info* info, void* bq_cache,
+                       float bq_radius, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, info, bq_cache, bq_radius,
+                       workspace, workspace_bytes, stream);
+}
+
+fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
+                         const fp_mdps_params* prm, int32_t* out_idx, fp_mdps_info* info,
+                         void* bq_cache, float bq_radius, void* workspace, size_t workspace_bytes,
+                         void* stream)
+{
+    if (!prm) return FP_ERR_NULL;
+    return run_sampler(xyz, B, N, n, start_idx, prm, out_idx, nullptr, info, bq_cache, bq_radius,
+                       workspace, workspace_bytes, stream);
+}
+
+fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N, const int32_t* center_idx, int32_t M,
+                        float radius, int32_t k, int32_t* out_idx, int32_t* out_cnt,
+                        const void* bq_cache, void* stream)
+{
+    if (!xyz || !center_idx || !out_idx) return FP_ERR_NULL;
+    if (B < 1 || N < 1 || M < 0 || k < 1 || B > 65535) return FP_ERR_SHAPE;
+    if (!(radius > 0.0f) || !isfinite(radius)) return FP_ERR_PARAM;
+    if (bq_cache && (reinterpret_cast<uintptr_t>(bq_cache) & 255u) != 0) return FP_ERR_WORKSPACE;
+    const float r2 = radius * radius;
+    hipError_t err = launch_ball_query(xyz, B, N, center_idx, M, r2, k, out_idx, out_cnt, bq_cache,
+                                       reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
+fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N, const int32_t* idx, int32_t M,
+                        float* out_xyz, void* stream)
+{
+    if (!xyz || !idx || !out_xyz) return FP_ERR_NULL;
+    if (B < 1 || N < 1 || M < 0) return FP_ERR_SHAPE;
+    hipError_t err = launch_gather(xyz, B, N, idx, M, out_xyz, reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
+fp_status fp_coverage(const float* xyz, int32_t B, int32_t N, const float* sample_xyz, int32_t n,
+                      float* out_cov2, void* stream)
+{
+    if (!xyz || !sample_xyz || !out_cov2) return FP_ERR_NULL;
+    if (B < 1 || N < 1 || n < 1 || B > 65535) return FP_ERR_SHAPE;
+    hipError_t err = launch_coverage(xyz, B, N, sample_xyz, n, out_cov2,
+                                     reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
+fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
+                  int32_t* points_per_thread)
+{
+    DeviceInfo di;
+    int cus = 256;
+    if (device_info(&di)) cus = di.cus < 256 ? di.cus : 256;
+    Plan plan;
+    if (!make_plan(B, N, cus, &plan)) return FP_ERR_SHAPE;
+    if (wg_per_cloud) *wg_per_cloud = plan.G;
+    if (threads) *threads = plan.T;
+    if (points_per_thread) *points_per_thread = plan.P;
+    return FP_OK;
+}
+
+void fp_set_wg_per_cloud(int32_t wg_per_cloud) { g_force_wg_per_cloud.store(wg_per_cloud > 0 ? wg_per_cloud : 0); }
+
+void fp_set_wait_limit_us(int64_t microseconds) { g_wait_limit_us.store(microseconds > 0 ? microseconds : 1); }
+
+const char* fp_status_string(fp_status s)
+{
+    switch (s) {
+        case FP_OK: return "ok";
+        case FP_ERR_NULL: return "a required pointer is NULL";
+        case FP_ERR_SHAPE: return "shape out of range";
+        case FP_ERR_PARAM: return "parameter out of range";
+        case FP_ERR_WORKSPACE: return "workspace or cache missing, misaligned or too small";
+        case FP_ERR_DEVICE: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

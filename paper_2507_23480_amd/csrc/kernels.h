@@ -1,0 +1,66 @@
+// Internal declarations shared by the HIP translation units of the library.
+#ifndef FASTPOINT_KERNELS_H_
+#define FASTPOINT_KERNELS_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fastpoint.h"
+
+namespace fastpoint {
+
+constexpr int kMaxGroup = 256;          // most workgroups one cloud is spread over
+constexpr int kLlSlotWords = 8;         // 64-bit words per workgroup slot of the pick exchange
+constexpr int kCandPerRound = 64;       // candidates per round of the threshold phase
+constexpr uint32_t kBqMagic = 0x46504251u;
+
+// Header at the start of a ball-query cache (device memory).
+struct BqHeader {
+    uint32_t magic;
+    int32_t B, N, n;
+    int64_t row_words;      // 64-bit words per (sample) row
+    uint32_t r2_bits;       // radius^2 (binary32 bits) the rows were recorded with
+    int32_t valid;          // set to 1 by the sampler kernel when it has finished
+    int64_t idx_offset;     // byte offset of the int32 [B][n] copy of the sample indices
+    int64_t bits_offset;    // byte offset of the uint64 [B][n][row_words] rows
+};
+
+struct SamplerArgs {
+    const float* xyz;
+    const int32_t* start_idx;
+    int32_t* out_idx;
+    float* out_mdc;
+    fp_mdps_info* info;
+    int32_t B, N, n, G;
+    int32_t m;                      // exact FPS iterations before the threshold phase (n-1: all)
+    int32_t nseg, fit_window, use_override;
+    double exponent, bias2;
+    float thr_override[FP_MAX_SEG];
+    uint64_t* bq_bits;
+    int32_t* bq_idx;
+    float bq_r2;
+    int64_t bq_row_words;
+    uint64_t* ll_pk;                // [groups][2][G][kLlSlotWords]
+    uint64_t* ll_cd;                // [groups][2][G][kCandPerRound][4]
+    int64_t wait_ticks;
+};
+
+struct Plan {
+    int G, T, P;        // workgroups per cloud, threads per workgroup, points per thread
+    int groups;         // clouds resident at once
+};
+
+const void* sampler_kernel_for(int threads, int points_per_thread, bool bq);
+hipError_t launch_zero_words(uint64_t* p, int64_t nwords, hipStream_t stream);
+
+hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* center_idx, int M,
+                             float r2, int k, int32_t* out_idx, int32_t* out_cnt,
+                             const void* bq_cache, hipStream_t stream);
+hipError_t launch_gather(const float* xyz, int B, int N, const int32_t* idx, int M, float* out,
+                         hipStream_t stream);
+hipError_t launch_coverage(const float* xyz, int B, int N, const float* sxyz, int n, float* out,
+                           hipStream_t stream);
+hipError_t launch_bq_header(void* cache, const BqHeader& h, hipStream_t stream);
+
+}  // namespace fastpoint
+#endif

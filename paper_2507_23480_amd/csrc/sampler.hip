@@ -1,0 +1,789 @@
+// Persistent sampler kernel for gfx950: exact farthest point sampling
+// (Algorithm 1) and minimum-distance-prediction sampling (Algorithm 2) of
+// FastPoint, arXiv 2507.23480, with the ball-query radius test recorded as a
+// by-product of the distance updates (Section 4.2).
+//
+// One cloud is owned by a group of G workgroups that stay resident for the
+// whole call.  Every thread keeps P points (x, y, z and the running minimum
+// squared distance) in registers; wave `gw` of the cloud owns the 64*P
+// consecutive indices [gw*64*P, (gw+1)*64*P), slot p of lane l being index
+// (gw*P + p)*64 + l, so that one 64-lane compare mask of a slot is one 64-bit
+// word of index-ordered bits.
+//
+// Per exact-FPS iteration: fold the last sample into the P distances, per-lane
+// arg-max, DPP max/min reduction inside the wave, one LDS record per wave, one
+// workgroup barrier, and -- when G > 1 -- an exchange between the workgroups of
+// the cloud through self-validating 64-bit words (payload in the low half, a
+// sequence stamp in the high half, relaxed agent-scope atomics, no fences).
+//
+// The threshold phase of Algorithm 2 uses the equivalent running-distance form:
+// point j is available at level l iff dists[j] >= R_l^2.  Each round takes the
+// first 64 available indices, resolves them in index order against the picks
+// accepted earlier in the round (exactly what picking them one at a time would
+// do), and folds all accepted picks into the distances in one sweep.
+//
+// All floating point here must round every operation separately: the file is
+// compiled with -ffp-contract=off and without packed fp32 instructions.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.h"
+
+#pragma clang fp contract(off)
+
+namespace fastpoint {
+namespace {
+
+constexpr int kCand = kCandPerRound;    // candidates examined per round of the threshold phase
+constexpr float kPadCoord = 3.0e38f;    // coordinates of slots beyond N: every distance becomes +inf
+constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
+
+// ---------------------------------------------------------------- wave helpers
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp(uint32_t v)
+{
+    // every lane has a valid source for the controls used here, so bound_ctrl is irrelevant;
+    // this form lets the compiler fuse the move into the following min/max
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xF, 0xF, true);
+}
+// after these four steps every lane holds the reduction over its row of 16 lanes
+__device__ __forceinline__ uint32_t row_max_u32(uint32_t v)
+{
+    v = max(v, dpp<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = max(v, dpp<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = max(v, dpp<0x141>(v));   // row_half_mirror
+    v = max(v, dpp<0x140>(v));   // row_mirror
+    return v;
+}
+__device__ __forceinline__ uint32_t row_min_u32(uint32_t v)
+{
+    v = min(v, dpp<0xB1>(v));
+    v = min(v, dpp<0x4E>(v));
+    v = min(v, dpp<0x141>(v));
+    v = min(v, dpp<0x140>(v));
+    return v;
+}
+__device__ __forceinline__ uint32_t rdlane(uint32_t v, int l)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, l);
+}
+__device__ __forceinline__ float rdlane_f(float v, int l)
+{
+    return __uint_as_float(rdlane(__float_as_uint(v), l));
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    v = row_max_u32(v);
+    return max(max(rdlane(v, 0), rdlane(v, 16)), max(rdlane(v, 32), rdlane(v, 48)));
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
+{
+    v = row_min_u32(v);
+    return min(min(rdlane(v, 0), rdlane(v, 16)), min(rdlane(v, 32), rdlane(v, 48)));
+}
+__device__ __forceinline__ int first_lane(uint64_t mask) { return __builtin_ctzll(mask); }
+__device__ __forceinline__ int lanes_below(uint64_t mask)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// squared distance, ((dx*dx)+(dy*dy))+(dz*dz), each operation rounded on its own
+__device__ __forceinline__ float dist2(float ax, float ay, float az, float bx, float by, float bz)
+{
+    float dx = ax - bx;
+    float dy = ay - by;
+    float dz = az - bz;
+    float t = dx * dx;
+    t = t + dy * dy;
+    t = t + dz * dz;
+    return t;
+}
+
+// ------------------------------------------------- words exchanged between workgroups
+__device__ __forceinline__ void ll_store(uint64_t* p, uint32_t val, uint32_t stamp)
+{
+    __hip_atomic_store(p, ((uint64_t)stamp << 32) | (uint64_t)val, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t ll_load(const uint64_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Waits until the NW words at p carry `stamp`; false if the wait limit expired.
+template <int NWORDS>
+__device__ __forceinline__ bool ll_wait(const uint64_t* p, uint32_t stamp, uint32_t (&val)[NWORDS],
+                                        int64_t wait_ticks)
+{
+    int64_t t0 = 0;
+    for (uint32_t spin = 0;; ++spin) {
+        uint64_t v[NWORDS];
+#pragma unroll
+        for (int k = 0; k < NWORDS; ++k) v[k] = ll_load(p + k);
+        bool ok = true;
+#pragma unroll
+        for (int k = 0; k < NWORDS; ++k) ok = ok && ((uint32_t)(v[k] >> 32) == stamp);
+        if (ok) {
+#pragma unroll
+            for (int k = 0; k < NWORDS; ++k) val[k] = (uint32_t)v[k];
+            return true;
+        }
+        if ((spin & 63u) == 63u) {
+            int64_t now = (int64_t)wall_clock64();
+            if (t0 == 0) t0 = now;
+            else if (now - t0 > wait_ticks) return false;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+}
+
+struct Rec {          // one arg-max candidate: squared distance bits, index, coordinates
+    uint32_t d, idx;
+    float x, y, z;
+    uint32_t fail;
+    uint32_t pad0, pad1;
+};
+
+struct Cand {         // a candidate or accepted pick of the threshold phase
+    uint32_t idx;
+    float x, y, z;
+};
+
+template <int T>
+struct Shared {
+    static constexpr int NW = T / 64;
+    Rec wrec[2][NW];
+    Rec win[2];
+    float ring[64];
+    float thr_meas[FP_MAX_SEG];
+    float thr[FP_MAX_SEG];
+    double terms[64];
+    double powb[FP_MAX_SEG];
+    int32_t level_start[FP_MAX_SEG];
+    int32_t level_exhausted[FP_MAX_SEG];
+    int32_t wcnt[NW];
+    Cand cand[kCand];
+    Cand pend[kCand];
+    int32_t pend_pos[kCand];
+    int32_t gpre[kMaxGroup + 1];
+    int32_t ctrl[4];      // [0] accepted picks of the round, [1] candidates of the round, [2] failure
+};
+
+// Everything one thread needs to know about where it sits.
+struct Where {
+    int tid, lane, w;     // thread, lane, wave in workgroup
+    int g, G, grp;        // workgroup in cloud, workgroups per cloud, group slot in the grid
+    int gw;               // wave in cloud
+    int c;                // cloud
+};
+
+// P floats that stay in registers; element [p] with a wave-uniform p compiles to
+// relative VGPR addressing, not to scratch memory
+template <int P>
+struct RegVec {
+    typedef float type __attribute__((ext_vector_type(P)));
+};
+
+template <int P, bool BQ>
+struct Points {
+    typename RegVec<P>::type x, y, z, d;
+};
+
+// Alg. 1 lines 4-7 for this thread's points; with BQ also the radius test of
+// Section 4.2, one 64-bit word per slot written to row `pos` of the cache.
+template <int P, bool BQ>
+__device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, float cz,
+                                     const SamplerArgs& a, const Where& wh, int pos)
+{
+    uint64_t myword = 0;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        float t = dist2(cx, cy, cz, pt.x[p], pt.y[p], pt.z[p]);
+        // distances are >= +0, so the unsigned order of the bit patterns is their order
+        pt.d[p] = __uint_as_float(min(__float_as_uint(pt.d[p]), __float_as_uint(t)));
+        if (BQ) {
+            uint64_t hit = __builtin_amdgcn_ballot_w64(t < a.bq_r2);
+            if (wh.lane == p) myword = hit;
+        }
+    }
+    if (BQ) {
+        // rows hold ceil(N/64) words (rounded up); slots wholly beyond N have no word
+        if (wh.lane < P && (int64_t)wh.gw * P + wh.lane < a.bq_row_words) {
+            uint64_t* row = a.bq_bits + ((int64_t)wh.c * a.n + pos) * a.bq_row_words +
+                            (int64_t)wh.gw * P;
+            row[wh.lane] = myword;
+        }
+    }
+}
+
+// Arg-max over the workgroup's points (lowest index among equals).  On return
+// every thread of the workgroup holds the record of the workgroup's best point
+// (G == 1) -- or wave 0 holds it (G > 1).
+template <int T, int P, bool BQ>
+__device__ __forceinline__ Rec wave_best(const Points<P, BQ>& pt, const Where& wh)
+{
+    uint32_t bits = __float_as_uint(pt.d[0]);          // distances are >= +0: unsigned order
+    int bp = 0;
+#pragma unroll
+    for (int p = 1; p < P; ++p) {
+        const uint32_t v = __float_as_uint(pt.d[p]);
+        if (v > bits) {
+            bits = v;
+            bp = p;
+        }
+    }
+    const uint32_t wmax = wave_max_u32(bits);
+    const uint32_t myj = (uint32_t)(((wh.gw * P + bp) << 6) | wh.lane);
+    const uint32_t widx = wave_min_u32(bits == wmax ? myj : kNoIdx);
+    const int slot = (int)(widx >> 6) - wh.gw * P;      // uniform
+    const int wl = (int)(widx & 63u);
+    const int slot_u = __builtin_amdgcn_readfirstlane(slot);
+    const float sx = pt.x[slot_u], sy = pt.y[slot_u], sz = pt.z[slot_u];
+    Rec r;
+    r.d = wmax;
+    r.idx = widx;
+    r.x = rdlane_f(sx, wl);
+    r.y = rdlane_f(sy, wl);
+    r.z = rdlane_f(sz, wl);
+    r.fail = 0;
+    r.pad0 = r.pad1 = 0;
+    return r;
+}
+
+// reduce `nrec` records held by lanes 0..nrec-1 of a wave (nrec <= 64)
+__device__ __forceinline__ Rec reduce_recs(Rec r, bool valid)
+{
+    const uint32_t d = valid ? r.d : 0u;
+    const uint32_t idx = valid ? r.idx : kNoIdx;
+    const uint32_t dmax = wave_max_u32(d);
+    const uint32_t imin = wave_min_u32((valid && d == dmax) ? idx : kNoIdx);
+    const uint64_t who = __builtin_amdgcn_ballot_w64(valid && idx == imin);
+    const int src = first_lane(who);
+    Rec o;
+    o.d = dmax;
+    o.idx = imin;
+    o.x = rdlane_f(r.x, src);
+    o.y = rdlane_f(r.y, src);
+    o.z = rdlane_f(r.z, src);
+    o.fail = __builtin_amdgcn_ballot_w64(valid && r.fail != 0) != 0 ? 1u : 0u;
+    o.pad0 = o.pad1 = 0;
+    return o;
+}
+
+// One arg-max over the whole cloud.  `it` counts the reductions done so far in
+// this kernel (LDS double buffering), `seq` the exchanges between workgroups.
+template <int T, int P, bool BQ>
+__device__ __forceinline__ Rec cloud_argmax(const Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                            const SamplerArgs& a, uint32_t& it, uint32_t& seq)
+{
+    constexpr int NW = T / 64;
+    const int buf = (int)(it & 1u);
+    ++it;
+    Rec mine = wave_best<T, P, BQ>(pt, wh);
+    if (wh.lane == 0) sh.wrec[buf][wh.w] = mine;
+    __syncthreads();
+    if (wh.G == 1) {
+        Rec r = sh.wrec[buf][wh.lane < NW ? wh.lane : 0];
+        return reduce_recs(r, wh.lane < NW);
+    }
+    ++seq;
+    if (wh.w == 0) {
+        Rec r = sh.wrec[buf][wh.lane < NW ? wh.lane : 0];
+        Rec wg = reduce_recs(r, wh.lane < NW);
+        const int par = (int)(seq & 1u);
+        uint64_t* base = a.ll_pk + ((int64_t)(wh.grp * 2 + par) * wh.G) * kLlSlotWords;
+        uint32_t v = wg.d;
+        v = wh.lane == 1 ? wg.idx : v;
+        v = wh.lane == 2 ? __float_as_uint(wg.x) : v;
+        v = wh.lane == 3 ? __float_as_uint(wg.y) : v;
+        v = wh.lane == 4 ? __float_as_uint(wg.z) : v;
+        if (wh.lane < 5) ll_store(base + (int64_t)wh.g * kLlSlotWords + wh.lane, v, seq);
+        Rec best;
+        best.d = 0;
+        best.idx = kNoIdx;
+        best.x = best.y = best.z = 0.0f;
+        best.fail = 0;
+        best.pad0 = best.pad1 = 0;
+        bool have = false;
+        for (int t = wh.lane; t < wh.G; t += 64) {
+            uint32_t val[5];
+            bool ok = ll_wait<5>(base + (int64_t)t * kLlSlotWords, seq, val, a.wait_ticks);
+            if (!ok) {
+                best.fail = 1;
+            } else if (!have || val[0] > best.d || (val[0] == best.d && val[1] < best.idx)) {
+                best.d = val[0];
+                best.idx = val[1];
+                best.x = __uint_as_float(val[2]);
+                best.y = __uint_as_float(val[3]);
+                best.z = __uint_as_float(val[4]);
+            }
+            have = true;
+        }
+        Rec all = reduce_recs(best, have);
+        if (wh.lane == 0) sh.win[buf] = all;
+    }
+    __syncthreads();
+    return sh.win[buf];
+}
+
+template <int T, int P, bool BQ>
+__device__ __forceinline__ void write_pick(const SamplerArgs& a, const Where& wh, int pos, uint32_t idx)
+{
+    a.out_idx[(int64_t)wh.c * a.n + pos] = (int32_t)idx;
+    if (BQ) a.bq_idx[(int64_t)wh.c * a.n + pos] = (int32_t)idx;
+}
+
+// x^e for an integer x >= 1 in binary64 using only + - * / (each correctly rounded
+// by IEEE 754), in a fixed order: ln x from the atanh series after scaling x into
+// [sqrt(1/2), sqrt(2)), then exp by its Taylor series after removing a multiple of ln 2.
+// A CPU reference that performs the same operations in the same order gets the same bits.
+__device__ __noinline__ double pow_int_base(int64_t x, double e)
+{
+    const double LN2 = 0.6931471805599453;
+    int k = 63 - __builtin_clzll((unsigned long long)x);
+    double f = (double)x * __longlong_as_double((long long)(1023 - k) << 52);   // exact, in [1,2)
+    if (f > 1.4142135623730951) {
+        f = f * 0.5;
+        k = k + 1;
+    }
+    const double s = (f - 1.0) / (f + 1.0);
+    const double s2 = s * s;
+    double sum = 0.0;
+#pragma unroll 1
+    for (int t = 12; t >= 0; --t) sum = sum * s2 + 1.0 / (double)(2 * t + 1);
+    const double lnx = ((double)k * LN2) + ((2.0 * s) * sum);
+    const double y = e * lnx;
+    const double q = floor(y / LN2 + 0.5);
+    const double r = y - q * LN2;
+    double acc = 1.0;
+#pragma unroll 1
+    for (int t = 20; t >= 1; --t) acc = 1.0 + acc * (r / (double)t);
+    return acc * __longlong_as_double((long long)(1023 + (int)q) << 52);
+}
+
+// ---- exact FPS for sample positions [i, upto): fold sample i-1, then arg-max
+// (Alg. 1 lines 3-8).  Returns false if a wait between workgroups expired.
+template <int T, int P, bool BQ>
+__device__ __forceinline__ bool fps_iterations(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                               const SamplerArgs& a, uint32_t& it, uint32_t& seq,
+                                               int& i, int upto, bool capture, int my_bl, bool writer,
+                                               float& lx, float& ly, float& lz)
+{
+    for (; i < upto; ++i) {
+        fold<P, BQ>(pt, lx, ly, lz, a, wh, i - 1);
+        const Rec r = cloud_argmax<T, P, BQ>(pt, sh, wh, a, it, seq);
+        if (r.fail) return false;
+        lx = r.x;
+        ly = r.y;
+        lz = r.z;
+        const float dpick = __uint_as_float(r.d);
+        if (writer) {
+            write_pick<T, P, BQ>(a, wh, i, r.idx);
+            if (a.out_mdc) a.out_mdc[(int64_t)wh.c * a.n + i] = dpick;
+        }
+        if (capture) {             // Alg. 2 line 11: keep the curve of the prefix
+            if (wh.tid == 0) sh.ring[i & 63] = dpick;
+            if (my_bl == i) sh.thr_meas[wh.tid] = dpick;
+        }
+    }
+    return true;
+}
+
+template <int T, int P, bool BQ>
+__device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                             const SamplerArgs& a, int npend)
+{
+    for (int s = 0; s < npend; ++s) {
+        const Cand pc = sh.pend[s];
+        fold<P, BQ>(pt, pc.x, pc.y, pc.z, a, wh, sh.pend_pos[s]);
+    }
+}
+
+// segment boundary b_l (curve index whose value becomes R_l), l = 1..nseg
+__device__ __forceinline__ int boundary_index(int n, int nseg, int l)
+{
+    int64_t b = ((int64_t)n * l) / nseg;
+    b = b < 1 ? 1 : b;
+    b = b > n - 1 ? n - 1 : b;
+    return (int)b;
+}
+
+// ------------------------------------------------------------------ one cloud
+template <int T, int P, bool BQ>
+__device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, const Where& wh,
+                                          uint32_t& it, uint32_t& seq)
+{
+    constexpr int NW = T / 64;
+    const int n = a.n, N = a.N;
+    const bool writer = (wh.g == 0 && wh.tid == 0);
+    const float* cloud = a.xyz + (int64_t)wh.c * N * 3;
+
+    const int start = a.start_idx ? a.start_idx[wh.c] : 0;
+    if (start < 0 || start >= N) {          // uniform over the group
+        if (wh.g == 0) {
+            for (int k = wh.tid; k < n; k += T) a.out_idx[(int64_t)wh.c * n + k] = -1;
+            if (wh.tid == 0 && a.info) {
+                fp_mdps_info inf = {};
+                inf.status = 1;
+                a.info[wh.c] = inf;
+            }
+        }
+        return;
+    }
+
+    Points<P, BQ> pt;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int j = ((wh.gw * P + p) << 6) | wh.lane;
+        if (j < N) {
+            pt.x[p] = cloud[(int64_t)j * 3 + 0];
+            pt.y[p] = cloud[(int64_t)j * 3 + 1];
+            pt.z[p] = cloud[(int64_t)j * 3 + 2];
+            pt.d[p] = __builtin_inff();
+        } else {
+            pt.x[p] = kPadCoord;
+            pt.y[p] = kPadCoord;
+            pt.z[p] = kPadCoord;
+            pt.d[p] = 0.0f;
+        }
+    }
+    if (wh.tid < FP_MAX_SEG) {
+        sh.level_start[wh.tid] = -1;
+        sh.level_exhausted[wh.tid] = 0;
+        sh.thr[wh.tid] = 0.0f;
+        sh.thr_meas[wh.tid] = 0.0f;
+    }
+    if (wh.tid == 0) sh.ctrl[2] = 0;
+    const int my_bl = wh.tid < a.nseg ? boundary_index(n, a.nseg, wh.tid + 1) : -1;
+
+    float lx = cloud[(int64_t)start * 3 + 0];
+    float ly = cloud[(int64_t)start * 3 + 1];
+    float lz = cloud[(int64_t)start * 3 + 2];
+    if (writer) {
+        write_pick<T, P, BQ>(a, wh, 0, (uint32_t)start);
+        if (a.out_mdc) a.out_mdc[(int64_t)wh.c * n] = __builtin_inff();
+    }
+    __syncthreads();
+
+    const int m = a.m;                 // exact FPS iterations before the threshold phase
+    const bool pure_fps = (m >= n - 1);
+    int i = 1;                         // next sample position to fill
+    int et_index = n;
+    int rounds = 0;
+    int npend = 0;
+
+    bool ok = fps_iterations<T, P, BQ>(pt, sh, wh, a, it, seq, i, pure_fps ? n : m + 1, !pure_fps, my_bl,
+                                       writer, lx, ly, lz);
+
+    if (ok && !pure_fps) {
+        // ---- thresholds from the estimated curve (Eq. 1 with a/x^e; Alg. 2 lines 13, 20)
+        __syncthreads();
+        if (a.use_override) {
+            if (wh.tid < a.nseg) sh.thr[wh.tid] = a.thr_override[wh.tid];
+        } else {
+            const int W = a.fit_window < m ? a.fit_window : m;
+            if (wh.tid < W) {
+                const int ii = m - W + 1 + wh.tid;
+                sh.terms[wh.tid] = (double)sh.ring[ii & 63] * pow_int_base(ii, a.exponent);
+            } else if (wh.tid >= 64 && wh.tid < 64 + a.nseg) {
+                const int l = wh.tid - 64;
+                sh.powb[l] = pow_int_base(boundary_index(n, a.nseg, l + 1), a.exponent);
+            }
+            __syncthreads();
+            if (wh.tid == 0) {
+                double acc = 0.0;
+                for (int t = 0; t < W; ++t) acc += sh.terms[t];
+                acc = acc / (double)W;
+                float prev = 0.0f;
+                for (int l = 0; l < a.nseg; ++l) {
+                    float r;
+                    if (boundary_index(n, a.nseg, l + 1) <= m) r = sh.thr_meas[l];
+                    else r = (float)((a.bias2 * acc) / sh.powb[l]);
+                    if (!(r >= 1.17549435e-38f)) r = 1.17549435e-38f;
+                    if (l >= 1 && r > prev) r = prev;
+                    sh.thr[l] = r;
+                    prev = r;
+                }
+            }
+        }
+        // the last prefix pick (position m) is not folded yet
+        if (wh.tid == 0) {
+            Cand c0;
+            c0.idx = 0;
+            c0.x = lx;
+            c0.y = ly;
+            c0.z = lz;
+            sh.pend[0] = c0;
+            sh.pend_pos[0] = m;
+        }
+        __syncthreads();
+        npend = 1;
+        int seg = 0;
+
+        // ---- threshold sampling (Alg. 2 lines 24-37), running-distance form
+        while (i < n) {
+            const int q = 1 + (int)(((int64_t)i * a.nseg) / n);
+            if (q > seg) {
+                seg = q;
+                if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = i;
+            }
+            fold_pending<T, P, BQ>(pt, sh, wh, a, npend);   // picks accepted since the last sweep
+            npend = 0;
+            const float r2 = sh.thr[seg - 1];
+            // samples of this level end where the quota rule would raise the level
+            const int64_t qend = ((int64_t)n * seg + a.nseg - 1) / a.nseg;
+            const int limit = (int)((qend < n ? qend : n) - i);
+            ++rounds;
+
+            // 1. how many of this wave's points are available
+            int cntw = 0;
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+                cntw += __builtin_popcountll(__builtin_amdgcn_ballot_w64(pt.d[p] >= r2));
+            if (wh.lane == 0) sh.wcnt[wh.w] = cntw;
+            __syncthreads();
+            int off = 0, tot = 0;
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                const int v = sh.wcnt[k];
+                off += (k < wh.w) ? v : 0;
+                tot += v;
+            }
+            // 2. the workgroup's first kCand available points, in index order
+            if (cntw > 0 && off < kCand) {
+                int base = off;
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    const bool av = pt.d[p] >= r2;
+                    const uint64_t mk = __builtin_amdgcn_ballot_w64(av);
+                    if (mk != 0 && base < kCand) {
+                        const int rank = base + lanes_below(mk);
+                        if (av && rank < kCand) {
+                            Cand cd;
+                            cd.idx = (uint32_t)(((wh.gw * P + p) << 6) | wh.lane);
+                            cd.x = pt.x[p];
+                            cd.y = pt.y[p];
+                            cd.z = pt.z[p];
+                            sh.cand[rank] = cd;
+                        }
+                        base += __builtin_popcountll(mk);
+                    }
+                }
+            }
+            __syncthreads();
+            int total = tot < kCand ? tot : kCand;
+
+            if (wh.G > 1) {
+                // 3. exchange: every workgroup publishes its candidates, all take the first
+                //    kCand of the cloud in workgroup (= index) order
+                ++seq;
+                const int par = (int)(seq & 1u);
+                uint64_t* pk = a.ll_pk + ((int64_t)(wh.grp * 2 + par) * wh.G) * kLlSlotWords;
+                uint64_t* cd = a.ll_cd + ((int64_t)(wh.grp * 2 + par) * wh.G) * (kCand * 4);
+                if (wh.tid < total * 4) {
+                    const int r = wh.tid >> 2, k = wh.tid & 3;
+                    const Cand cc = sh.cand[r];
+                    uint32_t v = cc.idx;
+                    v = k == 1 ? __float_as_uint(cc.x) : v;
+                    v = k == 2 ? __float_as_uint(cc.y) : v;
+                    v = k == 3 ? __float_as_uint(cc.z) : v;
+                    ll_store(cd + ((int64_t)wh.g * kCand + r) * 4 + k, v, seq);
+                }
+                if (wh.tid == 0) ll_store(pk + (int64_t)wh.g * kLlSlotWords + 5, (uint32_t)total, seq);
+                __syncthreads();          // sh.cand is about to be overwritten
+                if (wh.w == 0) {
+                    // lane t takes the counts of workgroups [t*per, (t+1)*per)
+                    const int per = (wh.G + 63) / 64;
+                    int sum = 0;
+                    bool bad = false;
+                    for (int k = 0; k < per; ++k) {
+                        const int t = wh.lane * per + k;
+                        if (t < wh.G) {
+                            uint32_t val[1];
+                            if (!ll_wait<1>(pk + (int64_t)t * kLlSlotWords + 5, seq, val, a.wait_ticks))
+                                bad = true;
+                            else
+                                sum += (int)val[0];
+                            sh.gpre[t + 1] = sum;      // inclusive inside the lane, fixed below
+                        }
+                    }
+                    int incl = sum;
+                    for (int s = 1; s < 64; s <<= 1) {
+                        const int up = __shfl_up(incl, s, 64);
+                        if (wh.lane >= s) incl += up;
+                    }
+                    const int excl = incl - sum;
+                    for (int k = 0; k < per; ++k) {
+                        const int t = wh.lane * per + k;
+                        if (t < wh.G) sh.gpre[t + 1] += excl;
+                    }
+                    if (wh.lane == 0) sh.gpre[0] = 0;
+                    if (__builtin_amdgcn_ballot_w64(bad) != 0 && wh.lane == 0) sh.ctrl[2] = 1;
+                }
+                __syncthreads();
+                const int alltot = sh.gpre[wh.G];
+                total = alltot < kCand ? alltot : kCand;
+                if (wh.tid < total * 4 && sh.ctrl[2] == 0) {
+                    const int r = wh.tid >> 2, k = wh.tid & 3;
+                    int lo = 0, hi = wh.G;             // workgroup whose range holds rank r
+                    while (hi - lo > 1) {
+                        const int mid = (lo + hi) >> 1;
+                        if (sh.gpre[mid] <= r) lo = mid;
+                        else hi = mid;
+                    }
+                    uint32_t val[1];
+                    val[0] = 0;
+                    const bool got = ll_wait<1>(cd + ((int64_t)lo * kCand + (r - sh.gpre[lo])) * 4 + k,
+                                                seq, val, a.wait_ticks);
+                    if (!got) sh.ctrl[2] = 1;
+                    uint32_t* dst = reinterpret_cast<uint32_t*>(&sh.cand[r]);
+                    dst[k] = val[0];
+                }
+                __syncthreads();
+                if (sh.ctrl[2] != 0) {
+                    ok = false;
+                    break;
+                }
+            }
+
+            if (total == 0) {              // level exhausted (Alg. 2 lines 34-36)
+                if (wh.tid == 0) sh.level_exhausted[seg - 1] = 1;
+                ++seg;
+                if (seg > a.nseg) break;   // early termination
+                if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = i;
+                continue;
+            }
+
+            // 4. resolve the candidates in index order: a candidate stays available iff no
+            //    pick accepted before it in this round lies closer than R_l
+            if (wh.w == 0) {
+                const bool has = wh.lane < total;
+                const Cand me = sh.cand[has ? wh.lane : 0];
+                uint64_t alive = __builtin_amdgcn_ballot_w64(has);
+                int nacc = 0;
+                while (alive != 0 && nacc < limit) {
+                    const int cl = first_lane(alive);
+                    const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
+                    const uint32_t aj = rdlane(me.idx, cl);
+                    if (wh.lane == 0) {
+                        Cand acc;
+                        acc.idx = aj;
+                        acc.x = ax;
+                        acc.y = ay;
+                        acc.z = az;
+                        sh.pend[nacc] = acc;
+                        sh.pend_pos[nacc] = i + nacc;
+                        if (wh.g == 0) write_pick<T, P, BQ>(a, wh, i + nacc, aj);
+                    }
+                    const float t = dist2(ax, ay, az, me.x, me.y, me.z);
+                    const uint64_t kill = __builtin_amdgcn_ballot_w64(t < r2);
+                    alive &= ~kill;
+                    alive &= ~(1ull << cl);
+                    ++nacc;
+                }
+                if (wh.lane == 0) sh.ctrl[0] = nacc;
+            }
+            __syncthreads();
+            npend = sh.ctrl[0];
+            const Cand lastp = sh.pend[npend - 1];
+            lx = lastp.x;
+            ly = lastp.y;
+            lz = lastp.z;
+            i += npend;
+        }
+
+        if (ok && i < n) {
+            // ---- early termination (Alg. 2 lines 39-53): dists is already the true running
+            //      minimum, so the remainder is plain FPS; its first fold repeats sample i-1
+            et_index = i;
+            ok = fps_iterations<T, P, BQ>(pt, sh, wh, a, it, seq, i, n, false, -1, writer, lx, ly, lz);
+            if (ok && BQ) fold<P, BQ>(pt, lx, ly, lz, a, wh, n - 1);
+        } else if (ok && BQ) {
+            fold_pending<T, P, BQ>(pt, sh, wh, a, npend);    // rows of the last picks
+        }
+    } else if (ok && BQ) {
+        // exact FPS: the last sample has not been folded, its row is still missing
+        fold<P, BQ>(pt, lx, ly, lz, a, wh, n - 1);
+    }
+
+    __syncthreads();
+    if (writer && a.info) {
+        fp_mdps_info inf = {};
+        inf.m = pure_fps ? n - 1 : m;
+        inf.et_index = et_index;
+        for (int l = 0; l < FP_MAX_SEG; ++l) {
+            inf.level_start[l] = sh.level_start[l];
+            inf.level_exhausted[l] = sh.level_exhausted[l];
+            inf.thr2[l] = sh.thr[l];
+        }
+        inf.rounds = rounds;
+        inf.status = ok ? 0 : 2;
+        a.info[wh.c] = inf;
+    }
+    if (!ok && wh.g == 0)
+        for (int k = wh.tid; k < n; k += T) a.out_idx[(int64_t)wh.c * n + k] = -1;
+    __syncthreads();
+}
+
+template <int T, int P, bool BQ>
+__global__ __launch_bounds__(T) void sampler_kernel(SamplerArgs a)
+{
+    __shared__ Shared<T> sh;
+    Where wh;
+    wh.tid = (int)threadIdx.x;
+    wh.lane = wh.tid & 63;
+    wh.w = wh.tid >> 6;
+    wh.G = a.G;
+    wh.grp = (int)blockIdx.x / a.G;
+    wh.g = (int)blockIdx.x % a.G;
+    wh.gw = wh.g * (T / 64) + wh.w;
+    const int ngroups = (int)gridDim.x / a.G;
+    uint32_t it = 0, seq = 0;
+    for (int c = wh.grp; c < a.B; c += ngroups) {
+        wh.c = c;
+        run_cloud<T, P, BQ>(a, sh, wh, it, seq);
+    }
+}
+
+// zeroes the exchange words before a launch (stamps start at 1 in every launch)
+__global__ void zero_words_kernel(uint64_t* p, int64_t nwords)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < nwords; i += stride) p[i] = 0;
+}
+
+template <int T, int P>
+const void* pick_bq(bool bq)
+{
+    return bq ? reinterpret_cast<const void*>(&sampler_kernel<T, P, true>)
+              : reinterpret_cast<const void*>(&sampler_kernel<T, P, false>);
+}
+
+}  // namespace
+
+const void* sampler_kernel_for(int threads, int points_per_thread, bool bq)
+{
+    if (threads == 256) {
+        switch (points_per_thread) {
+            case 2: return pick_bq<256, 2>(bq);
+            case 4: return pick_bq<256, 4>(bq);
+            case 8: return pick_bq<256, 8>(bq);
+            case 16: return pick_bq<256, 16>(bq);
+            case 32: return pick_bq<256, 32>(bq);
+            default: return nullptr;
+        }
+    }
+    return nullptr;
+}
+
+hipError_t launch_zero_words(uint64_t* p, int64_t nwords, hipStream_t stream)
+{
+    if (nwords <= 0) return hipSuccess;
+    int blocks = (int)((nwords + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(zero_words_kernel, dim3(blocks), dim3(256), 0, stream, p, nwords);
+    return hipGetLastError();
+}
+
+}  // namespace fastpoint

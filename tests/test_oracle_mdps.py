@@ -38,6 +38,20 @@ def test_line_examples_match_hand_derivation():
 
 
 # ------------------------------------------------------------------ estimator
+def test_series_power_function_agrees_with_libm():
+    # the fixed-order series is pinned to the library routine it replaces
+    rng = np.random.Generator(np.random.PCG64(7))
+    xs = [1, 2, 3, 5, 7, 8, 9, 10, 63, 64, 65, 1000, 65535, 65536, 10 ** 6, 2 ** 31 - 1]
+    xs += rng.integers(1, 2 ** 31, 200).tolist()
+    for x in xs:
+        for e in (-1.5, -0.3, 0.0, 0.5, 2.0 / 3.0, 0.8586, 1.0, 1.2069, 2.0, 3.25):
+            got = ref.pow_int_base(x, e)
+            want = math.pow(float(x), e)
+            assert abs(got - want) <= 2e-14 * want, (x, e, got, want)
+    assert ref.pow_int_base(1, 0.77) == 1.0
+    assert ref.pow_int_base(4, 1.0) == 4.0
+
+
 @pytest.mark.parametrize("e", [1.0, 0.5, 0.75])
 def test_estimator_recovers_exact_power_law(e):
     # If the measured prefix IS a power law a0/x^e, the predicted curve is that law.
