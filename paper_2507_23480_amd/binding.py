@@ -1,0 +1,254 @@
+"""Thin Python binding of the C ABI in include/fastpoint.h.
+
+Argument marshalling only: tensors in, tensors out, every step of the path runs
+in the HIP library.  PyTorch supplies device memory and the current stream.
+There is no CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import dataclasses
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
+MAX_SEG = 16
+
+EXPORTS = ["fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
+           "fp_ball_query", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
+           "fp_set_wait_limit_us", "fp_status_string"]
+
+
+class FpMdpsParams(ctypes.Structure):
+    _fields_ = [("p", ctypes.c_float), ("nseg", ctypes.c_int32), ("exponent", ctypes.c_double),
+                ("bias", ctypes.c_float), ("fit_window", ctypes.c_int32), ("m_min", ctypes.c_int32),
+                ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG)]
+
+
+class FpMdpsInfo(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_int32), ("et_index", ctypes.c_int32),
+                ("level_start", ctypes.c_int32 * MAX_SEG),
+                ("level_exhausted", ctypes.c_int32 * MAX_SEG),
+                ("thr2", ctypes.c_float * MAX_SEG),
+                ("rounds", ctypes.c_int32), ("status", ctypes.c_int32)]
+
+
+INFO_BYTES = ctypes.sizeof(FpMdpsInfo)
+
+
+@dataclasses.dataclass
+class MdpsParams:
+    """MDPS hyper-parameters (paper defaults p = 0.1, nseg = 6; exponent and bias are
+    fitted per workload, see calibration.py)."""
+    p: float = 0.1
+    nseg: int = 6
+    exponent: float = 1.0
+    bias: float = 1.0
+    fit_window: int = 32
+    m_min: int = 8
+    thr_override: Optional[Sequence[float]] = None
+
+    def to_c(self) -> FpMdpsParams:
+        c = FpMdpsParams()
+        c.p, c.nseg, c.exponent, c.bias = self.p, self.nseg, self.exponent, self.bias
+        c.fit_window, c.m_min = self.fit_window, self.m_min
+        c.use_override = 0
+        if self.thr_override is not None:
+            if len(self.thr_override) != self.nseg:
+                raise ValueError("thr_override needs nseg values")
+            c.use_override = 1
+            for i, v in enumerate(self.thr_override):
+                c.thr_override[i] = v
+        return c
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Loads libfastpoint_hip.so (built by build.py); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("HIP library not built: %s is missing (run paper_2507_23480_amd/build.py)"
+                           % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
+    lib.fp_workspace_bytes.argtypes = [i32, i32]
+    lib.fp_workspace_bytes.restype = ctypes.c_size_t
+    lib.fp_bq_cache_bytes.argtypes = [i32, i32, i32]
+    lib.fp_bq_cache_bytes.restype = ctypes.c_size_t
+    lib.fp_fps_exact.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, f32, vp, ctypes.c_size_t, vp]
+    lib.fp_fps_exact.restype = i32
+    lib.fp_mdps_sample.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(FpMdpsParams), vp, vp, vp, f32,
+                                   vp, ctypes.c_size_t, vp]
+    lib.fp_mdps_sample.restype = i32
+    lib.fp_ball_query.argtypes = [vp, i32, i32, vp, i32, f32, i32, vp, vp, vp, vp]
+    lib.fp_ball_query.restype = i32
+    lib.fp_gather_xyz.argtypes = [vp, i32, i32, vp, i32, vp, vp]
+    lib.fp_gather_xyz.restype = i32
+    lib.fp_coverage.argtypes = [vp, i32, i32, vp, i32, vp, vp]
+    lib.fp_coverage.restype = i32
+    lib.fp_plan.argtypes = [i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.fp_plan.restype = i32
+    lib.fp_set_wg_per_cloud.argtypes = [i32]
+    lib.fp_set_wg_per_cloud.restype = None
+    lib.fp_set_wait_limit_us.argtypes = [ctypes.c_int64]
+    lib.fp_set_wait_limit_us.restype = None
+    lib.fp_status_string.argtypes = [i32]
+    lib.fp_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise RuntimeError("%s failed: %s" % (what, load().fp_status_string(status).decode()))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _xyz(xyz: torch.Tensor) -> Tuple[int, int]:
+    if not (xyz.is_cuda and xyz.dtype == torch.float32 and xyz.dim() == 3 and xyz.shape[2] == 3
+            and xyz.is_contiguous()):
+        raise ValueError("xyz must be a contiguous CUDA float32 tensor [B][N][3]")
+    return int(xyz.shape[0]), int(xyz.shape[1])
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def plan(B: int, N: int) -> Tuple[int, int, int]:
+    """(workgroups per cloud, threads per workgroup, points per thread) for B clouds of N points."""
+    g, t, p = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(load().fp_plan(B, N, ctypes.byref(g), ctypes.byref(t), ctypes.byref(p)), "fp_plan")
+    return g.value, t.value, p.value
+
+
+def set_wg_per_cloud(g: int) -> None:
+    load().fp_set_wg_per_cloud(int(g))
+
+
+def set_wait_limit_us(us: int) -> None:
+    load().fp_set_wait_limit_us(int(us))
+
+
+_workspaces = {}
+
+
+def workspace(device: torch.device, B: int, N: int) -> torch.Tensor:
+    """A cached per-device workspace tensor (calls on one device must not overlap)."""
+    need = int(load().fp_workspace_bytes(B, N))
+    key = (device.type, device.index)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < need:
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
+    return ws
+
+
+def new_bq_cache(xyz: torch.Tensor, n: int) -> torch.Tensor:
+    B, N = _xyz(xyz)
+    need = int(load().fp_bq_cache_bytes(B, N, n))
+    if need == 0:
+        raise ValueError("bad shape for a ball-query cache")
+    return torch.empty(need, dtype=torch.uint8, device=xyz.device)
+
+
+def _start(start_idx, B, device) -> Optional[torch.Tensor]:
+    if start_idx is None:
+        return None
+    if isinstance(start_idx, torch.Tensor):
+        t = start_idx.to(device=device, dtype=torch.int32).contiguous()
+    else:
+        t = torch.as_tensor(start_idx, dtype=torch.int32, device=device).reshape(-1).contiguous()
+    if t.numel() != B:
+        raise ValueError("start_idx needs one entry per cloud")
+    return t
+
+
+def fps_exact(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool = False,
+              want_info: bool = False, bq_cache: Optional[torch.Tensor] = None,
+              bq_radius: float = 0.0):
+    """Exact farthest point sampling.  Returns idx [B][n] int32 (and mdc [B][n] float32,
+    info bytes [B][INFO_BYTES] uint8 when asked for)."""
+    B, N = _xyz(xyz)
+    st = _start(start_idx, B, xyz.device)
+    idx = torch.empty((B, n), dtype=torch.int32, device=xyz.device)
+    mdc = torch.empty((B, n), dtype=torch.float32, device=xyz.device) if want_mdc else None
+    info = torch.zeros((B, INFO_BYTES), dtype=torch.uint8, device=xyz.device) if want_info else None
+    ws = workspace(xyz.device, B, N)
+    _check(load().fp_fps_exact(xyz.data_ptr(), B, N, n, _ptr(st), idx.data_ptr(), _ptr(mdc), _ptr(info),
+                               _ptr(bq_cache), float(bq_radius), ws.data_ptr(), ws.numel(), _stream()),
+           "fp_fps_exact")
+    out = [idx]
+    if want_mdc:
+        out.append(mdc)
+    if want_info:
+        out.append(info)
+    return out[0] if len(out) == 1 else tuple(out)
+
+
+def mdps_sample(xyz: torch.Tensor, n: int, prm: MdpsParams, start_idx=None, want_info: bool = False,
+                bq_cache: Optional[torch.Tensor] = None, bq_radius: float = 0.0):
+    """Minimum distance prediction sampling.  Returns idx [B][n] int32 (and info bytes)."""
+    B, N = _xyz(xyz)
+    st = _start(start_idx, B, xyz.device)
+    idx = torch.empty((B, n), dtype=torch.int32, device=xyz.device)
+    info = torch.zeros((B, INFO_BYTES), dtype=torch.uint8, device=xyz.device) if want_info else None
+    ws = workspace(xyz.device, B, N)
+    c = prm.to_c()
+    _check(load().fp_mdps_sample(xyz.data_ptr(), B, N, n, _ptr(st), ctypes.byref(c), idx.data_ptr(),
+                                 _ptr(info), _ptr(bq_cache), float(bq_radius), ws.data_ptr(), ws.numel(),
+                                 _stream()), "fp_mdps_sample")
+    return (idx, info) if want_info else idx
+
+
+def ball_query(xyz: torch.Tensor, center_idx: torch.Tensor, radius: float, k: int,
+               bq_cache: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Ball query: (idx [B][M][k] int32, cnt [B][M] int32)."""
+    B, N = _xyz(xyz)
+    if not (center_idx.is_cuda and center_idx.dtype == torch.int32 and center_idx.dim() == 2
+            and center_idx.shape[0] == B and center_idx.is_contiguous()):
+        raise ValueError("center_idx must be a contiguous CUDA int32 tensor [B][M]")
+    M = int(center_idx.shape[1])
+    idx = torch.empty((B, M, k), dtype=torch.int32, device=xyz.device)
+    cnt = torch.empty((B, M), dtype=torch.int32, device=xyz.device)
+    _check(load().fp_ball_query(xyz.data_ptr(), B, N, center_idx.data_ptr(), M, float(radius), k,
+                                idx.data_ptr(), cnt.data_ptr(), _ptr(bq_cache), _stream()),
+           "fp_ball_query")
+    return idx, cnt
+
+
+def gather_xyz(xyz: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
+    B, N = _xyz(xyz)
+    M = int(idx.shape[1])
+    out = torch.empty((B, M, 3), dtype=torch.float32, device=xyz.device)
+    _check(load().fp_gather_xyz(xyz.data_ptr(), B, N, idx.data_ptr(), M, out.data_ptr(), _stream()),
+           "fp_gather_xyz")
+    return out
+
+
+def coverage2(xyz: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
+    """Squared coverage radius per cloud, [B] float32: max over points of the squared
+    distance to the nearest sample."""
+    B, N = _xyz(xyz)
+    s = gather_xyz(xyz, idx)
+    out = torch.empty(B, dtype=torch.float32, device=xyz.device)
+    _check(load().fp_coverage(xyz.data_ptr(), B, N, s.data_ptr(), int(idx.shape[1]), out.data_ptr(),
+                              _stream()), "fp_coverage")
+    return out
+
+
+def parse_info(info: torch.Tensor):
+    """Host copies of the per-cloud info records as FpMdpsInfo structures."""
+    raw = info.cpu().numpy().tobytes()
+    return [FpMdpsInfo.from_buffer_copy(raw[i * INFO_BYTES:(i + 1) * INFO_BYTES])
+            for i in range(info.shape[0])]

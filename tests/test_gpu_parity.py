@@ -1,0 +1,242 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through
+the C ABI (via the thin binding).  Index outputs and the binary32 curve must be
+bit-exact.  Sizes here finish in seconds on the oracle yet span several tiles,
+several workgroups per cloud and ragged tails."""
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2507_23480_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fp():
+    from paper_2507_23480_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    binding.set_wg_per_cloud(0)
+    yield binding
+    binding.set_wg_per_cloud(0)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def oracle_batch(fn, batch, *args):
+    """Runs an oracle function on every cloud of a batch (threads: ctypes drops the GIL)."""
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        return list(ex.map(lambda c: fn(c, *args), list(batch)))
+
+
+def rparams(prm):
+    return ref.MdpsParams(p=prm.p, nseg=prm.nseg, exponent=prm.exponent, bias=prm.bias,
+                          fit_window=prm.fit_window, m_min=prm.m_min, thr_override=prm.thr_override)
+
+
+def check_fps(fp, batch, n, start=None, G=0):
+    fp.set_wg_per_cloud(G)
+    try:
+        xyz = dev(batch)
+        B = batch.shape[0]
+        starts = [0] * B if start is None else list(start)
+        idx, mdc, info = fp.fps_exact(xyz, n, start_idx=None if start is None else starts,
+                                      want_mdc=True, want_info=True)
+        torch.cuda.synchronize()
+        idx, mdc = idx.cpu().numpy(), mdc.cpu().numpy()
+        infos = fp.parse_info(info)
+        want = [ref.fps_exact(batch[b], n, starts[b]) for b in range(B)]
+        for b in range(B):
+            assert infos[b].status == 0
+            assert np.array_equal(idx[b], want[b][0]), "fps idx cloud %d" % b
+            assert np.array_equal(mdc[b], want[b][1]), "fps curve cloud %d" % b
+    finally:
+        fp.set_wg_per_cloud(0)
+
+
+def check_mdps(fp, batch, n, prm, start=None, G=0):
+    fp.set_wg_per_cloud(G)
+    try:
+        xyz = dev(batch)
+        B = batch.shape[0]
+        starts = [0] * B if start is None else list(start)
+        idx, info = fp.mdps_sample(xyz, n, prm, start_idx=None if start is None else starts,
+                                   want_info=True)
+        torch.cuda.synchronize()
+        idx = idx.cpu().numpy()
+        infos = fp.parse_info(info)
+        rp = rparams(prm)
+        for b in range(B):
+            widx, winfo = ref.mdps_sample(batch[b], n, rp, starts[b])
+            gi = infos[b]
+            assert gi.status == 0
+            assert np.array_equal(np.array(gi.thr2[:prm.nseg], np.float32), winfo.thr2) or gi.m >= n - 1, \
+                "thresholds cloud %d" % b
+            assert np.array_equal(idx[b], widx), "mdps idx cloud %d" % b
+            assert gi.m == winfo.m and gi.et_index == winfo.et_index
+            if gi.m < n - 1:
+                assert list(gi.level_start[:prm.nseg]) == winfo.level_start.tolist()
+                assert list(gi.level_exhausted[:prm.nseg]) == winfo.level_exhausted.tolist()
+    finally:
+        fp.set_wg_per_cloud(0)
+
+
+# ----------------------------------------------------------------------------- FPS
+@pytest.mark.parametrize("N,n,G", [(9, 9, 0), (64, 64, 0), (257, 100, 0), (1000, 250, 0), (4096, 1024, 0),
+                                   (4097, 512, 0), (9000, 300, 0), (9000, 300, 1), (9000, 300, 2),
+                                   (20000, 400, 0), (20000, 400, 7), (33000, 200, 0)])
+def test_fps_matches_oracle_single_cloud(fp, N, n, G):
+    say("fps N=%d n=%d G=%d" % (N, n, G))
+    batch = inputs.uniform_cube(100 + N, N)[None]
+    check_fps(fp, batch, n, G=G)
+
+
+def test_fps_line_example_and_ties(fp):
+    line = np.zeros((1, 9, 3), np.float32)
+    line[0, :, 0] = np.arange(9)
+    check_fps(fp, line, 9)
+    for seed in (11, 12):
+        check_fps(fp, inputs.lattice_with_ties(seed, 500, 4)[None], 300, start=[3])
+    check_fps(fp, np.ones((1, 10, 3), np.float32), 5, start=[4])      # all points identical
+
+
+def test_fps_batches_and_start_indices(fp):
+    say("fps C2 batch")
+    batch = inputs.make_batch("C2")
+    check_fps(fp, batch, 512)
+    check_fps(fp, batch, 512, start=[(37 * b) % 1024 for b in range(16)])
+    say("fps batch of 300 small clouds (more clouds than resident workgroups)")
+    many = np.stack([inputs.uniform_cube(500 + b, 200) for b in range(300)])
+    check_fps(fp, many, 50)
+
+
+def test_fps_bad_start_index_gives_minus_one(fp):
+    batch = np.stack([inputs.uniform_cube(7, 300), inputs.uniform_cube(8, 300)])
+    idx, info = fp.fps_exact(dev(batch), 20, start_idx=[300, 5], want_info=True)
+    torch.cuda.synchronize()
+    idx = idx.cpu().numpy()
+    assert np.all(idx[0] == -1)
+    assert np.array_equal(idx[1], ref.fps_exact(batch[1], 20, 5)[0])
+    assert fp.parse_info(info)[0].status == 1
+
+
+# ---------------------------------------------------------------------------- MDPS
+@pytest.mark.parametrize("N,n,G,nseg,e,bias", [
+    (400, 100, 0, 6, 0.8, 1.0), (400, 100, 0, 6, 0.8, 1.3), (400, 100, 0, 6, 0.8, 0.7),
+    (4096, 1024, 0, 6, 0.8586, 1.04), (4096, 1024, 0, 1, 0.8586, 1.0), (4096, 1024, 0, 16, 0.8586, 1.1),
+    (4097, 700, 0, 6, 0.8, 1.0), (9000, 2000, 2, 6, 0.8, 1.05), (9000, 2000, 3, 6, 0.8, 0.9),
+    (20000, 5000, 0, 6, 0.8, 1.04), (20000, 5000, 7, 4, 0.8, 1.2), (300, 9, 0, 6, 1.0, 1.0)])
+def test_mdps_matches_oracle_single_cloud(fp, N, n, G, nseg, e, bias):
+    say("mdps N=%d n=%d G=%d nseg=%d e=%g bias=%g" % (N, n, G, nseg, e, bias))
+    batch = inputs.uniform_cube(200 + N, N)[None]
+    check_mdps(fp, batch, n, fp.MdpsParams(nseg=nseg, exponent=e, bias=bias), G=G)
+
+
+def test_mdps_line_examples_ties_and_overrides(fp):
+    line = np.zeros((1, 9, 3), np.float32)
+    line[0, :, 0] = np.arange(9)
+    check_mdps(fp, line, 5, fp.MdpsParams(p=0.2, nseg=1, m_min=1, thr_override=[3.0]))
+    check_mdps(fp, line, 5, fp.MdpsParams(p=0.2, nseg=1, m_min=1, thr_override=[4.0]))
+    check_mdps(fp, line, 6, fp.MdpsParams(p=0.2, nseg=2, m_min=1, thr_override=[10.0, 2.0]))
+    lat = inputs.lattice_with_ties(7, 600, 5)[None]
+    check_mdps(fp, lat, 200, fp.MdpsParams(exponent=0.8, bias=1.0), start=[5])
+    check_mdps(fp, lat, 200, fp.MdpsParams(nseg=3, thr_override=[float("inf")] * 3))   # == exact FPS
+    check_mdps(fp, lat, 200, fp.MdpsParams(nseg=1, thr_override=[1.17549435e-38]))
+
+
+def test_mdps_batches(fp):
+    say("mdps C2 batch")
+    batch = inputs.make_batch("C2")
+    check_mdps(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.1))
+    check_mdps(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.0),
+               start=[(91 * b) % 1024 for b in range(16)])
+
+
+# ---------------------------------------------------------------------- ball query
+def check_ball_query(fp, batch, centers, radius, k, cache=None):
+    xyz = dev(batch)
+    cidx = dev(centers.astype(np.int32))
+    idx, cnt = fp.ball_query(xyz, cidx, radius, k, bq_cache=cache)
+    torch.cuda.synchronize()
+    idx, cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+    for b in range(batch.shape[0]):
+        widx, wcnt = ref.ball_query(batch[b], centers[b], radius, k)
+        assert np.array_equal(cnt[b], wcnt), "ball query counts cloud %d" % b
+        assert np.array_equal(idx[b], widx), "ball query indices cloud %d" % b
+    return idx, cnt
+
+
+@pytest.mark.parametrize("N,M,radius,k", [(9, 9, 2.5, 4), (300, 300, 0.2, 8), (1000, 77, 0.15, 32),
+                                          (4096, 1024, 0.1, 32), (4099, 1030, 0.1, 5), (5000, 500, 2.0, 64)])
+def test_ball_query_brute_matches_oracle(fp, N, M, radius, k):
+    say("bq N=%d M=%d r=%g k=%d" % (N, M, radius, k))
+    if N == 9:
+        cloud = np.zeros((9, 3), np.float32)
+        cloud[:, 0] = np.arange(9)
+    else:
+        cloud = inputs.uniform_cube(300 + N, N)
+    centers = np.random.Generator(np.random.PCG64(N)).integers(0, N, (1, M))
+    check_ball_query(fp, cloud[None], centers, radius, k)
+
+
+def test_ball_query_out_of_range_centre(fp):
+    cloud = inputs.uniform_cube(5, 100)[None]
+    idx, cnt = fp.ball_query(dev(cloud), dev(np.array([[3, 100, -1]], np.int32)), 0.3, 4)
+    torch.cuda.synchronize()
+    idx, cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+    assert np.all(idx[0, 1:] == -1) and cnt[0, 1] == 0 and cnt[0, 2] == 0
+    w, wc = ref.ball_query(cloud[0], [3], 0.3, 4)
+    assert np.array_equal(idx[0, 0], w[0]) and cnt[0, 0] == wc[0]
+
+
+@pytest.mark.parametrize("sampler", ["fps", "mdps"])
+@pytest.mark.parametrize("N,n,G,radius,k", [(4096, 1024, 0, 0.1, 32), (9001, 1500, 3, 0.12, 16),
+                                            (700, 700, 0, 0.3, 8)])
+def test_cached_ball_query_equals_brute_force(fp, sampler, N, n, G, radius, k):
+    # Section 4.2: reading the radius tests recorded during sampling changes nothing
+    say("cached bq %s N=%d n=%d G=%d" % (sampler, N, n, G))
+    cloud = inputs.uniform_cube(400 + N, N)[None]
+    xyz = dev(cloud)
+    fp.set_wg_per_cloud(G)
+    try:
+        cache = fp.new_bq_cache(xyz, n)
+        if sampler == "fps":
+            idx = fp.fps_exact(xyz, n, bq_cache=cache, bq_radius=radius)
+        else:
+            idx = fp.mdps_sample(xyz, n, fp.MdpsParams(exponent=0.8, bias=1.05), bq_cache=cache,
+                                 bq_radius=radius)
+    finally:
+        fp.set_wg_per_cloud(0)
+    torch.cuda.synchronize()
+    centers = idx.cpu().numpy()
+    got, gcnt = check_ball_query(fp, cloud, centers, radius, k, cache=cache)
+    brute, bcnt = fp.ball_query(xyz, idx, radius, k)
+    torch.cuda.synchronize()
+    assert np.array_equal(got, brute.cpu().numpy()) and np.array_equal(gcnt, bcnt.cpu().numpy())
+    # centres that are not the cached samples, and another radius, fall back to brute force
+    other = np.random.Generator(np.random.PCG64(1)).integers(0, N, (1, 64))
+    check_ball_query(fp, cloud, other, radius, k, cache=cache)
+    check_ball_query(fp, cloud, centers[:, :50], radius * 1.5, k, cache=cache)
+
+
+def test_gather_and_coverage(fp):
+    batch = inputs.make_batch("C2", B=3)
+    idx = np.stack([ref.fps_exact(batch[b], 64)[0] for b in range(3)])
+    g = fp.gather_xyz(dev(batch), dev(idx))
+    cov = fp.coverage2(dev(batch), dev(idx))
+    torch.cuda.synchronize()
+    for b in range(3):
+        assert np.array_equal(g.cpu().numpy()[b], ref.gather_xyz(batch[b], idx[b]))
+        want = ref.coverage_radius(batch[b], idx[b])
+        assert abs(float(cov[b].sqrt()) - want) <= 1e-5 * want
