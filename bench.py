@@ -1,0 +1,291 @@
+#!/usr/bin/env python3
+"""Benchmark of the FPS / MDPS / ball-query hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of the workload, for
+every stage of its hierarchy:
+    exact path   fps_exact -> ball_query (brute force)          (Alg. 1 + Section 3.1)
+    FastPoint    mdps_sample (records the radius tests) -> ball_query (cache reader)
+                                                                (Alg. 2 + Section 4.2)
+    gather of the exact-FPS samples = input of the next stage
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-extra]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# Non-FMA, non-packed fp32 vector rate of MI355X: 256 CUs x 64 lanes x 2.4 GHz.  The
+# published 157.3 TFLOP/s counts an FMA as two flops and the packed dual-rate form;
+# this path may use neither (every operation is rounded on its own), hence 157.3 / 4.
+ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+HBM_PEAK_GBS = 8000.0
+OPS_PER_POINT_ITERATION = 10      # 3 sub, 3 mul, 2 add, 1 min, 1 compare (FPS min-update + arg-max)
+OPS_PER_PAIR_TEST = 9             # 3 sub, 3 mul, 2 add, 1 compare (ball query)
+
+# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); bytes, keyed by workload.  None where no counter run is recorded.
+TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--no-extra", action="store_true", help="skip the other workloads' summary")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+class Timer:
+    """Average duration of named calls, measured with events on the stream they run on."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.pending = []
+        self.acc = {}
+
+    def call(self, name, fn):
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        a.record()
+        out = fn()
+        b.record()
+        self.pending.append((name, a, b))
+        return out
+
+    def collect(self):
+        for name, a, b in self.pending:
+            t, c = self.acc.get(name, (0.0, 0))
+            self.acc[name] = (t + a.elapsed_time(b), c + 1)
+        self.pending = []
+
+    def reset(self):
+        self.pending, self.acc = [], {}
+
+    def mean_ms(self):
+        return {k: t / c for k, (t, c) in self.acc.items()}
+
+
+def make_context(torch, fp, inputs, calibration, name):
+    wl = inputs.WORKLOADS[name]
+    xyz = torch.from_numpy(inputs.make_batch(name)).cuda()
+    stages = []
+    x = xyz
+    for s, st in enumerate(wl.stages):
+        stages.append({"xyz": x, "n": st.n, "radius": st.radius, "k": st.k,
+                       "prm": calibration.params_for(name, s),
+                       "cache": fp.new_bq_cache(x, st.n)})
+        if s + 1 < len(wl.stages):
+            x = fp.gather_xyz(x, fp.fps_exact(x, st.n)).contiguous()
+    torch.cuda.synchronize()
+    return {"wl": wl, "stages": stages}
+
+
+def run_step(fp, ctx, timer, keep=None):
+    for s, sg in enumerate(ctx["stages"]):
+        x, n, r, k = sg["xyz"], sg["n"], sg["radius"], sg["k"]
+        idx = timer.call("fps_exact/s%d" % s, lambda: fp.fps_exact(x, n))
+        bq = timer.call("ball_query_brute/s%d" % s, lambda: fp.ball_query(x, idx, r, k))
+        midx = timer.call("mdps_sample+record/s%d" % s,
+                          lambda: fp.mdps_sample(x, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r))
+        mbq = timer.call("ball_query_cached/s%d" % s,
+                         lambda: fp.ball_query(x, midx, r, k, bq_cache=sg["cache"]))
+        if s + 1 < len(ctx["stages"]):
+            timer.call("gather/s%d" % s, lambda: fp.gather_xyz(x, idx))
+        if keep is not None:
+            keep.append((idx, bq, midx, mbq))
+
+
+def measure(torch, fp, ctx, steps, warmup):
+    timer = Timer(torch)
+    for _ in range(warmup):
+        run_step(fp, ctx, timer)
+    torch.cuda.synchronize()
+    timer.reset()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run_step(fp, ctx, timer)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    timer.collect()
+    return (t1 - t0) * 1e3 / steps, timer.mean_ms()
+
+
+def cached_words_read(torch, ctx, s, outs):
+    """64-bit words the cache reader has to read: per centre, whole 64-word blocks up to
+    the block holding its k-th hit (the whole row when it has fewer than k hits)."""
+    sg = ctx["stages"][s]
+    N, k = sg["xyz"].shape[1], sg["k"]
+    nwords = (N + 63) // 64
+    idx, cnt = outs
+    last = idx[:, :, k - 1].to(torch.int64) // 64 + 1
+    need = torch.where(cnt >= k, last, torch.full_like(last, nwords))
+    blocks = (need + 63) // 64
+    return int(torch.minimum(blocks * 64, torch.full_like(blocks, ((nwords + 63) // 64) * 64)).sum().item())
+
+
+def quality_and_rooflines(torch, fp, ctx, kernel_ms):
+    """Sampling quality of MDPS against exact FPS and achieved fraction of the binding
+    roofline of every kernel of the step (stage 0 is where the time goes)."""
+    timer = Timer(torch)
+    keep = []
+    run_step(fp, ctx, timer, keep)
+    torch.cuda.synchronize()
+    wl = ctx["wl"]
+    out = {"stages": []}
+    for s, sg in enumerate(ctx["stages"]):
+        x, n, k = sg["xyz"], sg["n"], sg["k"]
+        B, N = x.shape[0], x.shape[1]
+        idx, bq, midx, mbq = keep[s]
+        _, info = fp.mdps_sample(x, n, sg["prm"], want_info=True)
+        cov_f = fp.coverage2(x, idx).sqrt()
+        cov_m = fp.coverage2(x, midx).sqrt()
+        torch.cuda.synchronize()
+        infos = fp.parse_info(info)
+        ratio = (cov_m / cov_f)
+        brute_m = fp.ball_query(x, midx, sg["radius"], k)
+        torch.cuda.synchronize()
+        cached_equal = bool(torch.equal(brute_m[0], mbq[0]) and torch.equal(brute_m[1], mbq[1]))
+        ms = {key.split("/")[0]: v for key, v in kernel_ms.items() if key.endswith("/s%d" % s)}
+        point_iters = float(B) * (n - 1) * N
+        pairs = float(B) * n * N
+        roof = {}
+        if "fps_exact" in ms:
+            a = point_iters * OPS_PER_POINT_ITERATION / (ms["fps_exact"] * 1e-3) / 1e12
+            roof["fps_exact"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
+                                 "frac": a / ALU_PEAK_TOPS, "us_per_iteration": ms["fps_exact"] * 1e3 / max(n - 1, 1)}
+        if "mdps_sample+record" in ms:
+            a = point_iters * OPS_PER_POINT_ITERATION / (ms["mdps_sample+record"] * 1e-3) / 1e12
+            roof["mdps_sample+record"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS,
+                                          "unit": "TFLOP/s", "frac": a / ALU_PEAK_TOPS}
+        if "ball_query_brute" in ms:
+            a = pairs * OPS_PER_PAIR_TEST / (ms["ball_query_brute"] * 1e-3) / 1e12
+            roof["ball_query_brute"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS,
+                                        "unit": "TFLOP/s", "frac": a / ALU_PEAK_TOPS}
+        if "ball_query_cached" in ms:
+            byts = cached_words_read(torch, ctx, s, mbq) * 8 + float(B) * n * k * 4
+            a = byts / (ms["ball_query_cached"] * 1e-3) / 1e9
+            roof["ball_query_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": a / HBM_PEAK_GBS, "bytes": byts}
+        out["stages"].append({
+            "N": N, "n": n, "radius": sg["radius"], "k": k, "plan_G_T_P": list(fp.plan(B, N)),
+            "kernel_ms": ms,
+            "mdps_coverage_ratio_max": float(ratio.max()), "mdps_coverage_ratio_mean": float(ratio.mean()),
+            "mdps_fps_tail_fraction_mean": float(sum((n - i.et_index) / n for i in infos) / len(infos)),
+            "mdps_prefix_fraction": float(infos[0].m / n),
+            "mdps_rounds_mean": float(sum(i.rounds for i in infos) / len(infos)),
+            "mdps_last_level_exhausted": int(sum(1 for i in infos if i.et_index < n)),
+            "mdps_speedup_vs_fps": ms.get("fps_exact", 0.0) / ms["mdps_sample+record"] if ms.get("mdps_sample+record") else None,
+            "cached_ball_query_equals_brute": cached_equal,
+            "roofline": roof})
+    return out
+
+
+def cpu_baseline(inputs, name, budget_s=12.0):
+    """The CPU oracle, as it stands, on the same workload (one thread)."""
+    import numpy as np
+    from oracle import ref
+    from paper_2507_23480_amd import calibration
+    wl = inputs.WORKLOADS[name]
+    batch = inputs.make_batch(name)
+    done_points = 0
+    passes = 0
+    clouds = 0
+    t0 = time.perf_counter()
+    while True:
+        for b in range(wl.B):
+            x = batch[b]
+            for s, st in enumerate(wl.stages):
+                ent = calibration.table()[name][s]
+                prm = ref.MdpsParams(p=calibration.P_RATIO, nseg=calibration.NSEG, exponent=ent["exponent"],
+                                     bias=ent["bias"], fit_window=calibration.FIT_WINDOW,
+                                     m_min=calibration.M_MIN, level_scale=ent["level_scale"])
+                idx, _ = ref.fps_exact(x, st.n)
+                ref.ball_query(x, idx, st.radius, st.k)
+                midx, _ = ref.mdps_sample(x, st.n, prm)
+                ref.ball_query(x, midx, st.radius, st.k)
+                if s + 1 < len(wl.stages):
+                    x = ref.gather_xyz(x, idx)
+            done_points += wl.N
+            clouds += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
+        passes += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": done_points / dt / 1e6, "unit": "Mpoints/s", "cores": 1, "kind": "oracle",
+            "sample": "%d clouds of workload %s (all stages, same step as the GPU: fps_exact, ball_query, "
+                      "mdps_sample, ball_query) in %.1f s" % (clouds, name, dt),
+            "ms_per_batch_equivalent": dt * 1e3 / clouds * wl.B}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, "
+              "no sharding across devices in this library)" % args.gpus, file=sys.stderr)
+        return 2
+    import torch
+    from paper_2507_23480_amd import binding as fp, inputs, calibration
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    fp.load()
+    name = args.workload
+    ctx = make_context(torch, fp, inputs, calibration, name)
+    ms_per_step, kernel_ms = measure(torch, fp, ctx, args.steps, args.warmup)
+    wl = ctx["wl"]
+    detail = quality_and_rooflines(torch, fp, ctx, kernel_ms)
+    s0 = detail["stages"][0]
+    # dominant kernel of the step: the one with the largest share of the time
+    dom = max(s0["roofline"], key=lambda kname: s0["kernel_ms"].get(kname, 0.0))
+    roof = dict(s0["roofline"][dom])
+    roof["kernel"] = dom + " (stage 0)"
+    roof["ms_per_launch"] = s0["kernel_ms"][dom]
+    roof["traffic"] = TRAFFIC_BYTES.get(name)
+    line = {
+        "metric": "FPS+ball-query latency per batch (ms) and Mpoints/s; achieved HBM GB/s vs peak",
+        "value": wl.B * wl.N / (ms_per_step * 1e-3) / 1e6, "unit": "Mpoints/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s" % (name, wl.description), "B": wl.B, "N": wl.N,
+                   "stages": [{"n": st.n, "radius": st.radius, "k": st.k} for st in wl.stages],
+                   "step": "per stage: fps_exact, ball_query(brute), mdps_sample(+radius record), "
+                           "ball_query(cache reader), gather",
+                   "mdps": {"p": calibration.P_RATIO, "nseg": calibration.NSEG}},
+        "roofline": roof,
+        "detail": detail,
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(inputs, name)
+    if not args.no_extra:
+        extra = {}
+        for other in ["C1", "C2", "C3", "C4", "C5"]:
+            if other == name:
+                continue
+            octx = make_context(torch, fp, inputs, calibration, other)
+            k = 3 if other in ("C4", "C5") else 10
+            oms, okms = measure(torch, fp, octx, k, 1)
+            od = quality_and_rooflines(torch, fp, octx, okms)
+            owl = octx["wl"]
+            extra[other] = {"ms_per_step": oms, "Mpoints_per_s": owl.B * owl.N / (oms * 1e-3) / 1e6,
+                            "steps": k, "detail": od}
+            del octx
+            torch.cuda.empty_cache()
+        line["other_workloads"] = extra
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -53,6 +53,8 @@ typedef struct fp_mdps_params {
     int32_t m_min;        /* lower limit of the prefix length                                  */
     int32_t use_override; /* nonzero: skip the estimator, use thr_override                     */
     float   thr_override[FP_MAX_SEG]; /* squared thresholds R_l^2, l = 1..nseg, non-increasing */
+    float   level_scale[FP_MAX_SEG];  /* offline per-segment correction multiplying the predicted
+                                         SQUARED value of segment l (> 0; 1 = pure power function) */
 } fp_mdps_params;
 
 /* Per-cloud record written by the sampler kernels (device memory, [B], optional). */

@@ -115,6 +115,8 @@ typedef struct {
     int32_t m_min;        /* lower limit of prefix iterations                        */
     int32_t use_override; /* nonzero: take thresholds from thr_override (tests)      */
     float thr_override[REF_MAX_SEG];
+    float level_scale[REF_MAX_SEG]; /* offline per-segment correction of the predicted
+                                       SQUARED value (1 = pure power function)       */
 } ref_mdps_params;
 
 typedef struct {
@@ -182,8 +184,10 @@ double ref_pow_int_base(int64_t x, double e)
  *   C(x) = a / x^e ; a = mean over the last W prefix points of mdc[i] * i^e
  *   R_l^2 = curve value at the END of segment l, index b_l = floor(n*l/nseg)
  *           clamped to [1, n-1]: the measured value if b_l <= m, else the
- *           prediction times bias^2.  R_l serves as the lower bound of the
- *           spacing inside segment l (Section 4.1 step 3), hence the end.
+ *           prediction times bias^2 times level_scale[l] (an offline-fitted
+ *           shape correction per segment, 1 for the pure power function).  R_l
+ *           serves as the lower bound of the spacing inside segment l
+ *           (Section 4.1 step 3), hence the end.
  *   thresholds are kept >= FLT_MIN and non-increasing.
  */
 int ref_mdps_thresholds(const float *mdc, int32_t n, int32_t m,
@@ -215,7 +219,7 @@ int ref_mdps_thresholds(const float *mdc, int32_t n, int32_t m,
         if (b <= m)
             r = mdc[b];
         else
-            r = (float)((bias2 * a) / ref_pow_int_base(b, e));
+            r = (float)(((bias2 * (double)prm->level_scale[l - 1]) * a) / ref_pow_int_base(b, e));
         if (!(r >= FLT_MIN))
             r = FLT_MIN;
         if (l >= 2 && r > thr2[l - 2])

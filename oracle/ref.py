@@ -22,7 +22,8 @@ MAX_SEG = 16
 class _Params(ctypes.Structure):
     _fields_ = [("p", ctypes.c_float), ("nseg", ctypes.c_int32), ("exponent", ctypes.c_double),
                 ("bias", ctypes.c_float), ("fit_window", ctypes.c_int32), ("m_min", ctypes.c_int32),
-                ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG)]
+                ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG),
+                ("level_scale", ctypes.c_float * MAX_SEG)]
 
 
 class _Info(ctypes.Structure):
@@ -41,9 +42,16 @@ class MdpsParams:
     fit_window: int = 32
     m_min: int = 8
     thr_override: Optional[Sequence[float]] = None
+    level_scale: Optional[Sequence[float]] = None
 
     def to_c(self) -> _Params:
         c = _Params()
+        for i in range(MAX_SEG):
+            c.level_scale[i] = 1.0
+        if self.level_scale is not None:
+            assert len(self.level_scale) == self.nseg
+            for i, v in enumerate(self.level_scale):
+                c.level_scale[i] = v
         c.p, c.nseg, c.exponent, c.bias = self.p, self.nseg, self.exponent, self.bias
         c.fit_window, c.m_min = self.fit_window, self.m_min
         c.use_override = 0

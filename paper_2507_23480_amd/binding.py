@@ -25,7 +25,8 @@ EXPORTS = ["fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_s
 class FpMdpsParams(ctypes.Structure):
     _fields_ = [("p", ctypes.c_float), ("nseg", ctypes.c_int32), ("exponent", ctypes.c_double),
                 ("bias", ctypes.c_float), ("fit_window", ctypes.c_int32), ("m_min", ctypes.c_int32),
-                ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG)]
+                ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG),
+                ("level_scale", ctypes.c_float * MAX_SEG)]
 
 
 class FpMdpsInfo(ctypes.Structure):
@@ -50,9 +51,17 @@ class MdpsParams:
     fit_window: int = 32
     m_min: int = 8
     thr_override: Optional[Sequence[float]] = None
+    level_scale: Optional[Sequence[float]] = None
 
     def to_c(self) -> FpMdpsParams:
         c = FpMdpsParams()
+        for i in range(MAX_SEG):
+            c.level_scale[i] = 1.0
+        if self.level_scale is not None:
+            if len(self.level_scale) != self.nseg:
+                raise ValueError("level_scale needs nseg values")
+            for i, v in enumerate(self.level_scale):
+                c.level_scale[i] = v
         c.p, c.nseg, c.exponent, c.bias = self.p, self.nseg, self.exponent, self.bias
         c.fit_window, c.m_min = self.fit_window, self.m_min
         c.use_override = 0

@@ -63,29 +63,36 @@ bool shape_for(int64_t points_per_wg, Shape* s)
     return false;
 }
 
-// Splits B clouds of N points over at most `cus` resident workgroups.
+constexpr int kMaxPointsPerWg = 256 * 32;
+
+// Splits B clouds of N points over at most `cus` resident workgroups: G workgroups per
+// cloud, `groups` clouds resident at once (further clouds are taken in turn).
 bool make_plan(int B, int N, int cus, Plan* plan)
 {
     if (B < 1 || N < 1 || cus < 1) return false;
-    const int clouds_at_once = B < cus ? B : cus;
-    int gmax = cus / clouds_at_once;
-    if (gmax > kMaxGroup) gmax = kMaxGroup;
-    if (gmax < 1) gmax = 1;
+    int gcap = cus < kMaxGroup ? cus : kMaxGroup;              // most workgroups one cloud can get
+    int gneed = (int)(((int64_t)N + kMaxPointsPerWg - 1) / kMaxPointsPerWg);
+    if (gneed > gcap) return false;                            // cloud too large to stay resident
     int G = (int)(((int64_t)N + kTargetPointsPerWg - 1) / kTargetPointsPerWg);
+    if (G > gcap) G = gcap;
+    // keep every cloud resident when that still leaves each workgroup within its capacity
+    if ((int64_t)B * G > cus) {
+        int share = cus / (B < cus ? B : cus);
+        if (share < 1) share = 1;
+        G = share > gneed ? share : gneed;
+        if (G > gcap) G = gcap;
+    }
     const int forced = g_force_wg_per_cloud.load();
-    if (forced > 0) G = forced;
-    if (G > gmax) G = gmax;
+    if (forced > 0) G = forced < gneed ? gneed : (forced > gcap ? gcap : forced);
     if (G < 1) G = 1;
     Shape s;
-    while (!shape_for(((int64_t)N + G - 1) / G, &s)) {
-        if (G >= gmax) return false;
-        ++G;
-    }
+    if (!shape_for(((int64_t)N + G - 1) / G, &s)) return false;
     plan->G = G;
     plan->T = s.T;
     plan->P = s.P;
     int groups = cus / G;
     if (groups > B) groups = B;
+    if (groups < 1) groups = 1;
     plan->groups = groups;
     return true;
 }
@@ -144,6 +151,10 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
             if (!(prm->bias > 0.0f) || !isfinite(prm->bias) || !isfinite(prm->exponent))
                 return FP_ERR_PARAM;
             if (prm->fit_window < 1 || prm->fit_window > 64) return FP_ERR_PARAM;
+            for (int l = 0; l < prm->nseg; ++l) {
+                if (!(prm->level_scale[l] > 0.0f) || !isfinite(prm->level_scale[l])) return FP_ERR_PARAM;
+                a.level_scale[l] = prm->level_scale[l];
+            }
         }
         int64_t m = (int64_t)floor((double)prm->p * (double)n);
         if (m < prm->m_min) m = prm->m_min;

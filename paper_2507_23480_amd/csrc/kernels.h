@@ -36,6 +36,7 @@ struct SamplerArgs {
     int32_t nseg, fit_window, use_override;
     double exponent, bias2;
     float thr_override[FP_MAX_SEG];
+    float level_scale[FP_MAX_SEG];
     uint64_t* bq_bits;
     int32_t* bq_idx;
     float bq_r2;

@@ -37,6 +37,8 @@ namespace {
 constexpr int kCand = kCandPerRound;    // candidates examined per round of the threshold phase
 constexpr float kPadCoord = 3.0e38f;    // coordinates of slots beyond N: every distance becomes +inf
 constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
+constexpr int kStage = 256;             // ring of picks not yet written to global memory
+constexpr int kFlush = 128;             // ... written out once this many are waiting
 
 // ---------------------------------------------------------------- wave helpers
 template <int CTRL>
@@ -167,6 +169,8 @@ struct Shared {
     int32_t pend_pos[kCand];
     int32_t gpre[kMaxGroup + 1];
     int32_t ctrl[4];      // [0] accepted picks of the round, [1] candidates of the round, [2] failure
+    uint32_t st_idx[kStage];   // picks waiting to be written out (ring, by sample position)
+    float st_mdc[kStage];
 };
 
 // Everything one thread needs to know about where it sits.
@@ -326,11 +330,32 @@ __device__ __forceinline__ Rec cloud_argmax(const Points<P, BQ>& pt, Shared<T>& 
     return sh.win[buf];
 }
 
-template <int T, int P, bool BQ>
-__device__ __forceinline__ void write_pick(const SamplerArgs& a, const Where& wh, int pos, uint32_t idx)
+// Picks are staged in LDS and written to global memory in blocks: a global store inside the
+// iteration loop would make every iteration wait for the previous store to complete.
+template <int T>
+__device__ __forceinline__ void stage_pick(Shared<T>& sh, int pos, uint32_t idx, float d)
 {
-    a.out_idx[(int64_t)wh.c * a.n + pos] = (int32_t)idx;
-    if (BQ) a.bq_idx[(int64_t)wh.c * a.n + pos] = (int32_t)idx;
+    sh.st_idx[pos & (kStage - 1)] = idx;
+    sh.st_mdc[pos & (kStage - 1)] = d;
+}
+
+// Writes the staged picks [flushed, upto) when enough are waiting (or `force`).  Called by all
+// threads of the workgroup at a point where they are converged.
+template <int T, bool BQ>
+__device__ __forceinline__ void flush_picks(const SamplerArgs& a, Shared<T>& sh, const Where& wh,
+                                            int& flushed, int upto, bool force)
+{
+    if (upto - flushed < kFlush && !force) return;
+    __syncthreads();
+    if (wh.g == 0) {
+        for (int t = flushed + wh.tid; t < upto; t += T) {
+            const uint32_t v = sh.st_idx[t & (kStage - 1)];
+            a.out_idx[(int64_t)wh.c * a.n + t] = (int32_t)v;
+            if (BQ) a.bq_idx[(int64_t)wh.c * a.n + t] = (int32_t)v;
+            if (a.out_mdc) a.out_mdc[(int64_t)wh.c * a.n + t] = sh.st_mdc[t & (kStage - 1)];
+        }
+    }
+    flushed = upto;
 }
 
 // x^e for an integer x >= 1 in binary64 using only + - * / (each correctly rounded
@@ -366,10 +391,11 @@ __device__ __noinline__ double pow_int_base(int64_t x, double e)
 template <int T, int P, bool BQ>
 __device__ __forceinline__ bool fps_iterations(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                                const SamplerArgs& a, uint32_t& it, uint32_t& seq,
-                                               int& i, int upto, bool capture, int my_bl, bool writer,
+                                               int& i, int upto, bool capture, int my_bl, int& flushed,
                                                float& lx, float& ly, float& lz)
 {
     for (; i < upto; ++i) {
+        flush_picks<T, BQ>(a, sh, wh, flushed, i, false);
         fold<P, BQ>(pt, lx, ly, lz, a, wh, i - 1);
         const Rec r = cloud_argmax<T, P, BQ>(pt, sh, wh, a, it, seq);
         if (r.fail) return false;
@@ -377,10 +403,7 @@ __device__ __forceinline__ bool fps_iterations(Points<P, BQ>& pt, Shared<T>& sh,
         ly = r.y;
         lz = r.z;
         const float dpick = __uint_as_float(r.d);
-        if (writer) {
-            write_pick<T, P, BQ>(a, wh, i, r.idx);
-            if (a.out_mdc) a.out_mdc[(int64_t)wh.c * a.n + i] = dpick;
-        }
+        if (wh.tid == 0) stage_pick<T>(sh, i, r.idx, dpick);
         if (capture) {             // Alg. 2 line 11: keep the curve of the prefix
             if (wh.tid == 0) sh.ring[i & 63] = dpick;
             if (my_bl == i) sh.thr_meas[wh.tid] = dpick;
@@ -459,10 +482,8 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     float lx = cloud[(int64_t)start * 3 + 0];
     float ly = cloud[(int64_t)start * 3 + 1];
     float lz = cloud[(int64_t)start * 3 + 2];
-    if (writer) {
-        write_pick<T, P, BQ>(a, wh, 0, (uint32_t)start);
-        if (a.out_mdc) a.out_mdc[(int64_t)wh.c * n] = __builtin_inff();
-    }
+    if (wh.tid == 0) stage_pick<T>(sh, 0, (uint32_t)start, __builtin_inff());
+    int flushed = 0;                   // sample positions [0, flushed) are in global memory
     __syncthreads();
 
     const int m = a.m;                 // exact FPS iterations before the threshold phase
@@ -473,7 +494,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     int npend = 0;
 
     bool ok = fps_iterations<T, P, BQ>(pt, sh, wh, a, it, seq, i, pure_fps ? n : m + 1, !pure_fps, my_bl,
-                                       writer, lx, ly, lz);
+                                       flushed, lx, ly, lz);
 
     if (ok && !pure_fps) {
         // ---- thresholds from the estimated curve (Eq. 1 with a/x^e; Alg. 2 lines 13, 20)
@@ -498,7 +519,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 for (int l = 0; l < a.nseg; ++l) {
                     float r;
                     if (boundary_index(n, a.nseg, l + 1) <= m) r = sh.thr_meas[l];
-                    else r = (float)((a.bias2 * acc) / sh.powb[l]);
+                    else r = (float)(((a.bias2 * (double)a.level_scale[l]) * acc) / sh.powb[l]);
                     if (!(r >= 1.17549435e-38f)) r = 1.17549435e-38f;
                     if (l >= 1 && r > prev) r = prev;
                     sh.thr[l] = r;
@@ -522,6 +543,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 
         // ---- threshold sampling (Alg. 2 lines 24-37), running-distance form
         while (i < n) {
+            flush_picks<T, BQ>(a, sh, wh, flushed, i, false);
             const int q = 1 + (int)(((int64_t)i * a.nseg) / n);
             if (q > seg) {
                 seg = q;
@@ -673,7 +695,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                         acc.z = az;
                         sh.pend[nacc] = acc;
                         sh.pend_pos[nacc] = i + nacc;
-                        if (wh.g == 0) write_pick<T, P, BQ>(a, wh, i + nacc, aj);
+                        stage_pick<T>(sh, i + nacc, aj, 0.0f);
                     }
                     const float t = dist2(ax, ay, az, me.x, me.y, me.z);
                     const uint64_t kill = __builtin_amdgcn_ballot_w64(t < r2);
@@ -696,7 +718,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             // ---- early termination (Alg. 2 lines 39-53): dists is already the true running
             //      minimum, so the remainder is plain FPS; its first fold repeats sample i-1
             et_index = i;
-            ok = fps_iterations<T, P, BQ>(pt, sh, wh, a, it, seq, i, n, false, -1, writer, lx, ly, lz);
+            ok = fps_iterations<T, P, BQ>(pt, sh, wh, a, it, seq, i, n, false, -1, flushed, lx, ly, lz);
             if (ok && BQ) fold<P, BQ>(pt, lx, ly, lz, a, wh, n - 1);
         } else if (ok && BQ) {
             fold_pending<T, P, BQ>(pt, sh, wh, a, npend);    // rows of the last picks
@@ -706,6 +728,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         fold<P, BQ>(pt, lx, ly, lz, a, wh, n - 1);
     }
 
+    if (ok) flush_picks<T, BQ>(a, sh, wh, flushed, n, true);
     __syncthreads();
     if (writer && a.info) {
         fp_mdps_info inf = {};

@@ -42,7 +42,8 @@ def oracle_batch(fn, batch, *args):
 
 def rparams(prm):
     return ref.MdpsParams(p=prm.p, nseg=prm.nseg, exponent=prm.exponent, bias=prm.bias,
-                          fit_window=prm.fit_window, m_min=prm.m_min, thr_override=prm.thr_override)
+                          fit_window=prm.fit_window, m_min=prm.m_min, thr_override=prm.thr_override,
+                          level_scale=prm.level_scale)
 
 
 def check_fps(fp, batch, n, start=None, G=0):

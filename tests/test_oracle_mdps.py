@@ -70,6 +70,17 @@ def test_estimator_recovers_exact_power_law(e):
         assert np.all(thr[:-1] >= thr[1:])
 
 
+def test_level_scale_multiplies_the_predicted_squared_value():
+    n, m, a0, e = 3000, 300, 2.0, 1.0
+    mdc = np.empty(m + 1, np.float32)
+    mdc[0] = np.inf
+    mdc[1:] = (a0 / np.arange(1, m + 1)).astype(np.float32)
+    scale = [1.0, 0.9, 0.8, 0.7, 0.6, 0.5]
+    thr = ref.mdps_thresholds(mdc, n, m, ref.MdpsParams(exponent=e, bias=1.1, level_scale=scale))
+    b = np.array([min(n * l // 6, n - 1) for l in range(1, 7)], np.float64)
+    assert np.allclose(thr, 1.21 * np.array(scale) * a0 / b, rtol=3e-7)
+
+
 def test_thresholds_inside_the_prefix_are_the_measured_values():
     # boundaries b_l <= m take the measured curve (Alg. 2 line 13: measured prefix and
     # estimate are concatenated)
