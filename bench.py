@@ -41,6 +41,10 @@ def parse_args():
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads' summary")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--plain-launch", action="store_true",
+                    help="plain instead of cooperative kernel launches (for rocprofv3 traces)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -240,6 +244,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     fp.load()
+    if args.plain_launch:
+        fp.set_cooperative_launch(False)
     name = args.workload
     ctx = make_context(torch, fp, inputs, calibration, name)
     ms_per_step, kernel_ms = measure(torch, fp, ctx, args.steps, args.warmup)
@@ -283,6 +289,11 @@ def main():
             del octx
             torch.cuda.empty_cache()
         line["other_workloads"] = extra
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     print(json.dumps(line))
     return 0
 

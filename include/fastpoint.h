@@ -152,6 +152,13 @@ fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
  * Process-wide; not meant for concurrent use. */
 void fp_set_wg_per_cloud(int32_t wg_per_cloud);
 
+/* Multi-workgroup launches are cooperative by default (the runtime guarantees that all
+ * workgroups are resident, which the waits between them rely on).  0 switches to a plain
+ * launch, for tools that cannot trace cooperative launches: the grid never exceeds one
+ * workgroup per compute unit, so it is resident on an otherwise idle device, and a wait that
+ * cannot be met still ends through the wait limit.  Process-wide. */
+void fp_set_cooperative_launch(int32_t on);
+
 /* Upper limit, in microseconds, of any wait of one workgroup on another
  * (default 2 000 000).  A wait that expires ends the kernel with info.status 2. */
 void fp_set_wait_limit_us(int64_t microseconds);

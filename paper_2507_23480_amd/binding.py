@@ -19,7 +19,7 @@ MAX_SEG = 16
 
 EXPORTS = ["fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
            "fp_ball_query", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
-           "fp_set_wait_limit_us", "fp_status_string"]
+           "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
 
 
 class FpMdpsParams(ctypes.Structure):
@@ -106,6 +106,8 @@ def load() -> ctypes.CDLL:
     lib.fp_plan.restype = i32
     lib.fp_set_wg_per_cloud.argtypes = [i32]
     lib.fp_set_wg_per_cloud.restype = None
+    lib.fp_set_cooperative_launch.argtypes = [i32]
+    lib.fp_set_cooperative_launch.restype = None
     lib.fp_set_wait_limit_us.argtypes = [ctypes.c_int64]
     lib.fp_set_wait_limit_us.restype = None
     lib.fp_status_string.argtypes = [i32]
@@ -143,6 +145,10 @@ def plan(B: int, N: int) -> Tuple[int, int, int]:
 
 def set_wg_per_cloud(g: int) -> None:
     load().fp_set_wg_per_cloud(int(g))
+
+
+def set_cooperative_launch(on: bool) -> None:
+    load().fp_set_cooperative_launch(1 if on else 0)
 
 
 def set_wait_limit_us(us: int) -> None:

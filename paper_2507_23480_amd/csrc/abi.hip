@@ -15,6 +15,7 @@ namespace {
 
 std::atomic<int> g_force_wg_per_cloud{0};
 std::atomic<int64_t> g_wait_limit_us{2000000};
+std::atomic<int> g_cooperative{1};
 
 struct DeviceInfo {
     bool ok = false;
@@ -203,7 +204,10 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         // whole grid has to be resident
         if (launch_zero_words(a.ll_pk, kLlPkWords + kLlCdWords, stream) != hipSuccess)
             return FP_ERR_DEVICE;
-        err = hipLaunchCooperativeKernel(fn, dim3(grid), dim3((unsigned)plan.T), kargs, 0, stream);
+        if (g_cooperative.load())
+            err = hipLaunchCooperativeKernel(fn, dim3(grid), dim3((unsigned)plan.T), kargs, 0, stream);
+        else
+            err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)plan.T), kargs, 0, stream);
     } else {
         err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)plan.T), kargs, 0, stream);
     }
@@ -295,6 +299,8 @@ fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
 }
 
 void fp_set_wg_per_cloud(int32_t wg_per_cloud) { g_force_wg_per_cloud.store(wg_per_cloud > 0 ? wg_per_cloud : 0); }
+
+void fp_set_cooperative_launch(int32_t on) { g_cooperative.store(on ? 1 : 0); }
 
 void fp_set_wait_limit_us(int64_t microseconds) { g_wait_limit_us.store(microseconds > 0 ? microseconds : 1); }
 
