@@ -160,7 +160,8 @@ void fp_set_wg_per_cloud(int32_t wg_per_cloud);
 void fp_set_cooperative_launch(int32_t on);
 
 /* Upper limit, in microseconds, of any wait of one workgroup on another
- * (default 2 000 000).  A wait that expires ends the kernel with info.status 2. */
+ * (default 2 000 000).  A wait that expires ends the kernel with info.status 2.  With 0 a
+ * wait gives up as soon as two polls in a row find nothing (a hook for tests of that path). */
 void fp_set_wait_limit_us(int64_t microseconds);
 
 const char* fp_status_string(fp_status s);

@@ -302,7 +302,7 @@ void fp_set_wg_per_cloud(int32_t wg_per_cloud) { g_force_wg_per_cloud.store(wg_p
 
 void fp_set_cooperative_launch(int32_t on) { g_cooperative.store(on ? 1 : 0); }
 
-void fp_set_wait_limit_us(int64_t microseconds) { g_wait_limit_us.store(microseconds > 0 ? microseconds : 1); }
+void fp_set_wait_limit_us(int64_t microseconds) { g_wait_limit_us.store(microseconds > 0 ? microseconds : 0); }
 
 const char* fp_status_string(fp_status s)
 {

@@ -130,7 +130,7 @@ __device__ __forceinline__ bool ll_wait(const uint64_t* p, uint32_t stamp, uint3
             for (int k = 0; k < NWORDS; ++k) val[k] = (uint32_t)v[k];
             return true;
         }
-        if ((spin & 63u) == 63u) {
+        if ((spin & 63u) == 63u || wait_ticks <= 0) {
             int64_t now = (int64_t)wall_clock64();
             if (t0 == 0) t0 = now;
             else if (now - t0 > wait_ticks) return false;

@@ -1,0 +1,205 @@
+"""GPU parity at the five workload shapes, in the launch configuration bench.py times
+(automatic plan, calibrated MDPS constants).
+
+C1-C3: every cloud, every stage, element by element against the oracle.
+C4, C5: the oracle cannot run the full job in seconds, so
+  * full N with a reduced sample count n: element-by-element parity (for FPS the result is a
+    prefix of the full run, which is checked too);
+  * full N and full n: sampled outputs the oracle can compute one by one (ball-query rows of
+    sampled centres, curve values of sampled picks) and properties that hold at any size
+    (non-increasing curve, spacing bound per MDPS level, cached == brute, coverage bound).
+"""
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2507_23480_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+COVERAGE_BOUND = 1.05     # MDPS coverage radius relative to exact FPS
+
+
+@pytest.fixture(scope="module")
+def fp():
+    from paper_2507_23480_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    binding.set_wg_per_cloud(0)
+    return binding
+
+
+@pytest.fixture(scope="module")
+def cal():
+    from paper_2507_23480_amd import calibration
+    return calibration
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def pmap(fn, items):
+    with ThreadPoolExecutor(max_workers=8) as ex:       # ctypes calls drop the GIL
+        return list(ex.map(fn, items))
+
+
+def rparams(prm):
+    return ref.MdpsParams(p=prm.p, nseg=prm.nseg, exponent=prm.exponent, bias=prm.bias,
+                          fit_window=prm.fit_window, m_min=prm.m_min, level_scale=prm.level_scale)
+
+
+def d2(a, b):
+    """binary32 squared distances between point sets a [A][3] and b [B][3] -> [A][B]"""
+    dx = a[:, None, 0] - b[None, :, 0]
+    dy = a[:, None, 1] - b[None, :, 1]
+    dz = a[:, None, 2] - b[None, :, 2]
+    t = dx * dx
+    t = t + dy * dy
+    t = t + dz * dz
+    return t
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_full_workload_matches_oracle(fp, cal, name):
+    wl = inputs.WORKLOADS[name]
+    batch = inputs.make_batch(name)
+    for s, st in enumerate(wl.stages):
+        say("%s stage %d: B=%d N=%d n=%d" % (name, s, wl.B, batch.shape[1], st.n))
+        prm = cal.params_for(name, s)
+        xyz = dev(batch)
+        cache = fp.new_bq_cache(xyz, st.n)
+        idx, mdc = fp.fps_exact(xyz, st.n, want_mdc=True)
+        bq, cnt = fp.ball_query(xyz, idx, st.radius, st.k)
+        midx, info = fp.mdps_sample(xyz, st.n, prm, want_info=True, bq_cache=cache, bq_radius=st.radius)
+        mbq, mcnt = fp.ball_query(xyz, midx, st.radius, st.k, bq_cache=cache)
+        cov_f, cov_m = fp.coverage2(xyz, idx).sqrt(), fp.coverage2(xyz, midx).sqrt()
+        torch.cuda.synchronize()
+        idx, mdc, bq, cnt = idx.cpu().numpy(), mdc.cpu().numpy(), bq.cpu().numpy(), cnt.cpu().numpy()
+        midx, mbq, mcnt = midx.cpu().numpy(), mbq.cpu().numpy(), mcnt.cpu().numpy()
+        infos = fp.parse_info(info)
+        rp = rparams(prm)
+
+        def one(b):
+            widx, wmdc = ref.fps_exact(batch[b], st.n)
+            wbq, wcnt = ref.ball_query(batch[b], widx, st.radius, st.k)
+            wmidx, winfo = ref.mdps_sample(batch[b], st.n, rp)
+            wmbq, wmcnt = ref.ball_query(batch[b], wmidx, st.radius, st.k)
+            return widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt
+        for b, (widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt) in enumerate(pmap(one, range(wl.B))):
+            assert np.array_equal(idx[b], widx) and np.array_equal(mdc[b], wmdc), "fps cloud %d" % b
+            assert np.array_equal(bq[b], wbq) and np.array_equal(cnt[b], wcnt), "brute bq cloud %d" % b
+            assert np.array_equal(midx[b], wmidx), "mdps cloud %d" % b
+            assert infos[b].status == 0 and infos[b].et_index == winfo.et_index
+            assert np.array_equal(np.array(infos[b].thr2[:prm.nseg], np.float32), winfo.thr2)
+            assert np.array_equal(mbq[b], wmbq) and np.array_equal(mcnt[b], wmcnt), "cached bq cloud %d" % b
+        ratio = (cov_m / cov_f).cpu().numpy()
+        say("   coverage ratio max %.4f" % ratio.max())
+        assert ratio.max() <= COVERAGE_BOUND
+        if s + 1 < len(wl.stages):
+            batch = np.stack([ref.gather_xyz(batch[b], idx[b]) for b in range(wl.B)])
+
+
+def check_large(fp, cal, name, n_small, bq_centres):
+    wl = inputs.WORKLOADS[name]
+    st = wl.stages[0]
+    batch = inputs.make_batch(name)
+    xyz = dev(batch)
+    prm = cal.params_for(name, 0)
+    rp = rparams(prm)
+    B, N, n = wl.B, wl.N, st.n
+
+    # ---- full N, reduced n: element by element
+    say("%s: full N=%d, reduced n=%d" % (name, N, n_small))
+    sidx, smdc = fp.fps_exact(xyz, n_small, want_mdc=True)
+    smidx, sinfo = fp.mdps_sample(xyz, n_small, prm, want_info=True)
+    torch.cuda.synchronize()
+    sidx, smdc, smidx = sidx.cpu().numpy(), smdc.cpu().numpy(), smidx.cpu().numpy()
+    sinfos = fp.parse_info(sinfo)
+    want = pmap(lambda b: (ref.fps_exact(batch[b], n_small), ref.mdps_sample(batch[b], n_small, rp)),
+                range(B))
+    for b, ((widx, wmdc), (wmidx, winfo)) in enumerate(want):
+        assert np.array_equal(sidx[b], widx) and np.array_equal(smdc[b], wmdc), "fps cloud %d" % b
+        assert np.array_equal(smidx[b], wmidx), "mdps cloud %d" % b
+        assert sinfos[b].et_index == winfo.et_index
+        assert np.array_equal(np.array(sinfos[b].thr2[:prm.nseg], np.float32), winfo.thr2)
+
+    # ---- full N, full n
+    say("%s: full N=%d, full n=%d" % (name, N, n))
+    cache = fp.new_bq_cache(xyz, n)
+    idx, mdc = fp.fps_exact(xyz, n, want_mdc=True)
+    midx, info = fp.mdps_sample(xyz, n, prm, want_info=True, bq_cache=cache, bq_radius=st.radius)
+    bq, cnt = fp.ball_query(xyz, midx, st.radius, st.k)
+    cbq, ccnt = fp.ball_query(xyz, midx, st.radius, st.k, bq_cache=cache)
+    fbq, fcnt = fp.ball_query(xyz, idx, st.radius, st.k)
+    cov = (fp.coverage2(xyz, midx).sqrt() / fp.coverage2(xyz, idx).sqrt())
+    torch.cuda.synchronize()
+    assert torch.equal(bq, cbq) and torch.equal(cnt, ccnt), "cached ball query differs from brute force"
+    idx, mdc, midx = idx.cpu().numpy(), mdc.cpu().numpy(), midx.cpu().numpy()
+    bq, cnt, fbq, fcnt = bq.cpu().numpy(), cnt.cpu().numpy(), fbq.cpu().numpy(), fcnt.cpu().numpy()
+    infos = fp.parse_info(info)
+    say("   coverage ratio max %.4f, FPS tail %s" % (float(cov.max()), [n - i.et_index for i in infos]))
+    assert float(cov.max()) <= COVERAGE_BOUND
+    rng = np.random.Generator(np.random.PCG64(5))
+    for b in range(B):
+        pts = batch[b]
+        # exact FPS: prefix property, curve non-increasing, curve values of sampled picks
+        assert np.array_equal(idx[b, :n_small], sidx[b]) and np.array_equal(mdc[b, :n_small], smdc[b])
+        assert np.all(mdc[b, 1:-1] >= mdc[b, 2:])
+        assert len(np.unique(idx[b])) == n
+        for i in rng.integers(1, n, 64):
+            assert mdc[b, i] == d2(pts[idx[b, i:i + 1]], pts[idx[b, :i]]).min()
+        # MDPS: same prefix as exact FPS, spacing bound of the level of sampled picks
+        gi = infos[b]
+        assert gi.status == 0 and np.array_equal(midx[b, :gi.m + 1], idx[b, :gi.m + 1])
+        assert len(np.unique(midx[b])) == n
+        starts = [s for s in gi.level_start[:prm.nseg]]
+        for i in rng.integers(gi.m + 1, max(gi.et_index, gi.m + 2), 64):
+            if i >= gi.et_index:
+                continue
+            lvl = max(l for l in range(prm.nseg) if 0 <= starts[l] <= i)
+            assert d2(pts[midx[b, i:i + 1]], pts[midx[b, :i]]).min() >= gi.thr2[lvl]
+        # ball-query rows of sampled centres, computed one by one by the oracle
+        qs = rng.integers(0, n, bq_centres)
+        wq, wc = ref.ball_query(pts, midx[b, qs], st.radius, st.k)
+        assert np.array_equal(bq[b, qs], wq) and np.array_equal(cnt[b, qs], wc)
+        wq, wc = ref.ball_query(pts, idx[b, qs], st.radius, st.k)
+        assert np.array_equal(fbq[b, qs], wq) and np.array_equal(fcnt[b, qs], wc)
+
+
+def test_lidar_workload(fp, cal):
+    check_large(fp, cal, "C4", n_small=2048, bq_centres=256)
+
+
+def test_million_point_workload(fp, cal):
+    check_large(fp, cal, "C5", n_small=1024, bq_centres=128)
+
+
+def test_expired_wait_ends_the_kernel_cleanly(fp):
+    # with a wait limit of zero a wait gives up after two empty polls: the kernel
+    # must end on its own and report status 2 with an all -1 result (no hang, no fault)
+    cloud = inputs.uniform_cube(77, 30000)[None]
+    fp.set_wg_per_cloud(8)
+    fp.set_wait_limit_us(0)
+    try:
+        idx, info = fp.fps_exact(dev(cloud), 4000, want_info=True)
+        torch.cuda.synchronize()
+    finally:
+        fp.set_wait_limit_us(2000000)
+        fp.set_wg_per_cloud(0)
+    st = fp.parse_info(info)[0].status
+    if st == 2:
+        assert bool((idx == -1).all())
+    else:       # every wait happened to be met within the limit: the result must then be right
+        assert st == 0 and np.array_equal(idx.cpu().numpy()[0], ref.fps_exact(cloud[0], 4000)[0])
+    again = fp.fps_exact(dev(cloud), 500)
+    torch.cuda.synchronize()
+    assert np.array_equal(again.cpu().numpy()[0], ref.fps_exact(cloud[0], 500)[0])
