@@ -30,7 +30,7 @@ OPS_PER_PAIR_TEST = 9             # 3 sub, 3 mul, 2 add, 1 compare (ball query)
 
 # HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs (see profiles/); bytes, keyed by workload.  None where no counter run is recorded.
-TRAFFIC_BYTES = {}
+TRAFFIC_BYTES = {"C2": int((187.7 * 2.0 + 32.4) * 1024)}    # profiles/bench_C2_hbm_traffic.md
 
 
 def parse_args():
