@@ -103,7 +103,7 @@ inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 int64_t bq_row_words(int N) { return align_up(((int64_t)N + 63) / 64, 8); }
 
 constexpr int64_t kLlPkWords = (int64_t)2 * kMaxGroup * kLlSlotWords;             // all groups together
-constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandPerRound * 4;
+constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandPerRound * kCandWords;
 
 fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
                       const fp_mdps_params* prm, int32_t* out_idx, float* out_mdc, fp_mdps_info* info,

@@ -12,6 +12,7 @@ namespace fastpoint {
 constexpr int kMaxGroup = 256;          // most workgroups one cloud is spread over
 constexpr int kLlSlotWords = 8;         // 64-bit words per workgroup slot of the pick exchange
 constexpr int kCandPerRound = 64;       // candidates per round of the threshold phase
+constexpr int kCandWords = 5;           // exchanged 64-bit words per candidate (idx, x, y, z, distance)
 constexpr uint32_t kBqMagic = 0x46504251u;
 
 // Header at the start of a ball-query cache (device memory).
@@ -42,7 +43,7 @@ struct SamplerArgs {
     float bq_r2;
     int64_t bq_row_words;
     uint64_t* ll_pk;                // [groups][2][G][kLlSlotWords]
-    uint64_t* ll_cd;                // [groups][2][G][kCandPerRound][4]
+    uint64_t* ll_cd;                // [groups][2][G][kCandPerRound][kCandWords]
     int64_t wait_ticks;
 };
 

@@ -146,9 +146,11 @@ struct Rec {          // one arg-max candidate: squared distance bits, index, co
     uint32_t pad0, pad1;
 };
 
-struct Cand {         // a candidate or accepted pick of the threshold phase
+struct Cand {         // a candidate or accepted pick: index, coordinates, squared distance bits
     uint32_t idx;
     float x, y, z;
+    uint32_t d;
+    uint32_t pad0, pad1, pad2;
 };
 
 template <int T>
@@ -168,7 +170,8 @@ struct Shared {
     Cand pend[kCand];
     int32_t pend_pos[kCand];
     int32_t gpre[kMaxGroup + 1];
-    int32_t ctrl[4];      // [0] accepted picks of the round, [1] candidates of the round, [2] failure
+    int32_t ctrl[4];      // [0] accepted picks of the round, [1] points passing in the cloud,
+                          // [2] failure, [3] distance bits of the last accepted pick
     uint32_t st_idx[kStage];   // picks waiting to be written out (ring, by sample position)
     float st_mdc[kStage];
 };
@@ -386,32 +389,6 @@ __device__ __noinline__ double pow_int_base(int64_t x, double e)
     return acc * __longlong_as_double((long long)(1023 + (int)q) << 52);
 }
 
-// ---- exact FPS for sample positions [i, upto): fold sample i-1, then arg-max
-// (Alg. 1 lines 3-8).  Returns false if a wait between workgroups expired.
-template <int T, int P, bool BQ>
-__device__ __forceinline__ bool fps_iterations(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
-                                               const SamplerArgs& a, uint32_t& it, uint32_t& seq,
-                                               int& i, int upto, bool capture, int my_bl, int& flushed,
-                                               float& lx, float& ly, float& lz)
-{
-    for (; i < upto; ++i) {
-        flush_picks<T, BQ>(a, sh, wh, flushed, i, false);
-        fold<P, BQ>(pt, lx, ly, lz, a, wh, i - 1);
-        const Rec r = cloud_argmax<T, P, BQ>(pt, sh, wh, a, it, seq);
-        if (r.fail) return false;
-        lx = r.x;
-        ly = r.y;
-        lz = r.z;
-        const float dpick = __uint_as_float(r.d);
-        if (wh.tid == 0) stage_pick<T>(sh, i, r.idx, dpick);
-        if (capture) {             // Alg. 2 line 11: keep the curve of the prefix
-            if (wh.tid == 0) sh.ring[i & 63] = dpick;
-            if (my_bl == i) sh.thr_meas[wh.tid] = dpick;
-        }
-    }
-    return true;
-}
-
 template <int T, int P, bool BQ>
 __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                              const SamplerArgs& a, int npend)
@@ -431,12 +408,313 @@ __device__ __forceinline__ int boundary_index(int n, int nseg, int l)
     return (int)b;
 }
 
+// Progress of one cloud; every field is uniform over all workgroups of the cloud.
+struct CloudState {
+    int i;          // next sample position to fill
+    int npend;      // picks in sh.pend that are not folded into the distances yet
+    int flushed;    // sample positions [0, flushed) are in global memory
+    int rounds;     // candidate scans so far
+    float dlast;    // squared distance of the last exact-FPS pick at pick time; < 0: unknown
+    float om;       // an exact-FPS round takes the points above dlast * (1 - om) as candidates
+    int my_bl;      // thread l < nseg: segment boundary b_(l+1); else -1
+};
+
+// Curve capture of the prefix (Alg. 2 line 11), by the lanes of one wave.
+template <int T>
+__device__ __forceinline__ void capture_curve(Shared<T>& sh, const Where& wh, const CloudState& st, int pos,
+                                              float d)
+{
+    if (wh.tid == 0) sh.ring[pos & 63] = d;
+    if (st.my_bl == pos) sh.thr_meas[wh.tid] = d;
+}
+
+// One plain iteration of Alg. 1 (lines 4-8) on distances that are already up to date:
+// arg-max over the cloud, lowest index among equals.  Always makes progress; the batched
+// rounds below fall back to it.  Returns false if a wait between workgroups expired.
+template <int T, int P, bool BQ>
+__device__ __forceinline__ bool plain_pick(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                           const SamplerArgs& a, uint32_t& it, uint32_t& seq,
+                                           CloudState& st, bool capture)
+{
+    const Rec r = cloud_argmax<T, P, BQ>(pt, sh, wh, a, it, seq);
+    if (r.fail) return false;
+    const float dpick = __uint_as_float(r.d);
+    if (wh.tid == 0) {
+        stage_pick<T>(sh, st.i, r.idx, dpick);
+        Cand c;
+        c.idx = r.idx;
+        c.x = r.x;
+        c.y = r.y;
+        c.z = r.z;
+        c.d = r.d;
+        sh.pend[0] = c;
+        sh.pend_pos[0] = st.i;
+    }
+    if (capture && wh.w == 0) capture_curve<T>(sh, wh, st, st.i, dpick);
+    __syncthreads();
+    st.npend = 1;
+    st.dlast = dpick;
+    ++st.i;
+    return true;
+}
+
+// Collects the cloud's first kCand points (ascending index) whose distance passes the
+// threshold -- d > thr (STRICT) or d >= thr -- into sh.cand of every workgroup.
+// Returns the number collected (at most kCand), -1 if a wait expired; `alltot` receives the
+// number of points that pass in the whole cloud.
+template <int T, int P, bool BQ, bool STRICT>
+__device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                               const SamplerArgs& a, uint32_t& seq, float thr, int& alltot)
+{
+    constexpr int NW = T / 64;
+    // 1. how many of this wave's points pass
+    int cntw = 0;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const bool av = STRICT ? (pt.d[p] > thr) : (pt.d[p] >= thr);
+        cntw += __builtin_popcountll(__builtin_amdgcn_ballot_w64(av));
+    }
+    if (wh.lane == 0) sh.wcnt[wh.w] = cntw;
+    __syncthreads();
+    int off = 0, tot = 0;
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+        const int v = sh.wcnt[k];
+        off += (k < wh.w) ? v : 0;
+        tot += v;
+    }
+    // 2. the workgroup's first kCand of them, in index order
+    if (cntw > 0 && off < kCand) {
+        int base = off;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const bool av = STRICT ? (pt.d[p] > thr) : (pt.d[p] >= thr);
+            const uint64_t mk = __builtin_amdgcn_ballot_w64(av);
+            if (mk != 0 && base < kCand) {
+                const int rank = base + lanes_below(mk);
+                if (av && rank < kCand) {
+                    Cand cd;
+                    cd.idx = (uint32_t)(((wh.gw * P + p) << 6) | wh.lane);
+                    cd.x = pt.x[p];
+                    cd.y = pt.y[p];
+                    cd.z = pt.z[p];
+                    cd.d = __float_as_uint(pt.d[p]);
+                    sh.cand[rank] = cd;
+                }
+                base += __builtin_popcountll(mk);
+            }
+        }
+    }
+    __syncthreads();
+    int total = tot < kCand ? tot : kCand;
+    alltot = tot;
+    if (wh.G == 1) return total;
+
+    // 3. exchange: every workgroup publishes its list, all take the first kCand of the cloud
+    //    in workgroup (= index) order
+    ++seq;
+    const int par = (int)(seq & 1u);
+    uint64_t* pk = a.ll_pk + ((int64_t)(wh.grp * 2 + par) * wh.G) * kLlSlotWords;
+    uint64_t* cd = a.ll_cd + ((int64_t)(wh.grp * 2 + par) * wh.G) * (kCand * kCandWords);
+    for (int e = wh.tid; e < total * kCandWords; e += T) {
+        const int r = e / kCandWords, k = e - r * kCandWords;
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&sh.cand[r]);
+        ll_store(cd + ((int64_t)wh.g * kCand + r) * kCandWords + k, src[k], seq);
+    }
+    if (wh.tid == 0) ll_store(pk + (int64_t)wh.g * kLlSlotWords + 5, (uint32_t)tot, seq);
+    __syncthreads();          // sh.cand is about to be overwritten
+    if (wh.w == 0) {
+        // lane t takes the counts of workgroups [t*per, (t+1)*per)
+        const int per = (wh.G + 63) / 64;
+        int sum = 0, usum = 0;
+        bool bad = false;
+        for (int k = 0; k < per; ++k) {
+            const int t = wh.lane * per + k;
+            if (t < wh.G) {
+                uint32_t val[1];
+                if (!ll_wait<1>(pk + (int64_t)t * kLlSlotWords + 5, seq, val, a.wait_ticks)) {
+                    bad = true;
+                } else {
+                    usum += (int)val[0];
+                    sum += (int)val[0] < kCand ? (int)val[0] : kCand;
+                }
+                sh.gpre[t + 1] = sum;      // inclusive inside the lane, fixed below
+            }
+        }
+        int incl = sum;
+        for (int s = 1; s < 64; s <<= 1) {
+            const int up = __shfl_up(incl, s, 64);
+            if (wh.lane >= s) incl += up;
+        }
+        const int excl = incl - sum;
+        for (int k = 0; k < per; ++k) {
+            const int t = wh.lane * per + k;
+            if (t < wh.G) sh.gpre[t + 1] += excl;
+        }
+        for (int s = 32; s > 0; s >>= 1) usum += __shfl_xor(usum, s, 64);
+        const bool anybad = __builtin_amdgcn_ballot_w64(bad) != 0;
+        if (wh.lane == 0) {
+            sh.gpre[0] = 0;
+            sh.ctrl[1] = usum;
+            if (anybad) sh.ctrl[2] = 1;
+        }
+    }
+    __syncthreads();
+    alltot = sh.ctrl[1];
+    const int listed = sh.gpre[wh.G];
+    total = listed < kCand ? listed : kCand;
+    if (sh.ctrl[2] == 0) {
+        for (int e = wh.tid; e < total * kCandWords; e += T) {
+            const int r = e / kCandWords, k = e - r * kCandWords;
+            int lo = 0, hi = wh.G;             // workgroup whose range holds rank r
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (sh.gpre[mid] <= r) lo = mid;
+                else hi = mid;
+            }
+            uint32_t val[1];
+            val[0] = 0;
+            const bool got = ll_wait<1>(cd + ((int64_t)lo * kCand + (r - sh.gpre[lo])) * kCandWords + k, seq,
+                                        val, a.wait_ticks);
+            if (!got) sh.ctrl[2] = 1;
+            reinterpret_cast<uint32_t*>(&sh.cand[r])[k] = val[0];
+        }
+    }
+    __syncthreads();
+    return sh.ctrl[2] != 0 ? -1 : total;
+}
+
+// Threshold phase of Alg. 2 (lines 29-33 for up to kCand picks at once): the candidates are
+// taken in index order; one stays available iff no pick accepted before it in this round lies
+// closer than R_l.  Wave 0 of every workgroup does the same work; results go to sh.pend.
+template <int T>
+__device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh, const CloudState& st,
+                                                  int total, int limit, float r2)
+{
+    if (wh.w != 0) return;
+    const bool has = wh.lane < total;
+    const Cand me = sh.cand[has ? wh.lane : 0];
+    uint64_t alive = __builtin_amdgcn_ballot_w64(has);
+    int nacc = 0;
+    while (alive != 0 && nacc < limit) {
+        const int cl = first_lane(alive);
+        const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
+        const uint32_t aj = rdlane(me.idx, cl);
+        if (wh.lane == 0) {
+            Cand acc;
+            acc.idx = aj;
+            acc.x = ax;
+            acc.y = ay;
+            acc.z = az;
+            acc.d = 0;
+            sh.pend[nacc] = acc;
+            sh.pend_pos[nacc] = st.i + nacc;
+            stage_pick<T>(sh, st.i + nacc, aj, 0.0f);
+        }
+        const float t = dist2(ax, ay, az, me.x, me.y, me.z);
+        const uint64_t kill = __builtin_amdgcn_ballot_w64(t < r2);
+        alive &= ~kill;
+        alive &= ~(1ull << cl);
+        ++nacc;
+    }
+    if (wh.lane == 0) sh.ctrl[0] = nacc;
+}
+
+// Exact FPS for several picks at once.  The candidates are ALL points whose distance exceeds
+// tau, so every other point is at most tau and can only decrease.  Repeatedly: the candidate with
+// the largest up-to-date distance (lowest index among equals) is the true arg-max of Alg. 1
+// line 8 as long as that distance exceeds tau; accepting it lowers the other candidates'
+// distances exactly as the fold will.  Stops when no candidate exceeds tau any more.
+template <int T>
+__device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, const CloudState& st,
+                                              int total, int limit, float tau, bool capture)
+{
+    if (wh.w != 0) return;
+    const bool has = wh.lane < total;
+    const Cand me = sh.cand[has ? wh.lane : 0];
+    uint32_t cd = has ? me.d : 0u;                     // bit pattern; distances are >= +0
+    const uint32_t tau_bits = __float_as_uint(tau);    // tau >= 0
+    int nacc = 0;
+    float dl = st.dlast;
+    while (nacc < limit) {
+        const uint32_t dmax = wave_max_u32(cd);
+        if (!(dmax > tau_bits)) break;
+        uint64_t who = __builtin_amdgcn_ballot_w64(cd == dmax);
+        if (__builtin_popcountll(who) > 1) {            // equal distances: lowest index wins
+            const uint32_t imin = wave_min_u32(cd == dmax ? me.idx : kNoIdx);
+            who = __builtin_amdgcn_ballot_w64(cd == dmax && me.idx == imin);
+        }
+        const int cl = first_lane(who);
+        const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
+        const uint32_t aj = rdlane(me.idx, cl);
+        dl = __uint_as_float(dmax);
+        if (wh.lane == 0) {
+            Cand acc;
+            acc.idx = aj;
+            acc.x = ax;
+            acc.y = ay;
+            acc.z = az;
+            acc.d = dmax;
+            sh.pend[nacc] = acc;
+            sh.pend_pos[nacc] = st.i + nacc;
+            stage_pick<T>(sh, st.i + nacc, aj, dl);
+        }
+        if (capture) capture_curve<T>(sh, wh, st, st.i + nacc, dl);
+        const float t = dist2(ax, ay, az, me.x, me.y, me.z);
+        cd = has ? min(cd, __float_as_uint(t)) : 0u;
+        ++nacc;
+    }
+    if (wh.lane == 0) {
+        sh.ctrl[0] = nacc;
+        sh.ctrl[3] = (int)__float_as_uint(dl);
+    }
+}
+
+// ---- exact FPS for sample positions [st.i, upto) (Alg. 1 lines 3-8), in batched rounds with
+// plain iterations as the fallback.  Returns false if a wait between workgroups expired.
+template <int T, int P, bool BQ>
+__device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                           const SamplerArgs& a, uint32_t& it, uint32_t& seq,
+                                           CloudState& st, int upto, bool capture)
+{
+    while (st.i < upto) {
+        flush_picks<T, BQ>(a, sh, wh, st.flushed, st.i, false);
+        fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend);
+        st.npend = 0;
+        bool good = false;
+        int total = 0, alltot = 0;
+        float tau = 0.0f;
+        if (st.dlast > 0.0f && st.dlast < __builtin_inff()) {
+            for (int tries = 0; tries < 4 && !good; ++tries) {
+                tau = st.dlast - st.om * st.dlast;
+                total = scan_candidates<T, P, BQ, true>(pt, sh, wh, a, seq, tau, alltot);
+                if (total < 0) return false;
+                ++st.rounds;
+                if (alltot > 0 && alltot <= kCand) good = true;
+                else if (alltot == 0) st.om = st.om * 2.0f < 0.99f ? st.om * 2.0f : 0.99f;
+                else st.om = st.om * 0.5f;
+            }
+        }
+        if (!good) {
+            if (!plain_pick<T, P, BQ>(pt, sh, wh, a, it, seq, st, capture)) return false;
+            continue;
+        }
+        resolve_chain<T>(sh, wh, st, total, upto - st.i, tau, capture);
+        __syncthreads();
+        st.npend = sh.ctrl[0];
+        st.dlast = __uint_as_float((uint32_t)sh.ctrl[3]);
+        st.i += st.npend;
+        if (alltot < 32) st.om = st.om * 1.15f < 0.99f ? st.om * 1.15f : 0.99f;
+        else if (alltot > 52) st.om = st.om * 0.87f;
+    }
+    return true;
+}
+
 // ------------------------------------------------------------------ one cloud
 template <int T, int P, bool BQ>
 __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, const Where& wh,
                                           uint32_t& it, uint32_t& seq)
 {
-    constexpr int NW = T / 64;
     const int n = a.n, N = a.N;
     const bool writer = (wh.g == 0 && wh.tid == 0);
     const float* cloud = a.xyz + (int64_t)wh.c * N * 3;
@@ -476,25 +754,33 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         sh.thr[wh.tid] = 0.0f;
         sh.thr_meas[wh.tid] = 0.0f;
     }
-    if (wh.tid == 0) sh.ctrl[2] = 0;
-    const int my_bl = wh.tid < a.nseg ? boundary_index(n, a.nseg, wh.tid + 1) : -1;
-
-    float lx = cloud[(int64_t)start * 3 + 0];
-    float ly = cloud[(int64_t)start * 3 + 1];
-    float lz = cloud[(int64_t)start * 3 + 2];
-    if (wh.tid == 0) stage_pick<T>(sh, 0, (uint32_t)start, __builtin_inff());
-    int flushed = 0;                   // sample positions [0, flushed) are in global memory
+    CloudState st;
+    st.i = 1;
+    st.npend = 1;
+    st.flushed = 0;
+    st.rounds = 0;
+    st.dlast = -1.0f;
+    st.om = 0.25f;
+    st.my_bl = wh.tid < a.nseg ? boundary_index(n, a.nseg, wh.tid + 1) : -1;
+    if (wh.tid == 0) {
+        sh.ctrl[2] = 0;
+        Cand c0;                       // Alg. 1 line 1: the seed is sample 0, not folded yet
+        c0.idx = (uint32_t)start;
+        c0.x = cloud[(int64_t)start * 3 + 0];
+        c0.y = cloud[(int64_t)start * 3 + 1];
+        c0.z = cloud[(int64_t)start * 3 + 2];
+        c0.d = 0;
+        sh.pend[0] = c0;
+        sh.pend_pos[0] = 0;
+        stage_pick<T>(sh, 0, (uint32_t)start, __builtin_inff());
+    }
     __syncthreads();
 
-    const int m = a.m;                 // exact FPS iterations before the threshold phase
+    const int m = a.m;                 // exact FPS picks before the threshold phase
     const bool pure_fps = (m >= n - 1);
-    int i = 1;                         // next sample position to fill
     int et_index = n;
-    int rounds = 0;
-    int npend = 0;
 
-    bool ok = fps_iterations<T, P, BQ>(pt, sh, wh, a, it, seq, i, pure_fps ? n : m + 1, !pure_fps, my_bl,
-                                       flushed, lx, ly, lz);
+    bool ok = fps_rounds<T, P, BQ>(pt, sh, wh, a, it, seq, st, pure_fps ? n : m + 1, !pure_fps);
 
     if (ok && !pure_fps) {
         // ---- thresholds from the estimated curve (Eq. 1 with a/x^e; Alg. 2 lines 13, 20)
@@ -527,208 +813,55 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 }
             }
         }
-        // the last prefix pick (position m) is not folded yet
-        if (wh.tid == 0) {
-            Cand c0;
-            c0.idx = 0;
-            c0.x = lx;
-            c0.y = ly;
-            c0.z = lz;
-            sh.pend[0] = c0;
-            sh.pend_pos[0] = m;
-        }
         __syncthreads();
-        npend = 1;
         int seg = 0;
 
         // ---- threshold sampling (Alg. 2 lines 24-37), running-distance form
-        while (i < n) {
-            flush_picks<T, BQ>(a, sh, wh, flushed, i, false);
-            const int q = 1 + (int)(((int64_t)i * a.nseg) / n);
+        while (st.i < n) {
+            flush_picks<T, BQ>(a, sh, wh, st.flushed, st.i, false);
+            const int q = 1 + (int)(((int64_t)st.i * a.nseg) / n);
             if (q > seg) {
                 seg = q;
-                if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = i;
+                if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
             }
-            fold_pending<T, P, BQ>(pt, sh, wh, a, npend);   // picks accepted since the last sweep
-            npend = 0;
+            fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend);   // picks accepted since the last sweep
+            st.npend = 0;
             const float r2 = sh.thr[seg - 1];
             // samples of this level end where the quota rule would raise the level
             const int64_t qend = ((int64_t)n * seg + a.nseg - 1) / a.nseg;
-            const int limit = (int)((qend < n ? qend : n) - i);
-            ++rounds;
-
-            // 1. how many of this wave's points are available
-            int cntw = 0;
-#pragma unroll
-            for (int p = 0; p < P; ++p)
-                cntw += __builtin_popcountll(__builtin_amdgcn_ballot_w64(pt.d[p] >= r2));
-            if (wh.lane == 0) sh.wcnt[wh.w] = cntw;
-            __syncthreads();
-            int off = 0, tot = 0;
-#pragma unroll
-            for (int k = 0; k < NW; ++k) {
-                const int v = sh.wcnt[k];
-                off += (k < wh.w) ? v : 0;
-                tot += v;
+            const int limit = (int)((qend < n ? qend : n) - st.i);
+            ++st.rounds;
+            int alltot = 0;
+            const int total = scan_candidates<T, P, BQ, false>(pt, sh, wh, a, seq, r2, alltot);
+            if (total < 0) {
+                ok = false;
+                break;
             }
-            // 2. the workgroup's first kCand available points, in index order
-            if (cntw > 0 && off < kCand) {
-                int base = off;
-#pragma unroll
-                for (int p = 0; p < P; ++p) {
-                    const bool av = pt.d[p] >= r2;
-                    const uint64_t mk = __builtin_amdgcn_ballot_w64(av);
-                    if (mk != 0 && base < kCand) {
-                        const int rank = base + lanes_below(mk);
-                        if (av && rank < kCand) {
-                            Cand cd;
-                            cd.idx = (uint32_t)(((wh.gw * P + p) << 6) | wh.lane);
-                            cd.x = pt.x[p];
-                            cd.y = pt.y[p];
-                            cd.z = pt.z[p];
-                            sh.cand[rank] = cd;
-                        }
-                        base += __builtin_popcountll(mk);
-                    }
-                }
-            }
-            __syncthreads();
-            int total = tot < kCand ? tot : kCand;
-
-            if (wh.G > 1) {
-                // 3. exchange: every workgroup publishes its candidates, all take the first
-                //    kCand of the cloud in workgroup (= index) order
-                ++seq;
-                const int par = (int)(seq & 1u);
-                uint64_t* pk = a.ll_pk + ((int64_t)(wh.grp * 2 + par) * wh.G) * kLlSlotWords;
-                uint64_t* cd = a.ll_cd + ((int64_t)(wh.grp * 2 + par) * wh.G) * (kCand * 4);
-                if (wh.tid < total * 4) {
-                    const int r = wh.tid >> 2, k = wh.tid & 3;
-                    const Cand cc = sh.cand[r];
-                    uint32_t v = cc.idx;
-                    v = k == 1 ? __float_as_uint(cc.x) : v;
-                    v = k == 2 ? __float_as_uint(cc.y) : v;
-                    v = k == 3 ? __float_as_uint(cc.z) : v;
-                    ll_store(cd + ((int64_t)wh.g * kCand + r) * 4 + k, v, seq);
-                }
-                if (wh.tid == 0) ll_store(pk + (int64_t)wh.g * kLlSlotWords + 5, (uint32_t)total, seq);
-                __syncthreads();          // sh.cand is about to be overwritten
-                if (wh.w == 0) {
-                    // lane t takes the counts of workgroups [t*per, (t+1)*per)
-                    const int per = (wh.G + 63) / 64;
-                    int sum = 0;
-                    bool bad = false;
-                    for (int k = 0; k < per; ++k) {
-                        const int t = wh.lane * per + k;
-                        if (t < wh.G) {
-                            uint32_t val[1];
-                            if (!ll_wait<1>(pk + (int64_t)t * kLlSlotWords + 5, seq, val, a.wait_ticks))
-                                bad = true;
-                            else
-                                sum += (int)val[0];
-                            sh.gpre[t + 1] = sum;      // inclusive inside the lane, fixed below
-                        }
-                    }
-                    int incl = sum;
-                    for (int s = 1; s < 64; s <<= 1) {
-                        const int up = __shfl_up(incl, s, 64);
-                        if (wh.lane >= s) incl += up;
-                    }
-                    const int excl = incl - sum;
-                    for (int k = 0; k < per; ++k) {
-                        const int t = wh.lane * per + k;
-                        if (t < wh.G) sh.gpre[t + 1] += excl;
-                    }
-                    if (wh.lane == 0) sh.gpre[0] = 0;
-                    if (__builtin_amdgcn_ballot_w64(bad) != 0 && wh.lane == 0) sh.ctrl[2] = 1;
-                }
-                __syncthreads();
-                const int alltot = sh.gpre[wh.G];
-                total = alltot < kCand ? alltot : kCand;
-                if (wh.tid < total * 4 && sh.ctrl[2] == 0) {
-                    const int r = wh.tid >> 2, k = wh.tid & 3;
-                    int lo = 0, hi = wh.G;             // workgroup whose range holds rank r
-                    while (hi - lo > 1) {
-                        const int mid = (lo + hi) >> 1;
-                        if (sh.gpre[mid] <= r) lo = mid;
-                        else hi = mid;
-                    }
-                    uint32_t val[1];
-                    val[0] = 0;
-                    const bool got = ll_wait<1>(cd + ((int64_t)lo * kCand + (r - sh.gpre[lo])) * 4 + k,
-                                                seq, val, a.wait_ticks);
-                    if (!got) sh.ctrl[2] = 1;
-                    uint32_t* dst = reinterpret_cast<uint32_t*>(&sh.cand[r]);
-                    dst[k] = val[0];
-                }
-                __syncthreads();
-                if (sh.ctrl[2] != 0) {
-                    ok = false;
-                    break;
-                }
-            }
-
             if (total == 0) {              // level exhausted (Alg. 2 lines 34-36)
                 if (wh.tid == 0) sh.level_exhausted[seg - 1] = 1;
                 ++seg;
                 if (seg > a.nseg) break;   // early termination
-                if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = i;
+                if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
                 continue;
             }
-
-            // 4. resolve the candidates in index order: a candidate stays available iff no
-            //    pick accepted before it in this round lies closer than R_l
-            if (wh.w == 0) {
-                const bool has = wh.lane < total;
-                const Cand me = sh.cand[has ? wh.lane : 0];
-                uint64_t alive = __builtin_amdgcn_ballot_w64(has);
-                int nacc = 0;
-                while (alive != 0 && nacc < limit) {
-                    const int cl = first_lane(alive);
-                    const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
-                    const uint32_t aj = rdlane(me.idx, cl);
-                    if (wh.lane == 0) {
-                        Cand acc;
-                        acc.idx = aj;
-                        acc.x = ax;
-                        acc.y = ay;
-                        acc.z = az;
-                        sh.pend[nacc] = acc;
-                        sh.pend_pos[nacc] = i + nacc;
-                        stage_pick<T>(sh, i + nacc, aj, 0.0f);
-                    }
-                    const float t = dist2(ax, ay, az, me.x, me.y, me.z);
-                    const uint64_t kill = __builtin_amdgcn_ballot_w64(t < r2);
-                    alive &= ~kill;
-                    alive &= ~(1ull << cl);
-                    ++nacc;
-                }
-                if (wh.lane == 0) sh.ctrl[0] = nacc;
-            }
+            resolve_threshold<T>(sh, wh, st, total, limit, r2);
             __syncthreads();
-            npend = sh.ctrl[0];
-            const Cand lastp = sh.pend[npend - 1];
-            lx = lastp.x;
-            ly = lastp.y;
-            lz = lastp.z;
-            i += npend;
+            st.npend = sh.ctrl[0];
+            st.i += st.npend;
         }
 
-        if (ok && i < n) {
+        if (ok && st.i < n) {
             // ---- early termination (Alg. 2 lines 39-53): dists is already the true running
-            //      minimum, so the remainder is plain FPS; its first fold repeats sample i-1
-            et_index = i;
-            ok = fps_iterations<T, P, BQ>(pt, sh, wh, a, it, seq, i, n, false, -1, flushed, lx, ly, lz);
-            if (ok && BQ) fold<P, BQ>(pt, lx, ly, lz, a, wh, n - 1);
-        } else if (ok && BQ) {
-            fold_pending<T, P, BQ>(pt, sh, wh, a, npend);    // rows of the last picks
+            //      minimum, so the remainder is exact FPS on the same registers
+            et_index = st.i;
+            st.dlast = -1.0f;
+            ok = fps_rounds<T, P, BQ>(pt, sh, wh, a, it, seq, st, n, false);
         }
-    } else if (ok && BQ) {
-        // exact FPS: the last sample has not been folded, its row is still missing
-        fold<P, BQ>(pt, lx, ly, lz, a, wh, n - 1);
     }
+    // the rows of the picks that were never folded (at least the last sample) are still missing
+    if (ok && BQ) fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend);
 
-    if (ok) flush_picks<T, BQ>(a, sh, wh, flushed, n, true);
+    if (ok) flush_picks<T, BQ>(a, sh, wh, st.flushed, n, true);
     __syncthreads();
     if (writer && a.info) {
         fp_mdps_info inf = {};
@@ -739,7 +872,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             inf.level_exhausted[l] = sh.level_exhausted[l];
             inf.thr2[l] = sh.thr[l];
         }
-        inf.rounds = rounds;
+        inf.rounds = st.rounds;
         inf.status = ok ? 0 : 2;
         a.info[wh.c] = inf;
     }
