@@ -52,7 +52,7 @@ struct Shape {
 };
 constexpr Shape kShapes[] = {{256, 2}, {256, 4}, {256, 8}, {256, 16}, {256, 32}};
 constexpr int kNumShapes = (int)(sizeof(kShapes) / sizeof(kShapes[0]));
-constexpr int kTargetPointsPerWg = 4096;
+constexpr int kTargetPointsPerWg = 1024;
 
 bool shape_for(int64_t points_per_wg, Shape* s)
 {

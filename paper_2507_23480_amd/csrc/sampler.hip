@@ -41,6 +41,14 @@ constexpr int kStage = 256;             // ring of picks not yet written to glob
 constexpr int kFlush = 128;             // ... written out once this many are waiting
 
 // ---------------------------------------------------------------- wave helpers
+// Values that are equal in all lanes but come out of LDS or cross-lane operations: telling the
+// compiler so keeps the control flow that depends on them on the scalar unit.
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ float unif(float v)
+{
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(v)));
+}
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp(uint32_t v)
 {
@@ -76,12 +84,12 @@ __device__ __forceinline__ float rdlane_f(float v, int l)
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
     v = row_max_u32(v);
-    return max(max(rdlane(v, 0), rdlane(v, 16)), max(rdlane(v, 32), rdlane(v, 48)));
+    return uni(max(max(rdlane(v, 0), rdlane(v, 16)), max(rdlane(v, 32), rdlane(v, 48))));
 }
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
 {
     v = row_min_u32(v);
-    return min(min(rdlane(v, 0), rdlane(v, 16)), min(rdlane(v, 32), rdlane(v, 48)));
+    return uni(min(min(rdlane(v, 0), rdlane(v, 16)), min(rdlane(v, 32), rdlane(v, 48))));
 }
 __device__ __forceinline__ int first_lane(uint64_t mask) { return __builtin_ctzll(mask); }
 __device__ __forceinline__ int lanes_below(uint64_t mask)
@@ -168,7 +176,7 @@ struct Shared {
     int32_t wcnt[NW];
     Cand cand[kCand];
     Cand pend[kCand];
-    int32_t pend_pos[kCand];
+    int32_t bl[FP_MAX_SEG];    // segment boundaries b_l (curve positions that become thresholds)
     int32_t gpre[kMaxGroup + 1];
     int32_t ctrl[4];      // [0] accepted picks of the round, [1] points passing in the cloud,
                           // [2] failure, [3] distance bits of the last accepted pick
@@ -389,13 +397,17 @@ __device__ __noinline__ double pow_int_base(int64_t x, double e)
     return acc * __longlong_as_double((long long)(1023 + (int)q) << 52);
 }
 
+// Folds the picks waiting in sh.pend (sample positions base, base+1, ...) into the distances.
 template <int T, int P, bool BQ>
 __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
-                                             const SamplerArgs& a, int npend)
+                                             const SamplerArgs& a, int npend, int base)
 {
+    if (npend <= 0) return;
+    Cand nxt = sh.pend[0];
     for (int s = 0; s < npend; ++s) {
-        const Cand pc = sh.pend[s];
-        fold<P, BQ>(pt, pc.x, pc.y, pc.z, a, wh, sh.pend_pos[s]);
+        const Cand cur = nxt;
+        if (s + 1 < npend) nxt = sh.pend[s + 1];       // fetched while the current pick is folded
+        fold<P, BQ>(pt, cur.x, cur.y, cur.z, a, wh, base + s);
     }
 }
 
@@ -408,6 +420,16 @@ __device__ __forceinline__ int boundary_index(int n, int nseg, int l)
     return (int)b;
 }
 
+// Optional phase timing for tuning (-DFASTPOINT_PHASE_CLOCKS): wall-clock ticks spent in
+// fold / scan / resolve / plain picks, reported in info.thr2[8..11] (microseconds).
+#ifdef FASTPOINT_PHASE_CLOCKS
+#define PHASE_BEGIN() const long long phase_t0__ = wall_clock64()
+#define PHASE_END(st, k) (st).clk[k] += wall_clock64() - phase_t0__
+#else
+#define PHASE_BEGIN() do { } while (0)
+#define PHASE_END(st, k) do { } while (0)
+#endif
+
 // Progress of one cloud; every field is uniform over all workgroups of the cloud.
 struct CloudState {
     int i;          // next sample position to fill
@@ -417,6 +439,9 @@ struct CloudState {
     float dlast;    // squared distance of the last exact-FPS pick at pick time; < 0: unknown
     float om;       // an exact-FPS round takes the points above dlast * (1 - om) as candidates
     int my_bl;      // thread l < nseg: segment boundary b_(l+1); else -1
+#ifdef FASTPOINT_PHASE_CLOCKS
+    long long clk[4];
+#endif
 };
 
 // Curve capture of the prefix (Alg. 2 line 11), by the lanes of one wave.
@@ -437,8 +462,8 @@ __device__ __forceinline__ bool plain_pick(Points<P, BQ>& pt, Shared<T>& sh, con
                                            CloudState& st, bool capture)
 {
     const Rec r = cloud_argmax<T, P, BQ>(pt, sh, wh, a, it, seq);
-    if (r.fail) return false;
-    const float dpick = __uint_as_float(r.d);
+    if (uni(r.fail)) return false;
+    const float dpick = __uint_as_float(uni(r.d));
     if (wh.tid == 0) {
         stage_pick<T>(sh, st.i, r.idx, dpick);
         Cand c;
@@ -448,7 +473,6 @@ __device__ __forceinline__ bool plain_pick(Points<P, BQ>& pt, Shared<T>& sh, con
         c.z = r.z;
         c.d = r.d;
         sh.pend[0] = c;
-        sh.pend_pos[0] = st.i;
     }
     if (capture && wh.w == 0) capture_curve<T>(sh, wh, st, st.i, dpick);
     __syncthreads();
@@ -483,6 +507,8 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         off += (k < wh.w) ? v : 0;
         tot += v;
     }
+    off = uni(off);
+    tot = uni(tot);
     // 2. the workgroup's first kCand of them, in index order
     if (cntw > 0 && off < kCand) {
         int base = off;
@@ -560,10 +586,10 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         }
     }
     __syncthreads();
-    alltot = sh.ctrl[1];
-    const int listed = sh.gpre[wh.G];
+    alltot = uni(sh.ctrl[1]);
+    const int listed = uni(sh.gpre[wh.G]);
     total = listed < kCand ? listed : kCand;
-    if (sh.ctrl[2] == 0) {
+    if (uni(sh.ctrl[2]) == 0) {
         for (int e = wh.tid; e < total * kCandWords; e += T) {
             const int r = e / kCandWords, k = e - r * kCandWords;
             int lo = 0, hi = wh.G;             // workgroup whose range holds rank r
@@ -581,7 +607,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         }
     }
     __syncthreads();
-    return sh.ctrl[2] != 0 ? -1 : total;
+    return uni(sh.ctrl[2]) != 0 ? -1 : total;
 }
 
 // Threshold phase of Alg. 2 (lines 29-33 for up to kCand picks at once): the candidates are
@@ -592,30 +618,33 @@ __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh
                                                   int total, int limit, float r2)
 {
     if (wh.w != 0) return;
+    total = uni(total);
+    limit = uni(limit);
     const bool has = wh.lane < total;
     const Cand me = sh.cand[has ? wh.lane : 0];
     uint64_t alive = __builtin_amdgcn_ballot_w64(has);
     int nacc = 0;
+    Cand mine = me;                     // lane k ends up holding the k-th accepted pick
     while (alive != 0 && nacc < limit) {
         const int cl = first_lane(alive);
         const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
         const uint32_t aj = rdlane(me.idx, cl);
-        if (wh.lane == 0) {
-            Cand acc;
-            acc.idx = aj;
-            acc.x = ax;
-            acc.y = ay;
-            acc.z = az;
-            acc.d = 0;
-            sh.pend[nacc] = acc;
-            sh.pend_pos[nacc] = st.i + nacc;
-            stage_pick<T>(sh, st.i + nacc, aj, 0.0f);
+        if (wh.lane == nacc) {
+            mine.idx = aj;
+            mine.x = ax;
+            mine.y = ay;
+            mine.z = az;
         }
         const float t = dist2(ax, ay, az, me.x, me.y, me.z);
         const uint64_t kill = __builtin_amdgcn_ballot_w64(t < r2);
         alive &= ~kill;
         alive &= ~(1ull << cl);
         ++nacc;
+    }
+    if (wh.lane < nacc) {
+        mine.d = 0;
+        sh.pend[wh.lane] = mine;
+        stage_pick<T>(sh, st.i + wh.lane, mine.idx, 0.0f);
     }
     if (wh.lane == 0) sh.ctrl[0] = nacc;
 }
@@ -627,15 +656,18 @@ __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh
 // distances exactly as the fold will.  Stops when no candidate exceeds tau any more.
 template <int T>
 __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, const CloudState& st,
-                                              int total, int limit, float tau, bool capture)
+                                              int total, int limit, float tau, bool capture, int nseg)
 {
     if (wh.w != 0) return;
+    total = uni(total);
+    limit = uni(limit);
     const bool has = wh.lane < total;
     const Cand me = sh.cand[has ? wh.lane : 0];
     uint32_t cd = has ? me.d : 0u;                     // bit pattern; distances are >= +0
-    const uint32_t tau_bits = __float_as_uint(tau);    // tau >= 0
+    const uint32_t tau_bits = uni(__float_as_uint(tau));    // tau >= 0
     int nacc = 0;
-    float dl = st.dlast;
+    uint32_t dl = __float_as_uint(st.dlast);
+    Cand mine = me;                     // lane k ends up holding the k-th accepted pick
     while (nacc < limit) {
         const uint32_t dmax = wave_max_u32(cd);
         if (!(dmax > tau_bits)) break;
@@ -647,26 +679,32 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
         const int cl = first_lane(who);
         const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
         const uint32_t aj = rdlane(me.idx, cl);
-        dl = __uint_as_float(dmax);
-        if (wh.lane == 0) {
-            Cand acc;
-            acc.idx = aj;
-            acc.x = ax;
-            acc.y = ay;
-            acc.z = az;
-            acc.d = dmax;
-            sh.pend[nacc] = acc;
-            sh.pend_pos[nacc] = st.i + nacc;
-            stage_pick<T>(sh, st.i + nacc, aj, dl);
+        dl = dmax;
+        if (wh.lane == nacc) {
+            mine.idx = aj;
+            mine.x = ax;
+            mine.y = ay;
+            mine.z = az;
+            mine.d = dmax;
         }
-        if (capture) capture_curve<T>(sh, wh, st, st.i + nacc, dl);
         const float t = dist2(ax, ay, az, me.x, me.y, me.z);
         cd = has ? min(cd, __float_as_uint(t)) : 0u;
         ++nacc;
     }
+    if (wh.lane < nacc) {
+        const int pos = st.i + wh.lane;
+        const float d = __uint_as_float(mine.d);
+        sh.pend[wh.lane] = mine;
+        stage_pick<T>(sh, pos, mine.idx, d);
+        if (capture) {                  // Alg. 2 line 11: keep the curve of the prefix
+            sh.ring[pos & 63] = d;
+            for (int l = 0; l < nseg; ++l)
+                if (sh.bl[l] == pos) sh.thr_meas[l] = d;
+        }
+    }
     if (wh.lane == 0) {
         sh.ctrl[0] = nacc;
-        sh.ctrl[3] = (int)__float_as_uint(dl);
+        sh.ctrl[3] = (int)dl;
     }
 }
 
@@ -679,7 +717,11 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
 {
     while (st.i < upto) {
         flush_picks<T, BQ>(a, sh, wh, st.flushed, st.i, false);
-        fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend);
+        {
+            PHASE_BEGIN();
+            fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend, st.i - st.npend);
+            PHASE_END(st, 0);
+        }
         st.npend = 0;
         bool good = false;
         int total = 0, alltot = 0;
@@ -687,7 +729,9 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
         if (st.dlast > 0.0f && st.dlast < __builtin_inff()) {
             for (int tries = 0; tries < 4 && !good; ++tries) {
                 tau = st.dlast - st.om * st.dlast;
+                PHASE_BEGIN();
                 total = scan_candidates<T, P, BQ, true>(pt, sh, wh, a, seq, tau, alltot);
+                PHASE_END(st, 1);
                 if (total < 0) return false;
                 ++st.rounds;
                 if (alltot > 0 && alltot <= kCand) good = true;
@@ -696,13 +740,20 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
             }
         }
         if (!good) {
-            if (!plain_pick<T, P, BQ>(pt, sh, wh, a, it, seq, st, capture)) return false;
+            PHASE_BEGIN();
+            const bool picked = plain_pick<T, P, BQ>(pt, sh, wh, a, it, seq, st, capture);
+            PHASE_END(st, 3);
+            if (!picked) return false;
             continue;
         }
-        resolve_chain<T>(sh, wh, st, total, upto - st.i, tau, capture);
-        __syncthreads();
-        st.npend = sh.ctrl[0];
-        st.dlast = __uint_as_float((uint32_t)sh.ctrl[3]);
+        {
+            PHASE_BEGIN();
+            resolve_chain<T>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg);
+            __syncthreads();
+            PHASE_END(st, 2);
+        }
+        st.npend = uni(sh.ctrl[0]);
+        st.dlast = __uint_as_float(uni((uint32_t)sh.ctrl[3]));
         st.i += st.npend;
         if (alltot < 32) st.om = st.om * 1.15f < 0.99f ? st.om * 1.15f : 0.99f;
         else if (alltot > 52) st.om = st.om * 0.87f;
@@ -719,7 +770,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     const bool writer = (wh.g == 0 && wh.tid == 0);
     const float* cloud = a.xyz + (int64_t)wh.c * N * 3;
 
-    const int start = a.start_idx ? a.start_idx[wh.c] : 0;
+    const int start = uni(a.start_idx ? a.start_idx[wh.c] : 0);
     if (start < 0 || start >= N) {          // uniform over the group
         if (wh.g == 0) {
             for (int k = wh.tid; k < n; k += T) a.out_idx[(int64_t)wh.c * n + k] = -1;
@@ -753,6 +804,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         sh.level_exhausted[wh.tid] = 0;
         sh.thr[wh.tid] = 0.0f;
         sh.thr_meas[wh.tid] = 0.0f;
+        sh.bl[wh.tid] = wh.tid < a.nseg ? boundary_index(n, a.nseg, wh.tid + 1) : -1;
     }
     CloudState st;
     st.i = 1;
@@ -762,6 +814,9 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     st.dlast = -1.0f;
     st.om = 0.25f;
     st.my_bl = wh.tid < a.nseg ? boundary_index(n, a.nseg, wh.tid + 1) : -1;
+#ifdef FASTPOINT_PHASE_CLOCKS
+    st.clk[0] = st.clk[1] = st.clk[2] = st.clk[3] = 0;
+#endif
     if (wh.tid == 0) {
         sh.ctrl[2] = 0;
         Cand c0;                       // Alg. 1 line 1: the seed is sample 0, not folded yet
@@ -771,7 +826,6 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         c0.z = cloud[(int64_t)start * 3 + 2];
         c0.d = 0;
         sh.pend[0] = c0;
-        sh.pend_pos[0] = 0;
         stage_pick<T>(sh, 0, (uint32_t)start, __builtin_inff());
     }
     __syncthreads();
@@ -824,9 +878,9 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 seg = q;
                 if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
             }
-            fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend);   // picks accepted since the last sweep
+            fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend, st.i - st.npend);   // picks since the last sweep
             st.npend = 0;
-            const float r2 = sh.thr[seg - 1];
+            const float r2 = unif(sh.thr[seg - 1]);
             // samples of this level end where the quota rule would raise the level
             const int64_t qend = ((int64_t)n * seg + a.nseg - 1) / a.nseg;
             const int limit = (int)((qend < n ? qend : n) - st.i);
@@ -846,7 +900,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             }
             resolve_threshold<T>(sh, wh, st, total, limit, r2);
             __syncthreads();
-            st.npend = sh.ctrl[0];
+            st.npend = uni(sh.ctrl[0]);
             st.i += st.npend;
         }
 
@@ -859,7 +913,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         }
     }
     // the rows of the picks that were never folded (at least the last sample) are still missing
-    if (ok && BQ) fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend);
+    if (ok && BQ) fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend, st.i - st.npend);
 
     if (ok) flush_picks<T, BQ>(a, sh, wh, st.flushed, n, true);
     __syncthreads();
@@ -873,6 +927,10 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             inf.thr2[l] = sh.thr[l];
         }
         inf.rounds = st.rounds;
+#ifdef FASTPOINT_PHASE_CLOCKS
+        if (a.nseg <= 8)
+            for (int k = 0; k < 4; ++k) inf.thr2[8 + k] = (float)st.clk[k] * 0.01f;   // 100 MHz ticks
+#endif
         inf.status = ok ? 0 : 2;
         a.info[wh.c] = inf;
     }
