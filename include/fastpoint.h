@@ -117,7 +117,7 @@ fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n,
  * Ball query (Section 3.1 step 2): for centre q of cloud b (a point of that
  * cloud, center_idx[b][q]) the indices j with dist^2(centre, P[j]) < radius^2
  * (strict, binary32), ascending, first k kept; unused slots repeat the first
- * hit; out_cnt = min(hits, k).
+ * hit; out_cnt = min(hits, k).  1 <= k <= 254.
  *   center_idx [B][M] int32, out_idx [B][M][k] int32, out_cnt [B][M] int32 or NULL
  *   bq_cache   NULL = brute force over all N points.  Otherwise a cache filled
  *              by fp_fps_exact / fp_mdps_sample on the same xyz: centres that

@@ -256,7 +256,7 @@ fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N, const int32_t* c
                         const void* bq_cache, void* stream)
 {
     if (!xyz || !center_idx || !out_idx) return FP_ERR_NULL;
-    if (B < 1 || N < 1 || M < 0 || k < 1 || B > 65535) return FP_ERR_SHAPE;
+    if (B < 1 || N < 1 || M < 0 || k < 1 || k > 254 || B > 65535) return FP_ERR_SHAPE;
     if (!(radius > 0.0f) || !isfinite(radius)) return FP_ERR_PARAM;
     if (bq_cache && (reinterpret_cast<uintptr_t>(bq_cache) & 255u) != 0) return FP_ERR_WORKSPACE;
     const float r2 = radius * radius;

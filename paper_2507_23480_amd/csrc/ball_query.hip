@@ -3,9 +3,10 @@
 //
 // Two ball-query kernels produce identical output (first k hits by ascending
 // index, strict < on squared binary32 distances, padded with the first hit):
-//   * brute force, one centre per lane: the points are streamed in index order
-//     through scalar loads, so each lane scans "its" ball sequentially and the
-//     first-k rule and the early exit fall out of the loop order;
+//   * brute force, one centre per lane: the points are streamed in index order through
+//     scalar loads, so each lane scans "its" ball sequentially and the first-k rule and the
+//     early exit fall out of the loop order; the index range is split over the waves of a
+//     workgroup (more waves in flight) and the per-range hit lists are merged in LDS;
 //   * cache reader, one centre per wave: reads the bitmap row the sampler
 //     recorded for that sample (Section 4.2: the radius test was already done
 //     while the sample was folded into the distance array) and expands the
@@ -40,62 +41,102 @@ __device__ __forceinline__ int lanes_below(uint64_t mask)
 
 constexpr int kChunk = 16;      // points tested per pass of the brute-force inner loop
 
-__global__ __launch_bounds__(256) void bq_brute_kernel(const float* __restrict__ xyz, int N,
-                                                       const int32_t* __restrict__ center_idx, int M,
-                                                       float r2, int k, int32_t* __restrict__ out_idx,
-                                                       int32_t* __restrict__ out_cnt)
+// Brute-force ball query.  A workgroup of S waves owns 64 centres (one per lane); wave w scans
+// the w-th of S equal index ranges of the cloud, so S times as many waves are in flight as
+// there are groups of 64 centres and the scalar point loads of one wave hide behind the
+// arithmetic of the others.  Each wave keeps the first k hits of its range per centre in LDS;
+// the ranges are then concatenated in index order and cut at k.
+//   LDS: hits [S][64][k+1] int32, counts [S][64] int32  (dynamic, S*64*(k+2)*4 bytes)
+template <int S>
+__global__ __launch_bounds__(S * 64) void bq_brute_kernel(const float* __restrict__ xyz, int N,
+                                                          const int32_t* __restrict__ center_idx, int M,
+                                                          float r2, int k, int32_t* __restrict__ out_idx,
+                                                          int32_t* __restrict__ out_cnt)
 {
+    extern __shared__ int32_t lds[];
+    const int kp = k + 1;                                   // padded row: conflict-free columns
+    int32_t* hits = lds;                                    // [S][64][kp]
+    int32_t* counts = lds + S * 64 * kp;                    // [S][64]
     const int b = (int)blockIdx.y;
-    const int q = (int)blockIdx.x * 256 + (int)threadIdx.x;
+    const int lane = (int)threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);    // wave-uniform: scalar loads
+    const int q0 = (int)blockIdx.x * 64;
+    const int q = q0 + lane;
     const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
-    const bool active = q < M;
-    const int c = active ? center_idx[(int64_t)b * M + q] : 0;
-    const bool okc = active && c >= 0 && c < N;
-    const float cx = okc ? cloud[(int64_t)c * 3 + 0] : 0.0f;
+    const int c = q < M ? center_idx[(int64_t)b * M + q] : -1;
+    const bool okc = c >= 0 && c < N;
+    // a centre that does not exist compares false against every point
+    const float cx = okc ? cloud[(int64_t)c * 3 + 0] : __builtin_nanf("");
     const float cy = okc ? cloud[(int64_t)c * 3 + 1] : 0.0f;
     const float cz = okc ? cloud[(int64_t)c * 3 + 2] : 0.0f;
-    int32_t* row = out_idx + ((int64_t)b * M + (active ? q : 0)) * k;
-    int cnt = 0;
-    int first = -1;
 
-    const int nfull = N - (N % kChunk);
-    int j0 = 0;
+    int seg_len = (N + S - 1) / S;
+    seg_len = (seg_len + kChunk - 1) / kChunk * kChunk;
+    const int j_begin = w * seg_len < N ? w * seg_len : N;
+    const int j_end = (w + 1) * seg_len < N ? (w + 1) * seg_len : N;
+    int32_t* myrow = hits + ((int64_t)w * 64 + lane) * kp;
+    int cnt = 0;
+
+    const int nfull = j_begin + (j_end - j_begin) / kChunk * kChunk;
+    int j0 = j_begin;
     for (; j0 < nfull; j0 += kChunk) {
         if (__builtin_amdgcn_ballot_w64(okc && cnt < k) == 0) break;
-        bool hit[kChunk];
+        uint64_t m[kChunk];
         uint64_t any = 0;
+        const float* __restrict__ pb = cloud + (int64_t)j0 * 3;   // uniform address: scalar loads
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) {
-            const float* pj = cloud + (int64_t)(j0 + u) * 3;      // uniform address: scalar loads
-            const float t = dist2(cx, cy, cz, pj[0], pj[1], pj[2]);
-            hit[u] = okc && (t < r2);
-            any |= __builtin_amdgcn_ballot_w64(hit[u]);
+            const float t = dist2(cx, cy, cz, pb[3 * u + 0], pb[3 * u + 1], pb[3 * u + 2]);
+            m[u] = __builtin_amdgcn_ballot_w64(t < r2);
+            any |= m[u];
         }
         if (any != 0) {
 #pragma unroll
             for (int u = 0; u < kChunk; ++u) {
-                if (hit[u] && cnt < k) {
-                    row[cnt] = j0 + u;
-                    if (cnt == 0) first = j0 + u;
+                if (((m[u] >> lane) & 1ull) && cnt < k) {
+                    myrow[cnt] = j0 + u;
                     ++cnt;
                 }
             }
         }
     }
     if (j0 >= nfull) {
-        for (int j = nfull; j < N; ++j) {
+        for (int j = nfull; j < j_end; ++j) {
             const float* pj = cloud + (int64_t)j * 3;
             const float t = dist2(cx, cy, cz, pj[0], pj[1], pj[2]);
-            if (okc && t < r2 && cnt < k) {
-                row[cnt] = j;
-                if (cnt == 0) first = j;
+            if (t < r2 && cnt < k) {
+                myrow[cnt] = j;
                 ++cnt;
             }
         }
     }
-    if (active) {
-        for (int t = cnt; t < k; ++t) row[t] = first;
-        if (out_cnt) out_cnt[(int64_t)b * M + q] = cnt;
+    counts[w * 64 + lane] = cnt;
+    __syncthreads();
+
+    // concatenate the S ranges of every centre in index order, cut at k, pad with the first hit
+    for (int cc = w; cc < 64; cc += S) {
+        const int qq = q0 + cc;
+        if (qq >= M) break;
+        int off[S + 1];
+        off[0] = 0;
+#pragma unroll
+        for (int sgm = 0; sgm < S; ++sgm) off[sgm + 1] = off[sgm] + counts[sgm * 64 + cc];
+        const int total = off[S] < k ? off[S] : k;
+        int first = -1;
+#pragma unroll
+        for (int sgm = S - 1; sgm >= 0; --sgm)
+            if (off[sgm + 1] > off[sgm]) first = hits[((int64_t)sgm * 64 + cc) * kp];
+        int32_t* row = out_idx + ((int64_t)b * M + qq) * k;
+        for (int t = lane; t < k; t += 64) {
+            int v = first;
+            if (t < total) {
+#pragma unroll
+                for (int sgm = 0; sgm < S; ++sgm)
+                    if (t >= off[sgm] && t < off[sgm + 1]) v = hits[((int64_t)sgm * 64 + cc) * kp + (t - off[sgm])];
+            }
+            row[t] = v;
+        }
+        if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + qq] = total;
     }
 }
 
@@ -242,8 +283,23 @@ hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* cent
                            center_idx, M, r2, k, out_idx, out_cnt,
                            reinterpret_cast<const unsigned char*>(bq_cache));
     } else {
-        hipLaunchKernelGGL(bq_brute_kernel, dim3((unsigned)((M + 255) / 256), (unsigned)B), dim3(256), 0,
-                           stream, xyz, N, center_idx, M, r2, k, out_idx, out_cnt);
+        // as many waves per group of 64 centres as the hit lists leave room for in 48 KB of LDS
+        const dim3 grid((unsigned)((M + 63) / 64), (unsigned)B);
+        const size_t per_wave = (size_t)64 * (k + 2) * sizeof(int32_t);
+        if (8 * per_wave <= 48 * 1024)
+            hipLaunchKernelGGL(bq_brute_kernel<8>, grid, dim3(512), 8 * per_wave, stream, xyz, N, center_idx, M,
+                               r2, k, out_idx, out_cnt);
+        else if (4 * per_wave <= 48 * 1024)
+            hipLaunchKernelGGL(bq_brute_kernel<4>, grid, dim3(256), 4 * per_wave, stream, xyz, N, center_idx, M,
+                               r2, k, out_idx, out_cnt);
+        else if (2 * per_wave <= 48 * 1024)
+            hipLaunchKernelGGL(bq_brute_kernel<2>, grid, dim3(128), 2 * per_wave, stream, xyz, N, center_idx, M,
+                               r2, k, out_idx, out_cnt);
+        else if (per_wave <= 64 * 1024)
+            hipLaunchKernelGGL(bq_brute_kernel<1>, grid, dim3(64), per_wave, stream, xyz, N, center_idx, M, r2,
+                               k, out_idx, out_cnt);
+        else
+            return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
