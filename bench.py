@@ -28,9 +28,11 @@ HBM_PEAK_GBS = 8000.0
 OPS_PER_POINT_ITERATION = 10      # 3 sub, 3 mul, 2 add, 1 min, 1 compare (FPS min-update + arg-max)
 OPS_PER_PAIR_TEST = 9             # 3 sub, 3 mul, 2 add, 1 compare (ball query)
 
-# HBM traffic of the dominant kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs (see profiles/); bytes, keyed by workload.  None where no counter run is recorded.
-TRAFFIC_BYTES = {"C2": int((187.7 * 2.0 + 32.4) * 1024)}    # profiles/bench_C2_hbm_traffic.md
+# HBM traffic per launch of the kernels that can dominate the step, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs (profiles/bench_C2_hbm_traffic.md); bytes, keyed by workload and
+# kernel.  None where no counter run is recorded.
+TRAFFIC_BYTES = {"C2": {"fps_exact": int((226.0 * 2.0 + 32.4) * 1024),
+                        "mdps_sample+record": int((361.4 * 2.0 + 1088.0) * 1024)}}
 
 
 def parse_args():
@@ -257,7 +259,7 @@ def main():
     roof = dict(s0["roofline"][dom])
     roof["kernel"] = dom + " (stage 0)"
     roof["ms_per_launch"] = s0["kernel_ms"][dom]
-    roof["traffic"] = TRAFFIC_BYTES.get(name)
+    roof["traffic"] = TRAFFIC_BYTES.get(name, {}).get(dom)
     line = {
         "metric": "FPS+ball-query latency per batch (ms) and Mpoints/s; achieved HBM GB/s vs peak",
         "value": wl.B * wl.N / (ms_per_step * 1e-3) / 1e6, "unit": "Mpoints/s",
