@@ -206,27 +206,52 @@ struct Points {
 
 // Alg. 1 lines 4-7 for this thread's points; with BQ also the radius test of
 // Section 4.2, one 64-bit word per slot written to row `pos` of the cache.
+template <int P, bool BQ, int P0>
+__device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float cy, float cz, float bq_r2,
+                                            int lane, uint32_t& word_lo, uint32_t& word_hi)
+{
+    constexpr int GRP = P < 8 ? P : 8;      // slots whose radius tests are examined together
+    if constexpr (P0 < P) {
+        uint32_t tb[GRP];                   // squared distances as bit patterns (>= +0: unsigned order)
+        uint32_t tmin = 0xFFFFFFFFu;
+#pragma unroll
+        for (int u = 0; u < GRP; ++u) {
+            const int p = P0 + u;
+            tb[u] = __float_as_uint(dist2(cx, cy, cz, pt.x[p], pt.y[p], pt.z[p]));
+            pt.d[p] = __uint_as_float(min(__float_as_uint(pt.d[p]), tb[u]));
+            if (BQ) tmin = min(tmin, tb[u]);
+        }
+        if (BQ) {
+            // most balls miss most waves: one test per group on the vector unit; the per-slot
+            // masks are formed and routed to their lanes only when some point of the group hits
+            const uint32_t r2b = __float_as_uint(bq_r2);
+            if (__builtin_amdgcn_ballot_w64(tmin < r2b) != 0) {
+#pragma unroll
+                for (int u = 0; u < GRP; ++u) {
+                    const uint64_t hit = __builtin_amdgcn_ballot_w64(tb[u] < r2b);
+                    if (lane == P0 + u) {           // lane p collects the mask of slot p
+                        word_lo = (uint32_t)hit;
+                        word_hi = (uint32_t)(hit >> 32);
+                    }
+                }
+            }
+        }
+        fold_groups<P, BQ, P0 + GRP>(pt, cx, cy, cz, bq_r2, lane, word_lo, word_hi);
+    }
+}
+
 template <int P, bool BQ>
 __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, float cz,
                                      const SamplerArgs& a, const Where& wh, int pos)
 {
-    uint64_t myword = 0;
-#pragma unroll
-    for (int p = 0; p < P; ++p) {
-        float t = dist2(cx, cy, cz, pt.x[p], pt.y[p], pt.z[p]);
-        // distances are >= +0, so the unsigned order of the bit patterns is their order
-        pt.d[p] = __uint_as_float(min(__float_as_uint(pt.d[p]), __float_as_uint(t)));
-        if (BQ) {
-            uint64_t hit = __builtin_amdgcn_ballot_w64(t < a.bq_r2);
-            if (wh.lane == p) myword = hit;
-        }
-    }
+    uint32_t word_lo = 0, word_hi = 0;      // lane p < P collects the hit mask of slot p
+    fold_groups<P, BQ, 0>(pt, cx, cy, cz, a.bq_r2, wh.lane, word_lo, word_hi);
     if (BQ) {
         // rows hold ceil(N/64) words (rounded up); slots wholly beyond N have no word
         if (wh.lane < P && (int64_t)wh.gw * P + wh.lane < a.bq_row_words) {
             uint64_t* row = a.bq_bits + ((int64_t)wh.c * a.n + pos) * a.bq_row_words +
                             (int64_t)wh.gw * P;
-            row[wh.lane] = myword;
+            row[wh.lane] = ((uint64_t)word_hi << 32) | word_lo;
         }
     }
 }
