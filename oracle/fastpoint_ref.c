@@ -561,6 +561,53 @@ int ref_gather_xyz(const float *xyz, int32_t N, const int32_t *idx, int32_t M, f
     return 0;
 }
 
+/* ------------------------------------------------------ k nearest samples -- */
+/*
+ * k-NN of the up-sampling (feature propagation) step, Section 3.1: for every
+ * point of the cloud its k nearest SAMPLED points.  Section 4.2 ("Redundancy-Free
+ * k-NN") reaches the same result from a reduced search space, so the oracle is
+ * the plain definition: all n squared binary32 distances of point j, then k
+ * times the smallest one not taken yet.  The paper does not order equal
+ * distances; here the sample with the lower position q comes first.
+ *   sample_idx [n] indices into the cloud (the sampler's output), 1 <= k <= n
+ *   out_pos [N][k] positions q (into sample_idx), nearest first
+ *   out_d2  [N][k] the squared distances, ascending
+ */
+int ref_knn(const float *xyz, int32_t N, const int32_t *sample_idx, int32_t n, int32_t k,
+            int32_t *out_pos, float *out_d2)
+{
+    if (!xyz || !sample_idx || !out_pos || !out_d2 || N < 1 || n < 1 || k < 1 || k > n)
+        return -1;
+    for (int32_t q = 0; q < n; ++q)
+        if (sample_idx[q] < 0 || sample_idx[q] >= N)
+            return -1;
+    float *d = (float *)malloc((size_t)n * sizeof(float));
+    unsigned char *taken = (unsigned char *)malloc((size_t)n);
+    if (!d || !taken) {
+        free(d);
+        free(taken);
+        return -2;
+    }
+    for (int32_t j = 0; j < N; ++j) {
+        for (int32_t q = 0; q < n; ++q) {
+            d[q] = ref_dist2(xyz + 3 * (size_t)j, xyz + 3 * (size_t)sample_idx[q]);
+            taken[q] = 0;
+        }
+        for (int32_t t = 0; t < k; ++t) {
+            int32_t best = -1;
+            for (int32_t q = 0; q < n; ++q)
+                if (!taken[q] && (best < 0 || d[q] < d[best]))
+                    best = q;
+            taken[best] = 1;
+            out_pos[(size_t)j * k + t] = best;
+            out_d2[(size_t)j * k + t] = d[best];
+        }
+    }
+    free(d);
+    free(taken);
+    return 0;
+}
+
 /* --------------------------------------------------------- quality metrics -- */
 /* binary64 Euclidean distance from the binary32 inputs */
 static double ref_dist_f64(const float *a, const float *b)
