@@ -41,6 +41,7 @@ enum {
 };
 
 #define FP_MAX_SEG 16
+#define FP_KNN_MAX_K 8
 
 /* MDPS hyper-parameters (Section 4.1; Appendix A.3 for the estimator). Host struct. */
 typedef struct fp_mdps_params {
@@ -131,6 +132,34 @@ fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N,
                         const int32_t* center_idx, int32_t M, float radius, int32_t k,
                         int32_t* out_idx, int32_t* out_cnt,
                         const void* bq_cache, void* stream);
+
+/* Bytes of workspace fp_knn needs when it is given a cache (0 for shapes the library
+ * rejects).  Alignment: 256 bytes. */
+size_t fp_knn_workspace_bytes(int32_t B, int32_t N);
+
+/*
+ * k nearest samples of every point -- the k-NN of the up-sampling (feature propagation)
+ * step, Section 3.1: for point j of cloud b the k samples with the smallest squared
+ * binary32 distance, nearest first; among equal distances the lower position q first.
+ *   sample_idx [B][n] int32 indices into the cloud (a sampler's output), 1 <= k <= min(n, 8)
+ *   out_pos    [B][N][k] int32 positions q into sample_idx
+ *   out_d2     [B][N][k] float32 squared distances, ascending
+ *   bq_cache   NULL = every point is compared with all n samples.  Otherwise a cache
+ *              filled by fp_fps_exact / fp_mdps_sample on the same xyz whose samples are
+ *              sample_idx (redundancy-free k-NN, Section 4.2): the search space of a point
+ *              is the samples whose recorded ball contains it, which are its k nearest
+ *              whenever there are at least k of them; points with fewer, and clouds whose
+ *              sample list differs from the cached one, are searched by brute force in a
+ *              second pass.  Results are identical to the brute-force search.
+ *   out_deferred [B] int32 or NULL: with a cache, the number of points per cloud that took
+ *              the brute-force pass
+ *   workspace  required with a cache (fp_knn_workspace_bytes), else ignored
+ * A sample index outside [0,N) is never a neighbour; slots no sample fills hold
+ * position -1 and distance +inf.
+ */
+fp_status fp_knn(const float* xyz, int32_t B, int32_t N, const int32_t* sample_idx, int32_t n,
+                 int32_t k, int32_t* out_pos, float* out_d2, const void* bq_cache,
+                 int32_t* out_deferred, void* workspace, size_t workspace_bytes, void* stream);
 
 /* out_xyz[b][q] = xyz[b][idx[b][q]] -- input of the next stage of a hierarchy
  * (Section 3.1).  Indices outside [0,N) give NaN coordinates. */

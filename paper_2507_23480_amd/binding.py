@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
 EXPORTS = ["fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
-           "fp_ball_query", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
+           "fp_ball_query", "fp_knn_workspace_bytes", "fp_knn", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
 
 
@@ -98,6 +98,10 @@ def load() -> ctypes.CDLL:
     lib.fp_mdps_sample.restype = i32
     lib.fp_ball_query.argtypes = [vp, i32, i32, vp, i32, f32, i32, vp, vp, vp, vp]
     lib.fp_ball_query.restype = i32
+    lib.fp_knn_workspace_bytes.argtypes = [i32, i32]
+    lib.fp_knn_workspace_bytes.restype = ctypes.c_size_t
+    lib.fp_knn.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.fp_knn.restype = i32
     lib.fp_gather_xyz.argtypes = [vp, i32, i32, vp, i32, vp, vp]
     lib.fp_gather_xyz.restype = i32
     lib.fp_coverage.argtypes = [vp, i32, i32, vp, i32, vp, vp]
@@ -240,6 +244,30 @@ def ball_query(xyz: torch.Tensor, center_idx: torch.Tensor, radius: float, k: in
                                 idx.data_ptr(), cnt.data_ptr(), _ptr(bq_cache), _stream()),
            "fp_ball_query")
     return idx, cnt
+
+
+def knn(xyz: torch.Tensor, sample_idx: torch.Tensor, k: int, bq_cache: Optional[torch.Tensor] = None,
+        want_deferred: bool = False):
+    """k nearest samples of every point: (pos [B][N][k] int32 positions into sample_idx,
+    d2 [B][N][k] float32); with want_deferred also the per-cloud number of points that the
+    cached search handed to the brute-force pass."""
+    B, N = _xyz(xyz)
+    if not (sample_idx.is_cuda and sample_idx.dtype == torch.int32 and sample_idx.dim() == 2
+            and sample_idx.shape[0] == B and sample_idx.is_contiguous()):
+        raise ValueError("sample_idx must be a contiguous CUDA int32 tensor [B][n]")
+    n = int(sample_idx.shape[1])
+    pos = torch.empty((B, N, k), dtype=torch.int32, device=xyz.device)
+    d2 = torch.empty((B, N, k), dtype=torch.float32, device=xyz.device)
+    ws, ws_bytes, deferred = None, 0, None
+    if bq_cache is not None:
+        ws_bytes = int(load().fp_knn_workspace_bytes(B, N))
+        if ws_bytes == 0:
+            raise ValueError("shape (B=%d, N=%d) not supported" % (B, N))
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=xyz.device)
+        deferred = torch.zeros(B, dtype=torch.int32, device=xyz.device)
+    _check(load().fp_knn(xyz.data_ptr(), B, N, sample_idx.data_ptr(), n, k, pos.data_ptr(), d2.data_ptr(),
+                         _ptr(bq_cache), _ptr(deferred), _ptr(ws), ws_bytes, _stream()), "fp_knn")
+    return (pos, d2, deferred) if want_deferred else (pos, d2)
 
 
 def gather_xyz(xyz: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:

@@ -265,6 +265,36 @@ fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N, const int32_t* c
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }
 
+size_t fp_knn_workspace_bytes(int32_t B, int32_t N)
+{
+    if (B < 1 || N < 1 || B > 65535) return 0;
+    // per cloud: a flag, a counter and a list of up to N deferred points
+    return (size_t)(2 * align_up((int64_t)B * 4, 256) + align_up((int64_t)B * N * 4, 256));
+}
+
+fp_status fp_knn(const float* xyz, int32_t B, int32_t N, const int32_t* sample_idx, int32_t n, int32_t k,
+                 int32_t* out_pos, float* out_d2, const void* bq_cache, int32_t* out_deferred,
+                 void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!xyz || !sample_idx || !out_pos || !out_d2) return FP_ERR_NULL;
+    if (B < 1 || N < 1 || n < 1 || k < 1 || k > FP_KNN_MAX_K || k > n || B > 65535) return FP_ERR_SHAPE;
+    if ((int64_t)B * N > (int64_t)1 << 40) return FP_ERR_SHAPE;
+    int32_t *flags = nullptr, *count = nullptr, *list = nullptr;
+    if (bq_cache) {
+        if ((reinterpret_cast<uintptr_t>(bq_cache) & 255u) != 0) return FP_ERR_WORKSPACE;
+        if (!workspace || workspace_bytes < fp_knn_workspace_bytes(B, N) ||
+            (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+            return FP_ERR_WORKSPACE;
+        unsigned char* base = reinterpret_cast<unsigned char*>(workspace);
+        flags = reinterpret_cast<int32_t*>(base);
+        count = reinterpret_cast<int32_t*>(base + align_up((int64_t)B * 4, 256));
+        list = reinterpret_cast<int32_t*>(base + 2 * align_up((int64_t)B * 4, 256));
+    }
+    hipError_t err = launch_knn(xyz, B, N, sample_idx, n, k, out_pos, out_d2, bq_cache, flags, count, list,
+                                bq_cache ? out_deferred : nullptr, reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
 fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N, const int32_t* idx, int32_t M,
                         float* out_xyz, void* stream)
 {

@@ -1,0 +1,139 @@
+"""GPU parity of the k nearest samples (Section 3.1 feature propagation; redundancy-free form
+Section 4.2) against the CPU oracle, through the C ABI: positions bit-exact, squared
+distances bit-exact (same binary32 operations in the same order)."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2507_23480_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fp():
+    from paper_2507_23480_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    binding.set_wg_per_cloud(0)
+    yield binding
+    binding.set_wg_per_cloud(0)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def check_knn(fp, batch, sidx, k, cache=None):
+    out = fp.knn(dev(batch), dev(sidx.astype(np.int32)), k, bq_cache=cache, want_deferred=cache is not None)
+    torch.cuda.synchronize()
+    pos, d2 = out[0].cpu().numpy(), out[1].cpu().numpy()
+    for b in range(batch.shape[0]):
+        wp, wd = ref.knn(batch[b], sidx[b], k)
+        assert np.array_equal(pos[b], wp), "knn positions cloud %d" % b
+        assert np.array_equal(d2[b], wd), "knn distances cloud %d" % b
+    return out[2].cpu().numpy() if cache is not None else None
+
+
+@pytest.mark.parametrize("N,n,k", [(9, 5, 3), (64, 64, 1), (300, 40, 3), (1000, 257, 8), (2049, 513, 3),
+                                   (5000, 700, 5), (700, 2, 2)])
+def test_knn_brute_matches_oracle(fp, N, n, k):
+    say("knn brute N=%d n=%d k=%d" % (N, n, k))
+    if N == 9:
+        cloud = np.stack([np.arange(9), np.zeros(9), np.zeros(9)], axis=1).astype(np.float32)[None]
+        sidx = np.array([[0, 8, 4, 2, 6]])
+    else:
+        cloud = inputs.uniform_cube(900 + N, N)[None]
+        sidx = np.random.Generator(np.random.PCG64(N)).permutation(N)[:n][None]
+    check_knn(fp, cloud, sidx, k)
+
+
+def test_knn_ties_duplicates_and_batches(fp):
+    # lattice clouds: many equal distances, repeated samples; three clouds per call
+    batch = np.stack([inputs.lattice_with_ties(70 + b, 777, 5) for b in range(3)])
+    sidx = np.random.Generator(np.random.PCG64(7)).integers(0, 777, (3, 300))
+    check_knn(fp, batch, sidx, 3)
+    check_knn(fp, batch, sidx, 8)
+
+
+def test_knn_invalid_sample_is_never_a_neighbour(fp):
+    cloud = inputs.uniform_cube(33, 500)[None]
+    sidx = np.array([[5, -1, 17, 500, 40, 3]], dtype=np.int32)
+    pos, d2 = fp.knn(dev(cloud), dev(sidx), 3)
+    torch.cuda.synchronize()
+    valid = np.array([0, 2, 4, 5])
+    wp, wd = ref.knn(cloud[0], sidx[0, valid], 3)
+    assert np.array_equal(pos.cpu().numpy()[0], valid[wp])
+    assert np.array_equal(d2.cpu().numpy()[0], wd)
+    # fewer valid samples than k: the open slots say so
+    pos, d2 = fp.knn(dev(cloud), dev(np.array([[9, 600, -3]], dtype=np.int32)), 2)
+    torch.cuda.synchronize()
+    assert np.all(pos.cpu().numpy()[0, :, 0] == 0) and np.all(pos.cpu().numpy()[0, :, 1] == -1)
+    assert np.all(np.isinf(d2.cpu().numpy()[0, :, 1]))
+
+
+def test_knn_rejects_bad_shapes(fp):
+    cloud = dev(inputs.uniform_cube(1, 100)[None])
+    s = dev(np.arange(4, dtype=np.int32)[None])
+    with pytest.raises(RuntimeError):
+        fp.knn(cloud, s, 5)                   # k > n
+    with pytest.raises(RuntimeError):
+        fp.knn(cloud, dev(np.arange(20, dtype=np.int32)[None]), 9)   # k above the limit
+
+
+@pytest.mark.parametrize("sampler", ["fps", "mdps"])
+@pytest.mark.parametrize("N,n,G,radius,k", [(4096, 1024, 0, 0.15, 3), (9001, 1500, 3, 0.12, 3),
+                                            (700, 700, 0, 0.3, 8), (3000, 200, 0, 0.05, 3),
+                                            (2500, 300, 0, 0.6, 1)])
+def test_redundancy_free_knn_equals_oracle(fp, sampler, N, n, G, radius, k):
+    # Section 4.2: the recorded balls only shrink the search space; the result is the exact k-NN
+    say("knn cached %s N=%d n=%d G=%d r=%g k=%d" % (sampler, N, n, G, radius, k))
+    cloud = inputs.uniform_cube(500 + N, N)[None]
+    xyz = dev(cloud)
+    fp.set_wg_per_cloud(G)
+    try:
+        cache = fp.new_bq_cache(xyz, n)
+        if sampler == "fps":
+            idx = fp.fps_exact(xyz, n, bq_cache=cache, bq_radius=radius)
+        else:
+            idx = fp.mdps_sample(xyz, n, fp.MdpsParams(exponent=0.8, bias=1.05), bq_cache=cache,
+                                 bq_radius=radius)
+    finally:
+        fp.set_wg_per_cloud(0)
+    torch.cuda.synchronize()
+    sidx = idx.cpu().numpy()
+    deferred = check_knn(fp, cloud, sidx, k, cache=cache)
+    # the number of points sent to the brute-force pass is the number with fewer than k samples
+    # inside the radius
+    D = np.sort(ref.knn(cloud[0], sidx[0], k)[1], axis=1)
+    r2 = np.float32(radius) * np.float32(radius)
+    assert int(deferred[0]) == int(np.count_nonzero(~(D[:, k - 1] < r2)))
+    say("  deferred %d of %d" % (int(deferred[0]), N))
+    # a sample list that is not the cached one: everything is searched by brute force
+    other = np.random.Generator(np.random.PCG64(3)).permutation(N)[:n][None]
+    deferred = check_knn(fp, cloud, other, k, cache=cache)
+    assert int(deferred[0]) == N
+
+
+def test_redundancy_free_knn_batches(fp):
+    batch = inputs.make_batch("C2", B=5)
+    xyz = dev(batch)
+    cache = fp.new_bq_cache(xyz, 256)
+    idx = fp.fps_exact(xyz, 256, bq_cache=cache, bq_radius=0.25)
+    torch.cuda.synchronize()
+    sidx = idx.cpu().numpy()
+    deferred = check_knn(fp, batch, sidx, 3, cache=cache)
+    assert deferred.shape == (5,)
+    # one cloud's list altered: only that cloud loses the cache
+    sidx2 = sidx.copy()
+    sidx2[2, 10] = sidx2[2, 11]
+    deferred = check_knn(fp, batch, sidx2, 3, cache=cache)
+    assert int(deferred[2]) == batch.shape[1]
