@@ -181,6 +181,9 @@ fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
  * Process-wide; not meant for concurrent use. */
 void fp_set_wg_per_cloud(int32_t wg_per_cloud);
 
+/* Tuning hook: threads per sampler workgroup, 256 or 512.  Process-wide. */
+void fp_set_threads_per_wg(int32_t threads);
+
 /* Multi-workgroup launches are cooperative by default (the runtime guarantees that all
  * workgroups are resident, which the waits between them rely on).  0 switches to a plain
  * launch, for tools that cannot trace cooperative launches: the grid never exceeds one

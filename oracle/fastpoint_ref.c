@@ -570,14 +570,21 @@ int ref_gather_xyz(const float *xyz, int32_t N, const int32_t *idx, int32_t M, f
  * times the smallest one not taken yet.  The paper does not order equal
  * distances; here the sample with the lower position q comes first.
  *   sample_idx [n] indices into the cloud (the sampler's output), 1 <= k <= n
- *   out_pos [N][k] positions q (into sample_idx), nearest first
- *   out_d2  [N][k] the squared distances, ascending
+ *   point_idx  NULL: all N points, M = N.  Else [M] indices of the points wanted (lets a test
+ *              check a sample of a large cloud)
+ *   out_pos [M][k] positions q (into sample_idx), nearest first
+ *   out_d2  [M][k] the squared distances, ascending
  */
 int ref_knn(const float *xyz, int32_t N, const int32_t *sample_idx, int32_t n, int32_t k,
-            int32_t *out_pos, float *out_d2)
+            const int32_t *point_idx, int32_t M, int32_t *out_pos, float *out_d2)
 {
     if (!xyz || !sample_idx || !out_pos || !out_d2 || N < 1 || n < 1 || k < 1 || k > n)
         return -1;
+    if (!point_idx)
+        M = N;
+    for (int32_t r = 0; point_idx && r < M; ++r)
+        if (point_idx[r] < 0 || point_idx[r] >= N)
+            return -1;
     for (int32_t q = 0; q < n; ++q)
         if (sample_idx[q] < 0 || sample_idx[q] >= N)
             return -1;
@@ -588,7 +595,8 @@ int ref_knn(const float *xyz, int32_t N, const int32_t *sample_idx, int32_t n, i
         free(taken);
         return -2;
     }
-    for (int32_t j = 0; j < N; ++j) {
+    for (int32_t r = 0; r < M; ++r) {
+        int32_t j = point_idx ? point_idx[r] : r;
         for (int32_t q = 0; q < n; ++q) {
             d[q] = ref_dist2(xyz + 3 * (size_t)j, xyz + 3 * (size_t)sample_idx[q]);
             taken[q] = 0;
@@ -599,8 +607,8 @@ int ref_knn(const float *xyz, int32_t N, const int32_t *sample_idx, int32_t n, i
                 if (!taken[q] && (best < 0 || d[q] < d[best]))
                     best = q;
             taken[best] = 1;
-            out_pos[(size_t)j * k + t] = best;
-            out_d2[(size_t)j * k + t] = d[best];
+            out_pos[(size_t)r * k + t] = best;
+            out_d2[(size_t)r * k + t] = d[best];
         }
     }
     free(d);

@@ -92,7 +92,7 @@ def lib() -> ctypes.CDLL:
         _lib.ref_mdps_literal.argtypes = _lib.ref_mdps_sample.argtypes
         _lib.ref_ball_query.argtypes = [fp, i32, ip, i32, ctypes.c_float, i32, ip, ip]
         _lib.ref_gather_xyz.argtypes = [fp, i32, ip, i32, fp]
-        _lib.ref_knn.argtypes = [fp, i32, ip, i32, i32, ip, fp]
+        _lib.ref_knn.argtypes = [fp, i32, ip, i32, i32, ip, i32, ip, fp]
         _lib.ref_coverage_radius.argtypes = [fp, i32, ip, i32]
         _lib.ref_coverage_radius.restype = ctypes.c_double
         _lib.ref_mean_spacing.argtypes = [fp, ip, i32]
@@ -183,15 +183,18 @@ def ball_query(xyz, centers, radius: float, k: int) -> Tuple[np.ndarray, np.ndar
     return idx, cnt
 
 
-def knn(xyz, sample_idx, k: int) -> Tuple[np.ndarray, np.ndarray]:
-    """k nearest samples of every point of one cloud: (pos[N][k] int32 positions into
-    sample_idx, d2[N][k] float32 squared distances), nearest first, lower position on ties."""
+def knn(xyz, sample_idx, k: int, points=None) -> Tuple[np.ndarray, np.ndarray]:
+    """k nearest samples of every point of one cloud (or of the points listed in `points`):
+    (pos[M][k] int32 positions into sample_idx, d2[M][k] float32 squared distances), nearest
+    first, lower position on ties."""
     a = _cloud(xyz)
     s = np.ascontiguousarray(sample_idx, dtype=np.int32)
     N, n = a.shape[0], s.shape[0]
-    pos = np.empty((N, k), dtype=np.int32)
-    d2 = np.empty((N, k), dtype=np.float32)
-    rc = lib().ref_knn(_f(a), N, _i(s), n, k, _i(pos), _f(d2))
+    pts = None if points is None else np.ascontiguousarray(points, dtype=np.int32)
+    M = N if pts is None else pts.shape[0]
+    pos = np.empty((M, k), dtype=np.int32)
+    d2 = np.empty((M, k), dtype=np.float32)
+    rc = lib().ref_knn(_f(a), N, _i(s), n, k, None if pts is None else _i(pts), M, _i(pos), _f(d2))
     if rc != 0:
         raise ValueError("ref_knn rejected its arguments")
     return pos, d2

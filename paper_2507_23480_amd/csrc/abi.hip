@@ -51,11 +51,20 @@ struct Shape {
     int T, P;
 };
 constexpr Shape kShapes[] = {{256, 2}, {256, 4}, {256, 8}, {256, 16}, {256, 32}};
+constexpr Shape kShapes512[] = {{512, 2}, {512, 4}, {512, 8}, {512, 16}};
 constexpr int kNumShapes = (int)(sizeof(kShapes) / sizeof(kShapes[0]));
+constexpr int kNumShapes512 = (int)(sizeof(kShapes512) / sizeof(kShapes512[0]));
+std::atomic<int> g_threads{512};
 constexpr int kTargetPointsPerWg = 1024;
 
 bool shape_for(int64_t points_per_wg, Shape* s)
 {
+    if (g_threads.load() == 512)
+        for (int i = 0; i < kNumShapes512; ++i)
+            if ((int64_t)kShapes512[i].T * kShapes512[i].P >= points_per_wg) {
+                *s = kShapes512[i];
+                return true;
+            }
     for (int i = 0; i < kNumShapes; ++i)
         if ((int64_t)kShapes[i].T * kShapes[i].P >= points_per_wg) {
             *s = kShapes[i];
@@ -329,6 +338,8 @@ fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
 }
 
 void fp_set_wg_per_cloud(int32_t wg_per_cloud) { g_force_wg_per_cloud.store(wg_per_cloud > 0 ? wg_per_cloud : 0); }
+
+void fp_set_threads_per_wg(int32_t threads) { g_threads.store(threads == 256 ? 256 : 512); }
 
 void fp_set_cooperative_launch(int32_t on) { g_cooperative.store(on ? 1 : 0); }
 

@@ -1013,6 +1013,15 @@ const void* sampler_kernel_for(int threads, int points_per_thread, bool bq)
             default: return nullptr;
         }
     }
+    if (threads == 512) {
+        switch (points_per_thread) {
+            case 2: return pick_bq<512, 2>(bq);
+            case 4: return pick_bq<512, 4>(bq);
+            case 8: return pick_bq<512, 8>(bq);
+            case 16: return pick_bq<512, 16>(bq);
+            default: return nullptr;
+        }
+    }
     return nullptr;
 }
 

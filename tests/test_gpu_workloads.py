@@ -7,7 +7,8 @@ C4, C5: the oracle cannot run the full job in seconds, so
     prefix of the full run, which is checked too);
   * full N and full n: sampled outputs the oracle can compute one by one (ball-query rows of
     sampled centres, curve values of sampled picks) and properties that hold at any size
-    (non-increasing curve, spacing bound per MDPS level, cached == brute, coverage bound).
+    (non-increasing curve, spacing bound per MDPS level, cached == brute, coverage bound);
+    k-NN rows of sampled points, redundancy-free k-NN == brute force on every point.
 """
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -22,6 +23,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 COVERAGE_BOUND = 1.05     # MDPS coverage radius relative to exact FPS
+KNN_K = 3                 # neighbours of the up-sampling step (Section 3.1)
 
 
 @pytest.fixture(scope="module")
@@ -82,7 +84,11 @@ def test_full_workload_matches_oracle(fp, cal, name):
         midx, info = fp.mdps_sample(xyz, st.n, prm, want_info=True, bq_cache=cache, bq_radius=st.radius)
         mbq, mcnt = fp.ball_query(xyz, midx, st.radius, st.k, bq_cache=cache)
         cov_f, cov_m = fp.coverage2(xyz, idx).sqrt(), fp.coverage2(xyz, midx).sqrt()
+        kpos, kd2 = fp.knn(xyz, idx, KNN_K)
+        mkpos, mkd2, deferred = fp.knn(xyz, midx, KNN_K, bq_cache=cache, want_deferred=True)
         torch.cuda.synchronize()
+        say("   k-NN points searched by brute force: %s of %d" % (deferred.cpu().tolist(), batch.shape[1]))
+        kpos, kd2, mkpos, mkd2 = kpos.cpu().numpy(), kd2.cpu().numpy(), mkpos.cpu().numpy(), mkd2.cpu().numpy()
         idx, mdc, bq, cnt = idx.cpu().numpy(), mdc.cpu().numpy(), bq.cpu().numpy(), cnt.cpu().numpy()
         midx, mbq, mcnt = midx.cpu().numpy(), mbq.cpu().numpy(), mcnt.cpu().numpy()
         infos = fp.parse_info(info)
@@ -93,8 +99,11 @@ def test_full_workload_matches_oracle(fp, cal, name):
             wbq, wcnt = ref.ball_query(batch[b], widx, st.radius, st.k)
             wmidx, winfo = ref.mdps_sample(batch[b], st.n, rp)
             wmbq, wmcnt = ref.ball_query(batch[b], wmidx, st.radius, st.k)
-            return widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt
-        for b, (widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt) in enumerate(pmap(one, range(wl.B))):
+            return widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt, ref.knn(batch[b], widx, KNN_K), \
+                ref.knn(batch[b], wmidx, KNN_K)
+        for b, (widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt, wk, wmk) in enumerate(pmap(one, range(wl.B))):
+            assert np.array_equal(kpos[b], wk[0]) and np.array_equal(kd2[b], wk[1]), "brute k-NN cloud %d" % b
+            assert np.array_equal(mkpos[b], wmk[0]) and np.array_equal(mkd2[b], wmk[1]), "cached k-NN cloud %d" % b
             assert np.array_equal(idx[b], widx) and np.array_equal(mdc[b], wmdc), "fps cloud %d" % b
             assert np.array_equal(bq[b], wbq) and np.array_equal(cnt[b], wcnt), "brute bq cloud %d" % b
             assert np.array_equal(midx[b], wmidx), "mdps cloud %d" % b
@@ -141,8 +150,13 @@ def check_large(fp, cal, name, n_small, bq_centres):
     cbq, ccnt = fp.ball_query(xyz, midx, st.radius, st.k, bq_cache=cache)
     fbq, fcnt = fp.ball_query(xyz, idx, st.radius, st.k)
     cov = (fp.coverage2(xyz, midx).sqrt() / fp.coverage2(xyz, idx).sqrt())
+    kpos, kd2 = fp.knn(xyz, midx, KNN_K)
+    ckpos, ckd2, deferred = fp.knn(xyz, midx, KNN_K, bq_cache=cache, want_deferred=True)
     torch.cuda.synchronize()
     assert torch.equal(bq, cbq) and torch.equal(cnt, ccnt), "cached ball query differs from brute force"
+    assert torch.equal(kpos, ckpos) and torch.equal(kd2, ckd2), "redundancy-free k-NN differs from brute force"
+    say("   k-NN points searched by brute force: %s of %d" % (deferred.cpu().tolist(), N))
+    kpos, kd2 = kpos.cpu().numpy(), kd2.cpu().numpy()
     idx, mdc, midx = idx.cpu().numpy(), mdc.cpu().numpy(), midx.cpu().numpy()
     bq, cnt, fbq, fcnt = bq.cpu().numpy(), cnt.cpu().numpy(), fbq.cpu().numpy(), fcnt.cpu().numpy()
     infos = fp.parse_info(info)
@@ -173,6 +187,10 @@ def check_large(fp, cal, name, n_small, bq_centres):
         assert np.array_equal(bq[b, qs], wq) and np.array_equal(cnt[b, qs], wc)
         wq, wc = ref.ball_query(pts, idx[b, qs], st.radius, st.k)
         assert np.array_equal(fbq[b, qs], wq) and np.array_equal(fcnt[b, qs], wc)
+        # k-NN rows of sampled points
+        js = rng.integers(0, N, bq_centres)
+        wp, wd = ref.knn(pts, midx[b], KNN_K, points=js)
+        assert np.array_equal(kpos[b, js], wp) and np.array_equal(kd2[b, js], wd)
 
 
 def test_lidar_workload(fp, cal):

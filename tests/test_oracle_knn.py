@@ -110,6 +110,15 @@ def test_nearest_sample_distance_is_the_running_minimum_of_fps():
     assert abs(np.sqrt(float(d2[:, 0].max())) - ref.coverage_radius(xyz, idx[:n])) < 1e-6
 
 
+def test_point_subset_is_the_rows_of_the_full_result():
+    xyz = inputs.uniform_cube(71, 300)
+    sidx, _ = ref.fps_exact(xyz, 50)
+    pos, d2 = ref.knn(xyz, sidx, 4)
+    pts = np.array([299, 0, 17, 17, 123])
+    spos, sd2 = ref.knn(xyz, sidx, 4, points=pts)
+    assert np.array_equal(spos, pos[pts]) and np.array_equal(sd2, d2[pts])
+
+
 def test_rejects_bad_arguments():
     xyz = inputs.uniform_cube(61, 50)
     with pytest.raises(ValueError):
