@@ -214,11 +214,11 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         if (launch_zero_words(a.ll_pk, kLlPkWords + kLlCdWords, stream) != hipSuccess)
             return FP_ERR_DEVICE;
         if (g_cooperative.load())
-            err = hipLaunchCooperativeKernel(fn, dim3(grid), dim3((unsigned)plan.T), kargs, 0, stream);
+            err = hipLaunchCooperativeKernel(fn, dim3(grid), dim3((unsigned)plan.T + 64u), kargs, 0, stream);
         else
-            err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)plan.T), kargs, 0, stream);
+            err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)plan.T + 64u), kargs, 0, stream);
     } else {
-        err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)plan.T), kargs, 0, stream);
+        err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)plan.T + 64u), kargs, 0, stream);
     }
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }

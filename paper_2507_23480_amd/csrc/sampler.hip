@@ -16,6 +16,12 @@
 // the cloud through self-validating 64-bit words (payload in the low half, a
 // sequence stamp in the high half, relaxed agent-scope atomics, no fences).
 //
+// A workgroup has T threads that hold points plus one more wave, the control wave, that holds
+// none: it resolves the picks of a round one after the other (a chain of dependent steps) and
+// publishes each in LDS as soon as it is known, while the point waves fold the published picks
+// into their distances.  The fold, which is throughput bound, thereby hides behind the
+// resolution, which is latency bound.
+//
 // The threshold phase of Algorithm 2 uses the equivalent running-distance form:
 // point j is available at level l iff dists[j] >= R_l^2.  Each round takes the
 // first 64 available indices, resolves them in index order against the picks
@@ -39,6 +45,7 @@ constexpr float kPadCoord = 3.0e38f;    // coordinates of slots beyond N: every 
 constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
 constexpr int kStage = 256;             // ring of picks not yet written to global memory
 constexpr int kFlush = 128;             // ... written out once this many are waiting
+constexpr int kCtrlThreads = 64;        // the control wave, after the T point threads
 
 // ---------------------------------------------------------------- wave helpers
 // Values that are equal in all lanes but come out of LDS or cross-lane operations: telling the
@@ -84,12 +91,12 @@ __device__ __forceinline__ float rdlane_f(float v, int l)
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
     v = row_max_u32(v);
-    return uni(max(max(rdlane(v, 0), rdlane(v, 16)), max(rdlane(v, 32), rdlane(v, 48))));
+    return max(max(rdlane(v, 0), rdlane(v, 16)), max(rdlane(v, 32), rdlane(v, 48)));     // scalar unit
 }
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
 {
     v = row_min_u32(v);
-    return uni(min(min(rdlane(v, 0), rdlane(v, 16)), min(rdlane(v, 32), rdlane(v, 48))));
+    return min(min(rdlane(v, 0), rdlane(v, 16)), min(rdlane(v, 32), rdlane(v, 48)));
 }
 __device__ __forceinline__ int first_lane(uint64_t mask) { return __builtin_ctzll(mask); }
 __device__ __forceinline__ int lanes_below(uint64_t mask)
@@ -147,6 +154,28 @@ __device__ __forceinline__ bool ll_wait(const uint64_t* p, uint32_t stamp, uint3
     }
 }
 
+// Slots in LDS through which the control wave hands the picks of a round to the point waves,
+// in acceptance order.  A slot is one 64-bit word: low half = round tag << 8 | lane of the pick
+// in the candidate list (kLiveEnd: the round has no further pick), high half = the pick's
+// squared distance bits.  It is written by all lanes of the control wave with the same value (one
+// 64-bit store); readers take the pick's coordinates from the candidate list.  The LDS executes
+// the operations of one wave in issue order; the fences only restrain the compiler.
+constexpr uint32_t kLiveEnd = 0xFFu;
+
+__device__ __forceinline__ void lds_publish(uint64_t* p, uint32_t stamp, uint32_t dbits)
+{
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __hip_atomic_store(p, ((uint64_t)dbits << 32) | stamp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+}
+__device__ __forceinline__ uint32_t lds_observe(const uint64_t* p)
+{
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    const uint64_t v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    return (uint32_t)v;
+}
+
 struct Rec {          // one arg-max candidate: squared distance bits, index, coordinates
     uint32_t d, idx;
     float x, y, z;
@@ -180,12 +209,19 @@ struct Shared {
     int32_t gpre[kMaxGroup + 1];
     int32_t ctrl[4];      // [0] accepted picks of the round, [1] points passing in the cloud,
                           // [2] failure, [3] distance bits of the last accepted pick
+    // picks of the round being resolved, in acceptance order
+    uint64_t live[kCand + 2];
+#ifdef FASTPOINT_PHASE_CLOCKS
+    long long chain_cycles;   // shader clocks the control wave spent in the exact-FPS chain loop
+    long long chain_picks;
+#endif
     uint32_t st_idx[kStage];   // picks waiting to be written out (ring, by sample position)
     float st_mdc[kStage];
 };
 
 // Everything one thread needs to know about where it sits.
 struct Where {
+    bool ctrl;            // the control wave (holds no points)
     int tid, lane, w;     // thread, lane, wave in workgroup
     int g, G, grp;        // workgroup in cloud, workgroups per cloud, group slot in the grid
     int gw;               // wave in cloud
@@ -204,11 +240,23 @@ struct Points {
     typename RegVec<P>::type x, y, z, d;
 };
 
-// Alg. 1 lines 4-7 for this thread's points; with BQ also the radius test of
-// Section 4.2, one 64-bit word per slot written to row `pos` of the cache.
+// Radius-test results of up to 64 picks that a wave has folded but not written to the cache
+// yet: lane s holds the P 64-bit words (one per slot) of the s-th of those picks.
+template <int P>
+struct RowWords {
+    uint32_t lo[P], hi[P];
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int p = 0; p < P; ++p) lo[p] = hi[p] = 0;
+    }
+};
+
+// Alg. 1 lines 4-7 for this thread's points; with BQ also the radius test of Section 4.2: the
+// 64-bit hit mask of every slot goes to lane `s` of `rw`.
 template <int P, bool BQ, int P0>
 __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float cy, float cz, float bq_r2,
-                                            int lane, uint32_t& word_lo, uint32_t& word_hi)
+                                            int lane, int s, RowWords<P>& rw)
 {
     constexpr int GRP = P < 8 ? P : 8;      // slots whose radius tests are examined together
     if constexpr (P0 < P) {
@@ -223,36 +271,43 @@ __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float c
         }
         if (BQ) {
             // most balls miss most waves: one test per group on the vector unit; the per-slot
-            // masks are formed and routed to their lanes only when some point of the group hits
+            // masks are formed and kept only when some point of the group hits
             const uint32_t r2b = __float_as_uint(bq_r2);
             if (__builtin_amdgcn_ballot_w64(tmin < r2b) != 0) {
 #pragma unroll
                 for (int u = 0; u < GRP; ++u) {
                     const uint64_t hit = __builtin_amdgcn_ballot_w64(tb[u] < r2b);
-                    if (lane == P0 + u) {           // lane p collects the mask of slot p
-                        word_lo = (uint32_t)hit;
-                        word_hi = (uint32_t)(hit >> 32);
+                    if (lane == s) {
+                        rw.lo[P0 + u] = (uint32_t)hit;
+                        rw.hi[P0 + u] = (uint32_t)(hit >> 32);
                     }
                 }
             }
         }
-        fold_groups<P, BQ, P0 + GRP>(pt, cx, cy, cz, bq_r2, lane, word_lo, word_hi);
+        fold_groups<P, BQ, P0 + GRP>(pt, cx, cy, cz, bq_r2, lane, s, rw);
     }
 }
 
 template <int P, bool BQ>
 __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, float cz,
-                                     const SamplerArgs& a, const Where& wh, int pos)
+                                     const SamplerArgs& a, const Where& wh, int s, RowWords<P>& rw)
 {
-    uint32_t word_lo = 0, word_hi = 0;      // lane p < P collects the hit mask of slot p
-    fold_groups<P, BQ, 0>(pt, cx, cy, cz, a.bq_r2, wh.lane, word_lo, word_hi);
-    if (BQ) {
-        // rows hold ceil(N/64) words (rounded up); slots wholly beyond N have no word
-        if (wh.lane < P && (int64_t)wh.gw * P + wh.lane < a.bq_row_words) {
-            uint64_t* row = a.bq_bits + ((int64_t)wh.c * a.n + pos) * a.bq_row_words +
-                            (int64_t)wh.gw * P;
-            row[wh.lane] = ((uint64_t)word_hi << 32) | word_lo;
-        }
+    fold_groups<P, BQ, 0>(pt, cx, cy, cz, a.bq_r2, wh.lane, s, rw);
+}
+
+// Writes the words of `count` picks (sample positions base, base+1, ...; count <= 64) to their
+// cache rows: lane s writes the wave's P consecutive words of row base+s.
+template <int P, bool BQ>
+__device__ __forceinline__ void flush_rows(const RowWords<P>& rw, const SamplerArgs& a, const Where& wh,
+                                           int base, int count)
+{
+    if (!BQ) return;
+    if (wh.lane < count) {
+        uint64_t* row = a.bq_bits + ((int64_t)wh.c * a.n + base + wh.lane) * a.bq_row_words +
+                        (int64_t)wh.gw * P;
+#pragma unroll
+        for (int p = 0; p < P; ++p)      // rows hold ceil(N/64) words (rounded up); slots wholly beyond N have none
+            if ((int64_t)wh.gw * P + p < a.bq_row_words) row[p] = ((uint64_t)rw.hi[p] << 32) | rw.lo[p];
     }
 }
 
@@ -320,7 +375,7 @@ __device__ __forceinline__ Rec cloud_argmax(const Points<P, BQ>& pt, Shared<T>& 
     const int buf = (int)(it & 1u);
     ++it;
     Rec mine = wave_best<T, P, BQ>(pt, wh);
-    if (wh.lane == 0) sh.wrec[buf][wh.w] = mine;
+    if (wh.lane == 0 && !wh.ctrl) sh.wrec[buf][wh.w] = mine;
     __syncthreads();
     if (wh.G == 1) {
         Rec r = sh.wrec[buf][wh.lane < NW ? wh.lane : 0];
@@ -384,7 +439,7 @@ __device__ __forceinline__ void flush_picks(const SamplerArgs& a, Shared<T>& sh,
     if (upto - flushed < kFlush && !force) return;
     __syncthreads();
     if (wh.g == 0) {
-        for (int t = flushed + wh.tid; t < upto; t += T) {
+        for (int t = flushed + wh.tid; t < upto; t += T + kCtrlThreads) {
             const uint32_t v = sh.st_idx[t & (kStage - 1)];
             a.out_idx[(int64_t)wh.c * a.n + t] = (int32_t)v;
             if (BQ) a.bq_idx[(int64_t)wh.c * a.n + t] = (int32_t)v;
@@ -427,13 +482,43 @@ template <int T, int P, bool BQ>
 __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                              const SamplerArgs& a, int npend, int base)
 {
-    if (npend <= 0) return;
+    if (npend <= 0 || wh.ctrl) return;
+    RowWords<P> rw;
+    rw.clear();
     Cand nxt = sh.pend[0];
-    for (int s = 0; s < npend; ++s) {
+    for (int s = 0; s < npend; ++s) {                   // npend <= kCand
         const Cand cur = nxt;
         if (s + 1 < npend) nxt = sh.pend[s + 1];       // fetched while the current pick is folded
-        fold<P, BQ>(pt, cur.x, cur.y, cur.z, a, wh, base + s);
+        fold<P, BQ>(pt, cur.x, cur.y, cur.z, a, wh, s, rw);
     }
+    flush_rows<P, BQ>(rw, a, wh, base, npend);
+}
+
+// The point waves' side of a round that the control wave resolves: folds the picks (sample
+// positions base, base+1, ...) as they are published, until the slot that closes the round.
+// The next slot is requested before the current pick is folded.
+template <int T, int P, bool BQ>
+__device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                             const SamplerArgs& a, int base, uint32_t tag)
+{
+    int s = 0;
+    RowWords<P> rw;
+    rw.clear();
+    uint32_t slot = lds_observe(&sh.live[0]);
+    for (;;) {
+        slot = uni(slot);
+        if ((slot & ~0xFFu) != tag) {               // not written yet in this round
+            __builtin_amdgcn_s_sleep(1);
+            slot = lds_observe(&sh.live[s]);
+            continue;
+        }
+        if ((slot & 0xFFu) == kLiveEnd) break;
+        const Cand c = sh.cand[slot & 0xFFu];
+        slot = lds_observe(&sh.live[s + 1]);
+        fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, s, rw);
+        ++s;
+    }
+    flush_rows<P, BQ>(rw, a, wh, base, s);          // a round has at most kCand picks
 }
 
 // segment boundary b_l (curve index whose value becomes R_l), l = 1..nseg
@@ -461,6 +546,7 @@ struct CloudState {
     int npend;      // picks in sh.pend that are not folded into the distances yet
     int flushed;    // sample positions [0, flushed) are in global memory
     int rounds;     // candidate scans so far
+    int resolved;   // rounds the control wave has resolved; the next round's slots carry resolved + 1
     float dlast;    // squared distance of the last exact-FPS pick at pick time; < 0: unknown
     float om;       // an exact-FPS round takes the points above dlast * (1 - om) as candidates
     int my_bl;      // thread l < nseg: segment boundary b_(l+1); else -1
@@ -523,7 +609,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         const bool av = STRICT ? (pt.d[p] > thr) : (pt.d[p] >= thr);
         cntw += __builtin_popcountll(__builtin_amdgcn_ballot_w64(av));
     }
-    if (wh.lane == 0) sh.wcnt[wh.w] = cntw;
+    if (wh.lane == 0 && !wh.ctrl) sh.wcnt[wh.w] = cntw;     // the control wave has none (cntw == 0)
     __syncthreads();
     int off = 0, tot = 0;
 #pragma unroll
@@ -567,7 +653,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     const int par = (int)(seq & 1u);
     uint64_t* pk = a.ll_pk + ((int64_t)(wh.grp * 2 + par) * wh.G) * kLlSlotWords;
     uint64_t* cd = a.ll_cd + ((int64_t)(wh.grp * 2 + par) * wh.G) * (kCand * kCandWords);
-    for (int e = wh.tid; e < total * kCandWords; e += T) {
+    for (int e = wh.tid; e < total * kCandWords; e += T + kCtrlThreads) {
         const int r = e / kCandWords, k = e - r * kCandWords;
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&sh.cand[r]);
         ll_store(cd + ((int64_t)wh.g * kCand + r) * kCandWords + k, src[k], seq);
@@ -615,7 +701,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     const int listed = uni(sh.gpre[wh.G]);
     total = listed < kCand ? listed : kCand;
     if (uni(sh.ctrl[2]) == 0) {
-        for (int e = wh.tid; e < total * kCandWords; e += T) {
+        for (int e = wh.tid; e < total * kCandWords; e += T + kCtrlThreads) {
             const int r = e / kCandWords, k = e - r * kCandWords;
             int lo = 0, hi = wh.G;             // workgroup whose range holds rank r
             while (hi - lo > 1) {
@@ -637,39 +723,34 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
 
 // Threshold phase of Alg. 2 (lines 29-33 for up to kCand picks at once): the candidates are
 // taken in index order; one stays available iff no pick accepted before it in this round lies
-// closer than R_l.  Wave 0 of every workgroup does the same work; results go to sh.pend.
+// closer than R_l.  Run by the control wave of every workgroup (all do the same work); each
+// accepted pick is published at once for the point waves to fold.
 template <int T>
 __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh, const CloudState& st,
-                                                  int total, int limit, float r2)
+                                                  int total, int limit, float r2, uint32_t tag)
 {
-    if (wh.w != 0) return;
     total = uni(total);
     limit = uni(limit);
     const bool has = wh.lane < total;
     const Cand me = sh.cand[has ? wh.lane : 0];
     uint64_t alive = __builtin_amdgcn_ballot_w64(has);
     int nacc = 0;
-    Cand mine = me;                     // lane k ends up holding the k-th accepted pick
+    __builtin_amdgcn_s_setprio(3);
     while (alive != 0 && nacc < limit) {
         const int cl = first_lane(alive);
         const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
-        const uint32_t aj = rdlane(me.idx, cl);
-        if (wh.lane == nacc) {
-            mine.idx = aj;
-            mine.x = ax;
-            mine.y = ay;
-            mine.z = az;
-        }
+        lds_publish(&sh.live[nacc], tag | (uint32_t)cl, 0u);
         const float t = dist2(ax, ay, az, me.x, me.y, me.z);
-        const uint64_t kill = __builtin_amdgcn_ballot_w64(t < r2);
+        const uint64_t kill = __builtin_amdgcn_ballot_w64(t < r2);     // includes the pick itself
         alive &= ~kill;
         alive &= ~(1ull << cl);
-        ++nacc;
+        nacc = uni(nacc + 1);
     }
+    lds_publish(&sh.live[nacc], tag | kLiveEnd, 0u);
+    __builtin_amdgcn_s_setprio(0);
     if (wh.lane < nacc) {
-        mine.d = 0;
-        sh.pend[wh.lane] = mine;
-        stage_pick<T>(sh, st.i + wh.lane, mine.idx, 0.0f);
+        const uint32_t cl = (uint32_t)sh.live[wh.lane] & 0xFFu;
+        stage_pick<T>(sh, st.i + wh.lane, sh.cand[cl].idx, 0.0f);
     }
     if (wh.lane == 0) sh.ctrl[0] = nacc;
 }
@@ -678,12 +759,16 @@ __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh
 // tau, so every other point is at most tau and can only decrease.  Repeatedly: the candidate with
 // the largest up-to-date distance (lowest index among equals) is the true arg-max of Alg. 1
 // line 8 as long as that distance exceeds tau; accepting it lowers the other candidates'
-// distances exactly as the fold will.  Stops when no candidate exceeds tau any more.
+// distances exactly as the fold will.  Stops when no candidate exceeds tau any more.  Run by the
+// control wave; picks are published one by one like those of the threshold phase.
+// The candidates are in ascending index order, so the lowest lane among equal distances is the
+// lowest index.  One step is a chain of dependent instructions of a single wave: its length in
+// instructions is what a pick costs.
 template <int T>
 __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, const CloudState& st,
-                                              int total, int limit, float tau, bool capture, int nseg)
+                                              int total, int limit, float tau, bool capture, int nseg,
+                                              uint32_t tag)
 {
-    if (wh.w != 0) return;
     total = uni(total);
     limit = uni(limit);
     const bool has = wh.lane < total;
@@ -692,35 +777,34 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
     const uint32_t tau_bits = uni(__float_as_uint(tau));    // tau >= 0
     int nacc = 0;
     uint32_t dl = __float_as_uint(st.dlast);
-    Cand mine = me;                     // lane k ends up holding the k-th accepted pick
-    while (nacc < limit) {
-        const uint32_t dmax = wave_max_u32(cd);
-        if (!(dmax > tau_bits)) break;
-        uint64_t who = __builtin_amdgcn_ballot_w64(cd == dmax);
-        if (__builtin_popcountll(who) > 1) {            // equal distances: lowest index wins
-            const uint32_t imin = wave_min_u32(cd == dmax ? me.idx : kNoIdx);
-            who = __builtin_amdgcn_ballot_w64(cd == dmax && me.idx == imin);
-        }
-        const int cl = first_lane(who);
+    __builtin_amdgcn_s_setprio(3);
+#ifdef FASTPOINT_PHASE_CLOCKS
+    const long long chain_t0 = clock64();
+#endif
+    uint32_t dmax = wave_max_u32(cd);
+    while (nacc < limit && dmax > tau_bits) {
+        const int cl = first_lane(__builtin_amdgcn_ballot_w64(cd == dmax));
         const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
-        const uint32_t aj = rdlane(me.idx, cl);
+        lds_publish(&sh.live[nacc], tag | (uint32_t)cl, dmax);
         dl = dmax;
-        if (wh.lane == nacc) {
-            mine.idx = aj;
-            mine.x = ax;
-            mine.y = ay;
-            mine.z = az;
-            mine.d = dmax;
-        }
-        const float t = dist2(ax, ay, az, me.x, me.y, me.z);
-        cd = has ? min(cd, __float_as_uint(t)) : 0u;
-        ++nacc;
+        // lanes without a candidate hold 0 and stay there
+        cd = min(cd, __float_as_uint(dist2(ax, ay, az, me.x, me.y, me.z)));
+        nacc = uni(nacc + 1);
+        dmax = wave_max_u32(cd);
     }
+    lds_publish(&sh.live[nacc], tag | kLiveEnd, 0u);
+    __builtin_amdgcn_s_setprio(0);
+#ifdef FASTPOINT_PHASE_CLOCKS
+    if (wh.lane == 0) {
+        sh.chain_cycles += clock64() - chain_t0;
+        sh.chain_picks += nacc;
+    }
+#endif
     if (wh.lane < nacc) {
         const int pos = st.i + wh.lane;
-        const float d = __uint_as_float(mine.d);
-        sh.pend[wh.lane] = mine;
-        stage_pick<T>(sh, pos, mine.idx, d);
+        const uint64_t word = sh.live[wh.lane];
+        const float d = __uint_as_float((uint32_t)(word >> 32));
+        stage_pick<T>(sh, pos, sh.cand[(uint32_t)word & 0xFFu].idx, d);
         if (capture) {                  // Alg. 2 line 11: keep the curve of the prefix
             sh.ring[pos & 63] = d;
             for (int l = 0; l < nseg; ++l)
@@ -773,13 +857,16 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
         }
         {
             PHASE_BEGIN();
-            resolve_chain<T>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg);
+            const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
+            if (wh.ctrl) resolve_chain<T>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg, tag);
+            else follow_picks<T, P, BQ>(pt, sh, wh, a, st.i, tag);
             __syncthreads();
             PHASE_END(st, 2);
         }
-        st.npend = uni(sh.ctrl[0]);
+        ++st.resolved;
+        st.npend = 0;                               // folded while they were resolved
         st.dlast = __uint_as_float(uni((uint32_t)sh.ctrl[3]));
-        st.i += st.npend;
+        st.i += uni(sh.ctrl[0]);
         if (alltot < 32) st.om = st.om * 1.15f < 0.99f ? st.om * 1.15f : 0.99f;
         else if (alltot > 52) st.om = st.om * 0.87f;
     }
@@ -798,7 +885,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     const int start = uni(a.start_idx ? a.start_idx[wh.c] : 0);
     if (start < 0 || start >= N) {          // uniform over the group
         if (wh.g == 0) {
-            for (int k = wh.tid; k < n; k += T) a.out_idx[(int64_t)wh.c * n + k] = -1;
+            for (int k = wh.tid; k < n; k += T + kCtrlThreads) a.out_idx[(int64_t)wh.c * n + k] = -1;
             if (wh.tid == 0 && a.info) {
                 fp_mdps_info inf = {};
                 inf.status = 1;
@@ -824,6 +911,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             pt.d[p] = 0.0f;
         }
     }
+    if (wh.tid < kCand + 2) sh.live[wh.tid] = 0;       // round tags start at 1 in every cloud
     if (wh.tid < FP_MAX_SEG) {
         sh.level_start[wh.tid] = -1;
         sh.level_exhausted[wh.tid] = 0;
@@ -836,6 +924,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     st.npend = 1;
     st.flushed = 0;
     st.rounds = 0;
+    st.resolved = 0;
     st.dlast = -1.0f;
     st.om = 0.25f;
     st.my_bl = wh.tid < a.nseg ? boundary_index(n, a.nseg, wh.tid + 1) : -1;
@@ -844,6 +933,10 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #endif
     if (wh.tid == 0) {
         sh.ctrl[2] = 0;
+#ifdef FASTPOINT_PHASE_CLOCKS
+        sh.chain_cycles = 0;
+        sh.chain_picks = 0;
+#endif
         Cand c0;                       // Alg. 1 line 1: the seed is sample 0, not folded yet
         c0.idx = (uint32_t)start;
         c0.x = cloud[(int64_t)start * 3 + 0];
@@ -923,10 +1016,13 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
                 continue;
             }
-            resolve_threshold<T>(sh, wh, st, total, limit, r2);
+            const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
+            if (wh.ctrl) resolve_threshold<T>(sh, wh, st, total, limit, r2, tag);
+            else follow_picks<T, P, BQ>(pt, sh, wh, a, st.i, tag);
             __syncthreads();
-            st.npend = uni(sh.ctrl[0]);
-            st.i += st.npend;
+            ++st.resolved;
+            st.npend = 0;                           // folded while they were resolved
+            st.i += uni(sh.ctrl[0]);
         }
 
         if (ok && st.i < n) {
@@ -954,28 +1050,34 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         inf.rounds = st.rounds;
 #ifdef FASTPOINT_PHASE_CLOCKS
         if (a.nseg <= 8)
+        {
             for (int k = 0; k < 4; ++k) inf.thr2[8 + k] = (float)st.clk[k] * 0.01f;   // 100 MHz ticks
+            inf.thr2[12] = (float)sh.chain_cycles;
+            inf.thr2[13] = (float)sh.chain_picks;
+        }
 #endif
         inf.status = ok ? 0 : 2;
         a.info[wh.c] = inf;
     }
     if (!ok && wh.g == 0)
-        for (int k = wh.tid; k < n; k += T) a.out_idx[(int64_t)wh.c * n + k] = -1;
+        for (int k = wh.tid; k < n; k += T + kCtrlThreads) a.out_idx[(int64_t)wh.c * n + k] = -1;
     __syncthreads();
 }
 
 template <int T, int P, bool BQ>
-__global__ __launch_bounds__(T) void sampler_kernel(SamplerArgs a)
+__global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a)
 {
     __shared__ Shared<T> sh;
     Where wh;
     wh.tid = (int)threadIdx.x;
     wh.lane = wh.tid & 63;
-    wh.w = wh.tid >> 6;
+    wh.w = uni(wh.tid >> 6);
+    wh.ctrl = wh.w == T / 64;
     wh.G = a.G;
     wh.grp = (int)blockIdx.x / a.G;
     wh.g = (int)blockIdx.x % a.G;
-    wh.gw = wh.g * (T / 64) + wh.w;
+    // the control wave's slots lie beyond every point of the cloud: they are padding
+    wh.gw = wh.ctrl ? a.G * (T / 64) : wh.g * (T / 64) + wh.w;
     const int ngroups = (int)gridDim.x / a.G;
     uint32_t it = 0, seq = 0;
     for (int c = wh.grp; c < a.B; c += ngroups) {
