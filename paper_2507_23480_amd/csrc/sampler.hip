@@ -98,6 +98,18 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
     v = row_min_u32(v);
     return min(min(rdlane(v, 0), rdlane(v, 16)), min(rdlane(v, 32), rdlane(v, 48)));
 }
+// maximum over the wave as a scalar-unit value: the loop that uses it branches on it
+__device__ __forceinline__ uint32_t smax(uint32_t a, uint32_t b)
+{
+    uint32_t r;
+    asm("s_max_u32 %0, %1, %2" : "=s"(r) : "s"(a), "s"(b) : "scc");
+    return r;
+}
+__device__ __forceinline__ uint32_t wave_max_scalar(uint32_t v)
+{
+    v = row_max_u32(v);
+    return smax(smax(rdlane(v, 0), rdlane(v, 16)), smax(rdlane(v, 32), rdlane(v, 48)));
+}
 __device__ __forceinline__ int first_lane(uint64_t mask) { return __builtin_ctzll(mask); }
 __device__ __forceinline__ int lanes_below(uint64_t mask)
 {
@@ -168,6 +180,21 @@ __device__ __forceinline__ void lds_publish(uint64_t* p, uint32_t stamp, uint32_
     __hip_atomic_store(p, ((uint64_t)dbits << 32) | stamp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
 }
+// The control wave's position in the slot array and its round tag, both kept in vector registers
+// (they are operands of vector instructions in every step of a loop whose length in
+// instructions is what matters).
+struct LiveCursor {
+    uint32_t off, tag;
+    __device__ __forceinline__ LiveCursor(uint32_t round_tag) : off(0), tag(round_tag)
+    {
+        asm volatile("" : "+v"(off), "+v"(tag));
+    }
+    __device__ __forceinline__ void publish(uint64_t* slots, uint32_t lane_or_end, uint32_t dbits)
+    {
+        lds_publish(reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(slots) + off), tag | lane_or_end, dbits);
+        off += 8;
+    }
+};
 __device__ __forceinline__ uint32_t lds_observe(const uint64_t* p)
 {
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
@@ -735,18 +762,20 @@ __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh
     const Cand me = sh.cand[has ? wh.lane : 0];
     uint64_t alive = __builtin_amdgcn_ballot_w64(has);
     int nacc = 0;
+    LiveCursor cur(tag);
     __builtin_amdgcn_s_setprio(3);
+    asm volatile("" ::"v"(me.x), "v"(me.y), "v"(me.z));
     while (alive != 0 && nacc < limit) {
         const int cl = first_lane(alive);
         const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
-        lds_publish(&sh.live[nacc], tag | (uint32_t)cl, 0u);
+        cur.publish(sh.live, (uint32_t)cl, 0u);
         const float t = dist2(ax, ay, az, me.x, me.y, me.z);
         const uint64_t kill = __builtin_amdgcn_ballot_w64(t < r2);     // includes the pick itself
         alive &= ~kill;
         alive &= ~(1ull << cl);
         nacc = uni(nacc + 1);
     }
-    lds_publish(&sh.live[nacc], tag | kLiveEnd, 0u);
+    cur.publish(sh.live, kLiveEnd, 0u);
     __builtin_amdgcn_s_setprio(0);
     if (wh.lane < nacc) {
         const uint32_t cl = (uint32_t)sh.live[wh.lane] & 0xFFu;
@@ -764,6 +793,28 @@ __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh
 // The candidates are in ascending index order, so the lowest lane among equal distances is the
 // lowest index.  One step is a chain of dependent instructions of a single wave: its length in
 // instructions is what a pick costs.
+// One run of the chain: up to `limit` picks (CHECK) or as many as exceed tau (a candidate is
+// accepted at most once, so that needs no count).  Returns the number accepted.
+template <bool CHECK>
+__device__ __forceinline__ int chain_loop(uint64_t* live, LiveCursor& cur, const Cand& me, uint32_t& cd,
+                                          uint32_t tau_bits, int limit, uint32_t& dl)
+{
+    int nacc = 0;
+    uint32_t dmax = wave_max_scalar(cd);
+    while (dmax > tau_bits) {
+        if (CHECK && nacc >= limit) break;
+        const int cl = first_lane(__builtin_amdgcn_ballot_w64(cd == dmax));
+        const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
+        cur.publish(live, (uint32_t)cl, dmax);
+        dl = dmax;
+        // lanes without a candidate hold 0 and stay there
+        cd = min(cd, __float_as_uint(dist2(ax, ay, az, me.x, me.y, me.z)));
+        nacc = uni(nacc + 1);
+        dmax = wave_max_scalar(cd);
+    }
+    return nacc;
+}
+
 template <int T>
 __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, const CloudState& st,
                                               int total, int limit, float tau, bool capture, int nseg,
@@ -775,24 +826,17 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
     const Cand me = sh.cand[has ? wh.lane : 0];
     uint32_t cd = has ? me.d : 0u;                     // bit pattern; distances are >= +0
     const uint32_t tau_bits = uni(__float_as_uint(tau));    // tau >= 0
-    int nacc = 0;
     uint32_t dl = __float_as_uint(st.dlast);
+    LiveCursor cur(tag);
     __builtin_amdgcn_s_setprio(3);
 #ifdef FASTPOINT_PHASE_CLOCKS
     const long long chain_t0 = clock64();
 #endif
-    uint32_t dmax = wave_max_u32(cd);
-    while (nacc < limit && dmax > tau_bits) {
-        const int cl = first_lane(__builtin_amdgcn_ballot_w64(cd == dmax));
-        const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
-        lds_publish(&sh.live[nacc], tag | (uint32_t)cl, dmax);
-        dl = dmax;
-        // lanes without a candidate hold 0 and stay there
-        cd = min(cd, __float_as_uint(dist2(ax, ay, az, me.x, me.y, me.z)));
-        nacc = uni(nacc + 1);
-        dmax = wave_max_u32(cd);
-    }
-    lds_publish(&sh.live[nacc], tag | kLiveEnd, 0u);
+    // the candidates have arrived from LDS before the loop starts, not inside it
+    asm volatile("" ::"v"(me.x), "v"(me.y), "v"(me.z), "v"(cd));
+    const int nacc = limit >= total ? chain_loop<false>(sh.live, cur, me, cd, tau_bits, limit, dl)
+                                    : chain_loop<true>(sh.live, cur, me, cd, tau_bits, limit, dl);
+    cur.publish(sh.live, kLiveEnd, 0u);
     __builtin_amdgcn_s_setprio(0);
 #ifdef FASTPOINT_PHASE_CLOCKS
     if (wh.lane == 0) {
