@@ -9,6 +9,9 @@ every stage of its hierarchy:
     gather of the exact-FPS samples = input of the next stage
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
+Outside the timed step the k nearest samples of every point (the k-NN of the up-sampling
+step, redundancy-free form of Section 4.2) are timed per stage and reported under "detail".
+
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-extra]
 """
 import argparse
@@ -20,13 +23,17 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# Non-FMA, non-packed fp32 vector rate of MI355X: 256 CUs x 64 lanes x 2.4 GHz.  The
-# published 157.3 TFLOP/s counts an FMA as two flops and the packed dual-rate form;
-# this path may use neither (every operation is rounded on its own), hence 157.3 / 4.
-ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+# fp32 vector rate of MI355X without FMA: 256 CUs x 128 lanes x 2.4 GHz = 78.6 T operations/s.
+# The published 157.3 TFLOP/s counts an FMA as two flops; this path may not contract (every
+# operation is rounded on its own), hence half of it.  (Measured on the device: plain
+# add/sub/mul on register operands reach 73 T lane-operations/s when two or more waves share a
+# SIMD; min, compares, selects, cross-lane moves and operations with a scalar-register operand
+# run at half that rate, so the instruction mix of this path cannot reach the figure.)
+ALU_PEAK_TOPS = 256 * 128 * 2.4e9 / 1e12
 HBM_PEAK_GBS = 8000.0
 OPS_PER_POINT_ITERATION = 10      # 3 sub, 3 mul, 2 add, 1 min, 1 compare (FPS min-update + arg-max)
-OPS_PER_PAIR_TEST = 9             # 3 sub, 3 mul, 2 add, 1 compare (ball query)
+OPS_PER_PAIR_TEST = 9             # 3 sub, 3 mul, 2 add, 1 compare (ball query, k-NN)
+KNN_K = 3                         # neighbours of the up-sampling step (Section 3.1)
 
 # HBM traffic per launch of the kernels that can dominate the step, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs (profiles/bench_C2_hbm_traffic.md); bytes, keyed by workload and
@@ -181,6 +188,18 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             a = byts / (ms["ball_query_cached"] * 1e-3) / 1e9
             roof["ball_query_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                          "frac": a / HBM_PEAK_GBS, "bytes": byts}
+        knn = time_knn(torch, fp, sg, midx)
+        for kname in ("knn_brute", "knn_cached"):
+            ms[kname] = knn[kname + "_ms"]
+        a = float(B) * N * n * OPS_PER_PAIR_TEST / (knn["knn_brute_ms"] * 1e-3) / 1e12
+        roof["knn_brute"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
+                             "frac": a / ALU_PEAK_TOPS}
+        # the redundancy-free search reads every bitmap row once and writes the result
+        byts = float(B) * n * ((N + 63) // 64) * 8 + 2.0 * B * N * KNN_K * 4
+        a = byts / (knn["knn_cached_ms"] * 1e-3) / 1e9
+        roof["knn_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": a / HBM_PEAK_GBS, "bytes": byts,
+                              "points_searched_by_brute_force": knn["deferred_fraction"]}
         out["stages"].append({
             "N": N, "n": n, "radius": sg["radius"], "k": k, "plan_G_T_P": list(fp.plan(B, N)),
             "kernel_ms": ms,
@@ -193,6 +212,34 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             "cached_ball_query_equals_brute": cached_equal,
             "roofline": roof})
     return out
+
+
+def time_knn(torch, fp, sg, midx, reps=3):
+    """k nearest MDPS samples of every point of a stage: brute force and through the recorded
+    ball bitmaps (both give the same result; checked here).  Not part of the timed step."""
+    x = sg["xyz"]
+    res = {}
+    for kname, cache in (("knn_brute", None), ("knn_cached", sg["cache"])):
+        fp.knn(x, midx, KNN_K, bq_cache=cache)
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(reps):
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record()
+            out = fp.knn(x, midx, KNN_K, bq_cache=cache, want_deferred=cache is not None)
+            b.record()
+            torch.cuda.synchronize()
+            t = a.elapsed_time(b)
+            best = t if best is None else min(best, t)
+        res[kname + "_ms"] = best
+        res[kname] = out
+    same = torch.equal(res["knn_brute"][0], res["knn_cached"][0]) and \
+        torch.equal(res["knn_brute"][1], res["knn_cached"][1])
+    if not same:
+        raise RuntimeError("redundancy-free k-NN differs from the brute-force result")
+    res["deferred_fraction"] = float(res["knn_cached"][2].sum().item()) / (x.shape[0] * x.shape[1])
+    return res
 
 
 def cpu_baseline(inputs, name, budget_s=12.0):

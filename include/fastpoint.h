@@ -172,17 +172,15 @@ fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N,
 fp_status fp_coverage(const float* xyz, int32_t B, int32_t N,
                       const float* sample_xyz, int32_t n, float* out_cov2, void* stream);
 
-/* How the sampler splits one cloud: workgroups per cloud, threads per
- * workgroup, points per thread.  Returns FP_ERR_SHAPE if the cloud does not fit. */
+/* How the sampler splits one cloud: workgroups per cloud, threads per workgroup that
+ * hold points (a workgroup has one more wave, which holds none), points per thread.
+ * Returns FP_ERR_SHAPE if the cloud does not fit. */
 fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
                   int32_t* points_per_thread);
 
 /* Tuning hook for benchmarks: force workgroups per cloud (0 = automatic).
  * Process-wide; not meant for concurrent use. */
 void fp_set_wg_per_cloud(int32_t wg_per_cloud);
-
-/* Tuning hook: threads per sampler workgroup, 256 or 512.  Process-wide. */
-void fp_set_threads_per_wg(int32_t threads);
 
 /* Multi-workgroup launches are cooperative by default (the runtime guarantees that all
  * workgroups are resident, which the waits between them rely on).  0 switches to a plain

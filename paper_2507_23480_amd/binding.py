@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
 EXPORTS = ["fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
-           "fp_ball_query", "fp_knn_workspace_bytes", "fp_knn", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud", "fp_set_threads_per_wg",
+           "fp_ball_query", "fp_knn_workspace_bytes", "fp_knn", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
 
 
@@ -110,8 +110,6 @@ def load() -> ctypes.CDLL:
     lib.fp_plan.restype = i32
     lib.fp_set_wg_per_cloud.argtypes = [i32]
     lib.fp_set_wg_per_cloud.restype = None
-    lib.fp_set_threads_per_wg.argtypes = [i32]
-    lib.fp_set_threads_per_wg.restype = None
     lib.fp_set_cooperative_launch.argtypes = [i32]
     lib.fp_set_cooperative_launch.restype = None
     lib.fp_set_wait_limit_us.argtypes = [ctypes.c_int64]
@@ -151,10 +149,6 @@ def plan(B: int, N: int) -> Tuple[int, int, int]:
 
 def set_wg_per_cloud(g: int) -> None:
     load().fp_set_wg_per_cloud(int(g))
-
-
-def set_threads_per_wg(threads: int) -> None:
-    load().fp_set_threads_per_wg(int(threads))
 
 
 def set_cooperative_launch(on: bool) -> None:

@@ -50,21 +50,15 @@ bool device_info(DeviceInfo* out)
 struct Shape {
     int T, P;
 };
-constexpr Shape kShapes[] = {{256, 2}, {256, 4}, {256, 8}, {256, 16}, {256, 32}};
-constexpr Shape kShapes512[] = {{512, 2}, {512, 4}, {512, 8}, {512, 16}};
+// T threads hold points (two waves per SIMD, so that their plain fp32 operations issue
+// together); the launch adds one control wave
+constexpr Shape kShapes[] = {{512, 2}, {512, 4}, {512, 8}, {512, 16}};
 constexpr int kNumShapes = (int)(sizeof(kShapes) / sizeof(kShapes[0]));
-constexpr int kNumShapes512 = (int)(sizeof(kShapes512) / sizeof(kShapes512[0]));
-std::atomic<int> g_threads{512};
+constexpr int kCtrlThreads = 64;
 constexpr int kTargetPointsPerWg = 1024;
 
 bool shape_for(int64_t points_per_wg, Shape* s)
 {
-    if (g_threads.load() == 512)
-        for (int i = 0; i < kNumShapes512; ++i)
-            if ((int64_t)kShapes512[i].T * kShapes512[i].P >= points_per_wg) {
-                *s = kShapes512[i];
-                return true;
-            }
     for (int i = 0; i < kNumShapes; ++i)
         if ((int64_t)kShapes[i].T * kShapes[i].P >= points_per_wg) {
             *s = kShapes[i];
@@ -73,7 +67,7 @@ bool shape_for(int64_t points_per_wg, Shape* s)
     return false;
 }
 
-constexpr int kMaxPointsPerWg = 256 * 32;
+constexpr int kMaxPointsPerWg = 512 * 16;
 
 // Splits B clouds of N points over at most `cus` resident workgroups: G workgroups per
 // cloud, `groups` clouds resident at once (further clouds are taken in turn).
@@ -109,7 +103,8 @@ bool make_plan(int B, int N, int cus, Plan* plan)
 
 inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
-int64_t bq_row_words(int N) { return align_up(((int64_t)N + 63) / 64, 8); }
+int64_t bq_blocks(int N) { return ((int64_t)N + 63) / 64; }
+int64_t bq_col_words(int n) { return align_up((int64_t)n, 8); }
 
 constexpr int64_t kLlPkWords = (int64_t)2 * kMaxGroup * kLlSlotWords;             // all groups together
 constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandPerRound * kCandWords;
@@ -189,7 +184,8 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         h.B = B;
         h.N = N;
         h.n = n;
-        h.row_words = bq_row_words(N);
+        h.blocks = (int32_t)bq_blocks(N);
+        h.col_words = bq_col_words(n);
         const float r2 = bq_radius * bq_radius;
         memcpy(&h.r2_bits, &r2, sizeof(r2));
         h.valid = 1;
@@ -199,7 +195,8 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         a.bq_idx = reinterpret_cast<int32_t*>(base + h.idx_offset);
         a.bq_bits = reinterpret_cast<uint64_t*>(base + h.bits_offset);
         a.bq_r2 = r2;
-        a.bq_row_words = h.row_words;
+        a.bq_blocks = h.blocks;
+        a.bq_col_words = h.col_words;
         if (launch_bq_header(bq_cache, h, stream) != hipSuccess) return FP_ERR_DEVICE;
     }
 
@@ -214,11 +211,11 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         if (launch_zero_words(a.ll_pk, kLlPkWords + kLlCdWords, stream) != hipSuccess)
             return FP_ERR_DEVICE;
         if (g_cooperative.load())
-            err = hipLaunchCooperativeKernel(fn, dim3(grid), dim3((unsigned)plan.T + 64u), kargs, 0, stream);
+            err = hipLaunchCooperativeKernel(fn, dim3(grid), dim3((unsigned)(plan.T + kCtrlThreads)), kargs, 0, stream);
         else
-            err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)plan.T + 64u), kargs, 0, stream);
+            err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)(plan.T + kCtrlThreads)), kargs, 0, stream);
     } else {
-        err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)plan.T + 64u), kargs, 0, stream);
+        err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)(plan.T + kCtrlThreads)), kargs, 0, stream);
     }
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }
@@ -239,7 +236,7 @@ size_t fp_workspace_bytes(int32_t B, int32_t N)
 size_t fp_bq_cache_bytes(int32_t B, int32_t N, int32_t n)
 {
     if (B < 1 || N < 1 || n < 1 || n > N) return 0;
-    return (size_t)(256 + align_up((int64_t)B * n * 4, 256) + (int64_t)B * n * bq_row_words(N) * 8);
+    return (size_t)(256 + align_up((int64_t)B * n * 4, 256) + (int64_t)B * bq_blocks(N) * bq_col_words(n) * 8);
 }
 
 fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
@@ -338,8 +335,6 @@ fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
 }
 
 void fp_set_wg_per_cloud(int32_t wg_per_cloud) { g_force_wg_per_cloud.store(wg_per_cloud > 0 ? wg_per_cloud : 0); }
-
-void fp_set_threads_per_wg(int32_t threads) { g_threads.store(threads == 256 ? 256 : 512); }
 
 void fp_set_cooperative_launch(int32_t on) { g_cooperative.store(on ? 1 : 0); }
 

@@ -7,11 +7,10 @@
 //     scalar loads, so each lane scans "its" ball sequentially and the first-k rule and the
 //     early exit fall out of the loop order; the index range is split over the waves of a
 //     workgroup (more waves in flight) and the per-range hit lists are merged in LDS;
-//   * cache reader, one centre per wave: reads the bitmap row the sampler
-//     recorded for that sample (Section 4.2: the radius test was already done
-//     while the sample was folded into the distance array) and expands the
-//     first k set bits; a centre without a usable row is tested against all
-//     points by the same wave with a ballot per 64 points.
+//   * cache reader, one centre per lane: reads the words the sampler recorded for that
+//     sample (Section 4.2: the radius test was already done while the sample was folded
+//     into the distance array) and keeps the first k set bits; a centre without usable
+//     words is tested against all points by the same wave.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -40,6 +39,41 @@ __device__ __forceinline__ int lanes_below(uint64_t mask)
 }
 
 constexpr int kChunk = 16;      // points tested per pass of the brute-force inner loop
+
+// Last step of both ball-query kernels.  Each of the S waves of a workgroup has listed, per
+// centre, the first hits of its part of the index range (hits [S][64][kp], counts [S][64], in
+// LDS); the parts are concatenated in index order, cut at k and padded with the first hit.
+// Wave w writes the rows of centres w, w+S, ...
+template <int S>
+__device__ __forceinline__ void merge_ranges(const int32_t* hits, const int32_t* counts, int kp, int k, int b,
+                                             int q0, int M, int w, int lane, int32_t* __restrict__ out_idx,
+                                             int32_t* __restrict__ out_cnt)
+{
+    for (int cc = w; cc < 64; cc += S) {
+        const int qq = q0 + cc;
+        if (qq >= M) break;
+        int off[S + 1];
+        off[0] = 0;
+#pragma unroll
+        for (int sgm = 0; sgm < S; ++sgm) off[sgm + 1] = off[sgm] + counts[sgm * 64 + cc];
+        const int total = off[S] < k ? off[S] : k;
+        int first = -1;
+#pragma unroll
+        for (int sgm = S - 1; sgm >= 0; --sgm)
+            if (off[sgm + 1] > off[sgm]) first = hits[((int64_t)sgm * 64 + cc) * kp];
+        int32_t* row = out_idx + ((int64_t)b * M + qq) * k;
+        for (int t = lane; t < k; t += 64) {
+            int v = first;
+            if (t < total) {
+#pragma unroll
+                for (int sgm = 0; sgm < S; ++sgm)
+                    if (t >= off[sgm] && t < off[sgm + 1]) v = hits[((int64_t)sgm * 64 + cc) * kp + (t - off[sgm])];
+            }
+            row[t] = v;
+        }
+        if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + qq] = total;
+    }
+}
 
 // Brute-force ball query.  A workgroup of S waves owns 64 centres (one per lane); wave w scans
 // the w-th of S equal index ranges of the cloud, so S times as many waves are in flight as
@@ -112,102 +146,93 @@ __global__ __launch_bounds__(S * 64) void bq_brute_kernel(const float* __restric
     }
     counts[w * 64 + lane] = cnt;
     __syncthreads();
-
-    // concatenate the S ranges of every centre in index order, cut at k, pad with the first hit
-    for (int cc = w; cc < 64; cc += S) {
-        const int qq = q0 + cc;
-        if (qq >= M) break;
-        int off[S + 1];
-        off[0] = 0;
-#pragma unroll
-        for (int sgm = 0; sgm < S; ++sgm) off[sgm + 1] = off[sgm] + counts[sgm * 64 + cc];
-        const int total = off[S] < k ? off[S] : k;
-        int first = -1;
-#pragma unroll
-        for (int sgm = S - 1; sgm >= 0; --sgm)
-            if (off[sgm + 1] > off[sgm]) first = hits[((int64_t)sgm * 64 + cc) * kp];
-        int32_t* row = out_idx + ((int64_t)b * M + qq) * k;
-        for (int t = lane; t < k; t += 64) {
-            int v = first;
-            if (t < total) {
-#pragma unroll
-                for (int sgm = 0; sgm < S; ++sgm)
-                    if (t >= off[sgm] && t < off[sgm + 1]) v = hits[((int64_t)sgm * 64 + cc) * kp + (t - off[sgm])];
-            }
-            row[t] = v;
-        }
-        if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + qq] = total;
-    }
+    merge_ranges<S>(hits, counts, kp, k, b, q0, M, w, lane, out_idx, out_cnt);
 }
 
-// emit the set bits of one 64-bit hit word (indices base..base+63) into the row
-__device__ __forceinline__ void emit_word(uint64_t wd, int base, int lane, int k, int32_t* row,
-                                          int& cnt, int& first)
-{
-    if (cnt == 0) first = base + __builtin_ctzll(wd);
-    const bool bit = (wd >> lane) & 1ull;
-    const int rank = cnt + lanes_below(wd);
-    if (bit && rank < k) row[rank] = base + lane;
-    cnt += __builtin_popcountll(wd);
-}
+constexpr int kCachedUnroll = 8;     // cache words requested together by the cache reader
 
-__global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict__ xyz, int B, int N,
-                                                        const int32_t* __restrict__ center_idx, int M,
-                                                        float r2, int k, int32_t* __restrict__ out_idx,
-                                                        int32_t* __restrict__ out_cnt,
-                                                        const unsigned char* __restrict__ cache)
+// Cache reader.  A workgroup of S waves owns 64 consecutive centres of a cloud, one per lane;
+// wave w takes the w-th of S equal ranges of point blocks.  Word [block][q] of the cache holds
+// the radius tests of sample q against the 64 points of that block, and the words of consecutive
+// samples are contiguous: every load of a wave brings one block for all its 64 centres.  A lane
+// walks the set bits of its words in index order and keeps the first k of its range; the ranges
+// are merged as in the brute-force kernel.  Centres without a usable column (not the cached
+// sample of that position, or another radius) are tested against the points of the range instead.
+//   LDS: hits [S][64][k+1] int32, counts [S][64] int32  (dynamic)
+template <int S>
+__global__ __launch_bounds__(S * 64) void bq_cached_kernel(const float* __restrict__ xyz, int B, int N,
+                                                           const int32_t* __restrict__ center_idx, int M,
+                                                           float r2, int k, int32_t* __restrict__ out_idx,
+                                                           int32_t* __restrict__ out_cnt,
+                                                           const unsigned char* __restrict__ cache)
 {
+    extern __shared__ int32_t lds[];
+    const int kp = k + 1;                                   // padded row: conflict-free columns
+    int32_t* hits = lds;                                    // [S][64][kp]
+    int32_t* counts = lds + S * 64 * kp;                    // [S][64]
+    const int b = (int)blockIdx.y;
     const int lane = (int)threadIdx.x & 63;
-    const int64_t wave = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
-    if (wave >= (int64_t)B * M) return;
-    const int b = (int)(wave / M), q = (int)(wave % M);
+    const int w = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int q0 = (int)blockIdx.x * 64;
+    const int q = q0 + lane;
     const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
-    const int c = center_idx[(int64_t)b * M + q];
-    int32_t* row = out_idx + ((int64_t)b * M + q) * k;
+    const int c = q < M ? center_idx[(int64_t)b * M + q] : -1;
+    const bool okc = c >= 0 && c < N;
+    int32_t* myrow = hits + ((int64_t)w * 64 + lane) * kp;
     int cnt = 0;
-    int first = -1;
-    if (c >= 0 && c < N) {
-        const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
-        bool usable = h->magic == kBqMagic && h->B == B && h->N == N && q < h->n &&
-                      h->r2_bits == __float_as_uint(r2);
-        if (usable) {
-            const int32_t* cidx = reinterpret_cast<const int32_t*>(cache + h->idx_offset);
-            usable = cidx[(int64_t)b * h->n + q] == c;
-        }
-        if (usable) {
-            const uint64_t* bits = reinterpret_cast<const uint64_t*>(cache + h->bits_offset) +
-                                   ((int64_t)b * h->n + q) * h->row_words;
-            const int nwords = (N + 63) >> 6;
-            for (int w0 = 0; w0 < nwords && cnt < k; w0 += 64) {
-                const uint64_t word = (w0 + lane < nwords) ? bits[w0 + lane] : 0ull;
-                uint64_t nz = __builtin_amdgcn_ballot_w64(word != 0);
-                while (nz != 0 && cnt < k) {
-                    const int l = __builtin_ctzll(nz);
-                    nz &= nz - 1;
-                    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)word, l);
-                    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(word >> 32), l);
-                    emit_word(((uint64_t)hi << 32) | lo, (w0 + l) << 6, lane, k, row, cnt, first);
-                }
-            }
-        } else {
-            const float cx = cloud[(int64_t)c * 3 + 0];
-            const float cy = cloud[(int64_t)c * 3 + 1];
-            const float cz = cloud[(int64_t)c * 3 + 2];
-            for (int j0 = 0; j0 < N && cnt < k; j0 += 64) {
-                const int j = j0 + lane;
-                bool hit = false;
-                if (j < N) {
-                    const float* pj = cloud + (int64_t)j * 3;
-                    hit = dist2(cx, cy, cz, pj[0], pj[1], pj[2]) < r2;
-                }
-                const uint64_t wd = __builtin_amdgcn_ballot_w64(hit);
-                if (wd != 0) emit_word(wd, j0, lane, k, row, cnt, first);
-            }
-        }
-        cnt = cnt < k ? cnt : k;
+
+    // this wave's range of point blocks
+    const int blocks = (N + 63) >> 6;
+    const int per = (blocks + S - 1) / S;
+    const int blk_begin = w * per < blocks ? w * per : blocks;
+    const int blk_end = (w + 1) * per < blocks ? (w + 1) * per : blocks;
+
+    const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
+    bool usable = h->magic == kBqMagic && h->valid == 1 && h->B == B && h->N == N &&
+                  h->r2_bits == __float_as_uint(r2) && okc && q < h->n;
+    if (usable) {
+        const int32_t* cidx = reinterpret_cast<const int32_t*>(cache + h->idx_offset);
+        usable = cidx[(int64_t)b * h->n + q] == c;
     }
-    for (int t = cnt + lane; t < k; t += 64) row[t] = first;
-    if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = cnt;
+    if (__builtin_amdgcn_ballot_w64(usable) != 0) {
+        const int64_t col_words = h->col_words;
+        const uint64_t* __restrict__ col = reinterpret_cast<const uint64_t*>(cache + h->bits_offset) +
+                                           (int64_t)b * blocks * col_words + (usable ? q : 0);
+        for (int w0 = blk_begin; w0 < blk_end; w0 += kCachedUnroll) {
+            if (__builtin_amdgcn_ballot_w64(usable && cnt < k) == 0) break;
+            uint64_t wd[kCachedUnroll];
+#pragma unroll
+            for (int u = 0; u < kCachedUnroll; ++u)
+                wd[u] = (usable && w0 + u < blk_end) ? col[(int64_t)(w0 + u) * col_words] : 0ull;
+#pragma unroll
+            for (int u = 0; u < kCachedUnroll; ++u) {
+                uint64_t x = wd[u];
+                while (x != 0 && cnt < k) {
+                    myrow[cnt] = ((w0 + u) << 6) + __builtin_ctzll(x);
+                    ++cnt;
+                    x &= x - 1;
+                }
+            }
+        }
+    }
+    if (__builtin_amdgcn_ballot_w64(okc && !usable) != 0) {
+        const bool mine = okc && !usable;
+        const float cx = mine ? cloud[(int64_t)c * 3 + 0] : __builtin_nanf("");
+        const float cy = mine ? cloud[(int64_t)c * 3 + 1] : 0.0f;
+        const float cz = mine ? cloud[(int64_t)c * 3 + 2] : 0.0f;
+        const int j_end = blk_end * 64 < N ? blk_end * 64 : N;
+        for (int j = blk_begin * 64; j < j_end; ++j) {
+            if (__builtin_amdgcn_ballot_w64(mine && cnt < k) == 0) break;
+            const float* pj = cloud + (int64_t)j * 3;        // uniform address: scalar loads
+            if (dist2(cx, cy, cz, pj[0], pj[1], pj[2]) < r2 && cnt < k) {
+                myrow[cnt] = j;
+                ++cnt;
+            }
+        }
+    }
+    counts[w * 64 + lane] = cnt;
+    __syncthreads();
+    merge_ranges<S>(hits, counts, kp, k, b, q0, M, w, lane, out_idx, out_cnt);
 }
 
 __global__ void gather_kernel(const float* __restrict__ xyz, int B, int N,
@@ -276,16 +301,31 @@ hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* cent
                              const void* bq_cache, hipStream_t stream)
 {
     if (M == 0) return hipSuccess;
+    const dim3 grid((unsigned)((M + 63) / 64), (unsigned)B);
+    const size_t per_wave = (size_t)64 * (k + 2) * sizeof(int32_t);
     if (bq_cache) {
-        const int64_t waves = (int64_t)B * M;
-        const int64_t blocks = (waves + 3) / 4;
-        hipLaunchKernelGGL(bq_cached_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, xyz, B, N,
-                           center_idx, M, r2, k, out_idx, out_cnt,
-                           reinterpret_cast<const unsigned char*>(bq_cache));
+        // enough waves to fill the device, as far as the hit lists leave room in 48 KB of LDS
+        const unsigned char* cache = reinterpret_cast<const unsigned char*>(bq_cache);
+        const int64_t groups = (int64_t)grid.x * grid.y;
+        const int64_t blocks = ((int64_t)N + 63) / 64;
+        int want = groups >= 4096 ? 1 : groups >= 2048 ? 2 : groups >= 1024 ? 4 : 8;
+        while (want > 1 && ((size_t)want * per_wave > 48 * 1024 || blocks < (int64_t)want * 4)) want >>= 1;
+        if (want == 8)
+            hipLaunchKernelGGL(bq_cached_kernel<8>, grid, dim3(512), 8 * per_wave, stream, xyz, B, N, center_idx, M,
+                               r2, k, out_idx, out_cnt, cache);
+        else if (want == 4)
+            hipLaunchKernelGGL(bq_cached_kernel<4>, grid, dim3(256), 4 * per_wave, stream, xyz, B, N, center_idx, M,
+                               r2, k, out_idx, out_cnt, cache);
+        else if (want == 2)
+            hipLaunchKernelGGL(bq_cached_kernel<2>, grid, dim3(128), 2 * per_wave, stream, xyz, B, N, center_idx, M,
+                               r2, k, out_idx, out_cnt, cache);
+        else if (per_wave <= 64 * 1024)
+            hipLaunchKernelGGL(bq_cached_kernel<1>, grid, dim3(64), per_wave, stream, xyz, B, N, center_idx, M, r2,
+                               k, out_idx, out_cnt, cache);
+        else
+            return hipErrorInvalidValue;
     } else {
         // as many waves per group of 64 centres as the hit lists leave room for in 48 KB of LDS
-        const dim3 grid((unsigned)((M + 63) / 64), (unsigned)B);
-        const size_t per_wave = (size_t)64 * (k + 2) * sizeof(int32_t);
         if (8 * per_wave <= 48 * 1024)
             hipLaunchKernelGGL(bq_brute_kernel<8>, grid, dim3(512), 8 * per_wave, stream, xyz, N, center_idx, M,
                                r2, k, out_idx, out_cnt);

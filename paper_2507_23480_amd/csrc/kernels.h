@@ -15,15 +15,22 @@ constexpr int kCandPerRound = 64;       // candidates per round of the threshold
 constexpr int kCandWords = 5;           // exchanged 64-bit words per candidate (idx, x, y, z, distance)
 constexpr uint32_t kBqMagic = 0x46504251u;
 
-// Header at the start of a ball-query cache (device memory).
+// Header at the start of a ball-query cache (device memory).  The radius tests are kept as a
+// bit matrix per cloud, one 64-bit word per (block of 64 points, sample): word [w][q] holds, in
+// bit l, whether point 64*w + l lies inside the ball of sample q.  Words of one point block are
+// contiguous over the samples, so a wave of the sampler writes the words of up to 64 picks with
+// one store, a ball-query wave reads the words of 64 consecutive centres with one load, and a
+// k-NN wave streams the samples of its point block.
 struct BqHeader {
     uint32_t magic;
     int32_t B, N, n;
-    int64_t row_words;      // 64-bit words per (sample) row
-    uint32_t r2_bits;       // radius^2 (binary32 bits) the rows were recorded with
-    int32_t valid;          // set to 1 by the sampler kernel when it has finished
+    int32_t blocks;         // point blocks per cloud, ceil(N / 64)
+    int32_t reserved;
+    int64_t col_words;      // 64-bit words per point block (n rounded up to a multiple of 8)
+    uint32_t r2_bits;       // radius^2 (binary32 bits) the tests were recorded with
+    int32_t valid;          // 1 once the header is complete
     int64_t idx_offset;     // byte offset of the int32 [B][n] copy of the sample indices
-    int64_t bits_offset;    // byte offset of the uint64 [B][n][row_words] rows
+    int64_t bits_offset;    // byte offset of the uint64 [B][blocks][col_words] words
 };
 
 struct SamplerArgs {
@@ -41,7 +48,8 @@ struct SamplerArgs {
     uint64_t* bq_bits;
     int32_t* bq_idx;
     float bq_r2;
-    int64_t bq_row_words;
+    int32_t bq_blocks;
+    int64_t bq_col_words;
     uint64_t* ll_pk;                // [groups][2][G][kLlSlotWords]
     uint64_t* ll_cd;                // [groups][2][G][kCandPerRound][kCandWords]
     int64_t wait_ticks;

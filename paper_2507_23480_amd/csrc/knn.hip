@@ -10,12 +10,11 @@
 //   * brute force: a workgroup owns 512 points (two per thread, in registers); the samples are
 //     gathered 256 at a time into LDS and read back at a wave-uniform address (one broadcast
 //     read feeds 128 distance evaluations of a wave);
-//   * redundancy-free: the sampler recorded, for every sample, the bitmap of the points closer
-//     than the cache radius (the exclusion list at an extra radius of Section 4.2).  Read
-//     column-wise this is the list of samples near each point: only those distances are
-//     evaluated.  When a point has at least k samples inside the radius they are its k nearest
+//   * redundancy-free: the sampler recorded, for every sample, which points are closer than
+//     the cache radius (the exclusion list at an extra radius of Section 4.2).  Read per
+//     point this is the list of samples near it: only those distances are evaluated.  When a point has at least k samples inside the radius they are its k nearest
 //     (every other sample is farther than all of them); the remaining points are collected in a
-//     list and searched by brute force in a second launch.
+//     list and searched by brute force afterwards (a wave per point while the list is short).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -82,6 +81,16 @@ struct Nearest {
         d[0] = first ? dd : d[0];
         q[0] = first ? qq : q[0];
     }
+    __device__ __forceinline__ void pop()            // drops the nearest entry
+    {
+#pragma unroll
+        for (int i = 0; i + 1 < K; ++i) {
+            d[i] = d[i + 1];
+            q[i] = q[i + 1];
+        }
+        d[K - 1] = __builtin_inff();
+        q[K - 1] = -1;
+    }
     __device__ __forceinline__ void store(int k, int32_t* pos, float* d2) const
     {
 #pragma unroll
@@ -110,6 +119,7 @@ __device__ __forceinline__ void visit_sample(Nearest<K> (&nb)[2], const float (&
 
 constexpr int kTile = 256;          // samples staged in LDS per pass
 constexpr int kPointsPerWg = 512;   // two points per thread
+constexpr int kWaveListMax = 4096;  // deferred points per cloud up to which each gets a whole wave
 
 // Brute force over all n samples.  LIST = false: the workgroup takes points
 // [blockIdx.x*512, +512) of cloud blockIdx.y.  LIST = true: it takes that range of the cloud's
@@ -132,6 +142,7 @@ __global__ __launch_bounds__(256) void knn_brute_kernel(const float* __restrict_
     if (LIST) {
         total = count[b];
         if (blockIdx.x == 0 && tid == 0 && out_deferred) out_deferred[b] = total;
+        if (total <= kWaveListMax) return;           // short lists are searched a wave per point
     }
     const int e0 = (int)blockIdx.x * kPointsPerWg;
     if (e0 >= total) return;                         // same for the whole workgroup
@@ -188,6 +199,60 @@ __global__ __launch_bounds__(256) void knn_brute_kernel(const float* __restrict_
         }
 }
 
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v)
+{
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, s, 64));
+    return v;
+}
+
+// Brute force for a short list of deferred points: one wave per point, the samples dealt out to
+// the lanes (lane l takes positions l, l+64, ...), then the 64 sorted lists are merged by taking
+// k times the smallest head (lower position among equal distances).  A point searched by one
+// thread would walk all n samples alone, which takes far longer than the cached search it
+// follows.
+template <int K>
+__global__ __launch_bounds__(256) void knn_list_wave_kernel(const float* __restrict__ xyz, int N,
+                                                            const int32_t* __restrict__ sample_idx, int n, int k,
+                                                            int32_t* __restrict__ out_pos,
+                                                            float* __restrict__ out_d2,
+                                                            const int32_t* __restrict__ list,
+                                                            const int32_t* __restrict__ count)
+{
+    const int b = (int)blockIdx.y;
+    const int lane = (int)threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int total = count[b];
+    const int e = (int)blockIdx.x * 4 + wave;
+    if (total > kWaveListMax || e >= total) return;  // wave-uniform; the kernel has no barrier
+    const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
+    const int32_t* __restrict__ sidx = sample_idx + (int64_t)b * n;
+    const int j = __builtin_amdgcn_readfirstlane(list[(int64_t)b * N + e]);
+    const float px = cloud[(int64_t)j * 3 + 0], py = cloud[(int64_t)j * 3 + 1], pz = cloud[(int64_t)j * 3 + 2];
+    Nearest<K> nb;
+    nb.clear();
+    for (int q = lane; q < n; q += 64) {
+        const int si = sidx[q];
+        float d = __builtin_nanf("");                // no such sample: never nearer
+        if (si >= 0 && si < N)
+            d = dist2(px, py, pz, cloud[(int64_t)si * 3 + 0], cloud[(int64_t)si * 3 + 1],
+                      cloud[(int64_t)si * 3 + 2]);
+        nb.insert(d, q);
+    }
+    const int64_t o = ((int64_t)b * N + j) * k;
+    for (int t = 0; t < k; ++t) {
+        // distances are >= +0 or +inf: the unsigned order of the bit patterns is their order
+        const uint32_t head = __float_as_uint(nb.d[0]);
+        const uint32_t dmin = wave_min_u32(head);
+        const uint32_t qmin = wave_min_u32(head == dmin ? (uint32_t)nb.q[0] : 0xFFFFFFFFu);
+        if (head == dmin && (uint32_t)nb.q[0] == qmin) nb.pop();
+        if (lane == 0) {
+            out_pos[o + t] = (int32_t)qmin;          // 0xFFFFFFFF = -1: fewer than k valid samples
+            out_d2[o + t] = __uint_as_float(dmin);
+        }
+    }
+}
+
 // flags[b] = 1 when the cache was recorded for exactly this sample list of cloud b;
 // also empties the cloud's list of deferred points.
 __global__ __launch_bounds__(256) void knn_check_kernel(const int32_t* __restrict__ sample_idx, int B, int N,
@@ -211,12 +276,11 @@ __global__ __launch_bounds__(256) void knn_check_kernel(const int32_t* __restric
     }
 }
 
-constexpr int kWordsPerWave = 4;    // 64-bit bitmap words (64 points each) one wave owns
-
-// Redundancy-free search.  A wave owns 4 consecutive bitmap words = 256 points (lane l holds
-// bit l of each word); a workgroup's 4 waves cover 128 contiguous bytes of every row.  The rows
-// (one per sample) are read 64 at a time, one row per lane; rows whose 4 words are all zero --
-// nearly all of them -- cost nothing more.
+// Redundancy-free search.  A wave owns one block of 64 points (lane l holds point 64*w + l).
+// The cache keeps the words of a point block contiguous over the samples: the wave streams them
+// 64 samples per load (one word per lane), and only a sample whose word is not zero -- its ball
+// holds at least one of the 64 points -- costs anything more: its word and coordinates are
+// broadcast and the lanes whose bit is set evaluate their distance to it.
 template <int K>
 __global__ __launch_bounds__(256) void knn_cached_kernel(const float* __restrict__ xyz, int N,
                                                          const int32_t* __restrict__ sample_idx, int n, int k,
@@ -230,67 +294,34 @@ __global__ __launch_bounds__(256) void knn_cached_kernel(const float* __restrict
     const int b = (int)blockIdx.y;
     const int lane = (int)threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
-    const int nwords = (N + 63) >> 6;
-    const int wbase = ((int)blockIdx.x * 4 + wave) * kWordsPerWave;
-    if (wbase >= nwords) return;                     // wave-uniform; the kernel has no barrier
+    const int blocks = (N + 63) >> 6;
+    const int w = (int)blockIdx.x * 4 + wave;
+    if (w >= blocks) return;                         // wave-uniform; the kernel has no barrier
     const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
     const int32_t* __restrict__ sidx = sample_idx + (int64_t)b * n;
 
-    int j[kWordsPerWave];
-    float px[kWordsPerWave], py[kWordsPerWave], pz[kWordsPerWave];
-    int hits[kWordsPerWave];
-    Nearest<K> nb[kWordsPerWave];
-#pragma unroll
-    for (int u = 0; u < kWordsPerWave; ++u) {
-        j[u] = ((wbase + u) << 6) | lane;
-        px[u] = py[u] = pz[u] = __builtin_nanf("");
-        if (j[u] < N) {
-            px[u] = cloud[(int64_t)j[u] * 3 + 0];
-            py[u] = cloud[(int64_t)j[u] * 3 + 1];
-            pz[u] = cloud[(int64_t)j[u] * 3 + 2];
-        }
-        hits[u] = 0;
-        nb[u].clear();
+    const int j = (w << 6) | lane;
+    float px = __builtin_nanf(""), py = px, pz = px;
+    if (j < N) {
+        px = cloud[(int64_t)j * 3 + 0];
+        py = cloud[(int64_t)j * 3 + 1];
+        pz = cloud[(int64_t)j * 3 + 2];
     }
+    int hits = 0;
+    Nearest<K> nb;
+    nb.clear();
 
     const bool usable = __builtin_amdgcn_readfirstlane(flags[b]) != 0;
     if (usable) {
         const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
-        const int64_t row_words = h->row_words;
-        const uint64_t* __restrict__ bits =
-            reinterpret_cast<const uint64_t*>(cache + h->bits_offset) + (int64_t)b * n * row_words + wbase;
-        // words past ceil(N/64) belong to the row's padding and are not defined
-        uint64_t keep[kWordsPerWave];
-#pragma unroll
-        for (int u = 0; u < kWordsPerWave; ++u) keep[u] = (wbase + u < nwords) ? ~0ull : 0ull;
-
-        uint64_t cur[kWordsPerWave], nxt[kWordsPerWave];
-#pragma unroll
-        for (int u = 0; u < kWordsPerWave; ++u) cur[u] = 0;
-        if (lane < n) {
-            const ulonglong2* r = reinterpret_cast<const ulonglong2*>(bits + (int64_t)lane * row_words);
-            const ulonglong2 a = r[0], c = r[1];
-            cur[0] = a.x;
-            cur[1] = a.y;
-            cur[2] = c.x;
-            cur[3] = c.y;
-        }
+        const uint64_t* __restrict__ col = reinterpret_cast<const uint64_t*>(cache + h->bits_offset) +
+                                           ((int64_t)b * h->blocks + w) * h->col_words;
+        // two loads are always on their way while a block of 64 samples is examined
+        uint64_t cur = lane < n ? col[lane] : 0ull;
+        uint64_t nxt = 64 + lane < n ? col[64 + lane] : 0ull;
         for (int q0 = 0; q0 < n; q0 += 64) {
-            // the next 64 rows are requested before this block is examined
-#pragma unroll
-            for (int u = 0; u < kWordsPerWave; ++u) nxt[u] = 0;
-            if (q0 + 64 + lane < n) {
-                const ulonglong2* r =
-                    reinterpret_cast<const ulonglong2*>(bits + (int64_t)(q0 + 64 + lane) * row_words);
-                const ulonglong2 a = r[0], c = r[1];
-                nxt[0] = a.x;
-                nxt[1] = a.y;
-                nxt[2] = c.x;
-                nxt[3] = c.y;
-            }
-#pragma unroll
-            for (int u = 0; u < kWordsPerWave; ++u) cur[u] &= keep[u];
-            const bool nz = (cur[0] | cur[1] | cur[2] | cur[3]) != 0;
+            const uint64_t after = q0 + 128 + lane < n ? col[q0 + 128 + lane] : 0ull;
+            const bool nz = cur != 0;
             uint64_t rows = __builtin_amdgcn_ballot_w64(nz);
             if (rows != 0) {
                 float sx = __builtin_nanf(""), sy = sx, sz = sx;
@@ -306,40 +337,32 @@ __global__ __launch_bounds__(256) void knn_cached_kernel(const float* __restrict
                     const int l = __builtin_ctzll(rows);
                     rows &= rows - 1;
                     const float ax = rdlane_f(sx, l), ay = rdlane_f(sy, l), az = rdlane_f(sz, l);
-#pragma unroll
-                    for (int u = 0; u < kWordsPerWave; ++u) {
-                        const uint64_t wu = rdlane_u64(cur[u], l);
-                        if (wu != 0) {
-                            const bool hit = (wu >> lane) & 1ull;
-                            const float d = hit ? dist2(px[u], py[u], pz[u], ax, ay, az) : __builtin_inff();
-                            hits[u] += hit ? 1 : 0;
-                            nb[u].insert(d, q0 + l);
-                        }
-                    }
+                    const uint64_t wd = rdlane_u64(cur, l);
+                    const bool hit = (wd >> lane) & 1ull;
+                    const float d = hit ? dist2(px, py, pz, ax, ay, az) : __builtin_inff();
+                    hits += hit ? 1 : 0;
+                    nb.insert(d, q0 + l);
                 }
             }
-#pragma unroll
-            for (int u = 0; u < kWordsPerWave; ++u) cur[u] = nxt[u];
+            cur = nxt;
+            nxt = after;
         }
     }
 
-#pragma unroll
-    for (int u = 0; u < kWordsPerWave; ++u) {
-        const bool in = j[u] < N;
-        const bool done = in && usable && hits[u] >= k;
-        if (done) {
-            const int64_t o = ((int64_t)b * N + j[u]) * k;
-            nb[u].store(k, out_pos + o, out_d2 + o);
-        }
-        // fewer than k samples inside the radius: the point goes to the brute-force list
-        const bool defer = in && !done;
-        const uint64_t dm = __builtin_amdgcn_ballot_w64(defer);
-        if (dm != 0) {
-            int base = 0;
-            if (lane == __builtin_ctzll(dm)) base = atomicAdd(count + b, __builtin_popcountll(dm));
-            base = __builtin_amdgcn_readlane(base, __builtin_ctzll(dm));
-            if (defer) list[(int64_t)b * N + base + lanes_below(dm)] = j[u];
-        }
+    const bool in = j < N;
+    const bool done = in && usable && hits >= k;
+    if (done) {
+        const int64_t o = ((int64_t)b * N + j) * k;
+        nb.store(k, out_pos + o, out_d2 + o);
+    }
+    // fewer than k samples inside the radius: the point goes to the brute-force list
+    const bool defer = in && !done;
+    const uint64_t dm = __builtin_amdgcn_ballot_w64(defer);
+    if (dm != 0) {
+        int base = 0;
+        if (lane == __builtin_ctzll(dm)) base = atomicAdd(count + b, __builtin_popcountll(dm));
+        base = __builtin_amdgcn_readlane(base, __builtin_ctzll(dm));
+        if (defer) list[(int64_t)b * N + base + lanes_below(dm)] = j;
     }
 }
 
@@ -358,10 +381,12 @@ hipError_t launch_knn_k(const float* xyz, int B, int N, const int32_t* sample_id
     const unsigned char* cache = reinterpret_cast<const unsigned char*>(bq_cache);
     hipLaunchKernelGGL(knn_check_kernel, dim3((unsigned)B), dim3(256), 0, stream, sample_idx, B, N, n, cache,
                        flags, count);
-    const int nwords = (N + 63) >> 6;
-    const dim3 grid_words((unsigned)((nwords + 4 * kWordsPerWave - 1) / (4 * kWordsPerWave)), (unsigned)B);
+    const int blocks = (N + 63) >> 6;
+    const dim3 grid_words((unsigned)((blocks + 3) / 4), (unsigned)B);
     hipLaunchKernelGGL((knn_cached_kernel<K>), grid_words, dim3(256), 0, stream, xyz, N, sample_idx, n, k,
                        out_pos, out_d2, cache, (const int32_t*)flags, count, list);
+    hipLaunchKernelGGL((knn_list_wave_kernel<K>), dim3(kWaveListMax / 4, (unsigned)B), dim3(256), 0, stream, xyz,
+                       N, sample_idx, n, k, out_pos, out_d2, (const int32_t*)list, (const int32_t*)count);
     hipLaunchKernelGGL((knn_brute_kernel<K, true>), grid_pts, dim3(256), 0, stream, xyz, N, sample_idx, n, k,
                        out_pos, out_d2, (const int32_t*)list, (const int32_t*)count, out_deferred);
     return hipGetLastError();

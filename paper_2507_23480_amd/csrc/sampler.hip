@@ -322,19 +322,20 @@ __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, floa
     fold_groups<P, BQ, 0>(pt, cx, cy, cz, a.bq_r2, wh.lane, s, rw);
 }
 
-// Writes the words of `count` picks (sample positions base, base+1, ...; count <= 64) to their
-// cache rows: lane s writes the wave's P consecutive words of row base+s.
+// Writes the words of `count` picks (sample positions base, base+1, ...; count <= 64) to the
+// cache: for every slot p the lanes store the words [block gw*P + p][base .. base+count), which
+// are contiguous.
 template <int P, bool BQ>
 __device__ __forceinline__ void flush_rows(const RowWords<P>& rw, const SamplerArgs& a, const Where& wh,
                                            int base, int count)
 {
     if (!BQ) return;
-    if (wh.lane < count) {
-        uint64_t* row = a.bq_bits + ((int64_t)wh.c * a.n + base + wh.lane) * a.bq_row_words +
-                        (int64_t)wh.gw * P;
 #pragma unroll
-        for (int p = 0; p < P; ++p)      // rows hold ceil(N/64) words (rounded up); slots wholly beyond N have none
-            if ((int64_t)wh.gw * P + p < a.bq_row_words) row[p] = ((uint64_t)rw.hi[p] << 32) | rw.lo[p];
+    for (int p = 0; p < P; ++p) {
+        const int blk = wh.gw * P + p;              // slots wholly beyond N have no block
+        if (blk < a.bq_blocks && wh.lane < count)
+            a.bq_bits[((int64_t)wh.c * a.bq_blocks + blk) * a.bq_col_words + base + wh.lane] =
+                ((uint64_t)rw.hi[p] << 32) | rw.lo[p];
     }
 }
 
@@ -1149,16 +1150,6 @@ const void* pick_bq(bool bq)
 
 const void* sampler_kernel_for(int threads, int points_per_thread, bool bq)
 {
-    if (threads == 256) {
-        switch (points_per_thread) {
-            case 2: return pick_bq<256, 2>(bq);
-            case 4: return pick_bq<256, 4>(bq);
-            case 8: return pick_bq<256, 8>(bq);
-            case 16: return pick_bq<256, 16>(bq);
-            case 32: return pick_bq<256, 32>(bq);
-            default: return nullptr;
-        }
-    }
     if (threads == 512) {
         switch (points_per_thread) {
             case 2: return pick_bq<512, 2>(bq);
