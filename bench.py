@@ -6,8 +6,13 @@ every stage of its hierarchy:
     exact path   fps_exact -> ball_query (brute force)          (Alg. 1 + Section 3.1)
     FastPoint    mdps_sample (records the radius tests) -> ball_query (cache reader)
                                                                 (Alg. 2 + Section 4.2)
-    gather of the exact-FPS samples = input of the next stage
+    gather of the exact-FPS samples = input of the next stage (which waits for it)
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+Workloads whose clouds take one workgroup each leave most of the device idle, so their step
+runs the two paths of a stage on two streams and is replayed as one captured HIP graph (no
+host time between the launches); the replay's outputs are compared with the eager ones.  The
+per-kernel times and rooflines always come from calls that run alone on one stream.
 
 Outside the timed step the k nearest samples of every point (the k-NN of the up-sampling
 step, redundancy-free form of Section 4.2) are timed per stage and reported under "detail".
@@ -34,6 +39,8 @@ HBM_PEAK_GBS = 8000.0
 OPS_PER_POINT_ITERATION = 10      # 3 sub, 3 mul, 2 add, 1 min, 1 compare (FPS min-update + arg-max)
 OPS_PER_PAIR_TEST = 9             # 3 sub, 3 mul, 2 add, 1 compare (ball query, k-NN)
 KNN_K = 3                         # neighbours of the up-sampling step (Section 3.1)
+EAGER = "one stream, eager launches"
+GRAPH = "two streams, step replayed as one HIP graph"
 
 # HBM traffic per launch of the kernels that can dominate the step, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs (profiles/bench_C2_hbm_traffic.md); bytes, keyed by workload and
@@ -91,33 +98,64 @@ def make_context(torch, fp, inputs, calibration, name):
     wl = inputs.WORKLOADS[name]
     xyz = torch.from_numpy(inputs.make_batch(name)).cuda()
     stages = []
-    x = xyz
+    B, N = xyz.shape[0], xyz.shape[1]
     for s, st in enumerate(wl.stages):
-        stages.append({"xyz": x, "n": st.n, "radius": st.radius, "k": st.k,
+        stages.append({"B": B, "N": N, "n": st.n, "radius": st.radius, "k": st.k,
                        "prm": calibration.params_for(name, s),
-                       "cache": fp.new_bq_cache(x, st.n)})
-        if s + 1 < len(wl.stages):
-            x = fp.gather_xyz(x, fp.fps_exact(x, st.n)).contiguous()
+                       "cache": torch.empty(fp.load().fp_bq_cache_bytes(B, N, st.n), dtype=torch.uint8,
+                                            device="cuda"),
+                       "G": fp.plan(B, N)[0],
+                       "ws": [fp.new_workspace(xyz.device, B, N), fp.new_workspace(xyz.device, B, N)]})
+        N = st.n
     torch.cuda.synchronize()
-    return {"wl": wl, "stages": stages}
+    return {"wl": wl, "stages": stages, "xyz": xyz, "side": torch.cuda.Stream()}
 
 
 def run_step(fp, ctx, timer, keep=None):
+    """One step, every call on the current stream, each timed with events."""
+    x = ctx["xyz"]
     for s, sg in enumerate(ctx["stages"]):
-        x, n, r, k = sg["xyz"], sg["n"], sg["radius"], sg["k"]
-        idx = timer.call("fps_exact/s%d" % s, lambda: fp.fps_exact(x, n))
-        bq = timer.call("ball_query_brute/s%d" % s, lambda: fp.ball_query(x, idx, r, k))
+        n, r, k = sg["n"], sg["radius"], sg["k"]
+        xs = x
+        idx = timer.call("fps_exact/s%d" % s, lambda: fp.fps_exact(xs, n))
+        bq = timer.call("ball_query_brute/s%d" % s, lambda: fp.ball_query(xs, idx, r, k))
         midx = timer.call("mdps_sample+record/s%d" % s,
-                          lambda: fp.mdps_sample(x, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r))
+                          lambda: fp.mdps_sample(xs, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r))
         mbq = timer.call("ball_query_cached/s%d" % s,
-                         lambda: fp.ball_query(x, midx, r, k, bq_cache=sg["cache"]))
+                         lambda: fp.ball_query(xs, midx, r, k, bq_cache=sg["cache"]))
         if s + 1 < len(ctx["stages"]):
-            timer.call("gather/s%d" % s, lambda: fp.gather_xyz(x, idx))
+            x = timer.call("gather/s%d" % s, lambda: fp.gather_xyz(xs, idx))
         if keep is not None:
-            keep.append((idx, bq, midx, mbq))
+            keep.append((xs, idx, bq, midx, mbq))
 
 
-def measure(torch, fp, ctx, steps, warmup):
+def run_step_streams(torch, fp, ctx, keep=None):
+    """One step with the two sampling paths of a stage on two streams where both fit on the
+    device side by side (one workgroup per cloud): the exact path (fps_exact, ball query, gather)
+    on the current stream, the FastPoint path (mdps_sample with recording, cache reader) on a
+    second one that starts when the stage's input is ready.  The next stage waits for the gather."""
+    main = torch.cuda.current_stream()
+    side = ctx["side"]
+    x = ctx["xyz"]
+    for s, sg in enumerate(ctx["stages"]):
+        n, r, k = sg["n"], sg["radius"], sg["k"]
+        two = sg["G"] == 1
+        if two:
+            side.wait_stream(main)                  # the stage's input is ready
+        idx = fp.fps_exact(x, n, ws=sg["ws"][0])
+        bq = fp.ball_query(x, idx, r, k)
+        with torch.cuda.stream(side if two else main):
+            midx = fp.mdps_sample(x, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r, ws=sg["ws"][1])
+            mbq = fp.ball_query(x, midx, r, k, bq_cache=sg["cache"])
+        if keep is not None:
+            keep.append((x, idx, bq, midx, mbq))
+        if s + 1 < len(ctx["stages"]):
+            x = fp.gather_xyz(x, idx)
+    main.wait_stream(side)
+
+
+def measure_eager(torch, fp, ctx, steps, warmup):
+    """(ms per step, mean ms per kernel): every call alone, one stream, eager launches."""
     timer = Timer(torch)
     for _ in range(warmup):
         run_step(fp, ctx, timer)
@@ -127,16 +165,49 @@ def measure(torch, fp, ctx, steps, warmup):
     for _ in range(steps):
         run_step(fp, ctx, timer)
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    seq_ms = (time.perf_counter() - t0) * 1e3 / steps
     timer.collect()
-    return (t1 - t0) * 1e3 / steps, timer.mean_ms()
+    return seq_ms, timer.mean_ms()
+
+
+def one_workgroup_per_cloud(ctx):
+    """A cloud spread over several workgroups fills the device: nothing to run beside it."""
+    return all(sg["G"] == 1 for sg in ctx["stages"])
+
+
+def measure_graph(torch, fp, ctx, steps, warmup):
+    """ms per step for small clouds: two streams, the step captured once in a graph and
+    replayed; the replay's outputs are checked against the eager ones.  Called after all eager
+    measurements of the process: once a graph with a second stream has run, eager launches on
+    the streams that existed by then take tens of microseconds longer each."""
+    eager = []
+    run_step_streams(torch, fp, ctx, eager)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    held = []
+    with torch.cuda.graph(graph):
+        run_step_streams(torch, fp, ctx, held)
+    for _ in range(max(warmup, 1)):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    for got, want in zip(held, eager):
+        for g, w in zip(got[1:], want[1:]):
+            same = all(torch.equal(a, b) for a, b in zip(g, w)) if isinstance(g, tuple) else torch.equal(g, w)
+            if not same:
+                raise RuntimeError("graph replay of the step differs from the eager result")
+    return ms
 
 
 def cached_words_read(torch, ctx, s, outs):
     """64-bit words the cache reader has to read: per centre, whole 64-word blocks up to
     the block holding its k-th hit (the whole row when it has fewer than k hits)."""
     sg = ctx["stages"][s]
-    N, k = sg["xyz"].shape[1], sg["k"]
+    N, k = sg["N"], sg["k"]
     nwords = (N + 63) // 64
     idx, cnt = outs
     last = idx[:, :, k - 1].to(torch.int64) // 64 + 1
@@ -155,9 +226,9 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
     wl = ctx["wl"]
     out = {"stages": []}
     for s, sg in enumerate(ctx["stages"]):
-        x, n, k = sg["xyz"], sg["n"], sg["k"]
+        n, k = sg["n"], sg["k"]
+        x, idx, bq, midx, mbq = keep[s]
         B, N = x.shape[0], x.shape[1]
-        idx, bq, midx, mbq = keep[s]
         _, info = fp.mdps_sample(x, n, sg["prm"], want_info=True)
         cov_f = fp.coverage2(x, idx).sqrt()
         cov_m = fp.coverage2(x, midx).sqrt()
@@ -188,7 +259,7 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             a = byts / (ms["ball_query_cached"] * 1e-3) / 1e9
             roof["ball_query_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                          "frac": a / HBM_PEAK_GBS, "bytes": byts}
-        knn = time_knn(torch, fp, sg, midx)
+        knn = time_knn(torch, fp, x, sg, midx)
         for kname in ("knn_brute", "knn_cached"):
             ms[kname] = knn[kname + "_ms"]
         a = float(B) * N * n * OPS_PER_PAIR_TEST / (knn["knn_brute_ms"] * 1e-3) / 1e12
@@ -214,10 +285,9 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
     return out
 
 
-def time_knn(torch, fp, sg, midx, reps=3):
+def time_knn(torch, fp, x, sg, midx, reps=3):
     """k nearest MDPS samples of every point of a stage: brute force and through the recorded
     ball bitmaps (both give the same result; checked here).  Not part of the timed step."""
-    x = sg["xyz"]
     res = {}
     for kname, cache in (("knn_brute", None), ("knn_cached", sg["cache"])):
         fp.knn(x, midx, KNN_K, bq_cache=cache)
@@ -287,6 +357,7 @@ def main():
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, "
               "no sharding across devices in this library)" % args.gpus, file=sys.stderr)
         return 2
+    extra = {} if args.no_extra else other_workloads(args.workload)
     import torch
     from paper_2507_23480_amd import binding as fp, inputs, calibration
     if not torch.cuda.is_available():
@@ -295,9 +366,38 @@ def main():
     fp.load()
     if args.plain_launch:
         fp.set_cooperative_launch(False)
+    return run(args, torch, fp, inputs, calibration, extra)
+
+
+def other_workloads(name):
+    """The other workloads, each measured by a process of its own (started before this one
+    touches the GPU): cooperative launches and graph replays with a second stream slow each
+    other's launches down by tens of microseconds once both have run in one process."""
+    import subprocess
+    extra = {}
+    for other in ["C1", "C2", "C3", "C4", "C5"]:
+        if other == name:
+            continue
+        k = 3 if other in ("C4", "C5") else 10
+        cmd = [sys.executable, os.path.abspath(__file__), "--workload", other, "--no-extra", "--no-cpu",
+               "--steps", str(k), "--warmup", "1"]
+        try:
+            out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, timeout=240,
+                                 check=True).stdout.decode()
+            d = json.loads(out.strip().splitlines()[-1])
+            extra[other] = {"ms_per_step": d["ms_per_step"], "Mpoints_per_s": d["value"], "steps": k,
+                            "launch": d["config"]["launch"],
+                            "ms_per_step_one_stream_eager": d["config"]["ms_per_step_one_stream_eager"],
+                            "detail": d["detail"]}
+        except Exception as exc:                 # reported, not fatal: the headline line still prints
+            extra[other] = {"error": repr(exc)[:200]}
+    return extra
+
+
+def run(args, torch, fp, inputs, calibration, extra):
     name = args.workload
     ctx = make_context(torch, fp, inputs, calibration, name)
-    ms_per_step, kernel_ms = measure(torch, fp, ctx, args.steps, args.warmup)
+    seq_ms, kernel_ms = measure_eager(torch, fp, ctx, args.steps, args.warmup)
     wl = ctx["wl"]
     detail = quality_and_rooflines(torch, fp, ctx, kernel_ms)
     s0 = detail["stages"][0]
@@ -308,6 +408,10 @@ def main():
     roof["kernel"] = dom + " (stage 0)"
     roof["ms_per_launch"] = s0["kernel_ms"][dom]
     roof["traffic"] = TRAFFIC_BYTES.get(name, {}).get(dom)
+    # graph replay after all eager measurements of this process (see measure_graph)
+    ms_per_step, launch_mode = seq_ms, EAGER
+    if one_workgroup_per_cloud(ctx):
+        ms_per_step, launch_mode = measure_graph(torch, fp, ctx, args.steps, args.warmup), GRAPH
     line = {
         "metric": "FPS+ball-query latency per batch (ms) and Mpoints/s; achieved HBM GB/s vs peak",
         "value": wl.B * wl.N / (ms_per_step * 1e-3) / 1e6, "unit": "Mpoints/s",
@@ -318,26 +422,14 @@ def main():
                    "stages": [{"n": st.n, "radius": st.radius, "k": st.k} for st in wl.stages],
                    "step": "per stage: fps_exact, ball_query(brute), mdps_sample(+radius record), "
                            "ball_query(cache reader), gather",
+                   "launch": launch_mode, "ms_per_step_one_stream_eager": seq_ms,
                    "mdps": {"p": calibration.P_RATIO, "nseg": calibration.NSEG}},
         "roofline": roof,
         "detail": detail,
     }
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(inputs, name)
-    if not args.no_extra:
-        extra = {}
-        for other in ["C1", "C2", "C3", "C4", "C5"]:
-            if other == name:
-                continue
-            octx = make_context(torch, fp, inputs, calibration, other)
-            k = 3 if other in ("C4", "C5") else 10
-            oms, okms = measure(torch, fp, octx, k, 1)
-            od = quality_and_rooflines(torch, fp, octx, okms)
-            owl = octx["wl"]
-            extra[other] = {"ms_per_step": oms, "Mpoints_per_s": owl.B * owl.N / (oms * 1e-3) / 1e6,
-                            "steps": k, "detail": od}
-            del octx
-            torch.cuda.empty_cache()
+    if extra:
         line["other_workloads"] = extra
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")

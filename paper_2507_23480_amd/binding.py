@@ -173,6 +173,15 @@ def workspace(device: torch.device, B: int, N: int) -> torch.Tensor:
     return ws
 
 
+def new_workspace(device: torch.device, B: int, N: int) -> torch.Tensor:
+    """A workspace of its own, for sampler calls that run at the same time as others on the
+    device (another stream) or inside a captured graph."""
+    need = int(load().fp_workspace_bytes(B, N))
+    if need == 0:
+        raise ValueError("shape (B=%d, N=%d) not supported" % (B, N))
+    return torch.empty(need, dtype=torch.uint8, device=device)
+
+
 def new_bq_cache(xyz: torch.Tensor, n: int) -> torch.Tensor:
     B, N = _xyz(xyz)
     need = int(load().fp_bq_cache_bytes(B, N, n))
@@ -195,15 +204,17 @@ def _start(start_idx, B, device) -> Optional[torch.Tensor]:
 
 def fps_exact(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool = False,
               want_info: bool = False, bq_cache: Optional[torch.Tensor] = None,
-              bq_radius: float = 0.0):
+              bq_radius: float = 0.0, ws: Optional[torch.Tensor] = None):
     """Exact farthest point sampling.  Returns idx [B][n] int32 (and mdc [B][n] float32,
-    info bytes [B][INFO_BYTES] uint8 when asked for)."""
+    info bytes [B][INFO_BYTES] uint8 when asked for).  `ws`: a workspace from new_workspace
+    (default: the device's shared one)."""
     B, N = _xyz(xyz)
     st = _start(start_idx, B, xyz.device)
     idx = torch.empty((B, n), dtype=torch.int32, device=xyz.device)
     mdc = torch.empty((B, n), dtype=torch.float32, device=xyz.device) if want_mdc else None
     info = torch.zeros((B, INFO_BYTES), dtype=torch.uint8, device=xyz.device) if want_info else None
-    ws = workspace(xyz.device, B, N)
+    if ws is None:
+        ws = workspace(xyz.device, B, N)
     _check(load().fp_fps_exact(xyz.data_ptr(), B, N, n, _ptr(st), idx.data_ptr(), _ptr(mdc), _ptr(info),
                                _ptr(bq_cache), float(bq_radius), ws.data_ptr(), ws.numel(), _stream()),
            "fp_fps_exact")
@@ -216,13 +227,15 @@ def fps_exact(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool = False,
 
 
 def mdps_sample(xyz: torch.Tensor, n: int, prm: MdpsParams, start_idx=None, want_info: bool = False,
-                bq_cache: Optional[torch.Tensor] = None, bq_radius: float = 0.0):
+                bq_cache: Optional[torch.Tensor] = None, bq_radius: float = 0.0,
+                ws: Optional[torch.Tensor] = None):
     """Minimum distance prediction sampling.  Returns idx [B][n] int32 (and info bytes)."""
     B, N = _xyz(xyz)
     st = _start(start_idx, B, xyz.device)
     idx = torch.empty((B, n), dtype=torch.int32, device=xyz.device)
     info = torch.zeros((B, INFO_BYTES), dtype=torch.uint8, device=xyz.device) if want_info else None
-    ws = workspace(xyz.device, B, N)
+    if ws is None:
+        ws = workspace(xyz.device, B, N)
     c = prm.to_c()
     _check(load().fp_mdps_sample(xyz.data_ptr(), B, N, n, _ptr(st), ctypes.byref(c), idx.data_ptr(),
                                  _ptr(info), _ptr(bq_cache), float(bq_radius), ws.data_ptr(), ws.numel(),
