@@ -561,6 +561,87 @@ int ref_gather_xyz(const float *xyz, int32_t N, const int32_t *idx, int32_t M, f
     return 0;
 }
 
+/* ------------------------------------------------------- exclusion lists -- */
+/*
+ * Exclusion lists -- Algorithm 2 lines 15-22 (Section 4.1 step 2), plus the extra
+ * list at the ball-query radius of Section 4.2, as a data structure of its own:
+ * for every level l and every point i the points j with dist2(P_i, P_j) < thr2[l],
+ * in the order the paper's loop over j appends them (ascending j; i itself is a
+ * member whenever thr2[l] > 0).  One distance per pair serves all levels.
+ *   thr2    [L] squared radii, any order (the MDPS thresholds are non-increasing,
+ *           the ball-query radius may lie anywhere among them)
+ *   offsets [L*N + 1] row r = l*N + i occupies entries[offsets[r] .. offsets[r+1])
+ *   entries NULL: only the offsets are produced (a caller sizes the array from
+ *           offsets[L*N]); else it receives the members, `capacity` of them at most
+ * Returns 0, -1 on bad arguments, -2 if `capacity` is too small.
+ */
+int ref_excl_lists(const float *xyz, int32_t N, const float *thr2, int32_t L,
+                   int64_t *offsets, int32_t *entries, int64_t capacity)
+{
+    if (!xyz || !thr2 || !offsets || N < 1 || L < 1)
+        return -1;
+    const size_t rows = (size_t)L * (size_t)N;
+    for (size_t r = 0; r <= rows; ++r)
+        offsets[r] = 0;
+    /* sizes first: offsets[r + 1] = members of row r */
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t j = 0; j < N; ++j) {
+            float d = ref_dist2(xyz + 3 * (size_t)i, xyz + 3 * (size_t)j);
+            for (int32_t l = 0; l < L; ++l)
+                if (d < thr2[l])
+                    ++offsets[(size_t)l * N + i + 1];
+        }
+    for (size_t r = 0; r < rows; ++r)
+        offsets[r + 1] += offsets[r];
+    if (!entries)
+        return 0;
+    if (offsets[rows] > capacity)
+        return -2;
+    for (int32_t i = 0; i < N; ++i) {
+        for (int32_t j = 0; j < N; ++j) {
+            float d = ref_dist2(xyz + 3 * (size_t)i, xyz + 3 * (size_t)j);
+            for (int32_t l = 0; l < L; ++l)
+                if (d < thr2[l]) {
+                    /* append: the cursor of row r is kept in place of its start and put back below */
+                    size_t r = (size_t)l * N + i;
+                    entries[offsets[r]++] = j;
+                }
+        }
+    }
+    /* every row's cursor now sits at its end = the next row's start: shift back */
+    for (size_t r = rows; r > 0; --r)
+        offsets[r] = offsets[r - 1];
+    offsets[0] = 0;
+    return 0;
+}
+
+/*
+ * Ball query by lookup in an exclusion list (Section 4.2: the neighbours of a
+ * centre are its list at the query radius): the first k members of row
+ * level*N + centre in list order, unused slots repeating the first member,
+ * out_cnt = min(members, k).  An empty row gives -1 in every slot and count 0.
+ */
+int ref_ball_query_lists(const int64_t *offsets, const int32_t *entries, int32_t N, int32_t level,
+                         const int32_t *center_idx, int32_t M, int32_t k, int32_t *out_idx,
+                         int32_t *out_cnt)
+{
+    if (!offsets || !entries || !center_idx || !out_idx || N < 1 || level < 0 || M < 0 || k < 1)
+        return -1;
+    for (int32_t q = 0; q < M; ++q) {
+        int32_t c = center_idx[q];
+        if (c < 0 || c >= N)
+            return -1;
+        size_t r = (size_t)level * N + c;
+        int64_t len = offsets[r + 1] - offsets[r];
+        int32_t cnt = len < k ? (int32_t)len : k;
+        for (int32_t t = 0; t < k; ++t)
+            out_idx[(size_t)q * k + t] = cnt == 0 ? -1 : entries[offsets[r] + (t < cnt ? t : 0)];
+        if (out_cnt)
+            out_cnt[q] = cnt;
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------ k nearest samples -- */
 /*
  * k-NN of the up-sampling (feature propagation) step, Section 3.1: for every

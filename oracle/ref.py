@@ -92,6 +92,9 @@ def lib() -> ctypes.CDLL:
         _lib.ref_mdps_literal.argtypes = _lib.ref_mdps_sample.argtypes
         _lib.ref_ball_query.argtypes = [fp, i32, ip, i32, ctypes.c_float, i32, ip, ip]
         _lib.ref_gather_xyz.argtypes = [fp, i32, ip, i32, fp]
+        lp = ctypes.POINTER(ctypes.c_int64)
+        _lib.ref_excl_lists.argtypes = [fp, i32, fp, i32, lp, ip, ctypes.c_int64]
+        _lib.ref_ball_query_lists.argtypes = [lp, ip, i32, i32, ip, i32, i32, ip, ip]
         _lib.ref_knn.argtypes = [fp, i32, ip, i32, i32, ip, i32, ip, fp]
         _lib.ref_coverage_radius.argtypes = [fp, i32, ip, i32]
         _lib.ref_coverage_radius.restype = ctypes.c_double
@@ -180,6 +183,42 @@ def ball_query(xyz, centers, radius: float, k: int) -> Tuple[np.ndarray, np.ndar
     rc = lib().ref_ball_query(_f(a), a.shape[0], _i(c), M, np.float32(radius), k, _i(idx), _i(cnt))
     if rc != 0:
         raise ValueError("ref_ball_query rejected its arguments")
+    return idx, cnt
+
+
+def excl_lists(xyz, thr2) -> Tuple[np.ndarray, np.ndarray]:
+    """Exclusion lists of one cloud for the squared radii thr2[L] (Alg. 2 lines 15-22):
+    (offsets[L*N+1] int64, entries int32); row l*N+i holds the j with dist2(i,j) < thr2[l],
+    ascending."""
+    a = _cloud(xyz)
+    t = np.ascontiguousarray(thr2, dtype=np.float32).reshape(-1)
+    N, L = a.shape[0], t.shape[0]
+    off = np.empty(L * N + 1, dtype=np.int64)
+    lp = ctypes.POINTER(ctypes.c_int64)
+    rc = lib().ref_excl_lists(_f(a), N, _f(t), L, off.ctypes.data_as(lp), None, 0)
+    if rc != 0:
+        raise ValueError("ref_excl_lists rejected its arguments")
+    ent = np.empty(max(int(off[-1]), 1), dtype=np.int32)
+    rc = lib().ref_excl_lists(_f(a), N, _f(t), L, off.ctypes.data_as(lp), _i(ent), ent.shape[0])
+    if rc != 0:
+        raise ValueError("ref_excl_lists failed (%d)" % rc)
+    return off, ent[:int(off[-1])]
+
+
+def ball_query_lists(offsets, entries, N: int, level: int, centers, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Ball query by lookup in the exclusion lists: (idx[M][k] int32, cnt[M] int32)."""
+    off = np.ascontiguousarray(offsets, dtype=np.int64)
+    ent = np.ascontiguousarray(entries, dtype=np.int32)
+    if ent.shape[0] == 0:
+        ent = np.zeros(1, dtype=np.int32)
+    c = np.ascontiguousarray(centers, dtype=np.int32)
+    M = c.shape[0]
+    idx = np.empty((M, k), dtype=np.int32)
+    cnt = np.empty(M, dtype=np.int32)
+    rc = lib().ref_ball_query_lists(off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _i(ent), N, level,
+                                    _i(c), M, k, _i(idx), _i(cnt))
+    if rc != 0:
+        raise ValueError("ref_ball_query_lists rejected its arguments")
     return idx, cnt
 
 
