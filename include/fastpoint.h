@@ -161,6 +161,48 @@ fp_status fp_knn(const float* xyz, int32_t B, int32_t N, const int32_t* sample_i
                  int32_t k, int32_t* out_pos, float* out_d2, const void* bq_cache,
                  int32_t* out_deferred, void* workspace, size_t workspace_bytes, void* stream);
 
+#define FP_EXCL_MAX_LEVELS 17   /* FP_MAX_SEG thresholds and the ball-query radius */
+
+/* Bytes of workspace fp_excl_count / fp_excl_fill need (0 for shapes the library rejects).
+ * Alignment: 256 bytes. */
+size_t fp_excl_workspace_bytes(int32_t B, int32_t N, int32_t L);
+
+/*
+ * Exclusion lists as a data structure, Algorithm 2 lines 15-22 (Section 4.1 step 2) with
+ * the extra list at the ball-query radius of Section 4.2: for level l, cloud b and point i,
+ * row r = (l*B + b)*N + i holds the points j of the cloud with dist^2(P_i, P_j) < thr2[b][l]
+ * (strict, binary32) in ascending j -- the order in which the paper's loop over j appends
+ * them; i itself is a member whenever thr2[b][l] > 0.  One distance per examined pair serves
+ * all levels; a uniform grid limits the pairs examined to the 27 cells around a point.
+ * Two passes, as for any compressed-row structure:
+ *   fp_excl_count  builds the grid in the workspace and writes offsets [L*B*N + 1] int64:
+ *                  row r occupies entries[offsets[r] .. offsets[r+1]); offsets[L*B*N] is the
+ *                  number of members in total, which the caller reads back to size `entries`
+ *   fp_excl_fill   writes the members.  Same xyz, thr2, L and workspace as the count call,
+ *                  with nothing else using the workspace in between.  Members whose position
+ *                  is >= capacity are not written (no error is raised on the device).
+ *   thr2  [B][L] float32 squared radii, DEVICE memory (e.g. the thr2 fields of fp_mdps_info,
+ *         or radius*radius of a ball query), any order, 1 <= L <= FP_EXCL_MAX_LEVELS;
+ *         a value <= 0 or NaN gives empty rows
+ */
+fp_status fp_excl_count(const float* xyz, int32_t B, int32_t N, const float* thr2, int32_t L,
+                        int64_t* offsets, void* workspace, size_t workspace_bytes, void* stream);
+fp_status fp_excl_fill(const float* xyz, int32_t B, int32_t N, const float* thr2, int32_t L,
+                       const int64_t* offsets, int32_t* entries, int64_t capacity,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Ball query by lookup in exclusion lists (Section 4.2: the neighbours of a centre are its
+ * list at the query radius): the first k members of row (level*B + b)*N + center_idx[b][q],
+ * unused slots repeating the first member, out_cnt = min(members, k).  With the level's
+ * radius equal to the query radius this is fp_ball_query's result for any centre set.
+ * An empty row or a centre index outside [0,N) gives -1 in every slot and count 0.
+ *   out_idx [B][M][k] int32, out_cnt [B][M] int32 or NULL, 1 <= k
+ */
+fp_status fp_ball_query_lists(const int64_t* offsets, const int32_t* entries, int32_t B, int32_t N,
+                              int32_t level, int32_t L, const int32_t* center_idx, int32_t M, int32_t k,
+                              int32_t* out_idx, int32_t* out_cnt, void* stream);
+
 /* out_xyz[b][q] = xyz[b][idx[b][q]] -- input of the next stage of a hierarchy
  * (Section 3.1).  Indices outside [0,N) give NaN coordinates. */
 fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N,

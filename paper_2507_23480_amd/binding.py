@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
 EXPORTS = ["fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
-           "fp_ball_query", "fp_knn_workspace_bytes", "fp_knn", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
+           "fp_ball_query", "fp_knn_workspace_bytes", "fp_knn", "fp_excl_workspace_bytes", "fp_excl_count",
+           "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
 
 
@@ -102,6 +103,14 @@ def load() -> ctypes.CDLL:
     lib.fp_knn_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_knn.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.fp_knn.restype = i32
+    lib.fp_excl_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.fp_excl_workspace_bytes.restype = ctypes.c_size_t
+    lib.fp_excl_count.argtypes = [vp, i32, i32, vp, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.fp_excl_count.restype = i32
+    lib.fp_excl_fill.argtypes = [vp, i32, i32, vp, i32, vp, vp, ctypes.c_int64, vp, ctypes.c_size_t, vp]
+    lib.fp_excl_fill.restype = i32
+    lib.fp_ball_query_lists.argtypes = [vp, vp, i32, i32, i32, i32, vp, i32, i32, vp, vp, vp]
+    lib.fp_ball_query_lists.restype = i32
     lib.fp_gather_xyz.argtypes = [vp, i32, i32, vp, i32, vp, vp]
     lib.fp_gather_xyz.restype = i32
     lib.fp_coverage.argtypes = [vp, i32, i32, vp, i32, vp, vp]
@@ -281,6 +290,48 @@ def knn(xyz: torch.Tensor, sample_idx: torch.Tensor, k: int, bq_cache: Optional[
     _check(load().fp_knn(xyz.data_ptr(), B, N, sample_idx.data_ptr(), n, k, pos.data_ptr(), d2.data_ptr(),
                          _ptr(bq_cache), _ptr(deferred), _ptr(ws), ws_bytes, _stream()), "fp_knn")
     return (pos, d2, deferred) if want_deferred else (pos, d2)
+
+
+def excl_lists(xyz: torch.Tensor, thr2: torch.Tensor, ws: Optional[torch.Tensor] = None):
+    """Exclusion lists for the squared radii thr2 [B][L] (float32, on the device):
+    (offsets [L*B*N + 1] int64, entries int32); row (l*B + b)*N + i holds the points j of
+    cloud b with dist^2(i, j) < thr2[b][l], ascending.  Reads the total back between the two
+    passes (one synchronisation) to size `entries`."""
+    B, N = _xyz(xyz)
+    if not (thr2.is_cuda and thr2.dtype == torch.float32 and thr2.dim() == 2 and thr2.shape[0] == B
+            and thr2.is_contiguous()):
+        raise ValueError("thr2 must be a contiguous CUDA float32 tensor [B][L]")
+    L = int(thr2.shape[1])
+    need = int(load().fp_excl_workspace_bytes(B, N, L))
+    if need == 0:
+        raise ValueError("shape (B=%d, N=%d, L=%d) not supported" % (B, N, L))
+    if ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=xyz.device)
+    offsets = torch.empty(L * B * N + 1, dtype=torch.int64, device=xyz.device)
+    _check(load().fp_excl_count(xyz.data_ptr(), B, N, thr2.data_ptr(), L, offsets.data_ptr(), ws.data_ptr(),
+                                ws.numel(), _stream()), "fp_excl_count")
+    total = int(offsets[-1].item())
+    entries = torch.empty(max(total, 1), dtype=torch.int32, device=xyz.device)
+    _check(load().fp_excl_fill(xyz.data_ptr(), B, N, thr2.data_ptr(), L, offsets.data_ptr(), entries.data_ptr(),
+                               total, ws.data_ptr(), ws.numel(), _stream()), "fp_excl_fill")
+    return offsets, entries[:total]
+
+
+def ball_query_lists(offsets: torch.Tensor, entries: torch.Tensor, B: int, N: int, L: int, level: int,
+                     center_idx: torch.Tensor, k: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Ball query by lookup in exclusion lists: (idx [B][M][k] int32, cnt [B][M] int32)."""
+    if not (center_idx.is_cuda and center_idx.dtype == torch.int32 and center_idx.dim() == 2
+            and center_idx.shape[0] == B and center_idx.is_contiguous()):
+        raise ValueError("center_idx must be a contiguous CUDA int32 tensor [B][M]")
+    if offsets.numel() != L * B * N + 1 or offsets.dtype != torch.int64 or entries.dtype != torch.int32:
+        raise ValueError("offsets / entries do not belong to lists of this shape")
+    M = int(center_idx.shape[1])
+    idx = torch.empty((B, M, k), dtype=torch.int32, device=center_idx.device)
+    cnt = torch.empty((B, M), dtype=torch.int32, device=center_idx.device)
+    ent = entries if entries.numel() > 0 else torch.zeros(1, dtype=torch.int32, device=center_idx.device)
+    _check(load().fp_ball_query_lists(offsets.data_ptr(), ent.data_ptr(), B, N, level, L, center_idx.data_ptr(),
+                                      M, k, idx.data_ptr(), cnt.data_ptr(), _stream()), "fp_ball_query_lists")
+    return idx, cnt
 
 
 def gather_xyz(xyz: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:

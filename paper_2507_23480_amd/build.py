@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfastpoint_hip.so")
-SOURCES = ["sampler.hip", "ball_query.hip", "knn.hip", "abi.hip"]
+SOURCES = ["sampler.hip", "ball_query.hip", "knn.hip", "excl_lists.hip", "abi.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", *os.environ.get("FASTPOINT_EXTRA_FLAGS", "").split(), "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]

@@ -301,6 +301,56 @@ fp_status fp_knn(const float* xyz, int32_t B, int32_t N, const int32_t* sample_i
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }
 
+static bool excl_shape_ok(int32_t B, int32_t N, int32_t L)
+{
+    if (B < 1 || N < 1 || L < 1 || L > FP_EXCL_MAX_LEVELS || B > 65535) return false;
+    return (int64_t)L * B * N <= ((int64_t)1 << 40) && (int64_t)B * N <= ((int64_t)1 << 33);
+}
+
+size_t fp_excl_workspace_bytes(int32_t B, int32_t N, int32_t L)
+{
+    if (!excl_shape_ok(B, N, L)) return 0;
+    return (size_t)excl_layout(B, N, L).bytes;
+}
+
+fp_status fp_excl_count(const float* xyz, int32_t B, int32_t N, const float* thr2, int32_t L,
+                        int64_t* offsets, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!xyz || !thr2 || !offsets) return FP_ERR_NULL;
+    if (!excl_shape_ok(B, N, L)) return FP_ERR_SHAPE;
+    if (!workspace || workspace_bytes < fp_excl_workspace_bytes(B, N, L) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return FP_ERR_WORKSPACE;
+    hipError_t err = launch_excl_count(xyz, B, N, thr2, L, offsets, workspace,
+                                       reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
+fp_status fp_excl_fill(const float* xyz, int32_t B, int32_t N, const float* thr2, int32_t L,
+                       const int64_t* offsets, int32_t* entries, int64_t capacity, void* workspace,
+                       size_t workspace_bytes, void* stream)
+{
+    if (!xyz || !thr2 || !offsets || (!entries && capacity > 0)) return FP_ERR_NULL;
+    if (!excl_shape_ok(B, N, L) || capacity < 0) return FP_ERR_SHAPE;
+    if (!workspace || workspace_bytes < fp_excl_workspace_bytes(B, N, L) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return FP_ERR_WORKSPACE;
+    hipError_t err = launch_excl_fill(xyz, B, N, thr2, L, offsets, entries, capacity, workspace,
+                                      reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
+fp_status fp_ball_query_lists(const int64_t* offsets, const int32_t* entries, int32_t B, int32_t N,
+                              int32_t level, int32_t L, const int32_t* center_idx, int32_t M, int32_t k,
+                              int32_t* out_idx, int32_t* out_cnt, void* stream)
+{
+    if (!offsets || !entries || !center_idx || !out_idx) return FP_ERR_NULL;
+    if (!excl_shape_ok(B, N, L) || level < 0 || level >= L || M < 0 || k < 1) return FP_ERR_SHAPE;
+    hipError_t err = launch_bq_lists(offsets, entries, B, N, level, center_idx, M, k, out_idx, out_cnt,
+                                     reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
 fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N, const int32_t* idx, int32_t M,
                         float* out_xyz, void* stream)
 {

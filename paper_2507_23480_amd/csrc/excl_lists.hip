@@ -1,0 +1,623 @@
+// Exclusion lists of FastPoint (arXiv 2507.23480) as a data structure of their own, for gfx950:
+// Algorithm 2 lines 15-22 (Section 4.1 step 2) -- for every level l and every point i the points
+// j with dist2(P_i, P_j) < R_l^2, one distance per pair serving all levels -- plus the extra list
+// at the ball-query radius of Section 4.2, and the ball query that is a lookup in such a list.
+//
+// The paper builds the lists from all N^2 pairs.  Here a uniform grid with cells at least as
+// wide as the largest radius of the cloud limits the pairs that are examined to the 27 cells
+// around a point; the lists that come out are those of the all-pairs loop, in its order
+// (ascending j).
+//
+//   grid_*        bounding box, cell size and dimensions per cloud, points counted and scattered
+//                 into cell order (x, y, z and the original index as one 16-byte record)
+//   excl_count    one wave per point: the 9 runs of 3 x-adjacent cells are contiguous in cell
+//                 order; 64 candidates per pass, one distance each, compared with every level;
+//                 lane l keeps the size of the level-l list
+//   scan_*        sizes -> row offsets (64-bit, in place)
+//   excl_fill     one wave per point: the hits at the largest radius are collected in LDS, sorted
+//                 by index (bitonic network, one wave, no barriers), then walked in order; each
+//                 level keeps the members below its own radius (ballot compaction keeps the
+//                 order).  A point with more hits than the LDS buffer holds scans all N points
+//                 in index order instead, which needs no sort.
+//   bq_lists      first k members of a row, padded with the first
+//
+// Squared distances are evaluated as ((dx*dx)+(dy*dy))+(dz*dz), every operation rounded on its
+// own; the file is compiled with -ffp-contract=off and without packed fp32 instructions.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.h"
+
+#pragma clang fp contract(off)
+
+namespace fastpoint {
+namespace {
+
+constexpr int kWaves = 4;              // waves (= points) per workgroup of the list kernels
+constexpr int kSortCap = 2048;         // hits at the largest radius that one wave sorts in LDS
+constexpr int kScanBlock = 2048;       // elements per workgroup of the offset scan (256 threads x 8)
+constexpr float kCellSlack = 1.001f;   // cell width = largest radius x this (absorbs the rounding of
+                                       // the cell coordinate, at most 1024 cells per axis)
+
+__device__ __forceinline__ float dist2(float ax, float ay, float az, float bx, float by, float bz)
+{
+    float dx = ax - bx;
+    float dy = ay - by;
+    float dz = az - bz;
+    float t = dx * dx;
+    t = t + dy * dy;
+    t = t + dz * dz;
+    return t;
+}
+
+__device__ __forceinline__ int lanes_below(uint64_t mask)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+__device__ __forceinline__ uint32_t rdlane(uint32_t v, int l)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, l);
+}
+__device__ __forceinline__ float rdlane_f(float v, int l)
+{
+    return __uint_as_float(rdlane(__float_as_uint(v), l));
+}
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// order-preserving map of binary32 to uint32 (for atomicMin / atomicMax on coordinates)
+__device__ __forceinline__ uint32_t f2ord(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ord2f(uint32_t o)
+{
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
+}
+
+__device__ __forceinline__ int cell_coord(float x, float lo, float inv_h, int dim)
+{
+    int c = (int)((x - lo) * inv_h);
+    c = c < 0 ? 0 : c;
+    return c > dim - 1 ? dim - 1 : c;
+}
+
+// ----------------------------------------------------------------------------- grid
+__global__ void grid_init_kernel(ExclGrid* gp, int B, int32_t* cell_cnt, int64_t ncnt)
+{
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    if (t < B) {
+        gp[t].lo[0] = gp[t].lo[1] = gp[t].lo[2] = 0xFFFFFFFFu;
+        gp[t].hi[0] = gp[t].hi[1] = gp[t].hi[2] = 0u;
+    }
+    for (; t < ncnt; t += stride) cell_cnt[t] = 0;
+}
+
+__global__ __launch_bounds__(256) void grid_bounds_kernel(const float* __restrict__ xyz, int N, ExclGrid* gp)
+{
+    const int b = (int)blockIdx.y;
+    const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
+    uint32_t lo[3] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu}, hi[3] = {0u, 0u, 0u};
+    for (int i = (int)(blockIdx.x * 256 + threadIdx.x); i < N; i += (int)gridDim.x * 256) {
+#pragma unroll
+        for (int a = 0; a < 3; ++a) {
+            const uint32_t o = f2ord(cloud[(int64_t)i * 3 + a]);
+            lo[a] = min(lo[a], o);
+            hi[a] = max(hi[a], o);
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        for (int s = 32; s > 0; s >>= 1) {
+            lo[a] = min(lo[a], (uint32_t)__shfl_xor((int)lo[a], s, 64));
+            hi[a] = max(hi[a], (uint32_t)__shfl_xor((int)hi[a], s, 64));
+        }
+        if ((threadIdx.x & 63) == 0) {
+            atomicMin(&gp[b].lo[a], lo[a]);
+            atomicMax(&gp[b].hi[a], hi[a]);
+        }
+    }
+}
+
+// One thread per cloud: the largest radius, the cell width and the grid dimensions.
+__global__ void grid_setup_kernel(ExclGrid* gp, int B, const float* __restrict__ thr2, int L, int maxcells)
+{
+    const int b = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (b >= B) return;
+    ExclGrid g = gp[b];
+    float rmax2 = 0.0f;
+    int lmax = 0;
+    for (int l = 0; l < L; ++l) {
+        const float t = thr2[(int64_t)b * L + l];
+        if (t > rmax2) {            // NaN and values <= 0 never win
+            rmax2 = t;
+            lmax = l;
+        }
+    }
+    float ext[3];
+    for (int a = 0; a < 3; ++a) {
+        g.origin[a] = ord2f(g.lo[a]);
+        ext[a] = ord2f(g.hi[a]) - g.origin[a];
+        if (!(ext[a] >= 0.0f)) ext[a] = 0.0f;
+    }
+    float h = sqrtf(rmax2) * kCellSlack;
+    const float emax = fmaxf(ext[0], fmaxf(ext[1], ext[2]));
+    if (!(h > emax * (1.0f / 1024.0f))) h = emax * (1.0f / 1024.0f);      // at most 1024 cells per axis
+    if (!(h > 0.0f)) h = 1.0f;                                             // all points coincide, radius 0
+    int dim[3];
+    for (int it = 0; it < 200; ++it) {
+        int64_t cells = 1;
+        for (int a = 0; a < 3; ++a) {
+            const float q = ext[a] / h;
+            dim[a] = q < 1023.0f ? (int)q + 1 : 1024;
+            cells *= dim[a];
+        }
+        if (cells <= maxcells) break;
+        h = h * 1.26f;
+    }
+    if ((int64_t)dim[0] * dim[1] * dim[2] > maxcells) dim[0] = dim[1] = dim[2] = 1;   // h overflowed
+    g.inv_h = 1.0f / h;
+    if (!(g.inv_h > 0.0f)) {         // h = +inf: one cell
+        g.inv_h = 0.0f;
+        dim[0] = dim[1] = dim[2] = 1;
+    }
+    g.dim[0] = dim[0];
+    g.dim[1] = dim[1];
+    g.dim[2] = dim[2];
+    g.ncells = dim[0] * dim[1] * dim[2];
+    g.rmax2 = rmax2;
+    g.lmax = lmax;
+    gp[b] = g;
+}
+
+__device__ __forceinline__ int cell_of(const ExclGrid& g, float x, float y, float z, int& cx, int& cy, int& cz)
+{
+    cx = cell_coord(x, g.origin[0], g.inv_h, g.dim[0]);
+    cy = cell_coord(y, g.origin[1], g.inv_h, g.dim[1]);
+    cz = cell_coord(z, g.origin[2], g.inv_h, g.dim[2]);
+    return (cz * g.dim[1] + cy) * g.dim[0] + cx;
+}
+
+__global__ __launch_bounds__(256) void grid_count_kernel(const float* __restrict__ xyz, int N,
+                                                         const ExclGrid* __restrict__ gp, int32_t* cell_cnt,
+                                                         int maxcells)
+{
+    const int b = (int)blockIdx.y;
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (i >= N) return;
+    const ExclGrid g = gp[b];
+    const float* p = xyz + ((int64_t)b * N + i) * 3;
+    int cx, cy, cz;
+    const int c = cell_of(g, p[0], p[1], p[2], cx, cy, cz);
+    atomicAdd(&cell_cnt[(int64_t)b * maxcells + c], 1);
+}
+
+// One workgroup per cloud: cell_start = exclusive scan of the cell counts; the counts become
+// the scatter cursors.
+__global__ __launch_bounds__(1024) void grid_scan_kernel(const ExclGrid* __restrict__ gp, int32_t* cell_cnt,
+                                                         int32_t* cell_start, int maxcells)
+{
+    __shared__ int32_t wsum[16];
+    __shared__ int32_t carry_s;
+    const int b = (int)blockIdx.x;
+    const int ncells = gp[b].ncells;
+    int32_t* cnt = cell_cnt + (int64_t)b * maxcells;
+    int32_t* st = cell_start + (int64_t)b * (maxcells + 1);
+    const int tid = (int)threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int base = 0; base < ncells; base += 1024 * 8) {
+        int v[8];
+        int tsum = 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = base + tid * 8 + u;
+            v[u] = c < ncells ? cnt[c] : 0;
+            tsum += v[u];
+        }
+        int incl = tsum;
+        for (int s = 1; s < 64; s <<= 1) {
+            const int up = __shfl_up(incl, s, 64);
+            if (lane >= s) incl += up;
+        }
+        if (lane == 63) wsum[w] = incl;
+        __syncthreads();
+        int woff = 0;
+        for (int k = 0; k < 16; ++k) woff += (k < w) ? wsum[k] : 0;
+        int total = 0;
+        for (int k = 0; k < 16; ++k) total += wsum[k];
+        const int carry = carry_s;
+        int run = carry + woff + incl - tsum;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int c = base + tid * 8 + u;
+            if (c < ncells) {
+                st[c] = run;
+                cnt[c] = run;          // cursor of the scatter
+            }
+            run += v[u];
+        }
+        __syncthreads();
+        if (tid == 0) carry_s = carry + total;
+        __syncthreads();
+    }
+    if (tid == 0) st[ncells] = carry_s;
+}
+
+__global__ __launch_bounds__(256) void grid_scatter_kernel(const float* __restrict__ xyz, int N,
+                                                           const ExclGrid* __restrict__ gp, int32_t* cell_cur,
+                                                           float4* __restrict__ sorted, int maxcells)
+{
+    const int b = (int)blockIdx.y;
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (i >= N) return;
+    const ExclGrid g = gp[b];
+    const float* p = xyz + ((int64_t)b * N + i) * 3;
+    const float x = p[0], y = p[1], z = p[2];
+    int cx, cy, cz;
+    const int c = cell_of(g, x, y, z, cx, cy, cz);
+    const int pos = atomicAdd(&cell_cur[(int64_t)b * maxcells + c], 1);
+    sorted[(int64_t)b * N + pos] = make_float4(x, y, z, __int_as_float(i));
+}
+
+// ------------------------------------------------------------------ walking the 27 cells
+// Calls f(record, valid) for every point of the 27 cells around (cx, cy, cz), 64 per pass;
+// all lanes take part in every call.
+template <typename F>
+__device__ __forceinline__ void for_neighbours(const ExclGrid& g, const int32_t* __restrict__ st,
+                                               const float4* __restrict__ sorted, int cx, int cy, int cz,
+                                               int lane, F f)
+{
+    const int x0 = cx > 0 ? cx - 1 : 0;
+    const int x1 = cx < g.dim[0] - 1 ? cx + 1 : g.dim[0] - 1;
+    for (int dz = -1; dz <= 1; ++dz) {
+        const int z = cz + dz;
+        if (z < 0 || z >= g.dim[2]) continue;
+        for (int dy = -1; dy <= 1; ++dy) {
+            const int y = cy + dy;
+            if (y < 0 || y >= g.dim[1]) continue;
+            const int c0 = (z * g.dim[1] + y) * g.dim[0] + x0;
+            const int begin = uni(st[c0]);
+            const int end = uni(st[c0 + (x1 - x0) + 1]);
+            for (int t0 = begin; t0 < end; t0 += 64) {
+                const int t = t0 + lane;
+                const bool valid = t < end;
+                const float4 r = sorted[valid ? t : begin];
+                f(r, valid);
+            }
+        }
+    }
+}
+
+// Pass 1: lane l of the point's wave ends up with the size of the level-l list.
+__global__ __launch_bounds__(kWaves * 64) void excl_count_kernel(
+    const float* __restrict__ xyz, int B, int N, const float* __restrict__ thr2, int L,
+    int64_t* __restrict__ offsets, const ExclGrid* __restrict__ gp, const int32_t* __restrict__ cell_start,
+    const float4* __restrict__ sorted, int maxcells)
+{
+    const int b = (int)blockIdx.y;
+    const int lane = (int)threadIdx.x & 63;
+    const int i = uni((int)blockIdx.x * kWaves + ((int)threadIdx.x >> 6));
+    if (i >= N) return;
+    const ExclGrid g = gp[b];
+    const float* p = xyz + ((int64_t)b * N + i) * 3;
+    const float px = p[0], py = p[1], pz = p[2];
+    int cx, cy, cz;
+    cell_of(g, px, py, pz, cx, cy, cz);
+    const float mythr = lane < L ? thr2[(int64_t)b * L + lane] : 0.0f;
+    int mycnt = 0;
+    const float rmax2 = g.rmax2;
+    for_neighbours(g, cell_start + (int64_t)b * (maxcells + 1), sorted + (int64_t)b * N, cx, cy, cz, lane,
+                   [&](const float4& r, bool valid) {
+                       const float d = dist2(px, py, pz, r.x, r.y, r.z);
+                       if (__builtin_amdgcn_ballot_w64(valid && d < rmax2) == 0) return;
+                       for (int l = 0; l < L; ++l) {
+                           const float t = rdlane_f(mythr, l);
+                           const int pc = __builtin_popcountll(__builtin_amdgcn_ballot_w64(valid && d < t));
+                           mycnt += lane == l ? pc : 0;
+                       }
+                   });
+    if (lane < L) offsets[1 + ((int64_t)lane * B + b) * N + i] = mycnt;
+}
+
+// ----------------------------------------------------------- sizes -> offsets (in place)
+__global__ __launch_bounds__(256) void scan_blocks_kernel(int64_t* __restrict__ v, int64_t count,
+                                                          int64_t* __restrict__ totals)
+{
+    __shared__ int64_t wsum[4];
+    const int tid = (int)threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t base = (int64_t)blockIdx.x * kScanBlock + tid * 8;
+    int64_t e[8];
+    int64_t tsum = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        e[u] = base + u < count ? v[base + u] : 0;
+        tsum += e[u];
+    }
+    int64_t incl = tsum;
+    for (int s = 1; s < 64; s <<= 1) {
+        const int64_t up = __shfl_up(incl, s, 64);
+        if (lane >= s) incl += up;
+    }
+    if (lane == 63) wsum[w] = incl;
+    __syncthreads();
+    int64_t woff = 0;
+    for (int k = 0; k < 4; ++k) woff += (k < w) ? wsum[k] : 0;
+    int64_t run = woff + incl - tsum;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        run += e[u];
+        if (base + u < count) v[base + u] = run;            // inclusive within the block
+    }
+    if (tid == 255) totals[blockIdx.x] = run;
+}
+
+__global__ __launch_bounds__(1024) void scan_totals_kernel(int64_t* __restrict__ totals, int64_t nblk)
+{
+    __shared__ int64_t wsum[16];
+    __shared__ int64_t carry_s;
+    const int tid = (int)threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < nblk; base += 1024) {
+        const int64_t mine = base + tid < nblk ? totals[base + tid] : 0;
+        int64_t incl = mine;
+        for (int s = 1; s < 64; s <<= 1) {
+            const int64_t up = __shfl_up(incl, s, 64);
+            if (lane >= s) incl += up;
+        }
+        if (lane == 63) wsum[w] = incl;
+        __syncthreads();
+        int64_t woff = 0, total = 0;
+        for (int k = 0; k < 16; ++k) {
+            woff += (k < w) ? wsum[k] : 0;
+            total += wsum[k];
+        }
+        const int64_t carry = carry_s;
+        if (base + tid < nblk) totals[base + tid] = carry + woff + incl - mine;    // exclusive
+        __syncthreads();
+        if (tid == 0) carry_s = carry + total;
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void scan_add_kernel(int64_t* __restrict__ v, int64_t count,
+                                                       const int64_t* __restrict__ totals)
+{
+    const int64_t add = totals[blockIdx.x];
+    const int64_t base = (int64_t)blockIdx.x * kScanBlock;
+    for (int u = (int)threadIdx.x; u < kScanBlock; u += 256)
+        if (base + u < count) v[base + u] += add;
+}
+
+__global__ void zero_first_kernel(int64_t* p) { *p = 0; }
+
+// ------------------------------------------------------------------------- pass 2
+// Level cursors: lane l holds how many members of the level-l row are written already.
+struct Emit {
+    int64_t mybase;      // lane l: start of the level-l row
+    int mycur;           // lane l: members written
+    float mythr;
+    int L;
+    int32_t* entries;
+    int64_t capacity;
+    // j (valid lanes, ascending over the lanes) at squared distance d
+    __device__ __forceinline__ void operator()(int j, float d, bool valid, int lane)
+    {
+        for (int l = 0; l < L; ++l) {
+            const float t = rdlane_f(mythr, l);
+            const bool hit = valid && d < t;
+            const uint64_t mk = __builtin_amdgcn_ballot_w64(hit);
+            if (mk == 0) continue;
+            const uint32_t blo = rdlane((uint32_t)mybase, l), bhi = rdlane((uint32_t)(mybase >> 32), l);
+            const int64_t at = (int64_t)(((uint64_t)bhi << 32) | blo) + (int)rdlane((uint32_t)mycur, l) +
+                               lanes_below(mk);
+            if (hit && at < capacity) entries[at] = j;
+            mycur += lane == l ? __builtin_popcountll(mk) : 0;
+        }
+    }
+};
+
+// ascending bitonic sort of buf[0 .. n2) (n2 a power of two >= 64) by one wave
+__device__ __forceinline__ void wave_sort(uint32_t* buf, int n2, int lane)
+{
+    for (int k = 2; k <= n2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = lane; t < (n2 >> 1); t += 64) {
+                // t-th compare-exchange of this step: lower partner index
+                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                const int hi = lo | j;
+                const uint32_t a = buf[lo], b = buf[hi];
+                const bool up = (lo & k) == 0;
+                if ((a > b) == up) {
+                    buf[lo] = b;
+                    buf[hi] = a;
+                }
+            }
+            // one wave: its LDS operations execute in program order; keep the compiler from
+            // moving the next step's reads above these writes
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    }
+}
+
+__global__ __launch_bounds__(kWaves * 64) void excl_fill_kernel(
+    const float* __restrict__ xyz, int B, int N, const float* __restrict__ thr2, int L,
+    const int64_t* __restrict__ offsets, int32_t* __restrict__ entries, int64_t capacity,
+    const ExclGrid* __restrict__ gp, const int32_t* __restrict__ cell_start, const float4* __restrict__ sorted,
+    int maxcells)
+{
+    __shared__ uint32_t sortbuf[kWaves][kSortCap];
+    const int b = (int)blockIdx.y;
+    const int lane = (int)threadIdx.x & 63;
+    const int w = uni((int)threadIdx.x >> 6);
+    const int i = uni((int)blockIdx.x * kWaves + w);
+    if (i >= N) return;
+    const ExclGrid g = gp[b];
+    const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
+    const float px = cloud[(int64_t)i * 3 + 0], py = cloud[(int64_t)i * 3 + 1], pz = cloud[(int64_t)i * 3 + 2];
+    Emit em;
+    em.L = L;
+    em.entries = entries;
+    em.capacity = capacity;
+    em.mythr = lane < L ? thr2[(int64_t)b * L + lane] : 0.0f;
+    em.mybase = lane < L ? offsets[((int64_t)lane * B + b) * N + i] : 0;
+    em.mycur = 0;
+    const int64_t rmaxrow = ((int64_t)g.lmax * B + b) * N + i;
+    const int64_t hits64 = offsets[rmaxrow + 1] - offsets[rmaxrow];
+    if (hits64 <= 0) return;                 // rows of smaller radii are empty as well
+    if (hits64 <= kSortCap) {
+        const int H = (int)hits64;
+        uint32_t* buf = sortbuf[w];
+        int cx, cy, cz;
+        cell_of(g, px, py, pz, cx, cy, cz);
+        int got = 0;
+        const float rmax2 = g.rmax2;
+        for_neighbours(g, cell_start + (int64_t)b * (maxcells + 1), sorted + (int64_t)b * N, cx, cy, cz, lane,
+                       [&](const float4& r, bool valid) {
+                           const bool hit = valid && dist2(px, py, pz, r.x, r.y, r.z) < rmax2;
+                           const uint64_t mk = __builtin_amdgcn_ballot_w64(hit);
+                           const int at = got + lanes_below(mk);
+                           if (hit && at < kSortCap) buf[at] = (uint32_t)__float_as_int(r.w);
+                           got += __builtin_popcountll(mk);
+                       });
+        int n2 = 64;
+        while (n2 < H) n2 <<= 1;
+        for (int t = H + lane; t < n2; t += 64) buf[t] = 0xFFFFFFFFu;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        wave_sort(buf, n2, lane);
+        for (int t0 = 0; t0 < H; t0 += 64) {
+            const bool valid = t0 + lane < H;
+            const int j = valid ? (int)buf[t0 + lane] : i;
+            const float d = dist2(px, py, pz, cloud[(int64_t)j * 3 + 0], cloud[(int64_t)j * 3 + 1],
+                                  cloud[(int64_t)j * 3 + 2]);
+            em(j, d, valid, lane);
+        }
+    } else {
+        for (int j0 = 0; j0 < N; j0 += 64) {
+            const int j = j0 + lane;
+            const bool valid = j < N;
+            const int jj = valid ? j : i;
+            const float d = dist2(px, py, pz, cloud[(int64_t)jj * 3 + 0], cloud[(int64_t)jj * 3 + 1],
+                                  cloud[(int64_t)jj * 3 + 2]);
+            em(j, d, valid, lane);
+        }
+    }
+}
+
+// Ball query by lookup: one wave per centre.
+__global__ __launch_bounds__(256) void bq_lists_kernel(const int64_t* __restrict__ offsets,
+                                                       const int32_t* __restrict__ entries, int B, int N, int level,
+                                                       const int32_t* __restrict__ center_idx, int M, int k,
+                                                       int32_t* __restrict__ out_idx, int32_t* __restrict__ out_cnt)
+{
+    const int b = (int)blockIdx.y;
+    const int lane = (int)threadIdx.x & 63;
+    const int q = uni((int)blockIdx.x * 4 + ((int)threadIdx.x >> 6));
+    if (q >= M) return;
+    const int c = uni(center_idx[(int64_t)b * M + q]);
+    int32_t* row = out_idx + ((int64_t)b * M + q) * k;
+    int cnt = 0;
+    int64_t begin = 0;
+    if (c >= 0 && c < N) {
+        const int64_t r = ((int64_t)level * B + b) * N + c;
+        begin = offsets[r];
+        const int64_t len = offsets[r + 1] - begin;
+        cnt = len < k ? (int)len : k;
+    }
+    const int first = cnt > 0 ? entries[begin] : -1;
+    for (int t = lane; t < k; t += 64) row[t] = t < cnt ? entries[begin + t] : first;
+    if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = cnt;
+}
+
+}  // namespace
+
+ExclLayout excl_layout(int B, int N, int L)
+{
+    ExclLayout lay;
+    int64_t mc = N;
+    if (mc < 64) mc = 64;
+    if (mc > ((int64_t)1 << 21)) mc = (int64_t)1 << 21;
+    lay.maxcells = (int)mc;
+    auto up = [](int64_t v) { return (v + 255) / 256 * 256; };
+    int64_t at = 0;
+    lay.grid_off = at;
+    at += up((int64_t)B * (int64_t)sizeof(ExclGrid));
+    lay.cnt_off = at;
+    at += up((int64_t)B * mc * 4);
+    lay.start_off = at;
+    at += up((int64_t)B * (mc + 1) * 4);
+    lay.sorted_off = at;
+    at += up((int64_t)B * N * 16);
+    lay.totals_off = at;
+    const int64_t rows = (int64_t)L * B * N;
+    at += up(((rows + kScanBlock - 1) / kScanBlock + 1) * 8);
+    lay.bytes = at;
+    return lay;
+}
+
+hipError_t launch_excl_count(const float* xyz, int B, int N, const float* thr2, int L, int64_t* offsets,
+                             void* workspace, hipStream_t stream)
+{
+    const ExclLayout lay = excl_layout(B, N, L);
+    unsigned char* base = reinterpret_cast<unsigned char*>(workspace);
+    ExclGrid* gp = reinterpret_cast<ExclGrid*>(base + lay.grid_off);
+    int32_t* cnt = reinterpret_cast<int32_t*>(base + lay.cnt_off);
+    int32_t* st = reinterpret_cast<int32_t*>(base + lay.start_off);
+    float4* sorted = reinterpret_cast<float4*>(base + lay.sorted_off);
+    int64_t* totals = reinterpret_cast<int64_t*>(base + lay.totals_off);
+    const int64_t ncnt = (int64_t)B * lay.maxcells;
+    int initblocks = (int)((ncnt + 255) / 256);
+    if (initblocks > 2048) initblocks = 2048;
+    hipLaunchKernelGGL(grid_init_kernel, dim3(initblocks), dim3(256), 0, stream, gp, B, cnt, ncnt);
+    int bblocks = (N + 255) / 256;
+    if (bblocks > 256) bblocks = 256;
+    hipLaunchKernelGGL(grid_bounds_kernel, dim3(bblocks, B), dim3(256), 0, stream, xyz, N, gp);
+    hipLaunchKernelGGL(grid_setup_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, gp, B, thr2, L, lay.maxcells);
+    const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
+    hipLaunchKernelGGL(grid_count_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, lay.maxcells);
+    hipLaunchKernelGGL(grid_scan_kernel, dim3(B), dim3(1024), 0, stream, gp, cnt, st, lay.maxcells);
+    hipLaunchKernelGGL(grid_scatter_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, sorted, lay.maxcells);
+    const dim3 wgrid((unsigned)((N + kWaves - 1) / kWaves), (unsigned)B);
+    hipLaunchKernelGGL(excl_count_kernel, wgrid, dim3(kWaves * 64), 0, stream, xyz, B, N, thr2, L, offsets, gp, st,
+                       sorted, lay.maxcells);
+    const int64_t rows = (int64_t)L * B * N;
+    const int64_t nblk = (rows + kScanBlock - 1) / kScanBlock;
+    hipLaunchKernelGGL(zero_first_kernel, dim3(1), dim3(1), 0, stream, offsets);
+    hipLaunchKernelGGL(scan_blocks_kernel, dim3((unsigned)nblk), dim3(256), 0, stream, offsets + 1, rows, totals);
+    hipLaunchKernelGGL(scan_totals_kernel, dim3(1), dim3(1024), 0, stream, totals, nblk);
+    hipLaunchKernelGGL(scan_add_kernel, dim3((unsigned)nblk), dim3(256), 0, stream, offsets + 1, rows, totals);
+    return hipGetLastError();
+}
+
+hipError_t launch_excl_fill(const float* xyz, int B, int N, const float* thr2, int L, const int64_t* offsets,
+                            int32_t* entries, int64_t capacity, void* workspace, hipStream_t stream)
+{
+    const ExclLayout lay = excl_layout(B, N, L);
+    unsigned char* base = reinterpret_cast<unsigned char*>(workspace);
+    const ExclGrid* gp = reinterpret_cast<const ExclGrid*>(base + lay.grid_off);
+    const int32_t* st = reinterpret_cast<const int32_t*>(base + lay.start_off);
+    const float4* sorted = reinterpret_cast<const float4*>(base + lay.sorted_off);
+    const dim3 wgrid((unsigned)((N + kWaves - 1) / kWaves), (unsigned)B);
+    hipLaunchKernelGGL(excl_fill_kernel, wgrid, dim3(kWaves * 64), 0, stream, xyz, B, N, thr2, L, offsets, entries,
+                       capacity, gp, st, sorted, lay.maxcells);
+    return hipGetLastError();
+}
+
+hipError_t launch_bq_lists(const int64_t* offsets, const int32_t* entries, int B, int N, int level,
+                           const int32_t* center_idx, int M, int k, int32_t* out_idx, int32_t* out_cnt,
+                           hipStream_t stream)
+{
+    if (M == 0) return hipSuccess;
+    hipLaunchKernelGGL(bq_lists_kernel, dim3((unsigned)((M + 3) / 4), (unsigned)B), dim3(256), 0, stream, offsets,
+                       entries, B, N, level, center_idx, M, k, out_idx, out_cnt);
+    return hipGetLastError();
+}
+
+}  // namespace fastpoint

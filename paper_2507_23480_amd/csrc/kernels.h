@@ -75,5 +75,31 @@ hipError_t launch_knn(const float* xyz, int B, int N, const int32_t* sample_idx,
                       int32_t* count, int32_t* list, int32_t* out_deferred, hipStream_t stream);
 hipError_t launch_bq_header(void* cache, const BqHeader& h, hipStream_t stream);
 
+// Uniform grid of one cloud for the exclusion-list kernels (device memory, in the workspace).
+struct ExclGrid {
+    uint32_t lo[3], hi[3];   // bounding box as order-preserving integers (filled by atomics)
+    float origin[3];         // lower corner
+    float inv_h;             // 1 / cell width
+    int32_t dim[3];          // cells per axis
+    int32_t ncells;
+    float rmax2;             // largest squared radius of the cloud
+    int32_t lmax;            // its level
+};
+
+// Where the parts of an exclusion-list workspace lie (byte offsets).
+struct ExclLayout {
+    int maxcells;            // cells a cloud's grid may have
+    int64_t grid_off, cnt_off, start_off, sorted_off, totals_off, bytes;
+};
+
+ExclLayout excl_layout(int B, int N, int L);
+hipError_t launch_excl_count(const float* xyz, int B, int N, const float* thr2, int L, int64_t* offsets,
+                             void* workspace, hipStream_t stream);
+hipError_t launch_excl_fill(const float* xyz, int B, int N, const float* thr2, int L, const int64_t* offsets,
+                            int32_t* entries, int64_t capacity, void* workspace, hipStream_t stream);
+hipError_t launch_bq_lists(const int64_t* offsets, const int32_t* entries, int B, int N, int level,
+                           const int32_t* center_idx, int M, int k, int32_t* out_idx, int32_t* out_cnt,
+                           hipStream_t stream);
+
 }  // namespace fastpoint
 #endif

@@ -1,0 +1,219 @@
+"""GPU parity of the exclusion lists (Alg. 2 lines 15-22 with the extra ball-query level of
+Section 4.2) and of the ball query by lookup, through the C ABI, against the CPU oracle:
+offsets and members bit-exact (the lists are index sets decided by binary32 comparisons)."""
+import ctypes
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2507_23480_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fp():
+    from paper_2507_23480_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    binding.set_wg_per_cloud(0)
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def oracle_rows(batch, thr):
+    """Offsets and members in the library's row order (level, cloud, point)."""
+    B, N = batch.shape[0], batch.shape[1]
+    L = thr.shape[1]
+    with ThreadPoolExecutor(max_workers=8) as ex:            # ctypes calls drop the GIL
+        per = list(ex.map(lambda b: ref.excl_lists(batch[b], thr[b]), range(B)))
+    sizes = np.zeros(L * B * N, dtype=np.int64)
+    chunks = []
+    for l in range(L):
+        for b in range(B):
+            off, ent = per[b]
+            sizes[(l * B + b) * N:(l * B + b + 1) * N] = np.diff(off[l * N:(l + 1) * N + 1])
+            chunks.append(ent[off[l * N]:off[(l + 1) * N]])
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    return offsets, (np.concatenate(chunks) if chunks else np.zeros(0, np.int32))
+
+
+def check_lists(fp, batch, thr):
+    batch = np.ascontiguousarray(batch, dtype=np.float32)
+    thr = np.ascontiguousarray(thr, dtype=np.float32)
+    off, ent = fp.excl_lists(dev(batch), dev(thr))
+    torch.cuda.synchronize()
+    woff, went = oracle_rows(batch, thr)
+    assert np.array_equal(off.cpu().numpy(), woff), "offsets"
+    assert np.array_equal(ent.cpu().numpy(), went), "members"
+    return off, ent
+
+
+def line9():
+    return np.stack([np.arange(9), np.zeros(9), np.zeros(9)], axis=1).astype(np.float32)
+
+
+def test_line_example(fp):
+    check_lists(fp, line9()[None], np.array([[10.0, 2.0, 6.25]]))
+
+
+@pytest.mark.parametrize("N,thr", [(1, [0.5]), (63, [0.1, 0.01]), (64, [0.3]), (65, [0.02, 0.2, 0.07]),
+                                   (300, [0.09, 0.04, 0.01, 0.0025]), (1000, [0.01] * 17),
+                                   (2049, [0.004, 0.001, 0.002, 0.0005, 0.003, 0.00025, 0.0001])])
+def test_uniform_cube(fp, N, thr):
+    say("excl lists N=%d L=%d" % (N, len(thr)))
+    check_lists(fp, inputs.uniform_cube(1200 + N, N)[None], np.array([thr]))
+
+
+def test_batch_with_a_radius_set_per_cloud(fp):
+    batch = np.stack([inputs.uniform_cube(40 + b, 700) * (1.0 + b) for b in range(4)])
+    thr = np.array([[0.02, 0.005], [0.3, 0.0001], [1e-9, 0.05], [0.5, 0.5]], dtype=np.float32)
+    check_lists(fp, batch, thr)
+
+
+def test_ties_and_duplicates(fp):
+    batch = np.stack([inputs.lattice_with_ties(60 + b, 900, 4) for b in range(2)])
+    # radii on attainable squared distances (strict <) and between them
+    check_lists(fp, batch, np.array([[2.0, 1.0, 3.5, 0.5]] * 2))
+
+
+@pytest.mark.parametrize("N", [2048, 2100, 3000])
+def test_radius_beyond_the_cloud(fp, N):
+    # every point is in every list: the rows reach and pass the size one wave sorts in LDS
+    say("excl lists, all points, N=%d" % N)
+    check_lists(fp, inputs.uniform_cube(5, N)[None], np.array([[4.0, 0.01]]))
+
+
+def test_rows_around_the_sort_capacity(fp):
+    # clustered cloud: rows below, at and above the LDS capacity in one call
+    rng = np.random.Generator(np.random.PCG64(12))
+    dense = rng.normal(0.0, 0.01, (2500, 3))
+    sparse = rng.uniform(-1.0, 1.0, (1500, 3))
+    cloud = np.concatenate([dense, sparse]).astype(np.float32)
+    cloud = cloud[rng.permutation(4000)]
+    off, _ = check_lists(fp, cloud[None], np.array([[0.0009, 0.0001, 0.25]]))
+    sizes = np.diff(off.cpu().numpy())
+    assert sizes.max() > 2048 and sizes.min() >= 1
+
+
+def test_empty_levels(fp):
+    thr = np.array([[0.0, -1.0, np.nan, 0.01]], dtype=np.float32)
+    off, ent = check_lists(fp, inputs.uniform_cube(9, 500)[None], thr)
+    assert int(off[3 * 500]) == 0
+    off, ent = check_lists(fp, inputs.uniform_cube(9, 500)[None], np.array([[0.0, np.nan]], dtype=np.float32))
+    assert ent.numel() == 0
+
+
+def test_coincident_points(fp):
+    cloud = np.zeros((300, 3), dtype=np.float32) + np.float32(0.25)
+    check_lists(fp, cloud[None], np.array([[1e-30, 0.0]]))
+
+
+def test_infinite_radius(fp):
+    check_lists(fp, inputs.uniform_cube(3, 400)[None], np.array([[np.inf, 0.01]], dtype=np.float32))
+
+
+def test_fill_respects_capacity(fp):
+    lib = fp.load()
+    cloud = dev(inputs.uniform_cube(21, 800)[None])
+    thr = dev(np.array([[0.05, 0.01]], dtype=np.float32))
+    off, ent = fp.excl_lists(cloud, thr)
+    torch.cuda.synchronize()
+    total = ent.numel()
+    cap = total // 2
+    ws = torch.empty(lib.fp_excl_workspace_bytes(1, 800, 2), dtype=torch.uint8, device="cuda")
+    off2 = torch.empty_like(off)
+    part = torch.full((total,), -5, dtype=torch.int32, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    assert lib.fp_excl_count(cloud.data_ptr(), 1, 800, thr.data_ptr(), 2, off2.data_ptr(), ws.data_ptr(),
+                             ws.numel(), s) == 0
+    assert lib.fp_excl_fill(cloud.data_ptr(), 1, 800, thr.data_ptr(), 2, off2.data_ptr(), part.data_ptr(),
+                            ctypes.c_int64(cap), ws.data_ptr(), ws.numel(), s) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(off2, off)
+    assert torch.equal(part[:cap], ent[:cap]) and bool((part[cap:] == -5).all())
+
+
+def test_argument_checks(fp):
+    lib = fp.load()
+    assert lib.fp_excl_workspace_bytes(1, 100, 18) == 0
+    assert lib.fp_excl_workspace_bytes(0, 100, 2) == 0
+    cloud = dev(inputs.uniform_cube(1, 100)[None])
+    thr = dev(np.array([[0.1]], dtype=np.float32))
+    off = torch.empty(101, dtype=torch.int64, device="cuda")
+    ws = torch.empty(lib.fp_excl_workspace_bytes(1, 100, 1), dtype=torch.uint8, device="cuda")
+    assert lib.fp_excl_count(cloud.data_ptr(), 1, 100, thr.data_ptr(), 1, off.data_ptr(), ws.data_ptr(), 16, None) == -4
+    assert lib.fp_excl_count(None, 1, 100, thr.data_ptr(), 1, off.data_ptr(), ws.data_ptr(), ws.numel(), None) == -1
+    assert lib.fp_excl_count(cloud.data_ptr(), 1, 100, thr.data_ptr(), 0, off.data_ptr(), ws.data_ptr(),
+                             ws.numel(), None) == -2
+
+
+@pytest.mark.parametrize("k", [1, 16, 64])
+def test_lookup_equals_ball_query_for_any_centres(fp, k):
+    # the list at the query radius answers the ball query of ANY centre set, samples or not
+    B, N, M = 3, 1500, 333
+    batch = np.stack([inputs.uniform_cube(80 + b, N) for b in range(B)])
+    radius = 0.11
+    r2 = np.float32(radius) * np.float32(radius)
+    thr = np.array([[0.05, r2]] * B, dtype=np.float32)
+    x = dev(batch)
+    off, ent = fp.excl_lists(x, dev(thr))
+    centres = np.random.Generator(np.random.PCG64(k)).integers(0, N, (B, M)).astype(np.int32)
+    idx, cnt = fp.ball_query_lists(off, ent, B, N, 2, 1, dev(centres), k)
+    bidx, bcnt = fp.ball_query(x, dev(centres), radius, k)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, bidx) and torch.equal(cnt, bcnt)
+    for b in range(B):
+        widx, wcnt = ref.ball_query(batch[b], centres[b], radius, k)
+        assert np.array_equal(idx[b].cpu().numpy(), widx) and np.array_equal(cnt[b].cpu().numpy(), wcnt)
+
+
+def test_lookup_of_empty_rows_and_bad_centres(fp):
+    cloud = inputs.uniform_cube(2, 200)[None]
+    off, ent = fp.excl_lists(dev(cloud), dev(np.array([[0.0, 0.01]], dtype=np.float32)))
+    centres = dev(np.array([[3, -1, 200, 7]], dtype=np.int32))
+    idx, cnt = fp.ball_query_lists(off, ent, 1, 200, 2, 0, centres, 4)
+    torch.cuda.synchronize()
+    assert bool((idx == -1).all()) and bool((cnt == 0).all())
+    idx, cnt = fp.ball_query_lists(off, ent, 1, 200, 2, 1, centres, 4)
+    torch.cuda.synchronize()
+    assert idx[0, 1].tolist() == [-1] * 4 and idx[0, 2].tolist() == [-1] * 4 and cnt[0].tolist()[1:3] == [0, 0]
+    widx, wcnt = ref.ball_query(cloud[0], [3, 7], 0.1, 4)
+    assert idx[0, 0].tolist() == widx[0].tolist() and idx[0, 3].tolist() == widx[1].tolist()
+
+
+@pytest.mark.parametrize("name,clouds", [("C1", 1), ("C2", 4), ("C3", 2)])
+def test_workload_shapes_with_the_thresholds_of_mdps(fp, name, clouds):
+    """Stage 0 of a workload: levels = the nseg thresholds MDPS derived for each cloud (read
+    from the sampler's info records on the device) and the ball-query radius."""
+    from paper_2507_23480_amd import calibration
+    say("excl lists at workload", name)
+    wl = inputs.WORKLOADS[name]
+    st = wl.stages[0]
+    batch = inputs.make_batch(name)[:clouds]
+    x = dev(batch)
+    prm = calibration.params_for(name, 0)
+    _, info = fp.mdps_sample(x, st.n, prm, want_info=True)
+    torch.cuda.synchronize()
+    recs = fp.parse_info(info)
+    thr = np.array([[r.thr2[l] for l in range(prm.nseg)] + [np.float32(st.radius) * np.float32(st.radius)]
+                    for r in recs], dtype=np.float32)
+    off, ent = check_lists(fp, batch, thr)
+    # the extra level answers the stage's ball query for the MDPS samples
+    midx = fp.mdps_sample(x, st.n, prm)
+    idx, cnt = fp.ball_query_lists(off, ent, clouds, wl.N, prm.nseg + 1, prm.nseg, midx, st.k)
+    bidx, bcnt = fp.ball_query(x, midx, st.radius, st.k)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, bidx) and torch.equal(cnt, bcnt)
