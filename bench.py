@@ -271,6 +271,15 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         roof["knn_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": a / HBM_PEAK_GBS, "bytes": byts,
                               "points_searched_by_brute_force": knn["deferred_fraction"]}
+        ex = time_excl_lists(torch, fp, x, sg, infos, midx, mbq)
+        if ex is not None:
+            ms["excl_lists_count"], ms["excl_lists_fill"] = ex["count_ms"], ex["fill_ms"]
+            # the lists have to be written once and the points read once
+            byts = 4.0 * ex["members"] + 8.0 * ex["rows"] + 12.0 * B * N
+            a = byts / ((ex["count_ms"] + ex["fill_ms"]) * 1e-3) / 1e9
+            roof["excl_lists_build"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                        "frac": a / HBM_PEAK_GBS, "bytes": byts, "members": ex["members"],
+                                        "levels": ex["levels"], "lookup_equals_ball_query": ex["lookup_ok"]}
         out["stages"].append({
             "N": N, "n": n, "radius": sg["radius"], "k": k, "plan_G_T_P": list(fp.plan(B, N)),
             "kernel_ms": ms,
@@ -283,6 +292,61 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             "cached_ball_query_equals_brute": cached_equal,
             "roofline": roof})
     return out
+
+
+def time_excl_lists(torch, fp, x, sg, infos, midx, mbq, reps=3):
+    """Exclusion lists of a stage as a data structure (Alg. 2 lines 15-22): one level per MDPS
+    threshold of each cloud plus the ball-query radius; count and fill passes timed apart, and
+    the stage's ball query answered by lookup in the extra level.  Not part of the timed step.
+    Skipped for clouds whose lists would not be built in practice (N above 200 000)."""
+    import numpy as np
+    B, N = x.shape[0], x.shape[1]
+    if N > 200000:
+        return None
+    lib = fp.load()
+    nseg = sg["prm"].nseg
+    r2 = np.float32(sg["radius"]) * np.float32(sg["radius"])
+    thr = torch.tensor([[i.thr2[l] for l in range(nseg)] + [float(r2)] for i in infos],
+                       dtype=torch.float32, device=x.device)
+    L = nseg + 1
+    ws = torch.empty(lib.fp_excl_workspace_bytes(B, N, L), dtype=torch.uint8, device=x.device)
+    off = torch.empty(L * B * N + 1, dtype=torch.int64, device=x.device)
+    st = torch.cuda.current_stream().cuda_stream
+
+    def count():
+        if lib.fp_excl_count(x.data_ptr(), B, N, thr.data_ptr(), L, off.data_ptr(), ws.data_ptr(), ws.numel(), st):
+            raise RuntimeError("fp_excl_count failed")
+
+    def timed(fn):
+        best = None
+        for _ in range(reps):
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            t = a.elapsed_time(b)
+            best = t if best is None else min(best, t)
+        return best
+
+    count()
+    torch.cuda.synchronize()
+    total = int(off[-1].item())
+    ent = torch.empty(max(total, 1), dtype=torch.int32, device=x.device)
+
+    def fill():
+        if lib.fp_excl_fill(x.data_ptr(), B, N, thr.data_ptr(), L, off.data_ptr(), ent.data_ptr(), total,
+                            ws.data_ptr(), ws.numel(), st):
+            raise RuntimeError("fp_excl_fill failed")
+
+    res = {"count_ms": timed(count), "fill_ms": timed(fill), "members": total, "rows": L * B * N, "levels": L}
+    idx, cnt = fp.ball_query_lists(off, ent, B, N, L, nseg, midx, sg["k"])
+    torch.cuda.synchronize()
+    res["lookup_ok"] = bool(torch.equal(idx, mbq[0]) and torch.equal(cnt, mbq[1]))
+    if not res["lookup_ok"]:
+        raise RuntimeError("ball query by lookup differs from the cache reader's result")
+    return res
 
 
 def time_knn(torch, fp, x, sg, midx, reps=3):

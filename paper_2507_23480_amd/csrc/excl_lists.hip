@@ -97,6 +97,7 @@ __global__ void grid_init_kernel(ExclGrid* gp, int B, int32_t* cell_cnt, int64_t
 
 __global__ __launch_bounds__(256) void grid_bounds_kernel(const float* __restrict__ xyz, int N, ExclGrid* gp)
 {
+    __shared__ uint32_t slo[4][3], shi[4][3];
     const int b = (int)blockIdx.y;
     const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
     uint32_t lo[3] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu}, hi[3] = {0u, 0u, 0u};
@@ -115,9 +116,15 @@ __global__ __launch_bounds__(256) void grid_bounds_kernel(const float* __restric
             hi[a] = max(hi[a], (uint32_t)__shfl_xor((int)hi[a], s, 64));
         }
         if ((threadIdx.x & 63) == 0) {
-            atomicMin(&gp[b].lo[a], lo[a]);
-            atomicMax(&gp[b].hi[a], hi[a]);
+            slo[threadIdx.x >> 6][a] = lo[a];
+            shi[threadIdx.x >> 6][a] = hi[a];
         }
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {              // one atomic pair per axis and workgroup
+        const int a = (int)threadIdx.x;
+        atomicMin(&gp[b].lo[a], min(min(slo[0][a], slo[1][a]), min(slo[2][a], slo[3][a])));
+        atomicMax(&gp[b].hi[a], max(max(shi[0][a], shi[1][a]), max(shi[2][a], shi[3][a])));
     }
 }
 
@@ -159,7 +166,7 @@ __global__ void grid_setup_kernel(ExclGrid* gp, int B, const float* __restrict__
     }
     if ((int64_t)dim[0] * dim[1] * dim[2] > maxcells) dim[0] = dim[1] = dim[2] = 1;   // h overflowed
     g.inv_h = 1.0f / h;
-    if (!(g.inv_h > 0.0f)) {         // h = +inf: one cell
+    if (!(g.inv_h > 0.0f && g.inv_h < 3.0e38f)) {         // h = +inf or denormal: one cell
         g.inv_h = 0.0f;
         dim[0] = dim[1] = dim[2] = 1;
     }
@@ -264,7 +271,10 @@ __global__ __launch_bounds__(256) void grid_scatter_kernel(const float* __restri
 
 // ------------------------------------------------------------------ walking the 27 cells
 // Calls f(record, valid) for every point of the 27 cells around (cx, cy, cz), 64 per pass;
-// all lanes take part in every call.
+// all lanes take part in every call.  The 9 runs of x-adjacent cells are contiguous in cell
+// order: lanes 0..8 fetch the bounds of one run each, and the runs are then walked as one
+// sequence, so a pass is full except for the last and the loads of successive passes do not
+// wait for one another.
 template <typename F>
 __device__ __forceinline__ void for_neighbours(const ExclGrid& g, const int32_t* __restrict__ st,
                                                const float4* __restrict__ sorted, int cx, int cy, int cz,
@@ -272,22 +282,31 @@ __device__ __forceinline__ void for_neighbours(const ExclGrid& g, const int32_t*
 {
     const int x0 = cx > 0 ? cx - 1 : 0;
     const int x1 = cx < g.dim[0] - 1 ? cx + 1 : g.dim[0] - 1;
-    for (int dz = -1; dz <= 1; ++dz) {
-        const int z = cz + dz;
-        if (z < 0 || z >= g.dim[2]) continue;
-        for (int dy = -1; dy <= 1; ++dy) {
-            const int y = cy + dy;
-            if (y < 0 || y >= g.dim[1]) continue;
+    int mybegin = 0, mylen = 0;
+    if (lane < 9) {
+        const int z = cz + lane / 3 - 1, y = cy + lane % 3 - 1;
+        if (z >= 0 && z < g.dim[2] && y >= 0 && y < g.dim[1]) {
             const int c0 = (z * g.dim[1] + y) * g.dim[0] + x0;
-            const int begin = uni(st[c0]);
-            const int end = uni(st[c0 + (x1 - x0) + 1]);
-            for (int t0 = begin; t0 < end; t0 += 64) {
-                const int t = t0 + lane;
-                const bool valid = t < end;
-                const float4 r = sorted[valid ? t : begin];
-                f(r, valid);
-            }
+            mybegin = st[c0];
+            mylen = st[c0 + (x1 - x0) + 1] - mybegin;
         }
+    }
+    int begin[9], pre[10];
+    pre[0] = 0;
+#pragma unroll
+    for (int r = 0; r < 9; ++r) {
+        begin[r] = (int)rdlane((uint32_t)mybegin, r);
+        pre[r + 1] = pre[r] + (int)rdlane((uint32_t)mylen, r);
+    }
+    const int total = pre[9];
+    for (int t0 = 0; t0 < total; t0 += 64) {
+        const int t = t0 + lane;
+        const bool valid = t < total;
+        int at = begin[0] + t;
+#pragma unroll
+        for (int r = 1; r < 9; ++r) at = t >= pre[r] ? begin[r] + (t - pre[r]) : at;
+        const float4 rec = sorted[valid ? at : 0];
+        f(rec, valid);
     }
 }
 
@@ -485,13 +504,29 @@ __global__ __launch_bounds__(kWaves * 64) void excl_fill_kernel(
                            if (hit && at < kSortCap) buf[at] = (uint32_t)__float_as_int(r.w);
                            got += __builtin_popcountll(mk);
                        });
-        int n2 = 64;
-        while (n2 < H) n2 <<= 1;
-        for (int t = H + lane; t < n2; t += 64) buf[t] = 0xFFFFFFFFu;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        wave_sort(buf, n2, lane);
+        if (H <= 64) {
+            // one hit per lane: its place in index order is the number of smaller indices
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const uint32_t mine = lane < H ? buf[lane] : 0xFFFFFFFFu;
+            int rank = 0;
+            for (int t = 0; t < H; ++t) rank += rdlane(mine, t) < mine ? 1 : 0;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (lane < H) buf[rank] = mine;          // indices are distinct: ranks are a permutation
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+            int n2 = 128;
+            while (n2 < H) n2 <<= 1;
+            for (int t = H + lane; t < n2; t += 64) buf[t] = 0xFFFFFFFFu;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            wave_sort(buf, n2, lane);
+        }
         for (int t0 = 0; t0 < H; t0 += 64) {
             const bool valid = t0 + lane < H;
             const int j = valid ? (int)buf[t0 + lane] : i;
@@ -500,12 +535,14 @@ __global__ __launch_bounds__(kWaves * 64) void excl_fill_kernel(
             em(j, d, valid, lane);
         }
     } else {
+        const float rmax2 = g.rmax2;
         for (int j0 = 0; j0 < N; j0 += 64) {
             const int j = j0 + lane;
             const bool valid = j < N;
             const int jj = valid ? j : i;
             const float d = dist2(px, py, pz, cloud[(int64_t)jj * 3 + 0], cloud[(int64_t)jj * 3 + 1],
                                   cloud[(int64_t)jj * 3 + 2]);
+            if (__builtin_amdgcn_ballot_w64(valid && d < rmax2) == 0) continue;
             em(j, d, valid, lane);
         }
     }
@@ -576,8 +613,8 @@ hipError_t launch_excl_count(const float* xyz, int B, int N, const float* thr2, 
     int initblocks = (int)((ncnt + 255) / 256);
     if (initblocks > 2048) initblocks = 2048;
     hipLaunchKernelGGL(grid_init_kernel, dim3(initblocks), dim3(256), 0, stream, gp, B, cnt, ncnt);
-    int bblocks = (N + 255) / 256;
-    if (bblocks > 256) bblocks = 256;
+    int bblocks = (N + 2047) / 2048;
+    if (bblocks > 64) bblocks = 64;
     hipLaunchKernelGGL(grid_bounds_kernel, dim3(bblocks, B), dim3(256), 0, stream, xyz, N, gp);
     hipLaunchKernelGGL(grid_setup_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, gp, B, thr2, L, lay.maxcells);
     const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
