@@ -271,6 +271,16 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         roof["knn_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": a / HBM_PEAK_GBS, "bytes": byts,
                               "points_searched_by_brute_force": knn["deferred_fraction"]}
+        # exact FPS with pruned distance updates (outside the timed step): same samples, fewer
+        # distance evaluations; priced against the same algorithmic count as fps_exact
+        pr = time_call(torch, lambda: fp.fps_exact_pruned(x, n))
+        if not torch.equal(pr[1], idx):
+            raise RuntimeError("fps_exact_pruned differs from fps_exact")
+        ms["fps_exact_pruned"] = pr[0]
+        a = point_iters * OPS_PER_POINT_ITERATION / (pr[0] * 1e-3) / 1e12
+        roof["fps_exact_pruned"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
+                                    "frac": a / ALU_PEAK_TOPS, "equals_fps_exact": True,
+                                    "note": "algorithmic operations of the unpruned update / time"}
         ex = time_excl_lists(torch, fp, x, sg, infos, midx, mbq)
         if ex is not None:
             ms["excl_lists_count"], ms["excl_lists_fill"] = ex["count_ms"], ex["fill_ms"]
@@ -292,6 +302,23 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             "cached_ball_query_equals_brute": cached_equal,
             "roofline": roof})
     return out
+
+
+def time_call(torch, fn, reps=3):
+    """(best ms of `reps` calls timed with events after one warm-up, last result)."""
+    out = fn()
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(reps):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        out = fn()
+        b.record()
+        torch.cuda.synchronize()
+        t = a.elapsed_time(b)
+        best = t if best is None else min(best, t)
+    return best, out
 
 
 def time_excl_lists(torch, fp, x, sg, infos, midx, mbq, reps=3):
@@ -466,7 +493,8 @@ def run(args, torch, fp, inputs, calibration, extra):
     detail = quality_and_rooflines(torch, fp, ctx, kernel_ms)
     s0 = detail["stages"][0]
     # dominant kernel of the step: the one with the largest share of the time
-    in_step = [kname for kname in s0["roofline"] if not kname.startswith("knn_")]
+    in_step = [kname for kname in s0["roofline"]
+               if kname in ("fps_exact", "mdps_sample+record", "ball_query_brute", "ball_query_cached")]
     dom = max(in_step, key=lambda kname: s0["kernel_ms"].get(kname, 0.0))
     roof = dict(s0["roofline"][dom])
     roof["kernel"] = dom + " (stage 0)"

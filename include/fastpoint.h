@@ -100,6 +100,22 @@ fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Exact farthest point sampling with pruned distance updates -- the same result as
+ * fp_fps_exact, bit for bit, reached with fewer distance evaluations (the role QuickFPS plays
+ * for the exact iterations in Section 5.3 and Appendix B.3: an exact sampler that skips the
+ * updates that cannot change anything).  The cloud is first put into the order of a uniform
+ * grid traversed along a Z-order curve, so that the points a wavefront holds lie in a small
+ * box; a new sample is folded into a wavefront's distances only if it is closer to that box
+ * than the largest distance the wavefront still holds.  Arguments as fp_fps_exact without the
+ * ball-query cache; the workspace is larger (it also receives the reordered cloud).
+ */
+size_t fp_fps_pruned_workspace_bytes(int32_t B, int32_t N);
+fp_status fp_fps_exact_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
+                              const int32_t* start_idx, int32_t* out_idx, float* out_mdc,
+                              fp_mdps_info* info, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/*
  * Minimum Distance Prediction Sampling, Algorithm 2 (Section 4.1, Appendix A.1):
  * m = max(floor(p*n), m_min) exact FPS iterations that record the distance
  * curve, thresholds R_l from the estimated curve at the segment ends,

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
-EXPORTS = ["fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
+EXPORTS = ["fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
            "fp_ball_query", "fp_knn_workspace_bytes", "fp_knn", "fp_excl_workspace_bytes", "fp_excl_count",
            "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
@@ -94,6 +94,10 @@ def load() -> ctypes.CDLL:
     lib.fp_bq_cache_bytes.restype = ctypes.c_size_t
     lib.fp_fps_exact.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, f32, vp, ctypes.c_size_t, vp]
     lib.fp_fps_exact.restype = i32
+    lib.fp_fps_pruned_workspace_bytes.argtypes = [i32, i32]
+    lib.fp_fps_pruned_workspace_bytes.restype = ctypes.c_size_t
+    lib.fp_fps_exact_pruned.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.fp_fps_exact_pruned.restype = i32
     lib.fp_mdps_sample.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(FpMdpsParams), vp, vp, vp, f32,
                                    vp, ctypes.c_size_t, vp]
     lib.fp_mdps_sample.restype = i32
@@ -227,6 +231,33 @@ def fps_exact(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool = False,
     _check(load().fp_fps_exact(xyz.data_ptr(), B, N, n, _ptr(st), idx.data_ptr(), _ptr(mdc), _ptr(info),
                                _ptr(bq_cache), float(bq_radius), ws.data_ptr(), ws.numel(), _stream()),
            "fp_fps_exact")
+    out = [idx]
+    if want_mdc:
+        out.append(mdc)
+    if want_info:
+        out.append(info)
+    return out[0] if len(out) == 1 else tuple(out)
+
+
+def fps_exact_pruned(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool = False,
+                     want_info: bool = False, ws: Optional[torch.Tensor] = None):
+    """Exact farthest point sampling with pruned distance updates: the outputs of fps_exact."""
+    B, N = _xyz(xyz)
+    st = _start(start_idx, B, xyz.device)
+    idx = torch.empty((B, n), dtype=torch.int32, device=xyz.device)
+    mdc = torch.empty((B, n), dtype=torch.float32, device=xyz.device) if want_mdc else None
+    info = torch.zeros((B, INFO_BYTES), dtype=torch.uint8, device=xyz.device) if want_info else None
+    need = int(load().fp_fps_pruned_workspace_bytes(B, N))
+    if need == 0:
+        raise ValueError("shape (B=%d, N=%d) not supported" % (B, N))
+    if ws is None:
+        key = ("pruned", xyz.device.type, xyz.device.index)
+        ws = _workspaces.get(key)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(need, dtype=torch.uint8, device=xyz.device)
+            _workspaces[key] = ws
+    _check(load().fp_fps_exact_pruned(xyz.data_ptr(), B, N, n, _ptr(st), idx.data_ptr(), _ptr(mdc), _ptr(info),
+                                      ws.data_ptr(), ws.numel(), _stream()), "fp_fps_exact_pruned")
     out = [idx]
     if want_mdc:
         out.append(mdc)

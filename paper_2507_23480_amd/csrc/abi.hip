@@ -112,7 +112,7 @@ constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandPerRound * kCandWor
 fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
                       const fp_mdps_params* prm, int32_t* out_idx, float* out_mdc, fp_mdps_info* info,
                       void* bq_cache, float bq_radius, void* workspace, size_t workspace_bytes,
-                      void* stream_v)
+                      void* stream_v, bool pruned = false)
 {
     if (!xyz || !out_idx) return FP_ERR_NULL;
     if (B < 1 || N < 1 || n < 1 || n > N) return FP_ERR_SHAPE;
@@ -125,7 +125,8 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         if (!(bq_radius > 0.0f) || !isfinite(bq_radius)) return FP_ERR_PARAM;
         if ((reinterpret_cast<uintptr_t>(bq_cache) & 255u) != 0) return FP_ERR_WORKSPACE;
     }
-    if (!workspace || workspace_bytes < fp_workspace_bytes(B, N) ||
+    if (!workspace ||
+        workspace_bytes < (pruned ? fp_fps_pruned_workspace_bytes(B, N) : fp_workspace_bytes(B, N)) ||
         (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
         return FP_ERR_WORKSPACE;
 
@@ -176,6 +177,12 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
     a.ll_cd = a.ll_pk + kLlPkWords;
     a.wait_ticks = g_wait_limit_us.load() * di.wall_khz / 1000;
 
+    if (pruned) {
+        // the cloud in cell order, behind the exchange words
+        void* sort_ws = reinterpret_cast<unsigned char*>(workspace) + fp_workspace_bytes(B, N);
+        if (launch_spatial_sort(xyz, B, N, sort_ws, stream) != hipSuccess) return FP_ERR_DEVICE;
+        a.sorted = spatial_sorted(B, N, sort_ws);
+    }
     const bool bq = bq_cache != nullptr;
     if (bq) {
         BqHeader h;
@@ -200,7 +207,7 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         if (launch_bq_header(bq_cache, h, stream) != hipSuccess) return FP_ERR_DEVICE;
     }
 
-    const void* fn = sampler_kernel_for(plan.T, plan.P, bq);
+    const void* fn = sampler_kernel_for(plan.T, plan.P, bq, pruned);
     if (!fn) return FP_ERR_SHAPE;
     const unsigned grid = (unsigned)(plan.groups * plan.G);
     void* kargs[] = {&a};
@@ -245,6 +252,21 @@ fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n, const 
 {
     return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, info, bq_cache, bq_radius,
                        workspace, workspace_bytes, stream);
+}
+
+size_t fp_fps_pruned_workspace_bytes(int32_t B, int32_t N)
+{
+    if (B < 1 || N < 1 || B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return 0;
+    return fp_workspace_bytes(B, N) + (size_t)spatial_sort_bytes(B, N);
+}
+
+fp_status fp_fps_exact_pruned(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
+                              int32_t* out_idx, float* out_mdc, fp_mdps_info* info, void* workspace,
+                              size_t workspace_bytes, void* stream)
+{
+    if (B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return FP_ERR_SHAPE;
+    return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, info, nullptr, 0.0f, workspace,
+                       workspace_bytes, stream, true);
 }
 
 fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,

@@ -176,6 +176,7 @@ __global__ void grid_setup_kernel(ExclGrid* gp, int B, const float* __restrict__
     g.ncells = dim[0] * dim[1] * dim[2];
     g.rmax2 = rmax2;
     g.lmax = lmax;
+    g.morton_bits = 0;
     gp[b] = g;
 }
 
@@ -184,7 +185,63 @@ __device__ __forceinline__ int cell_of(const ExclGrid& g, float x, float y, floa
     cx = cell_coord(x, g.origin[0], g.inv_h, g.dim[0]);
     cy = cell_coord(y, g.origin[1], g.inv_h, g.dim[1]);
     cz = cell_coord(z, g.origin[2], g.inv_h, g.dim[2]);
+    if (g.morton_bits > 0) {
+        int id = 0;
+        for (int k = 0; k < g.morton_bits; ++k)
+            id |= (((cx >> k) & 1) << (3 * k)) | (((cy >> k) & 1) << (3 * k + 1)) | (((cz >> k) & 1) << (3 * k + 2));
+        return id;
+    }
     return (cz * g.dim[1] + cy) * g.dim[0] + cx;
+}
+
+// One thread per cloud: a cubic grid of 2^bits cells per axis over the bounding box.
+__global__ void sort_setup_kernel(ExclGrid* gp, int B, int bits)
+{
+    const int b = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (b >= B) return;
+    ExclGrid g = gp[b];
+    float emax = 0.0f;
+    for (int a = 0; a < 3; ++a) {
+        g.origin[a] = ord2f(g.lo[a]);
+        const float e = ord2f(g.hi[a]) - g.origin[a];
+        if (e > emax) emax = e;
+    }
+    const int dim = 1 << bits;
+    g.inv_h = emax > 0.0f ? (float)dim / emax : 0.0f;
+    if (!(g.inv_h < 3.0e38f)) g.inv_h = 0.0f;        // extent too small to divide: one cell
+    g.dim[0] = g.dim[1] = g.dim[2] = dim;
+    g.ncells = dim * dim * dim;
+    g.rmax2 = 0.0f;
+    g.lmax = 0;
+    g.morton_bits = bits;
+    gp[b] = g;
+}
+
+// Adds 1 to counter[cell] for every lane with `todo` and returns the value the counter had for
+// this lane (as if the lanes had added one after the other).  Lanes of a wave that share a cell
+// send one atomic together: clouds in scan order put most of a wave into one or two cells, and
+// thousands of single atomics on one address would queue up.  After a few distinct cells the
+// remaining lanes add on their own.
+__device__ __forceinline__ int grouped_add(int32_t* counter, int cell, bool todo, int lane)
+{
+    int pos = 0;
+    for (int it = 0; it < 6; ++it) {
+        const uint64_t act = __builtin_amdgcn_ballot_w64(todo);
+        if (act == 0) return pos;
+        const int leader = __builtin_ctzll(act);
+        const int c0 = (int)rdlane((uint32_t)cell, leader);
+        const bool mine = todo && cell == c0;
+        const uint64_t same = __builtin_amdgcn_ballot_w64(mine);
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&counter[c0], (int)__builtin_popcountll(same));
+        base = (int)rdlane((uint32_t)base, leader);
+        if (mine) {
+            pos = base + lanes_below(same);
+            todo = false;
+        }
+    }
+    if (todo) pos = atomicAdd(&counter[cell], 1);
+    return pos;
 }
 
 __global__ __launch_bounds__(256) void grid_count_kernel(const float* __restrict__ xyz, int N,
@@ -193,12 +250,12 @@ __global__ __launch_bounds__(256) void grid_count_kernel(const float* __restrict
 {
     const int b = (int)blockIdx.y;
     const int i = (int)(blockIdx.x * 256 + threadIdx.x);
-    if (i >= N) return;
+    const bool valid = i < N;
     const ExclGrid g = gp[b];
-    const float* p = xyz + ((int64_t)b * N + i) * 3;
+    const float* p = xyz + ((int64_t)b * N + (valid ? i : 0)) * 3;
     int cx, cy, cz;
     const int c = cell_of(g, p[0], p[1], p[2], cx, cy, cz);
-    atomicAdd(&cell_cnt[(int64_t)b * maxcells + c], 1);
+    grouped_add(cell_cnt + (int64_t)b * maxcells, c, valid, (int)threadIdx.x & 63);
 }
 
 // One workgroup per cloud: cell_start = exclusive scan of the cell counts; the counts become
@@ -259,14 +316,14 @@ __global__ __launch_bounds__(256) void grid_scatter_kernel(const float* __restri
 {
     const int b = (int)blockIdx.y;
     const int i = (int)(blockIdx.x * 256 + threadIdx.x);
-    if (i >= N) return;
+    const bool valid = i < N;
     const ExclGrid g = gp[b];
-    const float* p = xyz + ((int64_t)b * N + i) * 3;
+    const float* p = xyz + ((int64_t)b * N + (valid ? i : 0)) * 3;
     const float x = p[0], y = p[1], z = p[2];
     int cx, cy, cz;
     const int c = cell_of(g, x, y, z, cx, cy, cz);
-    const int pos = atomicAdd(&cell_cur[(int64_t)b * maxcells + c], 1);
-    sorted[(int64_t)b * N + pos] = make_float4(x, y, z, __int_as_float(i));
+    const int pos = grouped_add(cell_cur + (int64_t)b * maxcells, c, valid, (int)threadIdx.x & 63);
+    if (valid) sorted[(int64_t)b * N + pos] = make_float4(x, y, z, __int_as_float(i));
 }
 
 // ------------------------------------------------------------------ walking the 27 cells
@@ -597,6 +654,44 @@ ExclLayout excl_layout(int B, int N, int L)
     at += up(((rows + kScanBlock - 1) / kScanBlock + 1) * 8);
     lay.bytes = at;
     return lay;
+}
+
+static int sort_bits(int maxcells)
+{
+    int bits = 1;
+    while (bits < 7 && ((int64_t)1 << (3 * (bits + 1))) <= maxcells) ++bits;
+    return bits;
+}
+
+int64_t spatial_sort_bytes(int B, int N) { return excl_layout(B, N, 1).bytes; }
+
+const float4* spatial_sorted(int B, int N, const void* workspace)
+{
+    return reinterpret_cast<const float4*>(reinterpret_cast<const unsigned char*>(workspace) +
+                                           excl_layout(B, N, 1).sorted_off);
+}
+
+hipError_t launch_spatial_sort(const float* xyz, int B, int N, void* workspace, hipStream_t stream)
+{
+    const ExclLayout lay = excl_layout(B, N, 1);
+    unsigned char* base = reinterpret_cast<unsigned char*>(workspace);
+    ExclGrid* gp = reinterpret_cast<ExclGrid*>(base + lay.grid_off);
+    int32_t* cnt = reinterpret_cast<int32_t*>(base + lay.cnt_off);
+    int32_t* st = reinterpret_cast<int32_t*>(base + lay.start_off);
+    float4* sorted = reinterpret_cast<float4*>(base + lay.sorted_off);
+    const int64_t ncnt = (int64_t)B * lay.maxcells;
+    int initblocks = (int)((ncnt + 255) / 256);
+    if (initblocks > 2048) initblocks = 2048;
+    hipLaunchKernelGGL(grid_init_kernel, dim3(initblocks), dim3(256), 0, stream, gp, B, cnt, ncnt);
+    int bblocks = (N + 2047) / 2048;
+    if (bblocks > 64) bblocks = 64;
+    hipLaunchKernelGGL(grid_bounds_kernel, dim3(bblocks, B), dim3(256), 0, stream, xyz, N, gp);
+    hipLaunchKernelGGL(sort_setup_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, gp, B, sort_bits(lay.maxcells));
+    const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
+    hipLaunchKernelGGL(grid_count_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, lay.maxcells);
+    hipLaunchKernelGGL(grid_scan_kernel, dim3(B), dim3(1024), 0, stream, gp, cnt, st, lay.maxcells);
+    hipLaunchKernelGGL(grid_scatter_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, sorted, lay.maxcells);
+    return hipGetLastError();
 }
 
 hipError_t launch_excl_count(const float* xyz, int B, int N, const float* thr2, int L, int64_t* offsets,

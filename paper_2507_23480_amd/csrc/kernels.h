@@ -53,6 +53,7 @@ struct SamplerArgs {
     uint64_t* ll_pk;                // [groups][2][G][kLlSlotWords]
     uint64_t* ll_cd;                // [groups][2][G][kCandPerRound][kCandWords]
     int64_t wait_ticks;
+    const float4* sorted;           // cell-ordered variant: [B][N] records (x, y, z, index bits), else NULL
 };
 
 struct Plan {
@@ -60,7 +61,7 @@ struct Plan {
     int groups;         // clouds resident at once
 };
 
-const void* sampler_kernel_for(int threads, int points_per_thread, bool bq);
+const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm);
 hipError_t launch_zero_words(uint64_t* p, int64_t nwords, hipStream_t stream);
 
 hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* center_idx, int M,
@@ -84,6 +85,8 @@ struct ExclGrid {
     int32_t ncells;
     float rmax2;             // largest squared radius of the cloud
     int32_t lmax;            // its level
+    int32_t morton_bits;     // 0: cells numbered x-fastest; b > 0: 2^b cells per axis, numbered by
+                             // interleaving the bits of the three coordinates
 };
 
 // Where the parts of an exclusion-list workspace lie (byte offsets).
@@ -93,6 +96,11 @@ struct ExclLayout {
 };
 
 ExclLayout excl_layout(int B, int N, int L);
+// Sorts every cloud into the order of a 2^b x 2^b x 2^b grid over its bounding box, cells
+// numbered along a Z-order curve; leaves records (x, y, z, index bits) at spatial_sorted().
+hipError_t launch_spatial_sort(const float* xyz, int B, int N, void* workspace, hipStream_t stream);
+int64_t spatial_sort_bytes(int B, int N);
+const float4* spatial_sorted(int B, int N, const void* workspace);
 hipError_t launch_excl_count(const float* xyz, int B, int N, const float* thr2, int L, int64_t* offsets,
                              void* workspace, hipStream_t stream);
 hipError_t launch_excl_fill(const float* xyz, int B, int N, const float* thr2, int L, const int64_t* offsets,

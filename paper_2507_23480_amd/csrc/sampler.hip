@@ -262,10 +262,39 @@ struct RegVec {
     typedef float type __attribute__((ext_vector_type(P)));
 };
 
+template <int P>
+struct RegVecU {
+    typedef uint32_t type __attribute__((ext_vector_type(P)));
+};
+
 template <int P, bool BQ>
 struct Points {
     typename RegVec<P>::type x, y, z, d;
+    typename RegVecU<P>::type oi;       // cell-ordered variant: the point's index in the caller's cloud
+    float lox, loy, loz, hix, hiy, hiz; // cell-ordered variant: box of the wave's points (wave-uniform)
+    uint32_t ub;                        // ... and an upper bound of their running distances (bits)
 };
+
+// Cell-ordered variant: squared distance of a pick to the box of a wave's points, evaluated like
+// dist2 with the nearest box coordinate per axis.  Rounding is monotone, so dist2 of every point
+// of the wave is at least this value: a pick for which it is at least `ub` cannot lower any of the
+// wave's distances, and folding it would change nothing.
+template <int P, bool BQ>
+struct Points;
+template <int P, bool BQ>
+__device__ __forceinline__ float box_dist2(const Points<P, BQ>& pt, float cx, float cy, float cz);
+
+template <int P, bool BQ>
+__device__ __forceinline__ float box_dist2(const Points<P, BQ>& pt, float cx, float cy, float cz)
+{
+    const float dx = fmaxf(fmaxf(pt.lox - cx, cx - pt.hix), 0.0f);
+    const float dy = fmaxf(fmaxf(pt.loy - cy, cy - pt.hiy), 0.0f);
+    const float dz = fmaxf(fmaxf(pt.loz - cz, cz - pt.hiz), 0.0f);
+    float t = dx * dx;
+    t = t + dy * dy;
+    t = t + dz * dz;
+    return t;
+}
 
 // Radius-test results of up to 64 picks that a wave has folded but not written to the cache
 // yet: lane s holds the P 64-bit words (one per slot) of the s-th of those picks.
@@ -342,7 +371,7 @@ __device__ __forceinline__ void flush_rows(const RowWords<P>& rw, const SamplerA
 // Arg-max over the workgroup's points (lowest index among equals).  On return
 // every thread of the workgroup holds the record of the workgroup's best point
 // (G == 1) -- or wave 0 holds it (G > 1).
-template <int T, int P, bool BQ>
+template <int T, int P, bool BQ, bool PERM>
 __device__ __forceinline__ Rec wave_best(const Points<P, BQ>& pt, const Where& wh)
 {
     uint32_t bits = __float_as_uint(pt.d[0]);          // distances are >= +0: unsigned order
@@ -354,6 +383,34 @@ __device__ __forceinline__ Rec wave_best(const Points<P, BQ>& pt, const Where& w
             bits = v;
             bp = p;
         }
+    }
+    if constexpr (PERM) {
+        // positions are in cell order: the lowest index of the caller's cloud among equal maxima
+        uint32_t boi = pt.oi[0];
+        bits = __float_as_uint(pt.d[0]);
+        bp = 0;
+#pragma unroll
+        for (int p = 1; p < P; ++p) {
+            const uint32_t v = __float_as_uint(pt.d[p]);
+            if (v > bits || (v == bits && pt.oi[p] < boi)) {
+                bits = v;
+                boi = pt.oi[p];
+                bp = p;
+            }
+        }
+        const uint32_t wmax_p = wave_max_u32(bits);
+        const uint32_t widx_p = wave_min_u32(bits == wmax_p ? boi : kNoIdx);
+        const int wl_p = first_lane(__builtin_amdgcn_ballot_w64(bits == wmax_p && boi == widx_p));
+        const int slot_p = (int)rdlane((uint32_t)bp, wl_p);
+        Rec r;
+        r.d = wmax_p;
+        r.idx = widx_p;
+        r.x = rdlane_f(pt.x[slot_p], wl_p);
+        r.y = rdlane_f(pt.y[slot_p], wl_p);
+        r.z = rdlane_f(pt.z[slot_p], wl_p);
+        r.fail = 0;
+        r.pad0 = r.pad1 = 0;
+        return r;
     }
     const uint32_t wmax = wave_max_u32(bits);
     const uint32_t myj = (uint32_t)(((wh.gw * P + bp) << 6) | wh.lane);
@@ -395,14 +452,14 @@ __device__ __forceinline__ Rec reduce_recs(Rec r, bool valid)
 
 // One arg-max over the whole cloud.  `it` counts the reductions done so far in
 // this kernel (LDS double buffering), `seq` the exchanges between workgroups.
-template <int T, int P, bool BQ>
+template <int T, int P, bool BQ, bool PERM>
 __device__ __forceinline__ Rec cloud_argmax(const Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                             const SamplerArgs& a, uint32_t& it, uint32_t& seq)
 {
     constexpr int NW = T / 64;
     const int buf = (int)(it & 1u);
     ++it;
-    Rec mine = wave_best<T, P, BQ>(pt, wh);
+    Rec mine = wave_best<T, P, BQ, PERM>(pt, wh);
     if (wh.lane == 0 && !wh.ctrl) sh.wrec[buf][wh.w] = mine;
     __syncthreads();
     if (wh.G == 1) {
@@ -505,14 +562,42 @@ __device__ __noinline__ double pow_int_base(int64_t x, double e)
     return acc * __longlong_as_double((long long)(1023 + (int)q) << 52);
 }
 
+// Cell-ordered variant: which of the first `count` entries of `list` can lower a distance of
+// this wave (one entry per lane), and the wave's bound brought up to date.
+template <int P, bool BQ>
+__device__ __forceinline__ uint64_t near_mask(const Points<P, BQ>& pt, const Cand* list, int count, int lane)
+{
+    const Cand c = list[lane < count ? lane : 0];
+    const float bd = box_dist2<P, BQ>(pt, c.x, c.y, c.z);
+    return __builtin_amdgcn_ballot_w64(lane < count && __float_as_uint(bd) < pt.ub);
+}
+template <int P, bool BQ>
+__device__ __forceinline__ void refresh_bound(Points<P, BQ>& pt)
+{
+    uint32_t m = __float_as_uint(pt.d[0]);
+#pragma unroll
+    for (int p = 1; p < P; ++p) m = max(m, __float_as_uint(pt.d[p]));
+    pt.ub = wave_max_u32(m);
+}
+
 // Folds the picks waiting in sh.pend (sample positions base, base+1, ...) into the distances.
-template <int T, int P, bool BQ>
+template <int T, int P, bool BQ, bool PERM>
 __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                              const SamplerArgs& a, int npend, int base)
 {
     if (npend <= 0 || wh.ctrl) return;
     RowWords<P> rw;
     rw.clear();
+    if constexpr (PERM) {
+        uint64_t near = near_mask<P, BQ>(pt, sh.pend, npend, wh.lane);
+        while (near != 0) {
+            const int s = first_lane(near);
+            near &= near - 1;
+            const Cand cur = sh.pend[s];
+            fold<P, BQ>(pt, cur.x, cur.y, cur.z, a, wh, s, rw);
+        }
+        return;
+    }
     Cand nxt = sh.pend[0];
     for (int s = 0; s < npend; ++s) {                   // npend <= kCand
         const Cand cur = nxt;
@@ -524,14 +609,18 @@ __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, c
 
 // The point waves' side of a round that the control wave resolves: folds the picks (sample
 // positions base, base+1, ...) as they are published, until the slot that closes the round.
-// The next slot is requested before the current pick is folded.
-template <int T, int P, bool BQ>
+// The next slot is requested before the current pick is folded.  Cell-ordered variant: the
+// candidates of the round (`total` of them) are tested against the wave's box once, all
+// together; a published pick that is not near is passed over.
+template <int T, int P, bool BQ, bool PERM>
 __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
-                                             const SamplerArgs& a, int base, uint32_t tag)
+                                             const SamplerArgs& a, int base, uint32_t tag, int total)
 {
     int s = 0;
     RowWords<P> rw;
     rw.clear();
+    uint64_t near = ~0ull;
+    if constexpr (PERM) near = near_mask<P, BQ>(pt, sh.cand, total, wh.lane);
     uint32_t slot = lds_observe(&sh.live[0]);
     for (;;) {
         slot = uni(slot);
@@ -541,9 +630,12 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
             continue;
         }
         if ((slot & 0xFFu) == kLiveEnd) break;
-        const Cand c = sh.cand[slot & 0xFFu];
+        const uint32_t cl = slot & 0xFFu;
         slot = lds_observe(&sh.live[s + 1]);
-        fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, s, rw);
+        if (!PERM || ((near >> cl) & 1ull) != 0) {
+            const Cand c = sh.cand[cl];
+            fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, s, rw);
+        }
         ++s;
     }
     flush_rows<P, BQ>(rw, a, wh, base, s);          // a round has at most kCand picks
@@ -579,7 +671,7 @@ struct CloudState {
     float om;       // an exact-FPS round takes the points above dlast * (1 - om) as candidates
     int my_bl;      // thread l < nseg: segment boundary b_(l+1); else -1
 #ifdef FASTPOINT_PHASE_CLOCKS
-    long long clk[4];
+    long long clk[8];
 #endif
 };
 
@@ -595,12 +687,12 @@ __device__ __forceinline__ void capture_curve(Shared<T>& sh, const Where& wh, co
 // One plain iteration of Alg. 1 (lines 4-8) on distances that are already up to date:
 // arg-max over the cloud, lowest index among equals.  Always makes progress; the batched
 // rounds below fall back to it.  Returns false if a wait between workgroups expired.
-template <int T, int P, bool BQ>
+template <int T, int P, bool BQ, bool PERM>
 __device__ __forceinline__ bool plain_pick(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                            const SamplerArgs& a, uint32_t& it, uint32_t& seq,
                                            CloudState& st, bool capture)
 {
-    const Rec r = cloud_argmax<T, P, BQ>(pt, sh, wh, a, it, seq);
+    const Rec r = cloud_argmax<T, P, BQ, PERM>(pt, sh, wh, a, it, seq);
     if (uni(r.fail)) return false;
     const float dpick = __uint_as_float(uni(r.d));
     if (wh.tid == 0) {
@@ -625,7 +717,7 @@ __device__ __forceinline__ bool plain_pick(Points<P, BQ>& pt, Shared<T>& sh, con
 // threshold -- d > thr (STRICT) or d >= thr -- into sh.cand of every workgroup.
 // Returns the number collected (at most kCand), -1 if a wait expired; `alltot` receives the
 // number of points that pass in the whole cloud.
-template <int T, int P, bool BQ, bool STRICT>
+template <int T, int P, bool BQ, bool PERM, bool STRICT>
 __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                                const SamplerArgs& a, uint32_t& seq, float thr, int& alltot)
 {
@@ -659,7 +751,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
                 const int rank = base + lanes_below(mk);
                 if (av && rank < kCand) {
                     Cand cd;
-                    cd.idx = (uint32_t)(((wh.gw * P + p) << 6) | wh.lane);
+                    cd.idx = PERM ? pt.oi[p] : (uint32_t)(((wh.gw * P + p) << 6) | wh.lane);
                     cd.x = pt.x[p];
                     cd.y = pt.y[p];
                     cd.z = pt.z[p];
@@ -796,7 +888,7 @@ __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh
 // instructions is what a pick costs.
 // One run of the chain: up to `limit` picks (CHECK) or as many as exceed tau (a candidate is
 // accepted at most once, so that needs no count).  Returns the number accepted.
-template <bool CHECK>
+template <bool CHECK, bool PERM>
 __device__ __forceinline__ int chain_loop(uint64_t* live, LiveCursor& cur, const Cand& me, uint32_t& cd,
                                           uint32_t tau_bits, int limit, uint32_t& dl)
 {
@@ -804,7 +896,13 @@ __device__ __forceinline__ int chain_loop(uint64_t* live, LiveCursor& cur, const
     uint32_t dmax = wave_max_scalar(cd);
     while (dmax > tau_bits) {
         if (CHECK && nacc >= limit) break;
-        const int cl = first_lane(__builtin_amdgcn_ballot_w64(cd == dmax));
+        const uint64_t eq = __builtin_amdgcn_ballot_w64(cd == dmax);
+        int cl = first_lane(eq);
+        if (PERM && __builtin_expect(__builtin_popcountll(eq) > 1, 0)) {
+            // cell order: among equal distances the lowest index of the caller's cloud, not the lowest lane
+            const uint32_t imin = wave_min_u32(cd == dmax ? me.idx : kNoIdx);
+            cl = first_lane(__builtin_amdgcn_ballot_w64(cd == dmax && me.idx == imin));
+        }
         const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
         cur.publish(live, (uint32_t)cl, dmax);
         dl = dmax;
@@ -816,7 +914,7 @@ __device__ __forceinline__ int chain_loop(uint64_t* live, LiveCursor& cur, const
     return nacc;
 }
 
-template <int T>
+template <int T, bool PERM>
 __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, const CloudState& st,
                                               int total, int limit, float tau, bool capture, int nseg,
                                               uint32_t tag)
@@ -835,8 +933,8 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
 #endif
     // the candidates have arrived from LDS before the loop starts, not inside it
     asm volatile("" ::"v"(me.x), "v"(me.y), "v"(me.z), "v"(cd));
-    const int nacc = limit >= total ? chain_loop<false>(sh.live, cur, me, cd, tau_bits, limit, dl)
-                                    : chain_loop<true>(sh.live, cur, me, cd, tau_bits, limit, dl);
+    const int nacc = limit >= total ? chain_loop<false, PERM>(sh.live, cur, me, cd, tau_bits, limit, dl)
+                                    : chain_loop<true, PERM>(sh.live, cur, me, cd, tau_bits, limit, dl);
     cur.publish(sh.live, kLiveEnd, 0u);
     __builtin_amdgcn_s_setprio(0);
 #ifdef FASTPOINT_PHASE_CLOCKS
@@ -864,7 +962,7 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
 
 // ---- exact FPS for sample positions [st.i, upto) (Alg. 1 lines 3-8), in batched rounds with
 // plain iterations as the fallback.  Returns false if a wait between workgroups expired.
-template <int T, int P, bool BQ>
+template <int T, int P, bool BQ, bool PERM>
 __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                            const SamplerArgs& a, uint32_t& it, uint32_t& seq,
                                            CloudState& st, int upto, bool capture)
@@ -873,10 +971,11 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
         flush_picks<T, BQ>(a, sh, wh, st.flushed, st.i, false);
         {
             PHASE_BEGIN();
-            fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend, st.i - st.npend);
+            fold_pending<T, P, BQ, PERM>(pt, sh, wh, a, st.npend, st.i - st.npend);
             PHASE_END(st, 0);
         }
         st.npend = 0;
+        if constexpr (PERM) refresh_bound<P, BQ>(pt);
         bool good = false;
         int total = 0, alltot = 0;
         float tau = 0.0f;
@@ -884,7 +983,7 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
             for (int tries = 0; tries < 4 && !good; ++tries) {
                 tau = st.dlast - st.om * st.dlast;
                 PHASE_BEGIN();
-                total = scan_candidates<T, P, BQ, true>(pt, sh, wh, a, seq, tau, alltot);
+                total = scan_candidates<T, P, BQ, PERM, true>(pt, sh, wh, a, seq, tau, alltot);
                 PHASE_END(st, 1);
                 if (total < 0) return false;
                 ++st.rounds;
@@ -895,7 +994,7 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
         }
         if (!good) {
             PHASE_BEGIN();
-            const bool picked = plain_pick<T, P, BQ>(pt, sh, wh, a, it, seq, st, capture);
+            const bool picked = plain_pick<T, P, BQ, PERM>(pt, sh, wh, a, it, seq, st, capture);
             PHASE_END(st, 3);
             if (!picked) return false;
             continue;
@@ -903,8 +1002,8 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
         {
             PHASE_BEGIN();
             const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
-            if (wh.ctrl) resolve_chain<T>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg, tag);
-            else follow_picks<T, P, BQ>(pt, sh, wh, a, st.i, tag);
+            if (wh.ctrl) resolve_chain<T, PERM>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg, tag);
+            else follow_picks<T, P, BQ, PERM>(pt, sh, wh, a, st.i, tag, total);
             __syncthreads();
             PHASE_END(st, 2);
         }
@@ -919,7 +1018,7 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
 }
 
 // ------------------------------------------------------------------ one cloud
-template <int T, int P, bool BQ>
+template <int T, int P, bool BQ, bool PERM>
 __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, const Where& wh,
                                           uint32_t& it, uint32_t& seq)
 {
@@ -941,19 +1040,63 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     }
 
     Points<P, BQ> pt;
+    if constexpr (PERM) {
+        // positions follow the cell order of a.sorted; a record carries the point's own index
+        const float4* __restrict__ rec = a.sorted + (int64_t)wh.c * N;
+        float lo[3] = {__builtin_inff(), __builtin_inff(), __builtin_inff()};
+        float hi[3] = {-__builtin_inff(), -__builtin_inff(), -__builtin_inff()};
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
-        const int j = ((wh.gw * P + p) << 6) | wh.lane;
-        if (j < N) {
-            pt.x[p] = cloud[(int64_t)j * 3 + 0];
-            pt.y[p] = cloud[(int64_t)j * 3 + 1];
-            pt.z[p] = cloud[(int64_t)j * 3 + 2];
-            pt.d[p] = __builtin_inff();
-        } else {
-            pt.x[p] = kPadCoord;
-            pt.y[p] = kPadCoord;
-            pt.z[p] = kPadCoord;
-            pt.d[p] = 0.0f;
+        for (int p = 0; p < P; ++p) {
+            const int j = ((wh.gw * P + p) << 6) | wh.lane;
+            if (j < N) {
+                const float4 r = rec[j];
+                pt.x[p] = r.x;
+                pt.y[p] = r.y;
+                pt.z[p] = r.z;
+                pt.oi[p] = __float_as_uint(r.w);
+                pt.d[p] = __builtin_inff();
+                lo[0] = fminf(lo[0], r.x);
+                lo[1] = fminf(lo[1], r.y);
+                lo[2] = fminf(lo[2], r.z);
+                hi[0] = fmaxf(hi[0], r.x);
+                hi[1] = fmaxf(hi[1], r.y);
+                hi[2] = fmaxf(hi[2], r.z);
+            } else {
+                pt.x[p] = kPadCoord;
+                pt.y[p] = kPadCoord;
+                pt.z[p] = kPadCoord;
+                pt.oi[p] = kNoIdx;
+                pt.d[p] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 3; ++k)
+            for (int sft = 32; sft > 0; sft >>= 1) {
+                lo[k] = fminf(lo[k], __shfl_xor(lo[k], sft, 64));
+                hi[k] = fmaxf(hi[k], __shfl_xor(hi[k], sft, 64));
+            }
+        pt.lox = unif(lo[0]);
+        pt.loy = unif(lo[1]);
+        pt.loz = unif(lo[2]);
+        pt.hix = unif(hi[0]);
+        pt.hiy = unif(hi[1]);
+        pt.hiz = unif(hi[2]);
+        pt.ub = 0x7F800000u;
+    } else {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int j = ((wh.gw * P + p) << 6) | wh.lane;
+            if (j < N) {
+                pt.x[p] = cloud[(int64_t)j * 3 + 0];
+                pt.y[p] = cloud[(int64_t)j * 3 + 1];
+                pt.z[p] = cloud[(int64_t)j * 3 + 2];
+                pt.d[p] = __builtin_inff();
+            } else {
+                pt.x[p] = kPadCoord;
+                pt.y[p] = kPadCoord;
+                pt.z[p] = kPadCoord;
+                pt.d[p] = 0.0f;
+            }
         }
     }
     if (wh.tid < kCand + 2) sh.live[wh.tid] = 0;       // round tags start at 1 in every cloud
@@ -974,7 +1117,8 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     st.om = 0.25f;
     st.my_bl = wh.tid < a.nseg ? boundary_index(n, a.nseg, wh.tid + 1) : -1;
 #ifdef FASTPOINT_PHASE_CLOCKS
-    st.clk[0] = st.clk[1] = st.clk[2] = st.clk[3] = 0;
+    for (int k = 0; k < 8; ++k) st.clk[k] = 0;
+    const long long cloud_t0__ = wall_clock64();
 #endif
     if (wh.tid == 0) {
         sh.ctrl[2] = 0;
@@ -997,7 +1141,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     const bool pure_fps = (m >= n - 1);
     int et_index = n;
 
-    bool ok = fps_rounds<T, P, BQ>(pt, sh, wh, a, it, seq, st, pure_fps ? n : m + 1, !pure_fps);
+    bool ok = fps_rounds<T, P, BQ, PERM>(pt, sh, wh, a, it, seq, st, pure_fps ? n : m + 1, !pure_fps);
 
     if (ok && !pure_fps) {
         // ---- thresholds from the estimated curve (Eq. 1 with a/x^e; Alg. 2 lines 13, 20)
@@ -1032,6 +1176,9 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         }
         __syncthreads();
         int seg = 0;
+#ifdef FASTPOINT_PHASE_CLOCKS
+        const long long thrphase_t0 = wall_clock64();
+#endif
 
         // ---- threshold sampling (Alg. 2 lines 24-37), running-distance form
         while (st.i < n) {
@@ -1041,7 +1188,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 seg = q;
                 if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
             }
-            fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend, st.i - st.npend);   // picks since the last sweep
+            fold_pending<T, P, BQ, PERM>(pt, sh, wh, a, st.npend, st.i - st.npend);   // picks since the last sweep
             st.npend = 0;
             const float r2 = unif(sh.thr[seg - 1]);
             // samples of this level end where the quota rule would raise the level
@@ -1049,7 +1196,14 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             const int limit = (int)((qend < n ? qend : n) - st.i);
             ++st.rounds;
             int alltot = 0;
-            const int total = scan_candidates<T, P, BQ, false>(pt, sh, wh, a, seq, r2, alltot);
+#ifdef FASTPOINT_PHASE_CLOCKS
+            const long long thr_t0 = wall_clock64();
+#endif
+            const int total = scan_candidates<T, P, BQ, PERM, false>(pt, sh, wh, a, seq, r2, alltot);
+#ifdef FASTPOINT_PHASE_CLOCKS
+            const long long thr_t1 = wall_clock64();
+            st.clk[4] += thr_t1 - thr_t0;
+#endif
             if (total < 0) {
                 ok = false;
                 break;
@@ -1063,23 +1217,29 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             }
             const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
             if (wh.ctrl) resolve_threshold<T>(sh, wh, st, total, limit, r2, tag);
-            else follow_picks<T, P, BQ>(pt, sh, wh, a, st.i, tag);
+            else follow_picks<T, P, BQ, PERM>(pt, sh, wh, a, st.i, tag, total);
             __syncthreads();
             ++st.resolved;
             st.npend = 0;                           // folded while they were resolved
             st.i += uni(sh.ctrl[0]);
+#ifdef FASTPOINT_PHASE_CLOCKS
+            st.clk[5] += wall_clock64() - thr_t1;
+#endif
         }
 
+#ifdef FASTPOINT_PHASE_CLOCKS
+        st.clk[6] = wall_clock64() - thrphase_t0;
+#endif
         if (ok && st.i < n) {
             // ---- early termination (Alg. 2 lines 39-53): dists is already the true running
             //      minimum, so the remainder is exact FPS on the same registers
             et_index = st.i;
             st.dlast = -1.0f;
-            ok = fps_rounds<T, P, BQ>(pt, sh, wh, a, it, seq, st, n, false);
+            ok = fps_rounds<T, P, BQ, PERM>(pt, sh, wh, a, it, seq, st, n, false);
         }
     }
     // the rows of the picks that were never folded (at least the last sample) are still missing
-    if (ok && BQ) fold_pending<T, P, BQ>(pt, sh, wh, a, st.npend, st.i - st.npend);
+    if (ok && BQ) fold_pending<T, P, BQ, PERM>(pt, sh, wh, a, st.npend, st.i - st.npend);
 
     if (ok) flush_picks<T, BQ>(a, sh, wh, st.flushed, n, true);
     __syncthreads();
@@ -1097,6 +1257,8 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         if (a.nseg <= 8)
         {
             for (int k = 0; k < 4; ++k) inf.thr2[8 + k] = (float)st.clk[k] * 0.01f;   // 100 MHz ticks
+            st.clk[7] = wall_clock64() - cloud_t0__;
+            for (int k = 4; k < 8; ++k) inf.level_start[4 + k] = (int)st.clk[k];      // 10 ns ticks
             inf.thr2[12] = (float)sh.chain_cycles;
             inf.thr2[13] = (float)sh.chain_picks;
         }
@@ -1109,7 +1271,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     __syncthreads();
 }
 
-template <int T, int P, bool BQ>
+template <int T, int P, bool BQ, bool PERM>
 __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a)
 {
     __shared__ Shared<T> sh;
@@ -1127,7 +1289,7 @@ __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a
     uint32_t it = 0, seq = 0;
     for (int c = wh.grp; c < a.B; c += ngroups) {
         wh.c = c;
-        run_cloud<T, P, BQ>(a, sh, wh, it, seq);
+        run_cloud<T, P, BQ, PERM>(a, sh, wh, it, seq);
     }
 }
 
@@ -1140,22 +1302,23 @@ __global__ void zero_words_kernel(uint64_t* p, int64_t nwords)
 }
 
 template <int T, int P>
-const void* pick_bq(bool bq)
+const void* pick_bq(bool bq, bool perm)
 {
-    return bq ? reinterpret_cast<const void*>(&sampler_kernel<T, P, true>)
-              : reinterpret_cast<const void*>(&sampler_kernel<T, P, false>);
+    if (perm) return bq ? nullptr : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true>);
+    return bq ? reinterpret_cast<const void*>(&sampler_kernel<T, P, true, false>)
+              : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, false>);
 }
 
 }  // namespace
 
-const void* sampler_kernel_for(int threads, int points_per_thread, bool bq)
+const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm)
 {
     if (threads == 512) {
         switch (points_per_thread) {
-            case 2: return pick_bq<512, 2>(bq);
-            case 4: return pick_bq<512, 4>(bq);
-            case 8: return pick_bq<512, 8>(bq);
-            case 16: return pick_bq<512, 16>(bq);
+            case 2: return pick_bq<512, 2>(bq, perm);
+            case 4: return pick_bq<512, 4>(bq, perm);
+            case 8: return pick_bq<512, 8>(bq, perm);
+            case 16: return pick_bq<512, 16>(bq, perm);
             default: return nullptr;
         }
     }
