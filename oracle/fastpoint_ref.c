@@ -117,6 +117,9 @@ typedef struct {
     float thr_override[REF_MAX_SEG];
     float level_scale[REF_MAX_SEG]; /* offline per-segment correction of the predicted
                                        SQUARED value (1 = pure power function)       */
+    const float *mlp;     /* NULL: power-function estimator.  Else the weights of the
+                             MLP estimator of App. A.3 (REF_MLP_WEIGHTS floats, layout
+                             at ref_mlp_curve)                                       */
 } ref_mdps_params;
 
 typedef struct {
@@ -176,6 +179,106 @@ double ref_pow_int_base(int64_t x, double e)
     return ldexp(acc, (int)q);                           /* exact scaling */
 }
 
+/* ln v for a normal positive binary64 v, with + - * / only, in a fixed order:
+ * v = f * 2^k with f in [sqrt(1/2), sqrt(2)), ln f = 2 atanh((f-1)/(f+1)) by 13 terms of
+ * its series.  The same steps as inside ref_pow_int_base. */
+double ref_ln_fixed(double v)
+{
+    const double LN2 = 0.6931471805599453;
+    int k = 0;
+    double f = frexp(v, &k);          /* exact: v = f * 2^k, f in [0.5, 1) */
+    f = f * 2.0;
+    k = k - 1;                        /* f in [1, 2) */
+    if (f > 1.4142135623730951) {
+        f = f * 0.5;
+        k = k + 1;
+    }
+    double s = (f - 1.0) / (f + 1.0);
+    double s2 = s * s;
+    double sum = 0.0;
+    for (int t = 12; t >= 0; --t)
+        sum = sum * s2 + 1.0 / (double)(2 * t + 1);
+    return ((double)k * LN2) + ((2.0 * s) * sum);
+}
+
+/* exp y for |y| < 700, fixed order: y = q ln2 + r, q = round(y / ln2), exp r by 20 terms of
+ * its Taylor series, times 2^q. */
+double ref_exp_fixed(double y)
+{
+    const double LN2 = 0.6931471805599453;
+    double q = floor(y / LN2 + 0.5);
+    double r = y - q * LN2;
+    double acc = 1.0;
+    for (int t = 20; t >= 1; --t)
+        acc = 1.0 + acc * (r / (double)t);
+    return ldexp(acc, (int)q);
+}
+
+/*
+ * MLP curve estimator (Appendix A.3): a three-layer perceptron 32-128-128-64 that takes
+ * the first segment of the minimum distance curve "represented by 32 values" and returns
+ * the rest of the curve "represented by 64 values".  The paper fixes neither the
+ * representation, the activation nor the precision; this build takes
+ *   input k (0..31)   ln( mdc[i_k] / mdc[m] ),  i_k = max(1, floor(m (k+1) / 32))
+ *   output j (0..63)  ln( C(x_j) / mdc[m] ) at x_j = m + (n-1-m) (j+1) / 64
+ *   hidden layers with ReLU, the output layer linear, every layer with a bias
+ *   arithmetic in binary64, a neuron's sum starting from its bias and adding the
+ *   products in ascending input order, each product and sum rounded on its own
+ * (logarithms of ratios make the estimator independent of the cloud's scale and density).
+ * Weights, binary32, input-major so that consecutive outputs are adjacent:
+ *   W1[32][128] b1[128] W2[128][128] b2[128] W3[128][64] b3[64]   (REF_MLP_WEIGHTS floats)
+ *   out[64] receives the output layer
+ */
+#define REF_MLP_WEIGHTS (32 * 128 + 128 + 128 * 128 + 128 + 128 * 64 + 64)
+int ref_mlp_curve(const float *mdc, int32_t m, const float *w, double *out)
+{
+    if (!mdc || !w || !out || m < 1)
+        return -1;
+    double in[32], h1[128], h2[128];
+    for (int k = 0; k < 32; ++k) {
+        int64_t i = ((int64_t)m * (k + 1)) / 32;
+        if (i < 1)
+            i = 1;
+        in[k] = ref_ln_fixed((double)mdc[i] / (double)mdc[m]);
+    }
+    const float *W1 = w, *b1 = W1 + 32 * 128, *W2 = b1 + 128, *b2 = W2 + 128 * 128;
+    const float *W3 = b2 + 128, *b3 = W3 + 128 * 64;
+    for (int o = 0; o < 128; ++o) {
+        double acc = (double)b1[o];
+        for (int k = 0; k < 32; ++k)
+            acc = acc + (double)W1[k * 128 + o] * in[k];
+        h1[o] = acc > 0.0 ? acc : 0.0;
+    }
+    for (int o = 0; o < 128; ++o) {
+        double acc = (double)b2[o];
+        for (int k = 0; k < 128; ++k)
+            acc = acc + (double)W2[k * 128 + o] * h1[k];
+        h2[o] = acc > 0.0 ? acc : 0.0;
+    }
+    for (int o = 0; o < 64; ++o) {
+        double acc = (double)b3[o];
+        for (int k = 0; k < 128; ++k)
+            acc = acc + (double)W3[k * 64 + o] * h2[k];
+        out[o] = acc;
+    }
+    return 0;
+}
+
+/* The estimated curve at sample position b (m < b <= n-1), squared: linear interpolation
+ * of the MLP's outputs (log of the ratio to mdc[m]; the ratio is 1 at position m). */
+static double ref_mlp_value(const double *out, const float *mdc, int32_t n, int32_t m, int64_t b)
+{
+    double u = ((double)(b - m) * 64.0) / (double)(n - 1 - m);      /* in (0, 64] */
+    int j0 = (int)floor(u);
+    if (j0 > 64)
+        j0 = 64;
+    double frac = u - (double)j0;
+    double v0 = j0 == 0 ? 0.0 : out[j0 - 1];
+    double v1 = j0 >= 64 ? out[63] : out[j0];
+    double y = v0 + frac * (v1 - v0);
+    return (double)mdc[m] * ref_exp_fixed(y);
+}
+
 /*
  * Curve estimator and segment thresholds (Section 4.1 step 1, Eq. 1, with the
  * power-function estimator of Appendix A.3; Section 4.1 step 2 and Alg. 2 line
@@ -209,6 +312,9 @@ int ref_mdps_thresholds(const float *mdc, int32_t n, int32_t m,
         a += (double)mdc[i] * ref_pow_int_base(i, e);
     a = a / (double)W;
     double bias2 = (double)prm->bias * (double)prm->bias;
+    double mlp_out[64];
+    if (prm->mlp && ref_mlp_curve(mdc, m, prm->mlp, mlp_out) != 0)
+        return -1;
     for (int32_t l = 1; l <= prm->nseg; ++l) {
         int64_t b = ((int64_t)n * l) / prm->nseg;
         if (b < 1)
@@ -218,6 +324,8 @@ int ref_mdps_thresholds(const float *mdc, int32_t n, int32_t m,
         float r;
         if (b <= m)
             r = mdc[b];
+        else if (prm->mlp)
+            r = (float)((bias2 * (double)prm->level_scale[l - 1]) * ref_mlp_value(mlp_out, mdc, n, m, b));
         else
             r = (float)(((bias2 * (double)prm->level_scale[l - 1]) * a) / ref_pow_int_base(b, e));
         if (!(r >= FLT_MIN))

@@ -23,7 +23,11 @@ class _Params(ctypes.Structure):
     _fields_ = [("p", ctypes.c_float), ("nseg", ctypes.c_int32), ("exponent", ctypes.c_double),
                 ("bias", ctypes.c_float), ("fit_window", ctypes.c_int32), ("m_min", ctypes.c_int32),
                 ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG),
-                ("level_scale", ctypes.c_float * MAX_SEG)]
+                ("level_scale", ctypes.c_float * MAX_SEG),
+                ("mlp", ctypes.POINTER(ctypes.c_float))]
+
+
+MLP_WEIGHTS = 32 * 128 + 128 + 128 * 128 + 128 + 128 * 64 + 64
 
 
 class _Info(ctypes.Structure):
@@ -43,9 +47,15 @@ class MdpsParams:
     m_min: int = 8
     thr_override: Optional[Sequence[float]] = None
     level_scale: Optional[Sequence[float]] = None
+    mlp: Optional[np.ndarray] = None      # MLP_WEIGHTS float32 weights of the MLP estimator, or None
 
     def to_c(self) -> _Params:
         c = _Params()
+        if self.mlp is not None:
+            w = np.ascontiguousarray(self.mlp, dtype=np.float32).reshape(-1)
+            assert w.shape[0] == MLP_WEIGHTS
+            c._keep = w                      # the structure only holds a pointer
+            c.mlp = w.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
         for i in range(MAX_SEG):
             c.level_scale[i] = 1.0
         if self.level_scale is not None:
@@ -85,6 +95,11 @@ def lib() -> ctypes.CDLL:
         _lib.ref_fps_exact.argtypes = [fp, i32, i32, i32, ip, fp]
         _lib.ref_pow_int_base.argtypes = [ctypes.c_int64, ctypes.c_double]
         _lib.ref_pow_int_base.restype = ctypes.c_double
+        _lib.ref_ln_fixed.argtypes = [ctypes.c_double]
+        _lib.ref_ln_fixed.restype = ctypes.c_double
+        _lib.ref_exp_fixed.argtypes = [ctypes.c_double]
+        _lib.ref_exp_fixed.restype = ctypes.c_double
+        _lib.ref_mlp_curve.argtypes = [fp, i32, fp, ctypes.POINTER(ctypes.c_double)]
         _lib.ref_mdps_prefix_len.argtypes = [ctypes.POINTER(_Params), i32]
         _lib.ref_mdps_thresholds.argtypes = [fp, i32, i32, ctypes.POINTER(_Params), fp]
         _lib.ref_mdps_sample.argtypes = [fp, i32, i32, i32, ctypes.POINTER(_Params), ip,
@@ -131,6 +146,26 @@ def fps_exact(xyz, n: int, start: int = 0) -> Tuple[np.ndarray, np.ndarray]:
 def pow_int_base(x: int, e: float) -> float:
     """x^e for an integer x >= 1 by the oracle's fixed-order series."""
     return float(lib().ref_pow_int_base(int(x), float(e)))
+
+
+def ln_fixed(v: float) -> float:
+    return float(lib().ref_ln_fixed(float(v)))
+
+
+def exp_fixed(y: float) -> float:
+    return float(lib().ref_exp_fixed(float(y)))
+
+
+def mlp_curve(mdc, m: int, weights) -> np.ndarray:
+    """Output layer of the MLP estimator (64 log-ratios) for the prefix curve mdc[0..m]."""
+    a = np.ascontiguousarray(mdc, dtype=np.float32)
+    w = np.ascontiguousarray(weights, dtype=np.float32).reshape(-1)
+    assert w.shape[0] == MLP_WEIGHTS and a.shape[0] >= m + 1
+    out = np.empty(64, dtype=np.float64)
+    rc = lib().ref_mlp_curve(_f(a), m, _f(w), out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    if rc != 0:
+        raise ValueError("ref_mlp_curve rejected its arguments")
+    return out
 
 
 def mdps_prefix_len(prm: MdpsParams, n: int) -> int:
