@@ -56,7 +56,19 @@ typedef struct fp_mdps_params {
     float   thr_override[FP_MAX_SEG]; /* squared thresholds R_l^2, l = 1..nseg, non-increasing */
     float   level_scale[FP_MAX_SEG];  /* offline per-segment correction multiplying the predicted
                                          SQUARED value of segment l (> 0; 1 = pure power function) */
+    const float* mlp_weights; /* NULL: power-function estimator.  Else a DEVICE pointer to the
+                                 FP_MLP_WEIGHTS binary32 weights of the MLP estimator of Appendix
+                                 A.3, a perceptron 32-128-128-64 with ReLU after the two hidden
+                                 layers, input-major: W1[32][128] b1[128] W2[128][128] b2[128]
+                                 W3[128][64] b3[64].  Input k = ln(curve[i_k] / curve[m]) with
+                                 i_k = max(1, floor(m (k+1) / 32)); output j = ln(curve(x_j) /
+                                 curve[m]) at x_j = m + (n-1-m)(j+1)/64, interpolated linearly
+                                 between the x_j; binary64 arithmetic in a fixed order, so the
+                                 thresholds are reproducible bit for bit.  exponent and fit_window
+                                 are then unused; bias and level_scale still apply. */
 } fp_mdps_params;
+
+#define FP_MLP_WEIGHTS (32 * 128 + 128 + 128 * 128 + 128 + 128 * 64 + 64)
 
 /* Per-cloud record written by the sampler kernels (device memory, [B], optional). */
 typedef struct fp_mdps_info {

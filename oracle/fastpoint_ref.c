@@ -201,11 +201,16 @@ double ref_ln_fixed(double v)
     return ((double)k * LN2) + ((2.0 * s) * sum);
 }
 
-/* exp y for |y| < 700, fixed order: y = q ln2 + r, q = round(y / ln2), exp r by 20 terms of
- * its Taylor series, times 2^q. */
+/* exp y, fixed order: y = q ln2 + r, q = round(y / ln2), exp r by 20 terms of its Taylor
+ * series, times 2^q.  y is first brought into [-700, 700] (NaN counts as -700), so that
+ * the scaling by 2^q is exact and defined for whatever a network puts out. */
 double ref_exp_fixed(double y)
 {
     const double LN2 = 0.6931471805599453;
+    if (!(y >= -700.0))
+        y = -700.0;
+    if (y > 700.0)
+        y = 700.0;
     double q = floor(y / LN2 + 0.5);
     double r = y - q * LN2;
     double acc = 1.0;
@@ -239,7 +244,10 @@ int ref_mlp_curve(const float *mdc, int32_t m, const float *w, double *out)
         int64_t i = ((int64_t)m * (k + 1)) / 32;
         if (i < 1)
             i = 1;
-        in[k] = ref_ln_fixed((double)mdc[i] / (double)mdc[m]);
+        /* a curve never rises, so the ratio is >= 1; anything else (mdc[m] = 0: all
+         * remaining points coincide with samples) reads as 0 */
+        double ratio = (double)mdc[i] / (double)mdc[m];
+        in[k] = (ratio >= 1.0 && ratio <= 1e300) ? ref_ln_fixed(ratio) : 0.0;
     }
     const float *W1 = w, *b1 = W1 + 32 * 128, *W2 = b1 + 128, *b2 = W2 + 128 * 128;
     const float *W3 = b2 + 128, *b3 = W3 + 128 * 64;

@@ -27,7 +27,10 @@ class FpMdpsParams(ctypes.Structure):
     _fields_ = [("p", ctypes.c_float), ("nseg", ctypes.c_int32), ("exponent", ctypes.c_double),
                 ("bias", ctypes.c_float), ("fit_window", ctypes.c_int32), ("m_min", ctypes.c_int32),
                 ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG),
-                ("level_scale", ctypes.c_float * MAX_SEG)]
+                ("level_scale", ctypes.c_float * MAX_SEG), ("mlp_weights", ctypes.c_void_p)]
+
+
+MLP_WEIGHTS = 32 * 128 + 128 + 128 * 128 + 128 + 128 * 64 + 64
 
 
 class FpMdpsInfo(ctypes.Structure):
@@ -53,9 +56,15 @@ class MdpsParams:
     m_min: int = 8
     thr_override: Optional[Sequence[float]] = None
     level_scale: Optional[Sequence[float]] = None
+    mlp: Optional[torch.Tensor] = None    # MLP_WEIGHTS float32 weights on the device: the MLP estimator
 
     def to_c(self) -> FpMdpsParams:
         c = FpMdpsParams()
+        if self.mlp is not None:
+            if not (self.mlp.is_cuda and self.mlp.dtype == torch.float32 and self.mlp.is_contiguous()
+                    and self.mlp.numel() == MLP_WEIGHTS):
+                raise ValueError("mlp must be a contiguous CUDA float32 tensor of MLP_WEIGHTS values")
+            c.mlp_weights = self.mlp.data_ptr()
         for i in range(MAX_SEG):
             c.level_scale[i] = 1.0
         if self.level_scale is not None:

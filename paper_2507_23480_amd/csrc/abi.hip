@@ -171,6 +171,7 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         a.use_override = prm->use_override ? 1 : 0;
         a.exponent = prm->exponent;
         a.bias2 = (double)prm->bias * (double)prm->bias;
+        a.mlp = prm->use_override ? nullptr : prm->mlp_weights;
     }
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
     a.ll_pk = reinterpret_cast<uint64_t*>(workspace);

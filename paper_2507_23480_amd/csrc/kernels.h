@@ -53,6 +53,7 @@ struct SamplerArgs {
     uint64_t* ll_pk;                // [groups][2][G][kLlSlotWords]
     uint64_t* ll_cd;                // [groups][2][G][kCandPerRound][kCandWords]
     int64_t wait_ticks;
+    const float* mlp;               // weights of the MLP curve estimator, or NULL (power function)
     const float4* sorted;           // cell-ordered variant: [B][N] records (x, y, z, index bits), else NULL
 };
 

@@ -233,6 +233,9 @@ struct Shared {
     Cand cand[kCand];
     Cand pend[kCand];
     int32_t bl[FP_MAX_SEG];    // segment boundaries b_l (curve positions that become thresholds)
+    int32_t mlp_pos[32];       // MLP estimator: curve positions i_k of its 32 inputs (-1: not in use)
+    float mlp_val[32];         // ... the curve there
+    double mlp_a[128], mlp_b[128];   // ... activations of successive layers
     int32_t gpre[kMaxGroup + 1];
     int32_t ctrl[4];      // [0] accepted picks of the round, [1] points passing in the cloud,
                           // [2] failure, [3] distance bits of the last accepted pick
@@ -580,6 +583,52 @@ __device__ __forceinline__ void refresh_bound(Points<P, BQ>& pt)
     pt.ub = wave_max_u32(m);
 }
 
+// ln v for a normal positive binary64 v and exp y, with + - * / only in a fixed order (the steps
+// pow_int_base is made of): a CPU reference performing the same operations gets the same bits.
+__device__ __noinline__ double ln_fixed(double v)
+{
+    const double LN2 = 0.6931471805599453;
+    const long long bits = __double_as_longlong(v);
+    int k = (int)((bits >> 52) & 0x7FF) - 1023;
+    double f = __longlong_as_double((bits & 0x000FFFFFFFFFFFFFll) | (1023ll << 52));   // in [1,2)
+    if (f > 1.4142135623730951) {
+        f = f * 0.5;
+        k = k + 1;
+    }
+    const double s = (f - 1.0) / (f + 1.0);
+    const double s2 = s * s;
+    double sum = 0.0;
+#pragma unroll 1
+    for (int t = 12; t >= 0; --t) sum = sum * s2 + 1.0 / (double)(2 * t + 1);
+    return ((double)k * LN2) + ((2.0 * s) * sum);
+}
+__device__ __noinline__ double exp_fixed(double y)
+{
+    const double LN2 = 0.6931471805599453;
+    if (!(y >= -700.0)) y = -700.0;
+    if (y > 700.0) y = 700.0;
+    const double q = floor(y / LN2 + 0.5);
+    const double r = y - q * LN2;
+    double acc = 1.0;
+#pragma unroll 1
+    for (int t = 20; t >= 1; --t) acc = 1.0 + acc * (r / (double)t);
+    return acc * __longlong_as_double((long long)(1023 + (int)q) << 52);
+}
+
+// One layer of the MLP estimator: neuron `o` (of NOUT) starts from its bias and adds the products
+// with the NIN inputs in ascending order; weights input-major, so the threads of a wave read
+// adjacent words.
+template <int NIN, int NOUT, bool RELU>
+__device__ __forceinline__ void mlp_layer(const float* __restrict__ w, const float* __restrict__ bias,
+                                          const double* in, double* out, int o)
+{
+    if (o >= NOUT) return;
+    double acc = (double)bias[o];
+#pragma unroll 4
+    for (int k = 0; k < NIN; ++k) acc = acc + (double)w[k * NOUT + o] * in[k];
+    out[o] = (RELU && !(acc > 0.0)) ? 0.0 : acc;
+}
+
 // Folds the picks waiting in sh.pend (sample positions base, base+1, ...) into the distances.
 template <int T, int P, bool BQ, bool PERM>
 __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
@@ -682,6 +731,7 @@ __device__ __forceinline__ void capture_curve(Shared<T>& sh, const Where& wh, co
 {
     if (wh.tid == 0) sh.ring[pos & 63] = d;
     if (st.my_bl == pos) sh.thr_meas[wh.tid] = d;
+    if (wh.tid < 32 && sh.mlp_pos[wh.tid] == pos) sh.mlp_val[wh.tid] = d;
 }
 
 // One plain iteration of Alg. 1 (lines 4-8) on distances that are already up to date:
@@ -952,6 +1002,9 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
             sh.ring[pos & 63] = d;
             for (int l = 0; l < nseg; ++l)
                 if (sh.bl[l] == pos) sh.thr_meas[l] = d;
+            if (sh.mlp_pos[0] >= 0)
+                for (int k = 0; k < 32; ++k)
+                    if (sh.mlp_pos[k] == pos) sh.mlp_val[k] = d;
         }
     }
     if (wh.lane == 0) {
@@ -1100,6 +1153,11 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         }
     }
     if (wh.tid < kCand + 2) sh.live[wh.tid] = 0;       // round tags start at 1 in every cloud
+    if (wh.tid < 32) {
+        int64_t ik = ((int64_t)a.m * (wh.tid + 1)) / 32;
+        sh.mlp_pos[wh.tid] = a.mlp ? (int)(ik < 1 ? 1 : ik) : -1;
+        sh.mlp_val[wh.tid] = 0.0f;
+    }
     if (wh.tid < FP_MAX_SEG) {
         sh.level_start[wh.tid] = -1;
         sh.level_exhausted[wh.tid] = 0;
@@ -1148,6 +1206,51 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         __syncthreads();
         if (a.use_override) {
             if (wh.tid < a.nseg) sh.thr[wh.tid] = a.thr_override[wh.tid];
+        } else if (a.mlp) {
+            // ---- MLP estimator (Appendix A.3): 32 log-ratios of the prefix curve in, 64 log-ratios
+            //      of the rest of the curve out; every workgroup of the cloud computes the same
+            const float* __restrict__ W1 = a.mlp;
+            const float* __restrict__ b1 = W1 + 32 * 128;
+            const float* __restrict__ W2 = b1 + 128;
+            const float* __restrict__ b2 = W2 + 128 * 128;
+            const float* __restrict__ W3 = b2 + 128;
+            const float* __restrict__ b3 = W3 + 128 * 64;
+            const double last = (double)sh.ring[m & 63];
+            if (wh.tid < 32) {
+                const double ratio = (double)sh.mlp_val[wh.tid] / last;
+                sh.mlp_a[wh.tid] = (ratio >= 1.0 && ratio <= 1e300) ? ln_fixed(ratio) : 0.0;
+            }
+            __syncthreads();
+            mlp_layer<32, 128, true>(W1, b1, sh.mlp_a, sh.mlp_b, wh.tid);
+            __syncthreads();
+            mlp_layer<128, 128, true>(W2, b2, sh.mlp_b, sh.mlp_a, wh.tid);
+            __syncthreads();
+            mlp_layer<128, 64, false>(W3, b3, sh.mlp_a, sh.mlp_b, wh.tid);
+            __syncthreads();
+            if (wh.tid < a.nseg) {
+                // the estimated curve at this level's boundary: the outputs interpolated linearly
+                const int l = wh.tid;
+                const int64_t b = boundary_index(n, a.nseg, l + 1);
+                float r;
+                if (b <= m) {
+                    r = sh.thr_meas[l];
+                } else {
+                    const double u = ((double)(b - m) * 64.0) / (double)(n - 1 - m);
+                    int j0 = (int)floor(u);
+                    if (j0 > 64) j0 = 64;
+                    const double frac = u - (double)j0;
+                    const double v0 = j0 == 0 ? 0.0 : sh.mlp_b[j0 - 1];
+                    const double v1 = j0 >= 64 ? sh.mlp_b[63] : sh.mlp_b[j0];
+                    const double y = v0 + frac * (v1 - v0);
+                    r = (float)((a.bias2 * (double)a.level_scale[l]) * (last * exp_fixed(y)));
+                }
+                if (!(r >= 1.17549435e-38f)) r = 1.17549435e-38f;
+                sh.thr[l] = r;
+            }
+            __syncthreads();
+            if (wh.tid == 0)
+                for (int l = 1; l < a.nseg; ++l)
+                    if (sh.thr[l] > sh.thr[l - 1]) sh.thr[l] = sh.thr[l - 1];
         } else {
             const int W = a.fit_window < m ? a.fit_window : m;
             if (wh.tid < W) {

@@ -1,0 +1,215 @@
+"""Offline training of the MLP curve estimator (Appendix A.3 of the paper) per workload stage.
+
+The paper trains a three-layer perceptron 32-128-128-64 on the minimum distance curves of a
+data set's training split (SGD, learning rate 0.01, batch size 1, 20-30 epochs).  Here the
+"training split" is a set of clouds from the same seeded generators as the workloads, with
+seeds of their own (the calibration seeds); the workloads' own clouds are the test split.
+The curves come from exact FPS through the HIP library; the network is trained with plain
+PyTorch on the CPU and stored as binary32 in the layout the library reads
+(input-major: W1[32][128] b1[128] W2[128][128] b2[128] W3[128][64] b3[64]).
+
+Representation (the library's, include/fastpoint.h): input k = ln(curve[i_k] / curve[m]),
+i_k = max(1, floor(m (k+1) / 32)); target j = ln(curve(x_j) / curve[m]) at
+x_j = m + (n-1-m)(j+1)/64, the curve interpolated linearly in the logarithm between positions.
+
+After training, `bias` is searched as for the power-function estimator: the smallest factor
+for which the last level is exhausted on every training cloud and the coverage radius stays
+within 1.03x of exact FPS, plus a margin.
+
+Run  python -m paper_2507_23480_amd.mlp_estimator [C1 C2 ...]  on a GPU machine; it rewrites
+mlp_estimator.npz / mlp_estimator.json next to this file (or under $FASTPOINT_MLP_OUT).
+"""
+from __future__ import annotations
+
+import json
+import math
+import os
+import sys
+from typing import Dict, List
+
+import numpy as np
+
+from . import calibration
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+WEIGHTS_PATH = os.path.join(HERE, "mlp_estimator.npz")
+TABLE_PATH = os.path.join(HERE, "mlp_estimator.json")
+TRAINING_CLOUDS = {"C1": 192, "C2": 384, "C3": 64, "C4": 32, "C5": 10}
+EPOCHS = 30
+LEARNING_RATE = 0.01
+SIZES = [(32, 128), (128,), (128, 128), (128,), (128, 64), (64,)]
+
+_weights = None
+_table = None
+_device_cache = {}
+
+
+def prefix_len(n: int) -> int:
+    return max(int(math.floor(calibration.P_RATIO * n)), calibration.M_MIN)
+
+
+def representation(curves: np.ndarray, n: int, m: int):
+    """(inputs [B][32], targets [B][64]) of curves [B][n] (squared distances, entry 0 unused)."""
+    c = np.log(np.maximum(curves[:, 1:].astype(np.float64), 1e-300))      # c[:, i-1] = ln curve[i]
+    ik = np.maximum(1, (m * np.arange(1, 33)) // 32)
+    x = c[:, ik - 1] - c[:, m - 1:m]
+    xj = m + (n - 1 - m) * np.arange(1, 65) / 64.0
+    lo = np.floor(xj).astype(np.int64)
+    hi = np.minimum(lo + 1, n - 1)
+    f = xj - lo
+    y = (1 - f) * c[:, lo - 1] + f * c[:, hi - 1] - c[:, m - 1:m]
+    return x, y
+
+
+def train(x: np.ndarray, y: np.ndarray, seed: int = 0, log=print) -> np.ndarray:
+    import torch
+    torch.manual_seed(seed)
+    net = torch.nn.Sequential(torch.nn.Linear(32, 128), torch.nn.ReLU(), torch.nn.Linear(128, 128),
+                              torch.nn.ReLU(), torch.nn.Linear(128, 64)).double()
+    opt = torch.optim.SGD(net.parameters(), lr=LEARNING_RATE)
+    xt, yt = torch.from_numpy(x), torch.from_numpy(y)
+    gen = torch.Generator().manual_seed(seed)
+    for ep in range(EPOCHS):
+        tot = 0.0
+        for i in torch.randperm(xt.shape[0], generator=gen).tolist():     # batch size 1
+            opt.zero_grad()
+            loss = torch.nn.functional.mse_loss(net(xt[i:i + 1]), yt[i:i + 1])
+            loss.backward()
+            opt.step()
+            tot += float(loss)
+        if ep % 10 == 9 or ep == EPOCHS - 1:
+            log("    epoch %d: mean squared error of the log-ratios %.3e" % (ep + 1, tot / xt.shape[0]))
+    lin = [mod for mod in net if isinstance(mod, torch.nn.Linear)]
+    parts = []
+    for mod in lin:                      # torch keeps [out][in]; the library reads [in][out]
+        parts.append(mod.weight.detach().numpy().T.astype(np.float32).reshape(-1))
+        parts.append(mod.bias.detach().numpy().astype(np.float32))
+    return np.concatenate(parts)
+
+
+def forward(w: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """The network in numpy binary64 (for error statistics only)."""
+    off = 0
+    arrs = []
+    for s in SIZES:
+        k = int(np.prod(s))
+        arrs.append(w[off:off + k].astype(np.float64).reshape(s))
+        off += k
+    W1, b1, W2, b2, W3, b3 = arrs
+    h = np.maximum(x @ W1 + b1, 0.0)
+    h = np.maximum(h @ W2 + b2, 0.0)
+    return h @ W3 + b3
+
+
+def mape(w: np.ndarray, x: np.ndarray, y: np.ndarray) -> float:
+    """Mean absolute percentage error of the predicted curve (squared distances -> distances)."""
+    pred = forward(w, x)
+    return float(np.mean(np.abs(np.exp(0.5 * (pred - y)) - 1.0)) * 100.0)
+
+
+def weights() -> Dict[str, np.ndarray]:
+    global _weights
+    if _weights is None:
+        with np.load(WEIGHTS_PATH) as f:
+            _weights = {k: f[k] for k in f.files}
+    return _weights
+
+
+def table() -> Dict[str, List[dict]]:
+    global _table
+    if _table is None:
+        with open(TABLE_PATH) as f:
+            _table = json.load(f)
+    return _table
+
+
+def params_for(workload: str, stage: int):
+    """MdpsParams that use the trained MLP estimator of one workload stage."""
+    import torch
+    from . import binding
+    key = "%s/%d" % (workload, stage)
+    if key not in _device_cache:
+        _device_cache[key] = torch.from_numpy(weights()[key]).cuda()
+    ent = table()[workload][stage]
+    return binding.MdpsParams(p=calibration.P_RATIO, nseg=calibration.NSEG, bias=ent["bias"],
+                              m_min=calibration.M_MIN, mlp=_device_cache[key])
+
+
+def fit_stage(xyz, n: int, test_xyz, log=print):
+    import torch
+    from . import binding as fp
+    idx, mdc = fp.fps_exact(xyz, n, want_mdc=True)
+    _, tmdc = fp.fps_exact(test_xyz, n, want_mdc=True)
+    torch.cuda.synchronize()
+    N = xyz.shape[1]
+    m = prefix_len(n)
+    if m >= n - 1:
+        return None, {"N": int(N), "n": int(n), "bias": 1.0, "pure_fps": True}
+    x, y = representation(mdc.cpu().numpy(), n, m)
+    tx, ty = representation(tmdc.cpu().numpy(), n, m)
+    w = train(x, y, log=log)
+    ent = {"N": int(N), "n": int(n), "training_clouds": int(xyz.shape[0]),
+           "mape_percent_training": round(mape(w, x, y), 3), "mape_percent_workload": round(mape(w, tx, ty), 3)}
+    log("    MAPE of the estimated curve: %.2f %% on the training clouds, %.2f %% on the workload's clouds"
+        % (ent["mape_percent_training"], ent["mape_percent_workload"]))
+    wd = torch.from_numpy(w).cuda()
+    cov_fps = fp.coverage2(xyz, idx).sqrt()
+    bias = 1.0
+    while True:
+        prm = fp.MdpsParams(p=calibration.P_RATIO, nseg=calibration.NSEG, bias=bias, m_min=calibration.M_MIN,
+                            mlp=wd)
+        midx, info = fp.mdps_sample(xyz, n, prm, want_info=True)
+        cov = fp.coverage2(xyz, midx).sqrt()
+        torch.cuda.synchronize()
+        infos = fp.parse_info(info)
+        exhausted = all(i.level_exhausted[calibration.NSEG - 1] == 1 or i.et_index < n for i in infos)
+        worst = float((cov / cov_fps).max())
+        tail = float(np.mean([(n - i.et_index) / n for i in infos]))
+        if (exhausted and worst <= 1.03) or bias >= 1.5:
+            break
+        bias = round(bias + 0.01, 2)
+    log("    bias %.2f: worst coverage ratio %.4f, mean FPS tail %.1f %%" % (bias, worst, 100 * tail))
+    ent.update({"bias": round(bias + calibration.BIAS_MARGIN, 2), "bias_found": bias,
+                "training_tail_mean": round(tail, 4), "training_worst_coverage_ratio": round(worst, 4)})
+    return w, ent
+
+
+def train_workload(name: str, log=print):
+    import torch
+    from . import binding as fp, inputs
+    wl = inputs.WORKLOADS[name]
+    Bc = TRAINING_CLOUDS[name]
+    xyz = torch.from_numpy(inputs.make_batch(name, B=Bc, calibration=True)).cuda()
+    test = torch.from_numpy(inputs.make_batch(name)).cuda()
+    ws, ents = {}, []
+    for s, st in enumerate(wl.stages):
+        log("%s stage %d: %d training clouds of %d points -> %d samples" % (name, s, Bc, xyz.shape[1], st.n))
+        w, ent = fit_stage(xyz, st.n, test, log)
+        if w is not None:
+            ws["%s/%d" % (name, s)] = w
+        ents.append(ent)
+        if s + 1 < len(wl.stages):
+            xyz = fp.gather_xyz(xyz, fp.fps_exact(xyz, st.n)).contiguous()
+            test = fp.gather_xyz(test, fp.fps_exact(test, st.n)).contiguous()
+    return ws, ents
+
+
+def main(argv: List[str]) -> int:
+    names = argv or list(TRAINING_CLOUDS)
+    out_dir = os.environ.get("FASTPOINT_MLP_OUT", HERE)
+    all_w = dict(weights()) if os.path.exists(WEIGHTS_PATH) else {}
+    tab = dict(table()) if os.path.exists(TABLE_PATH) else {}
+    for name in names:
+        ws, ents = train_workload(name)
+        all_w.update(ws)
+        tab[name] = ents
+        np.savez(os.path.join(out_dir, "mlp_estimator.npz"), **all_w)
+        with open(os.path.join(out_dir, "mlp_estimator.json"), "w") as f:
+            json.dump(tab, f, indent=1, sort_keys=True)
+            f.write("\n")
+    print("wrote", out_dir)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv[1:]))
