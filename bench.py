@@ -108,7 +108,7 @@ def make_context(torch, fp, inputs, calibration, name):
                        "ws": [fp.new_workspace(xyz.device, B, N), fp.new_workspace(xyz.device, B, N)]})
         N = st.n
     torch.cuda.synchronize()
-    return {"wl": wl, "stages": stages, "xyz": xyz, "side": torch.cuda.Stream()}
+    return {"wl": wl, "name": name, "stages": stages, "xyz": xyz, "side": torch.cuda.Stream()}
 
 
 def run_step(fp, ctx, timer, keep=None):
@@ -281,6 +281,20 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         roof["fps_exact_pruned"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
                                     "frac": a / ALU_PEAK_TOPS, "equals_fps_exact": True,
                                     "note": "algorithmic operations of the unpruned update / time"}
+        # MDPS with the MLP curve estimator of Appendix A.3 in place of the power function
+        # (outside the timed step): latency and sampling quality
+        from paper_2507_23480_amd import mlp_estimator
+        mprm = mlp_estimator.params_for(ctx["name"], s)
+        ml = time_call(torch, lambda: fp.mdps_sample(x, n, mprm, want_info=True))
+        mcov = fp.coverage2(x, ml[1][0]).sqrt() / cov_f
+        torch.cuda.synchronize()
+        minfos = fp.parse_info(ml[1][1])
+        ms["mdps_sample_mlp"] = ml[0]
+        mlp_detail = {"coverage_ratio_max": float(mcov.max()), "coverage_ratio_mean": float(mcov.mean()),
+                      "fps_tail_fraction_mean": float(sum((n - i.et_index) / n for i in minfos) / len(minfos)),
+                      "last_level_exhausted": int(sum(1 for i in minfos if i.et_index < n)),
+                      "curve_mape_percent": mlp_estimator.table()[ctx["name"]][s].get("mape_percent_workload"),
+                      "bias": mprm.bias}
         ex = time_excl_lists(torch, fp, x, sg, infos, midx, mbq)
         if ex is not None:
             ms["excl_lists_count"], ms["excl_lists_fill"] = ex["count_ms"], ex["fill_ms"]
@@ -300,6 +314,7 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             "mdps_last_level_exhausted": int(sum(1 for i in infos if i.et_index < n)),
             "mdps_speedup_vs_fps": ms.get("fps_exact", 0.0) / ms["mdps_sample+record"] if ms.get("mdps_sample+record") else None,
             "cached_ball_query_equals_brute": cached_equal,
+            "mdps_mlp_estimator": mlp_detail,
             "roofline": roof})
     return out
 

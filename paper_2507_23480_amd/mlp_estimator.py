@@ -76,7 +76,7 @@ def train(x: np.ndarray, y: np.ndarray, seed: int = 0, log=print) -> np.ndarray:
             loss = torch.nn.functional.mse_loss(net(xt[i:i + 1]), yt[i:i + 1])
             loss.backward()
             opt.step()
-            tot += float(loss)
+            tot += float(loss.detach())
         if ep % 10 == 9 or ep == EPOCHS - 1:
             log("    epoch %d: mean squared error of the log-ratios %.3e" % (ep + 1, tot / xt.shape[0]))
     lin = [mod for mod in net if isinstance(mod, torch.nn.Linear)]

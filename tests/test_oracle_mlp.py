@@ -145,3 +145,23 @@ def test_sampling_with_the_mlp_equals_the_literal_transcription():
     b, ib = ref.mdps_literal(xyz, 200, prm)
     assert np.array_equal(a, b) and np.array_equal(ia.thr2, ib.thr2)
     assert len(set(a.tolist())) == 200
+
+
+def test_committed_weights_predict_the_curves_of_a_workload():
+    """The trained estimator of the object-classification stage on that workload's own clouds
+    (the test split of the training), curves from the oracle's exact FPS: the error of the
+    estimated curve stays in the range reported when it was trained, and the training module's
+    numpy network is the oracle's network."""
+    from paper_2507_23480_amd import inputs, mlp_estimator
+    wl = inputs.WORKLOADS["C2"]
+    n = wl.stages[0].n
+    m = mlp_estimator.prefix_len(n)
+    w = mlp_estimator.weights()["C2/0"]
+    batch = inputs.make_batch("C2")
+    curves = np.stack([ref.fps_exact(batch[b], n)[1] for b in range(wl.B)])
+    x, y = mlp_estimator.representation(curves, n, m)
+    assert mlp_estimator.mape(w, x, y) < 6.0
+    for b in range(3):
+        out = ref.mlp_curve(curves[b], m, w)
+        assert np.allclose(out, mlp_estimator.forward(w, x[b:b + 1])[0], rtol=1e-9, atol=1e-11)
+    assert mlp_estimator.table()["C2"][0]["mape_percent_workload"] < 6.0
