@@ -830,20 +830,38 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     }
     if (wh.tid == 0) ll_store(pk + (int64_t)wh.g * kLlSlotWords + 5, (uint32_t)tot, seq);
     __syncthreads();          // sh.cand is about to be overwritten
+    // More than 64 workgroups: thread t waits for the count of workgroup t, so that all waits
+    // are in flight together, and hands it over in LDS.  Up to 64: the lanes of wave 0 wait
+    // themselves (one count each), which saves the barrier.
+    const bool spread = wh.G > 64;
+    if (spread) {
+        if (wh.tid < wh.G) {
+            uint32_t val[1];
+            const bool got = ll_wait<1>(pk + (int64_t)wh.tid * kLlSlotWords + 5, seq, val, a.wait_ticks);
+            sh.gpre[wh.tid + 1] = got ? (int)val[0] : -1;
+        }
+        __syncthreads();
+    }
     if (wh.w == 0) {
-        // lane t takes the counts of workgroups [t*per, (t+1)*per)
+        // lane t adds up the counts of workgroups [t*per, (t+1)*per)
         const int per = (wh.G + 63) / 64;
         int sum = 0, usum = 0;
         bool bad = false;
         for (int k = 0; k < per; ++k) {
             const int t = wh.lane * per + k;
             if (t < wh.G) {
-                uint32_t val[1];
-                if (!ll_wait<1>(pk + (int64_t)t * kLlSlotWords + 5, seq, val, a.wait_ticks)) {
+                int v;
+                if (spread) {
+                    v = sh.gpre[t + 1];
+                } else {
+                    uint32_t val[1];
+                    v = ll_wait<1>(pk + (int64_t)t * kLlSlotWords + 5, seq, val, a.wait_ticks) ? (int)val[0] : -1;
+                }
+                if (v < 0) {
                     bad = true;
                 } else {
-                    usum += (int)val[0];
-                    sum += (int)val[0] < kCand ? (int)val[0] : kCand;
+                    usum += v;
+                    sum += v < kCand ? v : kCand;
                 }
                 sh.gpre[t + 1] = sum;      // inclusive inside the lane, fixed below
             }
