@@ -233,6 +233,7 @@ struct Shared {
     Cand cand[kCand];
     Cand pend[kCand];
     int32_t bl[FP_MAX_SEG];    // segment boundaries b_l (curve positions that become thresholds)
+    int32_t qend[FP_MAX_SEG + 1];   // qend[l] = ceil(n l / nseg): the quota rule raises the level to l + 1 there
     int32_t mlp_pos[32];       // MLP estimator: curve positions i_k of its 32 inputs (-1: not in use)
     float mlp_val[32];         // ... the curve there
     double mlp_a[128], mlp_b[128];   // ... activations of successive layers
@@ -1302,19 +1303,26 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #endif
 
         // ---- threshold sampling (Alg. 2 lines 24-37), running-distance form
+        // The quota rule (line 22) puts sample position i on level 1 + floor(i nseg / n), i.e. on a
+        // level above l as soon as i >= ceil(n l / nseg): the positions are tabulated once, a round
+        // then compares with the one that ends its level.
+        if (wh.tid <= a.nseg) sh.qend[wh.tid] = (int32_t)(((int64_t)n * wh.tid + a.nseg - 1) / a.nseg);
+        __syncthreads();
+        int level_end = 0;                 // qend[seg]: first position the quota rule puts above level seg
         while (st.i < n) {
             flush_picks<T, BQ>(a, sh, wh, st.flushed, st.i, false);
-            const int q = 1 + (int)(((int64_t)st.i * a.nseg) / n);
-            if (q > seg) {
-                seg = q;
+            if (st.i >= level_end) {
+                while (st.i >= level_end) {
+                    ++seg;
+                    level_end = uni(sh.qend[seg]);
+                }
                 if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
             }
             fold_pending<T, P, BQ, PERM>(pt, sh, wh, a, st.npend, st.i - st.npend);   // picks since the last sweep
             st.npend = 0;
             const float r2 = unif(sh.thr[seg - 1]);
             // samples of this level end where the quota rule would raise the level
-            const int64_t qend = ((int64_t)n * seg + a.nseg - 1) / a.nseg;
-            const int limit = (int)((qend < n ? qend : n) - st.i);
+            const int limit = (level_end < n ? level_end : n) - st.i;
             ++st.rounds;
             int alltot = 0;
 #ifdef FASTPOINT_PHASE_CLOCKS
@@ -1333,6 +1341,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 if (wh.tid == 0) sh.level_exhausted[seg - 1] = 1;
                 ++seg;
                 if (seg > a.nseg) break;   // early termination
+                level_end = uni(sh.qend[seg]);
                 if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
                 continue;
             }
@@ -1346,6 +1355,16 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #ifdef FASTPOINT_PHASE_CLOCKS
             st.clk[5] += wall_clock64() - thr_t1;
 #endif
+            if (alltot < kCand && st.i < level_end && st.i < n) {
+                // Every available point of the cloud was a candidate and the quota did not cut the
+                // round short: each one has been accepted or lies within R_l of an accepted one, so
+                // the level is exhausted (Alg. 2 lines 34-36) -- no scan is needed to find that out.
+                if (wh.tid == 0) sh.level_exhausted[seg - 1] = 1;
+                ++seg;
+                if (seg > a.nseg) break;   // early termination
+                level_end = uni(sh.qend[seg]);
+                if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
+            }
         }
 
 #ifdef FASTPOINT_PHASE_CLOCKS
