@@ -154,7 +154,8 @@ fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n,
  *              from the cache with no distance evaluation (redundancy-free ball
  *              query, Section 4.2); any other centre falls back to the brute-
  *              force test inside the same kernel.  Results are identical.
- * A centre index outside [0,N) yields a row of -1 and count 0.
+ * A centre index outside [0,N) yields a row of -1 and count 0.  M = 0 is accepted (the
+ * centre and output pointers may then be NULL).
  */
 fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N,
                         const int32_t* center_idx, int32_t M, float radius, int32_t k,

@@ -284,9 +284,11 @@ fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N, const int32_t* c
                         float radius, int32_t k, int32_t* out_idx, int32_t* out_cnt,
                         const void* bq_cache, void* stream)
 {
-    if (!xyz || !center_idx || !out_idx) return FP_ERR_NULL;
     if (B < 1 || N < 1 || M < 0 || k < 1 || k > 254 || B > 65535) return FP_ERR_SHAPE;
     if (!(radius > 0.0f) || !isfinite(radius)) return FP_ERR_PARAM;
+    if (!xyz) return FP_ERR_NULL;
+    if (M == 0) return FP_OK;                 // no centres: nothing to write, the arrays may be empty
+    if (!center_idx || !out_idx) return FP_ERR_NULL;
     if (bq_cache && (reinterpret_cast<uintptr_t>(bq_cache) & 255u) != 0) return FP_ERR_WORKSPACE;
     const float r2 = radius * radius;
     hipError_t err = launch_ball_query(xyz, B, N, center_idx, M, r2, k, out_idx, out_cnt, bq_cache,
@@ -367,8 +369,10 @@ fp_status fp_ball_query_lists(const int64_t* offsets, const int32_t* entries, in
                               int32_t level, int32_t L, const int32_t* center_idx, int32_t M, int32_t k,
                               int32_t* out_idx, int32_t* out_cnt, void* stream)
 {
-    if (!offsets || !entries || !center_idx || !out_idx) return FP_ERR_NULL;
     if (!excl_shape_ok(B, N, L) || level < 0 || level >= L || M < 0 || k < 1) return FP_ERR_SHAPE;
+    if (!offsets || !entries) return FP_ERR_NULL;
+    if (M == 0) return FP_OK;
+    if (!center_idx || !out_idx) return FP_ERR_NULL;
     hipError_t err = launch_bq_lists(offsets, entries, B, N, level, center_idx, M, k, out_idx, out_cnt,
                                      reinterpret_cast<hipStream_t>(stream));
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
@@ -377,8 +381,10 @@ fp_status fp_ball_query_lists(const int64_t* offsets, const int32_t* entries, in
 fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N, const int32_t* idx, int32_t M,
                         float* out_xyz, void* stream)
 {
-    if (!xyz || !idx || !out_xyz) return FP_ERR_NULL;
     if (B < 1 || N < 1 || M < 0) return FP_ERR_SHAPE;
+    if (!xyz) return FP_ERR_NULL;
+    if (M == 0) return FP_OK;
+    if (!idx || !out_xyz) return FP_ERR_NULL;
     hipError_t err = launch_gather(xyz, B, N, idx, M, out_xyz, reinterpret_cast<hipStream_t>(stream));
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }

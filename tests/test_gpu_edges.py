@@ -1,0 +1,160 @@
+"""Edge cases of the C ABI on the GPU: degenerate and maximum sizes, batches larger than the
+device holds at once, and the error codes of the argument checks (nothing is enqueued on an
+error).  Results against the CPU oracle, bit-exact."""
+import ctypes
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2507_23480_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fp():
+    from paper_2507_23480_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    binding.set_wg_per_cloud(0)
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.mark.parametrize("N,n", [(1, 1), (2, 1), (2, 2), (3, 3), (1000, 1), (1000, 2)])
+def test_smallest_shapes(fp, N, n):
+    cloud = inputs.uniform_cube(N, N)
+    x = dev(cloud[None])
+    want = ref.fps_exact(cloud, n)
+    idx, mdc = fp.fps_exact(x, n, want_mdc=True)
+    pidx = fp.fps_exact_pruned(x, n)
+    midx = fp.mdps_sample(x, n, fp.MdpsParams())            # n this small is exact FPS by definition
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy()[0], want[0]) and np.array_equal(mdc.cpu().numpy()[0], want[1])
+    assert np.array_equal(pidx.cpu().numpy()[0], want[0])
+    assert np.array_equal(midx.cpu().numpy()[0], ref.mdps_sample(cloud, n, ref.MdpsParams())[0])
+    bq, cnt = fp.ball_query(x, idx, 0.5, 3)
+    torch.cuda.synchronize()
+    wbq, wcnt = ref.ball_query(cloud, want[0], 0.5, 3)
+    assert np.array_equal(bq.cpu().numpy()[0], wbq) and np.array_equal(cnt.cpu().numpy()[0], wcnt)
+
+
+def test_more_clouds_than_the_device_holds_at_once(fp):
+    # 300 clouds: the workgroups take further clouds in turn
+    B, N, n = 300, 500, 120
+    batch = np.stack([inputs.uniform_cube(7000 + b, N) for b in range(B)])
+    x = dev(batch)
+    prm = fp.MdpsParams(exponent=0.9, bias=1.1)
+    rp = ref.MdpsParams(exponent=0.9, bias=1.1)
+    idx = fp.fps_exact(x, n).cpu().numpy()
+    pidx = fp.fps_exact_pruned(x, n).cpu().numpy()
+    cache = fp.new_bq_cache(x, n)
+    midx_t = fp.mdps_sample(x, n, prm, bq_cache=cache, bq_radius=0.2)
+    bq, cnt = fp.ball_query(x, midx_t, 0.2, 8, bq_cache=cache)
+    torch.cuda.synchronize()
+    midx = midx_t.cpu().numpy()
+    for b in range(B):
+        want = ref.fps_exact(batch[b], n)[0]
+        assert np.array_equal(idx[b], want), "fps cloud %d" % b
+        assert np.array_equal(pidx[b], want), "pruned fps cloud %d" % b
+        wm = ref.mdps_sample(batch[b], n, rp)[0]
+        assert np.array_equal(midx[b], wm), "mdps cloud %d" % b
+    for b in (0, 131, 299):
+        wbq, wcnt = ref.ball_query(batch[b], midx[b], 0.2, 8)
+        assert np.array_equal(bq[b].cpu().numpy(), wbq) and np.array_equal(cnt[b].cpu().numpy(), wcnt)
+
+
+def test_largest_cloud_the_sampler_takes(fp):
+    # 256 workgroups x 8192 points; one more point is refused
+    N = 256 * 8192
+    say("largest cloud", N)
+    rng = np.random.Generator(np.random.PCG64(99))
+    cloud = rng.uniform(0, 1, (N, 3)).astype(np.float32)
+    x = dev(cloud[None])
+    n = 48
+    want = ref.fps_exact(cloud, n)
+    idx, mdc = fp.fps_exact(x, n, want_mdc=True)
+    pidx = fp.fps_exact_pruned(x, n)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy()[0], want[0]) and np.array_equal(mdc.cpu().numpy()[0], want[1])
+    assert np.array_equal(pidx.cpu().numpy()[0], want[0])
+    lib = fp.load()
+    g, t, p = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    assert lib.fp_plan(1, N, ctypes.byref(g), ctypes.byref(t), ctypes.byref(p)) == 0 and g.value == 256
+    assert lib.fp_plan(1, N + 1, ctypes.byref(g), ctypes.byref(t), ctypes.byref(p)) == -2
+    big = torch.empty((1, N + 1, 3), dtype=torch.float32, device="cuda")
+    out = torch.empty((1, n), dtype=torch.int32, device="cuda")
+    ws = fp.new_workspace(x.device, 1, N)
+    assert lib.fp_fps_exact(big.data_ptr(), 1, N + 1, n, None, out.data_ptr(), None, None, None, 0.0,
+                            ws.data_ptr(), ws.numel(), None) == -2
+
+
+def test_ball_query_limits(fp):
+    cloud = inputs.uniform_cube(4, 300)
+    x = dev(cloud[None])
+    centres = np.arange(0, 300, 3, dtype=np.int32)
+    for radius, k in ((10.0, 254), (10.0, 1), (1e-6, 254), (0.3, 200)):
+        bq, cnt = fp.ball_query(x, dev(centres[None]), radius, k)
+        torch.cuda.synchronize()
+        wbq, wcnt = ref.ball_query(cloud, centres, radius, k)
+        assert np.array_equal(bq.cpu().numpy()[0], wbq) and np.array_equal(cnt.cpu().numpy()[0], wcnt)
+    empty = torch.empty((1, 0), dtype=torch.int32, device="cuda")
+    bq, cnt = fp.ball_query(x, empty, 0.1, 4)
+    torch.cuda.synchronize()
+    assert bq.shape == (1, 0, 4) and cnt.shape == (1, 0)
+
+
+def test_error_codes(fp):
+    lib = fp.load()
+    x = dev(inputs.uniform_cube(1, 200)[None])
+    out = torch.empty((1, 50), dtype=torch.int32, device="cuda")
+    ws = fp.new_workspace(x.device, 1, 200)
+    f = lambda *a: lib.fp_fps_exact(*a)
+    ok = (x.data_ptr(), 1, 200, 50, None, out.data_ptr(), None, None, None, 0.0, ws.data_ptr(), ws.numel(), None)
+    assert f(*ok) == 0
+    assert f(None, *ok[1:]) == -1                                     # xyz
+    assert f(*ok[:5], None, *ok[6:]) == -1                            # out_idx
+    assert f(*ok[:3], 201, *ok[4:]) == -2                             # n > N
+    assert f(*ok[:3], 0, *ok[4:]) == -2                               # n < 1
+    assert f(*ok[:1], 0, *ok[2:]) == -2                               # B < 1
+    assert f(*ok[:10], None, 0, None) == -4                           # no workspace
+    assert f(*ok[:10], ws.data_ptr() + 8, ws.numel() - 8, None) == -4  # misaligned
+    assert f(*ok[:11], 1024, None) == -4                              # too small
+    cache = fp.new_bq_cache(x, 50)
+    assert f(*ok[:8], cache.data_ptr(), 0.0, *ok[10:]) == -3          # cache without a radius
+    assert f(*ok[:8], cache.data_ptr() + 4, 0.1, *ok[10:]) == -4      # misaligned cache
+    torch.cuda.synchronize()
+
+    def mdps(**kw):
+        prm = fp.MdpsParams(**{k: v for k, v in kw.items() if k not in ("raw",)}).to_c()
+        for k, v in kw.get("raw", {}).items():
+            setattr(prm, k, v)
+        return lib.fp_mdps_sample(x.data_ptr(), 1, 200, 50, None, ctypes.byref(prm), out.data_ptr(), None, None,
+                                  0.0, ws.data_ptr(), ws.numel(), None)
+    assert mdps() == 0
+    assert mdps(raw={"p": 0.0}) == -3 and mdps(raw={"p": 1.0}) == -3
+    assert mdps(raw={"nseg": 0}) == -3 and mdps(raw={"nseg": 17}) == -3
+    assert mdps(raw={"bias": 0.0}) == -3 and mdps(raw={"fit_window": 65}) == -3 and mdps(raw={"m_min": 0}) == -3
+    assert lib.fp_mdps_sample(x.data_ptr(), 1, 200, 50, None, None, out.data_ptr(), None, None, 0.0,
+                              ws.data_ptr(), ws.numel(), None) == -1
+    torch.cuda.synchronize()
+
+    c = dev(np.zeros((1, 4), dtype=np.int32))
+    bo = torch.empty((1, 4, 8), dtype=torch.int32, device="cuda")
+    bq = lambda r, k: lib.fp_ball_query(x.data_ptr(), 1, 200, c.data_ptr(), 4, r, k, bo.data_ptr(), None, None, None)
+    assert bq(0.1, 8) == 0
+    assert bq(0.0, 8) == -3 and bq(-1.0, 8) == -3 and bq(float("inf"), 8) == -3 and bq(float("nan"), 8) == -3
+    assert bq(0.1, 0) == -2 and bq(0.1, 255) == -2
+    torch.cuda.synchronize()
+    assert lib.fp_status_string(0) == b"ok" and len(lib.fp_status_string(-3)) > 0
