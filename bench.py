@@ -271,6 +271,15 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         roof["knn_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": a / HBM_PEAK_GBS, "bytes": byts,
                               "points_searched_by_brute_force": knn["deferred_fraction"]}
+        # ball query through the uniform grid (outside the timed step): the brute-force result
+        gq = time_call(torch, lambda: fp.ball_query_grid(x, idx, sg["radius"], k))
+        if not (torch.equal(gq[1][0], bq[0]) and torch.equal(gq[1][1], bq[1])):
+            raise RuntimeError("ball_query_grid differs from the brute-force ball query")
+        ms["ball_query_grid"] = gq[0]
+        byts = 12.0 * B * N + 4.0 * B * n + 4.0 * B * n * (k + 1)
+        a = byts / (gq[0] * 1e-3) / 1e9
+        roof["ball_query_grid"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                   "frac": a / HBM_PEAK_GBS, "bytes": byts, "equals_brute_force": True}
         # exact FPS with pruned distance updates (outside the timed step): same samples, fewer
         # distance evaluations; priced against the same algorithmic count as fps_exact
         pr = time_call(torch, lambda: fp.fps_exact_pruned(x, n))

@@ -162,6 +162,19 @@ fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N,
                         int32_t* out_idx, int32_t* out_cnt,
                         const void* bq_cache, void* stream);
 
+/*
+ * Ball query through a uniform grid: the result of fp_ball_query without a cache, byte for
+ * byte, for any centre set, from the 27 grid cells around a centre instead of all N points
+ * (cells as wide as the radius; the hits are put back in index order, which is the order the
+ * scan over all points finds them in).  A centre whose ball holds more than 2048 points is
+ * scanned in index order over all points, which ends after k hits.  The grid is built in the
+ * workspace by every call.
+ */
+size_t fp_ball_query_grid_workspace_bytes(int32_t B, int32_t N);
+fp_status fp_ball_query_grid(const float* xyz, int32_t B, int32_t N, const int32_t* center_idx,
+                             int32_t M, float radius, int32_t k, int32_t* out_idx, int32_t* out_cnt,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace fp_knn needs when it is given a cache (0 for shapes the library
  * rejects).  Alignment: 256 bytes. */
 size_t fp_knn_workspace_bytes(int32_t B, int32_t N);

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
 EXPORTS = ["fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
-           "fp_ball_query", "fp_knn_workspace_bytes", "fp_knn", "fp_excl_workspace_bytes", "fp_excl_count",
+           "fp_ball_query", "fp_ball_query_grid_workspace_bytes", "fp_ball_query_grid", "fp_knn_workspace_bytes", "fp_knn", "fp_excl_workspace_bytes", "fp_excl_count",
            "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
 
@@ -112,6 +112,10 @@ def load() -> ctypes.CDLL:
     lib.fp_mdps_sample.restype = i32
     lib.fp_ball_query.argtypes = [vp, i32, i32, vp, i32, f32, i32, vp, vp, vp, vp]
     lib.fp_ball_query.restype = i32
+    lib.fp_ball_query_grid_workspace_bytes.argtypes = [i32, i32]
+    lib.fp_ball_query_grid_workspace_bytes.restype = ctypes.c_size_t
+    lib.fp_ball_query_grid.argtypes = [vp, i32, i32, vp, i32, f32, i32, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.fp_ball_query_grid.restype = i32
     lib.fp_knn_workspace_bytes.argtypes = [i32, i32]
     lib.fp_knn_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_knn.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -305,6 +309,31 @@ def ball_query(xyz: torch.Tensor, center_idx: torch.Tensor, radius: float, k: in
     _check(load().fp_ball_query(xyz.data_ptr(), B, N, center_idx.data_ptr(), M, float(radius), k,
                                 idx.data_ptr(), cnt.data_ptr(), _ptr(bq_cache), _stream()),
            "fp_ball_query")
+    return idx, cnt
+
+
+def ball_query_grid(xyz: torch.Tensor, center_idx: torch.Tensor, radius: float, k: int,
+                    ws: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Ball query through a uniform grid: the outputs of ball_query without a cache."""
+    B, N = _xyz(xyz)
+    if not (center_idx.is_cuda and center_idx.dtype == torch.int32 and center_idx.dim() == 2
+            and center_idx.shape[0] == B and center_idx.is_contiguous()):
+        raise ValueError("center_idx must be a contiguous CUDA int32 tensor [B][M]")
+    M = int(center_idx.shape[1])
+    idx = torch.empty((B, M, k), dtype=torch.int32, device=xyz.device)
+    cnt = torch.empty((B, M), dtype=torch.int32, device=xyz.device)
+    need = int(load().fp_ball_query_grid_workspace_bytes(B, N))
+    if need == 0:
+        raise ValueError("shape (B=%d, N=%d) not supported" % (B, N))
+    if ws is None:
+        key = ("grid", xyz.device.type, xyz.device.index)
+        ws = _workspaces.get(key)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(need, dtype=torch.uint8, device=xyz.device)
+            _workspaces[key] = ws
+    _check(load().fp_ball_query_grid(xyz.data_ptr(), B, N, _ptr(center_idx) if M else None, M, float(radius), k,
+                                     _ptr(idx) if M else None, _ptr(cnt) if M else None, ws.data_ptr(), ws.numel(),
+                                     _stream()), "fp_ball_query_grid")
     return idx, cnt
 
 

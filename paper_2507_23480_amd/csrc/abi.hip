@@ -296,6 +296,30 @@ fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N, const int32_t* c
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }
 
+size_t fp_ball_query_grid_workspace_bytes(int32_t B, int32_t N)
+{
+    if (B < 1 || N < 1 || B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return 0;
+    return (size_t)spatial_sort_bytes(B, N);
+}
+
+fp_status fp_ball_query_grid(const float* xyz, int32_t B, int32_t N, const int32_t* center_idx, int32_t M,
+                             float radius, int32_t k, int32_t* out_idx, int32_t* out_cnt, void* workspace,
+                             size_t workspace_bytes, void* stream)
+{
+    if (B < 1 || N < 1 || M < 0 || k < 1 || k > 254 || B > 65535) return FP_ERR_SHAPE;
+    if ((int64_t)B * N > ((int64_t)1 << 33)) return FP_ERR_SHAPE;
+    if (!(radius > 0.0f) || !isfinite(radius)) return FP_ERR_PARAM;
+    if (!xyz) return FP_ERR_NULL;
+    if (M == 0) return FP_OK;
+    if (!center_idx || !out_idx) return FP_ERR_NULL;
+    if (!workspace || workspace_bytes < fp_ball_query_grid_workspace_bytes(B, N) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return FP_ERR_WORKSPACE;
+    hipError_t err = launch_bq_grid(xyz, B, N, center_idx, M, radius * radius, k, out_idx, out_cnt, workspace,
+                                    reinterpret_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
 size_t fp_knn_workspace_bytes(int32_t B, int32_t N)
 {
     if (B < 1 || N < 1 || B > 65535) return 0;

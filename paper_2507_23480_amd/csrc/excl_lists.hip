@@ -129,7 +129,8 @@ __global__ __launch_bounds__(256) void grid_bounds_kernel(const float* __restric
 }
 
 // One thread per cloud: the largest radius, the cell width and the grid dimensions.
-__global__ void grid_setup_kernel(ExclGrid* gp, int B, const float* __restrict__ thr2, int L, int maxcells)
+__global__ void grid_setup_kernel(ExclGrid* gp, int B, const float* __restrict__ thr2, int L, int maxcells,
+                                  float r2_all)
 {
     const int b = (int)(blockIdx.x * blockDim.x + threadIdx.x);
     if (b >= B) return;
@@ -137,7 +138,7 @@ __global__ void grid_setup_kernel(ExclGrid* gp, int B, const float* __restrict__
     float rmax2 = 0.0f;
     int lmax = 0;
     for (int l = 0; l < L; ++l) {
-        const float t = thr2[(int64_t)b * L + l];
+        const float t = thr2 ? thr2[(int64_t)b * L + l] : r2_all;      // no table: one radius for all clouds
         if (t > rmax2) {            // NaN and values <= 0 never win
             rmax2 = t;
             lmax = l;
@@ -328,7 +329,7 @@ __global__ __launch_bounds__(256) void grid_scatter_kernel(const float* __restri
 
 // ------------------------------------------------------------------ walking the 27 cells
 // Calls f(record, valid) for every point of the 27 cells around (cx, cy, cz), 64 per pass;
-// all lanes take part in every call.  The 9 runs of x-adjacent cells are contiguous in cell
+// all lanes take part in every call; f returns false (the same in all lanes) to end the walk.  The 9 runs of x-adjacent cells are contiguous in cell
 // order: lanes 0..8 fetch the bounds of one run each, and the runs are then walked as one
 // sequence, so a pass is full except for the last and the loads of successive passes do not
 // wait for one another.
@@ -363,7 +364,7 @@ __device__ __forceinline__ void for_neighbours(const ExclGrid& g, const int32_t*
 #pragma unroll
         for (int r = 1; r < 9; ++r) at = t >= pre[r] ? begin[r] + (t - pre[r]) : at;
         const float4 rec = sorted[valid ? at : 0];
-        f(rec, valid);
+        if (!f(rec, valid)) break;
     }
 }
 
@@ -388,12 +389,13 @@ __global__ __launch_bounds__(kWaves * 64) void excl_count_kernel(
     for_neighbours(g, cell_start + (int64_t)b * (maxcells + 1), sorted + (int64_t)b * N, cx, cy, cz, lane,
                    [&](const float4& r, bool valid) {
                        const float d = dist2(px, py, pz, r.x, r.y, r.z);
-                       if (__builtin_amdgcn_ballot_w64(valid && d < rmax2) == 0) return;
+                       if (__builtin_amdgcn_ballot_w64(valid && d < rmax2) == 0) return true;
                        for (int l = 0; l < L; ++l) {
                            const float t = rdlane_f(mythr, l);
                            const int pc = __builtin_popcountll(__builtin_amdgcn_ballot_w64(valid && d < t));
                            mycnt += lane == l ? pc : 0;
                        }
+                       return true;
                    });
     if (lane < L) offsets[1 + ((int64_t)lane * B + b) * N + i] = mycnt;
 }
@@ -521,6 +523,34 @@ __device__ __forceinline__ void wave_sort(uint32_t* buf, int n2, int lane)
     }
 }
 
+// Orders buf[0 .. H) (distinct values) ascending: by counting across the lanes when there are
+// at most 64, else by the bitonic network.  One wave.
+__device__ __forceinline__ void wave_order(uint32_t* buf, int H, int lane)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (H <= 64) {
+        const uint32_t mine = lane < H ? buf[lane] : 0xFFFFFFFFu;
+        int rank = 0;
+        for (int t = 0; t < H; ++t) rank += rdlane(mine, t) < mine ? 1 : 0;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (lane < H) buf[rank] = mine;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+        int n2 = 128;
+        while (n2 < H) n2 <<= 1;
+        for (int t = H + lane; t < n2; t += 64) buf[t] = 0xFFFFFFFFu;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        wave_sort(buf, n2, lane);
+    }
+}
+
 __global__ __launch_bounds__(kWaves * 64) void excl_fill_kernel(
     const float* __restrict__ xyz, int B, int N, const float* __restrict__ thr2, int L,
     const int64_t* __restrict__ offsets, int32_t* __restrict__ entries, int64_t capacity,
@@ -560,30 +590,9 @@ __global__ __launch_bounds__(kWaves * 64) void excl_fill_kernel(
                            const int at = got + lanes_below(mk);
                            if (hit && at < kSortCap) buf[at] = (uint32_t)__float_as_int(r.w);
                            got += __builtin_popcountll(mk);
+                           return true;
                        });
-        if (H <= 64) {
-            // one hit per lane: its place in index order is the number of smaller indices
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const uint32_t mine = lane < H ? buf[lane] : 0xFFFFFFFFu;
-            int rank = 0;
-            for (int t = 0; t < H; ++t) rank += rdlane(mine, t) < mine ? 1 : 0;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            if (lane < H) buf[rank] = mine;          // indices are distinct: ranks are a permutation
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        } else {
-            int n2 = 128;
-            while (n2 < H) n2 <<= 1;
-            for (int t = H + lane; t < n2; t += 64) buf[t] = 0xFFFFFFFFu;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            wave_sort(buf, n2, lane);
-        }
+        wave_order(buf, H, lane);
         for (int t0 = 0; t0 < H; t0 += 64) {
             const bool valid = t0 + lane < H;
             const int j = valid ? (int)buf[t0 + lane] : i;
@@ -602,6 +611,73 @@ __global__ __launch_bounds__(kWaves * 64) void excl_fill_kernel(
             if (__builtin_amdgcn_ballot_w64(valid && d < rmax2) == 0) continue;
             em(j, d, valid, lane);
         }
+    }
+}
+
+// Ball query over the uniform grid: the result of the brute-force scan (first k hits by
+// ascending index, strict < on squared binary32 distances, unused slots repeat the first hit)
+// from the 27 cells around the centre.  One wave per centre collects the hits in LDS and orders
+// them by index; a ball with more hits than the buffer holds is scanned in index order over all
+// points instead, which ends after k hits -- and such a ball has them early.
+__global__ __launch_bounds__(kWaves * 64) void bq_grid_kernel(
+    const float* __restrict__ xyz, int N, const int32_t* __restrict__ center_idx, int M, float r2, int k,
+    int32_t* __restrict__ out_idx, int32_t* __restrict__ out_cnt, const ExclGrid* __restrict__ gp,
+    const int32_t* __restrict__ cell_start, const float4* __restrict__ sorted, int maxcells)
+{
+    __shared__ uint32_t sortbuf[kWaves][kSortCap];
+    const int b = (int)blockIdx.y;
+    const int lane = (int)threadIdx.x & 63;
+    const int w = uni((int)threadIdx.x >> 6);
+    const int q = uni((int)blockIdx.x * kWaves + w);
+    if (q >= M) return;
+    const int c = uni(center_idx[(int64_t)b * M + q]);
+    int32_t* row = out_idx + ((int64_t)b * M + q) * k;
+    if (c < 0 || c >= N) {
+        for (int t = lane; t < k; t += 64) row[t] = -1;
+        if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = 0;
+        return;
+    }
+    const ExclGrid g = gp[b];
+    const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
+    const float px = cloud[(int64_t)c * 3 + 0], py = cloud[(int64_t)c * 3 + 1], pz = cloud[(int64_t)c * 3 + 2];
+    uint32_t* buf = sortbuf[w];
+    int cx, cy, cz;
+    cell_of(g, px, py, pz, cx, cy, cz);
+    int got = 0;
+    // the walk ends as soon as the ball is known to hold more points than the buffer
+    const int enough = kSortCap;
+    for_neighbours(g, cell_start + (int64_t)b * (maxcells + 1), sorted + (int64_t)b * N, cx, cy, cz, lane,
+                   [&](const float4& r, bool valid) {
+                       const bool hit = valid && dist2(px, py, pz, r.x, r.y, r.z) < r2;
+                       const uint64_t mk = __builtin_amdgcn_ballot_w64(hit);
+                       const int at = got + lanes_below(mk);
+                       if (hit && at < kSortCap) buf[at] = (uint32_t)__float_as_int(r.w);
+                       got += __builtin_popcountll(mk);
+                       return got <= enough;
+                   });
+    if (got <= enough) {
+        wave_order(buf, got, lane);
+        const int cnt = got < k ? got : k;
+        const int first = cnt > 0 ? (int)buf[0] : -1;
+        for (int t = lane; t < k; t += 64) row[t] = t < cnt ? (int)buf[t] : first;
+        if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = cnt;
+    } else {
+        int cnt = 0, first = -1;
+        for (int j0 = 0; j0 < N && cnt < k; j0 += 64) {
+            const int j = j0 + lane;
+            const int jj = j < N ? j : c;
+            const bool hit = j < N && dist2(px, py, pz, cloud[(int64_t)jj * 3 + 0], cloud[(int64_t)jj * 3 + 1],
+                                            cloud[(int64_t)jj * 3 + 2]) < r2;
+            const uint64_t mk = __builtin_amdgcn_ballot_w64(hit);
+            if (mk == 0) continue;
+            if (first < 0) first = j0 + __builtin_ctzll(mk);
+            const int at = cnt + lanes_below(mk);
+            if (hit && at < k) row[at] = j;
+            cnt += __builtin_popcountll(mk);
+        }
+        cnt = cnt < k ? cnt : k;
+        for (int t = cnt + lane; t < k; t += 64) row[t] = first;
+        if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = cnt;
     }
 }
 
@@ -711,7 +787,8 @@ hipError_t launch_excl_count(const float* xyz, int B, int N, const float* thr2, 
     int bblocks = (N + 2047) / 2048;
     if (bblocks > 64) bblocks = 64;
     hipLaunchKernelGGL(grid_bounds_kernel, dim3(bblocks, B), dim3(256), 0, stream, xyz, N, gp);
-    hipLaunchKernelGGL(grid_setup_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, gp, B, thr2, L, lay.maxcells);
+    hipLaunchKernelGGL(grid_setup_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, gp, B, thr2, L, lay.maxcells,
+                       0.0f);
     const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
     hipLaunchKernelGGL(grid_count_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, lay.maxcells);
     hipLaunchKernelGGL(grid_scan_kernel, dim3(B), dim3(1024), 0, stream, gp, cnt, st, lay.maxcells);
@@ -739,6 +816,34 @@ hipError_t launch_excl_fill(const float* xyz, int B, int N, const float* thr2, i
     const dim3 wgrid((unsigned)((N + kWaves - 1) / kWaves), (unsigned)B);
     hipLaunchKernelGGL(excl_fill_kernel, wgrid, dim3(kWaves * 64), 0, stream, xyz, B, N, thr2, L, offsets, entries,
                        capacity, gp, st, sorted, lay.maxcells);
+    return hipGetLastError();
+}
+
+hipError_t launch_bq_grid(const float* xyz, int B, int N, const int32_t* center_idx, int M, float r2, int k,
+                          int32_t* out_idx, int32_t* out_cnt, void* workspace, hipStream_t stream)
+{
+    if (M == 0) return hipSuccess;
+    const ExclLayout lay = excl_layout(B, N, 1);
+    unsigned char* base = reinterpret_cast<unsigned char*>(workspace);
+    ExclGrid* gp = reinterpret_cast<ExclGrid*>(base + lay.grid_off);
+    int32_t* cnt = reinterpret_cast<int32_t*>(base + lay.cnt_off);
+    int32_t* st = reinterpret_cast<int32_t*>(base + lay.start_off);
+    float4* sorted = reinterpret_cast<float4*>(base + lay.sorted_off);
+    const int64_t ncnt = (int64_t)B * lay.maxcells;
+    int initblocks = (int)((ncnt + 255) / 256);
+    if (initblocks > 2048) initblocks = 2048;
+    hipLaunchKernelGGL(grid_init_kernel, dim3(initblocks), dim3(256), 0, stream, gp, B, cnt, ncnt);
+    int bblocks = (N + 2047) / 2048;
+    if (bblocks > 64) bblocks = 64;
+    hipLaunchKernelGGL(grid_bounds_kernel, dim3(bblocks, B), dim3(256), 0, stream, xyz, N, gp);
+    hipLaunchKernelGGL(grid_setup_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, gp, B,
+                       static_cast<const float*>(nullptr), 1, lay.maxcells, r2);
+    const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
+    hipLaunchKernelGGL(grid_count_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, lay.maxcells);
+    hipLaunchKernelGGL(grid_scan_kernel, dim3(B), dim3(1024), 0, stream, gp, cnt, st, lay.maxcells);
+    hipLaunchKernelGGL(grid_scatter_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, sorted, lay.maxcells);
+    hipLaunchKernelGGL(bq_grid_kernel, dim3((unsigned)((M + kWaves - 1) / kWaves), (unsigned)B), dim3(kWaves * 64), 0,
+                       stream, xyz, N, center_idx, M, r2, k, out_idx, out_cnt, gp, st, sorted, lay.maxcells);
     return hipGetLastError();
 }
 
