@@ -262,6 +262,12 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         knn = time_knn(torch, fp, x, sg, midx)
         for kname in ("knn_brute", "knn_cached"):
             ms[kname] = knn[kname + "_ms"]
+        # the same k-NN through a grid over the samples, search radius 3 x their coverage radius
+        kg_radius = 3.0 * float(cov_m.max())
+        kg = time_call(torch, lambda: fp.knn_grid(x, midx, KNN_K, kg_radius, want_deferred=True))
+        if not (torch.equal(kg[1][0], knn["knn_brute"][0]) and torch.equal(kg[1][1], knn["knn_brute"][1])):
+            raise RuntimeError("grid k-NN differs from the brute-force result")
+        ms["knn_grid"] = kg[0]
         a = float(B) * N * n * OPS_PER_PAIR_TEST / (knn["knn_brute_ms"] * 1e-3) / 1e12
         roof["knn_brute"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
                              "frac": a / ALU_PEAK_TOPS}
@@ -313,6 +319,11 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             roof["excl_lists_build"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                         "frac": a / HBM_PEAK_GBS, "bytes": byts, "members": ex["members"],
                                         "levels": ex["levels"], "lookup_equals_ball_query": ex["lookup_ok"]}
+        byts = 12.0 * B * N + 12.0 * B * n + 8.0 * B * N * KNN_K
+        a = byts / (ms["knn_grid"] * 1e-3) / 1e9
+        roof["knn_grid"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a / HBM_PEAK_GBS,
+                            "bytes": byts, "radius": kg_radius,
+                            "points_searched_by_brute_force": float(kg[1][2].sum().item()) / (B * N)}
         out["stages"].append({
             "N": N, "n": n, "radius": sg["radius"], "k": k, "plan_G_T_P": list(fp.plan(B, N)),
             "kernel_ms": ms,

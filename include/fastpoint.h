@@ -245,6 +245,19 @@ fp_status fp_ball_query_lists(const int64_t* offsets, const int32_t* entries, in
                               int32_t level, int32_t L, const int32_t* center_idx, int32_t M, int32_t k,
                               int32_t* out_idx, int32_t* out_cnt, void* stream);
 
+/*
+ * k nearest samples through a uniform grid over the samples: the result of fp_knn, bit for
+ * bit.  A point looks at the samples of the 27 cells around it (cells as wide as `radius`);
+ * when its k-th nearest among them is closer than `radius` no sample elsewhere can be nearer,
+ * and the point is done.  The remaining points (out_deferred[b] of them) are searched by brute
+ * force.  A radius of two to three times the samples' coverage radius settles almost every
+ * point in the grid.  Arguments as fp_knn without a cache.
+ */
+size_t fp_knn_grid_workspace_bytes(int32_t B, int32_t N, int32_t n);
+fp_status fp_knn_grid(const float* xyz, int32_t B, int32_t N, const int32_t* sample_idx, int32_t n,
+                      int32_t k, float radius, int32_t* out_pos, float* out_d2, int32_t* out_deferred,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* out_xyz[b][q] = xyz[b][idx[b][q]] -- input of the next stage of a hierarchy
  * (Section 3.1).  Indices outside [0,N) give NaN coordinates. */
 fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N,

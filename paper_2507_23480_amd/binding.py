@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
 EXPORTS = ["fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
-           "fp_ball_query", "fp_ball_query_grid_workspace_bytes", "fp_ball_query_grid", "fp_knn_workspace_bytes", "fp_knn", "fp_excl_workspace_bytes", "fp_excl_count",
+           "fp_ball_query", "fp_ball_query_grid_workspace_bytes", "fp_ball_query_grid", "fp_knn_workspace_bytes", "fp_knn", "fp_knn_grid_workspace_bytes", "fp_knn_grid", "fp_excl_workspace_bytes", "fp_excl_count",
            "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
 
@@ -120,6 +120,10 @@ def load() -> ctypes.CDLL:
     lib.fp_knn_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_knn.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.fp_knn.restype = i32
+    lib.fp_knn_grid_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.fp_knn_grid_workspace_bytes.restype = ctypes.c_size_t
+    lib.fp_knn_grid.argtypes = [vp, i32, i32, vp, i32, i32, f32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.fp_knn_grid.restype = i32
     lib.fp_excl_workspace_bytes.argtypes = [i32, i32, i32]
     lib.fp_excl_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_excl_count.argtypes = [vp, i32, i32, vp, i32, vp, vp, ctypes.c_size_t, vp]
@@ -401,6 +405,27 @@ def ball_query_lists(offsets: torch.Tensor, entries: torch.Tensor, B: int, N: in
     _check(load().fp_ball_query_lists(offsets.data_ptr(), ent.data_ptr(), B, N, level, L, center_idx.data_ptr(),
                                       M, k, idx.data_ptr(), cnt.data_ptr(), _stream()), "fp_ball_query_lists")
     return idx, cnt
+
+
+def knn_grid(xyz: torch.Tensor, sample_idx: torch.Tensor, k: int, radius: float, want_deferred: bool = False):
+    """k nearest samples through a grid over the samples (cells as wide as `radius`): the
+    outputs of knn; with want_deferred also the per-cloud number of points the grid did not
+    settle."""
+    B, N = _xyz(xyz)
+    if not (sample_idx.is_cuda and sample_idx.dtype == torch.int32 and sample_idx.dim() == 2
+            and sample_idx.shape[0] == B and sample_idx.is_contiguous()):
+        raise ValueError("sample_idx must be a contiguous CUDA int32 tensor [B][n]")
+    n = int(sample_idx.shape[1])
+    pos = torch.empty((B, N, k), dtype=torch.int32, device=xyz.device)
+    d2 = torch.empty((B, N, k), dtype=torch.float32, device=xyz.device)
+    need = int(load().fp_knn_grid_workspace_bytes(B, N, n))
+    if need == 0:
+        raise ValueError("shape (B=%d, N=%d, n=%d) not supported" % (B, N, n))
+    ws = torch.empty(need, dtype=torch.uint8, device=xyz.device)
+    deferred = torch.zeros(B, dtype=torch.int32, device=xyz.device)
+    _check(load().fp_knn_grid(xyz.data_ptr(), B, N, sample_idx.data_ptr(), n, k, float(radius), pos.data_ptr(),
+                              d2.data_ptr(), deferred.data_ptr(), ws.data_ptr(), need, _stream()), "fp_knn_grid")
+    return (pos, d2, deferred) if want_deferred else (pos, d2)
 
 
 def gather_xyz(xyz: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:

@@ -402,6 +402,39 @@ fp_status fp_ball_query_lists(const int64_t* offsets, const int32_t* entries, in
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }
 
+size_t fp_knn_grid_workspace_bytes(int32_t B, int32_t N, int32_t n)
+{
+    if (B < 1 || N < 1 || n < 1 || B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return 0;
+    // the deferred-point bookkeeping of fp_knn, the samples' coordinates, the grid over them
+    return fp_knn_workspace_bytes(B, N) + (size_t)align_up((int64_t)B * n * 12, 256) +
+           (size_t)spatial_sort_bytes(B, n);
+}
+
+fp_status fp_knn_grid(const float* xyz, int32_t B, int32_t N, const int32_t* sample_idx, int32_t n, int32_t k,
+                      float radius, int32_t* out_pos, float* out_d2, int32_t* out_deferred, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    if (!xyz || !sample_idx || !out_pos || !out_d2) return FP_ERR_NULL;
+    if (B < 1 || N < 1 || n < 1 || k < 1 || k > FP_KNN_MAX_K || k > n || B > 65535) return FP_ERR_SHAPE;
+    if ((int64_t)B * N > ((int64_t)1 << 33)) return FP_ERR_SHAPE;
+    if (!(radius > 0.0f) || !isfinite(radius)) return FP_ERR_PARAM;
+    if (!workspace || workspace_bytes < fp_knn_grid_workspace_bytes(B, N, n) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return FP_ERR_WORKSPACE;
+    unsigned char* base = reinterpret_cast<unsigned char*>(workspace);
+    int32_t* count = reinterpret_cast<int32_t*>(base + align_up((int64_t)B * 4, 256));
+    int32_t* list = reinterpret_cast<int32_t*>(base + 2 * align_up((int64_t)B * 4, 256));
+    float* sample_xyz = reinterpret_cast<float*>(base + fp_knn_workspace_bytes(B, N));
+    void* grid_ws = base + fp_knn_workspace_bytes(B, N) + align_up((int64_t)B * n * 12, 256);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (launch_gather(xyz, B, N, sample_idx, n, sample_xyz, st) != hipSuccess) return FP_ERR_DEVICE;
+    if (launch_knn_grid(xyz, B, N, sample_xyz, n, k, radius * radius, out_pos, out_d2, count, list, grid_ws, st) !=
+        hipSuccess)
+        return FP_ERR_DEVICE;
+    hipError_t err = launch_knn_deferred(xyz, B, N, sample_idx, n, k, out_pos, out_d2, count, list, out_deferred, st);
+    return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
+}
+
 fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N, const int32_t* idx, int32_t M,
                         float* out_xyz, void* stream)
 {

@@ -104,9 +104,12 @@ __global__ __launch_bounds__(256) void grid_bounds_kernel(const float* __restric
     for (int i = (int)(blockIdx.x * 256 + threadIdx.x); i < N; i += (int)gridDim.x * 256) {
 #pragma unroll
         for (int a = 0; a < 3; ++a) {
-            const uint32_t o = f2ord(cloud[(int64_t)i * 3 + a]);
-            lo[a] = min(lo[a], o);
-            hi[a] = max(hi[a], o);
+            const float v = cloud[(int64_t)i * 3 + a];
+            if (v == v) {                           // NaN coordinates (gathers of bad indices) do not count
+                const uint32_t o = f2ord(v);
+                lo[a] = min(lo[a], o);
+                hi[a] = max(hi[a], o);
+            }
         }
     }
 #pragma unroll
@@ -681,6 +684,94 @@ __global__ __launch_bounds__(kWaves * 64) void bq_grid_kernel(
     }
 }
 
+// k nearest samples through a grid over the SAMPLES (records carry the sample's position in the
+// list): one thread per point visits the samples of the 27 cells around it and keeps the K
+// nearest, ordered by (distance, position).  Every sample outside those cells is farther than the
+// cell width, which exceeds the search radius: when the K-th nearest found is closer than the
+// radius the result is exact.  The other points go to the cloud's list of deferred points, which
+// the brute-force kernels search afterwards.
+template <int K>
+__global__ __launch_bounds__(256) void knn_grid_kernel(const float* __restrict__ xyz, int N, int k, float r2,
+                                                       int32_t* __restrict__ out_pos, float* __restrict__ out_d2,
+                                                       const ExclGrid* __restrict__ gp,
+                                                       const int32_t* __restrict__ cell_start,
+                                                       const float4* __restrict__ sorted, int n, int maxcells,
+                                                       int32_t* __restrict__ count, int32_t* __restrict__ list)
+{
+    const int b = (int)blockIdx.y;
+    const int j = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (j >= N) return;
+    const ExclGrid g = gp[b];
+    const float* p = xyz + ((int64_t)b * N + j) * 3;
+    const float px = p[0], py = p[1], pz = p[2];
+    int cx, cy, cz;
+    cell_of(g, px, py, pz, cx, cy, cz);
+    float bd[K];
+    int32_t bq[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+        bd[i] = __builtin_inff();
+        bq[i] = -1;
+    }
+    const int32_t* __restrict__ st = cell_start + (int64_t)b * (maxcells + 1);
+    const float4* __restrict__ rec = sorted + (int64_t)b * n;
+    const int x0 = cx > 0 ? cx - 1 : 0;
+    const int x1 = cx < g.dim[0] - 1 ? cx + 1 : g.dim[0] - 1;
+    for (int dz = -1; dz <= 1; ++dz) {
+        const int z = cz + dz;
+        if (z < 0 || z >= g.dim[2]) continue;
+        for (int dy = -1; dy <= 1; ++dy) {
+            const int y = cy + dy;
+            if (y < 0 || y >= g.dim[1]) continue;
+            const int c0 = (z * g.dim[1] + y) * g.dim[0] + x0;
+            const int end = st[c0 + (x1 - x0) + 1];
+            for (int t = st[c0]; t < end; ++t) {
+                const float4 s = rec[t];
+                const float dd = dist2(px, py, pz, s.x, s.y, s.z);
+                const int32_t qq = __float_as_int(s.w);
+                if (!(dd < bd[K - 1] || (dd == bd[K - 1] && qq < bq[K - 1]))) continue;    // NaN: never
+#pragma unroll
+                for (int i = K - 1; i >= 1; --i) {
+                    const bool before = dd < bd[i - 1] || (dd == bd[i - 1] && qq < bq[i - 1]);
+                    const bool here = dd < bd[i] || (dd == bd[i] && qq < bq[i]);
+                    bd[i] = before ? bd[i - 1] : (here ? dd : bd[i]);
+                    bq[i] = before ? bq[i - 1] : (here ? qq : bq[i]);
+                }
+                const bool first = dd < bd[0] || (dd == bd[0] && qq < bq[0]);
+                bd[0] = first ? dd : bd[0];
+                bq[0] = first ? qq : bq[0];
+            }
+        }
+    }
+    float kth = __builtin_inff();
+    int32_t kq = -1;
+#pragma unroll
+    for (int i = 0; i < K; ++i)
+        if (i == k - 1) {
+            kth = bd[i];
+            kq = bq[i];
+        }
+    if (kq >= 0 && kth < r2) {
+        int32_t* pos = out_pos + ((int64_t)b * N + j) * k;
+        float* d2 = out_d2 + ((int64_t)b * N + j) * k;
+#pragma unroll
+        for (int i = 0; i < K; ++i)
+            if (i < k) {
+                pos[i] = bq[i];
+                d2[i] = bd[i];
+            }
+    } else {
+        const int at = atomicAdd(&count[b], 1);
+        list[(int64_t)b * N + at] = j;
+    }
+}
+
+__global__ void zero_ints_kernel(int32_t* p, int n)
+{
+    const int t = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (t < n) p[t] = 0;
+}
+
 // Ball query by lookup: one wave per centre.
 __global__ __launch_bounds__(256) void bq_lists_kernel(const int64_t* __restrict__ offsets,
                                                        const int32_t* __restrict__ entries, int B, int N, int level,
@@ -816,6 +907,45 @@ hipError_t launch_excl_fill(const float* xyz, int B, int N, const float* thr2, i
     const dim3 wgrid((unsigned)((N + kWaves - 1) / kWaves), (unsigned)B);
     hipLaunchKernelGGL(excl_fill_kernel, wgrid, dim3(kWaves * 64), 0, stream, xyz, B, N, thr2, L, offsets, entries,
                        capacity, gp, st, sorted, lay.maxcells);
+    return hipGetLastError();
+}
+
+// Grid over the samples (their coordinates gathered to sample_xyz [B][n][3]) and the search of
+// every point in it; the deferred points are left in `list` / `count` for the caller.
+hipError_t launch_knn_grid(const float* xyz, int B, int N, const float* sample_xyz, int n, int k, float r2,
+                           int32_t* out_pos, float* out_d2, int32_t* count, int32_t* list, void* grid_ws,
+                           hipStream_t stream)
+{
+    const ExclLayout lay = excl_layout(B, n, 1);
+    unsigned char* base = reinterpret_cast<unsigned char*>(grid_ws);
+    ExclGrid* gp = reinterpret_cast<ExclGrid*>(base + lay.grid_off);
+    int32_t* cnt = reinterpret_cast<int32_t*>(base + lay.cnt_off);
+    int32_t* st = reinterpret_cast<int32_t*>(base + lay.start_off);
+    float4* sorted = reinterpret_cast<float4*>(base + lay.sorted_off);
+    const int64_t ncnt = (int64_t)B * lay.maxcells;
+    int initblocks = (int)((ncnt + 255) / 256);
+    if (initblocks > 2048) initblocks = 2048;
+    hipLaunchKernelGGL(zero_ints_kernel, dim3((B + 255) / 256), dim3(256), 0, stream, count, B);
+    hipLaunchKernelGGL(grid_init_kernel, dim3(initblocks), dim3(256), 0, stream, gp, B, cnt, ncnt);
+    int bblocks = (n + 2047) / 2048;
+    if (bblocks > 64) bblocks = 64;
+    hipLaunchKernelGGL(grid_bounds_kernel, dim3(bblocks, B), dim3(256), 0, stream, sample_xyz, n, gp);
+    hipLaunchKernelGGL(grid_setup_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, gp, B,
+                       static_cast<const float*>(nullptr), 1, lay.maxcells, r2);
+    const dim3 sgrid((unsigned)((n + 255) / 256), (unsigned)B);
+    hipLaunchKernelGGL(grid_count_kernel, sgrid, dim3(256), 0, stream, sample_xyz, n, gp, cnt, lay.maxcells);
+    hipLaunchKernelGGL(grid_scan_kernel, dim3(B), dim3(1024), 0, stream, gp, cnt, st, lay.maxcells);
+    hipLaunchKernelGGL(grid_scatter_kernel, sgrid, dim3(256), 0, stream, sample_xyz, n, gp, cnt, sorted, lay.maxcells);
+    const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
+    if (k == 1)
+        hipLaunchKernelGGL(knn_grid_kernel<1>, pgrid, dim3(256), 0, stream, xyz, N, k, r2, out_pos, out_d2, gp, st,
+                           sorted, n, lay.maxcells, count, list);
+    else if (k <= 3)
+        hipLaunchKernelGGL(knn_grid_kernel<3>, pgrid, dim3(256), 0, stream, xyz, N, k, r2, out_pos, out_d2, gp, st,
+                           sorted, n, lay.maxcells, count, list);
+    else
+        hipLaunchKernelGGL(knn_grid_kernel<8>, pgrid, dim3(256), 0, stream, xyz, N, k, r2, out_pos, out_d2, gp, st,
+                           sorted, n, lay.maxcells, count, list);
     return hipGetLastError();
 }
 

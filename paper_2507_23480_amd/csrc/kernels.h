@@ -106,6 +106,12 @@ hipError_t launch_excl_count(const float* xyz, int B, int N, const float* thr2, 
                              void* workspace, hipStream_t stream);
 hipError_t launch_excl_fill(const float* xyz, int B, int N, const float* thr2, int L, const int64_t* offsets,
                             int32_t* entries, int64_t capacity, void* workspace, hipStream_t stream);
+hipError_t launch_knn_deferred(const float* xyz, int B, int N, const int32_t* sample_idx, int n, int k,
+                               int32_t* out_pos, float* out_d2, int32_t* count, int32_t* list,
+                               int32_t* out_deferred, hipStream_t stream);
+hipError_t launch_knn_grid(const float* xyz, int B, int N, const float* sample_xyz, int n, int k, float r2,
+                           int32_t* out_pos, float* out_d2, int32_t* count, int32_t* list, void* grid_ws,
+                           hipStream_t stream);
 hipError_t launch_bq_grid(const float* xyz, int B, int N, const int32_t* center_idx, int M, float r2, int k,
                           int32_t* out_idx, int32_t* out_cnt, void* workspace, hipStream_t stream);
 hipError_t launch_bq_lists(const int64_t* offsets, const int32_t* entries, int B, int N, int level,

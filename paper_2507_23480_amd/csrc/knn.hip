@@ -394,6 +394,38 @@ hipError_t launch_knn_k(const float* xyz, int B, int N, const int32_t* sample_id
 
 }  // namespace
 
+// The brute-force search of the points listed in list[b][0 .. count[b]) (left there by a first
+// pass that could not settle them): a wave per point while the list is short, the tiled kernel for
+// the rest.
+template <int K>
+hipError_t launch_knn_deferred_k(const float* xyz, int B, int N, const int32_t* sample_idx, int n, int k,
+                                 int32_t* out_pos, float* out_d2, int32_t* count, int32_t* list,
+                                 int32_t* out_deferred, hipStream_t stream)
+{
+    const dim3 grid_pts((unsigned)((N + kPointsPerWg - 1) / kPointsPerWg), (unsigned)B);
+    hipLaunchKernelGGL((knn_list_wave_kernel<K>), dim3(kWaveListMax / 4, (unsigned)B), dim3(256), 0, stream, xyz,
+                       N, sample_idx, n, k, out_pos, out_d2, (const int32_t*)list, (const int32_t*)count);
+    hipLaunchKernelGGL((knn_brute_kernel<K, true>), grid_pts, dim3(256), 0, stream, xyz, N, sample_idx, n, k,
+                       out_pos, out_d2, (const int32_t*)list, (const int32_t*)count, out_deferred);
+    return hipGetLastError();
+}
+
+hipError_t launch_knn_deferred(const float* xyz, int B, int N, const int32_t* sample_idx, int n, int k,
+                               int32_t* out_pos, float* out_d2, int32_t* count, int32_t* list,
+                               int32_t* out_deferred, hipStream_t stream)
+{
+    if (k == 1)
+        return launch_knn_deferred_k<1>(xyz, B, N, sample_idx, n, k, out_pos, out_d2, count, list, out_deferred,
+                                        stream);
+    if (k <= 3)
+        return launch_knn_deferred_k<3>(xyz, B, N, sample_idx, n, k, out_pos, out_d2, count, list, out_deferred,
+                                        stream);
+    if (k <= 8)
+        return launch_knn_deferred_k<8>(xyz, B, N, sample_idx, n, k, out_pos, out_d2, count, list, out_deferred,
+                                        stream);
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_knn(const float* xyz, int B, int N, const int32_t* sample_idx, int n, int k,
                       int32_t* out_pos, float* out_d2, const void* bq_cache, int32_t* flags,
                       int32_t* count, int32_t* list, int32_t* out_deferred, hipStream_t stream)
