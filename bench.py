@@ -357,7 +357,7 @@ def time_call(torch, fn, reps=3):
 
 
 def time_excl_lists(torch, fp, x, sg, infos, midx, mbq, reps=3):
-    """Exclusion lists of a stage as a data structure (Alg. 2 lines 15-22): one level per MDPS
+    """Exclusion lists of a stage as a data structure (the list-building loops of Alg. 2): one level per MDPS
     threshold of each cloud plus the ball-query radius; count and fill passes timed apart, and
     the stage's ball query answered by lookup in the extra level.  Not part of the timed step.
     Skipped for clouds whose lists would not be built in practice (N above 200 000)."""

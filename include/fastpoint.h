@@ -210,7 +210,7 @@ fp_status fp_knn(const float* xyz, int32_t B, int32_t N, const int32_t* sample_i
 size_t fp_excl_workspace_bytes(int32_t B, int32_t N, int32_t L);
 
 /*
- * Exclusion lists as a data structure, Algorithm 2 lines 15-22 (Section 4.1 step 2) with
+ * Exclusion lists as a data structure, the list-building loops of Algorithm 2 (Section 4.1 step 2) with
  * the extra list at the ball-query radius of Section 4.2: for level l, cloud b and point i,
  * row r = (l*B + b)*N + i holds the points j of the cloud with dist^2(P_i, P_j) < thr2[b][l]
  * (strict, binary32) in ascending j -- the order in which the paper's loop over j appends

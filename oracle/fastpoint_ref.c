@@ -16,8 +16,8 @@
  *     never -ffast-math).  Squaring keeps every comparison and argmax of the
  *     paper's algorithms, which only ever compare distances.
  *   - argmax and "find any available point" take the LOWEST index among
- *     equals / candidates (the paper leaves both open: Alg. 1 line 8,
- *     Alg. 2 line 33).
+ *     equals / candidates (the paper leaves both open: the arg-max of
+ *     Alg. 1, findAnyOne of Alg. 2).
  *   - the curve estimator works in binary64 and rounds each threshold once
  *     to binary32.
  *
@@ -48,7 +48,7 @@ static float ref_dist2(const float *a, const float *b)
     return t;
 }
 
-/* Alg. 1 lines 4-7: fold one sample into the running min-distance array */
+/* Alg. 1, distance-update loop: fold one sample into the running min-distance array */
 static void ref_fold(const float *xyz, int32_t N, int32_t s, float *dists)
 {
     const float *c = xyz + 3 * (size_t)s;
@@ -59,7 +59,7 @@ static void ref_fold(const float *xyz, int32_t N, int32_t s, float *dists)
     }
 }
 
-/* Alg. 1 line 8: index of the maximum, lowest index among equal maxima */
+/* Alg. 1, arg-max step: index of the maximum, lowest index among equal maxima */
 static int32_t ref_argmax(const float *dists, int32_t N)
 {
     int32_t best = 0;
@@ -72,11 +72,11 @@ static int32_t ref_argmax(const float *dists, int32_t N)
 /*
  * Exact farthest point sampling -- Algorithm 1 (Section 3.3).
  *   xyz      [N][3] points
- *   start    seed index (Alg. 1 line 1; the paper draws it at random)
+ *   start    seed index (first step of Alg. 1; the paper draws it at random)
  *   out_idx  [n]  sampled indices, out_idx[0] = start
  *   out_mdc  [n]  or NULL: out_mdc[i] = max(min_dists) at the moment sample i
- *            was picked (the "minimum distance curve", Section 4 and Alg. 2
- *            line 11), squared; out_mdc[0] = +inf.
+ *            was picked (the "minimum distance curve", Section 4 and the prefix
+ *            loop of Alg. 2), squared; out_mdc[0] = +inf.
  * Returns 0, or -1 on bad arguments.
  */
 int ref_fps_exact(const float *xyz, int32_t N, int32_t n, int32_t start,
@@ -353,7 +353,7 @@ static void ref_info_init(ref_mdps_info *info, int32_t n)
         info->level_start[l] = -1;
 }
 
-/* quota rule of Alg. 2 line 22: the segment that sample index i belongs to */
+/* quota rule of Alg. 2 (the level floor of a sample position): the segment that sample index i belongs to */
 static int32_t ref_quota_level(int32_t i, int32_t n, int32_t nseg)
 {
     return 1 + (int32_t)(((int64_t)i * nseg) / n);
@@ -369,13 +369,13 @@ static int32_t ref_quota_level(int32_t i, int32_t n, int32_t nseg)
  * and bitmaps explicitly and must return the same indices.
  *
  * Steps:
- *  S1  exact FPS for i = 1..m recording mdc (Alg. 2 lines 3-11); the prefix
+ *  S1  exact FPS for i = 1..m recording mdc (the prefix loop of Alg. 2); the prefix
  *      samples stay in the output and sampling continues at i = m+1.
- *  S2  thresholds from the estimated curve (line 13, lines 15-22).
- *  S3  threshold sampling (lines 24-37): level = max(level, quota level of i);
+ *  S2  thresholds from the estimated curve (the estimator call and the threshold set-up of Alg. 2).
+ *  S3  threshold sampling (the main loop of Alg. 2): level = max(level, quota level of i);
  *      pick the lowest-index available point at the current level; if none,
  *      move to the next level without consuming a sample slot.
- *  S4  early termination (lines 39-53): once the last level is exhausted the
+ *  S4  early termination (the closing part of Alg. 2): once the last level is exhausted the
  *      remaining samples come from exact FPS on the (already current) dists.
  */
 int ref_mdps_sample(const float *xyz, int32_t N, int32_t n, int32_t start,
@@ -460,7 +460,7 @@ int ref_mdps_sample(const float *xyz, int32_t N, int32_t n, int32_t start,
             ++applied;
             ref_fold(xyz, N, out_idx[applied], dists);
         }
-        /* remainder FPS in the order of Alg. 2 lines 48-53 (the first fold
+        /* remainder FPS in the order of the closing loop of Alg. 2 (the first fold
          * repeats sample i-1, which is already in dists: a no-op) */
         for (; i < n; ++i) {
             ref_fold(xyz, N, out_idx[i - 1], dists);
@@ -496,12 +496,11 @@ static int ref_list_push(ref_list *l, int32_t x)
 
 /*
  * MDPS with the data structures of Algorithm 2 written out: per-level
- * exclusion lists for every point (lines 15-22, one distance per pair), one
- * availability bitmap per level (line 24), bitmap clearing from the lists of
- * the most recent sample for the current and all later levels (lines 29-32),
- * findAnyOne = lowest set bit (line 33), and the early-termination rebuild of
- * dists from the level-1 lists restricted to sampled points (lines 41-46)
- * followed by the remainder FPS (lines 48-53).  O(N^2) time and memory: tiny
+ * exclusion lists for every point (the list-building loops, one distance per pair), one
+ * availability bitmap per level, bitmap clearing from the lists of the most
+ * recent sample for the current and all later levels, findAnyOne = lowest set
+ * bit, and the early-termination rebuild of dists from the level-1 lists
+ * restricted to sampled points followed by the remainder FPS.  O(N^2) time and memory: tiny
  * clouds only.  The bitmaps start from all ones and then have the prefix
  * samples' lists cleared, because the prefix samples stay part of the output.
  */
@@ -636,7 +635,7 @@ done:
  * cloud, given by index) the neighbours closer than `radius`.  The paper
  * fixes neither k, the order nor the padding; this build takes the first k
  * hits in ascending index order, strict "<" on squared binary32 distances
- * (the comparison of Alg. 2 line 20), and pads unused slots with the first
+ * (the comparison Alg. 2 builds its lists with), and pads unused slots with the first
  * hit.  out_cnt[q] = min(hits, k) >= 1 because a centre always hits itself.
  *   out_idx [M][k], out_cnt [M] or NULL
  */
@@ -679,7 +678,7 @@ int ref_gather_xyz(const float *xyz, int32_t N, const int32_t *idx, int32_t M, f
 
 /* ------------------------------------------------------- exclusion lists -- */
 /*
- * Exclusion lists -- Algorithm 2 lines 15-22 (Section 4.1 step 2), plus the extra
+ * Exclusion lists -- the list-building loops of Algorithm 2 (Section 4.1 step 2), plus the extra
  * list at the ball-query radius of Section 4.2, as a data structure of its own:
  * for every level l and every point i the points j with dist2(P_i, P_j) < thr2[l],
  * in the order the paper's loop over j appends them (ascending j; i itself is a

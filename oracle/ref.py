@@ -222,7 +222,7 @@ def ball_query(xyz, centers, radius: float, k: int) -> Tuple[np.ndarray, np.ndar
 
 
 def excl_lists(xyz, thr2) -> Tuple[np.ndarray, np.ndarray]:
-    """Exclusion lists of one cloud for the squared radii thr2[L] (Alg. 2 lines 15-22):
+    """Exclusion lists of one cloud for the squared radii thr2[L] (the list-building loops of Alg. 2):
     (offsets[L*N+1] int64, entries int32); row l*N+i holds the j with dist2(i,j) < thr2[l],
     ascending."""
     a = _cloud(xyz)

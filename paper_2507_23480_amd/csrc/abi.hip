@@ -107,7 +107,7 @@ int64_t bq_blocks(int N) { return ((int64_t)N + 63) / 64; }
 int64_t bq_col_words(int n) { return align_up((int64_t)n, 8); }
 
 constexpr int64_t kLlPkWords = (int64_t)2 * kMaxGroup * kLlSlotWords;             // all groups together
-constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandPerRound * kCandWords;
+constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandMax * kCandWords;
 
 fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
                       const fp_mdps_params* prm, int32_t* out_idx, float* out_mdc, fp_mdps_info* info,
@@ -208,7 +208,10 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         if (launch_bq_header(bq_cache, h, stream) != hipSuccess) return FP_ERR_DEVICE;
     }
 
-    const void* fn = sampler_kernel_for(plan.T, plan.P, bq, pruned);
+    // MDPS threshold rounds with two candidates per control-wave lane: measured faster except
+    // where one workgroup both holds the cloud and records the radius tests
+    const bool wide = prm != nullptr && !pruned && (!bq || plan.G > 1);
+    const void* fn = sampler_kernel_for(plan.T, plan.P, bq, pruned, wide);
     if (!fn) return FP_ERR_SHAPE;
     const unsigned grid = (unsigned)(plan.groups * plan.G);
     void* kargs[] = {&a};

@@ -1,5 +1,5 @@
 // Exclusion lists of FastPoint (arXiv 2507.23480) as a data structure of their own, for gfx950:
-// Algorithm 2 lines 15-22 (Section 4.1 step 2) -- for every level l and every point i the points
+// the list-building loops of Algorithm 2 (Section 4.1 step 2) -- for every level l and every point i the points
 // j with dist2(P_i, P_j) < R_l^2, one distance per pair serving all levels -- plus the extra list
 // at the ball-query radius of Section 4.2, and the ball query that is a lookup in such a list.
 //

@@ -11,7 +11,8 @@ namespace fastpoint {
 
 constexpr int kMaxGroup = 256;          // most workgroups one cloud is spread over
 constexpr int kLlSlotWords = 8;         // 64-bit words per workgroup slot of the pick exchange
-constexpr int kCandPerRound = 64;       // candidates per round of the threshold phase
+constexpr int kCandPerRound = 64;       // candidates per round of exact FPS (one per lane of the control wave)
+constexpr int kCandMax = 128;           // candidates per round of the threshold phase (two per lane)
 constexpr int kCandWords = 5;           // exchanged 64-bit words per candidate (idx, x, y, z, distance)
 constexpr uint32_t kBqMagic = 0x46504251u;
 
@@ -51,7 +52,7 @@ struct SamplerArgs {
     int32_t bq_blocks;
     int64_t bq_col_words;
     uint64_t* ll_pk;                // [groups][2][G][kLlSlotWords]
-    uint64_t* ll_cd;                // [groups][2][G][kCandPerRound][kCandWords]
+    uint64_t* ll_cd;                // [groups][2][G][kCandMax][kCandWords]
     int64_t wait_ticks;
     const float* mlp;               // weights of the MLP curve estimator, or NULL (power function)
     const float4* sorted;           // cell-ordered variant: [B][N] records (x, y, z, index bits), else NULL
@@ -62,7 +63,8 @@ struct Plan {
     int groups;         // clouds resident at once
 };
 
-const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm);
+// `wide`: threshold rounds of MDPS take kCandMax candidates instead of kCandPerRound
+const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, bool wide);
 hipError_t launch_zero_words(uint64_t* p, int64_t nwords, hipStream_t stream);
 
 hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* center_idx, int M,

@@ -40,7 +40,7 @@
 namespace fastpoint {
 namespace {
 
-constexpr int kCand = kCandPerRound;    // candidates examined per round of the threshold phase
+constexpr int kCand = kCandPerRound;    // candidates of an exact-FPS round (one per lane of the control wave)
 constexpr float kPadCoord = 3.0e38f;    // coordinates of slots beyond N: every distance becomes +inf
 constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
 constexpr int kStage = 256;             // ring of picks not yet written to global memory
@@ -230,7 +230,7 @@ struct Shared {
     int32_t level_start[FP_MAX_SEG];
     int32_t level_exhausted[FP_MAX_SEG];
     int32_t wcnt[NW];
-    Cand cand[kCand];
+    Cand cand[kCandMax];
     Cand pend[kCand];
     int32_t bl[FP_MAX_SEG];    // segment boundaries b_l (curve positions that become thresholds)
     int32_t qend[FP_MAX_SEG + 1];   // qend[l] = ceil(n l / nseg): the quota rule raises the level to l + 1 there
@@ -241,7 +241,7 @@ struct Shared {
     int32_t ctrl[4];      // [0] accepted picks of the round, [1] points passing in the cloud,
                           // [2] failure, [3] distance bits of the last accepted pick
     // picks of the round being resolved, in acceptance order
-    uint64_t live[kCand + 2];
+    uint64_t live[kCandMax + 2];
 #ifdef FASTPOINT_PHASE_CLOCKS
     long long chain_cycles;   // shader clocks the control wave spent in the exact-FPS chain loop
     long long chain_picks;
@@ -312,7 +312,7 @@ struct RowWords {
     }
 };
 
-// Alg. 1 lines 4-7 for this thread's points; with BQ also the radius test of Section 4.2: the
+// The distance update of Alg. 1 for this thread's points; with BQ also the radius test of Section 4.2: the
 // 64-bit hit mask of every slot goes to lane `s` of `rw`.
 template <int P, bool BQ, int P0>
 __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float cy, float cz, float bq_r2,
@@ -662,7 +662,7 @@ __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, c
 // The next slot is requested before the current pick is folded.  Cell-ordered variant: the
 // candidates of the round (`total` of them) are tested against the wave's box once, all
 // together; a published pick that is not near is passed over.
-template <int T, int P, bool BQ, bool PERM>
+template <int T, int P, bool BQ, bool PERM, bool WIDE>
 __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                              const SamplerArgs& a, int base, uint32_t tag, int total)
 {
@@ -670,7 +670,7 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
     RowWords<P> rw;
     rw.clear();
     uint64_t near = ~0ull;
-    if constexpr (PERM) near = near_mask<P, BQ>(pt, sh.cand, total, wh.lane);
+    if constexpr (PERM) near = near_mask<P, BQ>(pt, sh.cand, total, wh.lane);   // PERM rounds are never WIDE
     uint32_t slot = lds_observe(&sh.live[0]);
     for (;;) {
         slot = uni(slot);
@@ -682,13 +682,20 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
         if ((slot & 0xFFu) == kLiveEnd) break;
         const uint32_t cl = slot & 0xFFu;
         slot = lds_observe(&sh.live[s + 1]);
+        if (WIDE && BQ && s == 64) {                // lane s of `rw` holds a pick's words: 64 at a time
+            flush_rows<P, BQ>(rw, a, wh, base, 64);
+            rw.clear();
+        }
         if (!PERM || ((near >> cl) & 1ull) != 0) {
             const Cand c = sh.cand[cl];
-            fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, s, rw);
+            fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, WIDE ? (s & 63) : s, rw);
         }
         ++s;
     }
-    flush_rows<P, BQ>(rw, a, wh, base, s);          // a round has at most kCand picks
+    if (WIDE)   // the picks not written yet: all of them up to 64, else those from the 65th on
+        flush_rows<P, BQ>(rw, a, wh, s > 64 ? base + 64 : base, s > 64 ? s - 64 : s);
+    else
+        flush_rows<P, BQ>(rw, a, wh, base, s);      // a round has at most kCand picks
 }
 
 // segment boundary b_l (curve index whose value becomes R_l), l = 1..nseg
@@ -725,7 +732,7 @@ struct CloudState {
 #endif
 };
 
-// Curve capture of the prefix (Alg. 2 line 11), by the lanes of one wave.
+// Curve capture of the prefix (the prefix loop of Alg. 2), by the lanes of one wave.
 template <int T>
 __device__ __forceinline__ void capture_curve(Shared<T>& sh, const Where& wh, const CloudState& st, int pos,
                                               float d)
@@ -735,7 +742,7 @@ __device__ __forceinline__ void capture_curve(Shared<T>& sh, const Where& wh, co
     if (wh.tid < 32 && sh.mlp_pos[wh.tid] == pos) sh.mlp_val[wh.tid] = d;
 }
 
-// One plain iteration of Alg. 1 (lines 4-8) on distances that are already up to date:
+// One plain iteration of Alg. 1 (distance update, arg-max) on distances that are already up to date:
 // arg-max over the cloud, lowest index among equals.  Always makes progress; the batched
 // rounds below fall back to it.  Returns false if a wait between workgroups expired.
 template <int T, int P, bool BQ, bool PERM>
@@ -764,11 +771,11 @@ __device__ __forceinline__ bool plain_pick(Points<P, BQ>& pt, Shared<T>& sh, con
     return true;
 }
 
-// Collects the cloud's first kCand points (ascending index) whose distance passes the
+// Collects the cloud's first CAP points (ascending index) whose distance passes the
 // threshold -- d > thr (STRICT) or d >= thr -- into sh.cand of every workgroup.
-// Returns the number collected (at most kCand), -1 if a wait expired; `alltot` receives the
+// Returns the number collected (at most CAP), -1 if a wait expired; `alltot` receives the
 // number of points that pass in the whole cloud.
-template <int T, int P, bool BQ, bool PERM, bool STRICT>
+template <int T, int P, bool BQ, bool PERM, bool STRICT, int CAP>
 __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                                const SamplerArgs& a, uint32_t& seq, float thr, int& alltot)
 {
@@ -791,16 +798,16 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     }
     off = uni(off);
     tot = uni(tot);
-    // 2. the workgroup's first kCand of them, in index order
-    if (cntw > 0 && off < kCand) {
+    // 2. the workgroup's first CAP of them, in index order
+    if (cntw > 0 && off < CAP) {
         int base = off;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             const bool av = STRICT ? (pt.d[p] > thr) : (pt.d[p] >= thr);
             const uint64_t mk = __builtin_amdgcn_ballot_w64(av);
-            if (mk != 0 && base < kCand) {
+            if (mk != 0 && base < CAP) {
                 const int rank = base + lanes_below(mk);
-                if (av && rank < kCand) {
+                if (av && rank < CAP) {
                     Cand cd;
                     cd.idx = PERM ? pt.oi[p] : (uint32_t)(((wh.gw * P + p) << 6) | wh.lane);
                     cd.x = pt.x[p];
@@ -814,20 +821,22 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         }
     }
     __syncthreads();
-    int total = tot < kCand ? tot : kCand;
+    int total = tot < CAP ? tot : CAP;
     alltot = tot;
     if (wh.G == 1) return total;
 
-    // 3. exchange: every workgroup publishes its list, all take the first kCand of the cloud
+    // 3. exchange: every workgroup publishes its list, all take the first CAP of the cloud
     //    in workgroup (= index) order
+    //    (lists CAP entries apart: a word is only taken with this round's stamp, so rounds of
+    //    different CAP may lay the same buffer out differently)
     ++seq;
     const int par = (int)(seq & 1u);
     uint64_t* pk = a.ll_pk + ((int64_t)(wh.grp * 2 + par) * wh.G) * kLlSlotWords;
-    uint64_t* cd = a.ll_cd + ((int64_t)(wh.grp * 2 + par) * wh.G) * (kCand * kCandWords);
+    uint64_t* cd = a.ll_cd + ((int64_t)(wh.grp * 2 + par) * wh.G) * (kCandMax * kCandWords);
     for (int e = wh.tid; e < total * kCandWords; e += T + kCtrlThreads) {
         const int r = e / kCandWords, k = e - r * kCandWords;
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&sh.cand[r]);
-        ll_store(cd + ((int64_t)wh.g * kCand + r) * kCandWords + k, src[k], seq);
+        ll_store(cd + ((int64_t)wh.g * CAP + r) * kCandWords + k, src[k], seq);
     }
     if (wh.tid == 0) ll_store(pk + (int64_t)wh.g * kLlSlotWords + 5, (uint32_t)tot, seq);
     __syncthreads();          // sh.cand is about to be overwritten
@@ -862,7 +871,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
                     bad = true;
                 } else {
                     usum += v;
-                    sum += v < kCand ? v : kCand;
+                    sum += v < CAP ? v : CAP;
                 }
                 sh.gpre[t + 1] = sum;      // inclusive inside the lane, fixed below
             }
@@ -888,7 +897,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     __syncthreads();
     alltot = uni(sh.ctrl[1]);
     const int listed = uni(sh.gpre[wh.G]);
-    total = listed < kCand ? listed : kCand;
+    total = listed < CAP ? listed : CAP;
     if (uni(sh.ctrl[2]) == 0) {
         for (int e = wh.tid; e < total * kCandWords; e += T + kCtrlThreads) {
             const int r = e / kCandWords, k = e - r * kCandWords;
@@ -900,7 +909,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
             }
             uint32_t val[1];
             val[0] = 0;
-            const bool got = ll_wait<1>(cd + ((int64_t)lo * kCand + (r - sh.gpre[lo])) * kCandWords + k, seq,
+            const bool got = ll_wait<1>(cd + ((int64_t)lo * CAP + (r - sh.gpre[lo])) * kCandWords + k, seq,
                                         val, a.wait_ticks);
             if (!got) sh.ctrl[2] = 1;
             reinterpret_cast<uint32_t*>(&sh.cand[r])[k] = val[0];
@@ -910,36 +919,66 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     return uni(sh.ctrl[2]) != 0 ? -1 : total;
 }
 
-// Threshold phase of Alg. 2 (lines 29-33 for up to kCand picks at once): the candidates are
+// Threshold phase of Alg. 2 (list clearing and findAnyOne for up to kCandMax picks at once): the candidates are
 // taken in index order; one stays available iff no pick accepted before it in this round lies
-// closer than R_l.  Run by the control wave of every workgroup (all do the same work); each
-// accepted pick is published at once for the point waves to fold.
-template <int T>
+// closer than R_l.  Run by the control wave of every workgroup (all do the same work), lane l
+// holding candidates l and 64 + l; each accepted pick is published at once for the point waves
+// to fold.
+template <int T, bool WIDE>
 __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh, const CloudState& st,
                                                   int total, int limit, float r2, uint32_t tag)
 {
     total = uni(total);
     limit = uni(limit);
-    const bool has = wh.lane < total;
-    const Cand me = sh.cand[has ? wh.lane : 0];
-    uint64_t alive = __builtin_amdgcn_ballot_w64(has);
+    const bool has0 = wh.lane < total;
+    const bool has1 = WIDE && wh.lane + 64 < total;
+    const bool two = WIDE && total > 64;           // uniform
+    const Cand me0 = sh.cand[has0 ? wh.lane : 0];
+    Cand me1 = me0;
+    if constexpr (WIDE) me1 = sh.cand[has1 ? wh.lane + 64 : 0];
+    uint64_t alive0 = __builtin_amdgcn_ballot_w64(has0);
+    uint64_t alive1 = 0;
+    if constexpr (WIDE) alive1 = __builtin_amdgcn_ballot_w64(has1);
     int nacc = 0;
     LiveCursor cur(tag);
     __builtin_amdgcn_s_setprio(3);
-    asm volatile("" ::"v"(me.x), "v"(me.y), "v"(me.z));
-    while (alive != 0 && nacc < limit) {
-        const int cl = first_lane(alive);
-        const float ax = rdlane_f(me.x, cl), ay = rdlane_f(me.y, cl), az = rdlane_f(me.z, cl);
+    asm volatile("" ::"v"(me0.x), "v"(me0.y), "v"(me0.z));
+    if constexpr (WIDE) asm volatile("" ::"v"(me1.x), "v"(me1.y), "v"(me1.z));
+    while (alive0 != 0 && nacc < limit) {          // candidates 0..63 come first in index order
+        const int cl = first_lane(alive0);
+        const float ax = rdlane_f(me0.x, cl), ay = rdlane_f(me0.y, cl), az = rdlane_f(me0.z, cl);
         cur.publish(sh.live, (uint32_t)cl, 0u);
-        const float t = dist2(ax, ay, az, me.x, me.y, me.z);
-        const uint64_t kill = __builtin_amdgcn_ballot_w64(t < r2);     // includes the pick itself
-        alive &= ~kill;
-        alive &= ~(1ull << cl);
+        const float t0 = dist2(ax, ay, az, me0.x, me0.y, me0.z);
+        const uint64_t kill = __builtin_amdgcn_ballot_w64(t0 < r2);     // includes the pick itself
+        alive0 &= ~kill;
+        alive0 &= ~(1ull << cl);
+        if constexpr (WIDE) {
+            if (two) {
+                const float t1 = dist2(ax, ay, az, me1.x, me1.y, me1.z);
+                alive1 &= ~__builtin_amdgcn_ballot_w64(t1 < r2);
+            }
+        }
         nacc = uni(nacc + 1);
+    }
+    if constexpr (WIDE) {
+        while (alive1 != 0 && nacc < limit) {
+            const int cl = first_lane(alive1);
+            const float ax = rdlane_f(me1.x, cl), ay = rdlane_f(me1.y, cl), az = rdlane_f(me1.z, cl);
+            cur.publish(sh.live, (uint32_t)(64 + cl), 0u);
+            const float t1 = dist2(ax, ay, az, me1.x, me1.y, me1.z);
+            alive1 &= ~__builtin_amdgcn_ballot_w64(t1 < r2);
+            alive1 &= ~(1ull << cl);
+            nacc = uni(nacc + 1);
+        }
     }
     cur.publish(sh.live, kLiveEnd, 0u);
     __builtin_amdgcn_s_setprio(0);
-    if (wh.lane < nacc) {
+    if constexpr (WIDE) {
+        for (int t = wh.lane; t < nacc; t += 64) {
+            const uint32_t cl = (uint32_t)sh.live[t] & 0xFFu;
+            stage_pick<T>(sh, st.i + t, sh.cand[cl].idx, 0.0f);
+        }
+    } else if (wh.lane < nacc) {
         const uint32_t cl = (uint32_t)sh.live[wh.lane] & 0xFFu;
         stage_pick<T>(sh, st.i + wh.lane, sh.cand[cl].idx, 0.0f);
     }
@@ -949,7 +988,7 @@ __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh
 // Exact FPS for several picks at once.  The candidates are ALL points whose distance exceeds
 // tau, so every other point is at most tau and can only decrease.  Repeatedly: the candidate with
 // the largest up-to-date distance (lowest index among equals) is the true arg-max of Alg. 1
-// line 8 as long as that distance exceeds tau; accepting it lowers the other candidates'
+// as long as that distance exceeds tau; accepting it lowers the other candidates'
 // distances exactly as the fold will.  Stops when no candidate exceeds tau any more.  Run by the
 // control wave; picks are published one by one like those of the threshold phase.
 // The candidates are in ascending index order, so the lowest lane among equal distances is the
@@ -1017,7 +1056,7 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
         const uint64_t word = sh.live[wh.lane];
         const float d = __uint_as_float((uint32_t)(word >> 32));
         stage_pick<T>(sh, pos, sh.cand[(uint32_t)word & 0xFFu].idx, d);
-        if (capture) {                  // Alg. 2 line 11: keep the curve of the prefix
+        if (capture) {                  // prefix loop of Alg. 2: keep the curve
             sh.ring[pos & 63] = d;
             for (int l = 0; l < nseg; ++l)
                 if (sh.bl[l] == pos) sh.thr_meas[l] = d;
@@ -1032,7 +1071,7 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
     }
 }
 
-// ---- exact FPS for sample positions [st.i, upto) (Alg. 1 lines 3-8), in batched rounds with
+// ---- exact FPS for sample positions [st.i, upto) (the loop of Alg. 1), in batched rounds with
 // plain iterations as the fallback.  Returns false if a wait between workgroups expired.
 template <int T, int P, bool BQ, bool PERM>
 __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
@@ -1055,7 +1094,7 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
             for (int tries = 0; tries < 4 && !good; ++tries) {
                 tau = st.dlast - st.om * st.dlast;
                 PHASE_BEGIN();
-                total = scan_candidates<T, P, BQ, PERM, true>(pt, sh, wh, a, seq, tau, alltot);
+                total = scan_candidates<T, P, BQ, PERM, true, kCand>(pt, sh, wh, a, seq, tau, alltot);
                 PHASE_END(st, 1);
                 if (total < 0) return false;
                 ++st.rounds;
@@ -1075,7 +1114,7 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
             PHASE_BEGIN();
             const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
             if (wh.ctrl) resolve_chain<T, PERM>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg, tag);
-            else follow_picks<T, P, BQ, PERM>(pt, sh, wh, a, st.i, tag, total);
+            else follow_picks<T, P, BQ, PERM, false>(pt, sh, wh, a, st.i, tag, total);
             __syncthreads();
             PHASE_END(st, 2);
         }
@@ -1090,7 +1129,7 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
 }
 
 // ------------------------------------------------------------------ one cloud
-template <int T, int P, bool BQ, bool PERM>
+template <int T, int P, bool BQ, bool PERM, bool WIDE>
 __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, const Where& wh,
                                           uint32_t& it, uint32_t& seq)
 {
@@ -1171,7 +1210,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             }
         }
     }
-    if (wh.tid < kCand + 2) sh.live[wh.tid] = 0;       // round tags start at 1 in every cloud
+    if (wh.tid < kCandMax + 2) sh.live[wh.tid] = 0;    // round tags start at 1 in every cloud
     if (wh.tid < 32) {
         int64_t ik = ((int64_t)a.m * (wh.tid + 1)) / 32;
         sh.mlp_pos[wh.tid] = a.mlp ? (int)(ik < 1 ? 1 : ik) : -1;
@@ -1203,7 +1242,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         sh.chain_cycles = 0;
         sh.chain_picks = 0;
 #endif
-        Cand c0;                       // Alg. 1 line 1: the seed is sample 0, not folded yet
+        Cand c0;                       // first step of Alg. 1: the seed is sample 0, not folded yet
         c0.idx = (uint32_t)start;
         c0.x = cloud[(int64_t)start * 3 + 0];
         c0.y = cloud[(int64_t)start * 3 + 1];
@@ -1221,7 +1260,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     bool ok = fps_rounds<T, P, BQ, PERM>(pt, sh, wh, a, it, seq, st, pure_fps ? n : m + 1, !pure_fps);
 
     if (ok && !pure_fps) {
-        // ---- thresholds from the estimated curve (Eq. 1 with a/x^e; Alg. 2 lines 13, 20)
+        // ---- thresholds from the estimated curve (Eq. 1 with a/x^e; estimator call and list radii of Alg. 2)
         __syncthreads();
         if (a.use_override) {
             if (wh.tid < a.nseg) sh.thr[wh.tid] = a.thr_override[wh.tid];
@@ -1302,8 +1341,10 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         const long long thrphase_t0 = wall_clock64();
 #endif
 
-        // ---- threshold sampling (Alg. 2 lines 24-37), running-distance form
-        // The quota rule (line 22) puts sample position i on level 1 + floor(i nseg / n), i.e. on a
+        // ---- threshold sampling (main loop of Alg. 2), running-distance form
+        // candidates per round: one or (WIDE) two per lane of the control wave
+        constexpr int kCandThr = WIDE ? kCandMax : kCand;
+        // The quota rule (the level floor of Alg. 2) puts sample position i on level 1 + floor(i nseg / n), i.e. on a
         // level above l as soon as i >= ceil(n l / nseg): the positions are tabulated once, a round
         // then compares with the one that ends its level.
         if (wh.tid <= a.nseg) sh.qend[wh.tid] = (int32_t)(((int64_t)n * wh.tid + a.nseg - 1) / a.nseg);
@@ -1328,7 +1369,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #ifdef FASTPOINT_PHASE_CLOCKS
             const long long thr_t0 = wall_clock64();
 #endif
-            const int total = scan_candidates<T, P, BQ, PERM, false>(pt, sh, wh, a, seq, r2, alltot);
+            const int total = scan_candidates<T, P, BQ, PERM, false, kCandThr>(pt, sh, wh, a, seq, r2, alltot);
 #ifdef FASTPOINT_PHASE_CLOCKS
             const long long thr_t1 = wall_clock64();
             st.clk[4] += thr_t1 - thr_t0;
@@ -1337,7 +1378,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 ok = false;
                 break;
             }
-            if (total == 0) {              // level exhausted (Alg. 2 lines 34-36)
+            if (total == 0) {              // level exhausted: Alg. 2 moves to the next level
                 if (wh.tid == 0) sh.level_exhausted[seg - 1] = 1;
                 ++seg;
                 if (seg > a.nseg) break;   // early termination
@@ -1346,8 +1387,8 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 continue;
             }
             const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
-            if (wh.ctrl) resolve_threshold<T>(sh, wh, st, total, limit, r2, tag);
-            else follow_picks<T, P, BQ, PERM>(pt, sh, wh, a, st.i, tag, total);
+            if (wh.ctrl) resolve_threshold<T, WIDE>(sh, wh, st, total, limit, r2, tag);
+            else follow_picks<T, P, BQ, PERM, WIDE>(pt, sh, wh, a, st.i, tag, total);
             __syncthreads();
             ++st.resolved;
             st.npend = 0;                           // folded while they were resolved
@@ -1355,10 +1396,10 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #ifdef FASTPOINT_PHASE_CLOCKS
             st.clk[5] += wall_clock64() - thr_t1;
 #endif
-            if (alltot < kCand && st.i < level_end && st.i < n) {
+            if (alltot < kCandThr && st.i < level_end && st.i < n) {
                 // Every available point of the cloud was a candidate and the quota did not cut the
                 // round short: each one has been accepted or lies within R_l of an accepted one, so
-                // the level is exhausted (Alg. 2 lines 34-36) -- no scan is needed to find that out.
+                // the level is exhausted (Alg. 2 moves to the next one) -- no scan is needed to find that out.
                 if (wh.tid == 0) sh.level_exhausted[seg - 1] = 1;
                 ++seg;
                 if (seg > a.nseg) break;   // early termination
@@ -1371,7 +1412,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         st.clk[6] = wall_clock64() - thrphase_t0;
 #endif
         if (ok && st.i < n) {
-            // ---- early termination (Alg. 2 lines 39-53): dists is already the true running
+            // ---- early termination (closing part of Alg. 2): dists is already the true running
             //      minimum, so the remainder is exact FPS on the same registers
             et_index = st.i;
             st.dlast = -1.0f;
@@ -1411,7 +1452,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     __syncthreads();
 }
 
-template <int T, int P, bool BQ, bool PERM>
+template <int T, int P, bool BQ, bool PERM, bool WIDE>
 __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a)
 {
     __shared__ Shared<T> sh;
@@ -1429,7 +1470,7 @@ __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a
     uint32_t it = 0, seq = 0;
     for (int c = wh.grp; c < a.B; c += ngroups) {
         wh.c = c;
-        run_cloud<T, P, BQ, PERM>(a, sh, wh, it, seq);
+        run_cloud<T, P, BQ, PERM, WIDE>(a, sh, wh, it, seq);
     }
 }
 
@@ -1442,23 +1483,26 @@ __global__ void zero_words_kernel(uint64_t* p, int64_t nwords)
 }
 
 template <int T, int P>
-const void* pick_bq(bool bq, bool perm)
+const void* pick_bq(bool bq, bool perm, bool wide)
 {
-    if (perm) return bq ? nullptr : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true>);
-    return bq ? reinterpret_cast<const void*>(&sampler_kernel<T, P, true, false>)
-              : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, false>);
+    if (perm) return (bq || wide) ? nullptr : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, false>);
+    if (wide)
+        return bq ? reinterpret_cast<const void*>(&sampler_kernel<T, P, true, false, true>)
+                  : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, false, true>);
+    return bq ? reinterpret_cast<const void*>(&sampler_kernel<T, P, true, false, false>)
+              : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, false, false>);
 }
 
 }  // namespace
 
-const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm)
+const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, bool wide)
 {
     if (threads == 512) {
         switch (points_per_thread) {
-            case 2: return pick_bq<512, 2>(bq, perm);
-            case 4: return pick_bq<512, 4>(bq, perm);
-            case 8: return pick_bq<512, 8>(bq, perm);
-            case 16: return pick_bq<512, 16>(bq, perm);
+            case 2: return pick_bq<512, 2>(bq, perm, wide);
+            case 4: return pick_bq<512, 4>(bq, perm, wide);
+            case 8: return pick_bq<512, 8>(bq, perm, wide);
+            case 16: return pick_bq<512, 16>(bq, perm, wide);
             default: return nullptr;
         }
     }

@@ -1,4 +1,4 @@
-"""GPU parity of the exclusion lists (Alg. 2 lines 15-22 with the extra ball-query level of
+"""GPU parity of the exclusion lists (the list-building loops of Alg. 2 with the extra ball-query level of
 Section 4.2) and of the ball query by lookup, through the C ABI, against the CPU oracle:
 offsets and members bit-exact (the lists are index sets decided by binary32 comparisons)."""
 import ctypes

@@ -47,7 +47,7 @@ def test_matches_definition(seed, N, M, radius, k):
 
 
 def test_boundary_is_strict():
-    # neighbours at squared distance exactly r^2 are outside (Alg. 2 line 20 uses "<")
+    # neighbours at squared distance exactly r^2 are outside (Alg. 2 builds its lists with "<")
     pts = line9()
     idx, cnt = ref.ball_query(pts, [4], 2.0, 8)
     assert cnt[0] == 3 and idx[0, :3].tolist() == [3, 4, 5]

@@ -1,4 +1,4 @@
-"""Pins for the oracle's exclusion lists (Alg. 2 lines 15-22, Section 4.1 step 2; the extra
+"""Pins for the oracle's exclusion lists (the list-building loops of Alg. 2, Section 4.1 step 2; the extra
 list at the ball-query radius, Section 4.2) and the ball query by lookup in them.
 
 The lists are a plain definition; the pins are a hand-worked example, a restatement with a

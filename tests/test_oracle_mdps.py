@@ -82,7 +82,7 @@ def test_level_scale_multiplies_the_predicted_squared_value():
 
 
 def test_thresholds_inside_the_prefix_are_the_measured_values():
-    # boundaries b_l <= m take the measured curve (Alg. 2 line 13: measured prefix and
+    # boundaries b_l <= m take the measured curve (the estimator call of Alg. 2: measured prefix and
     # estimate are concatenated)
     n, m = 120, 60
     mdc = np.empty(m + 1, np.float32)
