@@ -296,6 +296,14 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         roof["fps_exact_pruned"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
                                     "frac": a / ALU_PEAK_TOPS, "equals_fps_exact": True,
                                     "note": "algorithmic operations of the unpruned update / time"}
+        # MDPS with pruned distance updates (outside the timed step): the samples of mdps_sample,
+        # timed without and with pruning (neither records the radius tests)
+        mp_plain = time_call(torch, lambda: fp.mdps_sample(x, n, sg["prm"]))
+        mp = time_call(torch, lambda: fp.mdps_sample_pruned(x, n, sg["prm"]))
+        if not (torch.equal(mp[1], midx) and torch.equal(mp_plain[1], midx)):
+            raise RuntimeError("mdps_sample_pruned differs from mdps_sample")
+        ms["mdps_sample"] = mp_plain[0]
+        ms["mdps_sample_pruned"] = mp[0]
         # MDPS with the MLP curve estimator of Appendix A.3 in place of the power function
         # (outside the timed step): latency and sampling quality
         from paper_2507_23480_amd import mlp_estimator

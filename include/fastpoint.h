@@ -143,6 +143,20 @@ fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Minimum Distance Prediction Sampling with pruned distance updates -- the same result as
+ * fp_mdps_sample, bit for bit: Algorithm 2 on the cell-ordered copy of the cloud that
+ * fp_fps_exact_pruned works on, so that the exact iterations (prefix and remainder) and the
+ * threshold-guided picks are folded only into the wavefronts they can affect.  "The lowest
+ * available index" of the threshold phase is found through a sliding window of indices, since
+ * the points are no longer held in index order.  Arguments as fp_mdps_sample without the
+ * ball-query cache; workspace of fp_fps_pruned_workspace_bytes(B, N) bytes.
+ */
+fp_status fp_mdps_sample_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
+                                const int32_t* start_idx, const fp_mdps_params* prm,
+                                int32_t* out_idx, fp_mdps_info* info,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Ball query (Section 3.1 step 2): for centre q of cloud b (a point of that
  * cloud, center_idx[b][q]) the indices j with dist^2(centre, P[j]) < radius^2
  * (strict, binary32), ascending, first k kept; unused slots repeat the first

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
-EXPORTS = ["fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
+EXPORTS = ["fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_mdps_sample_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
            "fp_ball_query", "fp_ball_query_grid_workspace_bytes", "fp_ball_query_grid", "fp_knn_workspace_bytes", "fp_knn", "fp_knn_grid_workspace_bytes", "fp_knn_grid", "fp_excl_workspace_bytes", "fp_excl_count",
            "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
@@ -107,6 +107,8 @@ def load() -> ctypes.CDLL:
     lib.fp_fps_pruned_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_fps_exact_pruned.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.fp_fps_exact_pruned.restype = i32
+    lib.fp_mdps_sample_pruned.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.fp_mdps_sample_pruned.restype = i32
     lib.fp_mdps_sample.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(FpMdpsParams), vp, vp, vp, f32,
                                    vp, ctypes.c_size_t, vp]
     lib.fp_mdps_sample.restype = i32
@@ -264,6 +266,18 @@ def fps_exact_pruned(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool =
     idx = torch.empty((B, n), dtype=torch.int32, device=xyz.device)
     mdc = torch.empty((B, n), dtype=torch.float32, device=xyz.device) if want_mdc else None
     info = torch.zeros((B, INFO_BYTES), dtype=torch.uint8, device=xyz.device) if want_info else None
+    ws = _pruned_workspace(xyz, B, N, ws)
+    _check(load().fp_fps_exact_pruned(xyz.data_ptr(), B, N, n, _ptr(st), idx.data_ptr(), _ptr(mdc), _ptr(info),
+                                      ws.data_ptr(), ws.numel(), _stream()), "fp_fps_exact_pruned")
+    out = [idx]
+    if want_mdc:
+        out.append(mdc)
+    if want_info:
+        out.append(info)
+    return out[0] if len(out) == 1 else tuple(out)
+
+
+def _pruned_workspace(xyz: torch.Tensor, B: int, N: int, ws: Optional[torch.Tensor]) -> torch.Tensor:
     need = int(load().fp_fps_pruned_workspace_bytes(B, N))
     if need == 0:
         raise ValueError("shape (B=%d, N=%d) not supported" % (B, N))
@@ -273,14 +287,21 @@ def fps_exact_pruned(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool =
         if ws is None or ws.numel() < need:
             ws = torch.empty(need, dtype=torch.uint8, device=xyz.device)
             _workspaces[key] = ws
-    _check(load().fp_fps_exact_pruned(xyz.data_ptr(), B, N, n, _ptr(st), idx.data_ptr(), _ptr(mdc), _ptr(info),
-                                      ws.data_ptr(), ws.numel(), _stream()), "fp_fps_exact_pruned")
-    out = [idx]
-    if want_mdc:
-        out.append(mdc)
-    if want_info:
-        out.append(info)
-    return out[0] if len(out) == 1 else tuple(out)
+    return ws
+
+
+def mdps_sample_pruned(xyz: torch.Tensor, n: int, prm: MdpsParams, start_idx=None, want_info: bool = False,
+                       ws: Optional[torch.Tensor] = None):
+    """Minimum distance prediction sampling with pruned distance updates: the outputs of mdps_sample."""
+    B, N = _xyz(xyz)
+    st = _start(start_idx, B, xyz.device)
+    idx = torch.empty((B, n), dtype=torch.int32, device=xyz.device)
+    info = torch.zeros((B, INFO_BYTES), dtype=torch.uint8, device=xyz.device) if want_info else None
+    ws = _pruned_workspace(xyz, B, N, ws)
+    c = prm.to_c()
+    _check(load().fp_mdps_sample_pruned(xyz.data_ptr(), B, N, n, _ptr(st), ctypes.byref(c), idx.data_ptr(),
+                                        _ptr(info), ws.data_ptr(), ws.numel(), _stream()), "fp_mdps_sample_pruned")
+    return (idx, info) if want_info else idx
 
 
 def mdps_sample(xyz: torch.Tensor, n: int, prm: MdpsParams, start_idx=None, want_info: bool = False,

@@ -210,8 +210,8 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
 
     // MDPS threshold rounds with two candidates per control-wave lane: measured faster except
     // where one workgroup both holds the cloud and records the radius tests
-    const bool wide = prm != nullptr && !pruned && (!bq || plan.G > 1);
-    const void* fn = sampler_kernel_for(plan.T, plan.P, bq, pruned, wide);
+    const int mode = prm == nullptr ? 0 : ((pruned || !bq || plan.G > 1) ? 2 : 1);
+    const void* fn = sampler_kernel_for(plan.T, plan.P, bq, pruned, mode);
     if (!fn) return FP_ERR_SHAPE;
     const unsigned grid = (unsigned)(plan.groups * plan.G);
     void* kargs[] = {&a};
@@ -270,6 +270,16 @@ fp_status fp_fps_exact_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
 {
     if (B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return FP_ERR_SHAPE;
     return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, info, nullptr, 0.0f, workspace,
+                       workspace_bytes, stream, true);
+}
+
+fp_status fp_mdps_sample_pruned(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
+                                const fp_mdps_params* prm, int32_t* out_idx, fp_mdps_info* info,
+                                void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!prm) return FP_ERR_NULL;
+    if (B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return FP_ERR_SHAPE;
+    return run_sampler(xyz, B, N, n, start_idx, prm, out_idx, nullptr, info, nullptr, 0.0f, workspace,
                        workspace_bytes, stream, true);
 }
 

@@ -63,8 +63,9 @@ struct Plan {
     int groups;         // clouds resident at once
 };
 
-// `wide`: threshold rounds of MDPS take kCandMax candidates instead of kCandPerRound
-const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, bool wide);
+// mode 0: exact FPS only; 1: MDPS, threshold rounds of kCandPerRound candidates; 2: MDPS, rounds of
+// kCandMax candidates.  NULL for a combination that is not built.
+const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, int mode);
 hipError_t launch_zero_words(uint64_t* p, int64_t nwords, hipStream_t stream);
 
 hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* center_idx, int M,

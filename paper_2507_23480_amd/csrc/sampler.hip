@@ -231,6 +231,7 @@ struct Shared {
     int32_t level_exhausted[FP_MAX_SEG];
     int32_t wcnt[NW];
     Cand cand[kCandMax];
+    int32_t rank[kCandMax];    // cell-ordered variant: position of a candidate among those of its round, by index
     Cand pend[kCand];
     int32_t bl[FP_MAX_SEG];    // segment boundaries b_l (curve positions that become thresholds)
     int32_t qend[FP_MAX_SEG + 1];   // qend[l] = ceil(n l / nseg): the quota rule raises the level to l + 1 there
@@ -669,8 +670,11 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
     int s = 0;
     RowWords<P> rw;
     rw.clear();
-    uint64_t near = ~0ull;
-    if constexpr (PERM) near = near_mask<P, BQ>(pt, sh.cand, total, wh.lane);   // PERM rounds are never WIDE
+    uint64_t near = ~0ull, near_hi = ~0ull;         // one bit per candidate (near_hi: candidates 64..127)
+    if constexpr (PERM) {
+        near = near_mask<P, BQ>(pt, sh.cand, total < 64 ? total : 64, wh.lane);
+        if constexpr (WIDE) near_hi = near_mask<P, BQ>(pt, sh.cand + 64, total - 64, wh.lane);
+    }
     uint32_t slot = lds_observe(&sh.live[0]);
     for (;;) {
         slot = uni(slot);
@@ -686,7 +690,8 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
             flush_rows<P, BQ>(rw, a, wh, base, 64);
             rw.clear();
         }
-        if (!PERM || ((near >> cl) & 1ull) != 0) {
+        const uint64_t nbit = (WIDE && cl >= 64u) ? (near_hi >> (cl - 64u)) : (near >> cl);
+        if (!PERM || (nbit & 1ull) != 0) {
             const Cand c = sh.cand[cl];
             fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, WIDE ? (s & 63) : s, rw);
         }
@@ -771,20 +776,31 @@ __device__ __forceinline__ bool plain_pick(Points<P, BQ>& pt, Shared<T>& sh, con
     return true;
 }
 
-// Collects the cloud's first CAP points (ascending index) whose distance passes the
-// threshold -- d > thr (STRICT) or d >= thr -- into sh.cand of every workgroup.
-// Returns the number collected (at most CAP), -1 if a wait expired; `alltot` receives the
-// number of points that pass in the whole cloud.
-template <int T, int P, bool BQ, bool PERM, bool STRICT, int CAP>
+// Whether slot p of this thread passes a scan: distance d > thr (STRICT) or d >= thr, and (WIN,
+// cell-ordered variant) the point's own index lies in [win_lo, win_lo + win_len).
+template <int P, bool BQ, bool STRICT, bool WIN>
+__device__ __forceinline__ bool passes(const Points<P, BQ>& pt, int p, float thr, uint32_t win_lo, uint32_t win_len)
+{
+    const bool av = STRICT ? (pt.d[p] > thr) : (pt.d[p] >= thr);
+    if constexpr (WIN) return av && (uint32_t)(pt.oi[p] - win_lo) < win_len;
+    return av;
+}
+
+// Collects the cloud's first CAP points (in the order the workgroups hold them: ascending index,
+// or cell order in the cell-ordered variant) that pass -- see passes() -- into sh.cand of every
+// workgroup.  Returns the number collected (at most CAP), -1 if a wait expired; `alltot`
+// receives the number of points that pass in the whole cloud.
+template <int T, int P, bool BQ, bool PERM, bool STRICT, int CAP, bool WIN = false>
 __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
-                                               const SamplerArgs& a, uint32_t& seq, float thr, int& alltot)
+                                               const SamplerArgs& a, uint32_t& seq, float thr, int& alltot,
+                                               uint32_t win_lo = 0, uint32_t win_len = 0)
 {
     constexpr int NW = T / 64;
     // 1. how many of this wave's points pass
     int cntw = 0;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-        const bool av = STRICT ? (pt.d[p] > thr) : (pt.d[p] >= thr);
+        const bool av = passes<P, BQ, STRICT, WIN>(pt, p, thr, win_lo, win_len);
         cntw += __builtin_popcountll(__builtin_amdgcn_ballot_w64(av));
     }
     if (wh.lane == 0 && !wh.ctrl) sh.wcnt[wh.w] = cntw;     // the control wave has none (cntw == 0)
@@ -803,7 +819,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         int base = off;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const bool av = STRICT ? (pt.d[p] > thr) : (pt.d[p] >= thr);
+            const bool av = passes<P, BQ, STRICT, WIN>(pt, p, thr, win_lo, win_len);
             const uint64_t mk = __builtin_amdgcn_ballot_w64(av);
             if (mk != 0 && base < CAP) {
                 const int rank = base + lanes_below(mk);
@@ -917,6 +933,45 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     }
     __syncthreads();
     return uni(sh.ctrl[2]) != 0 ? -1 : total;
+}
+
+// Cell-ordered variant: the candidates of a threshold round arrive in cell order, the rule of
+// the threshold phase takes them by index.  rank = number of candidates with a lower index (the
+// indices differ); the point waves count a share of the comparisons each.  Called by all threads.
+template <int T>
+__device__ __forceinline__ void sort_candidates(Shared<T>& sh, const Where& wh, int total)
+{
+    constexpr int NW = T / 64;
+    total = uni(total);
+    if (total < 2) return;
+    if (wh.tid < kCandMax) sh.rank[wh.tid] = 0;
+    __syncthreads();
+    if (!wh.ctrl) {
+        const int chunk = (total + NW - 1) / NW;
+        const int j0 = wh.w * chunk;
+        const int j1 = j0 + chunk < total ? j0 + chunk : total;
+        const bool h0 = wh.lane < total, h1 = wh.lane + 64 < total;
+        const uint32_t k0 = sh.cand[h0 ? wh.lane : 0].idx;
+        const uint32_t k1 = sh.cand[h1 ? wh.lane + 64 : 0].idx;
+        int r0 = 0, r1 = 0;
+        for (int j = j0; j < j1; ++j) {
+            const uint32_t key = sh.cand[j].idx;
+            r0 += key < k0 ? 1 : 0;
+            r1 += key < k1 ? 1 : 0;
+        }
+        if (h0 && r0 != 0) atomicAdd(&sh.rank[wh.lane], r0);
+        if (h1 && r1 != 0) atomicAdd(&sh.rank[wh.lane + 64], r1);
+    }
+    __syncthreads();
+    Cand me = {};
+    int r = 0;
+    if (wh.tid < total) {
+        me = sh.cand[wh.tid];
+        r = sh.rank[wh.tid];
+    }
+    __syncthreads();
+    if (wh.tid < total) sh.cand[r] = me;
+    __syncthreads();
 }
 
 // Threshold phase of Alg. 2 (list clearing and findAnyOne for up to kCandMax picks at once): the candidates are
@@ -1129,10 +1184,13 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
 }
 
 // ------------------------------------------------------------------ one cloud
-template <int T, int P, bool BQ, bool PERM, bool WIDE>
+// MODE 0: exact FPS only (the code of Alg. 2 is left out of the kernel); 1: MDPS with threshold rounds
+// of kCand candidates; 2: MDPS with threshold rounds of kCandMax candidates.
+template <int T, int P, bool BQ, bool PERM, int MODE>
 __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, const Where& wh,
                                           uint32_t& it, uint32_t& seq)
 {
+    constexpr bool WIDE = MODE == 2;
     const int n = a.n, N = a.N;
     const bool writer = (wh.g == 0 && wh.tid == 0);
     const float* cloud = a.xyz + (int64_t)wh.c * N * 3;
@@ -1254,12 +1312,12 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     __syncthreads();
 
     const int m = a.m;                 // exact FPS picks before the threshold phase
-    const bool pure_fps = (m >= n - 1);
+    const bool pure_fps = MODE == 0 || (m >= n - 1);
     int et_index = n;
 
     bool ok = fps_rounds<T, P, BQ, PERM>(pt, sh, wh, a, it, seq, st, pure_fps ? n : m + 1, !pure_fps);
 
-    if (ok && !pure_fps) {
+    if constexpr (MODE != 0) if (ok && !pure_fps) {
         // ---- thresholds from the estimated curve (Eq. 1 with a/x^e; estimator call and list radii of Alg. 2)
         __syncthreads();
         if (a.use_override) {
@@ -1350,6 +1408,14 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         if (wh.tid <= a.nseg) sh.qend[wh.tid] = (int32_t)(((int64_t)n * wh.tid + a.nseg - 1) / a.nseg);
         __syncthreads();
         int level_end = 0;                 // qend[seg]: first position the quota rule puts above level seg
+        // Cell-ordered variant: the points are not held in index order, so "the first available
+        // points by index" are found through a window of indices [win_lo, win_lo + win_len): within
+        // a level the picks have ascending indices and a point once unavailable stays so, hence
+        // every index below win_lo is settled; a round takes ALL available points of the window
+        // (the window is shortened and the scan repeated if they are more than a round holds) and
+        // puts them in index order -- the same candidates, in the same order, as the scan in index
+        // order would give, up to where the window ends.
+        uint32_t win_lo = 0, win_len = (uint32_t)N;
         while (st.i < n) {
             flush_picks<T, BQ>(a, sh, wh, st.flushed, st.i, false);
             if (st.i >= level_end) {
@@ -1358,9 +1424,11 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                     level_end = uni(sh.qend[seg]);
                 }
                 if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
+                win_lo = 0;                // a smaller radius: points settled so far may be available again
             }
             fold_pending<T, P, BQ, PERM>(pt, sh, wh, a, st.npend, st.i - st.npend);   // picks since the last sweep
             st.npend = 0;
+            if constexpr (PERM) refresh_bound<P, BQ>(pt);
             const float r2 = unif(sh.thr[seg - 1]);
             // samples of this level end where the quota rule would raise the level
             const int limit = (level_end < n ? level_end : n) - st.i;
@@ -1369,7 +1437,8 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #ifdef FASTPOINT_PHASE_CLOCKS
             const long long thr_t0 = wall_clock64();
 #endif
-            const int total = scan_candidates<T, P, BQ, PERM, false, kCandThr>(pt, sh, wh, a, seq, r2, alltot);
+            int total = scan_candidates<T, P, BQ, PERM, false, kCandThr, PERM>(pt, sh, wh, a, seq, r2, alltot,
+                                                                               win_lo, win_len);
 #ifdef FASTPOINT_PHASE_CLOCKS
             const long long thr_t1 = wall_clock64();
             st.clk[4] += thr_t1 - thr_t0;
@@ -1378,14 +1447,30 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 ok = false;
                 break;
             }
+            [[maybe_unused]] bool window_is_last = false;
+            if constexpr (PERM) {
+                window_is_last = (uint64_t)win_lo + win_len >= (uint64_t)N;
+                if (total >= 0 && alltot > kCandThr) {      // more than a round holds: a shorter window
+                    const uint64_t len = (uint64_t)win_len * (uint64_t)(kCandThr * 7 / 8) / (uint64_t)alltot;
+                    win_len = len < 1 ? 1u : (uint32_t)len;
+                    continue;
+                }
+                if (total == 0 && !window_is_last) {        // nothing available in the window: so little is left
+                    win_lo += win_len;                       // that all the indices beyond it come next
+                    win_len = (uint32_t)N;
+                    continue;
+                }
+            }
             if (total == 0) {              // level exhausted: Alg. 2 moves to the next level
                 if (wh.tid == 0) sh.level_exhausted[seg - 1] = 1;
                 ++seg;
                 if (seg > a.nseg) break;   // early termination
                 level_end = uni(sh.qend[seg]);
                 if (wh.tid == 0 && sh.level_start[seg - 1] < 0) sh.level_start[seg - 1] = st.i;
+                win_lo = 0;
                 continue;
             }
+            if constexpr (PERM) sort_candidates<T>(sh, wh, total);
             const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
             if (wh.ctrl) resolve_threshold<T, WIDE>(sh, wh, st, total, limit, r2, tag);
             else follow_picks<T, P, BQ, PERM, WIDE>(pt, sh, wh, a, st.i, tag, total);
@@ -1396,7 +1481,17 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #ifdef FASTPOINT_PHASE_CLOCKS
             st.clk[5] += wall_clock64() - thr_t1;
 #endif
-            if (alltot < kCandThr && st.i < level_end && st.i < n) {
+            bool exhausted = alltot < kCandThr;
+            if constexpr (PERM) {
+                // the quota did not cut the round short (checked below): the window is worked off;
+                // the next one is as long as should hold seven eighths of a round's candidates
+                exhausted = window_is_last;
+                win_lo = window_is_last ? 0u : win_lo + win_len;
+                uint64_t len = (uint64_t)win_len * (uint64_t)(kCandThr * 7 / 8) / (uint64_t)(alltot > 0 ? alltot : 1);
+                if (len > (uint64_t)win_len * 2) len = (uint64_t)win_len * 2;     // availability is uneven along the indices
+                win_len = len < 1 ? 1u : (len > (uint64_t)N ? (uint32_t)N : (uint32_t)len);
+            }
+            if (exhausted && st.i < level_end && st.i < n) {
                 // Every available point of the cloud was a candidate and the quota did not cut the
                 // round short: each one has been accepted or lies within R_l of an accepted one, so
                 // the level is exhausted (Alg. 2 moves to the next one) -- no scan is needed to find that out.
@@ -1452,7 +1547,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     __syncthreads();
 }
 
-template <int T, int P, bool BQ, bool PERM, bool WIDE>
+template <int T, int P, bool BQ, bool PERM, int MODE>
 __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a)
 {
     __shared__ Shared<T> sh;
@@ -1470,7 +1565,7 @@ __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a
     uint32_t it = 0, seq = 0;
     for (int c = wh.grp; c < a.B; c += ngroups) {
         wh.c = c;
-        run_cloud<T, P, BQ, PERM, WIDE>(a, sh, wh, it, seq);
+        run_cloud<T, P, BQ, PERM, MODE>(a, sh, wh, it, seq);
     }
 }
 
@@ -1482,27 +1577,40 @@ __global__ void zero_words_kernel(uint64_t* p, int64_t nwords)
     for (; i < nwords; i += stride) p[i] = 0;
 }
 
-template <int T, int P>
-const void* pick_bq(bool bq, bool perm, bool wide)
+template <int T, int P, bool BQ, bool PERM>
+const void* pick_mode(int mode)
 {
-    if (perm) return (bq || wide) ? nullptr : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, false>);
-    if (wide)
-        return bq ? reinterpret_cast<const void*>(&sampler_kernel<T, P, true, false, true>)
-                  : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, false, true>);
-    return bq ? reinterpret_cast<const void*>(&sampler_kernel<T, P, true, false, false>)
-              : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, false, false>);
+    switch (mode) {
+        case 0: return reinterpret_cast<const void*>(&sampler_kernel<T, P, BQ, PERM, 0>);
+        case 1: return reinterpret_cast<const void*>(&sampler_kernel<T, P, BQ, PERM, 1>);
+        case 2: return reinterpret_cast<const void*>(&sampler_kernel<T, P, BQ, PERM, 2>);
+        default: return nullptr;
+    }
+}
+
+template <int T, int P>
+const void* pick_bq(bool bq, bool perm, int mode)
+{
+    if (perm) {                     // cell-ordered: no recording, threshold rounds always wide
+        if (bq || mode == 1) return nullptr;
+        return mode == 0 ? reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, 0>)
+                         : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, 2>);
+    }
+    if (bq) return pick_mode<T, P, true, false>(mode);
+    // without recording the wide rounds were faster on every shape
+    return mode == 1 ? nullptr : pick_mode<T, P, false, false>(mode);
 }
 
 }  // namespace
 
-const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, bool wide)
+const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, int mode)
 {
     if (threads == 512) {
         switch (points_per_thread) {
-            case 2: return pick_bq<512, 2>(bq, perm, wide);
-            case 4: return pick_bq<512, 4>(bq, perm, wide);
-            case 8: return pick_bq<512, 8>(bq, perm, wide);
-            case 16: return pick_bq<512, 16>(bq, perm, wide);
+            case 2: return pick_bq<512, 2>(bq, perm, mode);
+            case 4: return pick_bq<512, 4>(bq, perm, mode);
+            case 8: return pick_bq<512, 8>(bq, perm, mode);
+            case 16: return pick_bq<512, 16>(bq, perm, mode);
             default: return nullptr;
         }
     }
