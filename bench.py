@@ -339,6 +339,11 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             "mdps_fps_tail_fraction_mean": float(sum((n - i.et_index) / n for i in infos) / len(infos)),
             "mdps_prefix_fraction": float(infos[0].m / n),
             "mdps_rounds_mean": float(sum(i.rounds for i in infos) / len(infos)),
+            # mean over the clouds of the time in each phase of Section 4.1 (device clock, the call
+            # without radius recording): exact FPS first, estimator, threshold sampling, remainder FPS
+            "mdps_phase_us": {name: float(sum(i.phase_ticks[j] for i in infos) / len(infos)) * 0.01
+                              for j, name in enumerate(["prefix_fps", "estimator_thresholds",
+                                                        "threshold_sampling", "remainder_fps"])},
             "mdps_last_level_exhausted": int(sum(1 for i in infos if i.et_index < n)),
             "mdps_speedup_vs_fps": ms.get("fps_exact", 0.0) / ms["mdps_sample+record"] if ms.get("mdps_sample+record") else None,
             "cached_ball_query_equals_brute": cached_equal,

@@ -81,6 +81,11 @@ typedef struct fp_mdps_info {
     int32_t rounds;                     /* candidate rounds of the threshold phase                */
     int32_t status;                     /* 0 ok; 1 start index out of range; 2 a bounded wait
                                            between workgroups expired (output invalid)            */
+    int32_t phase_ticks[4];             /* time the cloud spent in the four phases of Section 4.1,
+                                           in 10 ns ticks of the device's constant clock: exact FPS
+                                           iterations run first (all of them for fp_fps_exact),
+                                           estimator and thresholds, threshold-guided sampling,
+                                           exact FPS after early termination                      */
 } fp_mdps_info;
 
 /* Bytes of workspace fp_fps_exact / fp_mdps_sample need for B clouds of N points

@@ -38,7 +38,8 @@ class FpMdpsInfo(ctypes.Structure):
                 ("level_start", ctypes.c_int32 * MAX_SEG),
                 ("level_exhausted", ctypes.c_int32 * MAX_SEG),
                 ("thr2", ctypes.c_float * MAX_SEG),
-                ("rounds", ctypes.c_int32), ("status", ctypes.c_int32)]
+                ("rounds", ctypes.c_int32), ("status", ctypes.c_int32),
+                ("phase_ticks", ctypes.c_int32 * 4)]
 
 
 INFO_BYTES = ctypes.sizeof(FpMdpsInfo)

@@ -231,6 +231,7 @@ struct Shared {
     int32_t level_exhausted[FP_MAX_SEG];
     int32_t wcnt[NW];
     Cand cand[kCandMax];
+    long long phase_t[5];      // constant 100 MHz clock at the phase boundaries of the cloud in hand (thread 0)
     int32_t rank[kCandMax];    // cell-ordered variant: position of a candidate among those of its round, by index
     Cand pend[kCand];
     int32_t bl[FP_MAX_SEG];    // segment boundaries b_l (curve positions that become thresholds)
@@ -1314,9 +1315,17 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     const int m = a.m;                 // exact FPS picks before the threshold phase
     const bool pure_fps = MODE == 0 || (m >= n - 1);
     int et_index = n;
+    if (wh.tid == 0) {
+        const long long t = wall_clock64();
+        for (int k = 0; k < 5; ++k) sh.phase_t[k] = t;
+    }
 
     bool ok = fps_rounds<T, P, BQ, PERM>(pt, sh, wh, a, it, seq, st, pure_fps ? n : m + 1, !pure_fps);
 
+    if (wh.tid == 0) {
+        const long long t = wall_clock64();
+        for (int k = 1; k < 5; ++k) sh.phase_t[k] = t;
+    }
     if constexpr (MODE != 0) if (ok && !pure_fps) {
         // ---- thresholds from the estimated curve (Eq. 1 with a/x^e; estimator call and list radii of Alg. 2)
         __syncthreads();
@@ -1395,6 +1404,10 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         }
         __syncthreads();
         int seg = 0;
+        if (wh.tid == 0) {
+            const long long t = wall_clock64();
+            for (int k = 2; k < 5; ++k) sh.phase_t[k] = t;
+        }
 #ifdef FASTPOINT_PHASE_CLOCKS
         const long long thrphase_t0 = wall_clock64();
 #endif
@@ -1506,6 +1519,11 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #ifdef FASTPOINT_PHASE_CLOCKS
         st.clk[6] = wall_clock64() - thrphase_t0;
 #endif
+        if (wh.tid == 0) {
+            const long long t = wall_clock64();
+            sh.phase_t[3] = t;
+            sh.phase_t[4] = t;
+        }
         if (ok && st.i < n) {
             // ---- early termination (closing part of Alg. 2): dists is already the true running
             //      minimum, so the remainder is exact FPS on the same registers
@@ -1529,6 +1547,10 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             inf.thr2[l] = sh.thr[l];
         }
         inf.rounds = st.rounds;
+        if constexpr (MODE != 0) {
+            if (!pure_fps) sh.phase_t[4] = wall_clock64();          // end of the remainder FPS
+        }
+        for (int k = 0; k < 4; ++k) inf.phase_ticks[k] = (int32_t)(sh.phase_t[k + 1] - sh.phase_t[k]);
 #ifdef FASTPOINT_PHASE_CLOCKS
         if (a.nseg <= 8)
         {

@@ -158,3 +158,19 @@ def test_error_codes(fp):
     assert bq(0.1, 0) == -2 and bq(0.1, 255) == -2
     torch.cuda.synchronize()
     assert lib.fp_status_string(0) == b"ok" and len(lib.fp_status_string(-3)) > 0
+
+
+def test_phase_times_are_reported(fp):
+    """info.phase_ticks: the four phases of MDPS add up to less than the call, exact FPS has one."""
+    from paper_2507_23480_amd import calibration
+    x = dev(inputs.make_batch("C2"))
+    _, info = fp.mdps_sample(x, 512, calibration.params_for("C2", 0), want_info=True)
+    _, finfo = fp.fps_exact(x, 512, want_info=True)
+    torch.cuda.synchronize()
+    for i in fp.parse_info(info):
+        t = list(i.phase_ticks)
+        assert all(v >= 0 for v in t) and t[0] > 0 and t[2] > 0
+        assert sum(t) < 100 * 1000 * 100          # well under a second (10 ns ticks)
+    for i in fp.parse_info(finfo):
+        t = list(i.phase_ticks)
+        assert t[0] > 0 and t[1] == 0 and t[2] == 0 and t[3] == 0
