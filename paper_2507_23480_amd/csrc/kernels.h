@@ -13,7 +13,7 @@ constexpr int kMaxGroup = 256;          // most workgroups one cloud is spread o
 constexpr int kLlSlotWords = 8;         // 64-bit words per workgroup slot of the pick exchange
 constexpr int kCandPerRound = 64;       // candidates per round of exact FPS (one per lane of the control wave)
 constexpr int kCandMax = 128;           // candidates per round of the threshold phase (two per lane)
-constexpr int kCandWords = 5;           // exchanged 64-bit words per candidate (idx, x, y, z, distance)
+constexpr int kCandWords = 5;           // exchanged 64-bit words per candidate (x, y, z, index, distance)
 constexpr uint32_t kBqMagic = 0x46504251u;
 
 // Header at the start of a ball-query cache (device memory).  The radius tests are kept as a

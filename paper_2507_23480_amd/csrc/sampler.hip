@@ -210,9 +210,12 @@ struct Rec {          // one arg-max candidate: squared distance bits, index, co
     uint32_t pad0, pad1;
 };
 
-struct Cand {         // a candidate or accepted pick: index, coordinates, squared distance bits
-    uint32_t idx;
+// A candidate or accepted pick: coordinates, index, squared distance bits.  The coordinates and
+// the index are one aligned 16-byte quarter of the 32-byte record, so a lane that reads its own
+// record takes them with one 128-bit LDS read (32-bit reads 32 bytes apart collide eight ways).
+struct alignas(16) Cand {
     float x, y, z;
+    uint32_t idx;
     uint32_t d;
     uint32_t pad0, pad1, pad2;
 };
