@@ -336,6 +336,9 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             "N": N, "n": n, "radius": sg["radius"], "k": k, "plan_G_T_P": list(fp.plan(B, N)),
             "kernel_ms": ms,
             "mdps_coverage_ratio_max": float(ratio.max()), "mdps_coverage_ratio_mean": float(ratio.mean()),
+            # the paper's quality figure (Table 1): mean distance from a sample to the nearest other
+            # sample, MDPS relative to exact FPS
+            "mdps_sample_spacing_ratio": sample_spacing(torch, fp, x, midx) / sample_spacing(torch, fp, x, idx),
             "mdps_fps_tail_fraction_mean": float(sum((n - i.et_index) / n for i in infos) / len(infos)),
             "mdps_prefix_fraction": float(infos[0].m / n),
             "mdps_rounds_mean": float(sum(i.rounds for i in infos) / len(infos)),
@@ -350,6 +353,19 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             "mdps_mlp_estimator": mlp_detail,
             "roofline": roof})
     return out
+
+
+def sample_spacing(torch, fp, x, sidx):
+    """Mean over the clouds' samples of the distance to the nearest other sample (through fp_knn on
+    the gathered samples: the nearest sample of a sample is itself, the second is the one wanted)."""
+    xs = fp.gather_xyz(x, sidx).contiguous()
+    B, n = sidx.shape[0], sidx.shape[1]
+    if n < 2:
+        return 1.0
+    every = torch.arange(n, dtype=torch.int32, device=x.device).repeat(B, 1).contiguous()
+    _, d2 = fp.knn(xs, every, 2)
+    torch.cuda.synchronize()
+    return float(d2[:, :, 1].double().sqrt().mean())
 
 
 def time_call(torch, fn, reps=3):
