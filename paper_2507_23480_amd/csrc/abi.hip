@@ -186,26 +186,14 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
     }
     const bool bq = bq_cache != nullptr;
     if (bq) {
-        BqHeader h;
-        memset(&h, 0, sizeof(h));
-        h.magic = kBqMagic;
-        h.B = B;
-        h.N = N;
-        h.n = n;
-        h.blocks = (int32_t)bq_blocks(N);
-        h.col_words = bq_col_words(n);
-        const float r2 = bq_radius * bq_radius;
-        memcpy(&h.r2_bits, &r2, sizeof(r2));
-        h.valid = 1;
-        h.idx_offset = 256;
-        h.bits_offset = 256 + align_up((int64_t)B * n * 4, 256);
+        // layout: a 256-byte header (written by the sampler kernel), the copy of the sample
+        // indices, the radius-test words
         unsigned char* base = reinterpret_cast<unsigned char*>(bq_cache);
-        a.bq_idx = reinterpret_cast<int32_t*>(base + h.idx_offset);
-        a.bq_bits = reinterpret_cast<uint64_t*>(base + h.bits_offset);
-        a.bq_r2 = r2;
-        a.bq_blocks = h.blocks;
-        a.bq_col_words = h.col_words;
-        if (launch_bq_header(bq_cache, h, stream) != hipSuccess) return FP_ERR_DEVICE;
+        a.bq_idx = reinterpret_cast<int32_t*>(base + 256);
+        a.bq_bits = reinterpret_cast<uint64_t*>(base + 256 + align_up((int64_t)B * n * 4, 256));
+        a.bq_r2 = bq_radius * bq_radius;
+        a.bq_blocks = (int32_t)bq_blocks(N);
+        a.bq_col_words = bq_col_words(n);
     }
 
     // MDPS threshold rounds with two candidates per control-wave lane: measured faster except

@@ -292,8 +292,6 @@ __global__ __launch_bounds__(256) void coverage_kernel(const float* __restrict__
     if (threadIdx.x == 0) atomicMax(reinterpret_cast<unsigned int*>(out) + b, red[0]);
 }
 
-__global__ void bq_header_kernel(BqHeader* dst, BqHeader h) { *dst = h; }
-
 }  // namespace
 
 hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* center_idx, int M,
@@ -360,12 +358,6 @@ hipError_t launch_coverage(const float* xyz, int B, int N, const float* sxyz, in
     hipLaunchKernelGGL(zero_floats_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, stream, out, B);
     hipLaunchKernelGGL(coverage_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)B), dim3(256), 0,
                        stream, xyz, N, sxyz, n, out);
-    return hipGetLastError();
-}
-
-hipError_t launch_bq_header(void* cache, const BqHeader& h, hipStream_t stream)
-{
-    hipLaunchKernelGGL(bq_header_kernel, dim3(1), dim3(1), 0, stream, reinterpret_cast<BqHeader*>(cache), h);
     return hipGetLastError();
 }
 

@@ -78,7 +78,6 @@ hipError_t launch_coverage(const float* xyz, int B, int N, const float* sxyz, in
 hipError_t launch_knn(const float* xyz, int B, int N, const int32_t* sample_idx, int n, int k,
                       int32_t* out_pos, float* out_d2, const void* bq_cache, int32_t* flags,
                       int32_t* count, int32_t* list, int32_t* out_deferred, hipStream_t stream);
-hipError_t launch_bq_header(void* cache, const BqHeader& h, hipStream_t stream);
 
 // Uniform grid of one cloud for the exclusion-list kernels (device memory, in the workspace).
 struct ExclGrid {

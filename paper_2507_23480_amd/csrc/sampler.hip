@@ -1587,6 +1587,27 @@ __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a
     // the control wave's slots lie beyond every point of the cloud: they are padding
     wh.gw = wh.ctrl ? a.G * (T / 64) : wh.g * (T / 64) + wh.w;
     const int ngroups = (int)gridDim.x / a.G;
+    if constexpr (BQ) {
+        // the header of the ball-query cache (256 bytes in front of the copy of the sample indices):
+        // written here rather than by a launch of its own, which would lie in front of every
+        // recording sampler on the stream
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            unsigned char* base = reinterpret_cast<unsigned char*>(a.bq_idx) - 256;
+            BqHeader h;
+            h.magic = kBqMagic;
+            h.B = a.B;
+            h.N = a.N;
+            h.n = a.n;
+            h.blocks = a.bq_blocks;
+            h.reserved = 0;
+            h.col_words = a.bq_col_words;
+            h.r2_bits = __float_as_uint(a.bq_r2);
+            h.valid = 1;
+            h.idx_offset = 256;
+            h.bits_offset = (int64_t)(reinterpret_cast<unsigned char*>(a.bq_bits) - base);
+            *reinterpret_cast<BqHeader*>(base) = h;
+        }
+    }
     uint32_t it = 0, seq = 0;
     for (int c = wh.grp; c < a.B; c += ngroups) {
         wh.c = c;
