@@ -681,11 +681,13 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
     }
     uint32_t slot = lds_observe(&sh.live[0]);
     for (;;) {
+        // wait for slot s of this round (requested before the previous pick was folded); nothing
+        // but the slot changes in the inner loop, so the distances and row words stay where they
+        // are across it
         slot = uni(slot);
-        if ((slot & ~0xFFu) != tag) {               // not written yet in this round
+        while ((slot & ~0xFFu) != tag) {            // not written yet in this round
             __builtin_amdgcn_s_sleep(1);
-            slot = lds_observe(&sh.live[s]);
-            continue;
+            slot = uni(lds_observe(&sh.live[s]));
         }
         if ((slot & 0xFFu) == kLiveEnd) break;
         const uint32_t cl = slot & 0xFFu;
