@@ -195,12 +195,16 @@ struct LiveCursor {
         off += 8;
     }
 };
+// The low half of a slot (tag and candidate lane).  A 32-bit read on purpose: the unused high half of
+// a 64-bit read would occupy a register that the next instructions reuse, and the wait for that
+// would put the read of the slot and the read of the pick's coordinates one after the other.
 __device__ __forceinline__ uint32_t lds_observe(const uint64_t* p)
 {
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
-    const uint64_t v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    const uint32_t v = __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_WORKGROUP);
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
-    return (uint32_t)v;
+    return v;
 }
 
 struct Rec {          // one arg-max candidate: squared distance bits, index, coordinates
