@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "kernels.h"
 
 #pragma clang fp contract(off)
@@ -323,14 +325,33 @@ hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* cent
         else
             return hipErrorInvalidValue;
     } else {
-        // as many waves per group of 64 centres as the hit lists leave room for in 48 KB of LDS
-        if (8 * per_wave <= 48 * 1024)
+        // As many waves per group of 64 centres as the hit lists leave room for in LDS: 48 KB, so
+        // that several workgroups share a compute unit -- or, when the grid would leave most
+        // compute units empty anyway, 144 of the 160 KB, which shortens each wave's scan.
+        const int64_t groups = (int64_t)grid.x * grid.y;
+        const size_t budget = groups <= 512 ? (size_t)144 * 1024 : (size_t)48 * 1024;
+        // more than 64 KB has to be asked for, once per device
+        static std::atomic<uint64_t> lds_raised{0};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return hipErrorInvalidValue;
+        if (((lds_raised.load() >> dev) & 1u) == 0) {
+            const int most = 160 * 1024;
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&bq_brute_kernel<8>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, most) != hipSuccess ||
+                hipFuncSetAttribute(reinterpret_cast<const void*>(&bq_brute_kernel<4>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, most) != hipSuccess ||
+                hipFuncSetAttribute(reinterpret_cast<const void*>(&bq_brute_kernel<2>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, most) != hipSuccess)
+                return hipErrorInvalidValue;
+            lds_raised.fetch_or((uint64_t)1 << dev);
+        }
+        if (8 * per_wave <= budget)
             hipLaunchKernelGGL(bq_brute_kernel<8>, grid, dim3(512), 8 * per_wave, stream, xyz, N, center_idx, M,
                                r2, k, out_idx, out_cnt);
-        else if (4 * per_wave <= 48 * 1024)
+        else if (4 * per_wave <= budget)
             hipLaunchKernelGGL(bq_brute_kernel<4>, grid, dim3(256), 4 * per_wave, stream, xyz, N, center_idx, M,
                                r2, k, out_idx, out_cnt);
-        else if (2 * per_wave <= 48 * 1024)
+        else if (2 * per_wave <= budget)
             hipLaunchKernelGGL(bq_brute_kernel<2>, grid, dim3(128), 2 * per_wave, stream, xyz, N, center_idx, M,
                                r2, k, out_idx, out_cnt);
         else if (per_wave <= 64 * 1024)
