@@ -130,27 +130,36 @@ def run_step(fp, ctx, timer, keep=None):
 
 
 def run_step_streams(torch, fp, ctx, keep=None):
-    """One step with the two sampling paths of a stage on two streams where both fit on the
-    device side by side (one workgroup per cloud): the exact path (fps_exact, ball query, gather)
-    on the current stream, the FastPoint path (mdps_sample with recording, cache reader) on a
-    second one that starts when the stage's input is ready.  The next stage waits for the gather."""
+    """One step on two streams where the work of a stage fits on the device side by side (one
+    workgroup per cloud).  The samplers are what takes the time: mdps_sample (with recording) of
+    every stage runs on the second stream, one after the other, each as soon as its input (the
+    gather of the stage before) is there; exact FPS, the brute-force ball query, the gather and
+    the cache reader of the FastPoint path (which follows the mdps_sample whose cache it reads)
+    run on the current stream; only the last stage's cache reader stays behind its sampler."""
     main = torch.cuda.current_stream()
     side = ctx["side"]
     x = ctx["xyz"]
     for s, sg in enumerate(ctx["stages"]):
         n, r, k = sg["n"], sg["radius"], sg["k"]
         two = sg["G"] == 1
-        if two:
-            side.wait_stream(main)                  # the stage's input is ready
+        if two and s == 0:
+            side.wait_stream(main)                  # the first stage's input is ready
         idx = fp.fps_exact(x, n, ws=sg["ws"][0])
         bq = fp.ball_query(x, idx, r, k)
         with torch.cuda.stream(side if two else main):
             midx = fp.mdps_sample(x, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r, ws=sg["ws"][1])
+        last = s + 1 == len(ctx["stages"])
+        x_next = None if last else fp.gather_xyz(x, idx)
+        if two and not last:
+            # mdps_sample is the longer of the two samplers: its ball query goes behind the exact
+            # path's work, and the next mdps_sample starts as soon as the gather is done
+            main.wait_stream(side)
+            side.wait_stream(main)
+        with torch.cuda.stream(side if two and last else main):
             mbq = fp.ball_query(x, midx, r, k, bq_cache=sg["cache"])
         if keep is not None:
             keep.append((x, idx, bq, midx, mbq))
-        if s + 1 < len(ctx["stages"]):
-            x = fp.gather_xyz(x, idx)
+        x = x_next
     main.wait_stream(side)
 
 

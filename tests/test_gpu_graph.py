@@ -42,17 +42,22 @@ def test_graph_replay_of_two_stream_step_equals_eager_and_oracle():
     def step(keep):
         main = torch.cuda.current_stream()
         x = xyz
+        side.wait_stream(main)
         for s, sg in enumerate(stages):
-            side.wait_stream(main)
+            last = s + 1 == len(stages)
             idx = fp.fps_exact(x, sg["n"], ws=sg["ws"][0])
             bq = fp.ball_query(x, idx, sg["r"], sg["k"])
             with torch.cuda.stream(side):
                 midx = fp.mdps_sample(x, sg["n"], sg["prm"], bq_cache=sg["cache"], bq_radius=sg["r"],
                                       ws=sg["ws"][1])
+            x_next = None if last else fp.gather_xyz(x, idx)
+            if not last:
+                main.wait_stream(side)
+                side.wait_stream(main)
+            with torch.cuda.stream(side if last else main):
                 mbq = fp.ball_query(x, midx, sg["r"], sg["k"], bq_cache=sg["cache"])
             keep.append((idx, bq[0], bq[1], midx, mbq[0], mbq[1]))
-            if s + 1 < len(stages):
-                x = fp.gather_xyz(x, idx)
+            x = x_next
         main.wait_stream(side)
 
     eager = []
