@@ -573,6 +573,13 @@ def run(args, torch, fp, inputs, calibration, extra):
     roof["kernel"] = dom + " (stage 0)"
     roof["ms_per_launch"] = s0["kernel_ms"][dom]
     roof["traffic"] = TRAFFIC_BYTES.get(name, {}).get(dom)
+    if dom in ("fps_exact", "mdps_sample+record"):
+        # the sampler runs a cloud on plan.G workgroups, one per compute unit: what share of the
+        # device the launch can occupy at all, and the fraction of those units' peak
+        G = ctx["stages"][0]["G"]
+        units = min(256, wl.B * G)
+        roof["compute_units_in_use"] = units
+        roof["frac_of_units_in_use"] = roof["frac"] * 256.0 / units
     # graph replay after all eager measurements of this process (see measure_graph)
     ms_per_step, launch_mode = seq_ms, EAGER
     if one_workgroup_per_cloud(ctx):
