@@ -1187,8 +1187,8 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
         st.npend = 0;                               // folded while they were resolved
         st.dlast = __uint_as_float(uni((uint32_t)sh.ctrl[3]));
         st.i += uni(sh.ctrl[0]);
-        if (alltot < 32) st.om = st.om * 1.15f < 0.99f ? st.om * 1.15f : 0.99f;
-        else if (alltot > 52) st.om = st.om * 0.87f;
+        if (alltot < 40) st.om = st.om * 1.15f < 0.99f ? st.om * 1.15f : 0.99f;
+        else if (alltot > 58) st.om = st.om * 0.87f;
     }
     return true;
 }
