@@ -1087,7 +1087,56 @@ __device__ __forceinline__ int chain_loop(uint64_t* live, LiveCursor& cur, const
     return nacc;
 }
 
-template <int T, bool PERM>
+// The same run with two candidates per lane (lane l holds candidates l and 64 + l of the round's
+// list, which is in ascending index order -- or, cell-ordered variant, in any order with ties
+// settled by the points' own indices).  A step costs a third more instructions; a round takes
+// twice the candidates, which halves the scans and their exchanges between workgroups.
+template <bool CHECK, bool PERM>
+__device__ __forceinline__ int chain_loop_wide(uint64_t* live, LiveCursor& cur, const Cand& me0, const Cand& me1,
+                                               uint32_t& cd0, uint32_t& cd1, uint32_t tau_bits, int limit,
+                                               uint32_t& dl)
+{
+    int nacc = 0;
+    uint32_t dmax = wave_max_scalar(max(cd0, cd1));
+    while (dmax > tau_bits) {
+        if (CHECK && nacc >= limit) break;
+        uint64_t e0 = __builtin_amdgcn_ballot_w64(cd0 == dmax);
+        uint64_t e1 = __builtin_amdgcn_ballot_w64(cd1 == dmax);
+        if (PERM && __builtin_expect(__builtin_popcountll(e0) + __builtin_popcountll(e1) > 1, 0)) {
+            // cell order: among equal distances the lowest index of the caller's cloud
+            const uint32_t i0 = cd0 == dmax ? me0.idx : kNoIdx;
+            const uint32_t i1 = cd1 == dmax ? me1.idx : kNoIdx;
+            const uint32_t imin = wave_min_u32(min(i0, i1));
+            e0 = __builtin_amdgcn_ballot_w64(i0 == imin);
+            e1 = __builtin_amdgcn_ballot_w64(i1 == imin);
+        }
+        float ax, ay, az;
+        uint32_t slot;
+        if (e0 != 0) {                                  // the lower half of the list comes first
+            const int cl = first_lane(e0);
+            ax = rdlane_f(me0.x, cl);
+            ay = rdlane_f(me0.y, cl);
+            az = rdlane_f(me0.z, cl);
+            slot = (uint32_t)cl;
+        } else {
+            const int cl = first_lane(e1);
+            ax = rdlane_f(me1.x, cl);
+            ay = rdlane_f(me1.y, cl);
+            az = rdlane_f(me1.z, cl);
+            slot = 64u + (uint32_t)cl;
+        }
+        cur.publish(live, slot, dmax);
+        dl = dmax;
+        // lanes without a candidate hold 0 and stay there
+        cd0 = min(cd0, __float_as_uint(dist2(ax, ay, az, me0.x, me0.y, me0.z)));
+        cd1 = min(cd1, __float_as_uint(dist2(ax, ay, az, me1.x, me1.y, me1.z)));
+        nacc = uni(nacc + 1);
+        dmax = wave_max_scalar(max(cd0, cd1));
+    }
+    return nacc;
+}
+
+template <int T, bool PERM, bool WIDE>
 __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, const CloudState& st,
                                               int total, int limit, float tau, bool capture, int nseg,
                                               uint32_t tag)
@@ -1097,6 +1146,10 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
     const bool has = wh.lane < total;
     const Cand me = sh.cand[has ? wh.lane : 0];
     uint32_t cd = has ? me.d : 0u;                     // bit pattern; distances are >= +0
+    const bool has1 = WIDE && wh.lane + 64 < total;
+    Cand me1 = me;
+    if constexpr (WIDE) me1 = sh.cand[has1 ? wh.lane + 64 : 0];
+    uint32_t cd1 = has1 ? me1.d : 0u;
     const uint32_t tau_bits = uni(__float_as_uint(tau));    // tau >= 0
     uint32_t dl = __float_as_uint(st.dlast);
     LiveCursor cur(tag);
@@ -1106,8 +1159,16 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
 #endif
     // the candidates have arrived from LDS before the loop starts, not inside it
     asm volatile("" ::"v"(me.x), "v"(me.y), "v"(me.z), "v"(cd));
-    const int nacc = limit >= total ? chain_loop<false, PERM>(sh.live, cur, me, cd, tau_bits, limit, dl)
-                                    : chain_loop<true, PERM>(sh.live, cur, me, cd, tau_bits, limit, dl);
+    int nacc;
+    if constexpr (WIDE) {
+        asm volatile("" ::"v"(me1.x), "v"(me1.y), "v"(me1.z), "v"(cd1));
+        nacc = limit >= total
+                   ? chain_loop_wide<false, PERM>(sh.live, cur, me, me1, cd, cd1, tau_bits, limit, dl)
+                   : chain_loop_wide<true, PERM>(sh.live, cur, me, me1, cd, cd1, tau_bits, limit, dl);
+    } else {
+        nacc = limit >= total ? chain_loop<false, PERM>(sh.live, cur, me, cd, tau_bits, limit, dl)
+                              : chain_loop<true, PERM>(sh.live, cur, me, cd, tau_bits, limit, dl);
+    }
     cur.publish(sh.live, kLiveEnd, 0u);
     __builtin_amdgcn_s_setprio(0);
 #ifdef FASTPOINT_PHASE_CLOCKS
@@ -1116,9 +1177,9 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
         sh.chain_picks += nacc;
     }
 #endif
-    if (wh.lane < nacc) {
-        const int pos = st.i + wh.lane;
-        const uint64_t word = sh.live[wh.lane];
+    for (int t = wh.lane; t < nacc; t += 64) {             // a second turn only after a wide round
+        const int pos = st.i + t;
+        const uint64_t word = sh.live[t];
         const float d = __uint_as_float((uint32_t)(word >> 32));
         stage_pick<T>(sh, pos, sh.cand[(uint32_t)word & 0xFFu].idx, d);
         if (capture) {                  // prefix loop of Alg. 2: keep the curve
@@ -1138,11 +1199,12 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
 
 // ---- exact FPS for sample positions [st.i, upto) (the loop of Alg. 1), in batched rounds with
 // plain iterations as the fallback.  Returns false if a wait between workgroups expired.
-template <int T, int P, bool BQ, bool PERM>
-__device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
-                                           const SamplerArgs& a, uint32_t& it, uint32_t& seq,
-                                           CloudState& st, int upto, bool capture)
+template <int T, int P, bool BQ, bool PERM, bool kWideFps>
+__device__ __forceinline__ bool fps_rounds_of(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                              const SamplerArgs& a, uint32_t& it, uint32_t& seq,
+                                              CloudState& st, int upto, bool capture)
 {
+    constexpr int kCandFps = kWideFps ? kCandMax : kCand;
     while (st.i < upto) {
         flush_picks<T, BQ>(a, sh, wh, st.flushed, st.i, false);
         {
@@ -1159,11 +1221,11 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
             for (int tries = 0; tries < 4 && !good; ++tries) {
                 tau = st.dlast - st.om * st.dlast;
                 PHASE_BEGIN();
-                total = scan_candidates<T, P, BQ, PERM, true, kCand>(pt, sh, wh, a, seq, tau, alltot);
+                total = scan_candidates<T, P, BQ, PERM, true, kCandFps>(pt, sh, wh, a, seq, tau, alltot);
                 PHASE_END(st, 1);
                 if (total < 0) return false;
                 ++st.rounds;
-                if (alltot > 0 && alltot <= kCand) good = true;
+                if (alltot > 0 && alltot <= kCandFps) good = true;
                 else if (alltot == 0) st.om = st.om * 2.0f < 0.99f ? st.om * 2.0f : 0.99f;
                 else st.om = st.om * 0.5f;
             }
@@ -1178,8 +1240,8 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
         {
             PHASE_BEGIN();
             const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
-            if (wh.ctrl) resolve_chain<T, PERM>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg, tag);
-            else follow_picks<T, P, BQ, PERM, false>(pt, sh, wh, a, st.i, tag, total);
+            if (wh.ctrl) resolve_chain<T, PERM, kWideFps>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg, tag);
+            else follow_picks<T, P, BQ, PERM, kWideFps>(pt, sh, wh, a, st.i, tag, total);
             __syncthreads();
             PHASE_END(st, 2);
         }
@@ -1187,10 +1249,29 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
         st.npend = 0;                               // folded while they were resolved
         st.dlast = __uint_as_float(uni((uint32_t)sh.ctrl[3]));
         st.i += uni(sh.ctrl[0]);
-        if (alltot < 40) st.om = st.om * 1.15f < 0.99f ? st.om * 1.15f : 0.99f;
-        else if (alltot > 58) st.om = st.om * 0.87f;
+        if (alltot < 40 * (kCandFps / kCand)) st.om = st.om * 1.15f < 0.99f ? st.om * 1.15f : 0.99f;
+        else if (alltot > 58 * (kCandFps / kCand)) st.om = st.om * 0.87f;
     }
     return true;
+}
+
+// Rounds of 64 or of 128 candidates.  With four or more points per thread folding a pick takes the
+// point waves longer than finding it takes the control wave, so the longer chain step of a round
+// with two candidates per lane is hidden and the halved number of scans is a gain.  With two
+// points per thread the chain is what a pick costs, and the wide round pays only where a scan is
+// expensive: when the cloud is spread over many workgroups (measured: 24 yes, 4 and 1 no).
+template <int T, int P, bool BQ, bool PERM>
+__device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                           const SamplerArgs& a, uint32_t& it, uint32_t& seq,
+                                           CloudState& st, int upto, bool capture)
+{
+    if constexpr (P >= 4) {
+        return fps_rounds_of<T, P, BQ, PERM, true>(pt, sh, wh, a, it, seq, st, upto, capture);
+    } else {
+        if constexpr (!PERM)            // (the cell-ordered variant gained nothing there and pays for the code)
+            if (wh.G >= 8) return fps_rounds_of<T, P, BQ, PERM, true>(pt, sh, wh, a, it, seq, st, upto, capture);
+        return fps_rounds_of<T, P, BQ, PERM, false>(pt, sh, wh, a, it, seq, st, upto, capture);
+    }
 }
 
 // ------------------------------------------------------------------ one cloud
