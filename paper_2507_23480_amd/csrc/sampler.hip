@@ -1260,7 +1260,8 @@ __device__ __forceinline__ bool fps_rounds_of(Points<P, BQ>& pt, Shared<T>& sh, 
 // with two candidates per lane is hidden and the halved number of scans is a gain.  With two
 // points per thread the chain is what a pick costs, and the wide round pays only where a scan is
 // expensive: when the cloud is spread over many workgroups (measured: 24 yes, 4 and 1 no).
-template <int T, int P, bool BQ, bool PERM>
+// ONE_WG: the kernel is only ever launched with one workgroup per cloud.
+template <int T, int P, bool BQ, bool PERM, bool ONE_WG>
 __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                            const SamplerArgs& a, uint32_t& it, uint32_t& seq,
                                            CloudState& st, int upto, bool capture)
@@ -1268,7 +1269,7 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
     if constexpr (P >= 4) {
         return fps_rounds_of<T, P, BQ, PERM, true>(pt, sh, wh, a, it, seq, st, upto, capture);
     } else {
-        if constexpr (!PERM)            // (the cell-ordered variant gained nothing there and pays for the code)
+        if constexpr (!PERM && !ONE_WG) // (the cell-ordered variant gained nothing there and pays for the code)
             if (wh.G >= 8) return fps_rounds_of<T, P, BQ, PERM, true>(pt, sh, wh, a, it, seq, st, upto, capture);
         return fps_rounds_of<T, P, BQ, PERM, false>(pt, sh, wh, a, it, seq, st, upto, capture);
     }
@@ -1410,7 +1411,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         for (int k = 0; k < 5; ++k) sh.phase_t[k] = t;
     }
 
-    bool ok = fps_rounds<T, P, BQ, PERM>(pt, sh, wh, a, it, seq, st, pure_fps ? n : m + 1, !pure_fps);
+    bool ok = fps_rounds<T, P, BQ, PERM, MODE == 1>(pt, sh, wh, a, it, seq, st, pure_fps ? n : m + 1, !pure_fps);
 
     if (wh.tid == 0) {
         const long long t = wall_clock64();
@@ -1619,7 +1620,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             //      minimum, so the remainder is exact FPS on the same registers
             et_index = st.i;
             st.dlast = -1.0f;
-            ok = fps_rounds<T, P, BQ, PERM>(pt, sh, wh, a, it, seq, st, n, false);
+            ok = fps_rounds<T, P, BQ, PERM, MODE == 1>(pt, sh, wh, a, it, seq, st, n, false);
         }
     }
     // the rows of the picks that were never folded (at least the last sample) are still missing
