@@ -266,6 +266,7 @@ struct Where {
     int g, G, grp;        // workgroup in cloud, workgroups per cloud, group slot in the grid
     int gw;               // wave in cloud
     int c;                // cloud
+    uint64_t* rows;       // recording kernels: this wave's [P][64] radius-test words in LDS
 };
 
 // P floats that stay in registers; element [p] with a wave-uniform p compiles to
@@ -310,14 +311,20 @@ __device__ __forceinline__ float box_dist2(const Points<P, BQ>& pt, float cx, fl
 }
 
 // Radius-test results of up to 64 picks that a wave has folded but not written to the cache
-// yet: lane s holds the P 64-bit words (one per slot) of the s-th of those picks.
-template <int P>
+// yet: word [p][s] (one per slot p) of the s-th of those picks, in the wave's own part of LDS.
+// A hit mask is wave-uniform, so it is stored by all lanes at one address (one instruction, no
+// lane select); when the picks are written out lane s reads the words of pick s.  The LDS
+// executes a wave's operations in issue order, so the wave needs no barrier between the two.
+template <int P, bool BQ>
 struct RowWords {
-    uint32_t lo[P], hi[P];
-    __device__ __forceinline__ void clear()
+    uint64_t* row;
+    __device__ __forceinline__ void clear(const Where& wh)
     {
+        row = wh.rows;
+        if constexpr (BQ) {
 #pragma unroll
-        for (int p = 0; p < P; ++p) lo[p] = hi[p] = 0;
+            for (int p = 0; p < P; ++p) row[p * 64 + wh.lane] = 0;
+        }
     }
 };
 
@@ -325,7 +332,7 @@ struct RowWords {
 // 64-bit hit mask of every slot goes to lane `s` of `rw`.
 template <int P, bool BQ, int P0>
 __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float cy, float cz, float bq_r2,
-                                            int lane, int s, RowWords<P>& rw)
+                                            int s, RowWords<P, BQ>& rw)
 {
     constexpr int GRP = P < 8 ? P : 8;      // slots whose radius tests are examined together
     if constexpr (P0 < P) {
@@ -345,30 +352,26 @@ __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float c
             if (__builtin_amdgcn_ballot_w64(tmin < r2b) != 0) {
 #pragma unroll
                 for (int u = 0; u < GRP; ++u) {
-                    const uint64_t hit = __builtin_amdgcn_ballot_w64(tb[u] < r2b);
-                    if (lane == s) {
-                        rw.lo[P0 + u] = (uint32_t)hit;
-                        rw.hi[P0 + u] = (uint32_t)(hit >> 32);
-                    }
+                    rw.row[(P0 + u) * 64 + s] = __builtin_amdgcn_ballot_w64(tb[u] < r2b);
                 }
             }
         }
-        fold_groups<P, BQ, P0 + GRP>(pt, cx, cy, cz, bq_r2, lane, s, rw);
+        fold_groups<P, BQ, P0 + GRP>(pt, cx, cy, cz, bq_r2, s, rw);
     }
 }
 
 template <int P, bool BQ>
 __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, float cz,
-                                     const SamplerArgs& a, const Where& wh, int s, RowWords<P>& rw)
+                                     const SamplerArgs& a, const Where& wh, int s, RowWords<P, BQ>& rw)
 {
-    fold_groups<P, BQ, 0>(pt, cx, cy, cz, a.bq_r2, wh.lane, s, rw);
+    fold_groups<P, BQ, 0>(pt, cx, cy, cz, a.bq_r2, s, rw);
 }
 
 // Writes the words of `count` picks (sample positions base, base+1, ...; count <= 64) to the
 // cache: for every slot p the lanes store the words [block gw*P + p][base .. base+count), which
 // are contiguous.
 template <int P, bool BQ>
-__device__ __forceinline__ void flush_rows(const RowWords<P>& rw, const SamplerArgs& a, const Where& wh,
+__device__ __forceinline__ void flush_rows(const RowWords<P, BQ>& rw, const SamplerArgs& a, const Where& wh,
                                            int base, int count)
 {
     if (!BQ) return;
@@ -377,7 +380,7 @@ __device__ __forceinline__ void flush_rows(const RowWords<P>& rw, const SamplerA
         const int blk = wh.gw * P + p;              // slots wholly beyond N have no block
         if (blk < a.bq_blocks && wh.lane < count)
             a.bq_bits[((int64_t)wh.c * a.bq_blocks + blk) * a.bq_col_words + base + wh.lane] =
-                ((uint64_t)rw.hi[p] << 32) | rw.lo[p];
+                rw.row[p * 64 + wh.lane];
     }
 }
 
@@ -645,8 +648,8 @@ __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, c
                                              const SamplerArgs& a, int npend, int base)
 {
     if (npend <= 0 || wh.ctrl) return;
-    RowWords<P> rw;
-    rw.clear();
+    RowWords<P, BQ> rw;
+    rw.clear(wh);
     if constexpr (PERM) {
         uint64_t near = near_mask<P, BQ>(pt, sh.pend, npend, wh.lane);
         while (near != 0) {
@@ -676,8 +679,8 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
                                              const SamplerArgs& a, int base, uint32_t tag, int total)
 {
     int s = 0;
-    RowWords<P> rw;
-    rw.clear();
+    RowWords<P, BQ> rw;
+    rw.clear(wh);
     uint64_t near = ~0ull, near_hi = ~0ull;         // one bit per candidate (near_hi: candidates 64..127)
     if constexpr (PERM) {
         near = near_mask<P, BQ>(pt, sh.cand, total < 64 ? total : 64, wh.lane);
@@ -698,7 +701,7 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
         slot = lds_observe(&sh.live[s + 1]);
         if (WIDE && BQ && s == 64) {                // lane s of `rw` holds a pick's words: 64 at a time
             flush_rows<P, BQ>(rw, a, wh, base, 64);
-            rw.clear();
+            rw.clear(wh);
         }
         const uint64_t nbit = (WIDE && cl >= 64u) ? (near_hi >> (cl - 64u)) : (near >> cl);
         if (!PERM || (nbit & 1ull) != 0) {
@@ -1664,11 +1667,13 @@ template <int T, int P, bool BQ, bool PERM, int MODE>
 __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a)
 {
     __shared__ Shared<T> sh;
+    __shared__ uint64_t bq_rows[BQ ? (T / 64) * P * 64 : 1];     // radius-test words not written out yet
     Where wh;
     wh.tid = (int)threadIdx.x;
     wh.lane = wh.tid & 63;
     wh.w = uni(wh.tid >> 6);
     wh.ctrl = wh.w == T / 64;
+    wh.rows = bq_rows + (BQ && !wh.ctrl ? wh.w * P * 64 : 0);    // the control wave folds nothing
     wh.G = a.G;
     wh.grp = (int)blockIdx.x / a.G;
     wh.g = (int)blockIdx.x % a.G;
