@@ -174,3 +174,30 @@ def test_phase_times_are_reported(fp):
     for i in fp.parse_info(finfo):
         t = list(i.phase_ticks)
         assert t[0] > 0 and t[1] == 0 and t[2] == 0 and t[3] == 0
+
+
+def test_recording_with_sixteen_points_per_thread(fp):
+    """The largest kernel shape with radius recording (its radius-test rows take 64 KB of LDS):
+    the cache reader must give the brute-force bytes, the samples the oracle's."""
+    N, n, G = 150000, 96, 20                      # 7500 points per workgroup -> 16 per thread
+    say("recording, P=16", N)
+    cloud = np.random.Generator(np.random.PCG64(5)).uniform(0, 1, (N, 3)).astype(np.float32)
+    x = dev(cloud[None])
+    fp.set_wg_per_cloud(G)
+    try:
+        assert fp.plan(1, N) == (G, 512, 16)
+        cache = fp.new_bq_cache(x, n)
+        idx = fp.fps_exact(x, n, bq_cache=cache, bq_radius=0.05)
+        cbq = fp.ball_query(x, idx, 0.05, 16, bq_cache=cache)
+        cache2 = fp.new_bq_cache(x, n)
+        midx = fp.mdps_sample(x, n, fp.MdpsParams(exponent=0.7, bias=1.05), bq_cache=cache2, bq_radius=0.05)
+        mbq = fp.ball_query(x, midx, 0.05, 16, bq_cache=cache2)
+        torch.cuda.synchronize()
+    finally:
+        fp.set_wg_per_cloud(0)
+    assert np.array_equal(idx.cpu().numpy()[0], ref.fps_exact(cloud, n)[0])
+    assert np.array_equal(midx.cpu().numpy()[0], ref.mdps_sample(cloud, n, ref.MdpsParams(exponent=0.7, bias=1.05))[0])
+    for got, centres in ((cbq, idx), (mbq, midx)):
+        want = fp.ball_query(x, centres, 0.05, 16)
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
