@@ -573,6 +573,12 @@ def run(args, torch, fp, inputs, calibration, extra):
     roof["kernel"] = dom + " (stage 0)"
     roof["ms_per_launch"] = s0["kernel_ms"][dom]
     roof["traffic"] = TRAFFIC_BYTES.get(name, {}).get(dom)
+    if roof.get("bound") == "alu":
+        # the published peak needs packed binary32 instructions, which this path may not use (every
+        # operation rounds on its own); the rate the device reaches without them, measured here
+        probe = fp.probe_fp32_rate(ctx["xyz"].device) / 1e12
+        roof["plain_fp32_rate_measured"] = probe
+        roof["frac_of_plain_fp32_rate"] = roof["achieved"] / probe
     if dom in ("fps_exact", "mdps_sample+record"):
         # the sampler runs a cloud on plan.G workgroups, one per compute unit: what share of the
         # device the launch can occupy at all, and the fraction of those units' peak

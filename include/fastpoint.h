@@ -288,6 +288,15 @@ fp_status fp_gather_xyz(const float* xyz, int32_t B, int32_t N,
 fp_status fp_coverage(const float* xyz, int32_t B, int32_t N,
                       const float* sample_xyz, int32_t n, float* out_cov2, void* stream);
 
+/* Measurement aid: the plain binary32 rate this build can reach.  Every thread of
+ * `blocks` workgroups of 256 runs `iterations` times over eight independent chains of one
+ * multiplication and one addition, each rounded on its own like the distance update (the library
+ * is compiled without contraction and without packed binary32 instructions), and stores its sum in
+ * out[blocks * 256] (float32).  The operations performed are blocks * 256 * iterations * 16; the
+ * caller times the call.  Price a kernel's operations against this rate to see how much of the
+ * reachable arithmetic throughput it uses. */
+fp_status fp_probe_fp32_rate(int32_t blocks, int32_t iterations, float* out, void* stream);
+
 /* How the sampler splits one cloud: workgroups per cloud, threads per workgroup that
  * hold points (a workgroup has one more wave, which holds none), points per thread.
  * Returns FP_ERR_SHAPE if the cloud does not fit. */

@@ -19,7 +19,7 @@ MAX_SEG = 16
 
 EXPORTS = ["fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_mdps_sample_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
            "fp_ball_query", "fp_ball_query_grid_workspace_bytes", "fp_ball_query_grid", "fp_knn_workspace_bytes", "fp_knn", "fp_knn_grid_workspace_bytes", "fp_knn_grid", "fp_excl_workspace_bytes", "fp_excl_count",
-           "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_plan", "fp_set_wg_per_cloud",
+           "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_probe_fp32_rate", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
 
 
@@ -139,6 +139,8 @@ def load() -> ctypes.CDLL:
     lib.fp_gather_xyz.restype = i32
     lib.fp_coverage.argtypes = [vp, i32, i32, vp, i32, vp, vp]
     lib.fp_coverage.restype = i32
+    lib.fp_probe_fp32_rate.argtypes = [i32, i32, vp, vp]
+    lib.fp_probe_fp32_rate.restype = i32
     lib.fp_plan.argtypes = [i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.fp_plan.restype = i32
     lib.fp_set_wg_per_cloud.argtypes = [i32]
@@ -182,6 +184,23 @@ def plan(B: int, N: int) -> Tuple[int, int, int]:
 
 def set_wg_per_cloud(g: int) -> None:
     load().fp_set_wg_per_cloud(int(g))
+
+
+def probe_fp32_rate(device: torch.device, blocks: int = 8192, iterations: int = 4096, reps: int = 3) -> float:
+    """Plain binary32 operations per second (multiplications and additions rounded one by one, as
+    the distance update does them) that the device reaches with this build."""
+    out = torch.empty(blocks * 256, dtype=torch.float32, device=device)
+    best = None
+    for _ in range(reps + 1):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        _check(load().fp_probe_fp32_rate(blocks, iterations, out.data_ptr(), _stream()), "fp_probe_fp32_rate")
+        b.record()
+        torch.cuda.synchronize()
+        t = a.elapsed_time(b)
+        best = t if best is None else min(best, t)
+    return blocks * 256.0 * iterations * 16.0 / (best * 1e-3)
 
 
 def set_cooperative_launch(on: bool) -> None:

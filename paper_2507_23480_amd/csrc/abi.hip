@@ -457,6 +457,15 @@ fp_status fp_coverage(const float* xyz, int32_t B, int32_t N, const float* sampl
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }
 
+fp_status fp_probe_fp32_rate(int32_t blocks, int32_t iterations, float* out, void* stream)
+{
+    if (!out) return FP_ERR_NULL;
+    if (blocks < 1 || blocks > (1 << 20) || iterations < 1) return FP_ERR_SHAPE;
+    return launch_probe_fp32(blocks, iterations, out, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+               ? FP_OK
+               : FP_ERR_DEVICE;
+}
+
 fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
                   int32_t* points_per_thread)
 {

@@ -294,7 +294,34 @@ __global__ __launch_bounds__(256) void coverage_kernel(const float* __restrict__
     if (threadIdx.x == 0) atomicMax(reinterpret_cast<unsigned int*>(out) + b, red[0]);
 }
 
+// eight independent chains of a multiplication and an addition per thread (see fp_probe_fp32_rate)
+__global__ __launch_bounds__(256) void probe_fp32_kernel(float* __restrict__ out, int iterations, float m, float c)
+{
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = (float)(threadIdx.x + k) * 1.0e-3f;
+    for (int i = 0; i < iterations; ++i) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float t = v[k] * m;
+            v[k] = t + c;
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s = s + v[k];
+    out[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace
+
+hipError_t launch_probe_fp32(int blocks, int iterations, float* out, hipStream_t stream)
+{
+    // the factors are run-time values, so that the chains cannot be folded
+    hipLaunchKernelGGL(probe_fp32_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, out, iterations,
+                       0.9999f, 1.0e-4f);
+    return hipGetLastError();
+}
 
 hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* center_idx, int M,
                              float r2, int k, int32_t* out_idx, int32_t* out_cnt,

@@ -68,6 +68,7 @@ struct Plan {
 const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, int mode);
 hipError_t launch_zero_words(uint64_t* p, int64_t nwords, hipStream_t stream);
 
+hipError_t launch_probe_fp32(int blocks, int iterations, float* out, hipStream_t stream);
 hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* center_idx, int M,
                              float r2, int k, int32_t* out_idx, int32_t* out_cnt,
                              const void* bq_cache, hipStream_t stream);

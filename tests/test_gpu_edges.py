@@ -201,3 +201,14 @@ def test_recording_with_sixteen_points_per_thread(fp):
         want = fp.ball_query(x, centres, 0.05, 16)
         torch.cuda.synchronize()
         assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
+
+
+def test_plain_fp32_rate_probe(fp):
+    """The measurement aid runs and lands near 256 compute units x 64 lanes x the clock."""
+    rate = fp.probe_fp32_rate(torch.device("cuda:0"), blocks=4096, iterations=2048)
+    assert 5e12 < rate < 80e12
+    lib = fp.load()
+    out = torch.empty(256, dtype=torch.float32, device="cuda")
+    assert lib.fp_probe_fp32_rate(1, 0, out.data_ptr(), None) == -2
+    assert lib.fp_probe_fp32_rate(0, 10, out.data_ptr(), None) == -2
+    assert lib.fp_probe_fp32_rate(1, 10, None, None) == -1
