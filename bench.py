@@ -344,6 +344,9 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         out["stages"].append({
             "N": N, "n": n, "radius": sg["radius"], "k": k, "plan_G_T_P": list(fp.plan(B, N)),
             "kernel_ms": ms,
+            # microseconds per sample of a launch (all clouds of the batch run side by side)
+            "fps_exact_us_per_sample": ms["fps_exact"] * 1e3 / max(n - 1, 1) if "fps_exact" in ms else None,
+            "mdps_sample_us_per_sample": ms["mdps_sample"] * 1e3 / max(n - 1, 1) if "mdps_sample" in ms else None,
             "mdps_coverage_ratio_max": float(ratio.max()), "mdps_coverage_ratio_mean": float(ratio.mean()),
             # the paper's quality figure (Table 1): mean distance from a sample to the nearest other
             # sample, MDPS relative to exact FPS
