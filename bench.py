@@ -567,6 +567,9 @@ def run(args, torch, fp, inputs, calibration, extra):
     seq_ms, kernel_ms = measure_eager(torch, fp, ctx, args.steps, args.warmup)
     wl = ctx["wl"]
     detail = quality_and_rooflines(torch, fp, ctx, kernel_ms)
+    props = torch.cuda.get_device_properties(ctx["xyz"].device)
+    detail["device"] = {"name": props.name, "compute_units": int(props.multi_processor_count),
+                        "memory_gib": round(props.total_memory / 2.0 ** 30, 1)}
     s0 = detail["stages"][0]
     # dominant kernel of the step: the one with the largest share of the time
     in_step = [kname for kname in s0["roofline"]
