@@ -10,9 +10,9 @@ every stage of its hierarchy:
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
 Workloads whose clouds take one workgroup each leave most of the device idle, so their step
-runs the two paths of a stage on two streams and is replayed as one captured HIP graph (no
-host time between the launches); the replay's outputs are compared with the eager ones.  The
-per-kernel times and rooflines always come from calls that run alone on one stream.
+runs the calls that do not wait for each other on four streams and is replayed as one captured
+HIP graph (no host time between the launches); the replay's outputs are compared with the eager
+ones.  The per-kernel times and rooflines always come from calls that run alone on one stream.
 
 Outside the timed step the k nearest samples of every point (the k-NN of the up-sampling
 step, redundancy-free form of Section 4.2) are timed per stage and reported under "detail".
@@ -40,7 +40,7 @@ OPS_PER_POINT_ITERATION = 10      # 3 sub, 3 mul, 2 add, 1 min, 1 compare (FPS m
 OPS_PER_PAIR_TEST = 9             # 3 sub, 3 mul, 2 add, 1 compare (ball query, k-NN)
 KNN_K = 3                         # neighbours of the up-sampling step (Section 3.1)
 EAGER = "one stream, eager launches"
-GRAPH = "two streams, step replayed as one HIP graph"
+GRAPH = "four streams, step replayed as one HIP graph"
 
 # HBM traffic per launch of the kernels that can dominate the step, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs (profiles/bench_C2_hbm_traffic.md); bytes, keyed by workload and
@@ -108,7 +108,8 @@ def make_context(torch, fp, inputs, calibration, name):
                        "ws": [fp.new_workspace(xyz.device, B, N), fp.new_workspace(xyz.device, B, N)]})
         N = st.n
     torch.cuda.synchronize()
-    return {"wl": wl, "name": name, "stages": stages, "xyz": xyz, "side": torch.cuda.Stream()}
+    return {"wl": wl, "name": name, "stages": stages, "xyz": xyz, "side": torch.cuda.Stream(),
+            "aux": torch.cuda.Stream(), "bqs": torch.cuda.Stream()}
 
 
 def run_step(fp, ctx, timer, keep=None):
@@ -130,37 +131,33 @@ def run_step(fp, ctx, timer, keep=None):
 
 
 def run_step_streams(torch, fp, ctx, keep=None):
-    """One step on two streams where the work of a stage fits on the device side by side (one
-    workgroup per cloud).  The samplers are what takes the time: mdps_sample (with recording) of
-    every stage runs on the second stream, one after the other, each as soon as its input (the
-    gather of the stage before) is there; exact FPS, the brute-force ball query, the gather and
-    the cache reader of the FastPoint path (which follows the mdps_sample whose cache it reads)
-    run on the current stream; only the last stage's cache reader stays behind its sampler."""
+    """One step on four streams, for clouds that take one workgroup each (the work of all stages
+    fits on the device side by side).  What has to happen in order is exact FPS of stage s ->
+    gather -> the samplers of stage s+1: that chain runs on the current stream.  mdps_sample
+    (with recording) and the cache reader that follows it run on a stream per stage, two in
+    turn, as soon as the stage's input is there; the brute-force ball queries, which nothing
+    waits for, on a stream of their own."""
     main = torch.cuda.current_stream()
-    side = ctx["side"]
+    lanes = [ctx["side"], ctx["aux"]]
+    bqs = ctx["bqs"]
     x = ctx["xyz"]
     for s, sg in enumerate(ctx["stages"]):
         n, r, k = sg["n"], sg["radius"], sg["k"]
-        two = sg["G"] == 1
-        if two and s == 0:
-            side.wait_stream(main)                  # the first stage's input is ready
-        idx = fp.fps_exact(x, n, ws=sg["ws"][0])
-        bq = fp.ball_query(x, idx, r, k)
-        with torch.cuda.stream(side if two else main):
+        lane = lanes[s % 2]
+        lane.wait_stream(main)                      # the stage's input is ready
+        with torch.cuda.stream(lane):
             midx = fp.mdps_sample(x, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r, ws=sg["ws"][1])
-        last = s + 1 == len(ctx["stages"])
-        x_next = None if last else fp.gather_xyz(x, idx)
-        if two and not last:
-            # mdps_sample is the longer of the two samplers: its ball query goes behind the exact
-            # path's work, and the next mdps_sample starts as soon as the gather is done
-            main.wait_stream(side)
-            side.wait_stream(main)
-        with torch.cuda.stream(side if two and last else main):
             mbq = fp.ball_query(x, midx, r, k, bq_cache=sg["cache"])
+        idx = fp.fps_exact(x, n, ws=sg["ws"][0])
+        x_next = None if s + 1 == len(ctx["stages"]) else fp.gather_xyz(x, idx)
+        bqs.wait_stream(main)
+        with torch.cuda.stream(bqs):
+            bq = fp.ball_query(x, idx, r, k)
         if keep is not None:
             keep.append((x, idx, bq, midx, mbq))
         x = x_next
-    main.wait_stream(side)
+    for other in (lanes[0], lanes[1], bqs):
+        main.wait_stream(other)
 
 
 def measure_eager(torch, fp, ctx, steps, warmup):
@@ -185,7 +182,7 @@ def one_workgroup_per_cloud(ctx):
 
 
 def measure_graph(torch, fp, ctx, steps, warmup):
-    """ms per step for small clouds: two streams, the step captured once in a graph and
+    """ms per step for small clouds: four streams, the step captured once in a graph and
     replayed; the replay's outputs are checked against the eager ones.  Called after all eager
     measurements of the process: once a graph with a second stream has run, eager launches on
     the streams that existed by then take tens of microseconds longer each."""

@@ -1,7 +1,8 @@
 """The step of the object-classification workload (one workgroup per cloud) captured as a HIP
-graph with its two sampling paths on two streams, as bench.py replays it: every replay must give
-the eager result, with eager work of the library and synchronisations between the replays, and
-the eager result must be the oracle's.
+graph on four streams (the chain of exact samplers, a stream per stage in turn for mdps_sample
+and its cache reader, one for the brute-force ball queries), as bench.py replays it: every replay
+must give the eager result, with eager work of the library and synchronisations between the
+replays, and the eager result must be the oracle's.
 """
 import numpy as np
 import pytest
@@ -18,7 +19,7 @@ def rparams(prm):
                           fit_window=prm.fit_window, m_min=prm.m_min, level_scale=prm.level_scale)
 
 
-def test_graph_replay_of_two_stream_step_equals_eager_and_oracle():
+def test_graph_replay_of_four_stream_step_equals_eager_and_oracle():
     from paper_2507_23480_amd import binding as fp, calibration
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     fp.load()
@@ -28,7 +29,8 @@ def test_graph_replay_of_two_stream_step_equals_eager_and_oracle():
     batch = inputs.make_batch(name)
     xyz = torch.from_numpy(batch).cuda()
     B = wl.B
-    side = torch.cuda.Stream()
+    lanes = [torch.cuda.Stream(), torch.cuda.Stream()]
+    bqs = torch.cuda.Stream()
     N = wl.N
     stages = []
     for s, st in enumerate(wl.stages):
@@ -39,26 +41,28 @@ def test_graph_replay_of_two_stream_step_equals_eager_and_oracle():
                        "ws": [fp.new_workspace(xyz.device, B, N), fp.new_workspace(xyz.device, B, N)]})
         N = st.n
 
+    inputs_alive = []
+
     def step(keep):
         main = torch.cuda.current_stream()
         x = xyz
-        side.wait_stream(main)
         for s, sg in enumerate(stages):
-            last = s + 1 == len(stages)
-            idx = fp.fps_exact(x, sg["n"], ws=sg["ws"][0])
-            bq = fp.ball_query(x, idx, sg["r"], sg["k"])
-            with torch.cuda.stream(side):
+            lane = lanes[s % 2]
+            lane.wait_stream(main)
+            with torch.cuda.stream(lane):
                 midx = fp.mdps_sample(x, sg["n"], sg["prm"], bq_cache=sg["cache"], bq_radius=sg["r"],
                                       ws=sg["ws"][1])
-            x_next = None if last else fp.gather_xyz(x, idx)
-            if not last:
-                main.wait_stream(side)
-                side.wait_stream(main)
-            with torch.cuda.stream(side if last else main):
                 mbq = fp.ball_query(x, midx, sg["r"], sg["k"], bq_cache=sg["cache"])
+            idx = fp.fps_exact(x, sg["n"], ws=sg["ws"][0])
+            x_next = None if s + 1 == len(stages) else fp.gather_xyz(x, idx)
+            bqs.wait_stream(main)
+            with torch.cuda.stream(bqs):
+                bq = fp.ball_query(x, idx, sg["r"], sg["k"])
             keep.append((idx, bq[0], bq[1], midx, mbq[0], mbq[1]))
+            inputs_alive.append(x)               # a stage's input outlives the calls that read it
             x = x_next
-        main.wait_stream(side)
+        for other in (lanes[0], lanes[1], bqs):
+            main.wait_stream(other)
 
     eager = []
     step(eager)
