@@ -17,8 +17,10 @@
 //   excl_fill     one wave per point: the hits at the largest radius are collected in LDS, sorted
 //                 by index (bitonic network, one wave, no barriers), then walked in order; each
 //                 level keeps the members below its own radius (ballot compaction keeps the
-//                 order).  A point with more hits than the LDS buffer holds scans all N points
-//                 in index order instead, which needs no sort.
+//                 order).  A point with more hits than the LDS buffer holds is left to
+//   excl_fill_heavy: ascending index is the order of a bitmap -- the wave marks the hits of the
+//                 27 cells in a bitmap over a slab of 32768 or 65536 indices (LDS), reads it back 64
+//                 words a pass and walks the indices of the set bits; no sort.
 //   bq_lists      first k members of a row, padded with the first
 //
 // Squared distances are evaluated as ((dx*dx)+(dy*dy))+(dz*dz), every operation rounded on its
@@ -35,6 +37,8 @@ namespace {
 
 constexpr int kWaves = 4;              // waves (= points) per workgroup of the list kernels
 constexpr int kSortCap = 2048;         // hits at the largest radius that one wave sorts in LDS
+constexpr int kHeavyWaves = 4;         // waves (= points) per workgroup of the kernel for longer rows
+constexpr int kSlabWordsMax = 2048;    // 32-bit words of one wave's index bitmap: a slab of up to 65536 indices
 constexpr int kScanBlock = 2048;       // elements per workgroup of the offset scan (256 threads x 8)
 constexpr float kCellSlack = 1.001f;   // cell width = largest radius x this (absorbs the rounding of
                                        // the cell coordinate, at most 1024 cells per axis)
@@ -371,6 +375,40 @@ __device__ __forceinline__ void for_neighbours(const ExclGrid& g, const int32_t*
     }
 }
 
+// The same walk run by run (a last pass per run that may be partly empty; no search for the run a
+// position falls into): cheaper per pass, for points with many passes.  The record of the next
+// pass is requested before the current one is used.
+template <typename F>
+__device__ __forceinline__ void for_neighbour_runs(const ExclGrid& g, const int32_t* __restrict__ st,
+                                                   const float4* __restrict__ sorted, int cx, int cy, int cz,
+                                                   int lane, F f)
+{
+    const int x0 = cx > 0 ? cx - 1 : 0;
+    const int x1 = cx < g.dim[0] - 1 ? cx + 1 : g.dim[0] - 1;
+    int mybegin = 0, mylen = 0;
+    if (lane < 9) {
+        const int z = cz + lane / 3 - 1, y = cy + lane % 3 - 1;
+        if (z >= 0 && z < g.dim[2] && y >= 0 && y < g.dim[1]) {
+            const int c0 = (z * g.dim[1] + y) * g.dim[0] + x0;
+            mybegin = st[c0];
+            mylen = st[c0 + (x1 - x0) + 1] - mybegin;
+        }
+    }
+    for (int r = 0; r < 9; ++r) {
+        const int begin = (int)rdlane((uint32_t)mybegin, r);
+        const int len = (int)rdlane((uint32_t)mylen, r);
+        if (len <= 0) continue;
+        const float4* __restrict__ run = sorted + begin;
+        float4 cur = run[lane < len ? lane : 0];
+        for (int t0 = 0; t0 < len; t0 += 64) {
+            const int tn = t0 + 64 + lane;
+            const float4 nxt = run[tn < len ? tn : 0];
+            f(cur, t0 + lane < len);
+            cur = nxt;
+        }
+    }
+}
+
 // Pass 1: lane l of the point's wave ends up with the size of the level-l list.
 __global__ __launch_bounds__(kWaves * 64) void excl_count_kernel(
     const float* __restrict__ xyz, int B, int N, const float* __restrict__ thr2, int L,
@@ -389,17 +427,16 @@ __global__ __launch_bounds__(kWaves * 64) void excl_count_kernel(
     const float mythr = lane < L ? thr2[(int64_t)b * L + lane] : 0.0f;
     int mycnt = 0;
     const float rmax2 = g.rmax2;
-    for_neighbours(g, cell_start + (int64_t)b * (maxcells + 1), sorted + (int64_t)b * N, cx, cy, cz, lane,
-                   [&](const float4& r, bool valid) {
-                       const float d = dist2(px, py, pz, r.x, r.y, r.z);
-                       if (__builtin_amdgcn_ballot_w64(valid && d < rmax2) == 0) return true;
-                       for (int l = 0; l < L; ++l) {
-                           const float t = rdlane_f(mythr, l);
-                           const int pc = __builtin_popcountll(__builtin_amdgcn_ballot_w64(valid && d < t));
-                           mycnt += lane == l ? pc : 0;
-                       }
-                       return true;
-                   });
+    for_neighbour_runs(g, cell_start + (int64_t)b * (maxcells + 1), sorted + (int64_t)b * N, cx, cy, cz, lane,
+                       [&](const float4& r, bool valid) {
+                           const float d = dist2(px, py, pz, r.x, r.y, r.z);
+                           if (__builtin_amdgcn_ballot_w64(valid && d < rmax2) == 0) return;
+                           for (int l = 0; l < L; ++l) {
+                               const float t = rdlane_f(mythr, l);
+                               const int pc = __builtin_popcountll(__builtin_amdgcn_ballot_w64(valid && d < t));
+                               mycnt += lane == l ? pc : 0;
+                           }
+                       });
     if (lane < L) offsets[1 + ((int64_t)lane * B + b) * N + i] = mycnt;
 }
 
@@ -476,6 +513,17 @@ __global__ __launch_bounds__(256) void scan_add_kernel(int64_t* __restrict__ v, 
 __global__ void zero_first_kernel(int64_t* p) { *p = 0; }
 
 // ------------------------------------------------------------------------- pass 2
+// Which of the two fill kernels builds a row with `hits` members at the largest radius.  The
+// bitmap kernel takes the 27 cells once per slab of indices but orders nothing, the other takes
+// them once and sorts.  Measured on 120000 points in four slabs: the bitmap kernel is the cheaper
+// one from about 128 hits per slab of the cloud; the sort buffer's capacity is the limit in any case.
+__device__ __forceinline__ bool is_long_row(int64_t hits, int N, int slab_words)
+{
+    const int64_t slabs = ((int64_t)N + slab_words * 32 - 1) / (slab_words * 32);
+    const int64_t limit = 128 * slabs < kSortCap ? 128 * slabs : kSortCap;
+    return hits > limit;
+}
+
 // Level cursors: lane l holds how many members of the level-l row are written already.
 struct Emit {
     int64_t mybase;      // lane l: start of the level-l row
@@ -558,7 +606,7 @@ __global__ __launch_bounds__(kWaves * 64) void excl_fill_kernel(
     const float* __restrict__ xyz, int B, int N, const float* __restrict__ thr2, int L,
     const int64_t* __restrict__ offsets, int32_t* __restrict__ entries, int64_t capacity,
     const ExclGrid* __restrict__ gp, const int32_t* __restrict__ cell_start, const float4* __restrict__ sorted,
-    int maxcells)
+    int maxcells, int slab_words)
 {
     __shared__ uint32_t sortbuf[kWaves][kSortCap];
     const int b = (int)blockIdx.y;
@@ -579,7 +627,7 @@ __global__ __launch_bounds__(kWaves * 64) void excl_fill_kernel(
     const int64_t rmaxrow = ((int64_t)g.lmax * B + b) * N + i;
     const int64_t hits64 = offsets[rmaxrow + 1] - offsets[rmaxrow];
     if (hits64 <= 0) return;                 // rows of smaller radii are empty as well
-    if (hits64 <= kSortCap) {
+    if (!is_long_row(hits64, N, slab_words)) {
         const int H = (int)hits64;
         uint32_t* buf = sortbuf[w];
         int cx, cy, cz;
@@ -603,16 +651,109 @@ __global__ __launch_bounds__(kWaves * 64) void excl_fill_kernel(
                                   cloud[(int64_t)j * 3 + 2]);
             em(j, d, valid, lane);
         }
-    } else {
-        const float rmax2 = g.rmax2;
-        for (int j0 = 0; j0 < N; j0 += 64) {
-            const int j = j0 + lane;
-            const bool valid = j < N;
-            const int jj = valid ? j : i;
-            const float d = dist2(px, py, pz, cloud[(int64_t)jj * 3 + 0], cloud[(int64_t)jj * 3 + 1],
-                                  cloud[(int64_t)jj * 3 + 2]);
-            if (__builtin_amdgcn_ballot_w64(valid && d < rmax2) == 0) continue;
-            em(j, d, valid, lane);
+    }
+    // longer rows: excl_fill_heavy_kernel
+}
+
+// one wave: its LDS operations execute in program order; keeps the compiler from moving reads
+// above the writes they depend on
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Pass 2 for the rows that excl_fill_kernel leaves out (is_long_row).  One wave per point.  The hits of the 27 cells are marked in a bitmap over a
+// slab of slab_words * 32 consecutive indices; the bitmap is then read 64 words a pass (one per
+// lane), and the set bits of a pass are handed out 64 at a time in ascending order: lane t finds
+// the word that holds the t-th of them through the prefix sums of the words' bit counts, and
+// the bit inside the word.  The words are cleared as they are read.  A cloud with more points
+// than a slab takes the cells once per slab.
+__global__ __launch_bounds__(kHeavyWaves * 64) void excl_fill_heavy_kernel(
+    const float* __restrict__ xyz, int B, int N, const float* __restrict__ thr2, int L,
+    const int64_t* __restrict__ offsets, int32_t* __restrict__ entries, int64_t capacity,
+    const ExclGrid* __restrict__ gp, const int32_t* __restrict__ cell_start, const float4* __restrict__ sorted,
+    int maxcells, int slab_words)
+{
+    extern __shared__ uint32_t bitmap[];            // kHeavyWaves x slab_words
+    const int b = (int)blockIdx.y;
+    const int lane = (int)threadIdx.x & 63;
+    const int w = uni((int)threadIdx.x >> 6);
+    const int i = uni((int)blockIdx.x * kHeavyWaves + w);
+    if (i >= N) return;
+    const ExclGrid g = gp[b];
+    const int64_t rmaxrow = ((int64_t)g.lmax * B + b) * N + i;
+    if (!is_long_row(offsets[rmaxrow + 1] - offsets[rmaxrow], N, slab_words)) return;
+    const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
+    const float px = cloud[(int64_t)i * 3 + 0], py = cloud[(int64_t)i * 3 + 1], pz = cloud[(int64_t)i * 3 + 2];
+    Emit em;
+    em.L = L;
+    em.entries = entries;
+    em.capacity = capacity;
+    em.mythr = lane < L ? thr2[(int64_t)b * L + lane] : 0.0f;
+    em.mybase = lane < L ? offsets[((int64_t)lane * B + b) * N + i] : 0;
+    em.mycur = 0;
+    uint32_t* bm = bitmap + w * slab_words;
+    for (int t = lane; t < slab_words; t += 64) bm[t] = 0u;
+    wave_lds_sync();
+    int cx, cy, cz;
+    cell_of(g, px, py, pz, cx, cy, cz);
+    const float rmax2 = g.rmax2;
+    const int slab = slab_words * 32;
+    for (int base = 0; base < N; base += slab) {
+        const int span = N - base < slab ? N - base : slab;
+        for_neighbour_runs(g, cell_start + (int64_t)b * (maxcells + 1), sorted + (int64_t)b * N, cx, cy, cz, lane,
+                           [&](const float4& r, bool valid) {
+                               const uint32_t rel = (uint32_t)__float_as_int(r.w) - (uint32_t)base;
+                               const bool hit = valid && rel < (uint32_t)span &&
+                                                dist2(px, py, pz, r.x, r.y, r.z) < rmax2;
+                               if (hit) atomicOr(&bm[rel >> 5], 1u << (rel & 31u));
+                           });
+        wave_lds_sync();
+        const int words = (span + 31) >> 5;
+        for (int w0 = 0; w0 < words; w0 += 64) {
+            const int wi = w0 + lane;
+            uint32_t word = wi < words ? bm[wi] : 0u;
+            if (__builtin_amdgcn_ballot_w64(word != 0u) == 0) continue;
+            if (word != 0u) bm[wi] = 0u;
+            const int cnt = __builtin_popcount(word);
+            int incl = cnt;                                  // inclusive prefix sum over the lanes
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int o = __shfl_up(incl, (unsigned)d, 64);
+                incl += lane >= d ? o : 0;
+            }
+            const int total = (int)rdlane((uint32_t)incl, 63);          // <= 64 * 32
+            const int excl = incl - cnt;                                // set bits in the lanes below
+            for (int t0 = 0; t0 < total; t0 += 64) {
+                // lane t takes the (t0 + t)-th set bit of the pass: the word of the last lane whose
+                // bits start at or before it (the prefix is non-decreasing over the lanes) ...
+                const int want = t0 + lane;
+                const bool valid = want < total;
+                int src = 0;
+#pragma unroll
+                for (int step = 32; step > 0; step >>= 1) {
+                    const int below = __shfl(excl, src + step, 64);     // src + step <= 63
+                    src += below <= want ? step : 0;
+                }
+                uint32_t sw = (uint32_t)__shfl((int)word, src, 64);
+                int nth = want - __shfl(excl, src, 64);
+                // ... and in it the nth set bit: descend by halves
+                int bit = 0;
+#pragma unroll
+                for (int width = 16; width > 0; width >>= 1) {
+                    const int c = __builtin_popcount(sw & ((1u << width) - 1u));
+                    const bool up = nth >= c;
+                    nth -= up ? c : 0;
+                    bit += up ? width : 0;
+                    sw = up ? sw >> width : sw;
+                }
+                const int j = valid ? (int)((uint32_t)base + ((uint32_t)(w0 + src) << 5) + (uint32_t)bit) : i;
+                const float d = dist2(px, py, pz, cloud[(int64_t)j * 3 + 0], cloud[(int64_t)j * 3 + 1],
+                                      cloud[(int64_t)j * 3 + 2]);
+                em(j, d, valid, lane);
+            }
         }
     }
 }
@@ -905,8 +1046,17 @@ hipError_t launch_excl_fill(const float* xyz, int B, int N, const float* thr2, i
     const int32_t* st = reinterpret_cast<const int32_t*>(base + lay.start_off);
     const float4* sorted = reinterpret_cast<const float4*>(base + lay.sorted_off);
     const dim3 wgrid((unsigned)((N + kWaves - 1) / kWaves), (unsigned)B);
+    // index slab of the bitmap kernel: a smaller bitmap lets more waves run on a compute unit, a
+    // larger one takes the cells fewer times (measured on 120000 points: 32768 indices, four
+    // walks, ahead of 65536 and two)
+    const int slab_words = N <= 4 * 32768 ? kSlabWordsMax / 2 : kSlabWordsMax;
     hipLaunchKernelGGL(excl_fill_kernel, wgrid, dim3(kWaves * 64), 0, stream, xyz, B, N, thr2, L, offsets, entries,
-                       capacity, gp, st, sorted, lay.maxcells);
+                       capacity, gp, st, sorted, lay.maxcells, slab_words);
+    // the rows that kernel leaves out (its waves return at once for all others)
+    const dim3 hgrid((unsigned)((N + kHeavyWaves - 1) / kHeavyWaves), (unsigned)B);
+    hipLaunchKernelGGL(excl_fill_heavy_kernel, hgrid, dim3(kHeavyWaves * 64),
+                       (size_t)kHeavyWaves * slab_words * sizeof(uint32_t), stream, xyz, B, N, thr2, L, offsets,
+                       entries, capacity, gp, st, sorted, lay.maxcells, slab_words);
     return hipGetLastError();
 }
 

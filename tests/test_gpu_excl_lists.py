@@ -108,6 +108,43 @@ def test_rows_around_the_sort_capacity(fp):
     assert sizes.max() > 2048 and sizes.min() >= 1
 
 
+@pytest.mark.parametrize("N,cluster", [(70000, 2600), (70000, 300), (530000, 2600), (530000, 1100)])
+def test_long_rows_over_several_index_slabs(fp, N, cluster):
+    """Longer rows are built from a bitmap over slabs of 32768 or 65536 indices, shorter ones by
+    sorting; where the border lies depends on the number of slabs (128 members per slab).  Clouds
+    of more points than one slab, with a cluster whose members' indices lie in all of them:
+    3 slabs with rows of 2600 (bitmap) and 300 (sorted), 9 slabs with rows of 2600 (bitmap) and
+    1100 (sorted, the largest network).
+    The all-pairs oracle would take minutes here; the rows of sampled points are checked against
+    the oracle's ball query (first k members by index, k above the longest row; radii are powers
+    of two, so radius * radius is the list's squared radius exactly), every row size against the
+    number of rows that hold the point (the relation is symmetric)."""
+    rng = np.random.Generator(np.random.PCG64(31 + cluster))
+    dense = rng.normal(0.0, 0.002, (cluster, 3))
+    sparse = rng.uniform(-8.0, 8.0, (N - cluster, 3))
+    cloud = np.concatenate([dense, sparse]).astype(np.float32)
+    cloud = cloud[rng.permutation(N)]
+    radii = [2.0 ** -6, 2.0 ** -8]
+    thr = np.array([[r * r for r in radii]], dtype=np.float32)
+    say("excl lists, long rows over several slabs, N=%d, cluster of %d" % (N, cluster))
+    off, ent = fp.excl_lists(dev(cloud[None]), dev(thr))
+    torch.cuda.synchronize()
+    off, ent = off.cpu().numpy(), ent.cpu().numpy()
+    sizes = np.diff(off).reshape(2, N)
+    assert sizes[0].max() > 0.95 * cluster and sizes.min() >= 1
+    in_cluster = np.flatnonzero(sizes[0] > 0.5 * cluster)
+    assert in_cluster.min() < 32768 and in_cluster.max() >= 65536 * ((N - 1) // 65536)
+    picks = np.concatenate([in_cluster[:40], in_cluster[-40:], rng.integers(0, N, 60)]).astype(np.int32)
+    for l, r in enumerate(radii):
+        widx, wcnt = ref.ball_query(cloud, picks, r, 4096)
+        for t, i in enumerate(picks):
+            row = ent[off[l * N + i]:off[l * N + i + 1]]
+            assert row.shape[0] == wcnt[t], "row size, level %d point %d" % (l, i)
+            assert np.array_equal(row, widx[t, :wcnt[t]]), "row members, level %d point %d" % (l, i)
+        # symmetry: i is in the row of j exactly when j is in the row of i
+        assert np.array_equal(np.bincount(ent[off[l * N]:off[(l + 1) * N]], minlength=N), sizes[l])
+
+
 def test_empty_levels(fp):
     thr = np.array([[0.0, -1.0, np.nan, 0.01]], dtype=np.float32)
     off, ent = check_lists(fp, inputs.uniform_cube(9, 500)[None], thr)
