@@ -522,6 +522,7 @@ def main():
               "no sharding across devices in this library)" % args.gpus, file=sys.stderr)
         return 2
     extra = {} if args.no_extra else other_workloads(args.workload)
+    clock_reader = None if args.no_extra else start_clock_reader()
     import torch
     from paper_2507_23480_amd import binding as fp, inputs, calibration
     if not torch.cuda.is_available():
@@ -530,7 +531,43 @@ def main():
     fp.load()
     if args.plain_launch:
         fp.set_cooperative_launch(False)
-    return run(args, torch, fp, inputs, calibration, extra)
+    return run(args, torch, fp, inputs, calibration, extra, clock_reader)
+
+
+def start_clock_reader():
+    """A child process that reads the device's clocks once it is told to.  Started before this
+    process touches the GPU (afterwards it starts no programs)."""
+    import subprocess
+    try:
+        return subprocess.Popen(["sh", "-c", "read go; exec rocm-smi --showclocks --json"],
+                                stdin=subprocess.PIPE, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL)
+    except Exception:
+        return None
+
+
+def clocks_under_load(torch, fp, reader):
+    """Engine and memory clock (MHz) read by rocm-smi while a plain fp32 kernel of about a
+    second keeps every compute unit busy; None where rocm-smi gives no answer."""
+    if reader is None:
+        return None
+    try:
+        out = torch.empty(8192 * 256, dtype=torch.float32, device="cuda")
+        if fp.load().fp_probe_fp32_rate(8192, 1500000, out.data_ptr(), None) != 0:
+            raise RuntimeError("probe")
+        time.sleep(0.3)
+        text = reader.communicate(b"go\n", timeout=30)[0].decode()
+        torch.cuda.synchronize()
+        card = next(iter(json.loads(text[text.index("{"):]).values()))
+        mhz = lambda key: int("".join(ch for ch in card[key] if ch.isdigit()))
+        return {"sclk_mhz": mhz("sclk clock speed:"), "mclk_mhz": mhz("mclk clock speed:"),
+                "source": "rocm-smi --showclocks during a one-second fp32 kernel on all compute units"}
+    except Exception:
+        try:
+            reader.kill()
+            torch.cuda.synchronize()
+        except Exception:
+            pass
+        return None
 
 
 def other_workloads(name):
@@ -558,7 +595,7 @@ def other_workloads(name):
     return extra
 
 
-def run(args, torch, fp, inputs, calibration, extra):
+def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
     name = args.workload
     ctx = make_context(torch, fp, inputs, calibration, name)
     seq_ms, kernel_ms = measure_eager(torch, fp, ctx, args.steps, args.warmup)
@@ -567,6 +604,9 @@ def run(args, torch, fp, inputs, calibration, extra):
     props = torch.cuda.get_device_properties(ctx["xyz"].device)
     detail["device"] = {"name": props.name, "compute_units": int(props.multi_processor_count),
                         "memory_gib": round(props.total_memory / 2.0 ** 30, 1)}
+    clocks = clocks_under_load(torch, fp, clock_reader)
+    if clocks:
+        detail["device"]["clocks_under_load"] = clocks
     s0 = detail["stages"][0]
     # dominant kernel of the step: the one with the largest share of the time
     in_step = [kname for kname in s0["roofline"]
