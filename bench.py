@@ -83,15 +83,17 @@ class Timer:
 
     def collect(self):
         for name, a, b in self.pending:
-            t, c = self.acc.get(name, (0.0, 0))
-            self.acc[name] = (t + a.elapsed_time(b), c + 1)
+            self.acc.setdefault(name, []).append(a.elapsed_time(b))
         self.pending = []
 
     def reset(self):
         self.pending, self.acc = [], {}
 
     def mean_ms(self):
-        return {k: t / c for k, (t, c) in self.acc.items()}
+        return {k: sum(v) / len(v) for k, v in self.acc.items()}
+
+    def min_median_ms(self):
+        return {k: (min(v), sorted(v)[len(v) // 2]) for k, v in self.acc.items()}
 
 
 def make_context(torch, fp, inputs, calibration, name):
@@ -173,7 +175,7 @@ def measure_eager(torch, fp, ctx, steps, warmup):
     torch.cuda.synchronize()
     seq_ms = (time.perf_counter() - t0) * 1e3 / steps
     timer.collect()
-    return seq_ms, timer.mean_ms()
+    return seq_ms, timer.mean_ms(), timer.min_median_ms()
 
 
 def one_workgroup_per_cloud(ctx):
@@ -598,9 +600,13 @@ def other_workloads(name):
 def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
     name = args.workload
     ctx = make_context(torch, fp, inputs, calibration, name)
-    seq_ms, kernel_ms = measure_eager(torch, fp, ctx, args.steps, args.warmup)
+    seq_ms, kernel_ms, kernel_min_median = measure_eager(torch, fp, ctx, args.steps, args.warmup)
     wl = ctx["wl"]
     detail = quality_and_rooflines(torch, fp, ctx, kernel_ms)
+    for s, stage in enumerate(detail["stages"]):
+        # the timed step's kernels over the timed steps: (min, median) beside the mean in kernel_ms
+        stage["kernel_ms_min_median"] = {key.split("/")[0]: [round(v[0], 6), round(v[1], 6)]
+                                         for key, v in kernel_min_median.items() if key.endswith("/s%d" % s)}
     props = torch.cuda.get_device_properties(ctx["xyz"].device)
     detail["device"] = {"name": props.name, "compute_units": int(props.multi_processor_count),
                         "memory_gib": round(props.total_memory / 2.0 ** 30, 1)}
