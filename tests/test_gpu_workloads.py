@@ -201,6 +201,47 @@ def test_million_point_workload(fp, cal):
     check_large(fp, cal, "C5", n_small=1024, bq_centres=128)
 
 
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_point_order_of_the_cloud(fp, cal, name):
+    """The workloads whose points come in scanner order (surface by surface, ring by ring), run
+    again with every cloud shuffled.  Exact FPS does not depend on the order of the points except
+    through ties between equal distances: started from the same point it picks the same points
+    (checked pick by pick while the two curves agree, which they do where no tie occurs).
+    MDPS takes "the lowest available index", so its samples do depend on the order; the coverage
+    bound has to hold in either order."""
+    wl = inputs.WORKLOADS[name]
+    st = wl.stages[0]
+    batch = inputs.make_batch(name)
+    B, N, n = wl.B, wl.N, st.n
+    rng = np.random.Generator(np.random.PCG64(99))
+    perms = [rng.permutation(N) for _ in range(B)]
+    shuffled = np.stack([batch[b][perms[b]] for b in range(B)])
+    starts = [int(np.flatnonzero(perms[b] == 0)[0]) for b in range(B)]       # where point 0 went
+    prm = cal.params_for(name, 0)
+    x, xs = dev(batch), dev(shuffled)
+    say("%s: scanner order and shuffled" % name)
+    idx, mdc = fp.fps_exact(x, n, want_mdc=True)
+    sidx, smdc = fp.fps_exact(xs, n, start_idx=starts, want_mdc=True)
+    midx = fp.mdps_sample(x, n, prm)
+    smidx = fp.mdps_sample(xs, n, prm, start_idx=starts)
+    cov = fp.coverage2(x, midx).sqrt() / fp.coverage2(x, idx).sqrt()
+    scov = fp.coverage2(xs, smidx).sqrt() / fp.coverage2(xs, sidx).sqrt()
+    torch.cuda.synchronize()
+    say("   coverage ratio max: scanner order %.4f, shuffled %.4f" % (float(cov.max()), float(scov.max())))
+    assert float(cov.max()) <= COVERAGE_BOUND and float(scov.max()) <= COVERAGE_BOUND
+    idx, mdc, sidx, smdc = idx.cpu().numpy(), mdc.cpu().numpy(), sidx.cpu().numpy(), smdc.cpu().numpy()
+    for b in range(B):
+        back = perms[b][sidx[b]]                           # the shuffled run's picks as original indices
+        same = back == idx[b]
+        agree = int(n if same.all() else np.argmin(same))  # picks before the first difference
+        assert np.array_equal(smdc[b, :agree], mdc[b, :agree])
+        if agree < n:
+            # the runs part at a tie: two points at the same distance, taken in index order
+            assert smdc[b, agree] == mdc[b, agree], "cloud %d parts at pick %d without a tie" % (b, agree)
+        say("   cloud %d: identical picks %d of %d" % (b, agree, n))
+        assert agree > n // 20
+
+
 def test_expired_wait_ends_the_kernel_cleanly(fp):
     # with a wait limit of zero a wait gives up after two empty polls: the kernel
     # must end on its own and report status 2 with an all -1 result (no hang, no fault)
