@@ -45,8 +45,8 @@ GRAPH = "four streams, step replayed as one HIP graph"
 # HBM traffic per launch of the kernels that can dominate the step, from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs (profiles/bench_C2_hbm_traffic.md); bytes, keyed by workload and
 # kernel.  None where no counter run is recorded.
-TRAFFIC_BYTES = {"C2": {"fps_exact": int((400.9 + 32.0) * 1024),
-                        "mdps_sample+record": int((788.9 + 1088.1) * 1024)}}
+TRAFFIC_BYTES = {"C2": {"fps_exact": int((408.9 + 32.0) * 1024),
+                        "mdps_sample+record": int((794.9 + 1088.1) * 1024)}}
 
 
 def parse_args():
