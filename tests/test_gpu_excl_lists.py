@@ -83,6 +83,18 @@ def test_batch_with_a_radius_set_per_cloud(fp):
     check_lists(fp, batch, thr)
 
 
+def test_batch_with_long_rows(fp):
+    # several clouds whose rows are longer than what the sorting kernel takes, radii per cloud
+    rng = np.random.Generator(np.random.PCG64(8))
+    batch = np.stack([np.concatenate([rng.normal(0.0, 0.02 * (b + 1), (1200, 3)),
+                                      rng.uniform(-1.0, 1.0, (800, 3))])[rng.permutation(2000)]
+                      for b in range(3)]).astype(np.float32)
+    thr = np.array([[0.01, 0.0004], [0.0009, 0.04], [0.09, 0.09]], dtype=np.float32)
+    off, _ = check_lists(fp, batch, thr)
+    sizes = np.diff(off.cpu().numpy()).reshape(2, 3, 2000)
+    assert (sizes.max(axis=(0, 2)) > 600).all()           # every cloud has rows for the bitmap kernel
+
+
 def test_ties_and_duplicates(fp):
     batch = np.stack([inputs.lattice_with_ties(60 + b, 900, 4) for b in range(2)])
     # radii on attainable squared distances (strict <) and between them
