@@ -7,7 +7,10 @@ every stage of its hierarchy:
     FastPoint    mdps_sample (records the radius tests) -> ball_query (cache reader)
                                                                 (Alg. 2 + Section 4.2)
     gather of the exact-FPS samples = input of the next stage (which waits for it)
-Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+Inputs are resident in HBM before the timed region.  The last line of stdout is ONE compact JSON
+line (headline workload C5, the largest one; a short entry per workload C1-C5 with the time of
+each of the two paths); everything else measured goes to a side file (--detail-file, default
+gpurun_out/bench_detail.json).
 
 Workloads whose clouds take one workgroup each leave most of the device idle, so their step
 runs the calls that do not wait for each other on four streams and is replayed as one captured
@@ -17,7 +20,7 @@ ones.  The per-kernel times and rooflines always come from calls that run alone 
 Outside the timed step the k nearest samples of every point (the k-NN of the up-sampling
 step, redundancy-free form of Section 4.2) are timed per stage and reported under "detail".
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-extra]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--no-extra]
 """
 import argparse
 import json
@@ -39,6 +42,8 @@ HBM_PEAK_GBS = 8000.0
 OPS_PER_POINT_ITERATION = 10      # 3 sub, 3 mul, 2 add, 1 min, 1 compare (FPS min-update + arg-max)
 OPS_PER_PAIR_TEST = 9             # 3 sub, 3 mul, 2 add, 1 compare (ball query, k-NN)
 KNN_K = 3                         # neighbours of the up-sampling step (Section 3.1)
+CPU_SAMPLE_N = 1536               # cpu_baseline on C4 / C5: samples of each sampler that are timed ...
+CPU_SAMPLE_M = 1024               # ... and ball-query centres
 EAGER = "one stream, eager launches"
 GRAPH = "four streams, step replayed as one HIP graph"
 
@@ -54,7 +59,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C5", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--detail-file", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
+                    help="where everything that does not fit the one result line is written")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads' summary")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--plain-launch", action="store_true",
@@ -479,24 +486,57 @@ def time_knn(torch, fp, x, sg, midx, reps=3):
 
 
 def cpu_baseline(inputs, name, budget_s=12.0):
-    """The CPU oracle, as it stands, on the same workload (one thread)."""
+    """The CPU oracle, as it stands, on the same workload (one thread).
+
+    C1-C3: whole clouds through all stages until the time budget is used.  C4 and C5: the oracle
+    would need minutes for one step, so a bounded sample is timed -- exact FPS and MDPS for the first
+    CPU_SAMPLE_N samples and the ball query of CPU_SAMPLE_M centres on the first cloud at its full
+    size -- and reported as rates; the step time is extrapolated from them (every pick folds all N
+    points, every centre tests all N points) and says so."""
     import numpy as np
     from oracle import ref
     from paper_2507_23480_amd import calibration
     wl = inputs.WORKLOADS[name]
     batch = inputs.make_batch(name)
+
+    def params(s):
+        ent = calibration.table()[name][s]
+        return ref.MdpsParams(p=calibration.P_RATIO, nseg=calibration.NSEG, exponent=ent["exponent"],
+                              bias=ent["bias"], fit_window=calibration.FIT_WINDOW,
+                              m_min=calibration.M_MIN, level_scale=ent["level_scale"])
+
+    if name in ("C4", "C5"):
+        st = wl.stages[0]
+        x = batch[0]
+        ns, ms = CPU_SAMPLE_N, CPU_SAMPLE_M
+        t0 = time.perf_counter()
+        idx, _ = ref.fps_exact(x, ns)
+        t1 = time.perf_counter()
+        ref.mdps_sample(x, ns, params(0))
+        t2 = time.perf_counter()
+        ref.ball_query(x, idx[:ms], st.radius, st.k)
+        t3 = time.perf_counter()
+        fps_rate = (ns - 1) * float(wl.N) / (t1 - t0)             # point-iterations per second
+        mdps_rate = (ns - 1) * float(wl.N) / (t2 - t1)
+        bq_rate = ms * float(wl.N) / (t3 - t2)                    # pair tests per second
+        step_s = wl.B * ((st.n - 1) * float(wl.N) * (1.0 / fps_rate + 1.0 / mdps_rate) +
+                         2.0 * st.n * float(wl.N) / bq_rate)
+        return {"value": wl.B * wl.N / step_s / 1e6, "unit": "Mpoints/s", "cores": 1, "kind": "oracle",
+                "sample": "RATES, not a full run: on cloud 0 of %s at full N = %d the first %d samples of "
+                          "fps_exact (%.1f s) and of mdps_sample (%.1f s) and the ball query of %d centres "
+                          "(%.1f s); the step (B = %d, n = %d, M = n, both paths) extrapolated linearly in "
+                          "samples and centres" % (name, wl.N, ns, t1 - t0, t2 - t1, ms, t3 - t2, wl.B, st.n),
+                "fps_point_iterations_per_s": fps_rate, "mdps_point_iterations_per_s": mdps_rate,
+                "ball_query_pair_tests_per_s": bq_rate, "ms_per_step_extrapolated": step_s * 1e3}
+
     done_points = 0
-    passes = 0
     clouds = 0
     t0 = time.perf_counter()
     while True:
         for b in range(wl.B):
             x = batch[b]
             for s, st in enumerate(wl.stages):
-                ent = calibration.table()[name][s]
-                prm = ref.MdpsParams(p=calibration.P_RATIO, nseg=calibration.NSEG, exponent=ent["exponent"],
-                                     bias=ent["bias"], fit_window=calibration.FIT_WINDOW,
-                                     m_min=calibration.M_MIN, level_scale=ent["level_scale"])
+                prm = params(s)
                 idx, _ = ref.fps_exact(x, st.n)
                 ref.ball_query(x, idx, st.radius, st.k)
                 midx, _ = ref.mdps_sample(x, st.n, prm)
@@ -507,7 +547,6 @@ def cpu_baseline(inputs, name, budget_s=12.0):
             clouds += 1
             if time.perf_counter() - t0 > budget_s:
                 break
-        passes += 1
         if time.perf_counter() - t0 > budget_s:
             break
     dt = time.perf_counter() - t0
@@ -523,7 +562,8 @@ def main():
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, "
               "no sharding across devices in this library)" % args.gpus, file=sys.stderr)
         return 2
-    extra = {} if args.no_extra else other_workloads(args.workload)
+    os.makedirs(os.path.dirname(os.path.abspath(args.detail_file)), exist_ok=True)
+    extra = {} if args.no_extra else other_workloads(args.workload, args.detail_file)
     clock_reader = None if args.no_extra else start_clock_reader()
     import torch
     from paper_2507_23480_amd import binding as fp, inputs, calibration
@@ -572,29 +612,47 @@ def clocks_under_load(torch, fp, reader):
         return None
 
 
-def other_workloads(name):
+def other_workloads(name, detail_file):
     """The other workloads, each measured by a process of its own (started before this one
     touches the GPU): cooperative launches and graph replays with a second stream slow each
-    other's launches down by tens of microseconds once both have run in one process."""
+    other's launches down by tens of microseconds once both have run in one process.  Returns
+    {workload: its short summary}; each child writes its own detail file next to `detail_file`."""
     import subprocess
     extra = {}
+    stem, ext = os.path.splitext(detail_file)
     for other in ["C1", "C2", "C3", "C4", "C5"]:
         if other == name:
             continue
         k = 3 if other in ("C4", "C5") else 10
         cmd = [sys.executable, os.path.abspath(__file__), "--workload", other, "--no-extra", "--no-cpu",
-               "--steps", str(k), "--warmup", "1"]
+               "--steps", str(k), "--warmup", "1", "--detail-file", "%s_%s%s" % (stem, other, ext)]
         try:
             out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, timeout=240,
                                  check=True).stdout.decode()
             d = json.loads(out.strip().splitlines()[-1])
-            extra[other] = {"ms_per_step": d["ms_per_step"], "Mpoints_per_s": d["value"], "steps": k,
-                            "launch": d["config"]["launch"],
-                            "ms_per_step_one_stream_eager": d["config"]["ms_per_step_one_stream_eager"],
-                            "detail": d["detail"]}
+            extra[other] = d["workloads"][other]
         except Exception as exc:                 # reported, not fatal: the headline line still prints
-            extra[other] = {"error": repr(exc)[:200]}
+            extra[other] = {"error": repr(exc)[:120]}
     return extra
+
+
+def path_summary(wl, detail, ms_per_step, launch_mode, roof):
+    """The short entry of one workload: time of the exact path (fps_exact + brute-force ball query
+    [+ gather of the next stage's input]) and of the FastPoint path (mdps_sample recording the
+    radius tests + ball query from the record), summed over the stages, each kernel timed alone."""
+    exact = fast = 0.0
+    for st in detail["stages"]:
+        ms = st["kernel_ms"]
+        exact += ms["fps_exact"] + ms["ball_query_brute"] + ms.get("gather", 0.0)
+        fast += ms["mdps_sample+record"] + ms["ball_query_cached"]
+    pts = wl.B * wl.N / 1e6
+    s0 = detail["stages"][0]
+    return {"ms_per_step": round(ms_per_step, 4), "launch": "graph" if launch_mode == GRAPH else "eager",
+            "exact_path_ms": round(exact, 4), "fastpoint_path_ms": round(fast, 4),
+            "exact_Mpoints_s": round(pts / (exact * 1e-3), 2), "fastpoint_Mpoints_s": round(pts / (fast * 1e-3), 2),
+            "mdps_coverage_ratio_max": round(max(st["mdps_coverage_ratio_max"] for st in detail["stages"]), 4),
+            "mdps_over_fps_time": round(s0["kernel_ms"]["mdps_sample"] / s0["kernel_ms"]["fps_exact"], 3),
+            "dominant_kernel": roof["kernel"], "dominant_frac": round(roof["frac"], 4)}
 
 
 def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
@@ -639,6 +697,13 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
     ms_per_step, launch_mode = seq_ms, EAGER
     if one_workgroup_per_cloud(ctx):
         ms_per_step, launch_mode = measure_graph(torch, fp, ctx, args.steps, args.warmup), GRAPH
+    summary = path_summary(wl, detail, ms_per_step, launch_mode, roof)
+    workloads = dict(extra)
+    workloads[name] = summary
+    short_roof = {key: roof[key] for key in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel",
+                                               "ms_per_launch", "plain_fp32_rate_measured",
+                                               "frac_of_plain_fp32_rate", "compute_units_in_use", "bytes")
+                  if key in roof}
     line = {
         "metric": "FPS+ball-query latency per batch (ms) and Mpoints/s; achieved HBM GB/s vs peak",
         "value": wl.B * wl.N / (ms_per_step * 1e-3) / 1e6, "unit": "Mpoints/s",
@@ -647,23 +712,39 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (name, wl.description), "B": wl.B, "N": wl.N,
                    "stages": [{"n": st.n, "radius": st.radius, "k": st.k} for st in wl.stages],
-                   "step": "per stage: fps_exact, ball_query(brute), mdps_sample(+radius record), "
-                           "ball_query(cache reader), gather",
-                   "launch": launch_mode, "ms_per_step_one_stream_eager": seq_ms,
-                   "mdps": {"p": calibration.P_RATIO, "nseg": calibration.NSEG}},
-        "roofline": roof,
-        "detail": detail,
+                   "step": "per stage both paths: fps_exact + ball_query(brute) [+ gather]; "
+                           "mdps_sample(recording radius tests) + ball_query(from the record)",
+                   "launch": launch_mode, "mdps": {"p": calibration.P_RATIO, "nseg": calibration.NSEG}},
+        "paths": {"exact_path_ms": summary["exact_path_ms"], "fastpoint_path_ms": summary["fastpoint_path_ms"],
+                  "exact_Mpoints_s": summary["exact_Mpoints_s"],
+                  "fastpoint_Mpoints_s": summary["fastpoint_Mpoints_s"]},
+        "roofline": short_roof,
     }
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(inputs, name)
-    if extra:
-        line["other_workloads"] = extra
+    line["workloads"] = {key: workloads[key] for key in sorted(workloads)}
+    line["detail_file"] = os.path.relpath(args.detail_file, ROOT)
     if args.copy_probe:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
-    print(json.dumps(line))
+    full = dict(line)
+    full["roofline"] = roof
+    full["config"] = dict(line["config"], ms_per_step_one_stream_eager=seq_ms)
+    full["detail"] = detail
+    with open(args.detail_file, "w") as f:
+        json.dump(full, f, indent=1)
+        f.write("\n")
+    text = json.dumps(line)
+    if len(text) > 4000:                       # the driver reads the tail of stdout: keep the line short
+        for key in ("detail_file",):
+            line.pop(key, None)
+        for w in line["workloads"].values():
+            w.pop("dominant_kernel", None)
+        text = json.dumps(line)
+    sys.stdout.flush()
+    print(text, flush=True)
     return 0
 
 

@@ -289,8 +289,8 @@ static double ref_mlp_value(const double *out, const float *mdc, int32_t n, int3
 
 /*
  * Curve estimator and segment thresholds (Section 4.1 step 1, Eq. 1, with the
- * power-function estimator of Appendix A.3; Section 4.1 step 2 and Alg. 2 line
- * 20 for the thresholds).
+ * power-function estimator of Appendix A.3; the threshold set-up of Alg. 2,
+ * Section 4.1 step 2).
  *   mdc[0..m]  measured curve of the prefix (mdc[0] unused)
  *   C(x) = a / x^e ; a = mean over the last W prefix points of mdc[i] * i^e
  *   R_l^2 = curve value at the END of segment l, index b_l = floor(n*l/nseg)
@@ -495,15 +495,63 @@ static int ref_list_push(ref_list *l, int32_t x)
 }
 
 /*
- * MDPS with the data structures of Algorithm 2 written out: per-level
- * exclusion lists for every point (the list-building loops, one distance per pair), one
- * availability bitmap per level, bitmap clearing from the lists of the most
- * recent sample for the current and all later levels, findAnyOne = lowest set
- * bit, and the early-termination rebuild of dists from the level-1 lists
- * restricted to sampled points followed by the remainder FPS.  O(N^2) time and memory: tiny
- * clouds only.  The bitmaps start from all ones and then have the prefix
- * samples' lists cleared, because the prefix samples stay part of the output.
+ * MDPS with the data structures of Algorithm 2 kept explicitly, as a check that the
+ * running-distance form of ref_mdps_sample is the same method: an exclusion list per
+ * (level, point), an availability bitmap per level, and nothing else deciding a pick.
+ * O(N^2) time and memory: tiny clouds only.  The helpers below are the operations on the
+ * two structures; ref_mdps_literal strings them together.
  */
+
+/* All exclusion lists of a cloud: list (l, a) receives every b with dist2(a, b) < thr2[l],
+ * in ascending b; one distance per pair serves all levels. */
+static int lit_build_lists(const float *xyz, int32_t N, const float *thr2, int32_t nseg, ref_list *excl)
+{
+    for (int32_t a = 0; a < N; ++a)
+        for (int32_t b = 0; b < N; ++b) {
+            float d = ref_dist2(xyz + 3 * (size_t)a, xyz + 3 * (size_t)b);
+            for (int32_t l = 0; l < nseg; ++l)
+                if (d < thr2[l] && ref_list_push(&excl[(size_t)l * N + a], b) != 0)
+                    return -1;
+        }
+    return 0;
+}
+
+/* A sample makes the members of its lists unavailable on levels first_level .. nseg-1. */
+static void lit_exclude(uint8_t *bitmap, const ref_list *excl, int32_t N, int32_t nseg, int32_t first_level,
+                        int32_t sample)
+{
+    for (int32_t l = first_level; l < nseg; ++l) {
+        const ref_list *li = &excl[(size_t)l * N + sample];
+        for (int32_t t = 0; t < li->len; ++t)
+            bitmap[(size_t)l * N + li->v[t]] = 0;
+    }
+}
+
+/* "Any available point" of a level is taken to be the lowest index; -1 if the level has none. */
+static int32_t lit_lowest_available(const uint8_t *bitmap, int32_t N, int32_t level)
+{
+    for (int32_t j = 0; j < N; ++j)
+        if (bitmap[(size_t)level * N + j])
+            return j;
+    return -1;
+}
+
+/* Early termination: the distance of every point to its nearest sample, taken from the
+ * sampled members of its widest (level-1) list on top of what dists already holds. */
+static void lit_distances_from_lists(const float *xyz, int32_t N, const ref_list *excl,
+                                     const uint8_t *is_sampled, float *dists)
+{
+    for (int32_t a = 0; a < N; ++a) {
+        const ref_list *li = &excl[a];               /* level 1 is stored first */
+        for (int32_t t = 0; t < li->len; ++t)
+            if (is_sampled[li->v[t]]) {
+                float d = ref_dist2(xyz + 3 * (size_t)a, xyz + 3 * (size_t)li->v[t]);
+                if (dists[a] > d)
+                    dists[a] = d;
+            }
+    }
+}
+
 int ref_mdps_literal(const float *xyz, int32_t N, int32_t n, int32_t start,
                      const ref_mdps_params *prm, int32_t *out_idx, ref_mdps_info *info_out)
 {
@@ -530,7 +578,7 @@ int ref_mdps_literal(const float *xyz, int32_t N, int32_t n, int32_t start,
     if (!dists || !mdc || !excl || !bitmap || !is_sampled)
         goto done;
 
-    /* 1-1: prefix FPS, curve capture */
+    /* the exact iterations that open the method, with the curve they measure */
     for (int32_t j = 0; j < N; ++j)
         dists[j] = INFINITY;
     out_idx[0] = start;
@@ -541,26 +589,16 @@ int ref_mdps_literal(const float *xyz, int32_t N, int32_t n, int32_t start,
         out_idx[i] = best;
         mdc[i] = dists[best];
     }
-    /* 1-2: estimation */
     if (ref_mdps_thresholds(mdc, n, m, prm, info.thr2) != 0)
         goto done;
-    /* 2: exclusion lists, one distance per pair */
-    for (int32_t a = 0; a < N; ++a)
-        for (int32_t b = 0; b < N; ++b) {
-            float d = ref_dist2(xyz + 3 * (size_t)a, xyz + 3 * (size_t)b);
-            for (int32_t l = 0; l < nseg; ++l)
-                if (d < info.thr2[l])
-                    if (ref_list_push(&excl[(size_t)l * N + a], b) != 0)
-                        goto done;
-        }
-    /* 3: bitmaps */
+    if (lit_build_lists(xyz, N, info.thr2, nseg, excl) != 0)
+        goto done;
+    /* every point starts available on every level; the samples kept from the opening
+     * iterations (0..m-1; sample m is excluded by the loop below) then exclude theirs */
     memset(bitmap, 1, (size_t)nseg * (size_t)N);
-    for (int32_t s = 0; s < m; ++s)          /* prefix samples 0..m-1 */
-        for (int32_t l = 0; l < nseg; ++l) {
-            ref_list *li = &excl[(size_t)l * N + out_idx[s]];
-            for (int32_t t = 0; t < li->len; ++t)
-                bitmap[(size_t)l * N + li->v[t]] = 0;
-        }
+    for (int32_t s = 0; s < m; ++s)
+        lit_exclude(bitmap, excl, N, nseg, 0, out_idx[s]);
+
     int32_t seg = 0;
     int32_t i = m + 1;
     while (i < n) {
@@ -572,17 +610,8 @@ int ref_mdps_literal(const float *xyz, int32_t N, int32_t n, int32_t start,
         }
         if (seg > nseg)
             break;
-        for (int32_t l = seg - 1; l < nseg; ++l) {
-            ref_list *li = &excl[(size_t)l * N + out_idx[i - 1]];
-            for (int32_t t = 0; t < li->len; ++t)
-                bitmap[(size_t)l * N + li->v[t]] = 0;
-        }
-        int32_t pick = -1;
-        for (int32_t j = 0; j < N; ++j)
-            if (bitmap[(size_t)(seg - 1) * N + j]) {
-                pick = j;
-                break;
-            }
+        lit_exclude(bitmap, excl, N, nseg, seg - 1, out_idx[i - 1]);
+        int32_t pick = lit_lowest_available(bitmap, N, seg - 1);
         if (pick < 0) {
             info.level_exhausted[seg - 1] = 1;
             ++seg;
@@ -593,22 +622,13 @@ int ref_mdps_literal(const float *xyz, int32_t N, int32_t n, int32_t start,
         out_idx[i] = pick;
         ++i;
     }
-    /* 4: early termination */
     if (i < n) {
+        /* the last level ran out before n samples: the rest is exact FPS, on distances that
+         * so far only know the samples 0..m-1 */
         info.et_index = i;
         for (int32_t s = 0; s < i; ++s)
             is_sampled[out_idx[s]] = 1;
-        /* 4-1: dists still holds the prefix state (samples 0..m-1) */
-        for (int32_t a = 0; a < N; ++a) {
-            ref_list *li = &excl[(size_t)0 * N + a];
-            for (int32_t t = 0; t < li->len; ++t)
-                if (is_sampled[li->v[t]]) {
-                    float d = ref_dist2(xyz + 3 * (size_t)a, xyz + 3 * (size_t)li->v[t]);
-                    if (dists[a] > d)
-                        dists[a] = d;
-                }
-        }
-        /* 4-2: remainder FPS */
+        lit_distances_from_lists(xyz, N, excl, is_sampled, dists);
         for (; i < n; ++i) {
             ref_fold(xyz, N, out_idx[i - 1], dists);
             out_idx[i] = ref_argmax(dists, N);

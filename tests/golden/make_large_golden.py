@@ -1,0 +1,122 @@
+"""Writes the stored oracle results of the two large workloads (C4: 4 x 120000 -> 16384,
+C5: 1 x 1000000 -> 65536) at their full sample counts.
+
+The CPU oracle needs about 15 s per C4 cloud and about 10 minutes per sampler on the C5 cloud,
+too long for a test run, so its outputs are computed once by this script and kept next to it
+(`c4_full.npz`, `c5_full.npz`).  The GPU parity tests compare every element with them.
+
+This script calls ONLY the oracle (`oracle/ref.py`) and the seeded input generators
+(`paper_2507_23480_amd/inputs.py`); the MDPS constants are read as plain numbers from the JSON
+tables the calibration wrote and are stored in the output, so a test feeds exactly these to the
+GPU.  No value in the files comes from the HIP library.
+
+    python tests/golden/make_large_golden.py C4 C5            # everything that is missing
+    python tests/golden/make_large_golden.py --force C4       # recompute
+
+Stored per workload (B clouds, n samples, nseg levels):
+    fps_idx [B][n] int32, fps_mdc [B][n] float32          Algorithm 1 (ref_fps_exact)
+    per variant v of the estimator constants:
+    mdps_idx_v [B][n] int32, m_v [B], et_index_v [B], level_start_v [B][nseg],
+    level_exhausted_v [B][nseg] int32, thr2_v [B][nseg] float32      Algorithm 2 (ref_mdps_sample)
+    params_v                                              JSON text of the constants used
+"""
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(HERE))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from oracle import ref                                   # noqa: E402
+from paper_2507_23480_amd import inputs                  # noqa: E402
+
+PKG = os.path.join(ROOT, "paper_2507_23480_amd")
+# variant name -> table of fitted constants (plain JSON written by the calibration module)
+TABLES = {"calibrated": os.path.join(PKG, "mdps_calibration.json"),
+          "paper": os.path.join(PKG, "mdps_calibration_paper.json")}
+P_RATIO, NSEG, FIT_WINDOW, M_MIN = 0.1, 6, 32, 8
+
+
+def out_path(name):
+    return os.path.join(HERE, name.lower() + "_full.npz")
+
+
+def params_of(variant, name):
+    path = TABLES[variant]
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        ent = json.load(f).get(name)
+    if not ent:
+        return None
+    ent = ent[0]
+    return {"p": P_RATIO, "nseg": NSEG, "exponent": float(ent["exponent"]), "bias": float(ent["bias"]),
+            "fit_window": FIT_WINDOW, "m_min": M_MIN, "level_scale": [float(v) for v in ent["level_scale"]]}
+
+
+def run(name, force):
+    wl = inputs.WORKLOADS[name]
+    st = wl.stages[0]
+    batch = inputs.make_batch(name)
+    path = out_path(name)
+    have = {}
+    if os.path.exists(path) and not force:
+        with np.load(path) as z:
+            have = {k: z[k] for k in z.files}
+    jobs = []
+    if "fps_idx" not in have:
+        jobs += [("fps", None, b) for b in range(wl.B)]
+    variants = {}
+    for v in TABLES:
+        p = params_of(v, name)
+        if p is None:
+            continue
+        text = json.dumps(p, sort_keys=True)
+        if "params_" + v in have and str(have["params_" + v]) == text:
+            continue
+        variants[v] = p
+        jobs += [("mdps", v, b) for b in range(wl.B)]
+    if not jobs:
+        print(name, "nothing to do", flush=True)
+        return
+
+    def one(job):
+        kind, v, b = job
+        t0 = time.time()
+        if kind == "fps":
+            r = ref.fps_exact(batch[b], st.n)
+        else:
+            r = ref.mdps_sample(batch[b], st.n, ref.MdpsParams(**variants[v]))
+        print("%s %s %s cloud %d: %.0f s" % (name, kind, v or "", b, time.time() - t0), flush=True)
+        return r
+
+    with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1)) as ex:   # ctypes drops the GIL
+        results = list(ex.map(one, jobs))
+    fps = [r for j, r in zip(jobs, results) if j[0] == "fps"]
+    if fps:
+        have["fps_idx"] = np.stack([r[0] for r in fps])
+        have["fps_mdc"] = np.stack([r[1] for r in fps])
+    for v, p in variants.items():
+        rs = [r for j, r in zip(jobs, results) if j[0] == "mdps" and j[1] == v]
+        have["mdps_idx_" + v] = np.stack([r[0] for r in rs])
+        have["m_" + v] = np.array([r[1].m for r in rs], np.int32)
+        have["et_index_" + v] = np.array([r[1].et_index for r in rs], np.int32)
+        have["level_start_" + v] = np.stack([r[1].level_start for r in rs])
+        have["level_exhausted_" + v] = np.stack([r[1].level_exhausted for r in rs])
+        have["thr2_" + v] = np.stack([r[1].thr2 for r in rs])
+        have["params_" + v] = np.array(json.dumps(p, sort_keys=True))
+    np.savez_compressed(path, **have)
+    print("wrote", path, os.path.getsize(path), "bytes", flush=True)
+
+
+if __name__ == "__main__":
+    args = sys.argv[1:]
+    force = "--force" in args
+    for nm in [a for a in args if not a.startswith("--")] or ["C4", "C5"]:
+        run(nm, force)

@@ -1,0 +1,82 @@
+"""Repeat-run determinism of the kernels whose workgroups talk to each other: the same call
+twenty times on shapes spread over several workgroups has to give the same bytes every time
+(samples, curve, bookkeeping, the ball query answered from the recorded radius tests, exclusion
+list offsets and members).  The exchange between workgroups uses relaxed atomics on words that
+validate themselves by a sequence stamp; a word taken from the wrong round, a wait that lets a
+stale value through or a race in the list kernels would show here as a run that differs.  The
+first run is also compared with the oracle, so "the same every time" means "right every time"."""
+import numpy as np
+import pytest
+
+from oracle import ref
+from paper_2507_23480_amd import inputs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+RUNS = 20
+
+
+@pytest.fixture(scope="module")
+def fp():
+    from paper_2507_23480_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    binding.set_wg_per_cloud(0)
+    return binding
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def same(a, b):
+    return all(torch.equal(x, y) for x, y in zip(a, b))
+
+
+def info_words(fp, info):
+    """The per-cloud records without the phase timings (which are measurements, not results)."""
+    return [(i.m, i.et_index, list(i.level_start), list(i.level_exhausted), list(i.thr2), i.rounds, i.status)
+            for i in fp.parse_info(info)]
+
+
+@pytest.mark.parametrize("B,N,n,radius,k", [(3, 30000, 3000, 0.05, 16), (1, 200000, 6000, 0.03, 32)])
+def test_samplers_give_the_same_bytes_every_run(fp, B, N, n, radius, k):
+    batch = np.stack([inputs.uniform_cube(4100 + b, N) for b in range(B)])
+    xyz = torch.from_numpy(batch).cuda()
+    assert fp.plan(B, N)[0] > 1, "the shape has to spread a cloud over several workgroups"
+    prm = fp.MdpsParams(exponent=0.86, bias=1.05)
+    first = None
+    for run in range(RUNS):
+        cache = fp.new_bq_cache(xyz, n)
+        idx, mdc = fp.fps_exact(xyz, n, want_mdc=True)
+        midx, info = fp.mdps_sample(xyz, n, prm, want_info=True, bq_cache=cache, bq_radius=radius)
+        bq, cnt = fp.ball_query(xyz, midx, radius, k, bq_cache=cache)
+        torch.cuda.synchronize()
+        got = ([idx, mdc, midx, bq, cnt], info_words(fp, info))
+        if first is None:
+            first = got
+            rp = ref.MdpsParams(exponent=0.86, bias=1.05)
+            for b in range(B):
+                widx, wmdc = ref.fps_exact(batch[b], n)
+                wmidx, _ = ref.mdps_sample(batch[b], n, rp)
+                assert np.array_equal(idx[b].cpu().numpy(), widx) and np.array_equal(mdc[b].cpu().numpy(), wmdc)
+                assert np.array_equal(midx[b].cpu().numpy(), wmidx)
+            continue
+        assert same(got[0], first[0]) and got[1] == first[1], "run %d differs from run 0" % run
+    say("   %d runs of fps_exact, mdps_sample (recording) and the cached ball query: identical" % RUNS)
+
+
+def test_exclusion_lists_give_the_same_bytes_every_run(fp):
+    batch = np.stack([inputs.uniform_cube(4200 + b, 20000) for b in range(2)])
+    xyz = torch.from_numpy(batch).cuda()
+    thr = torch.tensor([[0.004, 0.001, 0.0004], [0.003, 0.002, 0.0001]], dtype=torch.float32).cuda()
+    first = None
+    for run in range(RUNS):
+        off, ent = fp.excl_lists(xyz, thr)
+        torch.cuda.synchronize()
+        if first is None:
+            first = (off.clone(), ent.clone())
+            continue
+        assert torch.equal(off, first[0]) and torch.equal(ent, first[1]), "run %d differs from run 0" % run
+    say("   %d runs of fp_excl_count / fp_excl_fill: identical (%d members)" % (RUNS, first[1].numel()))

@@ -266,3 +266,72 @@ def test_workload_shapes_with_the_thresholds_of_mdps(fp, name, clouds):
     bidx, bcnt = fp.ball_query(x, midx, st.radius, st.k)
     torch.cuda.synchronize()
     assert torch.equal(idx, bidx) and torch.equal(cnt, bcnt)
+
+
+def test_lidar_cloud_at_full_size(fp):
+    """One full cloud of the LiDAR-like workload (120 000 points in ring-major order, rows of
+    several thousand members near the sensor) with the levels of its own MDPS run and the
+    ball-query radius.  The oracle's all-pairs pass gives the size of EVERY row (its count pass;
+    about a minute on one core); the members of rows sampled over the whole index range, the
+    longest rows among them, are compared with the oracle's ball query (a row is the ball of its
+    point: first k members by index with k above the longest row); and the relation is checked
+    to be symmetric on all rows."""
+    from paper_2507_23480_amd import calibration
+    wl = inputs.WORKLOADS["C4"]
+    st = wl.stages[0]
+    cloud = inputs.make_cloud("C4", 1)
+    N = wl.N
+    x = dev(cloud[None])
+    prm = calibration.params_for("C4", 0)
+    _, info = fp.mdps_sample(x, st.n, prm, want_info=True)
+    torch.cuda.synchronize()
+    rec = fp.parse_info(info)[0]
+    radii2 = [rec.thr2[l] for l in range(prm.nseg)] + [np.float32(st.radius) * np.float32(st.radius)]
+    thr = np.array([radii2], dtype=np.float32)
+    L = thr.shape[1]
+    say("excl lists, C4 cloud at full size: N=%d, %d levels" % (N, L))
+    off, ent = fp.excl_lists(x, dev(thr))
+    torch.cuda.synchronize()
+    say("   %d members; oracle count pass over all pairs ..." % ent.numel())
+    woff = np.empty(L * N + 1, dtype=np.int64)
+    rc = ref.lib().ref_excl_lists(cloud.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), N,
+                                  thr[0].ctypes.data_as(ctypes.POINTER(ctypes.c_float)), L,
+                                  woff.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), None, 0)
+    assert rc == 0
+    assert np.array_equal(off.cpu().numpy(), woff), "row sizes differ from the oracle's"
+    say("   all %d row sizes equal the oracle's" % (L * N))
+    sizes = np.diff(woff).reshape(L, N)
+    for l in range(L):      # symmetry on every row: i is in the row of j exactly when j is in the row of i
+        counts = torch.bincount(ent[int(woff[l * N]):int(woff[(l + 1) * N])], minlength=N)
+        assert np.array_equal(counts.cpu().numpy(), sizes[l])
+    rng = np.random.Generator(np.random.PCG64(44))
+    widest = int(np.argmax(radii2))
+    picks = np.unique(np.concatenate([np.argsort(sizes[widest])[-150:], rng.integers(0, N, 1350),
+                                      np.arange(0, N, N // 100)])).astype(np.int32)
+    off_h = woff
+    for l in range(L):
+        kmax = int(sizes[l][picks].max()) + 1
+        radius = float(np.sqrt(np.float64(radii2[l])))
+        if np.float32(radius) * np.float32(radius) != np.float32(radii2[l]):
+            continue        # the level's squared radius is not the square of a binary32 radius: no ball query gives it
+        for c0 in range(0, len(picks), 128):
+            chunk = picks[c0:c0 + 128]
+            widx, wcnt = ref.ball_query(cloud, chunk, radius, kmax)
+            for t, i in enumerate(chunk):
+                a, b = int(off_h[l * N + i]), int(off_h[l * N + i + 1])
+                assert b - a == wcnt[t]
+                assert np.array_equal(ent[a:b].cpu().numpy(), widx[t, :wcnt[t]]), "members, level %d point %d" % (l, i)
+        say("   level %d: members of %d sampled rows (longest %d) equal the oracle's" % (l, len(picks), kmax - 1))
+
+
+def test_clouds_too_large_for_the_lists_are_refused(fp):
+    """The list kernels address a cloud's points and rows with the limits the header states; a
+    shape beyond them is refused on the host with FP_ERR_SHAPE and nothing is launched."""
+    lib = fp.load()
+    assert lib.fp_excl_workspace_bytes(1, 1 << 30, 17) == 0 or lib.fp_excl_workspace_bytes(70000, 1 << 20, 2) == 0
+    assert lib.fp_excl_workspace_bytes(70000, 100, 2) == 0          # more clouds than the grid kernels index
+    x = dev(inputs.uniform_cube(1, 100)[None])
+    thr = dev(np.array([[0.1]], dtype=np.float32))
+    off = torch.empty(101, dtype=torch.int64, device="cuda")
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    assert lib.fp_excl_count(x.data_ptr(), 70000, 100, thr.data_ptr(), 1, off.data_ptr(), ws.data_ptr(), 4096, None) == -2

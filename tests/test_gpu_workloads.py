@@ -1,15 +1,19 @@
 """GPU parity at the five workload shapes, in the launch configuration bench.py times
 (automatic plan, calibrated MDPS constants).
 
-C1-C3: every cloud, every stage, element by element against the oracle.
-C4, C5: the oracle cannot run the full job in seconds, so
-  * full N with a reduced sample count n: element-by-element parity (for FPS the result is a
-    prefix of the full run, which is checked too);
-  * full N and full n: sampled outputs the oracle can compute one by one (ball-query rows of
-    sampled centres, curve values of sampled picks) and properties that hold at any size
-    (non-increasing curve, spacing bound per MDPS level, cached == brute, coverage bound);
-    k-NN rows of sampled points, redundancy-free k-NN == brute force on every point.
+C1-C3: every cloud, every stage, element by element against the oracle, run live.
+C4, C5: the oracle needs minutes for the full job, so
+  * full N and full n: every sample of exact FPS (index and curve value) and of MDPS (index,
+    thresholds, prefix length, level starts, exhausted flags, early-termination position) is
+    compared with the oracle's results stored in tests/golden/c4_full.npz and c5_full.npz
+    (written by tests/golden/make_large_golden.py, which calls only the oracle; the MDPS constants
+    it used are stored with them and fed to the GPU here);
+  * ball-query and k-NN rows of a few thousand sampled centres / points, computed live by the
+    oracle; cached == brute on every row; coverage bound; properties that hold at any size;
+  * full N with a reduced sample count n once more live against the oracle.
 """
+import json
+import os
 import sys
 from concurrent.futures import ThreadPoolExecutor
 
@@ -117,6 +121,40 @@ def test_full_workload_matches_oracle(fp, cal, name):
             batch = np.stack([ref.gather_xyz(batch[b], idx[b]) for b in range(wl.B)])
 
 
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def check_against_stored_oracle(fp, name, xyz, idx, mdc):
+    """Every sample of the full-size run against the oracle's stored results: exact FPS as given,
+    MDPS run here with each stored set of estimator constants."""
+    wl = inputs.WORKLOADS[name]
+    n = wl.stages[0].n
+    with np.load(os.path.join(GOLDEN, name.lower() + "_full.npz")) as z:
+        gold = {k: z[k] for k in z.files}
+    assert gold["fps_idx"].shape == (wl.B, n)
+    assert np.array_equal(idx, gold["fps_idx"]), "%s exact FPS: samples differ from the stored oracle result" % name
+    assert np.array_equal(mdc, gold["fps_mdc"]), "%s exact FPS: curve differs from the stored oracle result" % name
+    variants = sorted(k[len("params_"):] for k in gold if k.startswith("params_"))
+    assert "calibrated" in variants
+    for v in variants:
+        p = json.loads(str(gold["params_" + v]))
+        prm = fp.MdpsParams(p=p["p"], nseg=p["nseg"], exponent=p["exponent"], bias=p["bias"],
+                            fit_window=p["fit_window"], m_min=p["m_min"], level_scale=p["level_scale"])
+        midx, info = fp.mdps_sample(xyz, n, prm, want_info=True)
+        torch.cuda.synchronize()
+        infos = fp.parse_info(info)
+        assert np.array_equal(midx.cpu().numpy(), gold["mdps_idx_" + v]), \
+            "%s MDPS (%s constants): samples differ from the stored oracle result" % (name, v)
+        for b, gi in enumerate(infos):
+            assert gi.status == 0 and gi.m == gold["m_" + v][b] and gi.et_index == gold["et_index_" + v][b]
+            assert np.array_equal(np.array(gi.thr2[:prm.nseg], np.float32), gold["thr2_" + v][b])
+            assert np.array_equal(np.array(gi.level_start[:prm.nseg]), gold["level_start_" + v][b])
+            assert np.array_equal(np.array(gi.level_exhausted[:prm.nseg]), gold["level_exhausted_" + v][b])
+        say("   %s constants: all %d x %d MDPS samples equal the stored oracle result (FPS tail %s)"
+            % (v, wl.B, n, [n - int(e) for e in gold["et_index_" + v]]))
+    return gold
+
+
 def check_large(fp, cal, name, n_small, bq_centres):
     wl = inputs.WORKLOADS[name]
     st = wl.stages[0]
@@ -162,6 +200,10 @@ def check_large(fp, cal, name, n_small, bq_centres):
     infos = fp.parse_info(info)
     say("   coverage ratio max %.4f, FPS tail %s" % (float(cov.max()), [n - i.et_index for i in infos]))
     assert float(cov.max()) <= COVERAGE_BOUND
+    gold = check_against_stored_oracle(fp, name, xyz, idx, mdc)
+    if json.loads(str(gold["params_calibrated"]))["bias"] == prm.bias:
+        # the recording run above used the stored constants: its samples are the stored ones too
+        assert np.array_equal(midx, gold["mdps_idx_calibrated"])
     rng = np.random.Generator(np.random.PCG64(5))
     for b in range(B):
         pts = batch[b]
@@ -194,11 +236,11 @@ def check_large(fp, cal, name, n_small, bq_centres):
 
 
 def test_lidar_workload(fp, cal):
-    check_large(fp, cal, "C4", n_small=2048, bq_centres=256)
+    check_large(fp, cal, "C4", n_small=2048, bq_centres=4096)
 
 
 def test_million_point_workload(fp, cal):
-    check_large(fp, cal, "C5", n_small=1024, bq_centres=128)
+    check_large(fp, cal, "C5", n_small=1024, bq_centres=2048)
 
 
 @pytest.mark.parametrize("name", ["C3", "C4"])

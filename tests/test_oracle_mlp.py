@@ -165,3 +165,54 @@ def test_committed_weights_predict_the_curves_of_a_workload():
         out = ref.mlp_curve(curves[b], m, w)
         assert np.allclose(out, mlp_estimator.forward(w, x[b:b + 1])[0], rtol=1e-9, atol=1e-11)
     assert mlp_estimator.table()["C2"][0]["mape_percent_workload"] < 6.0
+
+
+def test_exponent_outside_the_range_is_clamped():
+    """ref_exp_fixed brings its argument into [-700, 700] first (NaN counts as -700), so that the
+    scaling by a power of two stays exact whatever a network puts out: beyond the range the
+    result is that of the nearest end, pinned here against libm's exp at the two ends."""
+    top, bottom = math.exp(700.0), math.exp(-700.0)        # 1.0142320547350045e+304, 9.85967654375977e-305
+    assert top == pytest.approx(1.0142320547350045e304, rel=1e-15)
+    assert bottom == pytest.approx(9.85967654375977e-305, rel=1e-15)
+    assert ref.exp_fixed(700.0) == pytest.approx(top, rel=1e-13)
+    assert ref.exp_fixed(-700.0) == pytest.approx(bottom, rel=1e-13)
+    for y in (700.0000001, 1e4, 1e300, math.inf):
+        assert ref.exp_fixed(y) == ref.exp_fixed(700.0)
+    for y in (-700.0000001, -1e4, -1e300, -math.inf, math.nan):
+        assert ref.exp_fixed(y) == ref.exp_fixed(-700.0)
+    # just inside the range nothing is clamped
+    assert ref.exp_fixed(699.5) == pytest.approx(math.exp(699.5), rel=1e-13)
+    assert ref.exp_fixed(699.5) < ref.exp_fixed(700.0)
+
+
+def test_inputs_whose_ratio_is_not_a_finite_number_at_least_one_read_as_zero():
+    """A curve that has fallen to 0 at the end of the prefix (every remaining point coincides with
+    a sample) makes the ratios mdc[i] / mdc[m] infinite or 0/0, and a rising curve (never produced
+    by exact FPS) makes them smaller than 1: all such inputs read as 0.  Hand-set network in which
+    any input other than 0 would show: W1 = 1 everywhere, b1 = 1/2, W2 = identity, W3 = 1/128,
+    b3[j] = j/64  ->  with all inputs 0: h1 = h2 = 1/2, out[j] = 128 * (1/2) * (1/128) + j/64."""
+    parts = zeros()
+    parts[0][:] = 1.0
+    parts[1][:] = 0.5
+    parts[2][:] = np.eye(128, dtype=np.float32)
+    parts[4][:] = 1.0 / 128.0
+    parts[5][:] = np.arange(64, dtype=np.float32) / 64.0
+    w = pack(*parts)
+    want = 0.5 + np.arange(64) / 64.0
+    m = 64
+    dead = power_curve(m, 2.0, 1.0)
+    dead[m] = 0.0                        # ratios +inf
+    dead[40:m] = 0.0                     # ... and 0/0 for the inputs taken there
+    assert np.array_equal(ref.mlp_curve(dead, m, w), want)
+    rising = np.full(m + 1, 1.0, dtype=np.float32)
+    rising[m] = 2.0                      # every ratio 1/2 < 1
+    assert np.array_equal(ref.mlp_curve(rising, m, w), want)
+    # the same network on a falling curve does see its inputs (so the zeros above are the rule's doing)
+    live = power_curve(m, 2.0, 1.0)
+    assert np.all(ref.mlp_curve(live, m, w) > want + 1.0)
+    # thresholds from a dead prefix: mdc[m] * exp(.) = 0 for every boundary beyond the prefix,
+    # which the clamp raises to the smallest normal binary32 number
+    n = 640
+    prm = ref.MdpsParams(nseg=6, bias=1.2, mlp=w)
+    thr = ref.mdps_thresholds(dead, n, m, prm)
+    assert np.all(thr == np.float32(1.17549435e-38))
