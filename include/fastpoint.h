@@ -19,6 +19,9 @@
  *     results are therefore reproducible bit for bit.
  *   - Inputs must be finite with |coordinate| < 1e18.
  *   - Calls that share a workspace or a cache must not overlap in time.
+ *   - No global state: apart from the test and measurement hooks at the end of this
+ *     header nothing persists between calls, and calls with distinct workspaces may run
+ *     concurrently (other streams, other host threads).
  */
 #ifndef FASTPOINT_H_
 #define FASTPOINT_H_
@@ -37,7 +40,8 @@ enum {
     FP_ERR_SHAPE = -2,     /* B, N, n, M or k out of range / cloud too large     */
     FP_ERR_PARAM = -3,     /* radius or an MDPS parameter out of range           */
     FP_ERR_WORKSPACE = -4, /* workspace or cache missing, misaligned or too small */
-    FP_ERR_DEVICE = -5     /* a HIP runtime call failed                          */
+    FP_ERR_DEVICE = -5,    /* a HIP runtime call failed                          */
+    FP_ERR_CAPACITY = -6   /* beyond what the library's static scratch buffer holds */
 };
 
 #define FP_MAX_SEG 16
@@ -115,6 +119,26 @@ fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n,
                        const int32_t* start_idx, int32_t* out_idx, float* out_mdc,
                        fp_mdps_info* info, void* bq_cache, float bq_radius,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * fp_fps_exact for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same kernels and the same result as
+ * fp_fps_exact without a cache and without an info record, but the words the workgroups of a
+ * cloud exchange live in a device array that is part of the library (2 654 208 bytes, held by
+ * every GPU the library runs on until the process ends) instead of a caller's workspace.  The
+ * call allocates nothing, on the device or through any library; the first call on a device
+ * looks that device's copy of the array up (no allocation either), so make one call before a
+ * capture starts.  The caller still passes inputs and outputs (device memory, as above).
+ *   Limit: N <= FP_STATIC_MAX_POINTS points per cloud (what the array's exchange slots serve);
+ *   a larger N returns FP_ERR_CAPACITY and nothing is enqueued.
+ *   All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (other
+ *   streams, other threads) race and give wrong results; calls in stream order are fine, the
+ *   words are cleared by a kernel at the start of every call.
+ */
+#define FP_STATIC_MAX_POINTS 2097152
+fp_status fp_fps_exact_static(const float* xyz, int32_t B, int32_t N, int32_t n,
+                              const int32_t* start_idx, int32_t* out_idx, float* out_mdc,
+                              void* stream);
 
 /*
  * Exact farthest point sampling with pruned distance updates -- the same result as
@@ -303,15 +327,24 @@ fp_status fp_probe_fp32_rate(int32_t blocks, int32_t iterations, float* out, voi
 fp_status fp_plan(int32_t B, int32_t N, int32_t* wg_per_cloud, int32_t* threads,
                   int32_t* points_per_thread);
 
-/* Tuning hook for benchmarks: force workgroups per cloud (0 = automatic).
- * Process-wide; not meant for concurrent use. */
+/*
+ * ---- Test and measurement hooks -------------------------------------------------------
+ * The three setters below are the library's ONLY process-wide mutable state.  Every other
+ * entry point keeps its state in its arguments (workspace, cache, outputs) and is re-entrant
+ * with distinct workspaces.  The hooks exist for tests and profiling runs, take effect for
+ * calls made after they return, are not synchronised with calls in flight on other threads,
+ * and are left at their defaults by production callers.
+ */
+
+/* Force the number of workgroups per cloud (0 = automatic, the default).  Lets a test run a
+ * small cloud through the multi-workgroup exchange. */
 void fp_set_wg_per_cloud(int32_t wg_per_cloud);
 
 /* Multi-workgroup launches are cooperative by default (the runtime guarantees that all
  * workgroups are resident, which the waits between them rely on).  0 switches to a plain
  * launch, for tools that cannot trace cooperative launches: the grid never exceeds one
  * workgroup per compute unit, so it is resident on an otherwise idle device, and a wait that
- * cannot be met still ends through the wait limit.  Process-wide. */
+ * cannot be met still ends through the wait limit. */
 void fp_set_cooperative_launch(int32_t on);
 
 /* Upper limit, in microseconds, of any wait of one workgroup on another

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
-EXPORTS = ["fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_mdps_sample_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
+EXPORTS = ["fp_fps_exact_static", "fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_mdps_sample_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
            "fp_ball_query", "fp_ball_query_grid_workspace_bytes", "fp_ball_query_grid", "fp_knn_workspace_bytes", "fp_knn", "fp_knn_grid_workspace_bytes", "fp_knn_grid", "fp_excl_workspace_bytes", "fp_excl_count",
            "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_probe_fp32_rate", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
@@ -104,6 +104,8 @@ def load() -> ctypes.CDLL:
     lib.fp_bq_cache_bytes.restype = ctypes.c_size_t
     lib.fp_fps_exact.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, f32, vp, ctypes.c_size_t, vp]
     lib.fp_fps_exact.restype = i32
+    lib.fp_fps_exact_static.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.fp_fps_exact_static.restype = i32
     lib.fp_fps_pruned_workspace_bytes.argtypes = [i32, i32]
     lib.fp_fps_pruned_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_fps_exact_pruned.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -276,6 +278,22 @@ def fps_exact(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool = False,
     if want_info:
         out.append(info)
     return out[0] if len(out) == 1 else tuple(out)
+
+
+def fps_exact_static(xyz: torch.Tensor, n: int, out_idx: torch.Tensor, out_mdc: Optional[torch.Tensor] = None,
+                     start_idx: Optional[torch.Tensor] = None) -> None:
+    """fp_fps_exact_static: exact FPS into outputs the caller has allocated, the scratch memory
+    being the library's own static device array (the call allocates nothing).  out_idx [B][n]
+    int32, out_mdc [B][n] float32 or None, start_idx [B] int32 on the device or None."""
+    B, N = _xyz(xyz)
+    for t, dt in ((out_idx, torch.int32), (out_mdc, torch.float32)):
+        if t is not None and not (t.is_cuda and t.dtype == dt and t.is_contiguous() and tuple(t.shape) == (B, n)):
+            raise ValueError("outputs must be contiguous CUDA tensors [B][n]")
+    if start_idx is not None and not (start_idx.is_cuda and start_idx.dtype == torch.int32
+                                      and start_idx.is_contiguous() and start_idx.numel() == B):
+        raise ValueError("start_idx must be a contiguous CUDA int32 tensor [B]")
+    _check(load().fp_fps_exact_static(xyz.data_ptr(), B, N, n, _ptr(start_idx), out_idx.data_ptr(),
+                                      _ptr(out_mdc), _stream()), "fp_fps_exact_static")
 
 
 def fps_exact_pruned(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool = False,

@@ -21,7 +21,19 @@ struct DeviceInfo {
     bool ok = false;
     int cus = 0;
     int64_t wall_khz = 100000;
+    void* scratch = nullptr;      // this device's copy of the static scratch array (fp_fps_exact_static)
 };
+
+// exchange words between the workgroups of a cloud: what a sampler workspace holds
+constexpr int64_t kLlPkWords = (int64_t)2 * kMaxGroup * kLlSlotWords;             // all groups together
+constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandMax * kCandWords;
+constexpr size_t kScratchBytes = (size_t)((kLlPkWords + kLlCdWords) * 8);         // 2 654 208 bytes
+
+// Scratch of fp_fps_exact_static: the same exchange words, but in device memory that belongs to
+// the library's code object instead of a caller's workspace, so that the call allocates nothing.
+// Every GPU the library runs on holds its own copy at its own address until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 constexpr int kMaxDevices = 64;
 DeviceInfo g_dev[kMaxDevices];
@@ -106,8 +118,21 @@ inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 int64_t bq_blocks(int N) { return ((int64_t)N + 63) / 64; }
 int64_t bq_col_words(int n) { return align_up((int64_t)n, 8); }
 
-constexpr int64_t kLlPkWords = (int64_t)2 * kMaxGroup * kLlSlotWords;             // all groups together
-constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandMax * kCandWords;
+// The address of the current device's copy of `scratch`, looked up once per device (with that
+// device current) and kept; NULL if the runtime cannot give it.
+void* static_scratch()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (!g_dev[dev].scratch) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        if ((reinterpret_cast<uintptr_t>(ptr) & 255u) != 0) return nullptr;
+        g_dev[dev].scratch = ptr;
+    }
+    return g_dev[dev].scratch;
+}
 
 fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
                       const fp_mdps_params* prm, int32_t* out_idx, float* out_mdc, fp_mdps_info* info,
@@ -244,6 +269,18 @@ fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n, const 
 {
     return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, info, bq_cache, bq_radius,
                        workspace, workspace_bytes, stream);
+}
+
+fp_status fp_fps_exact_static(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
+                              int32_t* out_idx, float* out_mdc, void* stream)
+{
+    if (!xyz || !out_idx) return FP_ERR_NULL;
+    if (B < 1 || N < 1 || n < 1 || n > N) return FP_ERR_SHAPE;
+    if (N > FP_STATIC_MAX_POINTS) return FP_ERR_CAPACITY;
+    void* ws = static_scratch();
+    if (!ws) return FP_ERR_DEVICE;
+    return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, nullptr, nullptr, 0.0f, ws,
+                       kScratchBytes, stream);
 }
 
 size_t fp_fps_pruned_workspace_bytes(int32_t B, int32_t N)
@@ -495,6 +532,7 @@ const char* fp_status_string(fp_status s)
         case FP_ERR_PARAM: return "parameter out of range";
         case FP_ERR_WORKSPACE: return "workspace or cache missing, misaligned or too small";
         case FP_ERR_DEVICE: return "HIP runtime error";
+        case FP_ERR_CAPACITY: return "beyond the capacity of the library's static scratch buffer";
         default: return "unknown status";
     }
 }
