@@ -42,8 +42,11 @@ HBM_PEAK_GBS = 8000.0
 OPS_PER_POINT_ITERATION = 10      # 3 sub, 3 mul, 2 add, 1 min, 1 compare (FPS min-update + arg-max)
 OPS_PER_PAIR_TEST = 9             # 3 sub, 3 mul, 2 add, 1 compare (ball query, k-NN)
 KNN_K = 3                         # neighbours of the up-sampling step (Section 3.1)
-CPU_SAMPLE_N = 1536               # cpu_baseline on C4 / C5: samples of each sampler that are timed ...
-CPU_SAMPLE_M = 1024               # ... and ball-query centres
+# entries per cloud of the ball-query cache (blocks of 64 radius tests that found a point); 0 = the
+# library's default of 2 N + 16 n.  The LiDAR-like clouds have balls of several thousand points.
+BQ_CACHE_ENTRIES = {"C4": 10 * 120000}
+CPU_SAMPLE_N = 4096               # cpu_baseline on C4 / C5: samples of each sampler that are timed ...
+CPU_SAMPLE_M = 4096               # ... and ball-query centres
 EAGER = "one stream, eager launches"
 GRAPH = "four streams, step replayed as one HIP graph"
 
@@ -111,8 +114,8 @@ def make_context(torch, fp, inputs, calibration, name):
     for s, st in enumerate(wl.stages):
         stages.append({"B": B, "N": N, "n": st.n, "radius": st.radius, "k": st.k,
                        "prm": calibration.params_for(name, s),
-                       "cache": torch.empty(fp.load().fp_bq_cache_bytes(B, N, st.n), dtype=torch.uint8,
-                                            device="cuda"),
+                       "cache": torch.empty(fp.load().fp_bq_cache_bytes(
+                           B, N, st.n, BQ_CACHE_ENTRIES.get(name, 0) if s == 0 else 0), dtype=torch.uint8, device="cuda"),
                        "G": fp.plan(B, N)[0],
                        "ws": [fp.new_workspace(xyz.device, B, N), fp.new_workspace(xyz.device, B, N)]})
         N = st.n
@@ -218,19 +221,6 @@ def measure_graph(torch, fp, ctx, steps, warmup):
     return ms
 
 
-def cached_words_read(torch, ctx, s, outs):
-    """64-bit words the cache reader has to read: per centre, whole 64-word blocks up to
-    the block holding its k-th hit (the whole row when it has fewer than k hits)."""
-    sg = ctx["stages"][s]
-    N, k = sg["N"], sg["k"]
-    nwords = (N + 63) // 64
-    idx, cnt = outs
-    last = idx[:, :, k - 1].to(torch.int64) // 64 + 1
-    need = torch.where(cnt >= k, last, torch.full_like(last, nwords))
-    blocks = (need + 63) // 64
-    return int(torch.minimum(blocks * 64, torch.full_like(blocks, ((nwords + 63) // 64) * 64)).sum().item())
-
-
 def quality_and_rooflines(torch, fp, ctx, kernel_ms):
     """Sampling quality of MDPS against exact FPS and achieved fraction of the binding
     roofline of every kernel of the step (stage 0 is where the time goes)."""
@@ -270,10 +260,15 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             roof["ball_query_brute"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS,
                                         "unit": "TFLOP/s", "frac": a / ALU_PEAK_TOPS}
         if "ball_query_cached" in ms:
-            byts = cached_words_read(torch, ctx, s, mbq) * 8 + float(B) * n * k * 4
+            # algorithmic bytes: the recorded entries of the centres' rows (12 bytes each) and their
+            # offsets read, the result written
+            cstats = fp.bq_cache_stats(sg["cache"])
+            byts = 12.0 * sum(cstats["entries"]) + 8.0 * B * n + 4.0 * B * n * (k + 1)
             a = byts / (ms["ball_query_cached"] * 1e-3) / 1e9
             roof["ball_query_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                         "frac": a / HBM_PEAK_GBS, "bytes": byts}
+                                         "frac": a / HBM_PEAK_GBS, "bytes": byts,
+                                         "cache_bytes": cstats["bytes"], "cache_entries": cstats["entries"],
+                                         "cache_incomplete": cstats["incomplete"]}
         knn = time_knn(torch, fp, x, sg, midx)
         for kname in ("knn_brute", "knn_cached"):
             ms[kname] = knn[kname + "_ms"]
@@ -286,8 +281,9 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         a = float(B) * N * n * OPS_PER_PAIR_TEST / (knn["knn_brute_ms"] * 1e-3) / 1e12
         roof["knn_brute"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS, "unit": "TFLOP/s",
                              "frac": a / ALU_PEAK_TOPS}
-        # the redundancy-free search reads every bitmap row once and writes the result
-        byts = float(B) * n * ((N + 63) // 64) * 8 + 2.0 * B * N * KNN_K * 4
+        # the redundancy-free search reads the recorded entries (regrouped by point block) and the
+        # points, and writes the result
+        byts = (16.0 + 2 * 12.0) * sum(fp.bq_cache_stats(sg["cache"])["entries"]) + 12.0 * B * N + 2.0 * B * N * KNN_K * 4
         a = byts / (knn["knn_cached_ms"] * 1e-3) / 1e9
         roof["knn_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": a / HBM_PEAK_GBS, "bytes": byts,
@@ -640,15 +636,18 @@ def path_summary(wl, detail, ms_per_step, launch_mode, roof):
     """The short entry of one workload: time of the exact path (fps_exact + brute-force ball query
     [+ gather of the next stage's input]) and of the FastPoint path (mdps_sample recording the
     radius tests + ball query from the record), summed over the stages, each kernel timed alone."""
-    exact = fast = 0.0
+    exact = fast = fast_grid = 0.0
     for st in detail["stages"]:
         ms = st["kernel_ms"]
         exact += ms["fps_exact"] + ms["ball_query_brute"] + ms.get("gather", 0.0)
         fast += ms["mdps_sample+record"] + ms["ball_query_cached"]
+        # the same samples and neighbours without the record: plain MDPS, then the grid ball query
+        fast_grid += ms["mdps_sample"] + ms["ball_query_grid"]
     pts = wl.B * wl.N / 1e6
     s0 = detail["stages"][0]
     return {"ms_per_step": round(ms_per_step, 4), "launch": "graph" if launch_mode == GRAPH else "eager",
             "exact_path_ms": round(exact, 4), "fastpoint_path_ms": round(fast, 4),
+            "mdps_plus_grid_query_ms": round(fast_grid, 4),
             "exact_Mpoints_s": round(pts / (exact * 1e-3), 2), "fastpoint_Mpoints_s": round(pts / (fast * 1e-3), 2),
             "mdps_coverage_ratio_max": round(max(st["mdps_coverage_ratio_max"] for st in detail["stages"]), 4),
             "mdps_over_fps_time": round(s0["kernel_ms"]["mdps_sample"] / s0["kernel_ms"]["fps_exact"], 3),

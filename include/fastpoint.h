@@ -97,10 +97,19 @@ typedef struct fp_mdps_info {
 size_t fp_workspace_bytes(int32_t B, int32_t N);
 
 /* Bytes of the ball-query cache for B clouds of N points and n samples each.
- * The cache stores, for every sample, one bit per point: "closer than the
- * radius" -- the extra exclusion list at the ball-query radius of Section 4.2,
- * kept as bitmap rows.  Alignment: 256 bytes. */
-size_t fp_bq_cache_bytes(int32_t B, int32_t N, int32_t n);
+ * The cache stores the radius tests that found a point -- the extra exclusion list at the
+ * ball-query radius of Section 4.2 -- as entries (sample, block of 64 points, 64 test bits),
+ * only for blocks a ball reaches, first as the sampler produces them and then in sample order.
+ * entries_per_cloud is the caller's choice, <= 0 for the default of 2 N + 16 n (two lists of
+ * 16 and 12 bytes per entry: 85 MB for 10^6 points and 65 536 samples).  A ball holding h
+ * points needs at most h entries, and about h / 10 when neighbours in space are neighbours in
+ * the index order (scanner-ordered clouds); the sampler's wavefronts reserve entries 64 at a
+ * time, which can leave up to N + 128 of them unused.  A cloud whose balls reach more blocks than the
+ * cache holds is recorded incompletely and says so: readers then treat its centres like centres
+ * that were never recorded (brute force), so results do not change.  Alignment: 256 bytes.
+ * fp_bq_cache_entries: the entries per cloud that a buffer of `bytes` bytes holds (0: too small). */
+size_t fp_bq_cache_bytes(int32_t B, int32_t N, int32_t n, int64_t entries_per_cloud);
+int64_t fp_bq_cache_entries(size_t bytes, int32_t B, int32_t N, int32_t n);
 
 /*
  * Exact farthest point sampling, Algorithm 1 (Section 3.3).
@@ -110,14 +119,15 @@ size_t fp_bq_cache_bytes(int32_t B, int32_t N, int32_t n);
  *   out_mdc    [B][n] float32 or NULL: squared min-distance of each pick at pick
  *              time (the minimum distance curve of Section 4; +inf for the seed)
  *   info       [B] or NULL (only m, et_index = n and status are meaningful)
- *   bq_cache   NULL, or a buffer of fp_bq_cache_bytes(B,N,n) that receives the
- *              radius test of every (sample, point) pair as a by-product of the
- *              distance updates (Section 4.2); bq_radius is then required > 0
+ *   bq_cache   NULL, or a buffer of bq_cache_bytes bytes (fp_bq_cache_bytes) that receives
+ *              the radius tests of the (sample, point) pairs, those that found a point, as
+ *              a by-product of the distance updates (Section 4.2); bq_radius is then
+ *              required > 0
  * A seed index outside [0,N) makes that cloud's out_idx all -1 (info.status 1).
  */
 fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n,
                        const int32_t* start_idx, int32_t* out_idx, float* out_mdc,
-                       fp_mdps_info* info, void* bq_cache, float bq_radius,
+                       fp_mdps_info* info, void* bq_cache, size_t bq_cache_bytes, float bq_radius,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
@@ -168,7 +178,7 @@ fp_status fp_fps_exact_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
 fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n,
                          const int32_t* start_idx, const fp_mdps_params* prm,
                          int32_t* out_idx, fp_mdps_info* info,
-                         void* bq_cache, float bq_radius,
+                         void* bq_cache, size_t bq_cache_bytes, float bq_radius,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
@@ -195,8 +205,9 @@ fp_status fp_mdps_sample_pruned(const float* xyz, int32_t B, int32_t N, int32_t 
  *              by fp_fps_exact / fp_mdps_sample on the same xyz: centres that
  *              are the cached samples (same position q, same radius) are read
  *              from the cache with no distance evaluation (redundancy-free ball
- *              query, Section 4.2); any other centre falls back to the brute-
- *              force test inside the same kernel.  Results are identical.
+ *              query, Section 4.2); any other centre, and every centre of a cloud
+ *              whose record is incomplete, falls back to the brute-force test
+ *              inside the same kernel.  Results are identical.
  * A centre index outside [0,N) yields a row of -1 and count 0.  M = 0 is accepted (the
  * centre and output pointers may then be NULL).
  */
@@ -218,9 +229,11 @@ fp_status fp_ball_query_grid(const float* xyz, int32_t B, int32_t N, const int32
                              int32_t M, float radius, int32_t k, int32_t* out_idx, int32_t* out_cnt,
                              void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of workspace fp_knn needs when it is given a cache (0 for shapes the library
- * rejects).  Alignment: 256 bytes. */
-size_t fp_knn_workspace_bytes(int32_t B, int32_t N);
+/* Bytes of workspace fp_knn needs when it is given a cache of cache_entries entries per cloud
+ * (fp_bq_cache_entries; 0 for shapes the library rejects).  With a smaller workspace, down to
+ * cache_entries = 0, fp_knn still works: clouds whose record does not fit are searched by brute
+ * force.  Alignment: 256 bytes. */
+size_t fp_knn_workspace_bytes(int32_t B, int32_t N, int64_t cache_entries);
 
 /*
  * k nearest samples of every point -- the k-NN of the up-sampling (feature propagation)
@@ -234,8 +247,9 @@ size_t fp_knn_workspace_bytes(int32_t B, int32_t N);
  *              sample_idx (redundancy-free k-NN, Section 4.2): the search space of a point
  *              is the samples whose recorded ball contains it, which are its k nearest
  *              whenever there are at least k of them; points with fewer, and clouds whose
- *              sample list differs from the cached one, are searched by brute force in a
- *              second pass.  Results are identical to the brute-force search.
+ *              sample list differs from the cached one or whose record is incomplete, are
+ *              searched by brute force in a second pass.  Results are identical to the
+ *              brute-force search.
  *   out_deferred [B] int32 or NULL: with a cache, the number of points per cloud that took
  *              the brute-force pass
  *   workspace  required with a cache (fp_knn_workspace_bytes), else ignored

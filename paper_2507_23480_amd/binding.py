@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
-EXPORTS = ["fp_fps_exact_static", "fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_mdps_sample_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
+EXPORTS = ["fp_bq_cache_entries", "fp_fps_exact_static", "fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_mdps_sample_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
            "fp_ball_query", "fp_ball_query_grid_workspace_bytes", "fp_ball_query_grid", "fp_knn_workspace_bytes", "fp_knn", "fp_knn_grid_workspace_bytes", "fp_knn_grid", "fp_excl_workspace_bytes", "fp_excl_count",
            "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_probe_fp32_rate", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
@@ -100,9 +100,11 @@ def load() -> ctypes.CDLL:
     vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
     lib.fp_workspace_bytes.argtypes = [i32, i32]
     lib.fp_workspace_bytes.restype = ctypes.c_size_t
-    lib.fp_bq_cache_bytes.argtypes = [i32, i32, i32]
+    lib.fp_bq_cache_bytes.argtypes = [i32, i32, i32, ctypes.c_int64]
     lib.fp_bq_cache_bytes.restype = ctypes.c_size_t
-    lib.fp_fps_exact.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, f32, vp, ctypes.c_size_t, vp]
+    lib.fp_bq_cache_entries.argtypes = [ctypes.c_size_t, i32, i32, i32]
+    lib.fp_bq_cache_entries.restype = ctypes.c_int64
+    lib.fp_fps_exact.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, f32, vp, ctypes.c_size_t, vp]
     lib.fp_fps_exact.restype = i32
     lib.fp_fps_exact_static.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp]
     lib.fp_fps_exact_static.restype = i32
@@ -112,8 +114,8 @@ def load() -> ctypes.CDLL:
     lib.fp_fps_exact_pruned.restype = i32
     lib.fp_mdps_sample_pruned.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.fp_mdps_sample_pruned.restype = i32
-    lib.fp_mdps_sample.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(FpMdpsParams), vp, vp, vp, f32,
-                                   vp, ctypes.c_size_t, vp]
+    lib.fp_mdps_sample.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(FpMdpsParams), vp, vp, vp,
+                                   ctypes.c_size_t, f32, vp, ctypes.c_size_t, vp]
     lib.fp_mdps_sample.restype = i32
     lib.fp_ball_query.argtypes = [vp, i32, i32, vp, i32, f32, i32, vp, vp, vp, vp]
     lib.fp_ball_query.restype = i32
@@ -121,7 +123,7 @@ def load() -> ctypes.CDLL:
     lib.fp_ball_query_grid_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_ball_query_grid.argtypes = [vp, i32, i32, vp, i32, f32, i32, vp, vp, vp, ctypes.c_size_t, vp]
     lib.fp_ball_query_grid.restype = i32
-    lib.fp_knn_workspace_bytes.argtypes = [i32, i32]
+    lib.fp_knn_workspace_bytes.argtypes = [i32, i32, ctypes.c_int64]
     lib.fp_knn_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_knn.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.fp_knn.restype = i32
@@ -236,12 +238,32 @@ def new_workspace(device: torch.device, B: int, N: int) -> torch.Tensor:
     return torch.empty(need, dtype=torch.uint8, device=device)
 
 
-def new_bq_cache(xyz: torch.Tensor, n: int) -> torch.Tensor:
+def new_bq_cache(xyz: torch.Tensor, n: int, entries_per_cloud: int = 0) -> torch.Tensor:
+    """A ball-query cache for n samples of xyz; entries_per_cloud = 0 takes the default capacity
+    (2 N + 16 n non-empty blocks of 64 radius tests per cloud)."""
     B, N = _xyz(xyz)
-    need = int(load().fp_bq_cache_bytes(B, N, n))
+    need = int(load().fp_bq_cache_bytes(B, N, n, int(entries_per_cloud)))
     if need == 0:
         raise ValueError("bad shape for a ball-query cache")
     return torch.empty(need, dtype=torch.uint8, device=xyz.device)
+
+
+def bq_cache_stats(cache: torch.Tensor) -> dict:
+    """What a recorded ball-query cache holds (reads its header and counters back to the host):
+    entries per cloud it has room for, chunks of 64 entries the sampler's wavefronts took, whether a
+    cloud's record is incomplete, entries per cloud after grouping.  For sizing a cache."""
+    import struct
+    head = cache[:256].cpu().numpy().tobytes()
+    magic, B, N, n, blocks, valid, r2_bits, _ = struct.unpack_from("<Iiiiiiii", head, 0)
+    cap, idx_off, cur_off, ovf_off, rowcnt_off, fill_off, rowoff_off, raw_off, rows_off, nbytes = \
+        struct.unpack_from("<10q", head, 32)
+    if magic != 0x46504232 or valid != 1:
+        raise ValueError("not a recorded ball-query cache")
+    u32 = lambda off, count: cache[off:off + 4 * count].cpu().numpy().view("uint32")
+    rowoff = u32(rowoff_off, B * (n + 1)).reshape(B, n + 1)
+    return {"B": B, "N": N, "n": n, "entries_capacity": int(cap), "chunks_taken": u32(cur_off, B).tolist(),
+            "incomplete": [bool(v) for v in u32(ovf_off, B)], "entries": [int(v) for v in rowoff[:, n]],
+            "bytes": int(nbytes)}
 
 
 def _start(start_idx, B, device) -> Optional[torch.Tensor]:
@@ -270,7 +292,8 @@ def fps_exact(xyz: torch.Tensor, n: int, start_idx=None, want_mdc: bool = False,
     if ws is None:
         ws = workspace(xyz.device, B, N)
     _check(load().fp_fps_exact(xyz.data_ptr(), B, N, n, _ptr(st), idx.data_ptr(), _ptr(mdc), _ptr(info),
-                               _ptr(bq_cache), float(bq_radius), ws.data_ptr(), ws.numel(), _stream()),
+                               _ptr(bq_cache), 0 if bq_cache is None else bq_cache.numel(), float(bq_radius),
+                               ws.data_ptr(), ws.numel(), _stream()),
            "fp_fps_exact")
     out = [idx]
     if want_mdc:
@@ -354,8 +377,8 @@ def mdps_sample(xyz: torch.Tensor, n: int, prm: MdpsParams, start_idx=None, want
         ws = workspace(xyz.device, B, N)
     c = prm.to_c()
     _check(load().fp_mdps_sample(xyz.data_ptr(), B, N, n, _ptr(st), ctypes.byref(c), idx.data_ptr(),
-                                 _ptr(info), _ptr(bq_cache), float(bq_radius), ws.data_ptr(), ws.numel(),
-                                 _stream()), "fp_mdps_sample")
+                                 _ptr(info), _ptr(bq_cache), 0 if bq_cache is None else bq_cache.numel(),
+                                 float(bq_radius), ws.data_ptr(), ws.numel(), _stream()), "fp_mdps_sample")
     return (idx, info) if want_info else idx
 
 
@@ -414,7 +437,8 @@ def knn(xyz: torch.Tensor, sample_idx: torch.Tensor, k: int, bq_cache: Optional[
     d2 = torch.empty((B, N, k), dtype=torch.float32, device=xyz.device)
     ws, ws_bytes, deferred = None, 0, None
     if bq_cache is not None:
-        ws_bytes = int(load().fp_knn_workspace_bytes(B, N))
+        entries = int(load().fp_bq_cache_entries(bq_cache.numel(), B, N, n))
+        ws_bytes = int(load().fp_knn_workspace_bytes(B, N, entries))
         if ws_bytes == 0:
             raise ValueError("shape (B=%d, N=%d) not supported" % (B, N))
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device=xyz.device)

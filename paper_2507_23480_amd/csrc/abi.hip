@@ -116,7 +116,6 @@ bool make_plan(int B, int N, int cus, Plan* plan)
 inline int64_t align_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 int64_t bq_blocks(int N) { return ((int64_t)N + 63) / 64; }
-int64_t bq_col_words(int n) { return align_up((int64_t)n, 8); }
 
 // The address of the current device's copy of `scratch`, looked up once per device (with that
 // device current) and kept; NULL if the runtime cannot give it.
@@ -136,8 +135,8 @@ void* static_scratch()
 
 fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
                       const fp_mdps_params* prm, int32_t* out_idx, float* out_mdc, fp_mdps_info* info,
-                      void* bq_cache, float bq_radius, void* workspace, size_t workspace_bytes,
-                      void* stream_v, bool pruned = false)
+                      void* bq_cache, size_t bq_cache_bytes, float bq_radius, void* workspace,
+                      size_t workspace_bytes, void* stream_v, bool pruned = false)
 {
     if (!xyz || !out_idx) return FP_ERR_NULL;
     if (B < 1 || N < 1 || n < 1 || n > N) return FP_ERR_SHAPE;
@@ -210,15 +209,26 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         a.sorted = spatial_sorted(B, N, sort_ws);
     }
     const bool bq = bq_cache != nullptr;
+    uint64_t* bq_zero = nullptr;
+    int64_t bq_zero_words = 0;
     if (bq) {
-        // layout: a 256-byte header (written by the sampler kernel), the copy of the sample
-        // indices, the radius-test words
+        // layout (kernels.h): header (written by the sampler kernel), copy of the sample indices,
+        // per-cloud cursors and per-sample counts (zeroed here), row offsets, the two entry lists
+        const int64_t cap = fp_bq_cache_entries(bq_cache_bytes, B, N, n);
+        if (cap < kBqChunk) return FP_ERR_WORKSPACE;
+        const BqHeader lay = bq_layout(B, N, n, bq_radius * bq_radius, cap);
         unsigned char* base = reinterpret_cast<unsigned char*>(bq_cache);
-        a.bq_idx = reinterpret_cast<int32_t*>(base + 256);
-        a.bq_bits = reinterpret_cast<uint64_t*>(base + 256 + align_up((int64_t)B * n * 4, 256));
+        a.bq_base = base;
+        a.bq_idx = reinterpret_cast<int32_t*>(base + lay.idx_offset);
+        a.bq_cursor = reinterpret_cast<uint32_t*>(base + lay.cursor_offset);
+        a.bq_ovf = reinterpret_cast<uint32_t*>(base + lay.ovf_offset);
+        a.bq_fill = reinterpret_cast<uint32_t*>(base + lay.fill_offset);
+        a.bq_raw = reinterpret_cast<BqRaw*>(base + lay.raw_offset);
+        a.bq_cap = lay.cap;
         a.bq_r2 = bq_radius * bq_radius;
         a.bq_blocks = (int32_t)bq_blocks(N);
-        a.bq_col_words = bq_col_words(n);
+        bq_zero = reinterpret_cast<uint64_t*>(base + lay.cursor_offset);
+        bq_zero_words = (lay.rowoff_offset - lay.cursor_offset) / 8;      // cursors, flags, counts, chunk fills
     }
 
     // MDPS threshold rounds with two candidates per control-wave lane: measured faster except
@@ -229,18 +239,18 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
     const unsigned grid = (unsigned)(plan.groups * plan.G);
     void* kargs[] = {&a};
     hipError_t err;
+    // words that have to start at zero when the workgroups of a cloud wait on each other: the exchange
+    // words (stamps start at 1 in every launch) and the chunk counters of a ball-query cache.  (A
+    // cloud held by one workgroup has its counters zeroed by that workgroup.)
     if (plan.G > 1) {
-        // workgroups of a cloud wait on each other: stamps start from zeroed words and the
-        // whole grid has to be resident
-        if (launch_zero_words(a.ll_pk, kLlPkWords + kLlCdWords, stream) != hipSuccess)
+        if (launch_zero_words(a.ll_pk, kLlPkWords + kLlCdWords, bq_zero, bq_zero_words, stream) != hipSuccess)
             return FP_ERR_DEVICE;
-        if (g_cooperative.load())
-            err = hipLaunchCooperativeKernel(fn, dim3(grid), dim3((unsigned)(plan.T + kCtrlThreads)), kargs, 0, stream);
-        else
-            err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)(plan.T + kCtrlThreads)), kargs, 0, stream);
-    } else {
-        err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)(plan.T + kCtrlThreads)), kargs, 0, stream);
     }
+    if (plan.G > 1 && g_cooperative.load())    // the whole grid has to be resident
+        err = hipLaunchCooperativeKernel(fn, dim3(grid), dim3((unsigned)(plan.T + kCtrlThreads)), kargs, 0, stream);
+    else
+        err = hipLaunchKernel(fn, dim3(grid), dim3((unsigned)(plan.T + kCtrlThreads)), kargs, 0, stream);
+    if (err == hipSuccess && bq) err = launch_bq_group_by_sample(bq_cache, B, N, n, a.bq_cap, stream);
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }
 
@@ -257,18 +267,35 @@ size_t fp_workspace_bytes(int32_t B, int32_t N)
     return (size_t)((kLlPkWords + kLlCdWords) * 8);
 }
 
-size_t fp_bq_cache_bytes(int32_t B, int32_t N, int32_t n)
+size_t fp_bq_cache_bytes(int32_t B, int32_t N, int32_t n, int64_t entries_per_cloud)
 {
-    if (B < 1 || N < 1 || n < 1 || n > N) return 0;
-    return (size_t)(256 + align_up((int64_t)B * n * 4, 256) + (int64_t)B * bq_blocks(N) * bq_col_words(n) * 8);
+    if (B < 1 || N < 1 || n < 1 || n > N || B > 65535 || (int64_t)B * n > ((int64_t)1 << 31)) return 0;
+    int64_t cap = entries_per_cloud > 0 ? entries_per_cloud : bq_capacity(N, n);
+    cap = (cap + kBqChunk - 1) / kBqChunk * kBqChunk;   // whole chunks
+    if (cap > ((int64_t)1 << 31)) return 0;             // entries are addressed with 32 bits
+    return (size_t)bq_layout(B, N, n, 1.0f, cap).bytes;
+}
+
+int64_t fp_bq_cache_entries(size_t bytes, int32_t B, int32_t N, int32_t n)
+{
+    if (B < 1 || N < 1 || n < 1 || n > N || B > 65535 || (int64_t)B * n > ((int64_t)1 << 31)) return 0;
+    const int64_t fixed = bq_layout(B, N, n, 1.0f, 0).bytes;
+    if ((int64_t)bytes <= fixed) return 0;
+    // an upper estimate (every part is rounded up to 256 bytes), then down to what fits
+    int64_t cap = ((int64_t)bytes - fixed) / ((int64_t)B * (int64_t)(sizeof(BqRaw) + sizeof(BqEntry))) + kBqChunk;
+    if (cap > ((int64_t)1 << 31)) cap = (int64_t)1 << 31;
+    cap = cap / kBqChunk * kBqChunk;
+    while (cap > 0 && bq_layout(B, N, n, 1.0f, cap).bytes > (int64_t)bytes) cap -= kBqChunk;
+    return cap;
 }
 
 fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
                        int32_t* out_idx, float* out_mdc, fp_mdps_info* info, void* bq_cache,
-                       float bq_radius, void* workspace, size_t workspace_bytes, void* stream)
+                       size_t bq_cache_bytes, float bq_radius, void* workspace, size_t workspace_bytes,
+                       void* stream)
 {
-    return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, info, bq_cache, bq_radius,
-                       workspace, workspace_bytes, stream);
+    return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, info, bq_cache, bq_cache_bytes,
+                       bq_radius, workspace, workspace_bytes, stream);
 }
 
 fp_status fp_fps_exact_static(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
@@ -279,7 +306,7 @@ fp_status fp_fps_exact_static(const float* xyz, int32_t B, int32_t N, int32_t n,
     if (N > FP_STATIC_MAX_POINTS) return FP_ERR_CAPACITY;
     void* ws = static_scratch();
     if (!ws) return FP_ERR_DEVICE;
-    return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, nullptr, nullptr, 0.0f, ws,
+    return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, nullptr, nullptr, 0, 0.0f, ws,
                        kScratchBytes, stream);
 }
 
@@ -294,7 +321,7 @@ fp_status fp_fps_exact_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
                               size_t workspace_bytes, void* stream)
 {
     if (B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return FP_ERR_SHAPE;
-    return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, info, nullptr, 0.0f, workspace,
+    return run_sampler(xyz, B, N, n, start_idx, nullptr, out_idx, out_mdc, info, nullptr, 0, 0.0f, workspace,
                        workspace_bytes, stream, true);
 }
 
@@ -304,18 +331,18 @@ fp_status fp_mdps_sample_pruned(const float* xyz, int32_t B, int32_t N, int32_t 
 {
     if (!prm) return FP_ERR_NULL;
     if (B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return FP_ERR_SHAPE;
-    return run_sampler(xyz, B, N, n, start_idx, prm, out_idx, nullptr, info, nullptr, 0.0f, workspace,
+    return run_sampler(xyz, B, N, n, start_idx, prm, out_idx, nullptr, info, nullptr, 0, 0.0f, workspace,
                        workspace_bytes, stream, true);
 }
 
 fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
                          const fp_mdps_params* prm, int32_t* out_idx, fp_mdps_info* info,
-                         void* bq_cache, float bq_radius, void* workspace, size_t workspace_bytes,
-                         void* stream)
+                         void* bq_cache, size_t bq_cache_bytes, float bq_radius, void* workspace,
+                         size_t workspace_bytes, void* stream)
 {
     if (!prm) return FP_ERR_NULL;
-    return run_sampler(xyz, B, N, n, start_idx, prm, out_idx, nullptr, info, bq_cache, bq_radius,
-                       workspace, workspace_bytes, stream);
+    return run_sampler(xyz, B, N, n, start_idx, prm, out_idx, nullptr, info, bq_cache, bq_cache_bytes,
+                       bq_radius, workspace, workspace_bytes, stream);
 }
 
 fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N, const int32_t* center_idx, int32_t M,
@@ -358,11 +385,28 @@ fp_status fp_ball_query_grid(const float* xyz, int32_t B, int32_t N, const int32
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }
 
-size_t fp_knn_workspace_bytes(int32_t B, int32_t N)
+// parts of a k-NN workspace (byte offsets): per cloud a flag, a counter and a list of up to N
+// deferred points; with a cache also the entries of the cache regrouped by point block
+struct KnnLayout {
+    int64_t flags, count, list, blk_cnt, blk_off, blk_rows, bytes;
+};
+static KnnLayout knn_layout(int32_t B, int32_t N, int64_t cache_entries)
 {
-    if (B < 1 || N < 1 || B > 65535) return 0;
-    // per cloud: a flag, a counter and a list of up to N deferred points
-    return (size_t)(2 * align_up((int64_t)B * 4, 256) + align_up((int64_t)B * N * 4, 256));
+    KnnLayout l;
+    l.flags = 0;
+    l.count = align_up((int64_t)B * 4, 256);
+    l.list = l.count + align_up((int64_t)B * 4, 256);
+    l.blk_cnt = l.list + align_up((int64_t)B * N * 4, 256);
+    l.blk_off = l.blk_cnt + align_up((int64_t)B * bq_blocks(N) * 4, 256);
+    l.blk_rows = l.blk_off + align_up((int64_t)B * (bq_blocks(N) + 1) * 4, 256);
+    l.bytes = l.blk_rows + align_up((int64_t)B * cache_entries * (int64_t)sizeof(BqEntry), 256);
+    return l;
+}
+
+size_t fp_knn_workspace_bytes(int32_t B, int32_t N, int64_t cache_entries)
+{
+    if (B < 1 || N < 1 || cache_entries < 0 || cache_entries > ((int64_t)1 << 31) || B > 65535) return 0;
+    return (size_t)knn_layout(B, N, cache_entries).bytes;
 }
 
 fp_status fp_knn(const float* xyz, int32_t B, int32_t N, const int32_t* sample_idx, int32_t n, int32_t k,
@@ -370,21 +414,32 @@ fp_status fp_knn(const float* xyz, int32_t B, int32_t N, const int32_t* sample_i
                  void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!xyz || !sample_idx || !out_pos || !out_d2) return FP_ERR_NULL;
-    if (B < 1 || N < 1 || n < 1 || k < 1 || k > FP_KNN_MAX_K || k > n || B > 65535) return FP_ERR_SHAPE;
+    if (B < 1 || N < 1 || n < 1 || n > N || k < 1 || k > FP_KNN_MAX_K || k > n || B > 65535) return FP_ERR_SHAPE;
     if ((int64_t)B * N > (int64_t)1 << 40) return FP_ERR_SHAPE;
-    int32_t *flags = nullptr, *count = nullptr, *list = nullptr;
+    int32_t *flags = nullptr, *count = nullptr, *list = nullptr, *blk_cnt = nullptr;
+    uint32_t* blk_off = nullptr;
+    BqEntry* blk_rows = nullptr;
+    int64_t blk_rows_cap = 0;
     if (bq_cache) {
         if ((reinterpret_cast<uintptr_t>(bq_cache) & 255u) != 0) return FP_ERR_WORKSPACE;
-        if (!workspace || workspace_bytes < fp_knn_workspace_bytes(B, N) ||
+        if (!workspace || workspace_bytes < fp_knn_workspace_bytes(B, N, 0) ||
             (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
             return FP_ERR_WORKSPACE;
+        const KnnLayout l = knn_layout(B, N, 0);
+        // whatever lies behind the fixed parts holds the cache's entries regrouped by point block; a
+        // cloud with more entries than fit there is searched by brute force
+        blk_rows_cap = ((int64_t)workspace_bytes - l.blk_rows) / ((int64_t)B * (int64_t)sizeof(BqEntry));
         unsigned char* base = reinterpret_cast<unsigned char*>(workspace);
-        flags = reinterpret_cast<int32_t*>(base);
-        count = reinterpret_cast<int32_t*>(base + align_up((int64_t)B * 4, 256));
-        list = reinterpret_cast<int32_t*>(base + 2 * align_up((int64_t)B * 4, 256));
+        flags = reinterpret_cast<int32_t*>(base + l.flags);
+        count = reinterpret_cast<int32_t*>(base + l.count);
+        list = reinterpret_cast<int32_t*>(base + l.list);
+        blk_cnt = reinterpret_cast<int32_t*>(base + l.blk_cnt);
+        blk_off = reinterpret_cast<uint32_t*>(base + l.blk_off);
+        blk_rows = reinterpret_cast<BqEntry*>(base + l.blk_rows);
     }
     hipError_t err = launch_knn(xyz, B, N, sample_idx, n, k, out_pos, out_d2, bq_cache, flags, count, list,
-                                bq_cache ? out_deferred : nullptr, reinterpret_cast<hipStream_t>(stream));
+                                blk_cnt, blk_off, blk_rows, blk_rows_cap, bq_cache ? out_deferred : nullptr,
+                                reinterpret_cast<hipStream_t>(stream));
     return err == hipSuccess ? FP_OK : FP_ERR_DEVICE;
 }
 
@@ -444,7 +499,7 @@ size_t fp_knn_grid_workspace_bytes(int32_t B, int32_t N, int32_t n)
 {
     if (B < 1 || N < 1 || n < 1 || B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return 0;
     // the deferred-point bookkeeping of fp_knn, the samples' coordinates, the grid over them
-    return fp_knn_workspace_bytes(B, N) + (size_t)align_up((int64_t)B * n * 12, 256) +
+    return fp_knn_workspace_bytes(B, N, 0) + (size_t)align_up((int64_t)B * n * 12, 256) +
            (size_t)spatial_sort_bytes(B, n);
 }
 
@@ -462,8 +517,8 @@ fp_status fp_knn_grid(const float* xyz, int32_t B, int32_t N, const int32_t* sam
     unsigned char* base = reinterpret_cast<unsigned char*>(workspace);
     int32_t* count = reinterpret_cast<int32_t*>(base + align_up((int64_t)B * 4, 256));
     int32_t* list = reinterpret_cast<int32_t*>(base + 2 * align_up((int64_t)B * 4, 256));
-    float* sample_xyz = reinterpret_cast<float*>(base + fp_knn_workspace_bytes(B, N));
-    void* grid_ws = base + fp_knn_workspace_bytes(B, N) + align_up((int64_t)B * n * 12, 256);
+    float* sample_xyz = reinterpret_cast<float*>(base + fp_knn_workspace_bytes(B, N, 0));
+    void* grid_ws = base + fp_knn_workspace_bytes(B, N, 0) + align_up((int64_t)B * n * 12, 256);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (launch_gather(xyz, B, N, sample_idx, n, sample_xyz, st) != hipSuccess) return FP_ERR_DEVICE;
     if (launch_knn_grid(xyz, B, N, sample_xyz, n, k, radius * radius, out_pos, out_d2, count, list, grid_ws, st) !=

@@ -7,10 +7,11 @@
 //     scalar loads, so each lane scans "its" ball sequentially and the first-k rule and the
 //     early exit fall out of the loop order; the index range is split over the waves of a
 //     workgroup (more waves in flight) and the per-range hit lists are merged in LDS;
-//   * cache reader, one centre per lane: reads the words the sampler recorded for that
+//   * cache reader, one wave per centre: reads the entries the sampler recorded for that
 //     sample (Section 4.2: the radius test was already done while the sample was folded
-//     into the distance array) and keeps the first k set bits; a centre without usable
-//     words is tested against all points by the same wave.
+//     into the distance array), one per point block its ball reaches, and keeps the first k
+//     set bits in block order; a centre the record does not cover is tested against all
+//     points by the same wave.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -151,90 +152,285 @@ __global__ __launch_bounds__(S * 64) void bq_brute_kernel(const float* __restric
     merge_ranges<S>(hits, counts, kp, k, b, q0, M, w, lane, out_idx, out_cnt);
 }
 
-constexpr int kCachedUnroll = 8;     // cache words requested together by the cache reader
-
-// Cache reader.  A workgroup of S waves owns 64 consecutive centres of a cloud, one per lane;
-// wave w takes the w-th of S equal ranges of point blocks.  Word [block][q] of the cache holds
-// the radius tests of sample q against the 64 points of that block, and the words of consecutive
-// samples are contiguous: every load of a wave brings one block for all its 64 centres.  A lane
-// walks the set bits of its words in index order and keeps the first k of its range; the ranges
-// are merged as in the brute-force kernel.  Centres without a usable column (not the cached
-// sample of that position, or another radius) are tested against the points of the range instead.
-//   LDS: hits [S][64][k+1] int32, counts [S][64] int32  (dynamic)
-template <int S>
-__global__ __launch_bounds__(S * 64) void bq_cached_kernel(const float* __restrict__ xyz, int B, int N,
-                                                           const int32_t* __restrict__ center_idx, int M,
-                                                           float r2, int k, int32_t* __restrict__ out_idx,
-                                                           int32_t* __restrict__ out_cnt,
-                                                           const unsigned char* __restrict__ cache)
+// ------------------------------------------------------------------ the recorded radius tests
+// Grouping of a cache's entries (kernels.h) by a key -- the sample (rows the ball query reads) or
+// the point block (rows the k-NN search reads): count per key, exclusive scan, scatter.  The
+// entries of a row end up in no particular order; readers order them.
+// Places of cloud b's list that may hold an entry: the chunks handed out -- none when the record
+// is incomplete or would not fit the rows it is grouped into.  Place e holds an entry when
+// bq_place_used() says so.
+__device__ __forceinline__ int64_t bq_places(const BqHeader* h, const unsigned char* cache, int b, int64_t rows_cap)
 {
-    extern __shared__ int32_t lds[];
-    const int kp = k + 1;                                   // padded row: conflict-free columns
-    int32_t* hits = lds;                                    // [S][64][kp]
-    int32_t* counts = lds + S * 64 * kp;                    // [S][64]
+    if (reinterpret_cast<const uint32_t*>(cache + h->ovf_offset)[b] != 0) return 0;
+    const int64_t chunks = (int64_t) reinterpret_cast<const uint32_t*>(cache + h->cursor_offset)[b];
+    const int64_t most = h->cap / kBqChunk;
+    const int64_t places = (chunks < most ? chunks : most) * kBqChunk;
+    return places <= rows_cap ? places : 0;
+}
+__device__ __forceinline__ bool bq_place_used(const BqHeader* h, const unsigned char* cache, int b, int64_t e)
+{
+    const uint32_t* fill = reinterpret_cast<const uint32_t*>(cache + h->fill_offset) + (int64_t)b * (h->cap / kBqChunk);
+    return (uint32_t)(e % kBqChunk) < fill[e / kBqChunk];
+}
+
+// The three steps for the threads `tid` of `nthreads` that share cloud b (a whole grid row, or one
+// workgroup).
+template <bool BY_BLOCK>
+__device__ __forceinline__ void group_count(const BqHeader* h, const unsigned char* cache, int b, int32_t* cnt,
+                                            int keys, int64_t rows_cap, int64_t tid, int64_t nthreads)
+{
+    const int64_t E = bq_places(h, cache, b, rows_cap);
+    const BqRaw* __restrict__ raw = reinterpret_cast<const BqRaw*>(cache + h->raw_offset) + (int64_t)b * h->cap;
+    for (int64_t e = tid; e < E; e += nthreads) {
+        if (!bq_place_used(h, cache, b, e)) continue;
+        const uint32_t key = BY_BLOCK ? raw[e].blk : raw[e].q;
+        if (key < (uint32_t)keys) atomicAdd(cnt + (int64_t)b * keys + key, 1);
+    }
+}
+
+template <bool BY_BLOCK>
+__device__ __forceinline__ void group_scatter(const BqHeader* h, const unsigned char* cache, int b, int32_t* cnt,
+                                              const uint32_t* off, int keys, BqEntry* rows, int64_t rows_cap,
+                                              int64_t tid, int64_t nthreads)
+{
+    const int64_t E = bq_places(h, cache, b, rows_cap);
+    const BqRaw* __restrict__ raw = reinterpret_cast<const BqRaw*>(cache + h->raw_offset) + (int64_t)b * h->cap;
+    BqEntry* __restrict__ out = rows + (int64_t)b * rows_cap;
+    for (int64_t e = tid; e < E; e += nthreads) {
+        if (!bq_place_used(h, cache, b, e)) continue;
+        const BqRaw r = raw[e];
+        const uint32_t key = BY_BLOCK ? r.blk : r.q;
+        if (key >= (uint32_t)keys) continue;
+        const uint32_t first = __hip_atomic_load(off + (int64_t)b * ((int64_t)keys + 1) + key, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t at = first + (uint32_t)atomicAdd(cnt + (int64_t)b * keys + key, 1);
+        BqEntry g;
+        g.other = BY_BLOCK ? r.q : r.blk;
+        g.lo = (uint32_t)r.mask;
+        g.hi = (uint32_t)(r.mask >> 32);
+        out[at] = g;
+    }
+}
+
+// off[b][0 .. keys] = exclusive prefix sums of cnt[b][0 .. keys); cnt is set back to zero (the
+// scatter pass counts up again).  By the 1024 threads of one workgroup; a thread owns a run of keys.
+__device__ __forceinline__ void group_scan(int b, int32_t* cnt, uint32_t* off, int keys, uint32_t* part)
+{
+    const int tid = (int)threadIdx.x;
+    int32_t* c = cnt + (int64_t)b * keys;
+    uint32_t* o = off + (int64_t)b * ((int64_t)keys + 1);
+    const int per = (keys + 1023) / 1024;
+    const int k0 = (int64_t)tid * per < keys ? tid * per : keys;
+    const int k1 = (int64_t)k0 + per < keys ? k0 + per : keys;
+    uint32_t sum = 0;
+    for (int t = k0; t < k1; ++t)
+        sum += (uint32_t)__hip_atomic_load(c + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    part[tid] = sum;
+    __syncthreads();
+    for (int sft = 1; sft < 1024; sft <<= 1) {
+        const uint32_t v = tid >= sft ? part[tid - sft] : 0u;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    uint32_t run = part[tid] - sum;
+    for (int t = k0; t < k1; ++t) {
+        __hip_atomic_store(o + t, run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        run += (uint32_t)__hip_atomic_load(c + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(c + t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (tid == 1023) o[keys] = part[1023];
+}
+
+template <bool BY_BLOCK>
+__global__ __launch_bounds__(256) void bq_group_count_kernel(const unsigned char* __restrict__ cache,
+                                                             int32_t* __restrict__ cnt, int keys, int64_t rows_cap)
+{
+    const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
+    if (h->magic != kBqMagic || (int)blockIdx.y >= h->B) return;
+    group_count<BY_BLOCK>(h, cache, (int)blockIdx.y, cnt, keys, rows_cap, (int64_t)blockIdx.x * 256 + threadIdx.x,
+                          (int64_t)gridDim.x * 256);
+}
+
+__global__ __launch_bounds__(1024) void bq_group_scan_kernel(int32_t* __restrict__ cnt, uint32_t* __restrict__ off,
+                                                             int keys)
+{
+    __shared__ uint32_t part[1024];
+    group_scan((int)blockIdx.x, cnt, off, keys, part);
+}
+
+template <bool BY_BLOCK>
+__global__ __launch_bounds__(256) void bq_group_scatter_kernel(const unsigned char* __restrict__ cache,
+                                                               int32_t* __restrict__ cnt,
+                                                               const uint32_t* __restrict__ off, int keys,
+                                                               BqEntry* __restrict__ rows, int64_t rows_cap)
+{
+    const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
+    if (h->magic != kBqMagic || (int)blockIdx.y >= h->B) return;
+    group_scatter<BY_BLOCK>(h, cache, (int)blockIdx.y, cnt, off, keys, rows, rows_cap,
+                            (int64_t)blockIdx.x * 256 + threadIdx.x, (int64_t)gridDim.x * 256);
+}
+
+// Small clouds: the three steps by one workgroup per cloud in one launch (the counts are zeroed
+// here as well).  Counts and offsets go through device-scope atomics, so that what one thread
+// wrote before a barrier is what another reads after it.
+template <bool BY_BLOCK>
+__global__ __launch_bounds__(1024) void bq_group_small_kernel(const unsigned char* __restrict__ cache,
+                                                              int32_t* __restrict__ cnt, uint32_t* __restrict__ off,
+                                                              int keys, BqEntry* __restrict__ rows, int64_t rows_cap)
+{
+    __shared__ uint32_t part[1024];
+    const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
+    const int b = (int)blockIdx.x;
+    const bool ok = h->magic == kBqMagic && b < h->B;
+    for (int t = (int)threadIdx.x; t < keys; t += 1024)
+        __hip_atomic_store(cnt + (int64_t)b * keys + t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (ok) group_count<BY_BLOCK>(h, cache, b, cnt, keys, rows_cap, threadIdx.x, 1024);
+    __syncthreads();
+    group_scan(b, cnt, off, keys, part);
+    __syncthreads();
+    if (ok) group_scatter<BY_BLOCK>(h, cache, b, cnt, off, keys, rows, rows_cap, threadIdx.x, 1024);
+}
+
+__global__ void zero_ints_kernel(int32_t* p, int64_t n)
+{
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += (int64_t)gridDim.x * blockDim.x)
+        p[t] = 0;
+}
+
+__device__ __forceinline__ uint32_t rdlane_u32(uint32_t v, int l)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, l);
+}
+
+// Ball query from the recorded radius tests (Section 4.2): no distance is evaluated.  One wave per
+// centre.  The centre's row holds one entry per point block its ball reaches; the entries are put
+// in block order (a rank by counting when there are at most 64, else the smallest block not yet
+// taken is looked for k times at most), their set bits are the hits in index order, and the first k
+// are written.  A centre the record does not cover (not the recorded sample of that position,
+// another radius, a cloud whose list overflowed) is tested against all points by its wave, 64
+// points per step in index order.
+__global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict__ xyz, int B, int N,
+                                                        const int32_t* __restrict__ center_idx, int M,
+                                                        float r2, int k, int32_t* __restrict__ out_idx,
+                                                        int32_t* __restrict__ out_cnt,
+                                                        const unsigned char* __restrict__ cache)
+{
+    __shared__ uint32_t s_blk[4][64];
+    __shared__ uint64_t s_mask[4][64];
+    __shared__ int32_t s_out[4][256];
     const int b = (int)blockIdx.y;
     const int lane = (int)threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
-    const int q0 = (int)blockIdx.x * 64;
-    const int q = q0 + lane;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int q = (int)blockIdx.x * 4 + wave;
+    if (q >= M) return;                                     // wave-uniform; the kernel has no barrier
     const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
-    const int c = q < M ? center_idx[(int64_t)b * M + q] : -1;
-    const bool okc = c >= 0 && c < N;
-    int32_t* myrow = hits + ((int64_t)w * 64 + lane) * kp;
-    int cnt = 0;
-
-    // this wave's range of point blocks
-    const int blocks = (N + 63) >> 6;
-    const int per = (blocks + S - 1) / S;
-    const int blk_begin = w * per < blocks ? w * per : blocks;
-    const int blk_end = (w + 1) * per < blocks ? (w + 1) * per : blocks;
+    const int c = __builtin_amdgcn_readfirstlane(center_idx[(int64_t)b * M + q]);
+    int32_t* __restrict__ row = out_idx + ((int64_t)b * M + q) * k;
+    if (c < 0 || c >= N) {                                  // no such centre
+        for (int t = lane; t < k; t += 64) row[t] = -1;
+        if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = 0;
+        return;
+    }
+    uint32_t* blk_s = s_blk[wave];
+    uint64_t* mask_s = s_mask[wave];
+    int32_t* out_s = s_out[wave];
 
     const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
     bool usable = h->magic == kBqMagic && h->valid == 1 && h->B == B && h->N == N &&
-                  h->r2_bits == __float_as_uint(r2) && okc && q < h->n;
+                  h->r2_bits == __float_as_uint(r2) && q < h->n;
     if (usable) {
         const int32_t* cidx = reinterpret_cast<const int32_t*>(cache + h->idx_offset);
-        usable = cidx[(int64_t)b * h->n + q] == c;
+        usable = cidx[(int64_t)b * h->n + q] == c && reinterpret_cast<const uint32_t*>(cache + h->ovf_offset)[b] == 0;
     }
-    if (__builtin_amdgcn_ballot_w64(usable) != 0) {
-        const int64_t col_words = h->col_words;
-        const uint64_t* __restrict__ col = reinterpret_cast<const uint64_t*>(cache + h->bits_offset) +
-                                           (int64_t)b * blocks * col_words + (usable ? q : 0);
-        for (int w0 = blk_begin; w0 < blk_end; w0 += kCachedUnroll) {
-            if (__builtin_amdgcn_ballot_w64(usable && cnt < k) == 0) break;
-            uint64_t wd[kCachedUnroll];
+    usable = __builtin_amdgcn_readfirstlane(usable ? 1 : 0) != 0;
+    int nh = 0;                                             // hits kept so far (uniform)
+    if (usable) {
+        const uint32_t* off = reinterpret_cast<const uint32_t*>(cache + h->rowoff_offset) +
+                              (int64_t)b * ((int64_t)h->n + 1) + q;
+        const uint32_t o0 = off[0];
+        const int E = __builtin_amdgcn_readfirstlane((int)(off[1] - o0));
+        const BqEntry* __restrict__ ent = reinterpret_cast<const BqEntry*>(cache + h->rows_offset) +
+                                          (int64_t)b * h->cap + o0;
+        if (E <= 64) {
+            BqEntry me;
+            me.other = 0xFFFFFFFFu;
+            me.lo = me.hi = 0u;
+            if (lane < E) me = ent[lane];
+            int rank = 0;
+            for (int j = 0; j < E; ++j) rank += rdlane_u32(me.other, j) < me.other ? 1 : 0;
+            if (lane < E) {
+                blk_s[rank] = me.other;
+                mask_s[rank] = ((uint64_t)me.hi << 32) | me.lo;
+            }
+            // the same wave reads back what it wrote: the LDS keeps a wave's operations in order
+            const uint32_t bk = lane < E ? blk_s[lane] : 0u;
+            uint64_t m = lane < E ? mask_s[lane] : 0ull;
+            const int pc = __builtin_popcountll(m);
+            int incl = pc;
 #pragma unroll
-            for (int u = 0; u < kCachedUnroll; ++u)
-                wd[u] = (usable && w0 + u < blk_end) ? col[(int64_t)(w0 + u) * col_words] : 0ull;
-#pragma unroll
-            for (int u = 0; u < kCachedUnroll; ++u) {
-                uint64_t x = wd[u];
-                while (x != 0 && cnt < k) {
-                    myrow[cnt] = ((w0 + u) << 6) + __builtin_ctzll(x);
-                    ++cnt;
-                    x &= x - 1;
+            for (int sft = 1; sft < 64; sft <<= 1) {
+                const int up = __shfl_up(incl, sft, 64);
+                if (lane >= sft) incl += up;
+            }
+            const int total = __builtin_amdgcn_readlane(incl, 63);
+            int pos = incl - pc;
+            while (m != 0 && pos < k) {
+                out_s[pos] = (int32_t)((bk << 6) + (uint32_t)__builtin_ctzll(m));
+                ++pos;
+                m &= m - 1;
+            }
+            nh = total < k ? total : k;
+        } else {
+            int64_t last = -1;
+            while (nh < k) {
+                uint32_t best = 0xFFFFFFFFu;
+                uint64_t bm = 0;
+                for (int e0 = 0; e0 < E; e0 += 64) {
+                    if (e0 + lane < E) {
+                        const BqEntry g = ent[e0 + lane];
+                        if ((int64_t)g.other > last && g.other < best) {
+                            best = g.other;
+                            bm = ((uint64_t)g.hi << 32) | g.lo;
+                        }
+                    }
                 }
+                uint32_t wmin = best;
+#pragma unroll
+                for (int sft = 32; sft > 0; sft >>= 1) wmin = min(wmin, (uint32_t)__shfl_xor((int)wmin, sft, 64));
+                wmin = (uint32_t)__builtin_amdgcn_readfirstlane((int)wmin);
+                if (wmin == 0xFFFFFFFFu) break;             // every block is taken
+                const int src = __builtin_ctzll(__builtin_amdgcn_ballot_w64(best == wmin));   // blocks are distinct
+                const uint64_t m = ((uint64_t)rdlane_u32((uint32_t)(bm >> 32), src) << 32) |
+                                   rdlane_u32((uint32_t)bm, src);
+                const bool hit = (m >> lane) & 1ull;
+                const int pos = nh + lanes_below(m);
+                if (hit && pos < k) out_s[pos] = (int32_t)((wmin << 6) + (uint32_t)lane);
+                nh += __builtin_popcountll(m);
+                last = (int64_t)wmin;
             }
+            nh = nh < k ? nh : k;
         }
-    }
-    if (__builtin_amdgcn_ballot_w64(okc && !usable) != 0) {
-        const bool mine = okc && !usable;
-        const float cx = mine ? cloud[(int64_t)c * 3 + 0] : __builtin_nanf("");
-        const float cy = mine ? cloud[(int64_t)c * 3 + 1] : 0.0f;
-        const float cz = mine ? cloud[(int64_t)c * 3 + 2] : 0.0f;
-        const int j_end = blk_end * 64 < N ? blk_end * 64 : N;
-        for (int j = blk_begin * 64; j < j_end; ++j) {
-            if (__builtin_amdgcn_ballot_w64(mine && cnt < k) == 0) break;
-            const float* pj = cloud + (int64_t)j * 3;        // uniform address: scalar loads
-            if (dist2(cx, cy, cz, pj[0], pj[1], pj[2]) < r2 && cnt < k) {
-                myrow[cnt] = j;
-                ++cnt;
+    } else {
+        const float cx = cloud[(int64_t)c * 3 + 0], cy = cloud[(int64_t)c * 3 + 1], cz = cloud[(int64_t)c * 3 + 2];
+        for (int j0 = 0; j0 < N && nh < k; j0 += 64) {
+            const int j = j0 + lane;
+            bool hit = false;
+            if (j < N) {
+                const float* pj = cloud + (int64_t)j * 3;
+                hit = dist2(cx, cy, cz, pj[0], pj[1], pj[2]) < r2;
             }
+            const uint64_t m = __builtin_amdgcn_ballot_w64(hit);
+            const int pos = nh + lanes_below(m);
+            if (hit && pos < k) out_s[pos] = j;
+            nh += __builtin_popcountll(m);
         }
+        nh = nh < k ? nh : k;
     }
-    counts[w * 64 + lane] = cnt;
-    __syncthreads();
-    merge_ranges<S>(hits, counts, kp, k, b, q0, M, w, lane, out_idx, out_cnt);
+    const int first = nh > 0 ? out_s[0] : -1;
+    for (int t = lane; t < k; t += 64) row[t] = t < nh ? out_s[t] : first;
+    if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = nh;
 }
 
 __global__ void gather_kernel(const float* __restrict__ xyz, int B, int N,
@@ -331,26 +527,10 @@ hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* cent
     const dim3 grid((unsigned)((M + 63) / 64), (unsigned)B);
     const size_t per_wave = (size_t)64 * (k + 2) * sizeof(int32_t);
     if (bq_cache) {
-        // enough waves to fill the device, as far as the hit lists leave room in 48 KB of LDS
+        if (k > 254) return hipErrorInvalidValue;
         const unsigned char* cache = reinterpret_cast<const unsigned char*>(bq_cache);
-        const int64_t groups = (int64_t)grid.x * grid.y;
-        const int64_t blocks = ((int64_t)N + 63) / 64;
-        int want = groups >= 4096 ? 1 : groups >= 2048 ? 2 : groups >= 1024 ? 4 : 8;
-        while (want > 1 && ((size_t)want * per_wave > 48 * 1024 || blocks < (int64_t)want * 4)) want >>= 1;
-        if (want == 8)
-            hipLaunchKernelGGL(bq_cached_kernel<8>, grid, dim3(512), 8 * per_wave, stream, xyz, B, N, center_idx, M,
-                               r2, k, out_idx, out_cnt, cache);
-        else if (want == 4)
-            hipLaunchKernelGGL(bq_cached_kernel<4>, grid, dim3(256), 4 * per_wave, stream, xyz, B, N, center_idx, M,
-                               r2, k, out_idx, out_cnt, cache);
-        else if (want == 2)
-            hipLaunchKernelGGL(bq_cached_kernel<2>, grid, dim3(128), 2 * per_wave, stream, xyz, B, N, center_idx, M,
-                               r2, k, out_idx, out_cnt, cache);
-        else if (per_wave <= 64 * 1024)
-            hipLaunchKernelGGL(bq_cached_kernel<1>, grid, dim3(64), per_wave, stream, xyz, B, N, center_idx, M, r2,
-                               k, out_idx, out_cnt, cache);
-        else
-            return hipErrorInvalidValue;
+        hipLaunchKernelGGL(bq_cached_kernel, dim3((unsigned)((M + 3) / 4), (unsigned)B), dim3(256), 0, stream, xyz,
+                           B, N, center_idx, M, r2, k, out_idx, out_cnt, cache);
     } else {
         // As many waves per group of 64 centres as the hit lists leave room for in LDS: 48 KB, so
         // that several workgroups share a compute unit -- or, when the grid would leave most
@@ -388,6 +568,55 @@ hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* cent
             return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+namespace {
+// up to this size the grouping is one launch with one workgroup per cloud
+constexpr int64_t kGroupSmallEntries = 160 * 1024;
+constexpr int kGroupSmallKeys = 16 * 1024;
+
+template <bool BY_BLOCK>
+hipError_t group_entries(const unsigned char* cache, int B, int32_t* cnt, uint32_t* off, BqEntry* rows,
+                         int64_t rows_cap, int keys, hipStream_t stream)
+{
+    if (rows_cap <= kGroupSmallEntries && keys <= kGroupSmallKeys) {
+        hipLaunchKernelGGL((bq_group_small_kernel<BY_BLOCK>), dim3((unsigned)B), dim3(1024), 0, stream, cache, cnt,
+                           off, keys, rows, rows_cap);
+        return hipGetLastError();
+    }
+    int64_t gx = (rows_cap + 2047) / 2048;                // eight entries per thread when the list is full
+    if (gx > 8192) gx = 8192;
+    if (gx < 1) gx = 1;
+    const dim3 grid((unsigned)gx, (unsigned)B);
+    {
+        const int64_t words = (int64_t)B * keys;
+        int zb = (int)((words + 255) / 256);
+        if (zb > 1024) zb = 1024;
+        hipLaunchKernelGGL(zero_ints_kernel, dim3((unsigned)zb), dim3(256), 0, stream, cnt, words);
+    }
+    hipLaunchKernelGGL((bq_group_count_kernel<BY_BLOCK>), grid, dim3(256), 0, stream, cache, cnt, keys, rows_cap);
+    hipLaunchKernelGGL(bq_group_scan_kernel, dim3((unsigned)B), dim3(1024), 0, stream, cnt, off, keys);
+    hipLaunchKernelGGL((bq_group_scatter_kernel<BY_BLOCK>), grid, dim3(256), 0, stream, cache, cnt,
+                       (const uint32_t*)off, keys, rows, rows_cap);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_bq_group_by_sample(void* bq_cache, int B, int N, int n, int64_t cap, hipStream_t stream)
+{
+    unsigned char* cache = reinterpret_cast<unsigned char*>(bq_cache);
+    const BqHeader lay = bq_layout(B, N, n, 1.0f, cap);
+    return group_entries<false>(cache, B, reinterpret_cast<int32_t*>(cache + lay.rowcnt_offset),
+                                reinterpret_cast<uint32_t*>(cache + lay.rowoff_offset),
+                                reinterpret_cast<BqEntry*>(cache + lay.rows_offset), lay.cap, n, stream);
+}
+
+hipError_t launch_bq_group_by_block(const void* bq_cache, int B, int N, int32_t* cnt, uint32_t* off,
+                                    BqEntry* rows, int64_t rows_cap, hipStream_t stream)
+{
+    const int blocks = (int)(((int64_t)N + 63) / 64);
+    return group_entries<true>(reinterpret_cast<const unsigned char*>(bq_cache), B, cnt, off, rows, rows_cap,
+                               blocks, stream);
 }
 
 hipError_t launch_gather(const float* xyz, int B, int N, const int32_t* idx, int M, float* out,

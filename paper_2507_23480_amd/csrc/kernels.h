@@ -14,25 +14,74 @@ constexpr int kLlSlotWords = 8;         // 64-bit words per workgroup slot of th
 constexpr int kCandPerRound = 64;       // candidates per round of exact FPS (one per lane of the control wave)
 constexpr int kCandMax = 128;           // candidates per round of the threshold phase (two per lane)
 constexpr int kCandWords = 5;           // exchanged 64-bit words per candidate (x, y, z, index, distance)
-constexpr uint32_t kBqMagic = 0x46504251u;
+constexpr uint32_t kBqMagic = 0x46504232u;
 
-// Header at the start of a ball-query cache (device memory).  The radius tests are kept as a
-// bit matrix per cloud, one 64-bit word per (block of 64 points, sample): word [w][q] holds, in
-// bit l, whether point 64*w + l lies inside the ball of sample q.  Words of one point block are
-// contiguous over the samples, so a wave of the sampler writes the words of up to 64 picks with
-// one store, a ball-query wave reads the words of 64 consecutive centres with one load, and a
-// k-NN wave streams the samples of its point block.
+// Ball-query cache (device memory): the radius tests of Section 4.2 that found a point, and only
+// those.  While a sample is folded into the running distances every wave of the sampler compares
+// its points with the ball-query radius as well; a 64-bit word of such tests (one block of 64
+// consecutive points against one sample) that is not zero becomes one entry of a flat list per
+// cloud.  After the sampler a small pass puts the entries in sample order (rows in compressed-row
+// form), which is what the ball query reads; the k-NN search regroups them by point block.
+constexpr int kBqChunk = 64;        // entries a wave of the sampler reserves at a time
+constexpr uint32_t kBqNoChunk = 0xFFFFFFFFu;
+struct BqRaw {              // as appended by the sampler
+    uint64_t mask;          // bit l: point 64 * blk + l lies inside the ball of sample q
+    uint32_t blk;           // point block
+    uint32_t q;             // sample position
+};
+struct BqEntry {            // after grouping: the key (sample or block) is the row
+    uint32_t other;         // point block (rows by sample) or sample position (rows by block)
+    uint32_t lo, hi;        // the 64 tests
+};
 struct BqHeader {
     uint32_t magic;
     int32_t B, N, n;
     int32_t blocks;         // point blocks per cloud, ceil(N / 64)
-    int32_t reserved;
-    int64_t col_words;      // 64-bit words per point block (n rounded up to a multiple of 8)
-    uint32_t r2_bits;       // radius^2 (binary32 bits) the tests were recorded with
     int32_t valid;          // 1 once the header is complete
+    uint32_t r2_bits;       // radius^2 (binary32 bits) the tests were recorded with
+    int32_t reserved;
+    int64_t cap;            // entries a cloud's lists hold, a multiple of kBqChunk
     int64_t idx_offset;     // byte offset of the int32 [B][n] copy of the sample indices
-    int64_t bits_offset;    // byte offset of the uint64 [B][blocks][col_words] words
+    int64_t cursor_offset;  // uint32 [B]: chunks of kBqChunk entries handed out to the sampler's waves
+    int64_t ovf_offset;     // uint32 [B]: not 0 when a wave found no chunk left (entries were dropped)
+    int64_t rowcnt_offset;  // int32 [B][n]: entries of each sample
+    int64_t fill_offset;    // uint32 [B][cap / kBqChunk]: entries in use in each chunk
+    int64_t rowoff_offset;  // uint32 [B][n + 1]: first entry of each sample's row
+    int64_t raw_offset;     // BqRaw [B][cap]
+    int64_t rows_offset;    // BqEntry [B][cap], in sample order
+    int64_t bytes;
 };
+
+__host__ __device__ inline int64_t bq_align(int64_t v) { return (v + 255) / 256 * 256; }
+// entries per cloud the lists are sized for unless the caller says otherwise: two per point and
+// sixteen per sample
+__host__ __device__ inline int64_t bq_capacity(int32_t N, int32_t n) { return 2 * (int64_t)N + 16 * (int64_t)n; }
+__host__ __device__ inline BqHeader bq_layout(int32_t B, int32_t N, int32_t n, float r2, int64_t cap)
+{
+    BqHeader h;
+    h.magic = kBqMagic;
+    h.B = B;
+    h.N = N;
+    h.n = n;
+    h.blocks = (int32_t)(((int64_t)N + 63) / 64);
+    h.valid = 1;
+    union { float f; uint32_t u; } cv;
+    cv.f = r2;
+    h.r2_bits = cv.u;
+    h.reserved = 0;
+    h.cap = cap / kBqChunk * kBqChunk;
+    h.idx_offset = 256;
+    // cursor, overflow flags, row counts and chunk fills are one range, zeroed before the sampler runs
+    h.cursor_offset = h.idx_offset + bq_align((int64_t)B * n * 4);
+    h.ovf_offset = h.cursor_offset + bq_align((int64_t)B * 4);
+    h.rowcnt_offset = h.ovf_offset + bq_align((int64_t)B * 4);
+    h.fill_offset = h.rowcnt_offset + bq_align((int64_t)B * n * 4);
+    h.rowoff_offset = h.fill_offset + bq_align((int64_t)B * (h.cap / kBqChunk) * 4);
+    h.raw_offset = h.rowoff_offset + bq_align((int64_t)B * ((int64_t)n + 1) * 4);
+    h.rows_offset = h.raw_offset + bq_align((int64_t)B * h.cap * (int64_t)sizeof(BqRaw));
+    h.bytes = h.rows_offset + bq_align((int64_t)B * h.cap * (int64_t)sizeof(BqEntry));
+    return h;
+}
 
 struct SamplerArgs {
     const float* xyz;
@@ -46,11 +95,15 @@ struct SamplerArgs {
     double exponent, bias2;
     float thr_override[FP_MAX_SEG];
     float level_scale[FP_MAX_SEG];
-    uint64_t* bq_bits;
-    int32_t* bq_idx;
+    unsigned char* bq_base;         // ball-query cache (NULL: nothing is recorded) ...
+    int32_t* bq_idx;                // ... its copy of the sample indices [B][n]
+    BqRaw* bq_raw;                  // ... entries [B][bq_cap], in chunks of kBqChunk
+    uint32_t* bq_cursor;            // ... chunks handed out per cloud [B]
+    uint32_t* bq_ovf;               // ... overflow flag per cloud [B]
+    uint32_t* bq_fill;              // ... entries in use per chunk [B][bq_cap / kBqChunk]
+    int64_t bq_cap;
     float bq_r2;
     int32_t bq_blocks;
-    int64_t bq_col_words;
     uint64_t* ll_pk;                // [groups][2][G][kLlSlotWords]
     uint64_t* ll_cd;                // [groups][2][G][kCandMax][kCandWords]
     int64_t wait_ticks;
@@ -66,7 +119,16 @@ struct Plan {
 // mode 0: exact FPS only; 1: MDPS, threshold rounds of kCandPerRound candidates; 2: MDPS, rounds of
 // kCandMax candidates.  NULL for a combination that is not built.
 const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, int mode);
-hipError_t launch_zero_words(uint64_t* p, int64_t nwords, hipStream_t stream);
+// zeroes two ranges of 64-bit words (either may be empty)
+hipError_t launch_zero_words(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2, hipStream_t stream);
+// puts the entries the sampler appended to a cache of `cap` entries per cloud into sample order
+// (rows in compressed-row form)
+hipError_t launch_bq_group_by_sample(void* bq_cache, int B, int N, int n, int64_t cap, hipStream_t stream);
+// the same entries by point block, in caller memory: cnt int32 [B][blocks], off uint32 [B][blocks + 1],
+// rows BqEntry [B][rows_cap]; clouds with more entries than rows_cap are left out (the caller does
+// not read their rows); `cnt` ends up holding the row sizes
+hipError_t launch_bq_group_by_block(const void* bq_cache, int B, int N, int32_t* cnt, uint32_t* off,
+                                    BqEntry* rows, int64_t rows_cap, hipStream_t stream);
 
 hipError_t launch_probe_fp32(int blocks, int iterations, float* out, hipStream_t stream);
 hipError_t launch_ball_query(const float* xyz, int B, int N, const int32_t* center_idx, int M,
@@ -78,7 +140,8 @@ hipError_t launch_coverage(const float* xyz, int B, int N, const float* sxyz, in
                            hipStream_t stream);
 hipError_t launch_knn(const float* xyz, int B, int N, const int32_t* sample_idx, int n, int k,
                       int32_t* out_pos, float* out_d2, const void* bq_cache, int32_t* flags,
-                      int32_t* count, int32_t* list, int32_t* out_deferred, hipStream_t stream);
+                      int32_t* count, int32_t* list, int32_t* blk_cnt, uint32_t* blk_off, BqEntry* blk_rows,
+                      int64_t blk_rows_cap, int32_t* out_deferred, hipStream_t stream);
 
 // Uniform grid of one cloud for the exclusion-list kernels (device memory, in the workspace).
 struct ExclGrid {

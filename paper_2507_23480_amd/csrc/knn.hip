@@ -81,6 +81,21 @@ struct Nearest {
         d[0] = first ? dd : d[0];
         q[0] = first ? qq : q[0];
     }
+    // the same for samples that arrive in any order: among equal distances the lower position
+    // goes first (a sample must be offered once only)
+    __device__ __forceinline__ void insert_any(float dd, int32_t qq)
+    {
+#pragma unroll
+        for (int i = K - 1; i >= 1; --i) {
+            const bool before = dd < d[i - 1] || (dd == d[i - 1] && (uint32_t)qq < (uint32_t)q[i - 1]);
+            const bool here = dd < d[i] || (dd == d[i] && (uint32_t)qq < (uint32_t)q[i]);
+            d[i] = before ? d[i - 1] : (here ? dd : d[i]);
+            q[i] = before ? q[i - 1] : (here ? qq : q[i]);
+        }
+        const bool first = dd < d[0] || (dd == d[0] && (uint32_t)qq < (uint32_t)q[0]);
+        d[0] = first ? dd : d[0];
+        q[0] = first ? qq : q[0];
+    }
     __device__ __forceinline__ void pop()            // drops the nearest entry
     {
 #pragma unroll
@@ -258,11 +273,19 @@ __global__ __launch_bounds__(256) void knn_list_wave_kernel(const float* __restr
 __global__ __launch_bounds__(256) void knn_check_kernel(const int32_t* __restrict__ sample_idx, int B, int N,
                                                         int n, const unsigned char* __restrict__ cache,
                                                         int32_t* __restrict__ flags,
-                                                        int32_t* __restrict__ count)
+                                                        int32_t* __restrict__ count, int64_t rows_cap)
 {
     const int b = (int)blockIdx.x;
     const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
-    const bool ok = h->magic == kBqMagic && h->valid == 1 && h->B == B && h->N == N && h->n == n;
+    bool ok = h->magic == kBqMagic && h->valid == 1 && h->B == B && h->N == N && h->n == n;
+    // a list that overflowed has lost entries: a point could miss a sample that is near it
+    // (nor can one be used that does not fit the rows of the workspace)
+    if (ok) {
+        const int64_t chunks = (int64_t) reinterpret_cast<const uint32_t*>(cache + h->cursor_offset)[b];
+        const int64_t most = h->cap / kBqChunk;
+        ok = reinterpret_cast<const uint32_t*>(cache + h->ovf_offset)[b] == 0 &&
+             (chunks < most ? chunks : most) * kBqChunk <= rows_cap;
+    }
     int bad = 0;
     if (ok) {
         const int32_t* cidx = reinterpret_cast<const int32_t*>(cache + h->idx_offset);
@@ -277,19 +300,21 @@ __global__ __launch_bounds__(256) void knn_check_kernel(const int32_t* __restric
 }
 
 // Redundancy-free search.  A wave owns one block of 64 points (lane l holds point 64*w + l).
-// The cache keeps the words of a point block contiguous over the samples: the wave streams them
-// 64 samples per load (one word per lane), and only a sample whose word is not zero -- its ball
-// holds at least one of the 64 points -- costs anything more: its word and coordinates are
-// broadcast and the lanes whose bit is set evaluate their distance to it.
+// The entries of the cache, regrouped by point block, name the samples whose ball holds at least
+// one of the 64 points, with the 64 tests: the wave takes its block's entries 64 at a time (one per
+// lane, with the sample's coordinates), broadcasts them one after the other, and the lanes whose
+// bit is set evaluate their distance to that sample.  The entries come in no particular order, so
+// equal distances are ordered by sample position explicitly.
 template <int K>
 __global__ __launch_bounds__(256) void knn_cached_kernel(const float* __restrict__ xyz, int N,
                                                          const int32_t* __restrict__ sample_idx, int n, int k,
                                                          int32_t* __restrict__ out_pos,
                                                          float* __restrict__ out_d2,
-                                                         const unsigned char* __restrict__ cache,
                                                          const int32_t* __restrict__ flags,
                                                          int32_t* __restrict__ count,
-                                                         int32_t* __restrict__ list)
+                                                         int32_t* __restrict__ list,
+                                                         const uint32_t* __restrict__ blk_off,
+                                                         const BqEntry* __restrict__ blk_rows, int64_t cap)
 {
     const int b = (int)blockIdx.y;
     const int lane = (int)threadIdx.x & 63;
@@ -313,39 +338,34 @@ __global__ __launch_bounds__(256) void knn_cached_kernel(const float* __restrict
 
     const bool usable = __builtin_amdgcn_readfirstlane(flags[b]) != 0;
     if (usable) {
-        const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
-        const uint64_t* __restrict__ col = reinterpret_cast<const uint64_t*>(cache + h->bits_offset) +
-                                           ((int64_t)b * h->blocks + w) * h->col_words;
-        // two loads are always on their way while a block of 64 samples is examined
-        uint64_t cur = lane < n ? col[lane] : 0ull;
-        uint64_t nxt = 64 + lane < n ? col[64 + lane] : 0ull;
-        for (int q0 = 0; q0 < n; q0 += 64) {
-            const uint64_t after = q0 + 128 + lane < n ? col[q0 + 128 + lane] : 0ull;
-            const bool nz = cur != 0;
-            uint64_t rows = __builtin_amdgcn_ballot_w64(nz);
-            if (rows != 0) {
-                float sx = __builtin_nanf(""), sy = sx, sz = sx;
-                if (nz) {
-                    const int si = sidx[q0 + lane];
-                    if (si >= 0 && si < N) {
-                        sx = cloud[(int64_t)si * 3 + 0];
-                        sy = cloud[(int64_t)si * 3 + 1];
-                        sz = cloud[(int64_t)si * 3 + 2];
-                    }
-                }
-                while (rows != 0) {                  // ascending sample position
-                    const int l = __builtin_ctzll(rows);
-                    rows &= rows - 1;
-                    const float ax = rdlane_f(sx, l), ay = rdlane_f(sy, l), az = rdlane_f(sz, l);
-                    const uint64_t wd = rdlane_u64(cur, l);
-                    const bool hit = (wd >> lane) & 1ull;
-                    const float d = hit ? dist2(px, py, pz, ax, ay, az) : __builtin_inff();
-                    hits += hit ? 1 : 0;
-                    nb.insert(d, q0 + l);
+        const uint32_t* off = blk_off + (int64_t)b * ((int64_t)blocks + 1) + w;
+        const uint32_t o0 = off[0];
+        const int E = __builtin_amdgcn_readfirstlane((int)(off[1] - o0));
+        const BqEntry* __restrict__ ent = blk_rows + (int64_t)b * cap + o0;
+        for (int e0 = 0; e0 < E; e0 += 64) {
+            const int cntw = E - e0 < 64 ? E - e0 : 64;
+            BqEntry g;
+            g.other = 0u;
+            g.lo = g.hi = 0u;
+            float sx = __builtin_nanf(""), sy = sx, sz = sx;
+            if (lane < cntw) {
+                g = ent[e0 + lane];
+                const int si = g.other < (uint32_t)n ? sidx[g.other] : -1;
+                if (si >= 0 && si < N) {
+                    sx = cloud[(int64_t)si * 3 + 0];
+                    sy = cloud[(int64_t)si * 3 + 1];
+                    sz = cloud[(int64_t)si * 3 + 2];
                 }
             }
-            cur = nxt;
-            nxt = after;
+            const uint64_t mine = ((uint64_t)g.hi << 32) | g.lo;
+            for (int l = 0; l < cntw; ++l) {
+                const float ax = rdlane_f(sx, l), ay = rdlane_f(sy, l), az = rdlane_f(sz, l);
+                const uint64_t wd = rdlane_u64(mine, l);
+                const int qq = __builtin_amdgcn_readlane((int)g.other, l);
+                const bool hit = (wd >> lane) & 1ull;
+                hits += hit ? 1 : 0;
+                if (hit) nb.insert_any(dist2(px, py, pz, ax, ay, az), qq);
+            }
         }
     }
 
@@ -369,7 +389,8 @@ __global__ __launch_bounds__(256) void knn_cached_kernel(const float* __restrict
 template <int K>
 hipError_t launch_knn_k(const float* xyz, int B, int N, const int32_t* sample_idx, int n, int k,
                         int32_t* out_pos, float* out_d2, const void* bq_cache, int32_t* flags,
-                        int32_t* count, int32_t* list, int32_t* out_deferred, hipStream_t stream)
+                        int32_t* count, int32_t* list, int32_t* blk_cnt, uint32_t* blk_off, BqEntry* blk_rows,
+                        int64_t blk_rows_cap, int32_t* out_deferred, hipStream_t stream)
 {
     const dim3 grid_pts((unsigned)((N + kPointsPerWg - 1) / kPointsPerWg), (unsigned)B);
     if (!bq_cache) {
@@ -380,11 +401,16 @@ hipError_t launch_knn_k(const float* xyz, int B, int N, const int32_t* sample_id
     }
     const unsigned char* cache = reinterpret_cast<const unsigned char*>(bq_cache);
     hipLaunchKernelGGL(knn_check_kernel, dim3((unsigned)B), dim3(256), 0, stream, sample_idx, B, N, n, cache,
-                       flags, count);
+                       flags, count, blk_rows_cap);
+    // the recorded tests by point block (a cache recorded for another shape leaves rows that are
+    // never read: its flags are 0)
+    if (launch_bq_group_by_block(bq_cache, B, N, blk_cnt, blk_off, blk_rows, blk_rows_cap, stream) != hipSuccess)
+        return hipErrorInvalidValue;
     const int blocks = (N + 63) >> 6;
     const dim3 grid_words((unsigned)((blocks + 3) / 4), (unsigned)B);
     hipLaunchKernelGGL((knn_cached_kernel<K>), grid_words, dim3(256), 0, stream, xyz, N, sample_idx, n, k,
-                       out_pos, out_d2, cache, (const int32_t*)flags, count, list);
+                       out_pos, out_d2, (const int32_t*)flags, count, list, (const uint32_t*)blk_off,
+                       (const BqEntry*)blk_rows, blk_rows_cap);
     hipLaunchKernelGGL((knn_list_wave_kernel<K>), dim3(kWaveListMax / 4, (unsigned)B), dim3(256), 0, stream, xyz,
                        N, sample_idx, n, k, out_pos, out_d2, (const int32_t*)list, (const int32_t*)count);
     hipLaunchKernelGGL((knn_brute_kernel<K, true>), grid_pts, dim3(256), 0, stream, xyz, N, sample_idx, n, k,
@@ -428,17 +454,18 @@ hipError_t launch_knn_deferred(const float* xyz, int B, int N, const int32_t* sa
 
 hipError_t launch_knn(const float* xyz, int B, int N, const int32_t* sample_idx, int n, int k,
                       int32_t* out_pos, float* out_d2, const void* bq_cache, int32_t* flags,
-                      int32_t* count, int32_t* list, int32_t* out_deferred, hipStream_t stream)
+                      int32_t* count, int32_t* list, int32_t* blk_cnt, uint32_t* blk_off, BqEntry* blk_rows,
+                      int64_t blk_rows_cap, int32_t* out_deferred, hipStream_t stream)
 {
     if (k == 1)
         return launch_knn_k<1>(xyz, B, N, sample_idx, n, k, out_pos, out_d2, bq_cache, flags, count, list,
-                               out_deferred, stream);
+                               blk_cnt, blk_off, blk_rows, blk_rows_cap, out_deferred, stream);
     if (k <= 3)
         return launch_knn_k<3>(xyz, B, N, sample_idx, n, k, out_pos, out_d2, bq_cache, flags, count, list,
-                               out_deferred, stream);
+                               blk_cnt, blk_off, blk_rows, blk_rows_cap, out_deferred, stream);
     if (k <= 8)
         return launch_knn_k<8>(xyz, B, N, sample_idx, n, k, out_pos, out_d2, bq_cache, flags, count, list,
-                               out_deferred, stream);
+                               blk_cnt, blk_off, blk_rows, blk_rows_cap, out_deferred, stream);
     return hipErrorInvalidValue;
 }
 

@@ -287,6 +287,12 @@ struct Points {
     typename RegVecU<P>::type oi;       // cell-ordered variant: the point's index in the caller's cloud
     float lox, loy, loz, hix, hiy, hiz; // cell-ordered variant: box of the wave's points (wave-uniform)
     uint32_t ub;                        // ... and an upper bound of their running distances (bits)
+    // recording kernels: where this wave's next entry of the cloud's list goes.  [bq_cur, bq_lim) is
+    // what is left of the chunk the wave is filling; bq_nxt holds (in lane 0) the number of the chunk
+    // it has reserved for afterwards, asked for when the current one was taken, so that the answer
+    // has long arrived when it is needed.
+    uint32_t bq_cur, bq_lim, bq_nxt;
+    bool bq_dead;                       // no chunk was left: nothing more is recorded for this cloud
 };
 
 // Cell-ordered variant: squared distance of a pick to the box of a wave's points, evaluated like
@@ -336,23 +342,30 @@ __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float c
 {
     constexpr int GRP = P < 8 ? P : 8;      // slots whose radius tests are examined together
     if constexpr (P0 < P) {
-        uint32_t tb[GRP];                   // squared distances as bit patterns (>= +0: unsigned order)
-        uint32_t tmin = 0xFFFFFFFFu;
+        uint32_t tmin = 0xFFFFFFFFu;        // squared distances as bit patterns (>= +0: unsigned order)
 #pragma unroll
         for (int u = 0; u < GRP; ++u) {
             const int p = P0 + u;
-            tb[u] = __float_as_uint(dist2(cx, cy, cz, pt.x[p], pt.y[p], pt.z[p]));
-            pt.d[p] = __uint_as_float(min(__float_as_uint(pt.d[p]), tb[u]));
-            if (BQ) tmin = min(tmin, tb[u]);
+            const uint32_t tb = __float_as_uint(dist2(cx, cy, cz, pt.x[p], pt.y[p], pt.z[p]));
+            pt.d[p] = __uint_as_float(min(__float_as_uint(pt.d[p]), tb));
+            if (BQ) tmin = min(tmin, tb);
         }
         if (BQ) {
-            // most balls miss most waves: one test per group on the vector unit; the per-slot
-            // masks are formed and kept only when some point of the group hits
+            // most balls miss most waves: one test per group on the vector unit.  Only when some
+            // point of the group hits are the distances worked out once more to form the per-slot
+            // masks: kept from the update above they would stay alive across the test, and the
+            // compiler then moves every running distance of the thread from one register to another
+            // once per pick.  (The pick's coordinates pass through an empty asm statement so that the
+            // second evaluation is not merged with the first.)
             const uint32_t r2b = __float_as_uint(bq_r2);
             if (__builtin_amdgcn_ballot_w64(tmin < r2b) != 0) {
+                float hx = cx, hy = cy, hz = cz;
+                asm volatile("" : "+v"(hx), "+v"(hy), "+v"(hz));
 #pragma unroll
                 for (int u = 0; u < GRP; ++u) {
-                    rw.row[(P0 + u) * 64 + s] = __builtin_amdgcn_ballot_w64(tb[u] < r2b);
+                    const int p = P0 + u;
+                    const uint32_t tb = __float_as_uint(dist2(hx, hy, hz, pt.x[p], pt.y[p], pt.z[p]));
+                    rw.row[p * 64 + s] = __builtin_amdgcn_ballot_w64(tb < r2b);
                 }
             }
         }
@@ -367,20 +380,81 @@ __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, floa
     fold_groups<P, BQ, 0>(pt, cx, cy, cz, a.bq_r2, s, rw);
 }
 
-// Writes the words of `count` picks (sample positions base, base+1, ...; count <= 64) to the
-// cache: for every slot p the lanes store the words [block gw*P + p][base .. base+count), which
-// are contiguous.
+// Hands the words of `count` picks (sample positions base, base+1, ...; count <= 64) to the cache.
+// Lane s looks at the words of pick s; only a word that is not zero -- the ball holds one of the
+// block's 64 points -- becomes an entry (sample, block, word) of the cloud's list.  A wave fills
+// chunks of kBqChunk entries that it reserves from the cloud's chunk counter: the places inside a
+// chunk come from ballots and bit counts, and the atomic addition that reserves the next chunk is
+// issued when a chunk is taken and read when that chunk is full, so no wave ever waits for memory
+// here (except for its very first entry of a cloud).  After every call lane 0 notes how much of the
+// chunk is in use.  When no chunk is left the cloud's overflow flag is raised and the wave records
+// nothing more: readers then treat the cloud as not recorded.
 template <int P, bool BQ>
 __device__ __forceinline__ void flush_rows(const RowWords<P, BQ>& rw, const SamplerArgs& a, const Where& wh,
-                                           int base, int count)
+                                           Points<P, BQ>& pt, int base, int count)
 {
-    if (!BQ) return;
+    if constexpr (BQ) {
+        if (pt.bq_dead) return;
+        const bool mine = wh.lane < count;
+        uint64_t m[P];
+        int total = 0;
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
-        const int blk = wh.gw * P + p;              // slots wholly beyond N have no block
-        if (blk < a.bq_blocks && wh.lane < count)
-            a.bq_bits[((int64_t)wh.c * a.bq_blocks + blk) * a.bq_col_words + base + wh.lane] =
-                rw.row[p * 64 + wh.lane];
+        for (int p = 0; p < P; ++p) {
+            const int blk = wh.gw * P + p;              // slots wholly beyond N have no block
+            const uint64_t w = rw.row[p * 64 + wh.lane];
+            m[p] = __builtin_amdgcn_ballot_w64(mine && blk < a.bq_blocks && w != 0);
+            total += __builtin_popcountll(m[p]);
+        }
+        if (total == 0) return;                         // uniform
+        const uint32_t nchunks = (uint32_t)(a.bq_cap / kBqChunk);
+        uint32_t* cursor = a.bq_cursor + wh.c;
+        uint32_t* fill = a.bq_fill + (int64_t)wh.c * nchunks;
+        BqRaw* __restrict__ list = a.bq_raw + (int64_t)wh.c * a.bq_cap;
+        int done = 0;                                   // entries of this call that are placed (uniform)
+        while (done < total) {
+            if (pt.bq_cur == pt.bq_lim) {               // the chunk is full (or there is none yet)
+                uint32_t ch;
+                if (uni(pt.bq_nxt) == kBqNoChunk && pt.bq_lim == 0) {
+                    // the wave's first entry of this cloud: two chunks at once
+                    uint32_t c0 = 0;
+                    if (wh.lane == 0) c0 = __hip_atomic_fetch_add(cursor, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ch = uni(c0);
+                    pt.bq_nxt = ch + 1;
+                } else {
+                    ch = uni(pt.bq_nxt);
+                    uint32_t c1 = 0;
+                    if (wh.lane == 0) c1 = __hip_atomic_fetch_add(cursor, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    pt.bq_nxt = c1;                     // not looked at before the next chunk is needed
+                }
+                if (ch >= nchunks) {                    // the list is full
+                    if (wh.lane == 0) a.bq_ovf[wh.c] = 1u;
+                    pt.bq_dead = true;
+                    return;
+                }
+                pt.bq_cur = ch * (uint32_t)kBqChunk;
+                pt.bq_lim = pt.bq_cur + (uint32_t)kBqChunk;
+            }
+            const int room = (int)(pt.bq_lim - pt.bq_cur);
+            const int take = total - done < room ? total - done : room;
+            int before = 0;
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                if (m[p] != 0) {
+                    const int i = before + lanes_below(m[p]) - done;       // place among this turn's entries
+                    if (((m[p] >> wh.lane) & 1ull) != 0 && i >= 0 && i < take) {
+                        BqRaw e;
+                        e.mask = rw.row[p * 64 + wh.lane];
+                        e.blk = (uint32_t)(wh.gw * P + p);
+                        e.q = (uint32_t)(base + wh.lane);
+                        list[pt.bq_cur + (uint32_t)i] = e;
+                    }
+                    before += __builtin_popcountll(m[p]);
+                }
+            }
+            pt.bq_cur += (uint32_t)take;
+            done += take;
+            if (wh.lane == 0) fill[(pt.bq_lim - 1u) / (uint32_t)kBqChunk] = pt.bq_cur - (pt.bq_lim - (uint32_t)kBqChunk);
+        }
     }
 }
 
@@ -670,7 +744,7 @@ __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, c
         if (s + 1 < npend) nxt = sh.pend[s + 1];       // fetched while the current pick is folded
         fold<P, BQ>(pt, cur.x, cur.y, cur.z, a, wh, s, rw);
     }
-    flush_rows<P, BQ>(rw, a, wh, base, npend);
+    flush_rows<P, BQ>(rw, a, wh, pt, base, npend);
 }
 
 // The point waves' side of a round that the control wave resolves: folds the picks (sample
@@ -691,33 +765,47 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
         if constexpr (WIDE) near_hi = near_mask<P, BQ>(pt, sh.cand + 64, total - 64, wh.lane);
     }
     uint32_t slot = lds_observe(&sh.live[0]);
-    for (;;) {
-        // wait for slot s of this round (requested before the previous pick was folded); nothing
-        // but the slot changes in the inner loop, so the distances and row words stay where they
-        // are across it
-        slot = uni(slot);
-        while ((slot & ~0xFFu) != tag) {            // not written yet in this round
-            __builtin_amdgcn_s_sleep(1);
-            slot = uni(lds_observe(&sh.live[s]));
-        }
-        if ((slot & 0xFFu) == kLiveEnd) break;
-        const uint32_t cl = slot & 0xFFu;
-        slot = lds_observe(&sh.live[s + 1]);
-        if (WIDE && BQ && s == 64) {                // lane s of `rw` holds a pick's words: 64 at a time
-            flush_rows<P, BQ>(rw, a, wh, base, 64);
+    // Lane s of `rw` holds the words of a pick, so a recording wave takes a wide round in two halves
+    // of up to 64 picks and hands the first half's words over in between; that hand-over is kept
+    // out of the loop over the picks (whatever is written there would be carried, and copied,
+    // through every iteration).
+    constexpr int kHalves = (WIDE && BQ) ? 2 : 1;
+    bool ended = false;
+#pragma unroll 1
+    for (int half = 0; half < kHalves && !ended; ++half) {
+        const int stop = kHalves == 2 ? 64 * (half + 1) : 0x7FFFFFFF;
+        if (half == 1) {
+            flush_rows<P, BQ>(rw, a, wh, pt, base, 64);
             rw.clear(wh);
         }
-        const uint64_t nbit = (WIDE && cl >= 64u) ? (near_hi >> (cl - 64u)) : (near >> cl);
-        if (!PERM || (nbit & 1ull) != 0) {
-            const Cand c = sh.cand[cl];
-            fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, WIDE ? (s & 63) : s, rw);
+        for (;;) {
+            // wait for slot s of this round (requested before the previous pick was folded); nothing
+            // but the slot changes in the inner loop, so the distances and row words stay where they
+            // are across it
+            slot = uni(slot);
+            while ((slot & ~0xFFu) != tag) {        // not written yet in this round
+                __builtin_amdgcn_s_sleep(1);
+                slot = uni(lds_observe(&sh.live[s]));
+            }
+            if ((slot & 0xFFu) == kLiveEnd) {
+                ended = true;
+                break;
+            }
+            if (s == stop) break;                   // the slot stays in hand for the second half
+            const uint32_t cl = slot & 0xFFu;
+            slot = lds_observe(&sh.live[s + 1]);
+            const uint64_t nbit = (WIDE && cl >= 64u) ? (near_hi >> (cl - 64u)) : (near >> cl);
+            if (!PERM || (nbit & 1ull) != 0) {
+                const Cand c = sh.cand[cl];
+                fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, WIDE ? (s & 63) : s, rw);
+            }
+            ++s;
         }
-        ++s;
     }
     if (WIDE)   // the picks not written yet: all of them up to 64, else those from the 65th on
-        flush_rows<P, BQ>(rw, a, wh, s > 64 ? base + 64 : base, s > 64 ? s - 64 : s);
+        flush_rows<P, BQ>(rw, a, wh, pt, s > 64 ? base + 64 : base, s > 64 ? s - 64 : s);
     else
-        flush_rows<P, BQ>(rw, a, wh, base, s);      // a round has at most kCand picks
+        flush_rows<P, BQ>(rw, a, wh, pt, base, s);  // a round has at most kCand picks
 }
 
 // segment boundary b_l (curve index whose value becomes R_l), l = 1..nseg
@@ -1297,7 +1385,10 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     const int start = uni(a.start_idx ? a.start_idx[wh.c] : 0);
     if (start < 0 || start >= N) {          // uniform over the group
         if (wh.g == 0) {
-            for (int k = wh.tid; k < n; k += T + kCtrlThreads) a.out_idx[(int64_t)wh.c * n + k] = -1;
+            for (int k = wh.tid; k < n; k += T + kCtrlThreads) {
+                a.out_idx[(int64_t)wh.c * n + k] = -1;
+                if (BQ) a.bq_idx[(int64_t)wh.c * n + k] = -1;      // no centre matches this cloud's record
+            }
             if (wh.tid == 0 && a.info) {
                 fp_mdps_info inf = {};
                 inf.status = 1;
@@ -1364,6 +1455,21 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 pt.y[p] = kPadCoord;
                 pt.z[p] = kPadCoord;
                 pt.d[p] = 0.0f;
+            }
+        }
+    }
+    pt.bq_cur = pt.bq_lim = 0;
+    pt.bq_nxt = kBqNoChunk;
+    pt.bq_dead = false;
+    if constexpr (BQ) {
+        // a cloud held by one workgroup: its counters in the cache are zeroed here (the barrier below
+        // comes before the first entry); with several workgroups a launch in front has done it
+        if (wh.G == 1) {
+            const int nchunks = (int)(a.bq_cap / kBqChunk);
+            for (int t = wh.tid; t < nchunks; t += T + kCtrlThreads) a.bq_fill[(int64_t)wh.c * nchunks + t] = 0u;
+            if (wh.tid == 0) {
+                a.bq_cursor[wh.c] = 0u;
+                a.bq_ovf[wh.c] = 0u;
             }
         }
     }
@@ -1663,7 +1769,10 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         a.info[wh.c] = inf;
     }
     if (!ok && wh.g == 0)
-        for (int k = wh.tid; k < n; k += T + kCtrlThreads) a.out_idx[(int64_t)wh.c * n + k] = -1;
+        for (int k = wh.tid; k < n; k += T + kCtrlThreads) {
+            a.out_idx[(int64_t)wh.c * n + k] = -1;
+            if (BQ) a.bq_idx[(int64_t)wh.c * n + k] = -1;          // no centre matches this cloud's record
+        }
     __syncthreads();
 }
 
@@ -1688,22 +1797,8 @@ __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a
         // the header of the ball-query cache (256 bytes in front of the copy of the sample indices):
         // written here rather than by a launch of its own, which would lie in front of every
         // recording sampler on the stream
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            unsigned char* base = reinterpret_cast<unsigned char*>(a.bq_idx) - 256;
-            BqHeader h;
-            h.magic = kBqMagic;
-            h.B = a.B;
-            h.N = a.N;
-            h.n = a.n;
-            h.blocks = a.bq_blocks;
-            h.reserved = 0;
-            h.col_words = a.bq_col_words;
-            h.r2_bits = __float_as_uint(a.bq_r2);
-            h.valid = 1;
-            h.idx_offset = 256;
-            h.bits_offset = (int64_t)(reinterpret_cast<unsigned char*>(a.bq_bits) - base);
-            *reinterpret_cast<BqHeader*>(base) = h;
-        }
+        if (blockIdx.x == 0 && threadIdx.x == 0)
+            *reinterpret_cast<BqHeader*>(a.bq_base) = bq_layout(a.B, a.N, a.n, a.bq_r2, a.bq_cap);
     }
     uint32_t it = 0, seq = 0;
     for (int c = wh.grp; c < a.B; c += ngroups) {
@@ -1712,12 +1807,14 @@ __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a
     }
 }
 
-// zeroes the exchange words before a launch (stamps start at 1 in every launch)
-__global__ void zero_words_kernel(uint64_t* p, int64_t nwords)
+// zeroes two ranges of words before a launch: the exchange words (stamps start at 1 in every
+// launch) and the counters of a ball-query cache
+__global__ void zero_words_kernel(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < nwords; i += stride) p[i] = 0;
+    for (int64_t t = i; t < nwords; t += stride) p[t] = 0;
+    for (int64_t t = i; t < nwords2; t += stride) p2[t] = 0;
 }
 
 template <int T, int P, bool BQ, bool PERM>
@@ -1760,12 +1857,14 @@ const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool
     return nullptr;
 }
 
-hipError_t launch_zero_words(uint64_t* p, int64_t nwords, hipStream_t stream)
+hipError_t launch_zero_words(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2, hipStream_t stream)
 {
-    if (nwords <= 0) return hipSuccess;
-    int blocks = (int)((nwords + 255) / 256);
+    const int64_t most = nwords > nwords2 ? nwords : nwords2;
+    if (most <= 0) return hipSuccess;
+    int blocks = (int)((most + 255) / 256);
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(zero_words_kernel, dim3(blocks), dim3(256), 0, stream, p, nwords);
+    hipLaunchKernelGGL(zero_words_kernel, dim3(blocks), dim3(256), 0, stream, p, nwords > 0 ? nwords : 0, p2,
+                       nwords2 > 0 ? nwords2 : 0);
     return hipGetLastError();
 }
 

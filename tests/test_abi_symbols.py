@@ -38,8 +38,8 @@ def test_host_side_argument_checks_need_no_gpu():
     lib = binding.load()
     assert lib.fp_workspace_bytes(0, 10) == 0
     assert lib.fp_workspace_bytes(1, 10) > 0
-    assert lib.fp_bq_cache_bytes(1, 100, 101) == 0
-    assert lib.fp_bq_cache_bytes(2, 1000, 10) >= 256 + 2 * 10 * 4 + 2 * 10 * 16 * 8
+    assert lib.fp_bq_cache_bytes(1, 100, 101, 0) == 0
+    assert lib.fp_bq_cache_bytes(2, 1000, 10, 0) >= 256 + 2 * 10 * 4 + 2 * (2 * 1000 + 16 * 10) * (16 + 12)
     assert lib.fp_status_string(0) == b"ok"
     assert lib.fp_status_string(-2) == b"shape out of range"
     # NULL pointers are rejected before anything touches a device

@@ -96,7 +96,7 @@ def test_largest_cloud_the_sampler_takes(fp):
     big = torch.empty((1, N + 1, 3), dtype=torch.float32, device="cuda")
     out = torch.empty((1, n), dtype=torch.int32, device="cuda")
     ws = fp.new_workspace(x.device, 1, N)
-    assert lib.fp_fps_exact(big.data_ptr(), 1, N + 1, n, None, out.data_ptr(), None, None, None, 0.0,
+    assert lib.fp_fps_exact(big.data_ptr(), 1, N + 1, n, None, out.data_ptr(), None, None, None, 0, 0.0,
                             ws.data_ptr(), ws.numel(), None) == -2
 
 
@@ -121,19 +121,23 @@ def test_error_codes(fp):
     out = torch.empty((1, 50), dtype=torch.int32, device="cuda")
     ws = fp.new_workspace(x.device, 1, 200)
     f = lambda *a: lib.fp_fps_exact(*a)
-    ok = (x.data_ptr(), 1, 200, 50, None, out.data_ptr(), None, None, None, 0.0, ws.data_ptr(), ws.numel(), None)
+    ok = (x.data_ptr(), 1, 200, 50, None, out.data_ptr(), None, None, None, 0, 0.0, ws.data_ptr(), ws.numel(), None)
     assert f(*ok) == 0
     assert f(None, *ok[1:]) == -1                                     # xyz
     assert f(*ok[:5], None, *ok[6:]) == -1                            # out_idx
     assert f(*ok[:3], 201, *ok[4:]) == -2                             # n > N
     assert f(*ok[:3], 0, *ok[4:]) == -2                               # n < 1
     assert f(*ok[:1], 0, *ok[2:]) == -2                               # B < 1
-    assert f(*ok[:10], None, 0, None) == -4                           # no workspace
-    assert f(*ok[:10], ws.data_ptr() + 8, ws.numel() - 8, None) == -4  # misaligned
-    assert f(*ok[:11], 1024, None) == -4                              # too small
+    assert f(*ok[:11], None, 0, None) == -4                           # no workspace
+    assert f(*ok[:11], ws.data_ptr() + 8, ws.numel() - 8, None) == -4  # misaligned
+    assert f(*ok[:12], 1024, None) == -4                              # too small
     cache = fp.new_bq_cache(x, 50)
-    assert f(*ok[:8], cache.data_ptr(), 0.0, *ok[10:]) == -3          # cache without a radius
-    assert f(*ok[:8], cache.data_ptr() + 4, 0.1, *ok[10:]) == -4      # misaligned cache
+    assert f(*ok[:8], cache.data_ptr(), cache.numel(), 0.0, *ok[11:]) == -3          # cache without a radius
+    assert f(*ok[:8], cache.data_ptr() + 4, cache.numel() - 4, 0.1, *ok[11:]) == -4  # misaligned cache
+    assert f(*ok[:8], cache.data_ptr(), 1024, 0.1, *ok[11:]) == -4                   # cache too small for any entry
+    assert 2 * 200 + 16 * 50 <= lib.fp_bq_cache_entries(cache.numel(), 1, 200, 50) < 2 * 200 + 16 * 50 + 32
+    assert lib.fp_bq_cache_bytes(1, 200, 50, 0) == cache.numel()
+    assert lib.fp_bq_cache_entries(lib.fp_bq_cache_bytes(1, 200, 50, 12345), 1, 200, 50) >= 12345
     torch.cuda.synchronize()
 
     def mdps(**kw):
@@ -141,12 +145,12 @@ def test_error_codes(fp):
         for k, v in kw.get("raw", {}).items():
             setattr(prm, k, v)
         return lib.fp_mdps_sample(x.data_ptr(), 1, 200, 50, None, ctypes.byref(prm), out.data_ptr(), None, None,
-                                  0.0, ws.data_ptr(), ws.numel(), None)
+                                  0, 0.0, ws.data_ptr(), ws.numel(), None)
     assert mdps() == 0
     assert mdps(raw={"p": 0.0}) == -3 and mdps(raw={"p": 1.0}) == -3
     assert mdps(raw={"nseg": 0}) == -3 and mdps(raw={"nseg": 17}) == -3
     assert mdps(raw={"bias": 0.0}) == -3 and mdps(raw={"fit_window": 65}) == -3 and mdps(raw={"m_min": 0}) == -3
-    assert lib.fp_mdps_sample(x.data_ptr(), 1, 200, 50, None, None, out.data_ptr(), None, None, 0.0,
+    assert lib.fp_mdps_sample(x.data_ptr(), 1, 200, 50, None, None, out.data_ptr(), None, None, 0, 0.0,
                               ws.data_ptr(), ws.numel(), None) == -1
     torch.cuda.synchronize()
 

@@ -36,7 +36,7 @@ def test_graph_replay_of_four_stream_step_equals_eager_and_oracle():
     for s, st in enumerate(wl.stages):
         assert fp.plan(B, N)[0] == 1
         stages.append({"n": st.n, "r": st.radius, "k": st.k, "prm": calibration.params_for(name, s),
-                       "cache": torch.empty(fp.load().fp_bq_cache_bytes(B, N, st.n), dtype=torch.uint8,
+                       "cache": torch.empty(fp.load().fp_bq_cache_bytes(B, N, st.n, 0), dtype=torch.uint8,
                                             device="cuda"),
                        "ws": [fp.new_workspace(xyz.device, B, N), fp.new_workspace(xyz.device, B, N)]})
         N = st.n

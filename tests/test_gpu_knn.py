@@ -100,7 +100,9 @@ def test_redundancy_free_knn_equals_oracle(fp, sampler, N, n, G, radius, k):
     xyz = dev(cloud)
     fp.set_wg_per_cloud(G)
     try:
-        cache = fp.new_bq_cache(xyz, n)
+        # room for every block of every ball (and for the chunks the sampler's waves hold in reserve, at
+        # most 128 entries per 128 points): the record is complete whatever the radius
+        cache = fp.new_bq_cache(xyz, n, entries_per_cloud=n * ((N + 63) // 64) + N + 128)
         if sampler == "fps":
             idx = fp.fps_exact(xyz, n, bq_cache=cache, bq_radius=radius)
         else:
@@ -137,3 +139,27 @@ def test_redundancy_free_knn_batches(fp):
     sidx2[2, 10] = sidx2[2, 11]
     deferred = check_knn(fp, batch, sidx2, 3, cache=cache)
     assert int(deferred[2]) == batch.shape[1]
+
+
+def test_a_record_that_overflowed_is_not_used(fp):
+    """A cache too small for the balls' entries is recorded incompletely and says so: the k-NN
+    search and the ball query then take the brute-force way for that cloud, with the same result."""
+    N, n, radius, k = 3000, 400, 0.3, 3
+    batch = np.stack([inputs.uniform_cube(640 + b, N) for b in range(2)])
+    xyz = dev(batch)
+    small = fp.new_bq_cache(xyz, n, entries_per_cloud=500)       # the balls reach far more blocks than 500
+    roomy = fp.new_bq_cache(xyz, n, entries_per_cloud=n * ((N + 63) // 64) + N + 128)
+    idx = fp.fps_exact(xyz, n, bq_cache=small, bq_radius=radius)
+    idx2 = fp.fps_exact(xyz, n, bq_cache=roomy, bq_radius=radius)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2)
+    sidx = idx.cpu().numpy()
+    d_small = check_knn(fp, batch, sidx, k, cache=small)
+    d_roomy = check_knn(fp, batch, sidx, k, cache=roomy)
+    assert [int(v) for v in d_small] == [N, N] and max(int(v) for v in d_roomy) < N
+    for cache in (small, roomy):
+        bq, cnt = fp.ball_query(xyz, idx, radius, 16, bq_cache=cache)
+        torch.cuda.synchronize()
+        for b in range(2):
+            wq, wc = ref.ball_query(batch[b], sidx[b], radius, 16)
+            assert np.array_equal(bq[b].cpu().numpy(), wq) and np.array_equal(cnt[b].cpu().numpy(), wc)

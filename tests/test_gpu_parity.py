@@ -241,3 +241,26 @@ def test_gather_and_coverage(fp):
         assert np.array_equal(g.cpu().numpy()[b], ref.gather_xyz(batch[b], idx[b]))
         want = ref.coverage_radius(batch[b], idx[b])
         assert abs(float(cov[b].sqrt()) - want) <= 1e-5 * want
+
+
+def test_a_cloud_that_failed_leaves_no_usable_record(fp):
+    """A cache buffer is reused across calls.  When a later call fails for one cloud (seed index out
+    of range: all -1, status 1), the rows an earlier call recorded for that cloud describe other
+    coordinates: no centre may be answered from them."""
+    B, N, n, radius, k = 2, 2000, 120, 0.2, 8
+    first = np.stack([inputs.uniform_cube(300 + b, N) for b in range(B)])
+    second = np.stack([inputs.uniform_cube(310 + b, N) for b in range(B)])
+    x1, x2 = dev(first), dev(second)
+    cache = fp.new_bq_cache(x1, n)
+    idx1 = fp.fps_exact(x1, n, bq_cache=cache, bq_radius=radius)
+    idx2, info = fp.fps_exact(x2, n, start_idx=[0, N + 5], want_info=True, bq_cache=cache, bq_radius=radius)
+    torch.cuda.synchronize()
+    st = [i.status for i in fp.parse_info(info)]
+    assert st == [0, 1] and bool((idx2[1] == -1).all())
+    # centres: the first call's samples (what the stale rows were recorded for) on the new coordinates
+    centres = torch.stack([idx2[0], idx1[1]]).contiguous()
+    got, cnt = fp.ball_query(x2, centres, radius, k, bq_cache=cache)
+    torch.cuda.synchronize()
+    for b in range(B):
+        wq, wc = ref.ball_query(second[b], centres[b].cpu().numpy(), radius, k)
+        assert np.array_equal(got[b].cpu().numpy(), wq) and np.array_equal(cnt[b].cpu().numpy(), wc), "cloud %d" % b
