@@ -45,6 +45,7 @@ KNN_K = 3                         # neighbours of the up-sampling step (Section 
 # entries per cloud of the ball-query cache (blocks of 64 radius tests that found a point); 0 = the
 # library's default of 2 N + 16 n.  The LiDAR-like clouds have balls of several thousand points.
 BQ_CACHE_ENTRIES = {"C4": 10 * 120000}
+EXCL_MEMBER_BUDGET = 64 << 30      # bytes of exclusion-list members the benchmark is willing to build
 CPU_SAMPLE_N = 4096               # cpu_baseline on C4 / C5: samples of each sampler that are timed ...
 CPU_SAMPLE_M = 4096               # ... and ball-query centres
 EAGER = "one stream, eager launches"
@@ -329,8 +330,24 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
                       "last_level_exhausted": int(sum(1 for i in minfos if i.et_index < n)),
                       "curve_mape_percent": mlp_estimator.table()[ctx["name"]][s].get("mape_percent_workload"),
                       "bias": mprm.bias}
+        # MDPS with the estimator exactly as Appendix A.3 defines it (a / x^e, no per-segment
+        # factors; exponent and bias fitted the same way): latency and sampling quality
+        pprm = calibration_module().params_for(ctx["name"], s, "paper")
+        pp = time_call(torch, lambda: fp.mdps_sample(x, n, pprm, want_info=True))
+        pcov = fp.coverage2(x, pp[1][0]).sqrt() / cov_f
+        torch.cuda.synchronize()
+        pinfos = fp.parse_info(pp[1][1])
+        ms["mdps_sample_paper_estimator"] = pp[0]
+        paper_detail = {"coverage_ratio_max": float(pcov.max()), "coverage_ratio_mean": float(pcov.mean()),
+                        "fps_tail_fraction_mean": float(sum((n - i.et_index) / n for i in pinfos) / len(pinfos)),
+                        "last_level_exhausted": int(sum(1 for i in pinfos if i.et_index < n)),
+                        "sample_spacing_ratio": sample_spacing(torch, fp, x, pp[1][0]) / sample_spacing(torch, fp, x, idx),
+                        "bias": pprm.bias, "exponent": pprm.exponent}
         ex = time_excl_lists(torch, fp, x, sg, infos, midx, mbq)
-        if ex is not None:
+        if not ex["built"]:
+            roof["excl_lists_build"] = {"built": False, "members": ex["members"], "levels": ex["levels"],
+                                        "reason": ex["reason"]}
+        else:
             ms["excl_lists_count"], ms["excl_lists_fill"] = ex["count_ms"], ex["fill_ms"]
             # the lists have to be written once and the points read once
             byts = 4.0 * ex["members"] + 8.0 * ex["rows"] + 12.0 * B * N
@@ -365,8 +382,14 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             "mdps_speedup_vs_fps": ms.get("fps_exact", 0.0) / ms["mdps_sample+record"] if ms.get("mdps_sample+record") else None,
             "cached_ball_query_equals_brute": cached_equal,
             "mdps_mlp_estimator": mlp_detail,
+            "mdps_paper_estimator": paper_detail,
             "roofline": roof})
     return out
+
+
+def calibration_module():
+    from paper_2507_23480_amd import calibration
+    return calibration
 
 
 def sample_spacing(torch, fp, x, sidx):
@@ -403,11 +426,12 @@ def time_excl_lists(torch, fp, x, sg, infos, midx, mbq, reps=3):
     """Exclusion lists of a stage as a data structure (the list-building loops of Alg. 2): one level per MDPS
     threshold of each cloud plus the ball-query radius; count and fill passes timed apart, and
     the stage's ball query answered by lookup in the extra level.  Not part of the timed step.
-    Skipped for clouds whose lists would not be built in practice (N above 200 000)."""
+    The count pass always runs (it sizes the member array).  When the members would take more than
+    EXCL_MEMBER_BUDGET bytes the lists are not built: the result then says how many members there
+    are and what they would need (the large single cloud: its first-level radius spans whole
+    clusters)."""
     import numpy as np
     B, N = x.shape[0], x.shape[1]
-    if N > 200000:
-        return None
     lib = fp.load()
     nseg = sg["prm"].nseg
     r2 = np.float32(sg["radius"]) * np.float32(sg["radius"])
@@ -438,6 +462,11 @@ def time_excl_lists(torch, fp, x, sg, infos, midx, mbq, reps=3):
     count()
     torch.cuda.synchronize()
     total = int(off[-1].item())
+    if 4 * total > EXCL_MEMBER_BUDGET:
+        return {"built": False, "count_ms": timed(count) if N <= 200000 else None, "members": total,
+                "rows": L * B * N, "levels": L,
+                "reason": "%d members would take %.1f GB, above the benchmark's budget of %.0f GB for this "
+                          "structure" % (total, 4.0 * total / 1e9, EXCL_MEMBER_BUDGET / 1e9)}
     ent = torch.empty(max(total, 1), dtype=torch.int32, device=x.device)
 
     def fill():
@@ -445,7 +474,8 @@ def time_excl_lists(torch, fp, x, sg, infos, midx, mbq, reps=3):
                             ws.data_ptr(), ws.numel(), st):
             raise RuntimeError("fp_excl_fill failed")
 
-    res = {"count_ms": timed(count), "fill_ms": timed(fill), "members": total, "rows": L * B * N, "levels": L}
+    res = {"built": True, "count_ms": timed(count), "fill_ms": timed(fill), "members": total, "rows": L * B * N,
+           "levels": L}
     idx, cnt = fp.ball_query_lists(off, ent, B, N, L, nseg, midx, sg["k"])
     torch.cuda.synchronize()
     res["lookup_ok"] = bool(torch.equal(idx, mbq[0]) and torch.equal(cnt, mbq[1]))
@@ -518,12 +548,11 @@ def cpu_baseline(inputs, name, budget_s=12.0):
         step_s = wl.B * ((st.n - 1) * float(wl.N) * (1.0 / fps_rate + 1.0 / mdps_rate) +
                          2.0 * st.n * float(wl.N) / bq_rate)
         return {"value": wl.B * wl.N / step_s / 1e6, "unit": "Mpoints/s", "cores": 1, "kind": "oracle",
-                "sample": "RATES, not a full run: on cloud 0 of %s at full N = %d the first %d samples of "
-                          "fps_exact (%.1f s) and of mdps_sample (%.1f s) and the ball query of %d centres "
-                          "(%.1f s); the step (B = %d, n = %d, M = n, both paths) extrapolated linearly in "
-                          "samples and centres" % (name, wl.N, ns, t1 - t0, t2 - t1, ms, t3 - t2, wl.B, st.n),
-                "fps_point_iterations_per_s": fps_rate, "mdps_point_iterations_per_s": mdps_rate,
-                "ball_query_pair_tests_per_s": bq_rate, "ms_per_step_extrapolated": step_s * 1e3}
+                "sample": "RATES, not a full run: cloud 0 of %s at full N, first %d samples of fps_exact "
+                          "(%.1f s) and mdps_sample (%.1f s), ball query of %d centres (%.1f s); step "
+                          "extrapolated linearly in samples and centres" % (name, ns, t1 - t0, t2 - t1, ms, t3 - t2),
+                "fps_point_iterations_per_s": round(fps_rate), "mdps_point_iterations_per_s": round(mdps_rate),
+                "ball_query_pair_tests_per_s": round(bq_rate), "ms_per_step_extrapolated": round(step_s * 1e3)}
 
     done_points = 0
     clouds = 0
@@ -650,8 +679,14 @@ def path_summary(wl, detail, ms_per_step, launch_mode, roof):
             "mdps_plus_grid_query_ms": round(fast_grid, 4),
             "exact_Mpoints_s": round(pts / (exact * 1e-3), 2), "fastpoint_Mpoints_s": round(pts / (fast * 1e-3), 2),
             "mdps_coverage_ratio_max": round(max(st["mdps_coverage_ratio_max"] for st in detail["stages"]), 4),
+            # the estimator as the paper defines it (level_scale = 1): worst coverage ratio, share of the
+            # samples left to the exact iterations after early termination (stage 0)
+            "paper_est_coverage_max": round(max(st["mdps_paper_estimator"]["coverage_ratio_max"]
+                                                for st in detail["stages"]), 4),
+            "paper_est_fps_tail": round(s0["mdps_paper_estimator"]["fps_tail_fraction_mean"], 4),
+            "fps_tail": round(s0["mdps_fps_tail_fraction_mean"], 4),
             "mdps_over_fps_time": round(s0["kernel_ms"]["mdps_sample"] / s0["kernel_ms"]["fps_exact"], 3),
-            "dominant_kernel": roof["kernel"], "dominant_frac": round(roof["frac"], 4)}
+            "dominant_kernel": roof["kernel"].replace(" (stage 0)", ""), "dominant_frac": round(roof["frac"], 4)}
 
 
 def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
@@ -699,9 +734,9 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
     summary = path_summary(wl, detail, ms_per_step, launch_mode, roof)
     workloads = dict(extra)
     workloads[name] = summary
-    short_roof = {key: roof[key] for key in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel",
-                                               "ms_per_launch", "plain_fp32_rate_measured",
-                                               "frac_of_plain_fp32_rate", "compute_units_in_use", "bytes")
+    short_roof = {key: (round(roof[key], 5) if isinstance(roof[key], float) else roof[key])
+                  for key in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "ms_per_launch",
+                              "plain_fp32_rate_measured", "frac_of_plain_fp32_rate", "compute_units_in_use", "bytes")
                   if key in roof}
     line = {
         "metric": "FPS+ball-query latency per batch (ms) and Mpoints/s; achieved HBM GB/s vs peak",
@@ -711,8 +746,8 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (name, wl.description), "B": wl.B, "N": wl.N,
                    "stages": [{"n": st.n, "radius": st.radius, "k": st.k} for st in wl.stages],
-                   "step": "per stage both paths: fps_exact + ball_query(brute) [+ gather]; "
-                           "mdps_sample(recording radius tests) + ball_query(from the record)",
+                   "step": "per stage: fps_exact + ball_query(brute) [+ gather]; "
+                           "mdps_sample(+record) + ball_query(from record)",
                    "launch": launch_mode, "mdps": {"p": calibration.P_RATIO, "nseg": calibration.NSEG}},
         "paths": {"exact_path_ms": summary["exact_path_ms"], "fastpoint_path_ms": summary["fastpoint_path_ms"],
                   "exact_Mpoints_s": summary["exact_Mpoints_s"],
@@ -736,7 +771,7 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
         json.dump(full, f, indent=1)
         f.write("\n")
     text = json.dumps(line)
-    if len(text) > 4000:                       # the driver reads the tail of stdout: keep the line short
+    if len(text) > 3900:                       # the driver reads the tail of stdout: keep the line short
         for key in ("detail_file",):
             line.pop(key, None)
         for w in line["workloads"].values():

@@ -69,15 +69,33 @@ def run(name: str, log=print) -> List[dict]:
                 % (p, nseg, t, t_fps, rows[-1]["coverage_ratio_max"], 100 * rows[-1]["fps_tail_mean"]))
     finally:
         calibration.P_RATIO, calibration.NSEG = keep
+    # the two other estimators at the default p and nseg: the pure power function of Appendix A.3
+    # (no per-segment factors) and the MLP of the same appendix
+    from . import mlp_estimator
+    for label, prm in (("pure power function", calibration.params_for(name, 0, "paper")),
+                       ("MLP", mlp_estimator.params_for(name, 0))):
+        idx, info = fp.mdps_sample(x, st.n, prm, want_info=True)
+        cov = fp.coverage2(x, idx).sqrt() / cov_f
+        torch.cuda.synchronize()
+        infos = fp.parse_info(info)
+        t = _time(torch, lambda: fp.mdps_sample(x, st.n, prm))
+        rows.append({"p": prm.p, "nseg": prm.nseg, "exponent": prm.exponent, "bias": prm.bias, "estimator": label,
+                     "mdps_ms": t, "fps_ms": t_fps, "coverage_ratio_max": float(cov.max()),
+                     "coverage_ratio_mean": float(cov.mean()),
+                     "fps_tail_mean": float(np.mean([(st.n - i.et_index) / st.n for i in infos])),
+                     "rounds_mean": float(np.mean([i.rounds for i in infos]))})
+        log("%s: mdps %.3f ms, coverage max %.4f, tail %.1f %%"
+            % (label, t, rows[-1]["coverage_ratio_max"], 100 * rows[-1]["fps_tail_mean"]))
     return rows
 
 
 def markdown(name: str, rows: List[dict]) -> str:
-    out = ["| workload | p | nseg | exponent | bias | mdps_sample ms | fps_exact ms | coverage / FPS (max) | "
-           "coverage / FPS (mean) | exact-FPS tail | rounds |", "|---|---|---|---|---|---|---|---|---|---|---|"]
+    out = ["| workload | estimator | p | nseg | exponent | bias | mdps_sample ms | fps_exact ms | coverage / FPS (max) | "
+           "coverage / FPS (mean) | exact-FPS tail | rounds |", "|---|---|---|---|---|---|---|---|---|---|---|---|"]
     for r in rows:
-        out.append("| %s | %.2f | %d | %.3f | %.2f | %.3f | %.3f | %.4f | %.4f | %.1f %% | %.0f |"
-                   % (name, r["p"], r["nseg"], r["exponent"], r["bias"], r["mdps_ms"], r["fps_ms"],
+        out.append("| %s | %s | %.2f | %d | %.3f | %.2f | %.3f | %.3f | %.4f | %.4f | %.1f %% | %.0f |"
+                   % (name, r.get("estimator", "power function x segment factors"), r["p"], r["nseg"],
+                      r["exponent"], r["bias"], r["mdps_ms"], r["fps_ms"],
                       r["coverage_ratio_max"], r["coverage_ratio_mean"], 100 * r["fps_tail_mean"], r["rounds_mean"]))
     return "\n".join(out)
 
@@ -85,7 +103,7 @@ def markdown(name: str, rows: List[dict]) -> str:
 def main(argv: List[str]) -> int:
     for name in argv or ["C3"]:
         rows = run(name)
-        print(markdown(name, rows))
+        print(markdown(name, rows), flush=True)
     return 0
 
 

@@ -19,8 +19,13 @@ Per (workload, stage) the fit produces
                unbounded, an over-estimate only costs extra exact FPS iterations.
                BIAS_MARGIN is added on top for clouds the fit has not seen.
 
-Run  python -m paper_2507_23480_amd.calibration  on a GPU machine to rewrite
-mdps_calibration.json next to this file.
+Two tables are kept.  mdps_calibration.json holds the fit above: the power function of the
+appendix extended by the per-segment factors.  mdps_calibration_paper.json holds the estimator
+exactly as the appendix defines it -- a / x^e with a from the measured prefix, level_scale = 1
+everywhere -- with only the exponent and the safety factor `bias` fitted the same way.
+
+Run  python -m paper_2507_23480_amd.calibration [--paper] [workloads]  on a GPU machine to rewrite
+mdps_calibration.json (or, with --paper, mdps_calibration_paper.json) next to this file.
 """
 from __future__ import annotations
 
@@ -34,26 +39,28 @@ import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 TABLE_PATH = os.path.join(HERE, "mdps_calibration.json")
+PAPER_TABLE_PATH = os.path.join(HERE, "mdps_calibration_paper.json")
 
 CALIBRATION_CLOUDS = {"C1": 8, "C2": 32, "C3": 8, "C4": 8, "C5": 3}
 P_RATIO, NSEG, FIT_WINDOW, M_MIN = 0.1, 6, 32, 8
 BIAS_MARGIN = 0.02
 
-_table = None
+_tables = {}
 
 
-def table() -> Dict[str, List[dict]]:
-    global _table
-    if _table is None:
-        with open(TABLE_PATH) as f:
-            _table = json.load(f)
-    return _table
+def table(variant: str = "calibrated") -> Dict[str, List[dict]]:
+    """The fitted constants: "calibrated" (power function with per-segment factors) or "paper"
+    (the pure power function of Appendix A.3)."""
+    if variant not in _tables:
+        with open(TABLE_PATH if variant == "calibrated" else PAPER_TABLE_PATH) as f:
+            _tables[variant] = json.load(f)
+    return _tables[variant]
 
 
-def params_for(workload: str, stage: int):
+def params_for(workload: str, stage: int, variant: str = "calibrated"):
     """MdpsParams with the fitted constants of one workload stage."""
     from . import binding
-    ent = table()[workload][stage]
+    ent = table(variant)[workload][stage]
     return binding.MdpsParams(p=P_RATIO, nseg=NSEG, exponent=ent["exponent"], bias=ent["bias"],
                               fit_window=FIT_WINDOW, m_min=M_MIN, level_scale=ent["level_scale"])
 
@@ -62,8 +69,9 @@ def _boundaries(n: int) -> List[int]:
     return [min(max(n * l // NSEG, 1), n - 1) for l in range(1, NSEG + 1)]
 
 
-def fit_stage(xyz, n: int, log=print) -> dict:
-    """xyz: CUDA float32 [Bc][N][3] calibration clouds of one stage."""
+def fit_stage(xyz, n: int, log=print, pure: bool = False) -> dict:
+    """xyz: CUDA float32 [Bc][N][3] calibration clouds of one stage.  pure: no per-segment factors
+    (the estimator as Appendix A.3 defines it)."""
     import torch
     from . import binding as fp
     idx, mdc = fp.fps_exact(xyz, n, want_mdc=True)
@@ -90,7 +98,7 @@ def fit_stage(xyz, n: int, log=print) -> dict:
             if x > m:
                 ratios[b, l] = c[x] / (a / float(x) ** e)
     scale = np.exp(np.mean(np.log(ratios), axis=0))
-    scale = [float(round(s, 4)) for s in scale]
+    scale = [1.0] * NSEG if pure else [float(round(s, 4)) for s in scale]
     # spread of the last level decides where the bias search starts
     spread = float(np.max(np.sqrt(scale[-1] / ratios[:, -1])))
     bias = max(1.01, round(spread, 2))
@@ -117,7 +125,7 @@ def fit_stage(xyz, n: int, log=print) -> dict:
             "calibration_tail_mean": round(tail, 4), "calibration_worst_coverage_ratio": round(worst, 4)}
 
 
-def calibrate_workload(name: str, log=print) -> List[dict]:
+def calibrate_workload(name: str, log=print, pure: bool = False) -> List[dict]:
     import torch
     from . import binding as fp, inputs
     wl = inputs.WORKLOADS[name]
@@ -126,7 +134,7 @@ def calibrate_workload(name: str, log=print) -> List[dict]:
     out = []
     for s, st in enumerate(wl.stages):
         log("%s stage %d: %d calibration clouds of %d points -> %d samples" % (name, s, Bc, xyz.shape[1], st.n))
-        ent = fit_stage(xyz, st.n, log)
+        ent = fit_stage(xyz, st.n, log, pure)
         log("    exponent %.4f bias %.2f scale %s" % (ent["exponent"], ent["bias"], ent["level_scale"]))
         out.append(ent)
         if s + 1 < len(wl.stages):          # the next stage's input: the exact-FPS samples
@@ -135,14 +143,16 @@ def calibrate_workload(name: str, log=print) -> List[dict]:
 
 
 def main(argv: List[str]) -> int:
-    names = argv or list(CALIBRATION_CLOUDS)
+    pure = "--paper" in argv
+    names = [a for a in argv if not a.startswith("--")] or list(CALIBRATION_CLOUDS)
+    path = PAPER_TABLE_PATH if pure else TABLE_PATH
     result = {}
-    if os.path.exists(TABLE_PATH):
-        with open(TABLE_PATH) as f:
+    if os.path.exists(path):
+        with open(path) as f:
             result = json.load(f)
-    out_path = os.environ.get("FASTPOINT_CALIBRATION_OUT", TABLE_PATH)
+    out_path = os.environ.get("FASTPOINT_CALIBRATION_OUT", path)
     for name in names:
-        result[name] = calibrate_workload(name)
+        result[name] = calibrate_workload(name, pure=pure)
         with open(out_path, "w") as f:
             json.dump(result, f, indent=1, sort_keys=True)
             f.write("\n")

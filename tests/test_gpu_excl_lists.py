@@ -2,6 +2,7 @@
 Section 4.2) and of the ball query by lookup, through the C ABI, against the CPU oracle:
 offsets and members bit-exact (the lists are index sets decided by binary32 comparisons)."""
 import ctypes
+import os
 import sys
 from concurrent.futures import ThreadPoolExecutor
 
@@ -322,6 +323,57 @@ def test_lidar_cloud_at_full_size(fp):
                 assert b - a == wcnt[t]
                 assert np.array_equal(ent[a:b].cpu().numpy(), widx[t, :wcnt[t]]), "members, level %d point %d" % (l, i)
         say("   level %d: members of %d sampled rows (longest %d) equal the oracle's" % (l, len(picks), kmax - 1))
+
+
+def test_million_point_cloud_sampled_rows(fp):
+    """The large single cloud (10^6 points, 200 clusters) with the levels of its own MDPS run and the
+    ball-query radius: about 10^10 members (40 GB), which the device memory holds.  The all-pairs
+    oracle is out of reach at this size; the rows of points sampled over the whole index range are
+    compared with the oracle's ball query (a row is the ball of its point) on every level, and every
+    row's size with the number of members the oracle finds."""
+    gold = np.load(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "c5_full.npz"))
+    wl = inputs.WORKLOADS["C5"]
+    st = wl.stages[0]
+    N = wl.N
+    cloud = inputs.make_cloud("C5", 0)
+    radii2 = [np.float32(v) for v in gold["thr2_calibrated"][0]] + [np.float32(st.radius) * np.float32(st.radius)]
+    thr = np.array([radii2], dtype=np.float32)
+    L = thr.shape[1]
+    free, _ = torch.cuda.mem_get_info()
+    x = dev(cloud[None])
+    say("excl lists, C5 at full size: N=%d, %d levels" % (N, L))
+    lib = fp.load()
+    ws = torch.empty(lib.fp_excl_workspace_bytes(1, N, L), dtype=torch.uint8, device="cuda")
+    off = torch.empty(L * N + 1, dtype=torch.int64, device="cuda")
+    t = dev(thr)
+    s = torch.cuda.current_stream().cuda_stream
+    assert lib.fp_excl_count(x.data_ptr(), 1, N, t.data_ptr(), L, off.data_ptr(), ws.data_ptr(), ws.numel(), s) == 0
+    torch.cuda.synchronize()
+    total = int(off[-1].item())
+    say("   %d members (%.1f GB)" % (total, 4.0 * total / 1e9))
+    if 4 * total + (8 << 30) > free:
+        pytest.skip("not enough free device memory for the members of this cloud")
+    ent = torch.empty(total, dtype=torch.int32, device="cuda")
+    assert lib.fp_excl_fill(x.data_ptr(), 1, N, t.data_ptr(), L, off.data_ptr(), ent.data_ptr(), ctypes.c_int64(total),
+                            ws.data_ptr(), ws.numel(), s) == 0
+    torch.cuda.synchronize()
+    off_h = off.cpu().numpy()
+    rng = np.random.Generator(np.random.PCG64(45))
+    picks = np.unique(np.concatenate([rng.integers(0, N, 150), np.arange(0, N, N // 50)])).astype(np.int32)
+    for l in range(L):
+        radius = float(np.sqrt(np.float64(radii2[l])))
+        if np.float32(radius) * np.float32(radius) != np.float32(radii2[l]):
+            continue        # no binary32 radius squares to this level's value: no ball query gives the row
+        sizes = off_h[l * N + picks + 1] - off_h[l * N + picks]
+        kmax = int(sizes.max()) + 1
+        for c0 in range(0, len(picks), 32):
+            chunk = picks[c0:c0 + 32]
+            widx, wcnt = ref.ball_query(cloud, chunk, radius, kmax)
+            for tt, i in enumerate(chunk):
+                a, b = int(off_h[l * N + i]), int(off_h[l * N + i + 1])
+                assert b - a == wcnt[tt], "row size, level %d point %d" % (l, i)
+                assert np.array_equal(ent[a:b].cpu().numpy(), widx[tt, :wcnt[tt]]), "members, level %d point %d" % (l, i)
+        say("   level %d: %d sampled rows (longest %d) equal the oracle's" % (l, len(picks), kmax - 1))
 
 
 def test_clouds_too_large_for_the_lists_are_refused(fp):

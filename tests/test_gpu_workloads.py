@@ -88,6 +88,10 @@ def test_full_workload_matches_oracle(fp, cal, name):
         midx, info = fp.mdps_sample(xyz, st.n, prm, want_info=True, bq_cache=cache, bq_radius=st.radius)
         mbq, mcnt = fp.ball_query(xyz, midx, st.radius, st.k, bq_cache=cache)
         cov_f, cov_m = fp.coverage2(xyz, idx).sqrt(), fp.coverage2(xyz, midx).sqrt()
+        # the estimator exactly as Appendix A.3 defines it (no per-segment factors)
+        pprm = cal.params_for(name, s, "paper")
+        pidx, pinfo = fp.mdps_sample(xyz, st.n, pprm, want_info=True)
+        cov_p = fp.coverage2(xyz, pidx).sqrt()
         kpos, kd2 = fp.knn(xyz, idx, KNN_K)
         mkpos, mkd2, deferred = fp.knn(xyz, midx, KNN_K, bq_cache=cache, want_deferred=True)
         torch.cuda.synchronize()
@@ -96,7 +100,10 @@ def test_full_workload_matches_oracle(fp, cal, name):
         idx, mdc, bq, cnt = idx.cpu().numpy(), mdc.cpu().numpy(), bq.cpu().numpy(), cnt.cpu().numpy()
         midx, mbq, mcnt = midx.cpu().numpy(), mbq.cpu().numpy(), mcnt.cpu().numpy()
         infos = fp.parse_info(info)
+        pinfos = fp.parse_info(pinfo)
+        pidx = pidx.cpu().numpy()
         rp = rparams(prm)
+        rpp = rparams(pprm)
 
         def one(b):
             widx, wmdc = ref.fps_exact(batch[b], st.n)
@@ -104,8 +111,11 @@ def test_full_workload_matches_oracle(fp, cal, name):
             wmidx, winfo = ref.mdps_sample(batch[b], st.n, rp)
             wmbq, wmcnt = ref.ball_query(batch[b], wmidx, st.radius, st.k)
             return widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt, ref.knn(batch[b], widx, KNN_K), \
-                ref.knn(batch[b], wmidx, KNN_K)
-        for b, (widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt, wk, wmk) in enumerate(pmap(one, range(wl.B))):
+                ref.knn(batch[b], wmidx, KNN_K), ref.mdps_sample(batch[b], st.n, rpp)
+        for b, (widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt, wk, wmk, wp) in enumerate(pmap(one, range(wl.B))):
+            assert np.array_equal(pidx[b], wp[0]), "mdps with the pure power function, cloud %d" % b
+            assert pinfos[b].status == 0 and pinfos[b].et_index == wp[1].et_index
+            assert np.array_equal(np.array(pinfos[b].thr2[:pprm.nseg], np.float32), wp[1].thr2)
             assert np.array_equal(kpos[b], wk[0]) and np.array_equal(kd2[b], wk[1]), "brute k-NN cloud %d" % b
             assert np.array_equal(mkpos[b], wmk[0]) and np.array_equal(mkd2[b], wmk[1]), "cached k-NN cloud %d" % b
             assert np.array_equal(idx[b], widx) and np.array_equal(mdc[b], wmdc), "fps cloud %d" % b
@@ -115,8 +125,10 @@ def test_full_workload_matches_oracle(fp, cal, name):
             assert np.array_equal(np.array(infos[b].thr2[:prm.nseg], np.float32), winfo.thr2)
             assert np.array_equal(mbq[b], wmbq) and np.array_equal(mcnt[b], wmcnt), "cached bq cloud %d" % b
         ratio = (cov_m / cov_f).cpu().numpy()
-        say("   coverage ratio max %.4f" % ratio.max())
-        assert ratio.max() <= COVERAGE_BOUND
+        pratio = (cov_p / cov_f).cpu().numpy()
+        say("   coverage ratio max %.4f; pure power function (bias %.2f): %.4f, FPS tail %.1f%% of the samples"
+            % (ratio.max(), pprm.bias, pratio.max(), 100.0 * np.mean([(st.n - i.et_index) / st.n for i in pinfos])))
+        assert ratio.max() <= COVERAGE_BOUND and pratio.max() <= COVERAGE_BOUND
         if s + 1 < len(wl.stages):
             batch = np.stack([ref.gather_xyz(batch[b], idx[b]) for b in range(wl.B)])
 
@@ -135,7 +147,7 @@ def check_against_stored_oracle(fp, name, xyz, idx, mdc):
     assert np.array_equal(idx, gold["fps_idx"]), "%s exact FPS: samples differ from the stored oracle result" % name
     assert np.array_equal(mdc, gold["fps_mdc"]), "%s exact FPS: curve differs from the stored oracle result" % name
     variants = sorted(k[len("params_"):] for k in gold if k.startswith("params_"))
-    assert "calibrated" in variants
+    assert "calibrated" in variants and "paper" in variants
     for v in variants:
         p = json.loads(str(gold["params_" + v]))
         prm = fp.MdpsParams(p=p["p"], nseg=p["nseg"], exponent=p["exponent"], bias=p["bias"],
@@ -150,8 +162,12 @@ def check_against_stored_oracle(fp, name, xyz, idx, mdc):
             assert np.array_equal(np.array(gi.thr2[:prm.nseg], np.float32), gold["thr2_" + v][b])
             assert np.array_equal(np.array(gi.level_start[:prm.nseg]), gold["level_start_" + v][b])
             assert np.array_equal(np.array(gi.level_exhausted[:prm.nseg]), gold["level_exhausted_" + v][b])
-        say("   %s constants: all %d x %d MDPS samples equal the stored oracle result (FPS tail %s)"
-            % (v, wl.B, n, [n - int(e) for e in gold["et_index_" + v]]))
+        cov = fp.coverage2(xyz, midx).sqrt() / fp.coverage2(xyz, torch.from_numpy(gold["fps_idx"]).cuda()).sqrt()
+        torch.cuda.synchronize()
+        say("   %s constants (bias %.2f): all %d x %d MDPS samples equal the stored oracle result, FPS tail %s, "
+            "coverage ratio max %.4f" % (v, p["bias"], wl.B, n, [n - int(e) for e in gold["et_index_" + v]],
+                                          float(cov.max())))
+        assert float(cov.max()) <= COVERAGE_BOUND
     return gold
 
 
