@@ -213,33 +213,51 @@ __device__ __forceinline__ void group_scatter(const BqHeader* h, const unsigned 
 }
 
 // off[b][0 .. keys] = exclusive prefix sums of cnt[b][0 .. keys); cnt is set back to zero (the
-// scatter pass counts up again).  By the 1024 threads of one workgroup; a thread owns a run of keys.
-__device__ __forceinline__ void group_scan(int b, int32_t* cnt, uint32_t* off, int keys, uint32_t* part)
+// scatter pass counts up again).  By the 1024 threads of one workgroup (all of them call): the keys
+// are taken 4096 at a time, four consecutive ones per thread (so that the threads of a wave read
+// consecutive memory), scanned inside the wave by shuffles and across the 16 waves through LDS.
+__device__ __forceinline__ void group_scan(int b, int32_t* cnt, uint32_t* off, int keys, uint32_t* wsum)
 {
     const int tid = (int)threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     int32_t* c = cnt + (int64_t)b * keys;
     uint32_t* o = off + (int64_t)b * ((int64_t)keys + 1);
-    const int per = (keys + 1023) / 1024;
-    const int k0 = (int64_t)tid * per < keys ? tid * per : keys;
-    const int k1 = (int64_t)k0 + per < keys ? k0 + per : keys;
-    uint32_t sum = 0;
-    for (int t = k0; t < k1; ++t)
-        sum += (uint32_t)__hip_atomic_load(c + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    part[tid] = sum;
-    __syncthreads();
-    for (int sft = 1; sft < 1024; sft <<= 1) {
-        const uint32_t v = tid >= sft ? part[tid - sft] : 0u;
+    uint32_t carry = 0;
+    for (int base = 0; base < keys; base += 4096) {
+        const int k0 = base + tid * 4;
+        uint32_t v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            v[i] = k0 + i < keys ? (uint32_t)__hip_atomic_load(c + k0 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        const uint32_t mine = v[0] + v[1] + v[2] + v[3];
+        uint32_t incl = mine;
+#pragma unroll
+        for (int sft = 1; sft < 64; sft <<= 1) {
+            const uint32_t up = (uint32_t)__shfl_up((int)incl, sft, 64);
+            if (lane >= sft) incl += up;
+        }
+        if (lane == 63) wsum[wave] = incl;
         __syncthreads();
-        part[tid] += v;
-        __syncthreads();
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const uint32_t t = wsum[w];
+            before += w < wave ? t : 0u;
+            total += t;
+        }
+        uint32_t run = carry + before + incl - mine;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (k0 + i < keys) {
+                o[k0 + i] = run;
+                __hip_atomic_store(c + k0 + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            run += v[i];
+        }
+        carry += total;
+        __syncthreads();                 // wsum is written again in the next turn
     }
-    uint32_t run = part[tid] - sum;
-    for (int t = k0; t < k1; ++t) {
-        __hip_atomic_store(o + t, run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        run += (uint32_t)__hip_atomic_load(c + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(c + t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    if (tid == 1023) o[keys] = part[1023];
+    if (tid == 0) o[keys] = carry;
 }
 
 template <bool BY_BLOCK>
@@ -255,8 +273,8 @@ __global__ __launch_bounds__(256) void bq_group_count_kernel(const unsigned char
 __global__ __launch_bounds__(1024) void bq_group_scan_kernel(int32_t* __restrict__ cnt, uint32_t* __restrict__ off,
                                                              int keys)
 {
-    __shared__ uint32_t part[1024];
-    group_scan((int)blockIdx.x, cnt, off, keys, part);
+    __shared__ uint32_t wsum[16];
+    group_scan((int)blockIdx.x, cnt, off, keys, wsum);
 }
 
 template <bool BY_BLOCK>
@@ -279,7 +297,7 @@ __global__ __launch_bounds__(1024) void bq_group_small_kernel(const unsigned cha
                                                               int32_t* __restrict__ cnt, uint32_t* __restrict__ off,
                                                               int keys, BqEntry* __restrict__ rows, int64_t rows_cap)
 {
-    __shared__ uint32_t part[1024];
+    __shared__ uint32_t wsum[16];
     const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
     const int b = (int)blockIdx.x;
     const bool ok = h->magic == kBqMagic && b < h->B;
@@ -288,7 +306,7 @@ __global__ __launch_bounds__(1024) void bq_group_small_kernel(const unsigned cha
     __syncthreads();
     if (ok) group_count<BY_BLOCK>(h, cache, b, cnt, keys, rows_cap, threadIdx.x, 1024);
     __syncthreads();
-    group_scan(b, cnt, off, keys, part);
+    group_scan(b, cnt, off, keys, wsum);
     __syncthreads();
     if (ok) group_scatter<BY_BLOCK>(h, cache, b, cnt, off, keys, rows, rows_cap, threadIdx.x, 1024);
 }
