@@ -51,11 +51,17 @@ CPU_SAMPLE_M = 4096               # ... and ball-query centres
 EAGER = "one stream, eager launches"
 GRAPH = "four streams, step replayed as one HIP graph"
 
-# HBM traffic per launch of the kernels that can dominate the step, from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs (profiles/bench_C2_hbm_traffic.md); bytes, keyed by workload and
-# kernel.  None where no counter run is recorded.
-TRAFFIC_BYTES = {"C2": {"fps_exact": int((408.9 + 32.0) * 1024),
-                        "mdps_sample+record": int((794.9 + 1088.1) * 1024)}}
+# HBM traffic per launch (bytes fetched + written) of the kernels that can dominate the step, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/bench_C5_hbm_traffic.md, bench_C4_hbm_traffic.md,
+# bench_C2_hbm_traffic.md), keyed by workload and kernel.  None where no counter run is recorded.  The
+# samplers keep the cloud in registers: what they move beyond reading it once is the polling of the
+# words exchanged between the workgroups of a cloud.
+TRAFFIC_BYTES = {"C2": {"fps_exact": 454587, "mdps_sample+record": 2344271, "ball_query_cached": 1951986,
+                        "ball_query_brute": 2001511},
+                 "C4": {"fps_exact": 143807600, "mdps_sample+record": 362700744, "ball_query_cached": 38984780,
+                        "ball_query_brute": 90784615},
+                 "C5": {"fps_exact": 292510875, "mdps_sample+record": 390621436, "ball_query_cached": 19478260,
+                        "ball_query_brute": 204118505}}
 
 
 def parse_args():
