@@ -335,49 +335,58 @@ struct RowWords {
 };
 
 // The distance update of Alg. 1 for this thread's points; with BQ also the radius test of Section 4.2: the
-// 64-bit hit mask of every slot goes to lane `s` of `rw`.
-template <int P, bool BQ, int P0>
+// 64-bit hit mask of every slot goes to lane `s` of `rw`.  Most balls miss most waves of a large cloud:
+// there is one test per group of slots on the vector unit (the minimum of the group's distances against
+// the radius), and the per-slot masks are formed only when some point of the group hits.  How they
+// are formed depends on how often that happens.  DENSE (a cloud held by few waves: nearly every ball
+// reaches every wave): from the distances of the update, kept until the test.  Otherwise the
+// distances are worked out once more in the rare branch: kept alive from the update they cost eight
+// registers, and the compiler then moves every running distance of the thread from one register to
+// another once per pick.  (The pick's coordinates pass through an empty asm statement there, so that
+// the second evaluation is not merged with the first.)
+template <int P, bool BQ, bool DENSE, int P0>
 __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float cy, float cz, float bq_r2,
                                             int s, RowWords<P, BQ>& rw)
 {
     constexpr int GRP = P < 8 ? P : 8;      // slots whose radius tests are examined together
     if constexpr (P0 < P) {
-        uint32_t tmin = 0xFFFFFFFFu;        // squared distances as bit patterns (>= +0: unsigned order)
+        uint32_t tb[GRP];                   // squared distances as bit patterns (>= +0: unsigned order)
+        uint32_t tmin = 0xFFFFFFFFu;
 #pragma unroll
         for (int u = 0; u < GRP; ++u) {
             const int p = P0 + u;
-            const uint32_t tb = __float_as_uint(dist2(cx, cy, cz, pt.x[p], pt.y[p], pt.z[p]));
-            pt.d[p] = __uint_as_float(min(__float_as_uint(pt.d[p]), tb));
-            if (BQ) tmin = min(tmin, tb);
+            tb[u] = __float_as_uint(dist2(cx, cy, cz, pt.x[p], pt.y[p], pt.z[p]));
+            pt.d[p] = __uint_as_float(min(__float_as_uint(pt.d[p]), tb[u]));
+            if (BQ) tmin = min(tmin, tb[u]);
         }
         if (BQ) {
-            // most balls miss most waves: one test per group on the vector unit.  Only when some
-            // point of the group hits are the distances worked out once more to form the per-slot
-            // masks: kept from the update above they would stay alive across the test, and the
-            // compiler then moves every running distance of the thread from one register to another
-            // once per pick.  (The pick's coordinates pass through an empty asm statement so that the
-            // second evaluation is not merged with the first.)
             const uint32_t r2b = __float_as_uint(bq_r2);
             if (__builtin_amdgcn_ballot_w64(tmin < r2b) != 0) {
-                float hx = cx, hy = cy, hz = cz;
-                asm volatile("" : "+v"(hx), "+v"(hy), "+v"(hz));
+                if constexpr (DENSE) {
 #pragma unroll
-                for (int u = 0; u < GRP; ++u) {
-                    const int p = P0 + u;
-                    const uint32_t tb = __float_as_uint(dist2(hx, hy, hz, pt.x[p], pt.y[p], pt.z[p]));
-                    rw.row[p * 64 + s] = __builtin_amdgcn_ballot_w64(tb < r2b);
+                    for (int u = 0; u < GRP; ++u)
+                        rw.row[(P0 + u) * 64 + s] = __builtin_amdgcn_ballot_w64(tb[u] < r2b);
+                } else {
+                    float hx = cx, hy = cy, hz = cz;
+                    asm volatile("" : "+v"(hx), "+v"(hy), "+v"(hz));
+#pragma unroll
+                    for (int u = 0; u < GRP; ++u) {
+                        const int p = P0 + u;
+                        const uint32_t again = __float_as_uint(dist2(hx, hy, hz, pt.x[p], pt.y[p], pt.z[p]));
+                        rw.row[p * 64 + s] = __builtin_amdgcn_ballot_w64(again < r2b);
+                    }
                 }
             }
         }
-        fold_groups<P, BQ, P0 + GRP>(pt, cx, cy, cz, bq_r2, s, rw);
+        fold_groups<P, BQ, DENSE, P0 + GRP>(pt, cx, cy, cz, bq_r2, s, rw);
     }
 }
 
-template <int P, bool BQ>
+template <int P, bool BQ, bool DENSE = true>
 __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, float cz,
                                      const SamplerArgs& a, const Where& wh, int s, RowWords<P, BQ>& rw)
 {
-    fold_groups<P, BQ, 0>(pt, cx, cy, cz, a.bq_r2, s, rw);
+    fold_groups<P, BQ, DENSE, 0>(pt, cx, cy, cz, a.bq_r2, s, rw);
 }
 
 // Hands the words of `count` picks (sample positions base, base+1, ...; count <= 64) to the cache.
@@ -797,7 +806,8 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
             const uint64_t nbit = (WIDE && cl >= 64u) ? (near_hi >> (cl - 64u)) : (near >> cl);
             if (!PERM || (nbit & 1ull) != 0) {
                 const Cand c = sh.cand[cl];
-                fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, WIDE ? (s & 63) : s, rw);
+                // narrow rounds are those of clouds held by one or a few workgroups
+                fold<P, BQ, !WIDE>(pt, c.x, c.y, c.z, a, wh, WIDE ? (s & 63) : s, rw);
             }
             ++s;
         }
