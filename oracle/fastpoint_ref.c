@@ -120,6 +120,10 @@ typedef struct {
     const float *mlp;     /* NULL: power-function estimator.  Else the weights of the
                              MLP estimator of App. A.3 (REF_MLP_WEIGHTS floats, layout
                              at ref_mlp_curve)                                       */
+    int32_t scan_order;   /* which available point the threshold phase takes (Sec. 4.1
+                             step 3 says "randomly selected among the available points"):
+                             0 the lowest index; 1 the first in the scattered order of
+                             ref_scan_stride                                         */
 } ref_mdps_params;
 
 typedef struct {
@@ -360,6 +364,58 @@ static int32_t ref_quota_level(int32_t i, int32_t n, int32_t nseg)
 }
 
 /*
+ * Scattered scan order of the threshold phase.  The paper takes a random available point
+ * (Section 4.1 step 3); a fixed pseudo-random order keeps that spirit and stays reproducible:
+ * the points are visited in the order j_t = (t * A) mod N, t = 0, 1, ..., N-1, a walk with the
+ * golden-ratio stride, A = the smallest integer >= max(1, floor(0.6180339887498949 * N)) that has
+ * no common divisor with N (so that the walk visits every point once).  In a cloud whose
+ * neighbours in space are neighbours in the index (scans), consecutive points of the walk lie far
+ * apart.  ref_scan_stride returns A.
+ */
+static int64_t ref_gcd(int64_t a, int64_t b)
+{
+    while (b != 0) {
+        int64_t t = a % b;
+        a = b;
+        b = t;
+    }
+    return a;
+}
+
+int64_t ref_scan_stride(int32_t N)
+{
+    if (N < 1)
+        return 0;
+    int64_t A = (int64_t)floor(0.6180339887498949 * (double)N);
+    if (A < 1)
+        A = 1;
+    while (ref_gcd(A, (int64_t)N) != 1)
+        ++A;
+    return A;
+}
+
+/* The first available point (dists[j] >= r2) in the chosen scan order, -1 if there is none. */
+static int32_t ref_first_available(const float *dists, int32_t N, float r2, int32_t scan_order)
+{
+    if (scan_order == 0) {
+        for (int32_t j = 0; j < N; ++j)
+            if (dists[j] >= r2)
+                return j;
+        return -1;
+    }
+    const int64_t A = ref_scan_stride(N);
+    int64_t j = 0;
+    for (int32_t t = 0; t < N; ++t) {
+        if (dists[j] >= r2)
+            return (int32_t)j;
+        j += A;
+        if (j >= N)
+            j -= N;
+    }
+    return -1;
+}
+
+/*
  * MDPS -- Algorithm 2 (Appendix A.1), running-min-distance form.
  *
  * Availability of point j at level l is kept implicitly: the bitmap bit of
@@ -373,8 +429,9 @@ static int32_t ref_quota_level(int32_t i, int32_t n, int32_t nseg)
  *      samples stay in the output and sampling continues at i = m+1.
  *  S2  thresholds from the estimated curve (the estimator call and the threshold set-up of Alg. 2).
  *  S3  threshold sampling (the main loop of Alg. 2): level = max(level, quota level of i);
- *      pick the lowest-index available point at the current level; if none,
- *      move to the next level without consuming a sample slot.
+ *      pick the first available point of the current level in the scan order (the lowest
+ *      index, or the first of the scattered walk); if none, move to the next level without
+ *      consuming a sample slot.
  *  S4  early termination (the closing part of Alg. 2): once the last level is exhausted the
  *      remaining samples come from exact FPS on the (already current) dists.
  */
@@ -382,7 +439,7 @@ int ref_mdps_sample(const float *xyz, int32_t N, int32_t n, int32_t start,
                     const ref_mdps_params *prm, int32_t *out_idx, ref_mdps_info *info_out)
 {
     if (!xyz || !out_idx || !prm || N < 1 || n < 1 || n > N || start < 0 || start >= N ||
-        prm->nseg < 1 || prm->nseg > REF_MAX_SEG)
+        prm->nseg < 1 || prm->nseg > REF_MAX_SEG || prm->scan_order < 0 || prm->scan_order > 1)
         return -1;
     ref_mdps_info info;
     ref_info_init(&info, n);
@@ -437,12 +494,7 @@ int ref_mdps_sample(const float *xyz, int32_t N, int32_t n, int32_t start,
             ref_fold(xyz, N, out_idx[applied], dists);
         }
         float r2 = info.thr2[seg - 1];
-        int32_t pick = -1;
-        for (int32_t j = 0; j < N; ++j)
-            if (dists[j] >= r2) {
-                pick = j;
-                break;
-            }
+        int32_t pick = ref_first_available(dists, N, r2, prm->scan_order);
         if (pick < 0) {             /* level exhausted */
             info.level_exhausted[seg - 1] = 1;
             ++seg;
@@ -527,12 +579,19 @@ static void lit_exclude(uint8_t *bitmap, const ref_list *excl, int32_t N, int32_
     }
 }
 
-/* "Any available point" of a level is taken to be the lowest index; -1 if the level has none. */
-static int32_t lit_lowest_available(const uint8_t *bitmap, int32_t N, int32_t level)
+/* "Any available point" of a level is taken to be the first set bit in the scan order (the lowest
+ * index, or the first of the scattered walk of ref_scan_stride); -1 if the level has none. */
+static int32_t lit_first_available(const uint8_t *bitmap, int32_t N, int32_t level, int32_t scan_order)
 {
-    for (int32_t j = 0; j < N; ++j)
+    const int64_t A = scan_order == 0 ? 1 : ref_scan_stride(N);
+    int64_t j = 0;
+    for (int32_t t = 0; t < N; ++t) {
         if (bitmap[(size_t)level * N + j])
-            return j;
+            return (int32_t)j;
+        j += A;
+        if (j >= N)
+            j -= N;
+    }
     return -1;
 }
 
@@ -556,7 +615,7 @@ int ref_mdps_literal(const float *xyz, int32_t N, int32_t n, int32_t start,
                      const ref_mdps_params *prm, int32_t *out_idx, ref_mdps_info *info_out)
 {
     if (!xyz || !out_idx || !prm || N < 1 || n < 1 || n > N || start < 0 || start >= N ||
-        prm->nseg < 1 || prm->nseg > REF_MAX_SEG)
+        prm->nseg < 1 || prm->nseg > REF_MAX_SEG || prm->scan_order < 0 || prm->scan_order > 1)
         return -1;
     ref_mdps_info info;
     ref_info_init(&info, n);
@@ -611,7 +670,7 @@ int ref_mdps_literal(const float *xyz, int32_t N, int32_t n, int32_t start,
         if (seg > nseg)
             break;
         lit_exclude(bitmap, excl, N, nseg, seg - 1, out_idx[i - 1]);
-        int32_t pick = lit_lowest_available(bitmap, N, seg - 1);
+        int32_t pick = lit_first_available(bitmap, N, seg - 1, prm->scan_order);
         if (pick < 0) {
             info.level_exhausted[seg - 1] = 1;
             ++seg;

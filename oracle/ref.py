@@ -24,7 +24,7 @@ class _Params(ctypes.Structure):
                 ("bias", ctypes.c_float), ("fit_window", ctypes.c_int32), ("m_min", ctypes.c_int32),
                 ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG),
                 ("level_scale", ctypes.c_float * MAX_SEG),
-                ("mlp", ctypes.POINTER(ctypes.c_float))]
+                ("mlp", ctypes.POINTER(ctypes.c_float)), ("scan_order", ctypes.c_int32)]
 
 
 MLP_WEIGHTS = 32 * 128 + 128 + 128 * 128 + 128 + 128 * 64 + 64
@@ -48,6 +48,7 @@ class MdpsParams:
     thr_override: Optional[Sequence[float]] = None
     level_scale: Optional[Sequence[float]] = None
     mlp: Optional[np.ndarray] = None      # MLP_WEIGHTS float32 weights of the MLP estimator, or None
+    scan_order: int = 0                   # threshold phase: 0 lowest available index, 1 scattered walk
 
     def to_c(self) -> _Params:
         c = _Params()
@@ -64,6 +65,7 @@ class MdpsParams:
                 c.level_scale[i] = v
         c.p, c.nseg, c.exponent, c.bias = self.p, self.nseg, self.exponent, self.bias
         c.fit_window, c.m_min = self.fit_window, self.m_min
+        c.scan_order = self.scan_order
         c.use_override = 0
         if self.thr_override is not None:
             assert len(self.thr_override) == self.nseg
@@ -100,6 +102,8 @@ def lib() -> ctypes.CDLL:
         _lib.ref_exp_fixed.argtypes = [ctypes.c_double]
         _lib.ref_exp_fixed.restype = ctypes.c_double
         _lib.ref_mlp_curve.argtypes = [fp, i32, fp, ctypes.POINTER(ctypes.c_double)]
+        _lib.ref_scan_stride.argtypes = [i32]
+        _lib.ref_scan_stride.restype = ctypes.c_int64
         _lib.ref_mdps_prefix_len.argtypes = [ctypes.POINTER(_Params), i32]
         _lib.ref_mdps_thresholds.argtypes = [fp, i32, i32, ctypes.POINTER(_Params), fp]
         _lib.ref_mdps_sample.argtypes = [fp, i32, i32, i32, ctypes.POINTER(_Params), ip,
@@ -166,6 +170,11 @@ def mlp_curve(mdc, m: int, weights) -> np.ndarray:
     if rc != 0:
         raise ValueError("ref_mlp_curve rejected its arguments")
     return out
+
+
+def scan_stride(N: int) -> int:
+    """Stride A of the scattered scan order j_t = (t * A) mod N of a cloud of N points."""
+    return int(lib().ref_scan_stride(int(N)))
 
 
 def mdps_prefix_len(prm: MdpsParams, n: int) -> int:

@@ -239,3 +239,69 @@ def test_calibrated_sampling_quality_is_close_to_fps():
     assert info.level_exhausted[-1] == 1
     assert ref.coverage_radius(xyz, idx) <= 1.05 * ref.coverage_radius(xyz, fps)
     assert ref.mean_spacing(xyz, idx) >= 0.97 * ref.mean_spacing(xyz, fps)
+
+
+# ------------------------------------------------------------------ scattered scan order
+def test_scattered_order_hand_examples():
+    for l in open(os.path.join(GOLDEN, "mdps_line9_scattered.txt")):
+        if l.startswith("#") or not l.strip():
+            continue
+        head, want, et = [s.split() for s in l.split("|")]
+        n, nseg = int(head[1]), int(head[2])
+        thr = [float(v) for v in head[3:]]
+        prm = ref.MdpsParams(p=0.2, nseg=nseg, m_min=1, thr_override=thr, scan_order=1)
+        for fn in (ref.mdps_sample, ref.mdps_literal):
+            idx, info = fn(line9(), n, prm)
+            assert idx.tolist() == [int(v) for v in want], (head[0], fn.__name__)
+            assert info.et_index == int(et[0])
+
+
+def test_scan_stride_gives_a_walk_over_every_point():
+    assert ref.scan_stride(9) == 5 and ref.scan_stride(1) == 1 and ref.scan_stride(2) == 1
+    assert ref.scan_stride(10) == 7            # floor(6.18) = 6 shares the divisor 2 with 10
+    for N in list(range(1, 200)) + [1024, 4096, 24000, 120000, 1000000, 999983, 2 ** 21]:
+        A = ref.scan_stride(N)
+        assert A >= max(1, math.floor(0.6180339887498949 * N)) and math.gcd(A, N) == 1
+        assert A - math.floor(0.6180339887498949 * N) < 40          # the next coprime number is near
+        if N <= 4096:
+            walk = (np.arange(N, dtype=np.int64) * A) % N
+            assert np.array_equal(np.sort(walk), np.arange(N))
+
+
+@pytest.mark.parametrize("seed,N,n,nseg", [(3, 300, 120, 3), (4, 500, 200, 6), (5, 257, 257, 2)])
+def test_scattered_order_pick_is_the_first_available_of_the_walk(seed, N, n, nseg):
+    """Every sample of the threshold phase, recomputed from a distance matrix: it is available at the
+    level in force (no earlier sample closer than R_l), and no point earlier in the walk is."""
+    xyz = inputs.uniform_cube(seed, N)
+    prm = ref.MdpsParams(nseg=nseg, exponent=0.8, bias=1.1, scan_order=1)
+    idx, info = ref.mdps_sample(xyz, n, prm)
+    D = d2_matrix(xyz)
+    A = ref.scan_stride(N)
+    walk = (np.arange(N, dtype=np.int64) * A) % N
+    starts = [int(s) for s in info.level_start]
+    for i in range(info.m + 1, info.et_index):
+        level = max(l for l in range(nseg) if 0 <= starts[l] <= i)
+        mind = D[:, idx[:i]].min(axis=1)
+        avail = mind >= info.thr2[level]
+        assert avail[idx[i]], "sample %d is not available" % i
+        first = walk[np.flatnonzero(avail[walk])[0]]
+        assert first == idx[i], "sample %d is not the first available point of the walk" % i
+    assert len(set(idx.tolist())) == n or info.et_index < n
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_scattered_order_literal_form_agrees(seed):
+    xyz = inputs.uniform_cube(seed, 400 + 37 * seed)
+    for nseg, bias in ((1, 1.0), (4, 1.05), (6, 1.3)):
+        prm = ref.MdpsParams(nseg=nseg, exponent=0.85, bias=bias, scan_order=1)
+        a, ia = ref.mdps_sample(xyz, 150, prm)
+        b, ib = ref.mdps_literal(xyz, 150, prm)
+        assert np.array_equal(a, b) and ia.et_index == ib.et_index
+        assert np.array_equal(ia.level_start, ib.level_start)
+    # the order only matters in the threshold phase: thresholds no point meets give exact FPS
+    prm = ref.MdpsParams(nseg=2, thr_override=[np.inf, np.inf], scan_order=1)
+    assert np.array_equal(ref.mdps_sample(xyz, 150, prm)[0], ref.fps_exact(xyz, 150)[0])
+    # ... and a different order gives different samples than the index order where it can
+    p0 = ref.MdpsParams(nseg=4, exponent=0.85, bias=1.05)
+    p1 = ref.MdpsParams(nseg=4, exponent=0.85, bias=1.05, scan_order=1)
+    assert not np.array_equal(ref.mdps_sample(xyz, 150, p0)[0], ref.mdps_sample(xyz, 150, p1)[0])
