@@ -70,6 +70,18 @@ typedef struct fp_mdps_params {
                                  between the x_j; binary64 arithmetic in a fixed order, so the
                                  thresholds are reproducible bit for bit.  exponent and fit_window
                                  are then unused; bias and level_scale still apply. */
+    int32_t scan_order;   /* which available point the threshold phase takes next (Section 4.1
+                             step 3 leaves it open: any available point).  0: the lowest index.
+                             1: the first available point of the walk j_t = (t A) mod N,
+                             t = 0, 1, ..., where A is the smallest integer >= max(1, floor(
+                             0.6180339887498949 N)) that is coprime to N -- successive points of
+                             the walk lie far apart in index, so a cloud stored in scanner order
+                             is visited like a shuffled one and more picks of a round survive.
+                             The exact-FPS parts are not affected.  Order 1 needs the larger
+                             workspace of fp_mdps_scattered_workspace_bytes and does not record
+                             (bq_cache must be NULL; FP_ERR_PARAM otherwise, also for the
+                             cell-ordered entry point). */
+    int32_t reserved0;    /* 0 */
 } fp_mdps_params;
 
 #define FP_MLP_WEIGHTS (32 * 128 + 128 + 128 * 128 + 128 + 128 * 64 + 64)
@@ -134,7 +146,7 @@ fp_status fp_fps_exact(const float* xyz, int32_t B, int32_t N, int32_t n,
  * fp_fps_exact for callers that cannot allocate: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  The same kernels and the same result as
  * fp_fps_exact without a cache and without an info record, but the words the workgroups of a
- * cloud exchange live in a device array that is part of the library (2 654 208 bytes, held by
+ * cloud exchange live in a device array that is part of the library (2 658 304 bytes, held by
  * every GPU the library runs on until the process ends) instead of a caller's workspace.  The
  * call allocates nothing, on the device or through any library; the first call on a device
  * looks that device's copy of the array up (no allocation either), so make one call before a
@@ -155,7 +167,7 @@ fp_status fp_fps_exact_static(const float* xyz, int32_t B, int32_t N, int32_t n,
  * fp_fps_exact, bit for bit, reached with fewer distance evaluations (the role QuickFPS plays
  * for the exact iterations in Section 5.3 and Appendix B.3: an exact sampler that skips the
  * updates that cannot change anything).  The cloud is first put into the order of a uniform
- * grid traversed along a Z-order curve, so that the points a wavefront holds lie in a small
+ * grid traversed along a Hilbert curve, so that the points a wavefront holds lie in a small
  * box; a new sample is folded into a wavefront's distances only if it is closer to that box
  * than the largest distance the wavefront still holds.  Arguments as fp_fps_exact without the
  * ball-query cache; the workspace is larger (it also receives the reordered cloud).
@@ -174,7 +186,11 @@ fp_status fp_fps_exact_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
  * on exhaustion), and exact FPS for whatever remains once the last level is
  * exhausted.  If m >= n-1 the call is exact FPS.  Arguments as fp_fps_exact;
  * prm is a HOST pointer.
+ * With prm->scan_order = 1 (see fp_mdps_params) the workspace must hold
+ * fp_mdps_scattered_workspace_bytes(B, N) bytes: it also receives a copy of the cloud in the
+ * order of the walk (16 bytes per point), which is what the kernel then works on.
  */
+size_t fp_mdps_scattered_workspace_bytes(int32_t B, int32_t N);
 fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n,
                          const int32_t* start_idx, const fp_mdps_params* prm,
                          int32_t* out_idx, fp_mdps_info* info,

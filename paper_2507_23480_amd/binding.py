@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libfastpoint_hip.so")
 MAX_SEG = 16
 
-EXPORTS = ["fp_bq_cache_entries", "fp_fps_exact_static", "fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_mdps_sample_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
+EXPORTS = ["fp_mdps_scattered_workspace_bytes", "fp_bq_cache_entries", "fp_fps_exact_static", "fp_fps_pruned_workspace_bytes", "fp_fps_exact_pruned", "fp_mdps_sample_pruned", "fp_workspace_bytes", "fp_bq_cache_bytes", "fp_fps_exact", "fp_mdps_sample",
            "fp_ball_query", "fp_ball_query_grid_workspace_bytes", "fp_ball_query_grid", "fp_knn_workspace_bytes", "fp_knn", "fp_knn_grid_workspace_bytes", "fp_knn_grid", "fp_excl_workspace_bytes", "fp_excl_count",
            "fp_excl_fill", "fp_ball_query_lists", "fp_gather_xyz", "fp_coverage", "fp_probe_fp32_rate", "fp_plan", "fp_set_wg_per_cloud",
            "fp_set_wait_limit_us", "fp_set_cooperative_launch", "fp_status_string"]
@@ -27,7 +27,8 @@ class FpMdpsParams(ctypes.Structure):
     _fields_ = [("p", ctypes.c_float), ("nseg", ctypes.c_int32), ("exponent", ctypes.c_double),
                 ("bias", ctypes.c_float), ("fit_window", ctypes.c_int32), ("m_min", ctypes.c_int32),
                 ("use_override", ctypes.c_int32), ("thr_override", ctypes.c_float * MAX_SEG),
-                ("level_scale", ctypes.c_float * MAX_SEG), ("mlp_weights", ctypes.c_void_p)]
+                ("level_scale", ctypes.c_float * MAX_SEG), ("mlp_weights", ctypes.c_void_p),
+                ("scan_order", ctypes.c_int32), ("reserved0", ctypes.c_int32)]
 
 
 MLP_WEIGHTS = 32 * 128 + 128 + 128 * 128 + 128 + 128 * 64 + 64
@@ -58,6 +59,7 @@ class MdpsParams:
     thr_override: Optional[Sequence[float]] = None
     level_scale: Optional[Sequence[float]] = None
     mlp: Optional[torch.Tensor] = None    # MLP_WEIGHTS float32 weights on the device: the MLP estimator
+    scan_order: int = 0                   # threshold phase: 0 lowest available index, 1 scattered walk
 
     def to_c(self) -> FpMdpsParams:
         c = FpMdpsParams()
@@ -75,6 +77,7 @@ class MdpsParams:
                 c.level_scale[i] = v
         c.p, c.nseg, c.exponent, c.bias = self.p, self.nseg, self.exponent, self.bias
         c.fit_window, c.m_min = self.fit_window, self.m_min
+        c.scan_order = int(self.scan_order)
         c.use_override = 0
         if self.thr_override is not None:
             if len(self.thr_override) != self.nseg:
@@ -110,6 +113,8 @@ def load() -> ctypes.CDLL:
     lib.fp_fps_exact_static.restype = i32
     lib.fp_fps_pruned_workspace_bytes.argtypes = [i32, i32]
     lib.fp_fps_pruned_workspace_bytes.restype = ctypes.c_size_t
+    lib.fp_mdps_scattered_workspace_bytes.argtypes = [i32, i32]
+    lib.fp_mdps_scattered_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_fps_exact_pruned.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.fp_fps_exact_pruned.restype = i32
     lib.fp_mdps_sample_pruned.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -351,6 +356,18 @@ def _pruned_workspace(xyz: torch.Tensor, B: int, N: int, ws: Optional[torch.Tens
     return ws
 
 
+def _scattered_workspace(xyz: torch.Tensor, B: int, N: int) -> torch.Tensor:
+    need = int(load().fp_mdps_scattered_workspace_bytes(B, N))
+    if need == 0:
+        raise ValueError("shape (B=%d, N=%d) not supported" % (B, N))
+    key = ("scattered", xyz.device.type, xyz.device.index)
+    ws = _workspaces.get(key)
+    if ws is None or ws.numel() < need:
+        ws = torch.empty(need, dtype=torch.uint8, device=xyz.device)
+        _workspaces[key] = ws
+    return ws
+
+
 def mdps_sample_pruned(xyz: torch.Tensor, n: int, prm: MdpsParams, start_idx=None, want_info: bool = False,
                        ws: Optional[torch.Tensor] = None):
     """Minimum distance prediction sampling with pruned distance updates: the outputs of mdps_sample."""
@@ -374,7 +391,7 @@ def mdps_sample(xyz: torch.Tensor, n: int, prm: MdpsParams, start_idx=None, want
     idx = torch.empty((B, n), dtype=torch.int32, device=xyz.device)
     info = torch.zeros((B, INFO_BYTES), dtype=torch.uint8, device=xyz.device) if want_info else None
     if ws is None:
-        ws = workspace(xyz.device, B, N)
+        ws = _scattered_workspace(xyz, B, N) if prm.scan_order == 1 else workspace(xyz.device, B, N)
     c = prm.to_c()
     _check(load().fp_mdps_sample(xyz.data_ptr(), B, N, n, _ptr(st), ctypes.byref(c), idx.data_ptr(),
                                  _ptr(info), _ptr(bq_cache), 0 if bq_cache is None else bq_cache.numel(),

@@ -27,7 +27,9 @@ struct DeviceInfo {
 // exchange words between the workgroups of a cloud: what a sampler workspace holds
 constexpr int64_t kLlPkWords = (int64_t)2 * kMaxGroup * kLlSlotWords;             // all groups together
 constexpr int64_t kLlCdWords = (int64_t)2 * kMaxGroup * kCandMax * kCandWords;
-constexpr size_t kScratchBytes = (size_t)((kLlPkWords + kLlCdWords) * 8);         // 2 654 208 bytes
+constexpr int64_t kLlCtWords = (int64_t)2 * kMaxGroup;
+constexpr int64_t kLlWords = kLlPkWords + kLlCdWords + kLlCtWords;
+constexpr size_t kScratchBytes = (size_t)(kLlWords * 8);                          // 2 658 304 bytes
 
 // Scratch of fp_fps_exact_static: the same exchange words, but in device memory that belongs to
 // the library's code object instead of a caller's workspace, so that the call allocates nothing.
@@ -133,6 +135,54 @@ void* static_scratch()
     return g_dev[dev].scratch;
 }
 
+// Stride of the scattered scan order: the smallest integer >= max(1, floor(0.6180339887498949 N))
+// that has no common factor with N, so that t -> (t A) mod N visits every index once.
+int64_t scan_walk_stride(int32_t N)
+{
+    int64_t A = (int64_t)floor(0.6180339887498949 * (double)N);
+    if (A < 1) A = 1;
+    for (;; ++A) {
+        int64_t x = A, y = N;
+        while (y != 0) {
+            const int64_t r = x % y;
+            x = y;
+            y = r;
+        }
+        if (x == 1) return A;
+    }
+}
+
+// x with (A x) mod N == 1, for A coprime to N (extended Euclid); 0 for N == 1
+int64_t inverse_mod(int64_t A, int64_t N)
+{
+    int64_t r0 = N, r1 = A % N, t0 = 0, t1 = 1;
+    while (r1 != 0) {
+        const int64_t q = r0 / r1;
+        const int64_t r2 = r0 - q * r1, t2 = t0 - q * t1;
+        r0 = r1;
+        r1 = r2;
+        t0 = t1;
+        t1 = t2;
+    }
+    return ((t0 % N) + N) % N;
+}
+
+// Cell-ordered variant: words through which the workgroups of a cloud hand each other the relations
+// between the candidates of a window round, [resident clouds][2][kCandWin][16]; a cloud spread over
+// several workgroups leaves room for at most kMaxGroup / 2 resident clouds.
+constexpr int64_t kRelWordsPerCloud = (int64_t)2 * kCandWin * 16;
+int64_t rel_exchange_bytes(int32_t B)
+{
+    const int64_t clouds = B < kMaxGroup / 2 ? B : kMaxGroup / 2;
+#ifdef FASTPOINT_PHASE_CLOCKS
+    return clouds * kRelWordsPerCloud * 8 + kMaxGroup * 16 * 8;
+#else
+    return clouds * kRelWordsPerCloud * 8;
+#endif
+}
+
+int64_t scan_walk_bytes(int32_t B, int32_t N) { return align_up((int64_t)B * N * (int64_t)sizeof(float4), 256); }
+
 fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
                       const fp_mdps_params* prm, int32_t* out_idx, float* out_mdc, fp_mdps_info* info,
                       void* bq_cache, size_t bq_cache_bytes, float bq_radius, void* workspace,
@@ -149,8 +199,12 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         if (!(bq_radius > 0.0f) || !isfinite(bq_radius)) return FP_ERR_PARAM;
         if ((reinterpret_cast<uintptr_t>(bq_cache) & 255u) != 0) return FP_ERR_WORKSPACE;
     }
+    const bool walk = prm != nullptr && prm->scan_order == 1;
+    if (prm && (prm->scan_order < 0 || prm->scan_order > 1)) return FP_ERR_PARAM;
+    if (walk && bq_cache) return FP_ERR_PARAM;
     if (!workspace ||
-        workspace_bytes < (pruned ? fp_fps_pruned_workspace_bytes(B, N) : fp_workspace_bytes(B, N)) ||
+        workspace_bytes < (pruned ? fp_fps_pruned_workspace_bytes(B, N)
+                                  : (walk ? fp_mdps_scattered_workspace_bytes(B, N) : fp_workspace_bytes(B, N))) ||
         (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
         return FP_ERR_WORKSPACE;
 
@@ -200,6 +254,7 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_v);
     a.ll_pk = reinterpret_cast<uint64_t*>(workspace);
     a.ll_cd = a.ll_pk + kLlPkWords;
+    a.ll_ct = a.ll_cd + kLlCdWords;
     a.wait_ticks = g_wait_limit_us.load() * di.wall_khz / 1000;
 
     if (pruned) {
@@ -207,7 +262,21 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         void* sort_ws = reinterpret_cast<unsigned char*>(workspace) + fp_workspace_bytes(B, N);
         if (launch_spatial_sort(xyz, B, N, sort_ws, stream) != hipSuccess) return FP_ERR_DEVICE;
         a.sorted = spatial_sorted(B, N, sort_ws);
+        if (walk) a.walk_inv = (uint64_t)inverse_mod(scan_walk_stride(N), N);
+        a.ll_rel = reinterpret_cast<uint64_t*>(reinterpret_cast<unsigned char*>(sort_ws) + spatial_sort_bytes(B, N));
+#ifdef FASTPOINT_PHASE_CLOCKS
+        a.dbg = reinterpret_cast<long long*>(reinterpret_cast<unsigned char*>(workspace) +
+                                             fp_fps_pruned_workspace_bytes(B, N) - kMaxGroup * 16 * 8);
+#endif
     }
+    if (walk && !pruned && a.m < n - 1) {
+        // the cloud in the order of the walk, behind the exchange words (not needed when the prefix
+        // covers everything: the call is exact FPS then)
+        float4* rec = reinterpret_cast<float4*>(reinterpret_cast<unsigned char*>(workspace) + fp_workspace_bytes(B, N));
+        if (launch_scan_walk(xyz, B, N, scan_walk_stride(N), rec, stream) != hipSuccess) return FP_ERR_DEVICE;
+        a.sorted = rec;
+    }
+    const bool reordered = pruned || a.sorted != nullptr;
     const bool bq = bq_cache != nullptr;
     uint64_t* bq_zero = nullptr;
     int64_t bq_zero_words = 0;
@@ -233,8 +302,9 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
 
     // MDPS threshold rounds with two candidates per control-wave lane: measured faster except
     // where one workgroup both holds the cloud and records the radius tests
-    const int mode = prm == nullptr ? 0 : ((pruned || !bq || plan.G > 1) ? 2 : 1);
-    const void* fn = sampler_kernel_for(plan.T, plan.P, bq, pruned, mode);
+    const int mode = prm == nullptr ? 0
+                     : (walk && pruned ? 4 : (walk && a.sorted != nullptr ? 3 : ((pruned || !bq || plan.G > 1) ? 2 : 1)));
+    const void* fn = sampler_kernel_for(plan.T, plan.P, bq, reordered, mode);
     if (!fn) return FP_ERR_SHAPE;
     const unsigned grid = (unsigned)(plan.groups * plan.G);
     void* kargs[] = {&a};
@@ -243,7 +313,11 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
     // words (stamps start at 1 in every launch) and the chunk counters of a ball-query cache.  (A
     // cloud held by one workgroup has its counters zeroed by that workgroup.)
     if (plan.G > 1) {
-        if (launch_zero_words(a.ll_pk, kLlPkWords + kLlCdWords, bq_zero, bq_zero_words, stream) != hipSuccess)
+        if (pruned && prm) {                       // ... and, cell-ordered MDPS, the relation words
+            bq_zero = a.ll_rel;
+            bq_zero_words = (int64_t)plan.groups * kRelWordsPerCloud;
+        }
+        if (launch_zero_words(a.ll_pk, kLlWords, bq_zero, bq_zero_words, stream) != hipSuccess)
             return FP_ERR_DEVICE;
     }
     if (plan.G > 1 && g_cooperative.load())    // the whole grid has to be resident
@@ -264,7 +338,7 @@ extern "C" {
 size_t fp_workspace_bytes(int32_t B, int32_t N)
 {
     if (B < 1 || N < 1) return 0;
-    return (size_t)((kLlPkWords + kLlCdWords) * 8);
+    return (size_t)(kLlWords * 8);
 }
 
 size_t fp_bq_cache_bytes(int32_t B, int32_t N, int32_t n, int64_t entries_per_cloud)
@@ -310,10 +384,16 @@ fp_status fp_fps_exact_static(const float* xyz, int32_t B, int32_t N, int32_t n,
                        kScratchBytes, stream);
 }
 
+size_t fp_mdps_scattered_workspace_bytes(int32_t B, int32_t N)
+{
+    if (B < 1 || N < 1 || (int64_t)B * N > ((int64_t)1 << 33)) return 0;
+    return fp_workspace_bytes(B, N) + (size_t)scan_walk_bytes(B, N);
+}
+
 size_t fp_fps_pruned_workspace_bytes(int32_t B, int32_t N)
 {
     if (B < 1 || N < 1 || B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return 0;
-    return fp_workspace_bytes(B, N) + (size_t)spatial_sort_bytes(B, N);
+    return fp_workspace_bytes(B, N) + (size_t)spatial_sort_bytes(B, N) + (size_t)rel_exchange_bytes(B);
 }
 
 fp_status fp_fps_exact_pruned(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,

@@ -184,8 +184,45 @@ __global__ void grid_setup_kernel(ExclGrid* gp, int B, const float* __restrict__
     g.ncells = dim[0] * dim[1] * dim[2];
     g.rmax2 = rmax2;
     g.lmax = lmax;
-    g.morton_bits = 0;
+    g.curve_bits = 0;
     gp[b] = g;
+}
+
+// Position of cell (cx, cy, cz) of a 2^b x 2^b x 2^b grid along a Hilbert curve: consecutive
+// positions are cells that share a face, so a run of consecutive cells is a compact piece of space
+// wherever it starts (a curve by bit interleaving jumps across the grid at every power of two).
+// Skilling's transform of the coordinates (AIP Conf. Proc. 707, 2004): from the top bit down,
+// exchange or invert the low bits according to the bits above, Gray-code the result, and read the
+// three words bit by bit.
+__device__ __forceinline__ int hilbert_index(int cx, int cy, int cz, int b)
+{
+    uint32_t X[3] = {(uint32_t)cx, (uint32_t)cy, (uint32_t)cz};
+    const uint32_t top = 1u << (b - 1);
+    for (uint32_t q = top; q > 1; q >>= 1) {
+        const uint32_t low = q - 1;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            if (X[i] & q) {
+                X[0] ^= low;
+            } else {
+                const uint32_t t = (X[0] ^ X[i]) & low;
+                X[0] ^= t;
+                X[i] ^= t;
+            }
+        }
+    }
+    X[1] ^= X[0];
+    X[2] ^= X[1];
+    uint32_t t = 0;
+    for (uint32_t q = top; q > 1; q >>= 1)
+        if (X[2] & q) t ^= q - 1;
+    X[0] ^= t;
+    X[1] ^= t;
+    X[2] ^= t;
+    uint32_t id = 0;
+    for (int k = b - 1; k >= 0; --k)
+        id = (id << 3) | (((X[0] >> k) & 1u) << 2) | (((X[1] >> k) & 1u) << 1) | ((X[2] >> k) & 1u);
+    return (int)id;
 }
 
 __device__ __forceinline__ int cell_of(const ExclGrid& g, float x, float y, float z, int& cx, int& cy, int& cz)
@@ -193,12 +230,7 @@ __device__ __forceinline__ int cell_of(const ExclGrid& g, float x, float y, floa
     cx = cell_coord(x, g.origin[0], g.inv_h, g.dim[0]);
     cy = cell_coord(y, g.origin[1], g.inv_h, g.dim[1]);
     cz = cell_coord(z, g.origin[2], g.inv_h, g.dim[2]);
-    if (g.morton_bits > 0) {
-        int id = 0;
-        for (int k = 0; k < g.morton_bits; ++k)
-            id |= (((cx >> k) & 1) << (3 * k)) | (((cy >> k) & 1) << (3 * k + 1)) | (((cz >> k) & 1) << (3 * k + 2));
-        return id;
-    }
+    if (g.curve_bits > 0) return hilbert_index(cx, cy, cz, g.curve_bits);
     return (cz * g.dim[1] + cy) * g.dim[0] + cx;
 }
 
@@ -221,7 +253,7 @@ __global__ void sort_setup_kernel(ExclGrid* gp, int B, int bits)
     g.ncells = dim * dim * dim;
     g.rmax2 = 0.0f;
     g.lmax = 0;
-    g.morton_bits = bits;
+    g.curve_bits = bits;
     gp[b] = g;
 }
 

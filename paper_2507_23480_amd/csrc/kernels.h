@@ -13,6 +13,7 @@ constexpr int kMaxGroup = 256;          // most workgroups one cloud is spread o
 constexpr int kLlSlotWords = 8;         // 64-bit words per workgroup slot of the pick exchange
 constexpr int kCandPerRound = 64;       // candidates per round of exact FPS (one per lane of the control wave)
 constexpr int kCandMax = 128;           // candidates per round of the threshold phase (two per lane)
+constexpr int kCandWin = 256;           // candidates per round of the threshold phase, cell-ordered variant
 constexpr int kCandWords = 5;           // exchanged 64-bit words per candidate (x, y, z, index, distance)
 constexpr uint32_t kBqMagic = 0x46504232u;
 
@@ -106,9 +107,15 @@ struct SamplerArgs {
     int32_t bq_blocks;
     uint64_t* ll_pk;                // [groups][2][G][kLlSlotWords]
     uint64_t* ll_cd;                // [groups][2][G][kCandMax][kCandWords]
+    uint64_t* ll_ct;                // [groups][2][G] candidate counts of a scan
+#ifdef FASTPOINT_PHASE_CLOCKS
+    long long* dbg;                 // tuning builds: [G][16] clock sums of every workgroup of the last cloud
+#endif
+    uint64_t* ll_rel;               // cell-ordered variant: [groups][2][kCandWin][16] relation words of a window round
     int64_t wait_ticks;
     const float* mlp;               // weights of the MLP curve estimator, or NULL (power function)
     const float4* sorted;           // cell-ordered variant: [B][N] records (x, y, z, index bits), else NULL
+    uint64_t walk_inv;              // scattered scan order on cell-ordered records: 1/A mod N (place t of index j = j/A mod N)
 };
 
 struct Plan {
@@ -121,6 +128,9 @@ struct Plan {
 const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, int mode);
 // zeroes two ranges of 64-bit words (either may be empty)
 hipError_t launch_zero_words(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2, hipStream_t stream);
+// Scattered scan order of the threshold phase: writes the records (x, y, z, index bits) of every
+// cloud in the order of the walk j_t = (t stride) mod N into out[B][N]; stride coprime to N.
+hipError_t launch_scan_walk(const float* xyz, int B, int N, int64_t stride, float4* out, hipStream_t stream);
 // puts the entries the sampler appended to a cache of `cap` entries per cloud into sample order
 // (rows in compressed-row form)
 hipError_t launch_bq_group_by_sample(void* bq_cache, int B, int N, int n, int64_t cap, hipStream_t stream);
@@ -152,8 +162,8 @@ struct ExclGrid {
     int32_t ncells;
     float rmax2;             // largest squared radius of the cloud
     int32_t lmax;            // its level
-    int32_t morton_bits;     // 0: cells numbered x-fastest; b > 0: 2^b cells per axis, numbered by
-                             // interleaving the bits of the three coordinates
+    int32_t curve_bits;      // 0: cells numbered x-fastest; b > 0: 2^b cells per axis, numbered along
+                             // a Hilbert curve
 };
 
 // Where the parts of an exclusion-list workspace lie (byte offsets).
@@ -164,7 +174,7 @@ struct ExclLayout {
 
 ExclLayout excl_layout(int B, int N, int L);
 // Sorts every cloud into the order of a 2^b x 2^b x 2^b grid over its bounding box, cells
-// numbered along a Z-order curve; leaves records (x, y, z, index bits) at spatial_sorted().
+// numbered along a Hilbert curve; leaves records (x, y, z, index bits) at spatial_sorted().
 hipError_t launch_spatial_sort(const float* xyz, int B, int N, void* workspace, hipStream_t stream);
 int64_t spatial_sort_bytes(int B, int N);
 const float4* spatial_sorted(int B, int N, const void* workspace);

@@ -43,7 +43,7 @@ namespace {
 constexpr int kCand = kCandPerRound;    // candidates of an exact-FPS round (one per lane of the control wave)
 constexpr float kPadCoord = 3.0e38f;    // coordinates of slots beyond N: every distance becomes +inf
 constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
-constexpr int kStage = 256;             // ring of picks not yet written to global memory
+constexpr int kStage = 512;             // ring of picks not yet written to global memory (a round adds up to kCandWin)
 constexpr int kFlush = 128;             // ... written out once this many are waiting
 constexpr int kCtrlThreads = 64;        // the control wave, after the T point threads
 
@@ -87,6 +87,11 @@ __device__ __forceinline__ uint32_t rdlane(uint32_t v, int l)
 __device__ __forceinline__ float rdlane_f(float v, int l)
 {
     return __uint_as_float(rdlane(__float_as_uint(v), l));
+}
+// puts a wave-uniform value into lane `lane` of v
+__device__ __forceinline__ void set_lane(uint32_t& v, int my_lane, int lane, uint32_t uniform_value)
+{
+    v = my_lane == lane ? uniform_value : v;
 }
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
@@ -237,9 +242,8 @@ struct Shared {
     int32_t level_start[FP_MAX_SEG];
     int32_t level_exhausted[FP_MAX_SEG];
     int32_t wcnt[NW];
-    Cand cand[kCandMax];
+    Cand cand[kCandWin];
     long long phase_t[5];      // constant 100 MHz clock at the phase boundaries of the cloud in hand (thread 0)
-    int32_t rank[kCandMax];    // cell-ordered variant: position of a candidate among those of its round, by index
     Cand pend[kCand];
     int32_t bl[FP_MAX_SEG];    // segment boundaries b_l (curve positions that become thresholds)
     int32_t qend[FP_MAX_SEG + 1];   // qend[l] = ceil(n l / nseg): the quota rule raises the level to l + 1 there
@@ -251,9 +255,22 @@ struct Shared {
                           // [2] failure, [3] distance bits of the last accepted pick
     // picks of the round being resolved, in acceptance order
     uint64_t live[kCandMax + 2];
+    // scattered scan order: conf[2 c], conf[2 c + 1] = which candidates 0..63 / 64..127 of the round
+    // lie closer than R_l to candidate c (bit j of the word: candidate j or 64 + j); acc[s] =
+    // coordinates and index bits of the round's s-th accepted pick; progress = round number << 16 |
+    // kRoundOver once the round has no further pick | picks in acc so far
+    uint64_t conf[2 * kCandMax];
+    float4 acc[kCandMax];
+    // cell order: rel[j] = for candidate j of a window round, which candidates come before it in the
+    // order of the sampling rule (words 0..3) and which of those lie closer to it than R_l (words 4..7);
+    // took = the accepted candidates of the round, one bit each
+    uint64_t rel[kCandWin][8];
+    uint64_t took[kCandWin / 64];
+    uint32_t progress;
 #ifdef FASTPOINT_PHASE_CLOCKS
     long long chain_cycles;   // shader clocks the control wave spent in the exact-FPS chain loop
     long long chain_picks;
+    long long scan_clk[8];    // wall-clock ticks of thread 0 in the parts of scan_candidates (threshold scans)
 #endif
     uint32_t st_idx[kStage];   // picks waiting to be written out (ring, by sample position)
     float st_mdc[kStage];
@@ -285,6 +302,7 @@ template <int P, bool BQ>
 struct Points {
     typename RegVec<P>::type x, y, z, d;
     typename RegVecU<P>::type oi;       // cell-ordered variant: the point's index in the caller's cloud
+    typename RegVecU<P>::type rk;       // ... with the scattered scan order: its place t in the walk j_t = (t A) mod N
     float lox, loy, loz, hix, hiy, hiz; // cell-ordered variant: box of the wave's points (wave-uniform)
     uint32_t ub;                        // ... and an upper bound of their running distances (bits)
     // recording kernels: where this wave's next entry of the cloud's list goes.  [bq_cur, bq_lim) is
@@ -848,7 +866,7 @@ struct CloudState {
     float om;       // an exact-FPS round takes the points above dlast * (1 - om) as candidates
     int my_bl;      // thread l < nseg: segment boundary b_(l+1); else -1
 #ifdef FASTPOINT_PHASE_CLOCKS
-    long long clk[8];
+    long long clk[12];
 #endif
 };
 
@@ -892,30 +910,40 @@ __device__ __forceinline__ bool plain_pick(Points<P, BQ>& pt, Shared<T>& sh, con
 }
 
 // Whether slot p of this thread passes a scan: distance d > thr (STRICT) or d >= thr, and (WIN,
-// cell-ordered variant) the point's own index lies in [win_lo, win_lo + win_len).
-template <int P, bool BQ, bool STRICT, bool WIN>
+// cell-ordered variant) the point's own index -- RK: its place in the walk of the scattered scan
+// order -- lies in [win_lo, win_lo + win_len).
+template <int P, bool BQ, bool STRICT, bool WIN, bool RK>
 __device__ __forceinline__ bool passes(const Points<P, BQ>& pt, int p, float thr, uint32_t win_lo, uint32_t win_len)
 {
     const bool av = STRICT ? (pt.d[p] > thr) : (pt.d[p] >= thr);
-    if constexpr (WIN) return av && (uint32_t)(pt.oi[p] - win_lo) < win_len;
+    if constexpr (WIN) return av && (uint32_t)((RK ? pt.rk[p] : pt.oi[p]) - win_lo) < win_len;
     return av;
 }
 
 // Collects the cloud's first CAP points (in the order the workgroups hold them: ascending index,
 // or cell order in the cell-ordered variant) that pass -- see passes() -- into sh.cand of every
-// workgroup.  Returns the number collected (at most CAP), -1 if a wait expired; `alltot`
-// receives the number of points that pass in the whole cloud.
-template <int T, int P, bool BQ, bool PERM, bool STRICT, int CAP, bool WIN = false>
+// workgroup (RK: with the point's place in the walk instead of its distance).  Returns the number
+// collected (at most CAP), -1 if a wait expired; `alltot` receives the number of points that pass
+// in the whole cloud.  With several workgroups each hands on at most PUB of its own: when the
+// number returned is below both CAP and `alltot`, some workgroup held more than that.
+template <int T, int P, bool BQ, bool PERM, bool STRICT, int CAP, bool WIN = false, bool RK = false,
+          int PUB = CAP>
 __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                                const SamplerArgs& a, uint32_t& seq, float thr, int& alltot,
                                                uint32_t win_lo = 0, uint32_t win_len = 0)
 {
     constexpr int NW = T / 64;
     // 1. how many of this wave's points pass
+#ifdef FASTPOINT_PHASE_CLOCKS
+    long long sc_t = wall_clock64();
+#define SCAN_MARK(k) do { if (!STRICT && wh.tid == 0) { const long long now__ = wall_clock64(); sh.scan_clk[k] += now__ - sc_t; sc_t = now__; } } while (0)
+#else
+#define SCAN_MARK(k) do { } while (0)
+#endif
     int cntw = 0;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-        const bool av = passes<P, BQ, STRICT, WIN>(pt, p, thr, win_lo, win_len);
+        const bool av = passes<P, BQ, STRICT, WIN, RK>(pt, p, thr, win_lo, win_len);
         cntw += __builtin_popcountll(__builtin_amdgcn_ballot_w64(av));
     }
     if (wh.lane == 0 && !wh.ctrl) sh.wcnt[wh.w] = cntw;     // the control wave has none (cntw == 0)
@@ -934,7 +962,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         int base = off;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const bool av = passes<P, BQ, STRICT, WIN>(pt, p, thr, win_lo, win_len);
+            const bool av = passes<P, BQ, STRICT, WIN, RK>(pt, p, thr, win_lo, win_len);
             const uint64_t mk = __builtin_amdgcn_ballot_w64(av);
             if (mk != 0 && base < CAP) {
                 const int rank = base + lanes_below(mk);
@@ -944,7 +972,8 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
                     cd.x = pt.x[p];
                     cd.y = pt.y[p];
                     cd.z = pt.z[p];
-                    cd.d = __float_as_uint(pt.d[p]);
+                    // (a threshold round does not look at a candidate's distance: RK puts the place in the walk there)
+                    cd.d = RK ? pt.rk[p] : __float_as_uint(pt.d[p]);
                     sh.cand[rank] = cd;
                 }
                 base += __builtin_popcountll(mk);
@@ -952,6 +981,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         }
     }
     __syncthreads();
+    SCAN_MARK(0);
     int total = tot < CAP ? tot : CAP;
     alltot = tot;
     if (wh.G == 1) return total;
@@ -962,15 +992,20 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     //    different CAP may lay the same buffer out differently)
     ++seq;
     const int par = (int)(seq & 1u);
-    uint64_t* pk = a.ll_pk + ((int64_t)(wh.grp * 2 + par) * wh.G) * kLlSlotWords;
     uint64_t* cd = a.ll_cd + ((int64_t)(wh.grp * 2 + par) * wh.G) * (kCandMax * kCandWords);
-    for (int e = wh.tid; e < total * kCandWords; e += T + kCtrlThreads) {
+    static_assert(PUB <= CAP && PUB <= kCandMax, "a workgroup's list in the exchange buffer holds kCandMax entries");
+    const int publish = tot < PUB ? tot : PUB;     // (PUB < CAP: a workgroup hands on at most PUB of its own)
+    for (int e = wh.tid; e < publish * kCandWords; e += T + kCtrlThreads) {
         const int r = e / kCandWords, k = e - r * kCandWords;
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&sh.cand[r]);
-        ll_store(cd + ((int64_t)wh.g * CAP + r) * kCandWords + k, src[k], seq);
+        ll_store(cd + ((int64_t)wh.g * PUB + r) * kCandWords + k, src[k], seq);
     }
-    if (wh.tid == 0) ll_store(pk + (int64_t)wh.g * kLlSlotWords + 5, (uint32_t)tot, seq);
+    // (the counts of the cloud's workgroups lie side by side: a wave that waits for 64 of them touches
+    // eight lines of memory, not 64)
+    uint64_t* ct = a.ll_ct + (int64_t)(wh.grp * 2 + par) * wh.G;
+    if (wh.tid == 0) ll_store(ct + wh.g, (uint32_t)tot, seq);
     __syncthreads();          // sh.cand is about to be overwritten
+    SCAN_MARK(1);
     // More than 64 workgroups: thread t waits for the count of workgroup t, so that all waits
     // are in flight together, and hands it over in LDS.  Up to 64: the lanes of wave 0 wait
     // themselves (one count each), which saves the barrier.
@@ -978,10 +1013,11 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     if (spread) {
         if (wh.tid < wh.G) {
             uint32_t val[1];
-            const bool got = ll_wait<1>(pk + (int64_t)wh.tid * kLlSlotWords + 5, seq, val, a.wait_ticks);
+            const bool got = ll_wait<1>(ct + wh.tid, seq, val, a.wait_ticks);
             sh.gpre[wh.tid + 1] = got ? (int)val[0] : -1;
         }
         __syncthreads();
+        SCAN_MARK(2);
     }
     if (wh.w == 0) {
         // lane t adds up the counts of workgroups [t*per, (t+1)*per)
@@ -996,13 +1032,13 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
                     v = sh.gpre[t + 1];
                 } else {
                     uint32_t val[1];
-                    v = ll_wait<1>(pk + (int64_t)t * kLlSlotWords + 5, seq, val, a.wait_ticks) ? (int)val[0] : -1;
+                    v = ll_wait<1>(ct + t, seq, val, a.wait_ticks) ? (int)val[0] : -1;
                 }
                 if (v < 0) {
                     bad = true;
                 } else {
                     usum += v;
-                    sum += v < CAP ? v : CAP;
+                    sum += v < PUB ? v : PUB;
                 }
                 sh.gpre[t + 1] = sum;      // inclusive inside the lane, fixed below
             }
@@ -1026,67 +1062,47 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         }
     }
     __syncthreads();
+    SCAN_MARK(3);
     alltot = uni(sh.ctrl[1]);
     const int listed = uni(sh.gpre[wh.G]);
     total = listed < CAP ? listed : CAP;
     if (uni(sh.ctrl[2]) == 0) {
-        for (int e = wh.tid; e < total * kCandWords; e += T + kCtrlThreads) {
-            const int r = e / kCandWords, k = e - r * kCandWords;
-            int lo = 0, hi = wh.G;             // workgroup whose range holds rank r
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (sh.gpre[mid] <= r) lo = mid;
-                else hi = mid;
+        // a thread fetches up to NE words of the list: all of them are requested before the first is
+        // looked at (a word that has not arrived yet is then waited for on its own)
+        constexpr int NE = (CAP * kCandWords + T + kCtrlThreads - 1) / (T + kCtrlThreads);
+        const uint64_t* src[NE];
+        uint64_t got[NE];
+#pragma unroll
+        for (int u = 0; u < NE; ++u) {
+            const int e = wh.tid + u * (T + kCtrlThreads);
+            src[u] = nullptr;
+            if (e < total * kCandWords) {
+                const int r = e / kCandWords, k = e - r * kCandWords;
+                int lo = 0, hi = wh.G;         // workgroup whose range holds rank r
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (sh.gpre[mid] <= r) lo = mid;
+                    else hi = mid;
+                }
+                src[u] = cd + ((int64_t)lo * PUB + (r - sh.gpre[lo])) * kCandWords + k;
             }
-            uint32_t val[1];
-            val[0] = 0;
-            const bool got = ll_wait<1>(cd + ((int64_t)lo * CAP + (r - sh.gpre[lo])) * kCandWords + k, seq,
-                                        val, a.wait_ticks);
-            if (!got) sh.ctrl[2] = 1;
-            reinterpret_cast<uint32_t*>(&sh.cand[r])[k] = val[0];
+        }
+#pragma unroll
+        for (int u = 0; u < NE; ++u) got[u] = src[u] ? ll_load(src[u]) : 0;
+#pragma unroll
+        for (int u = 0; u < NE; ++u) {
+            if (src[u]) {
+                const int e = wh.tid + u * (T + kCtrlThreads);
+                uint32_t val[1];
+                val[0] = (uint32_t)got[u];
+                if ((uint32_t)(got[u] >> 32) != seq && !ll_wait<1>(src[u], seq, val, a.wait_ticks)) sh.ctrl[2] = 1;
+                reinterpret_cast<uint32_t*>(&sh.cand[e / kCandWords])[e % kCandWords] = val[0];
+            }
         }
     }
     __syncthreads();
+    SCAN_MARK(4);
     return uni(sh.ctrl[2]) != 0 ? -1 : total;
-}
-
-// Cell-ordered variant: the candidates of a threshold round arrive in cell order, the rule of
-// the threshold phase takes them by index.  rank = number of candidates with a lower index (the
-// indices differ); the point waves count a share of the comparisons each.  Called by all threads.
-template <int T>
-__device__ __forceinline__ void sort_candidates(Shared<T>& sh, const Where& wh, int total)
-{
-    constexpr int NW = T / 64;
-    total = uni(total);
-    if (total < 2) return;
-    if (wh.tid < kCandMax) sh.rank[wh.tid] = 0;
-    __syncthreads();
-    if (!wh.ctrl) {
-        const int chunk = (total + NW - 1) / NW;
-        const int j0 = wh.w * chunk;
-        const int j1 = j0 + chunk < total ? j0 + chunk : total;
-        const bool h0 = wh.lane < total, h1 = wh.lane + 64 < total;
-        const uint32_t k0 = sh.cand[h0 ? wh.lane : 0].idx;
-        const uint32_t k1 = sh.cand[h1 ? wh.lane + 64 : 0].idx;
-        int r0 = 0, r1 = 0;
-        for (int j = j0; j < j1; ++j) {
-            const uint32_t key = sh.cand[j].idx;
-            r0 += key < k0 ? 1 : 0;
-            r1 += key < k1 ? 1 : 0;
-        }
-        if (h0 && r0 != 0) atomicAdd(&sh.rank[wh.lane], r0);
-        if (h1 && r1 != 0) atomicAdd(&sh.rank[wh.lane + 64], r1);
-    }
-    __syncthreads();
-    Cand me = {};
-    int r = 0;
-    if (wh.tid < total) {
-        me = sh.cand[wh.tid];
-        r = sh.rank[wh.tid];
-    }
-    __syncthreads();
-    if (wh.tid < total) sh.cand[r] = me;
-    __syncthreads();
 }
 
 // Threshold phase of Alg. 2 (list clearing and findAnyOne for up to kCandMax picks at once): the candidates are
@@ -1153,6 +1169,318 @@ __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh
         stage_pick<T>(sh, st.i + wh.lane, sh.cand[cl].idx, 0.0f);
     }
     if (wh.lane == 0) sh.ctrl[0] = nacc;
+}
+
+// ---- Threshold rounds of the scattered scan order.  Whether a candidate of the round stays
+// available depends only on a yes/no relation between candidates -- "lies closer than R_l" -- so the
+// relation is worked out first, by all waves of the workgroup side by side, and the picks are then
+// resolved from its bits alone.  (With the scan in index order few candidates of a round survive and
+// this costs more than it saves; with the scattered order most of them do.)
+//
+// build_conflicts: wave w takes candidates w, w + NW + 1, ...; candidate c is read by all lanes
+// (one broadcast), lane j tests it against candidates j and 64 + j, and the two ballots are row c
+// of the relation.  dist2 gives the same bits with its points exchanged, so row c is also what
+// the fold of pick c will find for the other candidates.  Called by all threads; the rows are
+// complete after the next barrier.
+constexpr uint32_t kRoundOver = 0x8000u;
+
+template <int T>
+__device__ __forceinline__ void build_conflicts(Shared<T>& sh, const Where& wh, int total, float r2)
+{
+    constexpr int NWALL = T / 64 + 1;              // the control wave takes its share
+    total = uni(total);
+    const bool has0 = wh.lane < total;
+    const bool has1 = wh.lane + 64 < total;
+    const bool two = total > 64;                   // uniform
+    const Cand me0 = sh.cand[has0 ? wh.lane : 0];
+    const Cand me1 = sh.cand[has1 ? wh.lane + 64 : 0];
+    for (int c = wh.w; c < total; c += NWALL) {
+        const Cand pk = sh.cand[c];
+        const float t0 = dist2(pk.x, pk.y, pk.z, me0.x, me0.y, me0.z);
+        const uint64_t k0 = __builtin_amdgcn_ballot_w64(has0 && t0 < r2);
+        uint64_t k1 = 0;
+        if (two) {
+            const float t1 = dist2(pk.x, pk.y, pk.z, me1.x, me1.y, me1.z);
+            k1 = __builtin_amdgcn_ballot_w64(has1 && t1 < r2);
+        }
+        if (wh.lane == 0) {
+            sh.conf[2 * c] = k0;
+            sh.conf[2 * c + 1] = k1;
+        }
+    }
+}
+
+__device__ __forceinline__ uint64_t rdlane64(uint64_t v, int l)
+{
+    return ((uint64_t)rdlane((uint32_t)(v >> 32), l) << 32) | (uint64_t)rdlane((uint32_t)v, l);
+}
+
+__device__ __forceinline__ void progress_publish(uint32_t* p, uint32_t v)
+{
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+}
+__device__ __forceinline__ uint32_t progress_observe(const uint32_t* p)
+{
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    const uint32_t v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    return v;
+}
+
+// resolve_conflicts: the candidates are taken in the order of the list; one stays available iff no
+// pick accepted before it in this round lies closer than R_l.  Run by the control wave of every
+// workgroup (all do the same work): lane l keeps rows l and 64 + l of the relation in registers, the
+// set of candidates still available is two scalar 64-bit words, and a step is "lowest set bit,
+// fetch its row from the lane that holds it, clear the row's bits" -- no arithmetic on the chain.
+// The lane that holds an accepted candidate appends its coordinates to sh.acc, then the count in
+// sh.progress goes up: the point waves fold whatever the count covers.
+template <int T>
+__device__ __forceinline__ void resolve_conflicts(Shared<T>& sh, const Where& wh, const CloudState& st,
+                                                  int total, int limit, uint32_t round_no)
+{
+    total = uni(total);
+    limit = uni(limit);
+    const bool two = total > 64;                   // uniform
+    const bool has0 = wh.lane < total;
+    const bool has1 = wh.lane + 64 < total;
+    const Cand me0 = sh.cand[has0 ? wh.lane : 0];
+    const Cand me1 = sh.cand[has1 ? wh.lane + 64 : 0];
+    const uint64_t r00 = sh.conf[2 * wh.lane], r01 = sh.conf[2 * wh.lane + 1];
+    const uint64_t r11 = sh.conf[2 * (64 + wh.lane) + 1];
+    // (rows of lanes at or beyond `total` are left-overs of earlier rounds: never selected)
+    uint64_t alive0 = total >= 64 ? ~0ull : ((1ull << total) - 1ull);
+    uint64_t alive1 = !two ? 0ull : (total >= 128 ? ~0ull : ((1ull << (total - 64)) - 1ull));
+    int nacc = 0;
+    const uint32_t word = round_no << 16;
+    __builtin_amdgcn_s_setprio(3);
+    asm volatile("" ::"v"(r00), "v"(r01), "v"(r11), "v"(me0.x), "v"(me1.x));   // arrived before the loop starts
+    while (alive0 != 0 && nacc < limit) {          // candidates 0..63 come first
+        const int cl = first_lane(alive0);
+        if (wh.lane == cl) sh.acc[nacc] = make_float4(me0.x, me0.y, me0.z, __uint_as_float(me0.idx));
+        nacc = uni(nacc + 1);
+        progress_publish(&sh.progress, word | (uint32_t)nacc);
+        alive0 &= ~rdlane64(r00, cl);              // includes the pick itself (0 < R_l^2) ...
+        alive0 &= ~(1ull << cl);                   // ... whatever the threshold
+        if (two) alive1 &= ~rdlane64(r01, cl);
+    }
+    while (alive1 != 0 && nacc < limit) {
+        const int cl = first_lane(alive1);
+        if (wh.lane == cl) sh.acc[nacc] = make_float4(me1.x, me1.y, me1.z, __uint_as_float(me1.idx));
+        nacc = uni(nacc + 1);
+        progress_publish(&sh.progress, word | (uint32_t)nacc);
+        alive1 &= ~rdlane64(r11, cl);
+        alive1 &= ~(1ull << cl);
+    }
+    progress_publish(&sh.progress, word | kRoundOver | (uint32_t)nacc);
+    __builtin_amdgcn_s_setprio(0);
+    for (int t = wh.lane; t < nacc; t += 64) stage_pick<T>(sh, st.i + t, __float_as_uint(sh.acc[t].w), 0.0f);
+    if (wh.lane == 0) sh.ctrl[0] = nacc;
+}
+
+// The point waves' side of such a round: folds the picks of sh.acc up to the published count, looks
+// at the count again, and so on until the round is over.  No wait per pick: the control wave is far
+// ahead after the first few picks.
+template <int T, int P, bool BQ>
+__device__ __forceinline__ void follow_stream(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                              const SamplerArgs& a, uint32_t round_no)
+{
+    static_assert(!BQ, "the scattered scan order does not record");
+    RowWords<P, BQ> rw;
+    rw.clear(wh);
+    int done = 0;
+    for (;;) {
+        uint32_t pr = uni(progress_observe(&sh.progress));
+        while ((pr >> 16) != round_no || (int)(pr & 0xFFu) == done) {     // not of this round, or nothing new
+            if ((pr >> 16) == round_no && (pr & kRoundOver) != 0) return;
+            __builtin_amdgcn_s_sleep(1);
+            pr = uni(progress_observe(&sh.progress));
+        }
+        const int cnt = (int)(pr & 0xFFu);
+        for (int s = done; s < cnt; ++s) {
+            const float4 c = sh.acc[s];
+            fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, 0, rw);
+        }
+        done = cnt;
+        if ((pr & kRoundOver) != 0) return;
+    }
+}
+
+// ---- Threshold rounds of the cell-ordered variant.  The candidates of a round are ALL available
+// points of a window of keys (the point's index, or with the scattered scan order its place in the
+// walk), up to kCandWin of them, in no particular order.  Taking them one after the other in key
+// order, one is accepted iff no candidate accepted before it lies closer than R_l.  That is settled
+// without walking through them:
+//
+// build_relations (all waves): for candidate j, which candidates have a lower key (`before`) and
+// which of those lie closer than R_l (`blockers`), as bit sets over the candidate list.  Lane l
+// holds candidates l, 64 + l, ...; a wave takes one j at a time, reads it with one broadcast, and
+// each test over the list is a ballot.  dist2 gives the same bits with its points
+// exchanged, so a blocker bit is also what the fold of that pick will find for candidate j.
+//
+// settle_relations (control wave): a candidate all of whose blockers are rejected is accepted, one
+// with an accepted blocker is rejected; repeated until none is undecided.  The undecided candidate
+// with the lowest key is decided in every sweep (its blockers all are), so the sweeps end, and
+// they are as many as the longest chain of candidates each waiting for the one before -- a
+// handful when neighbours in key order are not neighbours in space.  The place of an accepted
+// candidate in the output is the number of accepted candidates before it; those from place `limit`
+// on are dropped (the level's quota ends the round there).
+constexpr int kWinWords = kCandWin / 64;
+
+constexpr int kRelWords = 4 * kWinWords;           // 32-bit words of a candidate's two bit sets
+
+template <int T, bool BYD>
+__device__ __forceinline__ void build_relations(Shared<T>& sh, const Where& wh, const SamplerArgs& a,
+                                                uint32_t seq, int total, float r2)
+{
+    constexpr int NWALL = T / 64 + 1;              // the control wave takes its share
+    total = uni(total);
+    const int nq = (total + 63) >> 6;              // uniform
+    Cand me[kWinWords];
+#pragma unroll
+    for (int q = 0; q < kWinWords; ++q) {
+        const int c = wh.lane + 64 * q;
+        me[q] = sh.cand[c < total ? c : 0];
+    }
+    // With several workgroups every one of them works out the sets of the candidates g, g + G, ...
+    // only and hands them to the others through stamped words (as the candidates themselves came).
+    const int first = wh.G == 1 ? wh.w : wh.g + wh.G * wh.w;
+    const int step = wh.G == 1 ? NWALL : wh.G * NWALL;
+    uint64_t* buf = wh.G == 1 ? nullptr : a.ll_rel + (int64_t)(wh.grp * 2 + (int)(seq & 1u)) * (kCandWin * kRelWords);
+    for (int j = first; j < total; j += step) {
+        const Cand pj = sh.cand[j];
+        const uint32_t kj = BYD ? pj.d : pj.idx;
+        uint32_t pay = 0;                           // lane l: word l of (before, blockers)
+#pragma unroll
+        for (int q = 0; q < kWinWords; ++q) {
+            uint64_t before = 0, blockers = 0;
+            if (q < nq) {
+                const bool earlier = wh.lane + 64 * q < total && (BYD ? me[q].d : me[q].idx) < kj;
+                const float t = dist2(pj.x, pj.y, pj.z, me[q].x, me[q].y, me[q].z);
+                before = __builtin_amdgcn_ballot_w64(earlier);
+                blockers = __builtin_amdgcn_ballot_w64(earlier && t < r2);
+            }
+            set_lane(pay, wh.lane, 2 * q, (uint32_t)before);
+            set_lane(pay, wh.lane, 2 * q + 1, (uint32_t)(before >> 32));
+            set_lane(pay, wh.lane, 2 * kWinWords + 2 * q, (uint32_t)blockers);
+            set_lane(pay, wh.lane, 2 * kWinWords + 2 * q + 1, (uint32_t)(blockers >> 32));
+        }
+        if (wh.lane < kRelWords) {
+            if (wh.G == 1) reinterpret_cast<uint32_t*>(&sh.rel[j][0])[wh.lane] = pay;
+            else ll_store(buf + (int64_t)j * kRelWords + wh.lane, pay, seq);
+        }
+    }
+    if (wh.G == 1) return;
+    constexpr int NE = (kCandWin * kRelWords + T + kCtrlThreads - 1) / (T + kCtrlThreads);
+    uint64_t got[NE];
+#pragma unroll
+    for (int u = 0; u < NE; ++u) {
+        const int e = wh.tid + u * (T + kCtrlThreads);
+        got[u] = e < total * kRelWords ? ll_load(buf + e) : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < NE; ++u) {
+        const int e = wh.tid + u * (T + kCtrlThreads);
+        if (e < total * kRelWords) {
+            uint32_t val[1];
+            val[0] = (uint32_t)got[u];
+            if ((uint32_t)(got[u] >> 32) != seq && !ll_wait<1>(buf + e, seq, val, a.wait_ticks)) sh.ctrl[2] = 1;
+            reinterpret_cast<uint32_t*>(&sh.rel[0][0])[e] = val[0];
+        }
+    }
+}
+
+template <int T>
+__device__ __forceinline__ void settle_relations(Shared<T>& sh, const Where& wh, const CloudState& st,
+                                                 int total, int limit)
+{
+    total = uni(total);
+    limit = uni(limit);
+    const int nq = (total + 63) >> 6;              // uniform
+    uint64_t blockers[kWinWords][kWinWords];
+    uint64_t und[kWinWords], acc[kWinWords], rej[kWinWords];
+#pragma unroll
+    for (int q = 0; q < kWinWords; ++q) {
+        const int c = wh.lane + 64 * q;
+        const bool has = c < total;
+        und[q] = __builtin_amdgcn_ballot_w64(has);
+        acc[q] = 0;
+        rej[q] = 0;
+#pragma unroll
+        for (int w = 0; w < kWinWords; ++w) blockers[q][w] = has ? sh.rel[c][kWinWords + w] : 0;
+    }
+    for (int sweep = 0; sweep <= total; ++sweep) {  // ends much earlier: see above
+        uint64_t left = 0;
+#pragma unroll
+        for (int q = 0; q < kWinWords; ++q) {
+            if (q < nq && und[q] != 0) {
+                uint64_t open = 0, hit = 0;
+#pragma unroll
+                for (int w = 0; w < kWinWords; ++w) {
+                    open |= blockers[q][w] & ~rej[w];
+                    hit |= blockers[q][w] & acc[w];
+                }
+                const bool mine = ((und[q] >> wh.lane) & 1ull) != 0;
+                const uint64_t na = __builtin_amdgcn_ballot_w64(mine && open == 0);
+                const uint64_t nr = __builtin_amdgcn_ballot_w64(mine && hit != 0);
+                acc[q] |= na;
+                rej[q] |= nr;
+                und[q] &= ~(na | nr);
+                left |= und[q];
+            }
+        }
+        if (left == 0) break;
+    }
+    int count = 0;
+#pragma unroll
+    for (int q = 0; q < kWinWords; ++q) count += __builtin_popcountll(acc[q]);
+    const int nacc = count < limit ? count : limit;
+#pragma unroll
+    for (int q = 0; q < kWinWords; ++q) {
+        const int c = wh.lane + 64 * q;
+        const bool mine = ((acc[q] >> wh.lane) & 1ull) != 0;
+        int place = 0;
+#pragma unroll
+        for (int w = 0; w < kWinWords; ++w)
+            if (q < nq && w < nq) place += __builtin_popcountll((mine ? sh.rel[c][w] : 0ull) & acc[w]);
+        const bool keep = mine && place < limit;
+        if (keep) stage_pick<T>(sh, st.i + place, sh.cand[c].idx, 0.0f);
+        const uint64_t took = __builtin_amdgcn_ballot_w64(keep);
+        if (wh.lane == 0) sh.took[q] = took;
+    }
+    if (wh.lane == 0) sh.ctrl[0] = nacc;
+}
+
+// The point waves' side: which candidates are near the wave's box (while the control wave settles
+// the round), then -- after the barrier -- the fold of the accepted ones among them.
+struct NearWords {
+    uint64_t w[kWinWords];
+};
+template <int T, int P, bool BQ>
+__device__ __forceinline__ NearWords near_candidates(const Points<P, BQ>& pt, const Shared<T>& sh,
+                                                     const Where& wh, int total)
+{
+    NearWords nw;
+#pragma unroll
+    for (int q = 0; q < kWinWords; ++q) nw.w[q] = near_mask<P, BQ>(pt, sh.cand + 64 * q, total - 64 * q, wh.lane);
+    return nw;
+}
+template <int T, int P, bool BQ>
+__device__ __forceinline__ void fold_accepted(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
+                                              const SamplerArgs& a, const NearWords& nw)
+{
+    RowWords<P, BQ> rw;
+    rw.clear(wh);
+#pragma unroll
+    for (int q = 0; q < kWinWords; ++q) {
+        uint64_t m = nw.w[q] & sh.took[q];
+        while (m != 0) {
+            const Cand c = sh.cand[64 * q + first_lane(m)];
+            m &= m - 1;
+            fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, 0, rw);
+        }
+    }
 }
 
 // Exact FPS for several picks at once.  The candidates are ALL points whose distance exceeds
@@ -1382,12 +1710,20 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
 
 // ------------------------------------------------------------------ one cloud
 // MODE 0: exact FPS only (the code of Alg. 2 is left out of the kernel); 1: MDPS with threshold rounds
-// of kCand candidates; 2: MDPS with threshold rounds of kCandMax candidates.
+// of kCand candidates; 2: MDPS with threshold rounds of kCandMax candidates; 3: MDPS with the
+// scattered scan order -- the records of a.sorted are in the order of the walk, so the first
+// kCandMax available positions are the candidates, already in the order the rule takes them; 4: the
+// same sampling rule on records in cell order (pruned distance updates): every point knows its
+// place t in the walk, and the windows of the cell-ordered variant run over t instead of the index.
 template <int T, int P, bool BQ, bool PERM, int MODE>
 __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, const Where& wh,
                                           uint32_t& it, uint32_t& seq)
 {
-    constexpr bool WIDE = MODE == 2;
+    constexpr bool WIDE = MODE >= 2;
+    constexpr bool WALK = MODE == 3;                // positions are the scan order itself
+    constexpr bool RANKED = MODE == 4;              // cell order, threshold phase by place in the walk
+    constexpr bool WINDOWS = PERM && !WALK;         // cell order: the lowest indices (places) through a window
+    static_assert(MODE < 3 || (PERM && !BQ), "the scattered scan order works on reordered records");
     const int n = a.n, N = a.N;
     const bool writer = (wh.g == 0 && wh.tid == 0);
     const float* cloud = a.xyz + (int64_t)wh.c * N * 3;
@@ -1423,6 +1759,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 pt.y[p] = r.y;
                 pt.z[p] = r.z;
                 pt.oi[p] = __float_as_uint(r.w);
+                if constexpr (RANKED) pt.rk[p] = (uint32_t)(((uint64_t)pt.oi[p] * a.walk_inv) % (uint64_t)N);
                 pt.d[p] = __builtin_inff();
                 lo[0] = fminf(lo[0], r.x);
                 lo[1] = fminf(lo[1], r.y);
@@ -1435,6 +1772,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 pt.y[p] = kPadCoord;
                 pt.z[p] = kPadCoord;
                 pt.oi[p] = kNoIdx;
+                if constexpr (RANKED) pt.rk[p] = kNoIdx;
                 pt.d[p] = 0.0f;
             }
         }
@@ -1484,6 +1822,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         }
     }
     if (wh.tid < kCandMax + 2) sh.live[wh.tid] = 0;    // round tags start at 1 in every cloud
+    if (wh.tid == 0) sh.progress = 0;
     if (wh.tid < 32) {
         int64_t ik = ((int64_t)a.m * (wh.tid + 1)) / 32;
         sh.mlp_pos[wh.tid] = a.mlp ? (int)(ik < 1 ? 1 : ik) : -1;
@@ -1506,7 +1845,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     st.om = 0.25f;
     st.my_bl = wh.tid < a.nseg ? boundary_index(n, a.nseg, wh.tid + 1) : -1;
 #ifdef FASTPOINT_PHASE_CLOCKS
-    for (int k = 0; k < 8; ++k) st.clk[k] = 0;
+    for (int k = 0; k < 12; ++k) st.clk[k] = 0;
     const long long cloud_t0__ = wall_clock64();
 #endif
     if (wh.tid == 0) {
@@ -1514,6 +1853,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #ifdef FASTPOINT_PHASE_CLOCKS
         sh.chain_cycles = 0;
         sh.chain_picks = 0;
+        for (int k = 0; k < 8; ++k) sh.scan_clk[k] = 0;
 #endif
         Cand c0;                       // first step of Alg. 1: the seed is sample 0, not folded yet
         c0.idx = (uint32_t)start;
@@ -1628,7 +1968,8 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 
         // ---- threshold sampling (main loop of Alg. 2), running-distance form
         // candidates per round: one or (WIDE) two per lane of the control wave
-        constexpr int kCandThr = WIDE ? kCandMax : kCand;
+        constexpr int kCandThr = WINDOWS ? kCandWin : (WIDE ? kCandMax : kCand);
+        [[maybe_unused]] constexpr int kWinAim = kCandWin * 3 / 4;      // candidates a window is sized for
         // The quota rule (the level floor of Alg. 2) puts sample position i on level 1 + floor(i nseg / n), i.e. on a
         // level above l as soon as i >= ceil(n l / nseg): the positions are tabulated once, a round
         // then compares with the one that ends its level.
@@ -1655,7 +1996,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             }
             fold_pending<T, P, BQ, PERM>(pt, sh, wh, a, st.npend, st.i - st.npend);   // picks since the last sweep
             st.npend = 0;
-            if constexpr (PERM) refresh_bound<P, BQ>(pt);
+            if constexpr (WINDOWS) refresh_bound<P, BQ>(pt);      // (else the last bound stays: never too low)
             const float r2 = unif(sh.thr[seg - 1]);
             // samples of this level end where the quota rule would raise the level
             const int limit = (level_end < n ? level_end : n) - st.i;
@@ -1664,8 +2005,9 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #ifdef FASTPOINT_PHASE_CLOCKS
             const long long thr_t0 = wall_clock64();
 #endif
-            int total = scan_candidates<T, P, BQ, PERM, false, kCandThr, PERM>(pt, sh, wh, a, seq, r2, alltot,
-                                                                               win_lo, win_len);
+            int total = scan_candidates<T, P, BQ, PERM, false, kCandThr, WINDOWS, RANKED,
+                                        (kCandThr < kCandMax ? kCandThr : kCandMax)>(pt, sh, wh, a, seq, r2, alltot,
+                                                                                     win_lo, win_len);
 #ifdef FASTPOINT_PHASE_CLOCKS
             const long long thr_t1 = wall_clock64();
             st.clk[4] += thr_t1 - thr_t0;
@@ -1675,10 +2017,11 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 break;
             }
             [[maybe_unused]] bool window_is_last = false;
-            if constexpr (PERM) {
+            if constexpr (WINDOWS) {
                 window_is_last = (uint64_t)win_lo + win_len >= (uint64_t)N;
-                if (total >= 0 && alltot > kCandThr) {      // more than a round holds: a shorter window
-                    const uint64_t len = (uint64_t)win_len * (uint64_t)(kCandThr * 7 / 8) / (uint64_t)alltot;
+                if (alltot > total) {       // more than a round (or a workgroup's list) holds: a shorter window
+                    uint64_t len = (uint64_t)win_len * (uint64_t)kWinAim / (uint64_t)alltot;
+                    if (len > win_len / 2) len = win_len / 2;
                     win_len = len < 1 ? 1u : (uint32_t)len;
                     continue;
                 }
@@ -1697,10 +2040,43 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 win_lo = 0;
                 continue;
             }
-            if constexpr (PERM) sort_candidates<T>(sh, wh, total);
-            const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
-            if (wh.ctrl) resolve_threshold<T, WIDE>(sh, wh, st, total, limit, r2, tag);
-            else follow_picks<T, P, BQ, PERM, WIDE>(pt, sh, wh, a, st.i, tag, total);
+#ifdef FASTPOINT_PHASE_CLOCKS
+            const long long thr_t2 = wall_clock64();
+#endif
+            if constexpr (WINDOWS) {
+                build_relations<T, RANKED>(sh, wh, a, seq, total, r2);
+                __syncthreads();
+                if (uni(sh.ctrl[2]) != 0) {     // a wait between workgroups expired
+                    ok = false;
+                    break;
+                }
+#ifdef FASTPOINT_PHASE_CLOCKS
+                const long long thr_t3 = wall_clock64();
+                st.clk[9] += thr_t3 - thr_t2;
+#endif
+                NearWords nw = {};
+                if (wh.ctrl) settle_relations<T>(sh, wh, st, total, limit);
+                else nw = near_candidates<T, P, BQ>(pt, sh, wh, total);
+                __syncthreads();
+#ifdef FASTPOINT_PHASE_CLOCKS
+                const long long thr_t4 = wall_clock64();
+                st.clk[10] += thr_t4 - thr_t3;
+#endif
+                if (!wh.ctrl) fold_accepted<T, P, BQ>(pt, sh, wh, a, nw);
+#ifdef FASTPOINT_PHASE_CLOCKS
+                st.clk[11] += wall_clock64() - thr_t4;
+#endif
+            } else if constexpr (WALK) {
+                const uint32_t round_no = ((uint32_t)(st.resolved + 1) & 0x7FFFu) + 1u;   // never 0
+                build_conflicts<T>(sh, wh, total, r2);
+                __syncthreads();
+                if (wh.ctrl) resolve_conflicts<T>(sh, wh, st, total, limit, round_no);
+                else follow_stream<T, P, BQ>(pt, sh, wh, a, round_no);
+            } else {
+                const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
+                if (wh.ctrl) resolve_threshold<T, WIDE>(sh, wh, st, total, limit, r2, tag);
+                else follow_picks<T, P, BQ, PERM, WIDE>(pt, sh, wh, a, st.i, tag, total);
+            }
             __syncthreads();
             ++st.resolved;
             st.npend = 0;                           // folded while they were resolved
@@ -1709,12 +2085,12 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             st.clk[5] += wall_clock64() - thr_t1;
 #endif
             bool exhausted = alltot < kCandThr;
-            if constexpr (PERM) {
+            if constexpr (WINDOWS) {
                 // the quota did not cut the round short (checked below): the window is worked off;
-                // the next one is as long as should hold seven eighths of a round's candidates
+                // the next one is as long as should hold three quarters of a round's candidates
                 exhausted = window_is_last;
                 win_lo = window_is_last ? 0u : win_lo + win_len;
-                uint64_t len = (uint64_t)win_len * (uint64_t)(kCandThr * 7 / 8) / (uint64_t)(alltot > 0 ? alltot : 1);
+                uint64_t len = (uint64_t)win_len * (uint64_t)kWinAim / (uint64_t)(alltot > 0 ? alltot : 1);
                 if (len > (uint64_t)win_len * 2) len = (uint64_t)win_len * 2;     // availability is uneven along the indices
                 win_len = len < 1 ? 1u : (len > (uint64_t)N ? (uint32_t)N : (uint32_t)len);
             }
@@ -1771,6 +2147,9 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             for (int k = 0; k < 4; ++k) inf.thr2[8 + k] = (float)st.clk[k] * 0.01f;   // 100 MHz ticks
             st.clk[7] = wall_clock64() - cloud_t0__;
             for (int k = 4; k < 8; ++k) inf.level_start[4 + k] = (int)st.clk[k];      // 10 ns ticks
+            for (int k = 8; k < 12; ++k) inf.level_exhausted[k] = (int)st.clk[k];
+            for (int k = 0; k < 4; ++k) inf.level_exhausted[12 + k] = (int)sh.scan_clk[k];
+            inf.thr2[14] = (float)sh.scan_clk[4];
             inf.thr2[12] = (float)sh.chain_cycles;
             inf.thr2[13] = (float)sh.chain_picks;
         }
@@ -1778,6 +2157,14 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         inf.status = ok ? 0 : 2;
         a.info[wh.c] = inf;
     }
+#ifdef FASTPOINT_PHASE_CLOCKS
+    if (a.dbg && wh.tid == 0) {
+        for (int k = 0; k < 8; ++k) a.dbg[wh.g * 16 + k] = sh.scan_clk[k];
+        for (int k = 8; k < 12; ++k) a.dbg[wh.g * 16 + k] = st.clk[k];
+        a.dbg[wh.g * 16 + 12] = st.clk[4];
+        a.dbg[wh.g * 16 + 13] = st.clk[5];
+    }
+#endif
     if (!ok && wh.g == 0)
         for (int k = wh.tid; k < n; k += T + kCtrlThreads) {
             a.out_idx[(int64_t)wh.c * n + k] = -1;
@@ -1841,11 +2228,14 @@ const void* pick_mode(int mode)
 template <int T, int P>
 const void* pick_bq(bool bq, bool perm, int mode)
 {
-    if (perm) {                     // cell-ordered: no recording, threshold rounds always wide
+    if (perm) {                     // reordered records: no recording, threshold rounds always wide
         if (bq || mode == 1) return nullptr;
+        if (mode == 3) return reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, 3>);
+        if (mode == 4) return reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, 4>);
         return mode == 0 ? reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, 0>)
                          : reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, 2>);
     }
+    if (mode >= 3) return nullptr;
     if (bq) return pick_mode<T, P, true, false>(mode);
     // without recording the wide rounds were faster on every shape
     return mode == 1 ? nullptr : pick_mode<T, P, false, false>(mode);
@@ -1865,6 +2255,30 @@ const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool
         }
     }
     return nullptr;
+}
+
+// Records (x, y, z, index bits) of every cloud in the order of the walk j_t = (t A) mod N.
+__global__ void scan_walk_kernel(const float* __restrict__ xyz, int64_t total, int N, uint64_t stride,
+                                 float4* __restrict__ out)
+{
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += step) {
+        const int64_t b = e / N;
+        const uint64_t t = (uint64_t)(e - b * N);
+        const uint32_t j = (uint32_t)((t * stride) % (uint64_t)N);         // t, A < 2^31: no overflow
+        const float* src = xyz + (b * N + (int64_t)j) * 3;
+        out[e] = make_float4(src[0], src[1], src[2], __uint_as_float(j));
+    }
+}
+
+hipError_t launch_scan_walk(const float* xyz, int B, int N, int64_t stride, float4* out, hipStream_t stream)
+{
+    const int64_t total = (int64_t)B * N;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(scan_walk_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, xyz, total, N,
+                       (uint64_t)stride, out);
+    return hipGetLastError();
 }
 
 hipError_t launch_zero_words(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2, hipStream_t stream)

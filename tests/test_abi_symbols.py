@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     from paper_2507_23480_amd import binding
     # fp_mdps_params: float,int32,double,float,int32,int32,int32,float[16],float[16],pointer; info: 2+16+16+16+2 words
-    assert ctypes.sizeof(binding.FpMdpsParams) == 168
+    assert ctypes.sizeof(binding.FpMdpsParams) == 176
     assert ctypes.sizeof(binding.FpMdpsInfo) == 4 * (2 + 16 + 16 + 16 + 2 + 4)
 
 

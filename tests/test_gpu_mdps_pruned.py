@@ -3,7 +3,10 @@ of Algorithm 2, through the C ABI: indices, thresholds and level bookkeeping bit
 pruned sampler holds the cloud in cell order and finds "the lowest available index" through a
 window of indices, so the cases stress what depends on that: clouds whose index order follows
 space and clouds where it does not, equal distances, windows that come up empty or too full,
-levels that end by quota and by exhaustion, several workgroups per cloud."""
+levels that end by quota and by exhaustion, several workgroups per cloud.  Every case runs with both
+scan orders of the threshold phase: the lowest available index, and the first available point of the
+scattered walk (there the windows run over a point's place in the walk instead of its index)."""
+import dataclasses
 import sys
 
 import numpy as np
@@ -26,6 +29,11 @@ def fp():
     binding.set_wg_per_cloud(0)
 
 
+@pytest.fixture(params=[0, 1], ids=["index_order", "scattered_order"])
+def order(request):
+    return request.param
+
+
 def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
@@ -38,10 +46,11 @@ def say(*a):
 def rparams(prm):
     return ref.MdpsParams(p=prm.p, nseg=prm.nseg, exponent=prm.exponent, bias=prm.bias,
                           fit_window=prm.fit_window, m_min=prm.m_min, thr_override=prm.thr_override,
-                          level_scale=prm.level_scale)
+                          level_scale=prm.level_scale, scan_order=prm.scan_order)
 
 
-def check(fp, batch, n, prm, start=None, G=0):
+def check(fp, batch, n, prm, start=None, G=0, order=0):
+    prm = dataclasses.replace(prm, scan_order=order)
     fp.set_wg_per_cloud(G)
     try:
         B = batch.shape[0]
@@ -67,12 +76,12 @@ def check(fp, batch, n, prm, start=None, G=0):
         fp.set_wg_per_cloud(0)
 
 
-def test_line_examples_and_overrides(fp):
+def test_line_examples_and_overrides(fp, order):
     line = np.zeros((1, 9, 3), np.float32)
     line[0, :, 0] = np.arange(9)
-    check(fp, line, 5, fp.MdpsParams(p=0.2, nseg=1, m_min=1, thr_override=[3.0]))
-    check(fp, line, 5, fp.MdpsParams(p=0.2, nseg=1, m_min=1, thr_override=[4.0]))
-    check(fp, line, 6, fp.MdpsParams(p=0.2, nseg=2, m_min=1, thr_override=[10.0, 2.0]))
+    check(fp, line, 5, fp.MdpsParams(p=0.2, nseg=1, m_min=1, thr_override=[3.0]), order=order)
+    check(fp, line, 5, fp.MdpsParams(p=0.2, nseg=1, m_min=1, thr_override=[4.0]), order=order)
+    check(fp, line, 6, fp.MdpsParams(p=0.2, nseg=2, m_min=1, thr_override=[10.0, 2.0]), order=order)
 
 
 @pytest.mark.parametrize("N,n,G,nseg,e,bias", [
@@ -80,46 +89,46 @@ def test_line_examples_and_overrides(fp):
     (4096, 1024, 0, 6, 0.8586, 1.04), (4096, 1024, 0, 1, 0.8586, 1.0), (4096, 1024, 0, 16, 0.8586, 1.1),
     (4097, 700, 0, 6, 0.8, 1.0), (9000, 2000, 2, 6, 0.8, 1.05), (9000, 2000, 3, 6, 0.8, 0.9),
     (20000, 5000, 0, 6, 0.8, 1.04), (20000, 5000, 7, 4, 0.8, 1.2), (300, 9, 0, 6, 1.0, 1.0)])
-def test_uniform_cube(fp, N, n, G, nseg, e, bias):
-    say("pruned mdps N=%d n=%d G=%d nseg=%d e=%g bias=%g" % (N, n, G, nseg, e, bias))
+def test_uniform_cube(fp, order, N, n, G, nseg, e, bias):
+    say("pruned mdps order=%d N=%d n=%d G=%d nseg=%d e=%g bias=%g" % (order, N, n, G, nseg, e, bias))
     batch = inputs.uniform_cube(200 + N, N)[None]
-    check(fp, batch, n, fp.MdpsParams(nseg=nseg, exponent=e, bias=bias), G=G)
+    check(fp, batch, n, fp.MdpsParams(nseg=nseg, exponent=e, bias=bias), G=G, order=order)
 
 
-def test_index_order_follows_space(fp):
+def test_index_order_follows_space(fp, order):
     # points sorted along x: a window of indices is a slab of space, so windows come up
     # full near unsampled slabs and empty elsewhere
     say("pruned mdps, cloud sorted along x")
     cloud = inputs.uniform_cube(71, 6000)
     cloud = cloud[np.argsort(cloud[:, 0], kind="stable")]
-    check(fp, cloud[None], 1500, fp.MdpsParams(exponent=0.8, bias=1.04))
-    check(fp, cloud[None], 1500, fp.MdpsParams(exponent=0.8, bias=1.04), start=[5999], G=4)
+    check(fp, cloud[None], 1500, fp.MdpsParams(exponent=0.8, bias=1.04), order=order)
+    check(fp, cloud[None], 1500, fp.MdpsParams(exponent=0.8, bias=1.04), start=[5999], G=4, order=order)
 
 
-def test_equal_distances_and_duplicates(fp):
+def test_equal_distances_and_duplicates(fp, order):
     lat = inputs.lattice_with_ties(7, 600, 5)[None]
-    check(fp, lat, 200, fp.MdpsParams(exponent=0.8, bias=1.0), start=[5])
-    check(fp, lat, 200, fp.MdpsParams(nseg=3, thr_override=[float("inf")] * 3))   # == exact FPS
-    check(fp, lat, 200, fp.MdpsParams(nseg=1, thr_override=[1.17549435e-38]))      # everything stays available
+    check(fp, lat, 200, fp.MdpsParams(exponent=0.8, bias=1.0), start=[5], order=order)
+    check(fp, lat, 200, fp.MdpsParams(nseg=3, thr_override=[float("inf")] * 3), order=order)   # == exact FPS
+    check(fp, lat, 200, fp.MdpsParams(nseg=1, thr_override=[1.17549435e-38]), order=order)      # everything stays available
     batch = np.stack([inputs.lattice_with_ties(20 + b, 1500, 5) for b in range(3)])
-    check(fp, batch, 500, fp.MdpsParams(exponent=0.8, bias=1.0), G=2)
+    check(fp, batch, 500, fp.MdpsParams(exponent=0.8, bias=1.0), G=2, order=order)
 
 
-def test_clustered_cloud(fp):
+def test_clustered_cloud(fp, order):
     # dense clusters and a sparse background: availability per index window varies widely
     rng = np.random.Generator(np.random.PCG64(77))
     parts = [rng.normal(c, 0.01, (1500, 3)) for c in rng.uniform(-1, 1, (4, 3))]
     parts.append(rng.uniform(-1, 1, (2000, 3)))
     cloud = np.concatenate(parts).astype(np.float32)          # index order: cluster by cluster
-    check(fp, cloud[None], 2000, fp.MdpsParams(exponent=0.8, bias=1.04))
-    check(fp, cloud[rng.permutation(cloud.shape[0])][None], 2000, fp.MdpsParams(exponent=0.8, bias=1.04), G=3)
+    check(fp, cloud[None], 2000, fp.MdpsParams(exponent=0.8, bias=1.04), order=order)
+    check(fp, cloud[rng.permutation(cloud.shape[0])][None], 2000, fp.MdpsParams(exponent=0.8, bias=1.04), G=3, order=order)
 
 
-def test_batches_and_start_indices(fp):
+def test_batches_and_start_indices(fp, order):
     say("pruned mdps C2 batch")
     batch = inputs.make_batch("C2")
-    check(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.1))
-    check(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.0), start=[(91 * b) % 1024 for b in range(16)])
+    check(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.1), order=order)
+    check(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.0), start=[(91 * b) % 1024 for b in range(16)], order=order)
 
 
 def test_mlp_estimator(fp):
@@ -150,15 +159,15 @@ def test_argument_checks(fp):
 
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
-def test_workloads_equal_mdps_sample(fp, name):
+def test_workloads_equal_mdps_sample(fp, order, name):
     """Full size, the configuration bench.py times: identical to mdps_sample (which the workload
     tests pin to the oracle), level bookkeeping included."""
     from paper_2507_23480_amd import calibration
-    say("pruned mdps at workload", name)
+    say("pruned mdps at workload", name, "scan order", order)
     wl = inputs.WORKLOADS[name]
     st = wl.stages[0]
     x = dev(inputs.make_batch(name))
-    prm = calibration.params_for(name, 0)
+    prm = dataclasses.replace(calibration.params_for(name, 0), scan_order=order)
     a, ainfo = fp.mdps_sample(x, st.n, prm, want_info=True)
     b, binfo = fp.mdps_sample_pruned(x, st.n, prm, want_info=True)
     torch.cuda.synchronize()

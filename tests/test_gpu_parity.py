@@ -43,7 +43,7 @@ def oracle_batch(fn, batch, *args):
 def rparams(prm):
     return ref.MdpsParams(p=prm.p, nseg=prm.nseg, exponent=prm.exponent, bias=prm.bias,
                           fit_window=prm.fit_window, m_min=prm.m_min, thr_override=prm.thr_override,
-                          level_scale=prm.level_scale)
+                          level_scale=prm.level_scale, scan_order=getattr(prm, "scan_order", 0))
 
 
 def check_fps(fp, batch, n, start=None, G=0):
@@ -162,6 +162,51 @@ def test_mdps_batches(fp):
     check_mdps(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.1))
     check_mdps(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.0),
                start=[(91 * b) % 1024 for b in range(16)])
+
+
+# ------------------------------------------------- MDPS, scattered scan order of the threshold phase
+@pytest.mark.parametrize("N,n,G,nseg,e,bias", [
+    (400, 100, 0, 6, 0.8, 1.0), (400, 100, 0, 6, 0.8, 1.3), (1000, 999, 0, 6, 0.8, 0.7),
+    (4096, 1024, 0, 6, 0.8586, 1.04), (4096, 1024, 0, 1, 0.8586, 1.0), (4096, 1024, 1, 16, 0.8586, 1.1),
+    (4097, 700, 0, 6, 0.8, 1.0), (6000, 1500, 3, 6, 0.8, 1.0), (9000, 2000, 2, 6, 0.8, 1.05),
+    (9000, 2000, 3, 6, 0.8, 0.9), (20000, 5000, 0, 6, 0.8, 1.04), (20000, 5000, 7, 4, 0.8, 1.2),
+    (300, 9, 0, 6, 1.0, 1.0), (33000, 8000, 0, 6, 0.8, 1.0)])
+def test_mdps_scattered_order_matches_oracle(fp, N, n, G, nseg, e, bias):
+    # workgroups per cloud chosen so that 2, 4, 8 and 16 points per thread all occur
+    say("mdps scattered N=%d n=%d G=%d nseg=%d e=%g bias=%g" % (N, n, G, nseg, e, bias))
+    batch = inputs.uniform_cube(300 + N, N)[None]
+    check_mdps(fp, batch, n, fp.MdpsParams(nseg=nseg, exponent=e, bias=bias, scan_order=1), G=G)
+
+
+def test_mdps_scattered_order_examples_ties_batches(fp):
+    line = np.zeros((1, 9, 3), np.float32)
+    line[0, :, 0] = np.arange(9)
+    check_mdps(fp, line, 5, fp.MdpsParams(p=0.2, nseg=1, m_min=1, thr_override=[3.0], scan_order=1))
+    check_mdps(fp, line, 6, fp.MdpsParams(p=0.2, nseg=2, m_min=1, thr_override=[10.0, 2.0], scan_order=1))
+    lat = inputs.lattice_with_ties(7, 600, 5)[None]
+    check_mdps(fp, lat, 200, fp.MdpsParams(exponent=0.8, bias=1.0, scan_order=1), start=[5])
+    check_mdps(fp, lat, 200, fp.MdpsParams(nseg=3, thr_override=[float("inf")] * 3, scan_order=1))   # == exact FPS
+    check_mdps(fp, lat, 200, fp.MdpsParams(nseg=1, thr_override=[1.17549435e-38], scan_order=1))
+    say("mdps scattered C2 batch")
+    batch = inputs.make_batch("C2")
+    check_mdps(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.1, scan_order=1))
+    check_mdps(fp, batch, 512, fp.MdpsParams(exponent=1.2069, bias=1.0, scan_order=1),
+               start=[(91 * b) % 1024 for b in range(16)])
+    say("mdps scattered, more clouds than resident workgroups")
+    many = np.stack([inputs.uniform_cube(700 + b, 200) for b in range(300)])
+    check_mdps(fp, many, 50, fp.MdpsParams(exponent=0.8, bias=1.0, scan_order=1))
+
+
+def test_mdps_scattered_order_refusals(fp):
+    xyz = dev(inputs.uniform_cube(5, 2000)[None])
+    prm = fp.MdpsParams(exponent=0.8, scan_order=1)
+    with pytest.raises(RuntimeError):         # does not record
+        fp.mdps_sample(xyz, 100, prm, bq_cache=fp.new_bq_cache(xyz, 100), bq_radius=0.1)
+    with pytest.raises(RuntimeError):         # the workspace of the index order is too small
+        fp.mdps_sample(xyz, 100, prm, ws=fp.new_workspace(xyz.device, 1, 2000))
+    with pytest.raises(RuntimeError):
+        fp.mdps_sample(xyz, 100, fp.MdpsParams(exponent=0.8, scan_order=2))
+    torch.cuda.synchronize()
 
 
 # ---------------------------------------------------------------------- ball query
