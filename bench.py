@@ -23,6 +23,7 @@ step, redundancy-free form of Section 4.2) are timed per stage and reported unde
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--no-extra]
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -322,6 +323,27 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             raise RuntimeError("mdps_sample_pruned differs from mdps_sample")
         ms["mdps_sample"] = mp_plain[0]
         ms["mdps_sample_pruned"] = mp[0]
+        # The scattered scan order of the threshold phase (Section 4.1 step 3 takes any available
+        # point; here the first one of a walk with a golden-ratio stride instead of the lowest
+        # index): on the cloud in walk order, and in cell order with pruned updates.  The fastest
+        # sampler of the library on large clouds; it does not record, so its ball query is the
+        # grid's (timed on its samples).
+        sprm = dataclasses.replace(sg["prm"], scan_order=1)
+        sc = time_call(torch, lambda: fp.mdps_sample(x, n, sprm, want_info=True))
+        scp = time_call(torch, lambda: fp.mdps_sample_pruned(x, n, sprm))
+        if not torch.equal(scp[1], sc[1][0]):
+            raise RuntimeError("mdps_sample_pruned differs from mdps_sample (scattered scan order)")
+        scov = fp.coverage2(x, scp[1]).sqrt() / cov_f
+        gqs = time_call(torch, lambda: fp.ball_query_grid(x, scp[1], sg["radius"], k))
+        torch.cuda.synchronize()
+        sinfos = fp.parse_info(sc[1][1])
+        ms["mdps_sample_scattered"] = sc[0]
+        ms["mdps_sample_pruned_scattered"] = scp[0]
+        ms["ball_query_grid_scattered"] = gqs[0]
+        scattered_detail = {"coverage_ratio_max": float(scov.max()), "coverage_ratio_mean": float(scov.mean()),
+                            "fps_tail_fraction_mean": float(sum((n - i.et_index) / n for i in sinfos) / len(sinfos)),
+                            "rounds_mean": float(sum(i.rounds for i in sinfos) / len(sinfos)),
+                            "sample_spacing_ratio": sample_spacing(torch, fp, x, scp[1]) / sample_spacing(torch, fp, x, idx)}
         # MDPS with the MLP curve estimator of Appendix A.3 in place of the power function
         # (outside the timed step): latency and sampling quality
         from paper_2507_23480_amd import mlp_estimator
@@ -389,6 +411,7 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             "cached_ball_query_equals_brute": cached_equal,
             "mdps_mlp_estimator": mlp_detail,
             "mdps_paper_estimator": paper_detail,
+            "mdps_scattered_order": scattered_detail,
             "roofline": roof})
     return out
 
@@ -671,18 +694,23 @@ def path_summary(wl, detail, ms_per_step, launch_mode, roof):
     """The short entry of one workload: time of the exact path (fps_exact + brute-force ball query
     [+ gather of the next stage's input]) and of the FastPoint path (mdps_sample recording the
     radius tests + ball query from the record), summed over the stages, each kernel timed alone."""
-    exact = fast = fast_grid = 0.0
+    exact = fast = fast_grid = best = 0.0
     for st in detail["stages"]:
         ms = st["kernel_ms"]
         exact += ms["fps_exact"] + ms["ball_query_brute"] + ms.get("gather", 0.0)
         fast += ms["mdps_sample+record"] + ms["ball_query_cached"]
         # the same samples and neighbours without the record: plain MDPS, then the grid ball query
         fast_grid += ms["mdps_sample"] + ms["ball_query_grid"]
+        # the fastest sampler and ball query per stage: MDPS with either scan order, with or without
+        # pruned updates, then the grid ball query on its samples (or the record where that wins)
+        best += min(min(ms["mdps_sample"], ms["mdps_sample_pruned"]) + ms["ball_query_grid"],
+                    min(ms["mdps_sample_scattered"], ms["mdps_sample_pruned_scattered"]) + ms["ball_query_grid_scattered"],
+                    ms["mdps_sample+record"] + ms["ball_query_cached"])
     pts = wl.B * wl.N / 1e6
     s0 = detail["stages"][0]
     return {"ms_per_step": round(ms_per_step, 4), "launch": "graph" if launch_mode == GRAPH else "eager",
             "exact_path_ms": round(exact, 4), "fastpoint_path_ms": round(fast, 4),
-            "mdps_plus_grid_query_ms": round(fast_grid, 4),
+            "mdps_plus_grid_query_ms": round(fast_grid, 4), "best_mdps_path_ms": round(best, 4),
             "exact_Mpoints_s": round(pts / (exact * 1e-3), 2), "fastpoint_Mpoints_s": round(pts / (fast * 1e-3), 2),
             "mdps_coverage_ratio_max": round(max(st["mdps_coverage_ratio_max"] for st in detail["stages"]), 4),
             # the estimator as the paper defines it (level_scale = 1): worst coverage ratio, share of the
@@ -692,6 +720,12 @@ def path_summary(wl, detail, ms_per_step, launch_mode, roof):
             "paper_est_fps_tail": round(s0["mdps_paper_estimator"]["fps_tail_fraction_mean"], 4),
             "fps_tail": round(s0["mdps_fps_tail_fraction_mean"], 4),
             "mdps_over_fps_time": round(s0["kernel_ms"]["mdps_sample"] / s0["kernel_ms"]["fps_exact"], 3),
+            # the fastest MDPS variant of stage 0 (scan order, pruning) against fps_exact, and its coverage
+            "best_mdps_over_fps_time": round(min(s0["kernel_ms"][v] for v in (
+                "mdps_sample", "mdps_sample_pruned", "mdps_sample_scattered", "mdps_sample_pruned_scattered"))
+                / s0["kernel_ms"]["fps_exact"], 3),
+            "scattered_coverage_max": round(max(st["mdps_scattered_order"]["coverage_ratio_max"]
+                                                for st in detail["stages"]), 4),
             "dominant_kernel": roof["kernel"].replace(" (stage 0)", ""), "dominant_frac": round(roof["frac"], 4)}
 
 
@@ -781,7 +815,8 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
         for key in ("detail_file",):
             line.pop(key, None)
         for w in line["workloads"].values():
-            w.pop("dominant_kernel", None)
+            for key in ("dominant_kernel", "exact_Mpoints_s", "fastpoint_Mpoints_s", "launch"):
+                w.pop(key, None)
         text = json.dumps(line)
     sys.stdout.flush()
     print(text, flush=True)

@@ -77,10 +77,10 @@ typedef struct fp_mdps_params {
                              0.6180339887498949 N)) that is coprime to N -- successive points of
                              the walk lie far apart in index, so a cloud stored in scanner order
                              is visited like a shuffled one and more picks of a round survive.
-                             The exact-FPS parts are not affected.  Order 1 needs the larger
-                             workspace of fp_mdps_scattered_workspace_bytes and does not record
-                             (bq_cache must be NULL; FP_ERR_PARAM otherwise, also for the
-                             cell-ordered entry point). */
+                             The exact-FPS parts are not affected.  With order 1 fp_mdps_sample
+                             needs the larger workspace of fp_mdps_scattered_workspace_bytes and
+                             does not record (bq_cache must be NULL; FP_ERR_PARAM otherwise);
+                             fp_mdps_sample_pruned takes either order. */
     int32_t reserved0;    /* 0 */
 } fp_mdps_params;
 
@@ -182,7 +182,7 @@ fp_status fp_fps_exact_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
  * Minimum Distance Prediction Sampling, Algorithm 2 (Section 4.1, Appendix A.1):
  * m = max(floor(p*n), m_min) exact FPS iterations that record the distance
  * curve, thresholds R_l from the estimated curve at the segment ends,
- * threshold-guided picks (lowest available index; level advances on quota or
+ * threshold-guided picks (next available point in prm->scan_order; level advances on quota or
  * on exhaustion), and exact FPS for whatever remains once the last level is
  * exhausted.  If m >= n-1 the call is exact FPS.  Arguments as fp_fps_exact;
  * prm is a HOST pointer.
@@ -201,10 +201,13 @@ fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n,
  * Minimum Distance Prediction Sampling with pruned distance updates -- the same result as
  * fp_mdps_sample, bit for bit: Algorithm 2 on the cell-ordered copy of the cloud that
  * fp_fps_exact_pruned works on, so that the exact iterations (prefix and remainder) and the
- * threshold-guided picks are folded only into the wavefronts they can affect.  "The lowest
- * available index" of the threshold phase is found through a sliding window of indices, since
- * the points are no longer held in index order.  Arguments as fp_mdps_sample without the
- * ball-query cache; workspace of fp_fps_pruned_workspace_bytes(B, N) bytes.
+ * threshold-guided picks are folded only into the wavefronts they can affect.  The points are
+ * no longer held in index order, so the next available points in the scan order (by index, or by
+ * place in the walk of prm->scan_order = 1) are found through a sliding window of that key: a
+ * round takes all available points of the window, up to 256, and settles which of them the
+ * rule of Section 4.1 step 3 would accept one after the other from the pairwise "closer than
+ * R_l" relation between them.  Arguments as fp_mdps_sample without the ball-query cache;
+ * workspace of fp_fps_pruned_workspace_bytes(B, N) bytes.
  */
 fp_status fp_mdps_sample_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
                                 const int32_t* start_idx, const fp_mdps_params* prm,

@@ -72,13 +72,22 @@ def run(name: str, log=print) -> List[dict]:
     # the two other estimators at the default p and nseg: the pure power function of Appendix A.3
     # (no per-segment factors) and the MLP of the same appendix
     from . import mlp_estimator
-    for label, prm in (("pure power function", calibration.params_for(name, 0, "paper")),
-                       ("MLP", mlp_estimator.params_for(name, 0))):
-        idx, info = fp.mdps_sample(x, st.n, prm, want_info=True)
+    # ... and, with the default estimator, the other scan order of the threshold phase and the
+    # cell-ordered sampler with pruned updates (both scan orders)
+    import dataclasses
+    base = calibration.params_for(name, 0)
+    scattered = dataclasses.replace(base, scan_order=1)
+    for label, prm, entry in (("pure power function", calibration.params_for(name, 0, "paper"), fp.mdps_sample),
+                              ("MLP", mlp_estimator.params_for(name, 0), fp.mdps_sample),
+                              ("segment factors, scattered scan order", scattered, fp.mdps_sample),
+                              ("segment factors, pruned updates", base, fp.mdps_sample_pruned),
+                              ("segment factors, scattered scan order, pruned updates", scattered,
+                               fp.mdps_sample_pruned)):
+        idx, info = entry(x, st.n, prm, want_info=True)
         cov = fp.coverage2(x, idx).sqrt() / cov_f
         torch.cuda.synchronize()
         infos = fp.parse_info(info)
-        t = _time(torch, lambda: fp.mdps_sample(x, st.n, prm))
+        t = _time(torch, lambda: entry(x, st.n, prm))
         rows.append({"p": prm.p, "nseg": prm.nseg, "exponent": prm.exponent, "bias": prm.bias, "estimator": label,
                      "mdps_ms": t, "fps_ms": t_fps, "coverage_ratio_max": float(cov.max()),
                      "coverage_ratio_mean": float(cov.mean()),

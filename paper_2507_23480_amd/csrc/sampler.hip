@@ -46,6 +46,7 @@ constexpr uint32_t kNoIdx = 0xFFFFFFFFu;
 constexpr int kStage = 512;             // ring of picks not yet written to global memory (a round adds up to kCandWin)
 constexpr int kFlush = 128;             // ... written out once this many are waiting
 constexpr int kCtrlThreads = 64;        // the control wave, after the T point threads
+constexpr int kRkStride = 512 + kCtrlThreads;   // threads of a workgroup
 
 // ---------------------------------------------------------------- wave helpers
 // Values that are equal in all lanes but come out of LDS or cross-lane operations: telling the
@@ -284,6 +285,9 @@ struct Where {
     int gw;               // wave in cloud
     int c;                // cloud
     uint64_t* rows;       // recording kernels: this wave's [P][64] radius-test words in LDS
+    uint32_t* rk;         // cell order with the scattered scan order: this thread's [P] places in the walk
+                          // j_t = (t A) mod N, in LDS kRkStride words apart (looked at once per scan:
+                          // in registers they would push other values out to scratch memory)
 };
 
 // P floats that stay in registers; element [p] with a wave-uniform p compiles to
@@ -302,7 +306,6 @@ template <int P, bool BQ>
 struct Points {
     typename RegVec<P>::type x, y, z, d;
     typename RegVecU<P>::type oi;       // cell-ordered variant: the point's index in the caller's cloud
-    typename RegVecU<P>::type rk;       // ... with the scattered scan order: its place t in the walk j_t = (t A) mod N
     float lox, loy, loz, hix, hiy, hiz; // cell-ordered variant: box of the wave's points (wave-uniform)
     uint32_t ub;                        // ... and an upper bound of their running distances (bits)
     // recording kernels: where this wave's next entry of the cloud's list goes.  [bq_cur, bq_lim) is
@@ -913,10 +916,11 @@ __device__ __forceinline__ bool plain_pick(Points<P, BQ>& pt, Shared<T>& sh, con
 // cell-ordered variant) the point's own index -- RK: its place in the walk of the scattered scan
 // order -- lies in [win_lo, win_lo + win_len).
 template <int P, bool BQ, bool STRICT, bool WIN, bool RK>
-__device__ __forceinline__ bool passes(const Points<P, BQ>& pt, int p, float thr, uint32_t win_lo, uint32_t win_len)
+__device__ __forceinline__ bool passes(const Points<P, BQ>& pt, const uint32_t* rk, int p, float thr,
+                                       uint32_t win_lo, uint32_t win_len)
 {
     const bool av = STRICT ? (pt.d[p] > thr) : (pt.d[p] >= thr);
-    if constexpr (WIN) return av && (uint32_t)((RK ? pt.rk[p] : pt.oi[p]) - win_lo) < win_len;
+    if constexpr (WIN) return av && (uint32_t)((RK ? rk[p * kRkStride] : pt.oi[p]) - win_lo) < win_len;
     return av;
 }
 
@@ -943,7 +947,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     int cntw = 0;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-        const bool av = passes<P, BQ, STRICT, WIN, RK>(pt, p, thr, win_lo, win_len);
+        const bool av = passes<P, BQ, STRICT, WIN, RK>(pt, wh.rk, p, thr, win_lo, win_len);
         cntw += __builtin_popcountll(__builtin_amdgcn_ballot_w64(av));
     }
     if (wh.lane == 0 && !wh.ctrl) sh.wcnt[wh.w] = cntw;     // the control wave has none (cntw == 0)
@@ -962,7 +966,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         int base = off;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
-            const bool av = passes<P, BQ, STRICT, WIN, RK>(pt, p, thr, win_lo, win_len);
+            const bool av = passes<P, BQ, STRICT, WIN, RK>(pt, wh.rk, p, thr, win_lo, win_len);
             const uint64_t mk = __builtin_amdgcn_ballot_w64(av);
             if (mk != 0 && base < CAP) {
                 const int rank = base + lanes_below(mk);
@@ -973,7 +977,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
                     cd.y = pt.y[p];
                     cd.z = pt.z[p];
                     // (a threshold round does not look at a candidate's distance: RK puts the place in the walk there)
-                    cd.d = RK ? pt.rk[p] : __float_as_uint(pt.d[p]);
+                    cd.d = RK ? wh.rk[p * kRkStride] : __float_as_uint(pt.d[p]);
                     sh.cand[rank] = cd;
                 }
                 base += __builtin_popcountll(mk);
@@ -1759,7 +1763,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 pt.y[p] = r.y;
                 pt.z[p] = r.z;
                 pt.oi[p] = __float_as_uint(r.w);
-                if constexpr (RANKED) pt.rk[p] = (uint32_t)(((uint64_t)pt.oi[p] * a.walk_inv) % (uint64_t)N);
+                if constexpr (RANKED) wh.rk[p * kRkStride] = (uint32_t)(((uint64_t)pt.oi[p] * a.walk_inv) % (uint64_t)N);
                 pt.d[p] = __builtin_inff();
                 lo[0] = fminf(lo[0], r.x);
                 lo[1] = fminf(lo[1], r.y);
@@ -1772,7 +1776,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 pt.y[p] = kPadCoord;
                 pt.z[p] = kPadCoord;
                 pt.oi[p] = kNoIdx;
-                if constexpr (RANKED) pt.rk[p] = kNoIdx;
+                if constexpr (RANKED) wh.rk[p * kRkStride] = kNoIdx;
                 pt.d[p] = 0.0f;
             }
         }
@@ -2184,6 +2188,9 @@ __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a
     wh.w = uni(wh.tid >> 6);
     wh.ctrl = wh.w == T / 64;
     wh.rows = bq_rows + (BQ && !wh.ctrl ? wh.w * P * 64 : 0);    // the control wave folds nothing
+    static_assert(T + kCtrlThreads == kRkStride, "stride of the places in the walk");
+    __shared__ uint32_t rk_words[MODE == 4 ? kRkStride * P : 1];
+    wh.rk = rk_words + (MODE == 4 ? wh.tid : 0);
     wh.G = a.G;
     wh.grp = (int)blockIdx.x / a.G;
     wh.g = (int)blockIdx.x % a.G;

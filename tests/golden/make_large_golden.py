@@ -37,9 +37,11 @@ from oracle import ref                                   # noqa: E402
 from paper_2507_23480_amd import inputs                  # noqa: E402
 
 PKG = os.path.join(ROOT, "paper_2507_23480_amd")
-# variant name -> table of fitted constants (plain JSON written by the calibration module)
-TABLES = {"calibrated": os.path.join(PKG, "mdps_calibration.json"),
-          "paper": os.path.join(PKG, "mdps_calibration_paper.json")}
+# variant name -> (table of fitted constants: plain JSON written by the calibration module,
+#                  scan order of the threshold phase: 0 lowest available index, 1 scattered walk)
+TABLES = {"calibrated": (os.path.join(PKG, "mdps_calibration.json"), 0),
+          "paper": (os.path.join(PKG, "mdps_calibration_paper.json"), 0),
+          "scattered": (os.path.join(PKG, "mdps_calibration.json"), 1)}
 P_RATIO, NSEG, FIT_WINDOW, M_MIN = 0.1, 6, 32, 8
 
 
@@ -48,7 +50,7 @@ def out_path(name):
 
 
 def params_of(variant, name):
-    path = TABLES[variant]
+    path, scan_order = TABLES[variant]
     if not os.path.exists(path):
         return None
     with open(path) as f:
@@ -57,7 +59,8 @@ def params_of(variant, name):
         return None
     ent = ent[0]
     return {"p": P_RATIO, "nseg": NSEG, "exponent": float(ent["exponent"]), "bias": float(ent["bias"]),
-            "fit_window": FIT_WINDOW, "m_min": M_MIN, "level_scale": [float(v) for v in ent["level_scale"]]}
+            "fit_window": FIT_WINDOW, "m_min": M_MIN, "level_scale": [float(v) for v in ent["level_scale"]],
+            "scan_order": scan_order}
 
 
 def run(name, force):
@@ -78,8 +81,11 @@ def run(name, force):
         if p is None:
             continue
         text = json.dumps(p, sort_keys=True)
-        if "params_" + v in have and str(have["params_" + v]) == text:
-            continue
+        if "params_" + v in have:
+            stored = json.loads(str(have["params_" + v]))
+            stored.setdefault("scan_order", 0)          # files written before the field existed
+            if stored == p:
+                continue
         variants[v] = p
         jobs += [("mdps", v, b) for b in range(wl.B)]
     if not jobs:

@@ -12,6 +12,7 @@ C4, C5: the oracle needs minutes for the full job, so
     oracle; cached == brute on every row; coverage bound; properties that hold at any size;
   * full N with a reduced sample count n once more live against the oracle.
 """
+import dataclasses
 import json
 import os
 import sys
@@ -60,7 +61,8 @@ def pmap(fn, items):
 
 def rparams(prm):
     return ref.MdpsParams(p=prm.p, nseg=prm.nseg, exponent=prm.exponent, bias=prm.bias,
-                          fit_window=prm.fit_window, m_min=prm.m_min, level_scale=prm.level_scale)
+                          fit_window=prm.fit_window, m_min=prm.m_min, level_scale=prm.level_scale,
+                          scan_order=prm.scan_order)
 
 
 def d2(a, b):
@@ -92,9 +94,17 @@ def test_full_workload_matches_oracle(fp, cal, name):
         pprm = cal.params_for(name, s, "paper")
         pidx, pinfo = fp.mdps_sample(xyz, st.n, pprm, want_info=True)
         cov_p = fp.coverage2(xyz, pidx).sqrt()
+        # the scattered scan order of the threshold phase, on the cloud in walk order and in cell order
+        sprm = dataclasses.replace(prm, scan_order=1)
+        sidx, sinfo = fp.mdps_sample(xyz, st.n, sprm, want_info=True)
+        spidx, spinfo = fp.mdps_sample_pruned(xyz, st.n, sprm, want_info=True)
+        cov_s = fp.coverage2(xyz, sidx).sqrt()
         kpos, kd2 = fp.knn(xyz, idx, KNN_K)
         mkpos, mkd2, deferred = fp.knn(xyz, midx, KNN_K, bq_cache=cache, want_deferred=True)
         torch.cuda.synchronize()
+        assert torch.equal(sidx, spidx)
+        sidx, sinfos, spinfos = sidx.cpu().numpy(), fp.parse_info(sinfo), fp.parse_info(spinfo)
+        rps = rparams(sprm)
         say("   k-NN points searched by brute force: %s of %d" % (deferred.cpu().tolist(), batch.shape[1]))
         kpos, kd2, mkpos, mkd2 = kpos.cpu().numpy(), kd2.cpu().numpy(), mkpos.cpu().numpy(), mkd2.cpu().numpy()
         idx, mdc, bq, cnt = idx.cpu().numpy(), mdc.cpu().numpy(), bq.cpu().numpy(), cnt.cpu().numpy()
@@ -111,8 +121,15 @@ def test_full_workload_matches_oracle(fp, cal, name):
             wmidx, winfo = ref.mdps_sample(batch[b], st.n, rp)
             wmbq, wmcnt = ref.ball_query(batch[b], wmidx, st.radius, st.k)
             return widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt, ref.knn(batch[b], widx, KNN_K), \
-                ref.knn(batch[b], wmidx, KNN_K), ref.mdps_sample(batch[b], st.n, rpp)
-        for b, (widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt, wk, wmk, wp) in enumerate(pmap(one, range(wl.B))):
+                ref.knn(batch[b], wmidx, KNN_K), ref.mdps_sample(batch[b], st.n, rpp), \
+                ref.mdps_sample(batch[b], st.n, rps)
+        for b, (widx, wmdc, wbq, wcnt, wmidx, winfo, wmbq, wmcnt, wk, wmk, wp, ws) in enumerate(pmap(one, range(wl.B))):
+            assert np.array_equal(sidx[b], ws[0]), "mdps with the scattered scan order, cloud %d" % b
+            for gi in (sinfos[b], spinfos[b]):
+                assert gi.status == 0 and gi.et_index == ws[1].et_index
+                assert np.array_equal(np.array(gi.thr2[:prm.nseg], np.float32), ws[1].thr2)
+                assert list(gi.level_start[:prm.nseg]) == ws[1].level_start.tolist()
+                assert list(gi.level_exhausted[:prm.nseg]) == ws[1].level_exhausted.tolist()
             assert np.array_equal(pidx[b], wp[0]), "mdps with the pure power function, cloud %d" % b
             assert pinfos[b].status == 0 and pinfos[b].et_index == wp[1].et_index
             assert np.array_equal(np.array(pinfos[b].thr2[:pprm.nseg], np.float32), wp[1].thr2)
@@ -128,7 +145,9 @@ def test_full_workload_matches_oracle(fp, cal, name):
         pratio = (cov_p / cov_f).cpu().numpy()
         say("   coverage ratio max %.4f; pure power function (bias %.2f): %.4f, FPS tail %.1f%% of the samples"
             % (ratio.max(), pprm.bias, pratio.max(), 100.0 * np.mean([(st.n - i.et_index) / st.n for i in pinfos])))
-        assert ratio.max() <= COVERAGE_BOUND and pratio.max() <= COVERAGE_BOUND
+        sratio = (cov_s / cov_f).cpu().numpy()
+        say("   scattered scan order: coverage ratio max %.4f" % sratio.max())
+        assert ratio.max() <= COVERAGE_BOUND and pratio.max() <= COVERAGE_BOUND and sratio.max() <= COVERAGE_BOUND
         if s + 1 < len(wl.stages):
             batch = np.stack([ref.gather_xyz(batch[b], idx[b]) for b in range(wl.B)])
 
@@ -147,21 +166,24 @@ def check_against_stored_oracle(fp, name, xyz, idx, mdc):
     assert np.array_equal(idx, gold["fps_idx"]), "%s exact FPS: samples differ from the stored oracle result" % name
     assert np.array_equal(mdc, gold["fps_mdc"]), "%s exact FPS: curve differs from the stored oracle result" % name
     variants = sorted(k[len("params_"):] for k in gold if k.startswith("params_"))
-    assert "calibrated" in variants and "paper" in variants
+    assert "calibrated" in variants and "paper" in variants and "scattered" in variants
     for v in variants:
         p = json.loads(str(gold["params_" + v]))
         prm = fp.MdpsParams(p=p["p"], nseg=p["nseg"], exponent=p["exponent"], bias=p["bias"],
-                            fit_window=p["fit_window"], m_min=p["m_min"], level_scale=p["level_scale"])
-        midx, info = fp.mdps_sample(xyz, n, prm, want_info=True)
-        torch.cuda.synchronize()
-        infos = fp.parse_info(info)
-        assert np.array_equal(midx.cpu().numpy(), gold["mdps_idx_" + v]), \
-            "%s MDPS (%s constants): samples differ from the stored oracle result" % (name, v)
-        for b, gi in enumerate(infos):
-            assert gi.status == 0 and gi.m == gold["m_" + v][b] and gi.et_index == gold["et_index_" + v][b]
-            assert np.array_equal(np.array(gi.thr2[:prm.nseg], np.float32), gold["thr2_" + v][b])
-            assert np.array_equal(np.array(gi.level_start[:prm.nseg]), gold["level_start_" + v][b])
-            assert np.array_equal(np.array(gi.level_exhausted[:prm.nseg]), gold["level_exhausted_" + v][b])
+                            fit_window=p["fit_window"], m_min=p["m_min"], level_scale=p["level_scale"],
+                            scan_order=p.get("scan_order", 0))
+        # both entry points: the cloud as given (or in the order of the walk), and in cell order
+        for entry in (fp.mdps_sample, fp.mdps_sample_pruned):
+            midx, info = entry(xyz, n, prm, want_info=True)
+            torch.cuda.synchronize()
+            infos = fp.parse_info(info)
+            assert np.array_equal(midx.cpu().numpy(), gold["mdps_idx_" + v]), \
+                "%s %s (%s constants): samples differ from the stored oracle result" % (name, entry.__name__, v)
+            for b, gi in enumerate(infos):
+                assert gi.status == 0 and gi.m == gold["m_" + v][b] and gi.et_index == gold["et_index_" + v][b]
+                assert np.array_equal(np.array(gi.thr2[:prm.nseg], np.float32), gold["thr2_" + v][b])
+                assert np.array_equal(np.array(gi.level_start[:prm.nseg]), gold["level_start_" + v][b])
+                assert np.array_equal(np.array(gi.level_exhausted[:prm.nseg]), gold["level_exhausted_" + v][b])
         cov = fp.coverage2(xyz, midx).sqrt() / fp.coverage2(xyz, torch.from_numpy(gold["fps_idx"]).cuda()).sqrt()
         torch.cuda.synchronize()
         say("   %s constants (bias %.2f): all %d x %d MDPS samples equal the stored oracle result, FPS tail %s, "
