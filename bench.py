@@ -65,6 +65,13 @@ TRAFFIC_BYTES = {"C2": {"fps_exact": 454587, "mdps_sample+record": 2344271, "bal
                         "ball_query_brute": 204118505}}
 
 
+PRUNED_RECORD_FROM = 1 << 18
+
+
+def record_sampler(fp, sg):
+    return fp.mdps_sample_pruned if sg["pruned_record"] else fp.mdps_sample
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -125,6 +132,9 @@ def make_context(torch, fp, inputs, calibration, name):
                        "cache": torch.empty(fp.load().fp_bq_cache_bytes(
                            B, N, st.n, BQ_CACHE_ENTRIES.get(name, 0) if s == 0 else 0), dtype=torch.uint8, device="cuda"),
                        "G": fp.plan(B, N)[0],
+                       # which recording sampler the step runs: the cell-ordered one (pruned updates)
+                       # from a quarter of a million points per cloud on, where folds dominate a round
+                       "pruned_record": N >= PRUNED_RECORD_FROM,
                        "ws": [fp.new_workspace(xyz.device, B, N), fp.new_workspace(xyz.device, B, N)]})
         N = st.n
     torch.cuda.synchronize()
@@ -141,7 +151,7 @@ def run_step(fp, ctx, timer, keep=None):
         idx = timer.call("fps_exact/s%d" % s, lambda: fp.fps_exact(xs, n))
         bq = timer.call("ball_query_brute/s%d" % s, lambda: fp.ball_query(xs, idx, r, k))
         midx = timer.call("mdps_sample+record/s%d" % s,
-                          lambda: fp.mdps_sample(xs, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r))
+                          lambda: record_sampler(fp, sg)(xs, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r))
         mbq = timer.call("ball_query_cached/s%d" % s,
                          lambda: fp.ball_query(xs, midx, r, k, bq_cache=sg["cache"]))
         if s + 1 < len(ctx["stages"]):
@@ -166,7 +176,7 @@ def run_step_streams(torch, fp, ctx, keep=None):
         lane = lanes[s % 2]
         lane.wait_stream(main)                      # the stage's input is ready
         with torch.cuda.stream(lane):
-            midx = fp.mdps_sample(x, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r, ws=sg["ws"][1])
+            midx = fp.mdps_sample(x, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r, ws=sg["ws"][1])   # (small clouds)
             mbq = fp.ball_query(x, midx, r, k, bq_cache=sg["cache"])
         idx = fp.fps_exact(x, n, ws=sg["ws"][0])
         x_next = None if s + 1 == len(ctx["stages"]) else fp.gather_xyz(x, idx)
@@ -263,6 +273,9 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             a = point_iters * OPS_PER_POINT_ITERATION / (ms["mdps_sample+record"] * 1e-3) / 1e12
             roof["mdps_sample+record"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS,
                                           "unit": "TFLOP/s", "frac": a / ALU_PEAK_TOPS}
+            if sg["pruned_record"]:
+                roof["mdps_sample+record"]["note"] = ("algorithmic operations of the unpruned update / time: "
+                                                      "the cell-ordered sampler skips most of them")
         if "ball_query_brute" in ms:
             a = pairs * OPS_PER_PAIR_TEST / (ms["ball_query_brute"] * 1e-3) / 1e12
             roof["ball_query_brute"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS,
@@ -323,6 +336,17 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             raise RuntimeError("mdps_sample_pruned differs from mdps_sample")
         ms["mdps_sample"] = mp_plain[0]
         ms["mdps_sample_pruned"] = mp[0]
+        # both recording samplers with their readers (the step runs the one named in record_sampler)
+        other = torch.empty_like(sg["cache"])
+        for label, entry in (("mdps_sample+record_index_order", fp.mdps_sample),
+                             ("mdps_sample_pruned+record", fp.mdps_sample_pruned)):
+            rec = time_call(torch, lambda: entry(x, n, sg["prm"], bq_cache=other, bq_radius=sg["radius"]))
+            rd = time_call(torch, lambda: fp.ball_query(x, rec[1], sg["radius"], k, bq_cache=other))
+            if not (torch.equal(rec[1], midx) and torch.equal(rd[1][0], mbq[0]) and torch.equal(rd[1][1], mbq[1])):
+                raise RuntimeError(label + ": samples or neighbours differ from the step's")
+            ms[label] = rec[0]
+            ms[label.replace("mdps_sample", "ball_query_cached_after")] = rd[0]
+        del other
         # The scattered scan order of the threshold phase (Section 4.1 step 3 takes any available
         # point; here the first one of a walk with a golden-ratio stride instead of the lowest
         # index): on the cloud in walk order, and in cell order with pruned updates.  The fastest
@@ -390,6 +414,7 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
                             "points_searched_by_brute_force": float(kg[1][2].sum().item()) / (B * N)}
         out["stages"].append({
             "N": N, "n": n, "radius": sg["radius"], "k": k, "plan_G_T_P": list(fp.plan(B, N)),
+            "record_sampler": "mdps_sample_pruned" if sg["pruned_record"] else "mdps_sample",
             "kernel_ms": ms,
             # microseconds per sample of a launch (all clouds of the batch run side by side)
             "fps_exact_us_per_sample": ms["fps_exact"] * 1e3 / max(n - 1, 1) if "fps_exact" in ms else None,
@@ -705,7 +730,8 @@ def path_summary(wl, detail, ms_per_step, launch_mode, roof):
         # pruned updates, then the grid ball query on its samples (or the record where that wins)
         best += min(min(ms["mdps_sample"], ms["mdps_sample_pruned"]) + ms["ball_query_grid"],
                     min(ms["mdps_sample_scattered"], ms["mdps_sample_pruned_scattered"]) + ms["ball_query_grid_scattered"],
-                    ms["mdps_sample+record"] + ms["ball_query_cached"])
+                    ms["mdps_sample+record_index_order"] + ms["ball_query_cached_after+record_index_order"],
+                    ms["mdps_sample_pruned+record"] + ms["ball_query_cached_after_pruned+record"])
     pts = wl.B * wl.N / 1e6
     s0 = detail["stages"][0]
     return {"ms_per_step": round(ms_per_step, 4), "launch": "graph" if launch_mode == GRAPH else "eager",
@@ -754,6 +780,8 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
     roof["kernel"] = dom + " (stage 0)"
     roof["ms_per_launch"] = s0["kernel_ms"][dom]
     roof["traffic"] = TRAFFIC_BYTES.get(name, {}).get(dom)
+    if dom == "mdps_sample+record" and ctx["stages"][0]["pruned_record"]:
+        roof["traffic"] = None                     # the counters were read for the index-ordered sampler
     if roof.get("bound") == "alu":
         # the published peak needs packed binary32 instructions, which this path may not use (every
         # operation rounds on its own); the rate the device reaches without them, measured here
@@ -787,7 +815,8 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
         "config": {"workload": "%s: %s" % (name, wl.description), "B": wl.B, "N": wl.N,
                    "stages": [{"n": st.n, "radius": st.radius, "k": st.k} for st in wl.stages],
                    "step": "per stage: fps_exact + ball_query(brute) [+ gather]; "
-                           "mdps_sample(+record) + ball_query(from record)",
+                           "%s(+record) + ball_query(from record)"
+                           % ("mdps_sample_pruned" if ctx["stages"][0]["pruned_record"] else "mdps_sample"),
                    "launch": launch_mode, "mdps": {"p": calibration.P_RATIO, "nseg": calibration.NSEG}},
         "paths": {"exact_path_ms": summary["exact_path_ms"], "fastpoint_path_ms": summary["fastpoint_path_ms"],
                   "exact_Mpoints_s": summary["exact_Mpoints_s"],

@@ -113,7 +113,7 @@ size_t fp_workspace_bytes(int32_t B, int32_t N);
  * ball-query radius of Section 4.2 -- as entries (sample, block of 64 points, 64 test bits),
  * only for blocks a ball reaches, first as the sampler produces them and then in sample order.
  * entries_per_cloud is the caller's choice, <= 0 for the default of 2 N + 16 n (two lists of
- * 16 and 12 bytes per entry: 85 MB for 10^6 points and 65 536 samples).  A ball holding h
+ * 16 and 12 bytes per entry, plus 4 bytes per point: 90 MB for 10^6 points and 65 536 samples).  A ball holding h
  * points needs at most h entries, and about h / 10 when neighbours in space are neighbours in
  * the index order (scanner-ordered clouds); the sampler's wavefronts reserve entries 64 at a
  * time, which can leave up to N + 128 of them unused.  A cloud whose balls reach more blocks than the
@@ -206,12 +206,17 @@ fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n,
  * place in the walk of prm->scan_order = 1) are found through a sliding window of that key: a
  * round takes all available points of the window, up to 256, and settles which of them the
  * rule of Section 4.1 step 3 would accept one after the other from the pairwise "closer than
- * R_l" relation between them.  Arguments as fp_mdps_sample without the ball-query cache;
- * workspace of fp_fps_pruned_workspace_bytes(B, N) bytes.
+ * R_l" relation between them.  Arguments as fp_mdps_sample; workspace of
+ * fp_fps_pruned_workspace_bytes(B, N) bytes.  With a bq_cache the radius tests are recorded as
+ * by fp_mdps_sample (a sample is then also folded into every wavefront its ball can reach); the
+ * blocks of such a record are 64 consecutive positions of the cell order and the record carries the
+ * index at every position: fp_ball_query reads it like any other record (same result), fp_knn
+ * does not use it (it searches all points by brute force, same result).
  */
 fp_status fp_mdps_sample_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
                                 const int32_t* start_idx, const fp_mdps_params* prm,
                                 int32_t* out_idx, fp_mdps_info* info,
+                                void* bq_cache, size_t bq_cache_bytes, float bq_radius,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*

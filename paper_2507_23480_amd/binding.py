@@ -117,7 +117,8 @@ def load() -> ctypes.CDLL:
     lib.fp_mdps_scattered_workspace_bytes.restype = ctypes.c_size_t
     lib.fp_fps_exact_pruned.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.fp_fps_exact_pruned.restype = i32
-    lib.fp_mdps_sample_pruned.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.fp_mdps_sample_pruned.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(FpMdpsParams), vp, vp, vp,
+                                          ctypes.c_size_t, f32, vp, ctypes.c_size_t, vp]
     lib.fp_mdps_sample_pruned.restype = i32
     lib.fp_mdps_sample.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(FpMdpsParams), vp, vp, vp,
                                    ctypes.c_size_t, f32, vp, ctypes.c_size_t, vp]
@@ -259,16 +260,16 @@ def bq_cache_stats(cache: torch.Tensor) -> dict:
     cloud's record is incomplete, entries per cloud after grouping.  For sizing a cache."""
     import struct
     head = cache[:256].cpu().numpy().tobytes()
-    magic, B, N, n, blocks, valid, r2_bits, _ = struct.unpack_from("<Iiiiiiii", head, 0)
-    cap, idx_off, cur_off, ovf_off, rowcnt_off, fill_off, rowoff_off, raw_off, rows_off, nbytes = \
-        struct.unpack_from("<10q", head, 32)
+    magic, B, N, n, blocks, valid, r2_bits, order = struct.unpack_from("<Iiiiiiii", head, 0)
+    cap, idx_off, cur_off, ovf_off, rowcnt_off, fill_off, rowoff_off, raw_off, rows_off, map_off, nbytes = \
+        struct.unpack_from("<11q", head, 32)
     if magic != 0x46504232 or valid != 1:
         raise ValueError("not a recorded ball-query cache")
     u32 = lambda off, count: cache[off:off + 4 * count].cpu().numpy().view("uint32")
     rowoff = u32(rowoff_off, B * (n + 1)).reshape(B, n + 1)
     return {"B": B, "N": N, "n": n, "entries_capacity": int(cap), "chunks_taken": u32(cur_off, B).tolist(),
             "incomplete": [bool(v) for v in u32(ovf_off, B)], "entries": [int(v) for v in rowoff[:, n]],
-            "bytes": int(nbytes)}
+            "bytes": int(nbytes), "cell_order": bool(order)}
 
 
 def _start(start_idx, B, device) -> Optional[torch.Tensor]:
@@ -369,7 +370,8 @@ def _scattered_workspace(xyz: torch.Tensor, B: int, N: int) -> torch.Tensor:
 
 
 def mdps_sample_pruned(xyz: torch.Tensor, n: int, prm: MdpsParams, start_idx=None, want_info: bool = False,
-                       ws: Optional[torch.Tensor] = None):
+                       ws: Optional[torch.Tensor] = None, bq_cache: Optional[torch.Tensor] = None,
+                       bq_radius: float = 0.0):
     """Minimum distance prediction sampling with pruned distance updates: the outputs of mdps_sample."""
     B, N = _xyz(xyz)
     st = _start(start_idx, B, xyz.device)
@@ -378,7 +380,9 @@ def mdps_sample_pruned(xyz: torch.Tensor, n: int, prm: MdpsParams, start_idx=Non
     ws = _pruned_workspace(xyz, B, N, ws)
     c = prm.to_c()
     _check(load().fp_mdps_sample_pruned(xyz.data_ptr(), B, N, n, _ptr(st), ctypes.byref(c), idx.data_ptr(),
-                                        _ptr(info), ws.data_ptr(), ws.numel(), _stream()), "fp_mdps_sample_pruned")
+                                        _ptr(info), _ptr(bq_cache), 0 if bq_cache is None else bq_cache.numel(),
+                                        float(bq_radius), ws.data_ptr(), ws.numel(), _stream()),
+           "fp_mdps_sample_pruned")
     return (idx, info) if want_info else idx
 
 

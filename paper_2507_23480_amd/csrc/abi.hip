@@ -201,7 +201,7 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
     }
     const bool walk = prm != nullptr && prm->scan_order == 1;
     if (prm && (prm->scan_order < 0 || prm->scan_order > 1)) return FP_ERR_PARAM;
-    if (walk && bq_cache) return FP_ERR_PARAM;
+    if (bq_cache && ((walk && !pruned) || (pruned && !prm))) return FP_ERR_PARAM;
     if (!workspace ||
         workspace_bytes < (pruned ? fp_fps_pruned_workspace_bytes(B, N)
                                   : (walk ? fp_mdps_scattered_workspace_bytes(B, N) : fp_workspace_bytes(B, N))) ||
@@ -293,6 +293,7 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
         a.bq_ovf = reinterpret_cast<uint32_t*>(base + lay.ovf_offset);
         a.bq_fill = reinterpret_cast<uint32_t*>(base + lay.fill_offset);
         a.bq_raw = reinterpret_cast<BqRaw*>(base + lay.raw_offset);
+        a.bq_map = reinterpret_cast<int32_t*>(base + lay.map_offset);
         a.bq_cap = lay.cap;
         a.bq_r2 = bq_radius * bq_radius;
         a.bq_blocks = (int32_t)bq_blocks(N);
@@ -313,11 +314,9 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
     // words (stamps start at 1 in every launch) and the chunk counters of a ball-query cache.  (A
     // cloud held by one workgroup has its counters zeroed by that workgroup.)
     if (plan.G > 1) {
-        if (pruned && prm) {                       // ... and, cell-ordered MDPS, the relation words
-            bq_zero = a.ll_rel;
-            bq_zero_words = (int64_t)plan.groups * kRelWordsPerCloud;
-        }
-        if (launch_zero_words(a.ll_pk, kLlWords, bq_zero, bq_zero_words, stream) != hipSuccess)
+        // ... and, cell-ordered MDPS, the relation words
+        const int64_t rel_words = pruned && prm ? (int64_t)plan.groups * kRelWordsPerCloud : 0;
+        if (launch_zero_words(a.ll_pk, kLlWords, bq_zero, bq_zero_words, a.ll_rel, rel_words, stream) != hipSuccess)
             return FP_ERR_DEVICE;
     }
     if (plan.G > 1 && g_cooperative.load())    // the whole grid has to be resident
@@ -407,12 +406,13 @@ fp_status fp_fps_exact_pruned(const float* xyz, int32_t B, int32_t N, int32_t n,
 
 fp_status fp_mdps_sample_pruned(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,
                                 const fp_mdps_params* prm, int32_t* out_idx, fp_mdps_info* info,
-                                void* workspace, size_t workspace_bytes, void* stream)
+                                void* bq_cache, size_t bq_cache_bytes, float bq_radius, void* workspace,
+                                size_t workspace_bytes, void* stream)
 {
     if (!prm) return FP_ERR_NULL;
     if (B > 65535 || (int64_t)B * N > ((int64_t)1 << 33)) return FP_ERR_SHAPE;
-    return run_sampler(xyz, B, N, n, start_idx, prm, out_idx, nullptr, info, nullptr, 0, 0.0f, workspace,
-                       workspace_bytes, stream, true);
+    return run_sampler(xyz, B, N, n, start_idx, prm, out_idx, nullptr, info, bq_cache, bq_cache_bytes, bq_radius,
+                       workspace, workspace_bytes, stream, true);
 }
 
 fp_status fp_mdps_sample(const float* xyz, int32_t B, int32_t N, int32_t n, const int32_t* start_idx,

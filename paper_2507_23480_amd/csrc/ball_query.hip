@@ -329,6 +329,10 @@ __device__ __forceinline__ uint32_t rdlane_u32(uint32_t v, int l)
 // are written.  A centre the record does not cover (not the recorded sample of that position,
 // another radius, a cloud whose list overflowed) is tested against all points by its wave, 64
 // points per step in index order.
+// most hits of a ball that the reader of a cell-ordered record sorts (a ball with more is searched
+// by brute force)
+constexpr int kCellHits = 512;
+
 __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict__ xyz, int B, int N,
                                                         const int32_t* __restrict__ center_idx, int M,
                                                         float r2, int k, int32_t* __restrict__ out_idx,
@@ -338,6 +342,7 @@ __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict_
     __shared__ uint32_t s_blk[4][64];
     __shared__ uint64_t s_mask[4][64];
     __shared__ int32_t s_out[4][256];
+    __shared__ int32_t s_hit[4][kCellHits];
     const int b = (int)blockIdx.y;
     const int lane = (int)threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
@@ -364,6 +369,7 @@ __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict_
     }
     usable = __builtin_amdgcn_readfirstlane(usable ? 1 : 0) != 0;
     int nh = 0;                                             // hits kept so far (uniform)
+    bool done = false;
     if (usable) {
         const uint32_t* off = reinterpret_cast<const uint32_t*>(cache + h->rowoff_offset) +
                               (int64_t)b * ((int64_t)h->n + 1) + q;
@@ -371,7 +377,58 @@ __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict_
         const int E = __builtin_amdgcn_readfirstlane((int)(off[1] - o0));
         const BqEntry* __restrict__ ent = reinterpret_cast<const BqEntry*>(cache + h->rows_offset) +
                                           (int64_t)b * h->cap + o0;
-        if (E <= 64) {
+        done = true;
+        if (h->order == 1) {
+            // A record of the cell-ordered sampler: a block is 64 consecutive positions of that order
+            // and map[] gives the index of the point at a position.  All hits of the ball are turned
+            // into indices, then the k lowest are taken one at a time (a point is in the ball once,
+            // so the values differ).
+            const int32_t* __restrict__ map = reinterpret_cast<const int32_t*>(cache + h->map_offset) + (int64_t)b * N;
+            int32_t* hit_s = s_hit[wave];
+            int total = 0;
+            for (int e0 = 0; e0 < E; e0 += 64) {
+                BqEntry g;
+                g.other = 0u;
+                g.lo = g.hi = 0u;
+                if (e0 + lane < E) g = ent[e0 + lane];
+                uint64_t m = ((uint64_t)g.hi << 32) | g.lo;
+                const int pc = __builtin_popcountll(m);
+                int incl = pc;
+#pragma unroll
+                for (int sft = 1; sft < 64; sft <<= 1) {
+                    const int up = __shfl_up(incl, sft, 64);
+                    if (lane >= sft) incl += up;
+                }
+                int pos = total + incl - pc;
+                while (m != 0) {
+                    if (pos < kCellHits) hit_s[pos] = map[(int64_t)(g.other << 6) + __builtin_ctzll(m)];
+                    ++pos;
+                    m &= m - 1;
+                }
+                total += __builtin_amdgcn_readlane(incl, 63);
+            }
+            if (total > kCellHits) {
+                done = false;
+            } else {
+                // the same wave reads back what it wrote: the LDS keeps a wave's operations in order
+                int32_t v[kCellHits / 64];
+#pragma unroll
+                for (int i = 0; i < kCellHits / 64; ++i) v[i] = lane + 64 * i < total ? hit_s[lane + 64 * i] : 0x7FFFFFFF;
+                const int want = total < k ? total : k;
+                for (int t = 0; t < want; ++t) {
+                    int32_t mn = v[0];
+#pragma unroll
+                    for (int i = 1; i < kCellHits / 64; ++i) mn = min(mn, v[i]);
+#pragma unroll
+                    for (int sft = 32; sft > 0; sft >>= 1) mn = min(mn, __shfl_xor(mn, sft, 64));
+                    mn = __builtin_amdgcn_readfirstlane(mn);
+#pragma unroll
+                    for (int i = 0; i < kCellHits / 64; ++i) v[i] = v[i] == mn ? 0x7FFFFFFF : v[i];
+                    if (lane == 0) out_s[t] = mn;
+                }
+                nh = want;
+            }
+        } else if (E <= 64) {
             BqEntry me;
             me.other = 0xFFFFFFFFu;
             me.lo = me.hi = 0u;
@@ -430,8 +487,10 @@ __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict_
             }
             nh = nh < k ? nh : k;
         }
-    } else {
+    }
+    if (!done) {
         const float cx = cloud[(int64_t)c * 3 + 0], cy = cloud[(int64_t)c * 3 + 1], cz = cloud[(int64_t)c * 3 + 2];
+        nh = 0;
         for (int j0 = 0; j0 < N && nh < k; j0 += 64) {
             const int j = j0 + lane;
             bool hit = false;

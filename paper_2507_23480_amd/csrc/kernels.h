@@ -40,7 +40,8 @@ struct BqHeader {
     int32_t blocks;         // point blocks per cloud, ceil(N / 64)
     int32_t valid;          // 1 once the header is complete
     uint32_t r2_bits;       // radius^2 (binary32 bits) the tests were recorded with
-    int32_t reserved;
+    int32_t order;          // 0: a block is 64 consecutive indices; 1: 64 consecutive positions of the
+                            // sampler's cell order, map[] gives the index at a position
     int64_t cap;            // entries a cloud's lists hold, a multiple of kBqChunk
     int64_t idx_offset;     // byte offset of the int32 [B][n] copy of the sample indices
     int64_t cursor_offset;  // uint32 [B]: chunks of kBqChunk entries handed out to the sampler's waves
@@ -50,6 +51,7 @@ struct BqHeader {
     int64_t rowoff_offset;  // uint32 [B][n + 1]: first entry of each sample's row
     int64_t raw_offset;     // BqRaw [B][cap]
     int64_t rows_offset;    // BqEntry [B][cap], in sample order
+    int64_t map_offset;     // int32 [B][N]: index of the point at each position (order 1 only)
     int64_t bytes;
 };
 
@@ -57,7 +59,7 @@ __host__ __device__ inline int64_t bq_align(int64_t v) { return (v + 255) / 256 
 // entries per cloud the lists are sized for unless the caller says otherwise: two per point and
 // sixteen per sample
 __host__ __device__ inline int64_t bq_capacity(int32_t N, int32_t n) { return 2 * (int64_t)N + 16 * (int64_t)n; }
-__host__ __device__ inline BqHeader bq_layout(int32_t B, int32_t N, int32_t n, float r2, int64_t cap)
+__host__ __device__ inline BqHeader bq_layout(int32_t B, int32_t N, int32_t n, float r2, int64_t cap, int32_t order = 0)
 {
     BqHeader h;
     h.magic = kBqMagic;
@@ -69,7 +71,7 @@ __host__ __device__ inline BqHeader bq_layout(int32_t B, int32_t N, int32_t n, f
     union { float f; uint32_t u; } cv;
     cv.f = r2;
     h.r2_bits = cv.u;
-    h.reserved = 0;
+    h.order = order;
     h.cap = cap / kBqChunk * kBqChunk;
     h.idx_offset = 256;
     // cursor, overflow flags, row counts and chunk fills are one range, zeroed before the sampler runs
@@ -80,7 +82,8 @@ __host__ __device__ inline BqHeader bq_layout(int32_t B, int32_t N, int32_t n, f
     h.rowoff_offset = h.fill_offset + bq_align((int64_t)B * (h.cap / kBqChunk) * 4);
     h.raw_offset = h.rowoff_offset + bq_align((int64_t)B * ((int64_t)n + 1) * 4);
     h.rows_offset = h.raw_offset + bq_align((int64_t)B * h.cap * (int64_t)sizeof(BqRaw));
-    h.bytes = h.rows_offset + bq_align((int64_t)B * h.cap * (int64_t)sizeof(BqEntry));
+    h.map_offset = h.rows_offset + bq_align((int64_t)B * h.cap * (int64_t)sizeof(BqEntry));
+    h.bytes = h.map_offset + bq_align((int64_t)B * N * 4);
     return h;
 }
 
@@ -98,6 +101,7 @@ struct SamplerArgs {
     float level_scale[FP_MAX_SEG];
     unsigned char* bq_base;         // ball-query cache (NULL: nothing is recorded) ...
     int32_t* bq_idx;                // ... its copy of the sample indices [B][n]
+    int32_t* bq_map;                // ... cell-ordered sampler: [B][N] index of the point at each position
     BqRaw* bq_raw;                  // ... entries [B][bq_cap], in chunks of kBqChunk
     uint32_t* bq_cursor;            // ... chunks handed out per cloud [B]
     uint32_t* bq_ovf;               // ... overflow flag per cloud [B]
@@ -127,7 +131,8 @@ struct Plan {
 // kCandMax candidates.  NULL for a combination that is not built.
 const void* sampler_kernel_for(int threads, int points_per_thread, bool bq, bool perm, int mode);
 // zeroes two ranges of 64-bit words (either may be empty)
-hipError_t launch_zero_words(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2, hipStream_t stream);
+hipError_t launch_zero_words(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2, uint64_t* p3,
+                             int64_t nwords3, hipStream_t stream);
 // Scattered scan order of the threshold phase: writes the records (x, y, z, index bits) of every
 // cloud in the order of the walk j_t = (t stride) mod N into out[B][N]; stride coprime to N.
 hipError_t launch_scan_walk(const float* xyz, int B, int N, int64_t stride, float4* out, hipStream_t stream);

@@ -277,7 +277,9 @@ __global__ __launch_bounds__(256) void knn_check_kernel(const int32_t* __restric
 {
     const int b = (int)blockIdx.x;
     const BqHeader* h = reinterpret_cast<const BqHeader*>(cache);
-    bool ok = h->magic == kBqMagic && h->valid == 1 && h->B == B && h->N == N && h->n == n;
+    // (a record whose blocks are positions of the sampler's cell order is not searched here: every
+    // point of such a cloud goes to the brute-force pass)
+    bool ok = h->magic == kBqMagic && h->valid == 1 && h->order == 0 && h->B == B && h->N == N && h->n == n;
     // a list that overflowed has lost entries: a point could miss a sample that is near it
     // (nor can one be used that does not fit the rows of the workspace)
     if (ok) {

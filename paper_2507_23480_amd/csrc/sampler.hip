@@ -267,6 +267,7 @@ struct Shared {
     // took = the accepted candidates of the round, one bit each
     uint64_t rel[kCandWin][8];
     uint64_t took[kCandWin / 64];
+    uint16_t place[kCandWin];  // ... and of each accepted one its place among the round's picks
     uint32_t progress;
 #ifdef FASTPOINT_PHASE_CLOCKS
     long long chain_cycles;   // shader clocks the control wave spent in the exact-FPS chain loop
@@ -410,7 +411,8 @@ __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, floa
     fold_groups<P, BQ, DENSE, 0>(pt, cx, cy, cz, a.bq_r2, s, rw);
 }
 
-// Hands the words of `count` picks (sample positions base, base+1, ...; count <= 64) to the cache.
+// Hands the words of `count` picks (sample positions base, base+1, ...; count <= 64; or, with
+// my_offset >= 0, base + my_offset for the pick of this lane) to the cache.
 // Lane s looks at the words of pick s; only a word that is not zero -- the ball holds one of the
 // block's 64 points -- becomes an entry (sample, block, word) of the cloud's list.  A wave fills
 // chunks of kBqChunk entries that it reserves from the cloud's chunk counter: the places inside a
@@ -421,7 +423,7 @@ __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, floa
 // nothing more: readers then treat the cloud as not recorded.
 template <int P, bool BQ>
 __device__ __forceinline__ void flush_rows(const RowWords<P, BQ>& rw, const SamplerArgs& a, const Where& wh,
-                                           Points<P, BQ>& pt, int base, int count)
+                                           Points<P, BQ>& pt, int base, int count, int my_offset = -1)
 {
     if constexpr (BQ) {
         if (pt.bq_dead) return;
@@ -475,7 +477,7 @@ __device__ __forceinline__ void flush_rows(const RowWords<P, BQ>& rw, const Samp
                         BqRaw e;
                         e.mask = rw.row[p * 64 + wh.lane];
                         e.blk = (uint32_t)(wh.gw * P + p);
-                        e.q = (uint32_t)(base + wh.lane);
+                        e.q = (uint32_t)(base + (my_offset >= 0 ? my_offset : wh.lane));
                         list[pt.bq_cur + (uint32_t)i] = e;
                     }
                     before += __builtin_popcountll(m[p]);
@@ -687,11 +689,14 @@ __device__ __noinline__ double pow_int_base(int64_t x, double e)
 // Cell-ordered variant: which of the first `count` entries of `list` can lower a distance of
 // this wave (one entry per lane), and the wave's bound brought up to date.
 template <int P, bool BQ>
-__device__ __forceinline__ uint64_t near_mask(const Points<P, BQ>& pt, const Cand* list, int count, int lane)
+__device__ __forceinline__ uint64_t near_mask(const Points<P, BQ>& pt, const Cand* list, int count, int lane,
+                                              float bq_r2)
 {
     const Cand c = list[lane < count ? lane : 0];
     const float bd = box_dist2<P, BQ>(pt, c.x, c.y, c.z);
-    return __builtin_amdgcn_ballot_w64(lane < count && __float_as_uint(bd) < pt.ub);
+    // a recording kernel also needs the picks whose ball can reach into the box
+    const uint32_t reach = BQ ? max(pt.ub, __float_as_uint(bq_r2)) : pt.ub;
+    return __builtin_amdgcn_ballot_w64(lane < count && __float_as_uint(bd) < reach);
 }
 template <int P, bool BQ>
 __device__ __forceinline__ void refresh_bound(Points<P, BQ>& pt)
@@ -759,13 +764,14 @@ __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, c
     RowWords<P, BQ> rw;
     rw.clear(wh);
     if constexpr (PERM) {
-        uint64_t near = near_mask<P, BQ>(pt, sh.pend, npend, wh.lane);
+        uint64_t near = near_mask<P, BQ>(pt, sh.pend, npend, wh.lane, a.bq_r2);
         while (near != 0) {
             const int s = first_lane(near);
             near &= near - 1;
             const Cand cur = sh.pend[s];
             fold<P, BQ>(pt, cur.x, cur.y, cur.z, a, wh, s, rw);
         }
+        flush_rows<P, BQ>(rw, a, wh, pt, base, npend);
         return;
     }
     Cand nxt = sh.pend[0];
@@ -791,8 +797,8 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
     rw.clear(wh);
     uint64_t near = ~0ull, near_hi = ~0ull;         // one bit per candidate (near_hi: candidates 64..127)
     if constexpr (PERM) {
-        near = near_mask<P, BQ>(pt, sh.cand, total < 64 ? total : 64, wh.lane);
-        if constexpr (WIDE) near_hi = near_mask<P, BQ>(pt, sh.cand + 64, total - 64, wh.lane);
+        near = near_mask<P, BQ>(pt, sh.cand, total < 64 ? total : 64, wh.lane, a.bq_r2);
+        if constexpr (WIDE) near_hi = near_mask<P, BQ>(pt, sh.cand + 64, total - 64, wh.lane, a.bq_r2);
     }
     uint32_t slot = lds_observe(&sh.live[0]);
     // Lane s of `rw` holds the words of a pick, so a recording wave takes a wide round in two halves
@@ -1449,7 +1455,10 @@ __device__ __forceinline__ void settle_relations(Shared<T>& sh, const Where& wh,
         for (int w = 0; w < kWinWords; ++w)
             if (q < nq && w < nq) place += __builtin_popcountll((mine ? sh.rel[c][w] : 0ull) & acc[w]);
         const bool keep = mine && place < limit;
-        if (keep) stage_pick<T>(sh, st.i + place, sh.cand[c].idx, 0.0f);
+        if (keep) {
+            stage_pick<T>(sh, st.i + place, sh.cand[c].idx, 0.0f);
+            sh.place[c] = (uint16_t)place;
+        }
         const uint64_t took = __builtin_amdgcn_ballot_w64(keep);
         if (wh.lane == 0) sh.took[q] = took;
     }
@@ -1463,28 +1472,43 @@ struct NearWords {
 };
 template <int T, int P, bool BQ>
 __device__ __forceinline__ NearWords near_candidates(const Points<P, BQ>& pt, const Shared<T>& sh,
-                                                     const Where& wh, int total)
+                                                     const Where& wh, int total, float bq_r2)
 {
     NearWords nw;
 #pragma unroll
-    for (int q = 0; q < kWinWords; ++q) nw.w[q] = near_mask<P, BQ>(pt, sh.cand + 64 * q, total - 64 * q, wh.lane);
+    for (int q = 0; q < kWinWords; ++q) nw.w[q] = near_mask<P, BQ>(pt, sh.cand + 64 * q, total - 64 * q, wh.lane, bq_r2);
     return nw;
 }
 template <int T, int P, bool BQ>
 __device__ __forceinline__ void fold_accepted(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
-                                              const SamplerArgs& a, const NearWords& nw)
+                                              const SamplerArgs& a, const NearWords& nw, int base)
 {
     RowWords<P, BQ> rw;
-    rw.clear(wh);
+    rw.row = wh.rows;
+    int s = 0;                    // picks folded and not handed to the record yet: lane t holds the words of the t-th
+    int my_place = 0;             // ... and the place of that pick among the round's picks
 #pragma unroll
     for (int q = 0; q < kWinWords; ++q) {
         uint64_t m = nw.w[q] & sh.took[q];
         while (m != 0) {
-            const Cand c = sh.cand[64 * q + first_lane(m)];
+            const int cl = 64 * q + first_lane(m);
+            const Cand c = sh.cand[cl];
             m &= m - 1;
-            fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, 0, rw);
+            if constexpr (BQ) {
+                if (s == 0) rw.clear(wh);
+                if (wh.lane == s) my_place = (int)sh.place[cl];
+            }
+            fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, s, rw);
+            if constexpr (BQ) {
+                if (++s == 64) {
+                    flush_rows<P, BQ>(rw, a, wh, pt, base, 64, my_place);
+                    s = 0;
+                }
+            }
         }
     }
+    if constexpr (BQ)
+        if (s > 0) flush_rows<P, BQ>(rw, a, wh, pt, base, s, my_place);
 }
 
 // Exact FPS for several picks at once.  The candidates are ALL points whose distance exceeds
@@ -1727,7 +1751,8 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
     constexpr bool WALK = MODE == 3;                // positions are the scan order itself
     constexpr bool RANKED = MODE == 4;              // cell order, threshold phase by place in the walk
     constexpr bool WINDOWS = PERM && !WALK;         // cell order: the lowest indices (places) through a window
-    static_assert(MODE < 3 || (PERM && !BQ), "the scattered scan order works on reordered records");
+    static_assert(MODE < 3 || PERM, "the scattered scan order works on reordered records");
+    static_assert(MODE != 3 || !BQ, "records in walk order are not recorded");
     const int n = a.n, N = a.N;
     const bool writer = (wh.g == 0 && wh.tid == 0);
     const float* cloud = a.xyz + (int64_t)wh.c * N * 3;
@@ -1763,6 +1788,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 pt.y[p] = r.y;
                 pt.z[p] = r.z;
                 pt.oi[p] = __float_as_uint(r.w);
+                if constexpr (BQ) a.bq_map[(int64_t)wh.c * N + j] = (int32_t)pt.oi[p];
                 if constexpr (RANKED) wh.rk[p * kRkStride] = (uint32_t)(((uint64_t)pt.oi[p] * a.walk_inv) % (uint64_t)N);
                 pt.d[p] = __builtin_inff();
                 lo[0] = fminf(lo[0], r.x);
@@ -2060,13 +2086,13 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
 #endif
                 NearWords nw = {};
                 if (wh.ctrl) settle_relations<T>(sh, wh, st, total, limit);
-                else nw = near_candidates<T, P, BQ>(pt, sh, wh, total);
+                else nw = near_candidates<T, P, BQ>(pt, sh, wh, total, a.bq_r2);
                 __syncthreads();
 #ifdef FASTPOINT_PHASE_CLOCKS
                 const long long thr_t4 = wall_clock64();
                 st.clk[10] += thr_t4 - thr_t3;
 #endif
-                if (!wh.ctrl) fold_accepted<T, P, BQ>(pt, sh, wh, a, nw);
+                if (!wh.ctrl) fold_accepted<T, P, BQ>(pt, sh, wh, a, nw, st.i);
 #ifdef FASTPOINT_PHASE_CLOCKS
                 st.clk[11] += wall_clock64() - thr_t4;
 #endif
@@ -2202,7 +2228,7 @@ __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a
         // written here rather than by a launch of its own, which would lie in front of every
         // recording sampler on the stream
         if (blockIdx.x == 0 && threadIdx.x == 0)
-            *reinterpret_cast<BqHeader*>(a.bq_base) = bq_layout(a.B, a.N, a.n, a.bq_r2, a.bq_cap);
+            *reinterpret_cast<BqHeader*>(a.bq_base) = bq_layout(a.B, a.N, a.n, a.bq_r2, a.bq_cap, PERM ? 1 : 0);
     }
     uint32_t it = 0, seq = 0;
     for (int c = wh.grp; c < a.B; c += ngroups) {
@@ -2211,14 +2237,16 @@ __global__ __launch_bounds__(T + kCtrlThreads) void sampler_kernel(SamplerArgs a
     }
 }
 
-// zeroes two ranges of words before a launch: the exchange words (stamps start at 1 in every
-// launch) and the counters of a ball-query cache
-__global__ void zero_words_kernel(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2)
+// zeroes up to three ranges of words before a launch: the exchange words (stamps start at 1 in
+// every launch), the counters of a ball-query cache, the relation words of the cell-ordered sampler
+__global__ void zero_words_kernel(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2, uint64_t* p3,
+                                  int64_t nwords3)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t t = i; t < nwords; t += stride) p[t] = 0;
     for (int64_t t = i; t < nwords2; t += stride) p2[t] = 0;
+    for (int64_t t = i; t < nwords3; t += stride) p3[t] = 0;
 }
 
 template <int T, int P, bool BQ, bool PERM>
@@ -2235,8 +2263,13 @@ const void* pick_mode(int mode)
 template <int T, int P>
 const void* pick_bq(bool bq, bool perm, int mode)
 {
-    if (perm) {                     // reordered records: no recording, threshold rounds always wide
-        if (bq || mode == 1) return nullptr;
+    if (perm) {                     // reordered records: threshold rounds always wide; MDPS in cell order records
+        if (mode == 1) return nullptr;
+        if (bq) {
+            if (mode == 2) return reinterpret_cast<const void*>(&sampler_kernel<T, P, true, true, 2>);
+            if (mode == 4) return reinterpret_cast<const void*>(&sampler_kernel<T, P, true, true, 4>);
+            return nullptr;
+        }
         if (mode == 3) return reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, 3>);
         if (mode == 4) return reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, 4>);
         return mode == 0 ? reinterpret_cast<const void*>(&sampler_kernel<T, P, false, true, 0>)
@@ -2288,14 +2321,16 @@ hipError_t launch_scan_walk(const float* xyz, int B, int N, int64_t stride, floa
     return hipGetLastError();
 }
 
-hipError_t launch_zero_words(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2, hipStream_t stream)
+hipError_t launch_zero_words(uint64_t* p, int64_t nwords, uint64_t* p2, int64_t nwords2, uint64_t* p3,
+                             int64_t nwords3, hipStream_t stream)
 {
-    const int64_t most = nwords > nwords2 ? nwords : nwords2;
+    int64_t most = nwords > nwords2 ? nwords : nwords2;
+    most = most > nwords3 ? most : nwords3;
     if (most <= 0) return hipSuccess;
     int blocks = (int)((most + 255) / 256);
     if (blocks > 1024) blocks = 1024;
     hipLaunchKernelGGL(zero_words_kernel, dim3(blocks), dim3(256), 0, stream, p, nwords > 0 ? nwords : 0, p2,
-                       nwords2 > 0 ? nwords2 : 0);
+                       nwords2 > 0 ? nwords2 : 0, p3, nwords3 > 0 ? nwords3 : 0);
     return hipGetLastError();
 }
 

@@ -67,6 +67,38 @@ def test_samplers_give_the_same_bytes_every_run(fp, B, N, n, radius, k):
     say("   %d runs of fps_exact, mdps_sample (recording) and the cached ball query: identical" % RUNS)
 
 
+@pytest.mark.parametrize("order", [0, 1])
+def test_cell_ordered_sampler_gives_the_same_results_every_run(fp, order):
+    """The cell-ordered sampler sorts the cloud with atomics, so the order of the points inside a
+    cell -- and with it the contents of its record -- may differ between runs; what leaves the
+    library may not: samples, bookkeeping, the ball query read from the record."""
+    B, N, n, radius, k = 2, 60000, 5000, 0.04, 16
+    batch = np.stack([inputs.uniform_cube(4300 + b, N) for b in range(B)])
+    xyz = torch.from_numpy(batch).cuda()
+    assert fp.plan(B, N)[0] > 1
+    prm = fp.MdpsParams(exponent=0.86, bias=1.05, scan_order=order)
+    first = None
+    for run in range(RUNS):
+        cache = fp.new_bq_cache(xyz, n)
+        midx, info = fp.mdps_sample_pruned(xyz, n, prm, want_info=True, bq_cache=cache, bq_radius=radius)
+        bq, cnt = fp.ball_query(xyz, midx, radius, k, bq_cache=cache)
+        torch.cuda.synchronize()
+        got = ([midx, bq, cnt], info_words(fp, info))
+        if first is None:
+            first = got
+            rp = ref.MdpsParams(exponent=0.86, bias=1.05, scan_order=order)
+            for b in range(B):
+                wmidx, _ = ref.mdps_sample(batch[b], n, rp)
+                assert np.array_equal(midx[b].cpu().numpy(), wmidx)
+                wbq, wcnt = ref.ball_query(batch[b], wmidx, radius, k)
+                assert np.array_equal(bq[b].cpu().numpy(), wbq) and np.array_equal(cnt[b].cpu().numpy(), wcnt)
+            assert not any(fp.bq_cache_stats(cache)["incomplete"])
+            continue
+        assert same(got[0], first[0]) and got[1] == first[1], "run %d differs from run 0" % run
+    say("   %d runs of mdps_sample_pruned (recording, scan order %d) and the ball query from its record: identical"
+        % (RUNS, order))
+
+
 def test_exclusion_lists_give_the_same_bytes_every_run(fp):
     batch = np.stack([inputs.uniform_cube(4200 + b, 20000) for b in range(2)])
     xyz = torch.from_numpy(batch).cuda()

@@ -149,7 +149,7 @@ def test_argument_checks(fp):
     import ctypes
     c = fp.MdpsParams().to_c()
     call = lambda xp, n, p, wsb: lib.fp_mdps_sample_pruned(xp, 1, 300, n, None, p, out.data_ptr(), None,
-                                                            ws.data_ptr(), wsb, None)
+                                                            None, 0, 0.0, ws.data_ptr(), wsb, None)
     assert call(x.data_ptr(), 10, None, ws.numel()) == -1
     assert call(None, 10, ctypes.byref(c), ws.numel()) == -1
     assert call(x.data_ptr(), 301, ctypes.byref(c), ws.numel()) == -2

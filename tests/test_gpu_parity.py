@@ -246,9 +246,10 @@ def test_ball_query_out_of_range_centre(fp):
     assert np.array_equal(idx[0, 0], w[0]) and cnt[0, 0] == wc[0]
 
 
-@pytest.mark.parametrize("sampler", ["fps", "mdps"])
+@pytest.mark.parametrize("sampler", ["fps", "mdps", "mdps_pruned", "mdps_pruned_scattered"])
 @pytest.mark.parametrize("N,n,G,radius,k", [(4096, 1024, 0, 0.1, 32), (9001, 1500, 3, 0.12, 16),
-                                            (700, 700, 0, 0.3, 8)])
+                                            (700, 700, 0, 0.3, 8), (20000, 3000, 0, 0.05, 32),
+                                            (6000, 900, 2, 0.5, 64)])
 def test_cached_ball_query_equals_brute_force(fp, sampler, N, n, G, radius, k):
     # Section 4.2: reading the radius tests recorded during sampling changes nothing
     say("cached bq %s N=%d n=%d G=%d" % (sampler, N, n, G))
@@ -256,15 +257,23 @@ def test_cached_ball_query_equals_brute_force(fp, sampler, N, n, G, radius, k):
     xyz = dev(cloud)
     fp.set_wg_per_cloud(G)
     try:
-        cache = fp.new_bq_cache(xyz, n)
+        cache = fp.new_bq_cache(xyz, n, entries_per_cloud=n * ((N + 63) // 64) + N + 128)
+        prm = fp.MdpsParams(exponent=0.8, bias=1.05)
         if sampler == "fps":
             idx = fp.fps_exact(xyz, n, bq_cache=cache, bq_radius=radius)
+        elif sampler == "mdps":
+            idx = fp.mdps_sample(xyz, n, prm, bq_cache=cache, bq_radius=radius)
         else:
-            idx = fp.mdps_sample(xyz, n, fp.MdpsParams(exponent=0.8, bias=1.05), bq_cache=cache,
-                                 bq_radius=radius)
+            # the cell-ordered sampler records blocks of positions; a radius of half the cloud (last
+            # case) gives balls of more hits than the reader sorts, which it then searches by brute force
+            prm.scan_order = 1 if sampler == "mdps_pruned_scattered" else 0
+            idx = fp.mdps_sample_pruned(xyz, n, prm, bq_cache=cache, bq_radius=radius)
+            assert torch.equal(idx, fp.mdps_sample(xyz, n, prm))
+            assert fp.bq_cache_stats(cache)["cell_order"]
     finally:
         fp.set_wg_per_cloud(0)
     torch.cuda.synchronize()
+    assert not any(fp.bq_cache_stats(cache)["incomplete"])
     centers = idx.cpu().numpy()
     got, gcnt = check_ball_query(fp, cloud, centers, radius, k, cache=cache)
     brute, bcnt = fp.ball_query(xyz, idx, radius, k)
