@@ -57,12 +57,13 @@ GRAPH = "four streams, step replayed as one HIP graph"
 # bench_C2_hbm_traffic.md), keyed by workload and kernel.  None where no counter run is recorded.  The
 # samplers keep the cloud in registers: what they move beyond reading it once is the polling of the
 # words exchanged between the workgroups of a cloud.
-TRAFFIC_BYTES = {"C2": {"fps_exact": 454587, "mdps_sample+record": 2344271, "ball_query_cached": 1951986,
-                        "ball_query_brute": 2001511},
-                 "C4": {"fps_exact": 143807600, "mdps_sample+record": 362700744, "ball_query_cached": 38984780,
-                        "ball_query_brute": 90784615},
-                 "C5": {"fps_exact": 292510875, "mdps_sample+record": 390621436, "ball_query_cached": 19478260,
-                        "ball_query_brute": 204118505}}
+TRAFFIC_BYTES = {"C2": {"fps_exact": 446396, "mdps_sample+record": 2353485, "ball_query_cached": 1959153,
+                        "ball_query_brute": 2003559},
+                 "C4": {"fps_exact": 90525757, "mdps_sample+record": 298704061, "ball_query_cached": 39007323,
+                        "ball_query_brute": 90791490},
+                 # (C5: the step's recorder is the cell-ordered one, its reader the one for cell-ordered records)
+                 "C5": {"fps_exact": 167294614, "mdps_sample+record": 264458538, "ball_query_cached": 27160357,
+                        "ball_query_brute": 204116585}}
 
 
 PRUNED_RECORD_FROM = 1 << 18
@@ -780,8 +781,6 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
     roof["kernel"] = dom + " (stage 0)"
     roof["ms_per_launch"] = s0["kernel_ms"][dom]
     roof["traffic"] = TRAFFIC_BYTES.get(name, {}).get(dom)
-    if dom == "mdps_sample+record" and ctx["stages"][0]["pruned_record"]:
-        roof["traffic"] = None                     # the counters were read for the index-ordered sampler
     if roof.get("bound") == "alu":
         # the published peak needs packed binary32 instructions, which this path may not use (every
         # operation rounds on its own); the rate the device reaches without them, measured here

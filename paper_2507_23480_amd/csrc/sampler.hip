@@ -173,12 +173,14 @@ __device__ __forceinline__ bool ll_wait(const uint64_t* p, uint32_t stamp, uint3
 }
 
 // Slots in LDS through which the control wave hands the picks of a round to the point waves,
-// in acceptance order.  A slot is one 64-bit word: low half = round tag << 8 | lane of the pick
+// in acceptance order.  A slot is one 64-bit word: low half = round tag << 9 | lane of the pick
 // in the candidate list (kLiveEnd: the round has no further pick), high half = the pick's
 // squared distance bits.  It is written by all lanes of the control wave with the same value (one
 // 64-bit store); readers take the pick's coordinates from the candidate list.  The LDS executes
 // the operations of one wave in issue order; the fences only restrain the compiler.
-constexpr uint32_t kLiveEnd = 0xFFu;
+constexpr uint32_t kLiveMask = 0x1FFu;     // a round has up to 256 candidates
+constexpr uint32_t kLiveEnd = kLiveMask;
+constexpr int kLiveShift = 9;
 
 __device__ __forceinline__ void lds_publish(uint64_t* p, uint32_t stamp, uint32_t dbits)
 {
@@ -255,7 +257,7 @@ struct Shared {
     int32_t ctrl[4];      // [0] accepted picks of the round, [1] points passing in the cloud,
                           // [2] failure, [3] distance bits of the last accepted pick
     // picks of the round being resolved, in acceptance order
-    uint64_t live[kCandMax + 2];
+    uint64_t live[kCandWin + 2];
     // scattered scan order: conf[2 c], conf[2 c + 1] = which candidates 0..63 / 64..127 of the round
     // lie closer than R_l to candidate c (bit j of the word: candidate j or 64 + j); acc[s] =
     // coordinates and index bits of the round's s-th accepted pick; progress = round number << 16 |
@@ -788,30 +790,33 @@ __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, c
 // The next slot is requested before the current pick is folded.  Cell-ordered variant: the
 // candidates of the round (`total` of them) are tested against the wave's box once, all
 // together; a published pick that is not near is passed over.
-template <int T, int P, bool BQ, bool PERM, bool WIDE>
+template <int T, int P, bool BQ, bool PERM, int NQ>
 __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                              const SamplerArgs& a, int base, uint32_t tag, int total)
 {
     int s = 0;
     RowWords<P, BQ> rw;
     rw.clear(wh);
-    uint64_t near = ~0ull, near_hi = ~0ull;         // one bit per candidate (near_hi: candidates 64..127)
-    if constexpr (PERM) {
-        near = near_mask<P, BQ>(pt, sh.cand, total < 64 ? total : 64, wh.lane, a.bq_r2);
-        if constexpr (WIDE) near_hi = near_mask<P, BQ>(pt, sh.cand + 64, total - 64, wh.lane, a.bq_r2);
+    uint64_t near[NQ];                              // one bit per candidate (word q: candidates 64 q ...)
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        near[q] = ~0ull;
+        if constexpr (PERM) near[q] = near_mask<P, BQ>(pt, sh.cand + 64 * q, total - 64 * q, wh.lane, a.bq_r2);
     }
     uint32_t slot = lds_observe(&sh.live[0]);
-    // Lane s of `rw` holds the words of a pick, so a recording wave takes a wide round in two halves
-    // of up to 64 picks and hands the first half's words over in between; that hand-over is kept
-    // out of the loop over the picks (whatever is written there would be carried, and copied,
-    // through every iteration).
-    constexpr int kHalves = (WIDE && BQ) ? 2 : 1;
+    // Lane s of `rw` holds the words of a pick, so a recording wave takes a round of more than 64
+    // candidates in parts of up to 64 picks and hands a part's words over before the next; that
+    // hand-over is kept out of the loop over the picks (whatever is written there would be carried,
+    // and copied, through every iteration).
+    constexpr int kParts = BQ ? NQ : 1;
     bool ended = false;
+    int handed = 0;                                 // picks whose words the record has
 #pragma unroll 1
-    for (int half = 0; half < kHalves && !ended; ++half) {
-        const int stop = kHalves == 2 ? 64 * (half + 1) : 0x7FFFFFFF;
-        if (half == 1) {
-            flush_rows<P, BQ>(rw, a, wh, pt, base, 64);
+    for (int part = 0; part < kParts && !ended; ++part) {
+        const int stop = kParts > 1 ? 64 * (part + 1) : 0x7FFFFFFF;
+        if (part >= 1) {
+            flush_rows<P, BQ>(rw, a, wh, pt, base + handed, 64);
+            handed += 64;
             rw.clear(wh);
         }
         for (;;) {
@@ -819,30 +824,29 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
             // but the slot changes in the inner loop, so the distances and row words stay where they
             // are across it
             slot = uni(slot);
-            while ((slot & ~0xFFu) != tag) {        // not written yet in this round
+            while ((slot & ~kLiveMask) != tag) {    // not written yet in this round
                 __builtin_amdgcn_s_sleep(1);
                 slot = uni(lds_observe(&sh.live[s]));
             }
-            if ((slot & 0xFFu) == kLiveEnd) {
+            if ((slot & kLiveMask) == kLiveEnd) {
                 ended = true;
                 break;
             }
-            if (s == stop) break;                   // the slot stays in hand for the second half
-            const uint32_t cl = slot & 0xFFu;
+            if (s == stop) break;                   // the slot stays in hand for the next part
+            const uint32_t cl = slot & kLiveMask;
             slot = lds_observe(&sh.live[s + 1]);
-            const uint64_t nbit = (WIDE && cl >= 64u) ? (near_hi >> (cl - 64u)) : (near >> cl);
-            if (!PERM || (nbit & 1ull) != 0) {
+            uint64_t nword = near[0];
+#pragma unroll
+            for (int q = 1; q < NQ; ++q) nword = (cl >> 6) == (uint32_t)q ? near[q] : nword;
+            if (!PERM || ((nword >> (cl & 63u)) & 1ull) != 0) {
                 const Cand c = sh.cand[cl];
                 // narrow rounds are those of clouds held by one or a few workgroups
-                fold<P, BQ, !WIDE>(pt, c.x, c.y, c.z, a, wh, WIDE ? (s & 63) : s, rw);
+                fold<P, BQ, NQ == 1>(pt, c.x, c.y, c.z, a, wh, kParts > 1 ? (s & 63) : s, rw);
             }
             ++s;
         }
     }
-    if (WIDE)   // the picks not written yet: all of them up to 64, else those from the 65th on
-        flush_rows<P, BQ>(rw, a, wh, pt, s > 64 ? base + 64 : base, s > 64 ? s - 64 : s);
-    else
-        flush_rows<P, BQ>(rw, a, wh, pt, base, s);  // a round has at most kCand picks
+    flush_rows<P, BQ>(rw, a, wh, pt, base + handed, s - handed);   // the picks not handed over yet
 }
 
 // segment boundary b_l (curve index whose value becomes R_l), l = 1..nseg
@@ -1171,11 +1175,11 @@ __device__ __forceinline__ void resolve_threshold(Shared<T>& sh, const Where& wh
     __builtin_amdgcn_s_setprio(0);
     if constexpr (WIDE) {
         for (int t = wh.lane; t < nacc; t += 64) {
-            const uint32_t cl = (uint32_t)sh.live[t] & 0xFFu;
+            const uint32_t cl = (uint32_t)sh.live[t] & kLiveMask;
             stage_pick<T>(sh, st.i + t, sh.cand[cl].idx, 0.0f);
         }
     } else if (wh.lane < nacc) {
-        const uint32_t cl = (uint32_t)sh.live[wh.lane] & 0xFFu;
+        const uint32_t cl = (uint32_t)sh.live[wh.lane] & kLiveMask;
         stage_pick<T>(sh, st.i + wh.lane, sh.cand[cl].idx, 0.0f);
     }
     if (wh.lane == 0) sh.ctrl[0] = nacc;
@@ -1597,20 +1601,21 @@ __device__ __forceinline__ int chain_loop_wide(uint64_t* live, LiveCursor& cur, 
     return nacc;
 }
 
-template <int T, bool PERM, bool WIDE>
+template <int T, bool PERM, int NQ>
 __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, const CloudState& st,
                                               int total, int limit, float tau, bool capture, int nseg,
                                               uint32_t tag)
 {
     total = uni(total);
     limit = uni(limit);
-    const bool has = wh.lane < total;
-    const Cand me = sh.cand[has ? wh.lane : 0];
-    uint32_t cd = has ? me.d : 0u;                     // bit pattern; distances are >= +0
-    const bool has1 = WIDE && wh.lane + 64 < total;
-    Cand me1 = me;
-    if constexpr (WIDE) me1 = sh.cand[has1 ? wh.lane + 64 : 0];
-    uint32_t cd1 = has1 ? me1.d : 0u;
+    Cand me[NQ];
+    uint32_t cd[NQ];                                   // bit patterns; distances are >= +0
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const bool has = wh.lane + 64 * q < total;
+        me[q] = sh.cand[has ? wh.lane + 64 * q : 0];
+        cd[q] = has ? me[q].d : 0u;
+    }
     const uint32_t tau_bits = uni(__float_as_uint(tau));    // tau >= 0
     uint32_t dl = __float_as_uint(st.dlast);
     LiveCursor cur(tag);
@@ -1619,16 +1624,17 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
     const long long chain_t0 = clock64();
 #endif
     // the candidates have arrived from LDS before the loop starts, not inside it
-    asm volatile("" ::"v"(me.x), "v"(me.y), "v"(me.z), "v"(cd));
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) asm volatile("" ::"v"(me[q].x), "v"(me[q].y), "v"(me[q].z), "v"(cd[q]));
     int nacc;
-    if constexpr (WIDE) {
-        asm volatile("" ::"v"(me1.x), "v"(me1.y), "v"(me1.z), "v"(cd1));
+    static_assert(NQ <= 2, "the chain is written for one or two candidates per lane");
+    if constexpr (NQ > 1) {
         nacc = limit >= total
-                   ? chain_loop_wide<false, PERM>(sh.live, cur, me, me1, cd, cd1, tau_bits, limit, dl)
-                   : chain_loop_wide<true, PERM>(sh.live, cur, me, me1, cd, cd1, tau_bits, limit, dl);
+                   ? chain_loop_wide<false, PERM>(sh.live, cur, me[0], me[1], cd[0], cd[1], tau_bits, limit, dl)
+                   : chain_loop_wide<true, PERM>(sh.live, cur, me[0], me[1], cd[0], cd[1], tau_bits, limit, dl);
     } else {
-        nacc = limit >= total ? chain_loop<false, PERM>(sh.live, cur, me, cd, tau_bits, limit, dl)
-                              : chain_loop<true, PERM>(sh.live, cur, me, cd, tau_bits, limit, dl);
+        nacc = limit >= total ? chain_loop<false, PERM>(sh.live, cur, me[0], cd[0], tau_bits, limit, dl)
+                              : chain_loop<true, PERM>(sh.live, cur, me[0], cd[0], tau_bits, limit, dl);
     }
     cur.publish(sh.live, kLiveEnd, 0u);
     __builtin_amdgcn_s_setprio(0);
@@ -1642,7 +1648,7 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
         const int pos = st.i + t;
         const uint64_t word = sh.live[t];
         const float d = __uint_as_float((uint32_t)(word >> 32));
-        stage_pick<T>(sh, pos, sh.cand[(uint32_t)word & 0xFFu].idx, d);
+        stage_pick<T>(sh, pos, sh.cand[(uint32_t)word & kLiveMask].idx, d);
         if (capture) {                  // prefix loop of Alg. 2: keep the curve
             sh.ring[pos & 63] = d;
             for (int l = 0; l < nseg; ++l)
@@ -1660,12 +1666,12 @@ __device__ __forceinline__ void resolve_chain(Shared<T>& sh, const Where& wh, co
 
 // ---- exact FPS for sample positions [st.i, upto) (the loop of Alg. 1), in batched rounds with
 // plain iterations as the fallback.  Returns false if a wait between workgroups expired.
-template <int T, int P, bool BQ, bool PERM, bool kWideFps>
+template <int T, int P, bool BQ, bool PERM, int kFpsQ>
 __device__ __forceinline__ bool fps_rounds_of(Points<P, BQ>& pt, Shared<T>& sh, const Where& wh,
                                               const SamplerArgs& a, uint32_t& it, uint32_t& seq,
                                               CloudState& st, int upto, bool capture)
 {
-    constexpr int kCandFps = kWideFps ? kCandMax : kCand;
+    constexpr int kCandFps = 64 * kFpsQ;            // candidates of a round: one, two or four per lane of the control wave
     while (st.i < upto) {
         flush_picks<T, BQ>(a, sh, wh, st.flushed, st.i, false);
         {
@@ -1682,11 +1688,12 @@ __device__ __forceinline__ bool fps_rounds_of(Points<P, BQ>& pt, Shared<T>& sh, 
             for (int tries = 0; tries < 4 && !good; ++tries) {
                 tau = st.dlast - st.om * st.dlast;
                 PHASE_BEGIN();
-                total = scan_candidates<T, P, BQ, PERM, true, kCandFps>(pt, sh, wh, a, seq, tau, alltot);
+                total = scan_candidates<T, P, BQ, PERM, true, kCandFps, false, false,
+                                        (kCandFps < kCandMax ? kCandFps : kCandMax)>(pt, sh, wh, a, seq, tau, alltot);
                 PHASE_END(st, 1);
                 if (total < 0) return false;
                 ++st.rounds;
-                if (alltot > 0 && alltot <= kCandFps) good = true;
+                if (alltot > 0 && alltot == total) good = true;      // all of them are in the list
                 else if (alltot == 0) st.om = st.om * 2.0f < 0.99f ? st.om * 2.0f : 0.99f;
                 else st.om = st.om * 0.5f;
             }
@@ -1700,9 +1707,9 @@ __device__ __forceinline__ bool fps_rounds_of(Points<P, BQ>& pt, Shared<T>& sh, 
         }
         {
             PHASE_BEGIN();
-            const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
-            if (wh.ctrl) resolve_chain<T, PERM, kWideFps>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg, tag);
-            else follow_picks<T, P, BQ, PERM, kWideFps>(pt, sh, wh, a, st.i, tag, total);
+            const uint32_t tag = (uint32_t)(st.resolved + 1) << kLiveShift;
+            if (wh.ctrl) resolve_chain<T, PERM, kFpsQ>(sh, wh, st, total, upto - st.i, tau, capture, a.nseg, tag);
+            else follow_picks<T, P, BQ, PERM, kFpsQ>(pt, sh, wh, a, st.i, tag, total);
             __syncthreads();
             PHASE_END(st, 2);
         }
@@ -1716,7 +1723,7 @@ __device__ __forceinline__ bool fps_rounds_of(Points<P, BQ>& pt, Shared<T>& sh, 
     return true;
 }
 
-// Rounds of 64 or of 128 candidates.  With four or more points per thread folding a pick takes the
+// Rounds of 64, 128 or 256 candidates.  With four or more points per thread folding a pick takes the
 // point waves longer than finding it takes the control wave, so the longer chain step of a round
 // with two candidates per lane is hidden and the halved number of scans is a gain.  With two
 // points per thread the chain is what a pick costs, and the wide round pays only where a scan is
@@ -1727,12 +1734,16 @@ __device__ __forceinline__ bool fps_rounds(Points<P, BQ>& pt, Shared<T>& sh, con
                                            const SamplerArgs& a, uint32_t& it, uint32_t& seq,
                                            CloudState& st, int upto, bool capture)
 {
+    // (Four candidates per lane, rounds of 256, were measured with eight points per thread, where a
+    // fold takes 260 ns: the million-point cloud then needs 436 scans instead of 814, but a chain step
+    // grows to 355 ns and becomes what a pick costs -- 23.2 ms either way; and a chain loop written
+    // for any number of candidates per lane was a tenth slower with two than the one written for two.)
     if constexpr (P >= 4) {
-        return fps_rounds_of<T, P, BQ, PERM, true>(pt, sh, wh, a, it, seq, st, upto, capture);
+        return fps_rounds_of<T, P, BQ, PERM, 2>(pt, sh, wh, a, it, seq, st, upto, capture);
     } else {
         if constexpr (!PERM && !ONE_WG) // (the cell-ordered variant gained nothing there and pays for the code)
-            if (wh.G >= 8) return fps_rounds_of<T, P, BQ, PERM, true>(pt, sh, wh, a, it, seq, st, upto, capture);
-        return fps_rounds_of<T, P, BQ, PERM, false>(pt, sh, wh, a, it, seq, st, upto, capture);
+            if (wh.G >= 8) return fps_rounds_of<T, P, BQ, PERM, 2>(pt, sh, wh, a, it, seq, st, upto, capture);
+        return fps_rounds_of<T, P, BQ, PERM, 1>(pt, sh, wh, a, it, seq, st, upto, capture);
     }
 }
 
@@ -1851,7 +1862,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
             }
         }
     }
-    if (wh.tid < kCandMax + 2) sh.live[wh.tid] = 0;    // round tags start at 1 in every cloud
+    if (wh.tid < kCandWin + 2) sh.live[wh.tid] = 0;    // round tags start at 1 in every cloud
     if (wh.tid == 0) sh.progress = 0;
     if (wh.tid < 32) {
         int64_t ik = ((int64_t)a.m * (wh.tid + 1)) / 32;
@@ -2103,9 +2114,9 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
                 if (wh.ctrl) resolve_conflicts<T>(sh, wh, st, total, limit, round_no);
                 else follow_stream<T, P, BQ>(pt, sh, wh, a, round_no);
             } else {
-                const uint32_t tag = (uint32_t)(st.resolved + 1) << 8;
+                const uint32_t tag = (uint32_t)(st.resolved + 1) << kLiveShift;
                 if (wh.ctrl) resolve_threshold<T, WIDE>(sh, wh, st, total, limit, r2, tag);
-                else follow_picks<T, P, BQ, PERM, WIDE>(pt, sh, wh, a, st.i, tag, total);
+                else follow_picks<T, P, BQ, PERM, (WIDE ? 2 : 1)>(pt, sh, wh, a, st.i, tag, total);
             }
             __syncthreads();
             ++st.resolved;

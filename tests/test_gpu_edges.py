@@ -50,6 +50,34 @@ def test_smallest_shapes(fp, N, n):
     assert np.array_equal(bq.cpu().numpy()[0], wbq) and np.array_equal(cnt.cpu().numpy()[0], wcnt)
 
 
+@pytest.mark.parametrize("N,n", [(1, 1), (2, 2), (3, 3), (10, 10), (63, 40), (64, 64), (65, 65), (129, 100),
+                                 (257, 257), (1000, 2)])
+def test_smallest_shapes_with_a_threshold_phase(fp, N, n):
+    """Small clouds with a prefix of one or two exact iterations, so that nearly every sample comes from
+    the threshold phase or its early termination: both scan orders, the cloud as given and in cell
+    order, with and without a record, n up to N (every point is sampled)."""
+    cloud = inputs.uniform_cube(900 + N, N)
+    x = dev(cloud[None])
+    for order in (0, 1):
+        for thr in ([0.05, 0.01], [1e-30, 1e-30], [float("inf"), 4.0]):
+            prm = fp.MdpsParams(p=0.01, nseg=2, m_min=1, thr_override=thr, scan_order=order)
+            rp = ref.MdpsParams(p=0.01, nseg=2, m_min=1, thr_override=thr, scan_order=order)
+            want, winfo = ref.mdps_sample(cloud, n, rp)
+            a, ainfo = fp.mdps_sample(x, n, prm, want_info=True)
+            b, binfo = fp.mdps_sample_pruned(x, n, prm, want_info=True)
+            cache = fp.new_bq_cache(x, n, entries_per_cloud=n * ((N + 63) // 64) + N + 128)
+            c = fp.mdps_sample_pruned(x, n, prm, bq_cache=cache, bq_radius=0.3)
+            bq, cnt = fp.ball_query(x, c, 0.3, 5, bq_cache=cache)
+            torch.cuda.synchronize()
+            for got, info in ((a, ainfo), (b, binfo), (c, None)):
+                assert np.array_equal(got.cpu().numpy()[0], want), "N=%d n=%d order=%d thr=%s" % (N, n, order, thr)
+                if info is not None:
+                    gi = fp.parse_info(info)[0]
+                    assert gi.status == 0 and gi.m == winfo.m and gi.et_index == winfo.et_index
+            wbq, wcnt = ref.ball_query(cloud, want, 0.3, 5)
+            assert np.array_equal(bq.cpu().numpy()[0], wbq) and np.array_equal(cnt.cpu().numpy()[0], wcnt)
+
+
 def test_more_clouds_than_the_device_holds_at_once(fp):
     # 300 clouds: the workgroups take further clouds in turn
     B, N, n = 300, 500, 120
