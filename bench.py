@@ -66,7 +66,7 @@ TRAFFIC_BYTES = {"C2": {"fps_exact": 446396, "mdps_sample+record": 2353485, "bal
                         "ball_query_brute": 204116585}}
 
 
-PRUNED_RECORD_FROM = 1 << 18
+PRUNED_RECORD_FROM = 1 << 14
 
 
 def record_sampler(fp, sg):
@@ -128,14 +128,18 @@ def make_context(torch, fp, inputs, calibration, name):
     stages = []
     B, N = xyz.shape[0], xyz.shape[1]
     for s, st in enumerate(wl.stages):
+        prm = calibration.params_for(name, s)
+        pruned = N >= PRUNED_RECORD_FROM
         stages.append({"B": B, "N": N, "n": st.n, "radius": st.radius, "k": st.k,
-                       "prm": calibration.params_for(name, s),
+                       "prm": prm,
+                       # the step's MDPS: from 16384 points per cloud on the cell-ordered sampler with
+                       # the scattered scan order of the threshold phase (the paper's step takes any
+                       # available point), below that the index-ordered one with the lowest index
+                       "step_prm": dataclasses.replace(prm, scan_order=1) if pruned else prm,
                        "cache": torch.empty(fp.load().fp_bq_cache_bytes(
                            B, N, st.n, BQ_CACHE_ENTRIES.get(name, 0) if s == 0 else 0), dtype=torch.uint8, device="cuda"),
                        "G": fp.plan(B, N)[0],
-                       # which recording sampler the step runs: the cell-ordered one (pruned updates)
-                       # from a quarter of a million points per cloud on, where folds dominate a round
-                       "pruned_record": N >= PRUNED_RECORD_FROM,
+                       "pruned_record": pruned,
                        "ws": [fp.new_workspace(xyz.device, B, N), fp.new_workspace(xyz.device, B, N)]})
         N = st.n
     torch.cuda.synchronize()
@@ -152,7 +156,7 @@ def run_step(fp, ctx, timer, keep=None):
         idx = timer.call("fps_exact/s%d" % s, lambda: fp.fps_exact(xs, n))
         bq = timer.call("ball_query_brute/s%d" % s, lambda: fp.ball_query(xs, idx, r, k))
         midx = timer.call("mdps_sample+record/s%d" % s,
-                          lambda: record_sampler(fp, sg)(xs, n, sg["prm"], bq_cache=sg["cache"], bq_radius=r))
+                          lambda: record_sampler(fp, sg)(xs, n, sg["step_prm"], bq_cache=sg["cache"], bq_radius=r))
         mbq = timer.call("ball_query_cached/s%d" % s,
                          lambda: fp.ball_query(xs, midx, r, k, bq_cache=sg["cache"]))
         if s + 1 < len(ctx["stages"]):
@@ -296,7 +300,7 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
             ms[kname] = knn[kname + "_ms"]
         # the same k-NN through a grid over the samples, search radius 3 x their coverage radius
         kg_radius = 3.0 * float(cov_m.max())
-        kg = time_call(torch, lambda: fp.knn_grid(x, midx, KNN_K, kg_radius, want_deferred=True))
+        kg = time_call(torch, lambda: fp.knn_grid(x, knn["samples"], KNN_K, kg_radius, want_deferred=True))
         if not (torch.equal(kg[1][0], knn["knn_brute"][0]) and torch.equal(kg[1][1], knn["knn_brute"][1])):
             raise RuntimeError("grid k-NN differs from the brute-force result")
         ms["knn_grid"] = kg[0]
@@ -305,7 +309,7 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
                              "frac": a / ALU_PEAK_TOPS}
         # the redundancy-free search reads the recorded entries (regrouped by point block) and the
         # points, and writes the result
-        byts = (16.0 + 2 * 12.0) * sum(fp.bq_cache_stats(sg["cache"])["entries"]) + 12.0 * B * N + 2.0 * B * N * KNN_K * 4
+        byts = (16.0 + 2 * 12.0) * sum(fp.bq_cache_stats(knn["cache"])["entries"]) + 12.0 * B * N + 2.0 * B * N * KNN_K * 4
         a = byts / (knn["knn_cached_ms"] * 1e-3) / 1e9
         roof["knn_cached"] = {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": a / HBM_PEAK_GBS, "bytes": byts,
@@ -333,18 +337,23 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         # timed without and with pruning (neither records the radius tests)
         mp_plain = time_call(torch, lambda: fp.mdps_sample(x, n, sg["prm"]))
         mp = time_call(torch, lambda: fp.mdps_sample_pruned(x, n, sg["prm"]))
-        if not (torch.equal(mp[1], midx) and torch.equal(mp_plain[1], midx)):
+        if not torch.equal(mp[1], mp_plain[1]):
             raise RuntimeError("mdps_sample_pruned differs from mdps_sample")
         ms["mdps_sample"] = mp_plain[0]
         ms["mdps_sample_pruned"] = mp[0]
         # both recording samplers with their readers (the step runs the one named in record_sampler)
         other = torch.empty_like(sg["cache"])
-        for label, entry in (("mdps_sample+record_index_order", fp.mdps_sample),
-                             ("mdps_sample_pruned+record", fp.mdps_sample_pruned)):
-            rec = time_call(torch, lambda: entry(x, n, sg["prm"], bq_cache=other, bq_radius=sg["radius"]))
+        for label, entry, prm_r in (("mdps_sample+record_index_order", fp.mdps_sample, sg["prm"]),
+                                    ("mdps_sample_pruned+record", fp.mdps_sample_pruned, sg["prm"]),
+                                    ("mdps_sample_pruned+record_scattered", fp.mdps_sample_pruned,
+                                     dataclasses.replace(sg["prm"], scan_order=1))):
+            rec = time_call(torch, lambda: entry(x, n, prm_r, bq_cache=other, bq_radius=sg["radius"]))
             rd = time_call(torch, lambda: fp.ball_query(x, rec[1], sg["radius"], k, bq_cache=other))
-            if not (torch.equal(rec[1], midx) and torch.equal(rd[1][0], mbq[0]) and torch.equal(rd[1][1], mbq[1])):
-                raise RuntimeError(label + ": samples or neighbours differ from the step's")
+            chk = fp.ball_query_grid(x, rec[1], sg["radius"], k)
+            if not (torch.equal(rd[1][0], chk[0]) and torch.equal(rd[1][1], chk[1])):
+                raise RuntimeError(label + ": neighbours read from the record differ from the grid query's")
+            if prm_r.scan_order == sg["step_prm"].scan_order and not torch.equal(rec[1], midx):
+                raise RuntimeError(label + ": samples differ from the step's")
             ms[label] = rec[0]
             ms[label.replace("mdps_sample", "ball_query_cached_after")] = rd[0]
         del other
@@ -543,7 +552,13 @@ def time_knn(torch, fp, x, sg, midx, reps=3):
     """k nearest MDPS samples of every point of a stage: brute force and through the recorded
     ball bitmaps (both give the same result; checked here).  Not part of the timed step."""
     res = {}
-    for kname, cache in (("knn_brute", None), ("knn_cached", sg["cache"])):
+    kcache = sg["cache"]
+    if sg["pruned_record"]:
+        # the step's record is in cell order, which the k-NN search does not read: record once more
+        # with the index-ordered sampler (its samples are those of the same constants with scan order 0)
+        kcache = torch.empty_like(sg["cache"])
+        midx = fp.mdps_sample(x, midx.shape[1], sg["prm"], bq_cache=kcache, bq_radius=sg["radius"])
+    for kname, cache in (("knn_brute", None), ("knn_cached", kcache)):
         fp.knn(x, midx, KNN_K, bq_cache=cache)
         torch.cuda.synchronize()
         best = None
@@ -563,6 +578,8 @@ def time_knn(torch, fp, x, sg, midx, reps=3):
     if not same:
         raise RuntimeError("redundancy-free k-NN differs from the brute-force result")
     res["deferred_fraction"] = float(res["knn_cached"][2].sum().item()) / (x.shape[0] * x.shape[1])
+    res["samples"] = midx
+    res["cache"] = kcache
     return res
 
 
@@ -732,7 +749,8 @@ def path_summary(wl, detail, ms_per_step, launch_mode, roof):
         best += min(min(ms["mdps_sample"], ms["mdps_sample_pruned"]) + ms["ball_query_grid"],
                     min(ms["mdps_sample_scattered"], ms["mdps_sample_pruned_scattered"]) + ms["ball_query_grid_scattered"],
                     ms["mdps_sample+record_index_order"] + ms["ball_query_cached_after+record_index_order"],
-                    ms["mdps_sample_pruned+record"] + ms["ball_query_cached_after_pruned+record"])
+                    ms["mdps_sample_pruned+record"] + ms["ball_query_cached_after_pruned+record"],
+                    ms["mdps_sample_pruned+record_scattered"] + ms["ball_query_cached_after_pruned+record_scattered"])
     pts = wl.B * wl.N / 1e6
     s0 = detail["stages"][0]
     return {"ms_per_step": round(ms_per_step, 4), "launch": "graph" if launch_mode == GRAPH else "eager",
@@ -815,7 +833,7 @@ def run(args, torch, fp, inputs, calibration, extra, clock_reader=None):
                    "stages": [{"n": st.n, "radius": st.radius, "k": st.k} for st in wl.stages],
                    "step": "per stage: fps_exact + ball_query(brute) [+ gather]; "
                            "%s(+record) + ball_query(from record)"
-                           % ("mdps_sample_pruned" if ctx["stages"][0]["pruned_record"] else "mdps_sample"),
+                           % ("mdps_sample_pruned[scan order 1]" if ctx["stages"][0]["pruned_record"] else "mdps_sample"),
                    "launch": launch_mode, "mdps": {"p": calibration.P_RATIO, "nseg": calibration.NSEG}},
         "paths": {"exact_path_ms": summary["exact_path_ms"], "fastpoint_path_ms": summary["fastpoint_path_ms"],
                   "exact_Mpoints_s": summary["exact_Mpoints_s"],

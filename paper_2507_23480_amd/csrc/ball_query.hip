@@ -329,9 +329,8 @@ __device__ __forceinline__ uint32_t rdlane_u32(uint32_t v, int l)
 // are written.  A centre the record does not cover (not the recorded sample of that position,
 // another radius, a cloud whose list overflowed) is tested against all points by its wave, 64
 // points per step in index order.
-// most hits of a ball that the reader of a cell-ordered record sorts (a ball with more is searched
-// by brute force)
-constexpr int kCellHits = 512;
+// hits of a ball that the reader of a cell-ordered record looks at together
+constexpr int kCellBatch = 256;
 
 __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict__ xyz, int B, int N,
                                                         const int32_t* __restrict__ center_idx, int M,
@@ -342,7 +341,7 @@ __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict_
     __shared__ uint32_t s_blk[4][64];
     __shared__ uint64_t s_mask[4][64];
     __shared__ int32_t s_out[4][256];
-    __shared__ int32_t s_hit[4][kCellHits];
+    __shared__ int32_t s_hit[4][kCellBatch];
     const int b = (int)blockIdx.y;
     const int lane = (int)threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
@@ -380,18 +379,20 @@ __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict_
         done = true;
         if (h->order == 1) {
             // A record of the cell-ordered sampler: a block is 64 consecutive positions of that order
-            // and map[] gives the index of the point at a position.  All hits of the ball are turned
-            // into indices, then the k lowest are taken one at a time (a point is in the ball once,
-            // so the values differ).
+            // and map[] gives the index of the point at a position, so the hits do not come out in
+            // index order.  The wave keeps the k lowest indices seen so far (in out_s, ascending) and
+            // takes the hits in batches of kCellBatch: a batch is turned into indices, and the k lowest
+            // of kept values and batch are taken one at a time (a point is in the ball once, so the
+            // values differ).
             const int32_t* __restrict__ map = reinterpret_cast<const int32_t*>(cache + h->map_offset) + (int64_t)b * N;
             int32_t* hit_s = s_hit[wave];
-            int total = 0;
+            int kept = 0;
             for (int e0 = 0; e0 < E; e0 += 64) {
                 BqEntry g;
                 g.other = 0u;
                 g.lo = g.hi = 0u;
                 if (e0 + lane < E) g = ent[e0 + lane];
-                uint64_t m = ((uint64_t)g.hi << 32) | g.lo;
+                const uint64_t m = ((uint64_t)g.hi << 32) | g.lo;
                 const int pc = __builtin_popcountll(m);
                 int incl = pc;
 #pragma unroll
@@ -399,35 +400,45 @@ __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict_
                     const int up = __shfl_up(incl, sft, 64);
                     if (lane >= sft) incl += up;
                 }
-                int pos = total + incl - pc;
-                while (m != 0) {
-                    if (pos < kCellHits) hit_s[pos] = map[(int64_t)(g.other << 6) + __builtin_ctzll(m)];
-                    ++pos;
-                    m &= m - 1;
+                const int gsum = __builtin_amdgcn_readlane(incl, 63);     // hits of these 64 entries
+                const int excl = incl - pc;
+                const int ne = E - e0 < 64 ? E - e0 : 64;
+                for (int b0 = 0; b0 < gsum; b0 += kCellBatch) {
+                    // entry by entry: the 64 lanes read the indices of the block's 64 positions (one
+                    // line of memory), the lanes whose bit is set keep theirs
+                    for (int e = 0; e < ne; ++e) {
+                        const int ex = __builtin_amdgcn_readlane(excl, e), en = __builtin_amdgcn_readlane(pc, e);
+                        if (en == 0 || ex + en <= b0 || ex >= b0 + kCellBatch) continue;     // wave-uniform
+                        const uint64_t em = ((uint64_t)rdlane_u32(g.hi, e) << 32) | rdlane_u32(g.lo, e);
+                        const int64_t pos = ((int64_t)rdlane_u32(g.other, e) << 6) + lane;
+                        const int32_t at = pos < N ? map[pos] : 0;
+                        const int r = ex + lanes_below(em);
+                        if (((em >> lane) & 1ull) != 0 && r >= b0 && r < b0 + kCellBatch) hit_s[r - b0] = at;
+                    }
+                    const int fresh = gsum - b0 < kCellBatch ? gsum - b0 : kCellBatch;
+                    // the same wave reads back what it wrote: the LDS keeps a wave's operations in order
+                    int32_t v[8];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        v[i] = lane + 64 * i < kept ? out_s[lane + 64 * i] : 0x7FFFFFFF;
+                        v[4 + i] = lane + 64 * i < fresh ? hit_s[lane + 64 * i] : 0x7FFFFFFF;
+                    }
+                    const int want = kept + fresh < k ? kept + fresh : k;
+                    for (int t = 0; t < want; ++t) {
+                        int32_t mn = v[0];
+#pragma unroll
+                        for (int i = 1; i < 8; ++i) mn = min(mn, v[i]);
+#pragma unroll
+                        for (int sft = 32; sft > 0; sft >>= 1) mn = min(mn, __shfl_xor(mn, sft, 64));
+                        mn = __builtin_amdgcn_readfirstlane(mn);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) v[i] = v[i] == mn ? 0x7FFFFFFF : v[i];
+                        if (lane == 0) out_s[t] = mn;
+                    }
+                    kept = want;
                 }
-                total += __builtin_amdgcn_readlane(incl, 63);
             }
-            if (total > kCellHits) {
-                done = false;
-            } else {
-                // the same wave reads back what it wrote: the LDS keeps a wave's operations in order
-                int32_t v[kCellHits / 64];
-#pragma unroll
-                for (int i = 0; i < kCellHits / 64; ++i) v[i] = lane + 64 * i < total ? hit_s[lane + 64 * i] : 0x7FFFFFFF;
-                const int want = total < k ? total : k;
-                for (int t = 0; t < want; ++t) {
-                    int32_t mn = v[0];
-#pragma unroll
-                    for (int i = 1; i < kCellHits / 64; ++i) mn = min(mn, v[i]);
-#pragma unroll
-                    for (int sft = 32; sft > 0; sft >>= 1) mn = min(mn, __shfl_xor(mn, sft, 64));
-                    mn = __builtin_amdgcn_readfirstlane(mn);
-#pragma unroll
-                    for (int i = 0; i < kCellHits / 64; ++i) v[i] = v[i] == mn ? 0x7FFFFFFF : v[i];
-                    if (lane == 0) out_s[t] = mn;
-                }
-                nh = want;
-            }
+            nh = kept;
         } else if (E <= 64) {
             BqEntry me;
             me.other = 0xFFFFFFFFu;
