@@ -57,13 +57,13 @@ GRAPH = "four streams, step replayed as one HIP graph"
 # bench_C2_hbm_traffic.md), keyed by workload and kernel.  None where no counter run is recorded.  The
 # samplers keep the cloud in registers: what they move beyond reading it once is the polling of the
 # words exchanged between the workgroups of a cloud.
-TRAFFIC_BYTES = {"C2": {"fps_exact": 446396, "mdps_sample+record": 2353485, "ball_query_cached": 1959153,
-                        "ball_query_brute": 2003559},
-                 "C4": {"fps_exact": 90525757, "mdps_sample+record": 298704061, "ball_query_cached": 39007323,
-                        "ball_query_brute": 90791490},
-                 # (C5: the step's recorder is the cell-ordered one, its reader the one for cell-ordered records)
-                 "C5": {"fps_exact": 167294614, "mdps_sample+record": 264458538, "ball_query_cached": 27160357,
-                        "ball_query_brute": 204116585}}
+TRAFFIC_BYTES = {"C2": {"fps_exact": 453562, "mdps_sample+record": 2349387, "ball_query_cached": 1960174,
+                        "ball_query_brute": 2003556},
+                 # (C4, C5: the step's recorder is the cell-ordered one, its reader the one for cell-ordered records)
+                 "C4": {"fps_exact": 90375661, "mdps_sample+record": 249180026, "ball_query_cached": 59744860,
+                        "ball_query_brute": 90790985},
+                 "C5": {"fps_exact": 167113356, "mdps_sample+record": 273323826, "ball_query_cached": 29152740,
+                        "ball_query_brute": 204116661}}
 
 
 PRUNED_RECORD_FROM = 1 << 14

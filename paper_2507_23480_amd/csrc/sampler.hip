@@ -814,11 +814,7 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
 #pragma unroll 1
     for (int part = 0; part < kParts && !ended; ++part) {
         const int stop = kParts > 1 ? 64 * (part + 1) : 0x7FFFFFFF;
-        if (part >= 1) {
-            flush_rows<P, BQ>(rw, a, wh, pt, base + handed, 64);
-            handed += 64;
-            rw.clear(wh);
-        }
+        if (part >= 1) rw.clear(wh);
         for (;;) {
             // wait for slot s of this round (requested before the previous pick was folded); nothing
             // but the slot changes in the inner loop, so the distances and row words stay where they
@@ -845,8 +841,10 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
             }
             ++s;
         }
+        // the words of this part's picks (the one place where they are handed over: the code is long)
+        flush_rows<P, BQ>(rw, a, wh, pt, base + handed, s - handed);
+        handed = s;
     }
-    flush_rows<P, BQ>(rw, a, wh, pt, base + handed, s - handed);   // the picks not handed over yet
 }
 
 // segment boundary b_l (curve index whose value becomes R_l), l = 1..nseg
@@ -1489,30 +1487,36 @@ __device__ __forceinline__ void fold_accepted(Points<P, BQ>& pt, Shared<T>& sh, 
 {
     RowWords<P, BQ> rw;
     rw.row = wh.rows;
-    int s = 0;                    // picks folded and not handed to the record yet: lane t holds the words of the t-th
-    int my_place = 0;             // ... and the place of that pick among the round's picks
+    uint64_t m[kWinWords];
+    uint64_t left = 0;
 #pragma unroll
     for (int q = 0; q < kWinWords; ++q) {
-        uint64_t m = nw.w[q] & sh.took[q];
-        while (m != 0) {
-            const int cl = 64 * q + first_lane(m);
-            const Cand c = sh.cand[cl];
-            m &= m - 1;
-            if constexpr (BQ) {
-                if (s == 0) rw.clear(wh);
-                if (wh.lane == s) my_place = (int)sh.place[cl];
-            }
-            fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, s, rw);
-            if constexpr (BQ) {
-                if (++s == 64) {
-                    flush_rows<P, BQ>(rw, a, wh, pt, base, 64, my_place);
-                    s = 0;
-                }
-            }
-        }
+        m[q] = nw.w[q] & sh.took[q];
+        left |= m[q];
     }
-    if constexpr (BQ)
-        if (s > 0) flush_rows<P, BQ>(rw, a, wh, pt, base, s, my_place);
+    // a recording wave takes its picks up to 64 at a time: lane t of the row buffer holds the words of
+    // the t-th of them and the place of that pick among the round's picks
+#pragma unroll 1
+    while (left != 0) {
+        if constexpr (BQ) rw.clear(wh);
+        int s = 0;
+        int my_place = 0;
+        left = 0;
+#pragma unroll
+        for (int q = 0; q < kWinWords; ++q) {
+            while (m[q] != 0 && (!BQ || s < 64)) {
+                const int cl = 64 * q + first_lane(m[q]);
+                const Cand c = sh.cand[cl];
+                m[q] &= m[q] - 1;
+                if constexpr (BQ)
+                    if (wh.lane == s) my_place = (int)sh.place[cl];
+                fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, BQ ? s : 0, rw);
+                ++s;
+            }
+            left |= m[q];
+        }
+        flush_rows<P, BQ>(rw, a, wh, pt, base, s, my_place);
+    }
 }
 
 // Exact FPS for several picks at once.  The candidates are ALL points whose distance exceeds
@@ -2010,7 +2014,7 @@ __device__ __forceinline__ void run_cloud(const SamplerArgs& a, Shared<T>& sh, c
         // ---- threshold sampling (main loop of Alg. 2), running-distance form
         // candidates per round: one or (WIDE) two per lane of the control wave
         constexpr int kCandThr = WINDOWS ? kCandWin : (WIDE ? kCandMax : kCand);
-        [[maybe_unused]] constexpr int kWinAim = kCandWin * 3 / 4;      // candidates a window is sized for
+        [[maybe_unused]] constexpr int kWinAim = kCandWin * 3 / 4;      // candidates a window is sized for (7/8: more repeated scans on the LiDAR clouds than rounds saved)
         // The quota rule (the level floor of Alg. 2) puts sample position i on level 1 + floor(i nseg / n), i.e. on a
         // level above l as soon as i >= ceil(n l / nseg): the positions are tabulated once, a round
         // then compares with the one that ends its level.
