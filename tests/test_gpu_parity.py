@@ -249,7 +249,8 @@ def test_ball_query_out_of_range_centre(fp):
 @pytest.mark.parametrize("sampler", ["fps", "mdps", "mdps_pruned", "mdps_pruned_scattered"])
 @pytest.mark.parametrize("N,n,G,radius,k", [(4096, 1024, 0, 0.1, 32), (9001, 1500, 3, 0.12, 16),
                                             (700, 700, 0, 0.3, 8), (20000, 3000, 0, 0.05, 32),
-                                            (6000, 900, 2, 0.5, 64)])
+                                            (6000, 900, 2, 0.5, 64), (6000, 900, 0, 0.5, 100),
+                                            (40000, 500, 0, 0.6, 16)])
 def test_cached_ball_query_equals_brute_force(fp, sampler, N, n, G, radius, k):
     # Section 4.2: reading the radius tests recorded during sampling changes nothing
     say("cached bq %s N=%d n=%d G=%d" % (sampler, N, n, G))
@@ -264,8 +265,8 @@ def test_cached_ball_query_equals_brute_force(fp, sampler, N, n, G, radius, k):
         elif sampler == "mdps":
             idx = fp.mdps_sample(xyz, n, prm, bq_cache=cache, bq_radius=radius)
         else:
-            # the cell-ordered sampler records blocks of positions; a radius of half the cloud (last
-            # case) gives balls of more hits than the reader sorts, which it then searches by brute force
+            # the cell-ordered sampler records blocks of positions; a radius of half the cloud gives
+            # balls of thousands of hits, which the reader goes through in batches
             prm.scan_order = 1 if sampler == "mdps_pruned_scattered" else 0
             idx = fp.mdps_sample_pruned(xyz, n, prm, bq_cache=cache, bq_radius=radius)
             assert torch.equal(idx, fp.mdps_sample(xyz, n, prm))
