@@ -77,7 +77,9 @@ def run(name: str, log=print) -> List[dict]:
     import dataclasses
     base = calibration.params_for(name, 0)
     scattered = dataclasses.replace(base, scan_order=1)
-    for label, prm, entry in (("pure power function", calibration.params_for(name, 0, "paper"), fp.mdps_sample),
+    paper = calibration.params_for(name, 0, "paper")
+    for label, prm, entry in (("pure power function", paper, fp.mdps_sample),
+                              ("pure power function, no bias", dataclasses.replace(paper, bias=1.0), fp.mdps_sample),
                               ("MLP", mlp_estimator.params_for(name, 0), fp.mdps_sample),
                               ("segment factors, scattered scan order", scattered, fp.mdps_sample),
                               ("segment factors, pruned updates", base, fp.mdps_sample_pruned),
