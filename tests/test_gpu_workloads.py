@@ -231,6 +231,25 @@ def check_large(fp, cal, name, n_small, bq_centres):
     torch.cuda.synchronize()
     assert torch.equal(bq, cbq) and torch.equal(cnt, ccnt), "cached ball query differs from brute force"
     assert torch.equal(kpos, ckpos) and torch.equal(kd2, ckd2), "redundancy-free k-NN differs from brute force"
+    # the cell-ordered recorder at full size, both scan orders: its samples are those of mdps_sample (compared
+    # with the stored oracle results below), the ball query read from its record is the brute-force one
+    # (sampled rows of which are compared with the oracle below), and the k-NN search, which does not
+    # read such a record, still returns the brute-force result
+    for order in (0, 1):
+        oprm = dataclasses.replace(prm, scan_order=order)
+        pcache = fp.new_bq_cache(xyz, n, 10 * N if name == "C4" else 0)
+        pidx = fp.mdps_sample_pruned(xyz, n, oprm, bq_cache=pcache, bq_radius=st.radius)
+        assert torch.equal(pidx, fp.mdps_sample(xyz, n, oprm))
+        pbq, pcnt = fp.ball_query(xyz, pidx, st.radius, st.k, bq_cache=pcache)
+        wbq, wcnt = (bq, cnt) if order == 0 else fp.ball_query(xyz, pidx, st.radius, st.k)
+        torch.cuda.synchronize()
+        assert not any(fp.bq_cache_stats(pcache)["incomplete"])
+        assert torch.equal(pbq, wbq) and torch.equal(pcnt, wcnt), "ball query from the cell-ordered record, order %d" % order
+        if order == 0:
+            pk = fp.knn(xyz, pidx, KNN_K, bq_cache=pcache)
+            torch.cuda.synchronize()
+            assert torch.equal(pk[0], kpos) and torch.equal(pk[1], kd2)
+        del pcache
     say("   k-NN points searched by brute force: %s of %d" % (deferred.cpu().tolist(), N))
     kpos, kd2 = kpos.cpu().numpy(), kd2.cpu().numpy()
     idx, mdc, midx = idx.cpu().numpy(), mdc.cpu().numpy(), midx.cpu().numpy()
