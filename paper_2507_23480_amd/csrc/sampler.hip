@@ -28,6 +28,15 @@
 // accepted earlier in the round (exactly what picking them one at a time would
 // do), and folds all accepted picks into the distances in one sweep.
 //
+// Which available point the threshold phase takes next is left open by Section 4.1 step 3; two
+// deterministic orders are built: the lowest index, and the first point of a scattered walk over the
+// indices (j_t = (t A) mod N).  Three layouts of a cloud in the registers serve them: the cloud as
+// given (index order), a copy in the order of the walk (positions are places in the walk), and a
+// copy in the order of a Hilbert curve over a grid (cell order) -- there a wave's points lie in a
+// small box, a pick is folded only into the waves it can affect, and a round's candidates are all
+// available points of a window of indices (or places in the walk), settled together from the pairwise
+// relations "comes before" and "lies closer than R_l" instead of one after the other.
+//
 // All floating point here must round every operation separately: the file is
 // compiled with -ffp-contract=off and without packed fp32 instructions.
 #include <hip/hip_runtime.h>
