@@ -202,6 +202,7 @@ fp_status run_sampler(const float* xyz, int32_t B, int32_t N, int32_t n, const i
     const bool walk = prm != nullptr && prm->scan_order == 1;
     if (prm && (prm->scan_order < 0 || prm->scan_order > 1)) return FP_ERR_PARAM;
     if (bq_cache && ((walk && !pruned) || (pruned && !prm))) return FP_ERR_PARAM;
+    if (walk && !pruned && fp_mdps_scattered_workspace_bytes(B, N) == 0) return FP_ERR_SHAPE;
     if (!workspace ||
         workspace_bytes < (pruned ? fp_fps_pruned_workspace_bytes(B, N)
                                   : (walk ? fp_mdps_scattered_workspace_bytes(B, N) : fp_workspace_bytes(B, N))) ||

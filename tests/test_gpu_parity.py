@@ -206,6 +206,15 @@ def test_mdps_scattered_order_refusals(fp):
         fp.mdps_sample(xyz, 100, prm, ws=fp.new_workspace(xyz.device, 1, 2000))
     with pytest.raises(RuntimeError):
         fp.mdps_sample(xyz, 100, fp.MdpsParams(exponent=0.8, scan_order=2))
+    # a batch whose copy in walk order would not be addressable: refused before anything is read
+    import ctypes
+    lib = fp.load()
+    assert lib.fp_mdps_scattered_workspace_bytes(5000, 1 << 21) == 0
+    out = torch.empty(16, dtype=torch.int32, device="cuda")
+    ws = fp.new_workspace(xyz.device, 1, 2000)
+    c = prm.to_c()
+    assert lib.fp_mdps_sample(xyz.data_ptr(), 5000, 1 << 21, 4, None, ctypes.byref(c), out.data_ptr(), None, None, 0,
+                              0.0, ws.data_ptr(), ws.numel(), None) == -2
     torch.cuda.synchronize()
 
 
