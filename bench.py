@@ -57,13 +57,13 @@ GRAPH = "four streams, step replayed as one HIP graph"
 # bench_C2_hbm_traffic.md), keyed by workload and kernel.  None where no counter run is recorded.  The
 # samplers keep the cloud in registers: what they move beyond reading it once is the polling of the
 # words exchanged between the workgroups of a cloud.
-TRAFFIC_BYTES = {"C2": {"fps_exact": 453562, "mdps_sample+record": 2349387, "ball_query_cached": 1960174,
-                        "ball_query_brute": 2003556},
+TRAFFIC_BYTES = {"C2": {"fps_exact": 451515, "mdps_sample+record": 2381384, "ball_query_cached": 1960176,
+                        "ball_query_brute": 2003558},
                  # (C4, C5: the step's recorder is the cell-ordered one, its reader the one for cell-ordered records)
-                 "C4": {"fps_exact": 90375661, "mdps_sample+record": 249180026, "ball_query_cached": 59744860,
-                        "ball_query_brute": 90790985},
-                 "C5": {"fps_exact": 167113356, "mdps_sample+record": 273323826, "ball_query_cached": 29152740,
-                        "ball_query_brute": 204116661}}
+                 "C4": {"fps_exact": 90513941, "mdps_sample+record": 249870127, "ball_query_cached": 59836625,
+                        "ball_query_brute": 90814037},
+                 "C5": {"fps_exact": 166428283, "mdps_sample+record": 264025455, "ball_query_cached": 29160476,
+                        "ball_query_brute": 204116251}}
 
 
 PRUNED_RECORD_FROM = 1 << 14

@@ -226,7 +226,7 @@ fp_status fp_mdps_sample_pruned(const float* xyz, int32_t B, int32_t N, int32_t 
  * hit; out_cnt = min(hits, k).  1 <= k <= 254.
  *   center_idx [B][M] int32, out_idx [B][M][k] int32, out_cnt [B][M] int32 or NULL
  *   bq_cache   NULL = brute force over all N points.  Otherwise a cache filled
- *              by fp_fps_exact / fp_mdps_sample on the same xyz: centres that
+ *              by fp_fps_exact / fp_mdps_sample / fp_mdps_sample_pruned on the same xyz: centres that
  *              are the cached samples (same position q, same radius) are read
  *              from the cache with no distance evaluation (redundancy-free ball
  *              query, Section 4.2); any other centre, and every centre of a cloud

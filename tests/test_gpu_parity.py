@@ -259,7 +259,8 @@ def test_ball_query_out_of_range_centre(fp):
 @pytest.mark.parametrize("N,n,G,radius,k", [(4096, 1024, 0, 0.1, 32), (9001, 1500, 3, 0.12, 16),
                                             (700, 700, 0, 0.3, 8), (20000, 3000, 0, 0.05, 32),
                                             (6000, 900, 2, 0.5, 64), (6000, 900, 0, 0.5, 100),
-                                            (40000, 500, 0, 0.6, 16)])
+                                            (40000, 500, 0, 0.6, 16), (9000, 1200, 2, 0.1, 16),
+                                            (1000, 1000, 1, 0.2, 16)])
 def test_cached_ball_query_equals_brute_force(fp, sampler, N, n, G, radius, k):
     # Section 4.2: reading the radius tests recorded during sampling changes nothing
     say("cached bq %s N=%d n=%d G=%d" % (sampler, N, n, G))
