@@ -40,6 +40,7 @@ constexpr int kSortCap = 2048;         // hits at the largest radius that one wa
 constexpr int kHeavyWaves = 4;         // waves (= points) per workgroup of the kernel for longer rows
 constexpr int kSlabWordsMax = 2048;    // 32-bit words of one wave's index bitmap: a slab of up to 65536 indices
 constexpr int kScanBlock = 2048;       // elements per workgroup of the offset scan (256 threads x 8)
+constexpr int kCellTile = 16384;       // cells per workgroup of the scan over a grid's cells (1024 threads x 16)
 constexpr float kCellSlack = 1.001f;   // cell width = largest radius x this (absorbs the rounding of
                                        // the cell coordinate, at most 1024 cells per axis)
 
@@ -300,54 +301,135 @@ __global__ __launch_bounds__(256) void grid_count_kernel(const float* __restrict
 
 // One workgroup per cloud: cell_start = exclusive scan of the cell counts; the counts become
 // the scatter cursors.
-__global__ __launch_bounds__(1024) void grid_scan_kernel(const ExclGrid* __restrict__ gp, int32_t* cell_cnt,
-                                                         int32_t* cell_start, int maxcells)
+// Exclusive scan of the cell counts of every cloud (cell starts, and the cursors of the scatter), in
+// tiles of kCellTile cells: a first launch adds up every tile, the second gives every tile the sum
+// of the tiles in front of it and scans inside.  A thread takes 16 consecutive cells (four 16-byte
+// reads and writes where the arrays are aligned for them).
+constexpr int kCellPer = 16;
+static_assert(kCellTile == 1024 * kCellPer, "a tile is what one workgroup takes in one turn");
+
+__device__ __forceinline__ void load_cells(const int32_t* cnt, int c0, int ncells, bool wide, int (&v)[kCellPer])
+{
+    if (c0 + kCellPer <= ncells && wide) {
+#pragma unroll
+        for (int q = 0; q < kCellPer / 4; ++q) {
+            const int4 t = reinterpret_cast<const int4*>(cnt + c0)[q];
+            v[4 * q] = t.x;
+            v[4 * q + 1] = t.y;
+            v[4 * q + 2] = t.z;
+            v[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < kCellPer; ++u) v[u] = c0 + u < ncells ? cnt[c0 + u] : 0;
+    }
+}
+
+// sum over the workgroup (1024 threads); every thread gets it
+__device__ __forceinline__ int block_sum_1024(int v, int32_t* wsum16)
+{
+    const int tid = (int)threadIdx.x, lane = tid & 63, w = tid >> 6;
+    for (int s = 32; s > 0; s >>= 1) v += __shfl_xor(v, s, 64);
+    if (lane == 0) wsum16[w] = v;
+    __syncthreads();
+    int total = 0;
+    for (int k = 0; k < 16; ++k) total += wsum16[k];
+    __syncthreads();
+    return total;
+}
+
+__global__ __launch_bounds__(1024) void grid_tile_sum_kernel(const ExclGrid* __restrict__ gp,
+                                                             const int32_t* __restrict__ cell_cnt,
+                                                             int32_t* __restrict__ tile_sum, int maxcells, int tiles)
 {
     __shared__ int32_t wsum[16];
-    __shared__ int32_t carry_s;
-    const int b = (int)blockIdx.x;
+    const int b = (int)blockIdx.y, t = (int)blockIdx.x;
     const int ncells = gp[b].ncells;
+    const int32_t* cnt = cell_cnt + (int64_t)b * maxcells;
+    const bool wide = (reinterpret_cast<uintptr_t>(cnt) & 15u) == 0;
+    int v[kCellPer];
+    load_cells(cnt, t * kCellTile + (int)threadIdx.x * kCellPer, ncells, wide, v);
+    int tsum = 0;
+#pragma unroll
+    for (int u = 0; u < kCellPer; ++u) tsum += v[u];
+    const int total = block_sum_1024(tsum, wsum);
+    if (threadIdx.x == 0) tile_sum[(int64_t)b * tiles + t] = total;
+}
+
+__global__ __launch_bounds__(1024) void grid_scan_kernel(const ExclGrid* __restrict__ gp, int32_t* cell_cnt,
+                                                         int32_t* cell_start, const int32_t* __restrict__ tile_sum,
+                                                         int maxcells, int tiles)
+{
+    __shared__ int32_t wsum[16];
+    const int b = (int)blockIdx.y, t = (int)blockIdx.x;
+    const int ncells = gp[b].ncells;
+    const int base = t * kCellTile;
+    if (base >= ncells) return;                          // uniform over the workgroup
     int32_t* cnt = cell_cnt + (int64_t)b * maxcells;
     int32_t* st = cell_start + (int64_t)b * (maxcells + 1);
+    const bool cnt_wide = (reinterpret_cast<uintptr_t>(cnt) & 15u) == 0;
+    const bool st_wide = (reinterpret_cast<uintptr_t>(st) & 15u) == 0;
     const int tid = (int)threadIdx.x, lane = tid & 63, w = tid >> 6;
-    if (tid == 0) carry_s = 0;
-    __syncthreads();
-    for (int base = 0; base < ncells; base += 1024 * 8) {
-        int v[8];
-        int tsum = 0;
+    // what lies in front of this tile
+    int front = 0;
+    for (int k = tid; k < t; k += 1024) front += tile_sum[(int64_t)b * tiles + k];
+    const int carry = block_sum_1024(front, wsum);
+    const int c0 = base + tid * kCellPer;
+    const bool full = c0 + kCellPer <= ncells;
+    int v[kCellPer];
+    load_cells(cnt, c0, ncells, cnt_wide, v);
+    int tsum = 0;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int c = base + tid * 8 + u;
-            v[u] = c < ncells ? cnt[c] : 0;
-            tsum += v[u];
-        }
-        int incl = tsum;
-        for (int s = 1; s < 64; s <<= 1) {
-            const int up = __shfl_up(incl, s, 64);
-            if (lane >= s) incl += up;
-        }
-        if (lane == 63) wsum[w] = incl;
-        __syncthreads();
-        int woff = 0;
-        for (int k = 0; k < 16; ++k) woff += (k < w) ? wsum[k] : 0;
-        int total = 0;
-        for (int k = 0; k < 16; ++k) total += wsum[k];
-        const int carry = carry_s;
-        int run = carry + woff + incl - tsum;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int c = base + tid * 8 + u;
-            if (c < ncells) {
-                st[c] = run;
-                cnt[c] = run;          // cursor of the scatter
-            }
-            run += v[u];
-        }
-        __syncthreads();
-        if (tid == 0) carry_s = carry + total;
-        __syncthreads();
+    for (int u = 0; u < kCellPer; ++u) tsum += v[u];
+    int incl = tsum;
+    for (int s = 1; s < 64; s <<= 1) {
+        const int up = __shfl_up(incl, s, 64);
+        if (lane >= s) incl += up;
     }
-    if (tid == 0) st[ncells] = carry_s;
+    if (lane == 63) wsum[w] = incl;
+    __syncthreads();
+    int woff = 0;
+    for (int k = 0; k < 16; ++k) woff += (k < w) ? wsum[k] : 0;
+    int total = 0;
+    for (int k = 0; k < 16; ++k) total += wsum[k];
+    int run = carry + woff + incl - tsum;
+#pragma unroll
+    for (int u = 0; u < kCellPer; ++u) {                 // v becomes the exclusive prefix: start and scatter cursor
+        const int mine = v[u];
+        v[u] = run;
+        run += mine;
+    }
+    if (full && cnt_wide) {
+#pragma unroll
+        for (int q = 0; q < kCellPer / 4; ++q)
+            reinterpret_cast<int4*>(cnt + c0)[q] = make_int4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    } else {
+#pragma unroll
+        for (int u = 0; u < kCellPer; ++u)
+            if (c0 + u < ncells) cnt[c0 + u] = v[u];
+    }
+    if (full && st_wide) {
+#pragma unroll
+        for (int q = 0; q < kCellPer / 4; ++q)
+            reinterpret_cast<int4*>(st + c0)[q] = make_int4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    } else {
+#pragma unroll
+        for (int u = 0; u < kCellPer; ++u)
+            if (c0 + u < ncells) st[c0 + u] = v[u];
+    }
+    if (tid == 0 && base + kCellTile >= ncells) st[ncells] = carry + total;      // the cloud's last tile
+}
+
+// the two launches of the scan
+static void launch_cell_scan(const ExclGrid* gp, int32_t* cnt, int32_t* st, int32_t* tile_sum, int B, int maxcells,
+                             hipStream_t stream)
+{
+    const int tiles = (maxcells + kCellTile - 1) / kCellTile;
+    const dim3 grid((unsigned)tiles, (unsigned)B);
+    hipLaunchKernelGGL(grid_tile_sum_kernel, grid, dim3(1024), 0, stream, gp, (const int32_t*)cnt, tile_sum, maxcells,
+                       tiles);
+    hipLaunchKernelGGL(grid_scan_kernel, grid, dim3(1024), 0, stream, gp, cnt, st, (const int32_t*)tile_sum, maxcells,
+                       tiles);
 }
 
 __global__ __launch_bounds__(256) void grid_scatter_kernel(const float* __restrict__ xyz, int N,
@@ -992,6 +1074,8 @@ ExclLayout excl_layout(int B, int N, int L)
     lay.totals_off = at;
     const int64_t rows = (int64_t)L * B * N;
     at += up(((rows + kScanBlock - 1) / kScanBlock + 1) * 8);
+    lay.tiles_off = at;              // sums of the cell counts per tile of kCellTile cells (the scan over the cells)
+    at += up((int64_t)B * ((mc + kCellTile - 1) / kCellTile) * 4);
     lay.bytes = at;
     return lay;
 }
@@ -1029,7 +1113,7 @@ hipError_t launch_spatial_sort(const float* xyz, int B, int N, void* workspace, 
     hipLaunchKernelGGL(sort_setup_kernel, dim3((B + 63) / 64), dim3(64), 0, stream, gp, B, sort_bits(lay.maxcells));
     const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
     hipLaunchKernelGGL(grid_count_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, lay.maxcells);
-    hipLaunchKernelGGL(grid_scan_kernel, dim3(B), dim3(1024), 0, stream, gp, cnt, st, lay.maxcells);
+    launch_cell_scan(gp, cnt, st, reinterpret_cast<int32_t*>(base + lay.tiles_off), B, lay.maxcells, stream);
     hipLaunchKernelGGL(grid_scatter_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, sorted, lay.maxcells);
     return hipGetLastError();
 }
@@ -1055,7 +1139,7 @@ hipError_t launch_excl_count(const float* xyz, int B, int N, const float* thr2, 
                        0.0f);
     const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
     hipLaunchKernelGGL(grid_count_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, lay.maxcells);
-    hipLaunchKernelGGL(grid_scan_kernel, dim3(B), dim3(1024), 0, stream, gp, cnt, st, lay.maxcells);
+    launch_cell_scan(gp, cnt, st, reinterpret_cast<int32_t*>(base + lay.tiles_off), B, lay.maxcells, stream);
     hipLaunchKernelGGL(grid_scatter_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, sorted, lay.maxcells);
     const dim3 wgrid((unsigned)((N + kWaves - 1) / kWaves), (unsigned)B);
     hipLaunchKernelGGL(excl_count_kernel, wgrid, dim3(kWaves * 64), 0, stream, xyz, B, N, thr2, L, offsets, gp, st,
@@ -1116,7 +1200,7 @@ hipError_t launch_knn_grid(const float* xyz, int B, int N, const float* sample_x
                        static_cast<const float*>(nullptr), 1, lay.maxcells, r2);
     const dim3 sgrid((unsigned)((n + 255) / 256), (unsigned)B);
     hipLaunchKernelGGL(grid_count_kernel, sgrid, dim3(256), 0, stream, sample_xyz, n, gp, cnt, lay.maxcells);
-    hipLaunchKernelGGL(grid_scan_kernel, dim3(B), dim3(1024), 0, stream, gp, cnt, st, lay.maxcells);
+    launch_cell_scan(gp, cnt, st, reinterpret_cast<int32_t*>(base + lay.tiles_off), B, lay.maxcells, stream);
     hipLaunchKernelGGL(grid_scatter_kernel, sgrid, dim3(256), 0, stream, sample_xyz, n, gp, cnt, sorted, lay.maxcells);
     const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
     if (k == 1)
@@ -1152,7 +1236,7 @@ hipError_t launch_bq_grid(const float* xyz, int B, int N, const int32_t* center_
                        static_cast<const float*>(nullptr), 1, lay.maxcells, r2);
     const dim3 pgrid((unsigned)((N + 255) / 256), (unsigned)B);
     hipLaunchKernelGGL(grid_count_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, lay.maxcells);
-    hipLaunchKernelGGL(grid_scan_kernel, dim3(B), dim3(1024), 0, stream, gp, cnt, st, lay.maxcells);
+    launch_cell_scan(gp, cnt, st, reinterpret_cast<int32_t*>(base + lay.tiles_off), B, lay.maxcells, stream);
     hipLaunchKernelGGL(grid_scatter_kernel, pgrid, dim3(256), 0, stream, xyz, N, gp, cnt, sorted, lay.maxcells);
     hipLaunchKernelGGL(bq_grid_kernel, dim3((unsigned)((M + kWaves - 1) / kWaves), (unsigned)B), dim3(kWaves * 64), 0,
                        stream, xyz, N, center_idx, M, r2, k, out_idx, out_cnt, gp, st, sorted, lay.maxcells);

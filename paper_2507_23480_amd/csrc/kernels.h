@@ -174,7 +174,7 @@ struct ExclGrid {
 // Where the parts of an exclusion-list workspace lie (byte offsets).
 struct ExclLayout {
     int maxcells;            // cells a cloud's grid may have
-    int64_t grid_off, cnt_off, start_off, sorted_off, totals_off, bytes;
+    int64_t grid_off, cnt_off, start_off, sorted_off, totals_off, tiles_off, bytes;
 };
 
 ExclLayout excl_layout(int B, int N, int L);
