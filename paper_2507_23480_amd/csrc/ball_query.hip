@@ -329,8 +329,10 @@ __device__ __forceinline__ uint32_t rdlane_u32(uint32_t v, int l)
 // are written.  A centre the record does not cover (not the recorded sample of that position,
 // another radius, a cloud whose list overflowed) is tested against all points by its wave, 64
 // points per step in index order.
-// hits of a ball that the reader of a cell-ordered record looks at together
+// hits of a ball that the reader of a cell-ordered record looks at together, and the entries whose
+// index reads it issues before using the first
 constexpr int kCellBatch = 256;
+constexpr int kCellLoads = 8;
 
 __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict__ xyz, int B, int N,
                                                         const int32_t* __restrict__ center_idx, int M,
@@ -380,64 +382,71 @@ __global__ __launch_bounds__(256) void bq_cached_kernel(const float* __restrict_
         if (h->order == 1) {
             // A record of the cell-ordered sampler: a block is 64 consecutive positions of that order
             // and map[] gives the index of the point at a position, so the hits do not come out in
-            // index order.  The wave keeps the k lowest indices seen so far (in out_s, ascending) and
-            // takes the hits in batches of kCellBatch: a batch is turned into indices, and the k lowest
-            // of kept values and batch are taken one at a time (a point is in the ball once, so the
-            // values differ).
+            // index order.  The wave keeps the k lowest indices seen so far (in out_s, ascending); once
+            // it has k of them the largest is a bound, and only hits with an index below it are
+            // collected (in hit_s).  When hit_s fills, and at the end, the k lowest of kept and
+            // collected values are taken one at a time (a point is in the ball once, so the values
+            // differ).  Entry by entry the 64 lanes read the indices of the block's 64 positions (one
+            // line of memory); the reads of kCellLoads entries are issued together.
             const int32_t* __restrict__ map = reinterpret_cast<const int32_t*>(cache + h->map_offset) + (int64_t)b * N;
             int32_t* hit_s = s_hit[wave];
-            int kept = 0;
+            int kept = 0, fresh = 0;
+            int32_t bound = 0x7FFFFFFF;
+            auto take_lowest = [&]() {
+                // the same wave reads back what it wrote: the LDS keeps a wave's operations in order
+                int32_t v[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    v[i] = lane + 64 * i < kept ? out_s[lane + 64 * i] : 0x7FFFFFFF;
+                    v[4 + i] = lane + 64 * i < fresh ? hit_s[lane + 64 * i] : 0x7FFFFFFF;
+                }
+                const int want = kept + fresh < k ? kept + fresh : k;
+                int32_t mn = 0x7FFFFFFF;
+                for (int t = 0; t < want; ++t) {
+                    mn = v[0];
+#pragma unroll
+                    for (int i = 1; i < 8; ++i) mn = min(mn, v[i]);
+#pragma unroll
+                    for (int sft = 32; sft > 0; sft >>= 1) mn = min(mn, __shfl_xor(mn, sft, 64));
+                    mn = __builtin_amdgcn_readfirstlane(mn);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = v[i] == mn ? 0x7FFFFFFF : v[i];
+                    if (lane == 0) out_s[t] = mn;
+                }
+                kept = want;
+                fresh = 0;
+                bound = kept == k ? mn : 0x7FFFFFFF;
+            };
             for (int e0 = 0; e0 < E; e0 += 64) {
                 BqEntry g;
                 g.other = 0u;
                 g.lo = g.hi = 0u;
                 if (e0 + lane < E) g = ent[e0 + lane];
-                const uint64_t m = ((uint64_t)g.hi << 32) | g.lo;
-                const int pc = __builtin_popcountll(m);
-                int incl = pc;
-#pragma unroll
-                for (int sft = 1; sft < 64; sft <<= 1) {
-                    const int up = __shfl_up(incl, sft, 64);
-                    if (lane >= sft) incl += up;
-                }
-                const int gsum = __builtin_amdgcn_readlane(incl, 63);     // hits of these 64 entries
-                const int excl = incl - pc;
                 const int ne = E - e0 < 64 ? E - e0 : 64;
-                for (int b0 = 0; b0 < gsum; b0 += kCellBatch) {
-                    // entry by entry: the 64 lanes read the indices of the block's 64 positions (one
-                    // line of memory), the lanes whose bit is set keep theirs
-                    for (int e = 0; e < ne; ++e) {
-                        const int ex = __builtin_amdgcn_readlane(excl, e), en = __builtin_amdgcn_readlane(pc, e);
-                        if (en == 0 || ex + en <= b0 || ex >= b0 + kCellBatch) continue;     // wave-uniform
-                        const uint64_t em = ((uint64_t)rdlane_u32(g.hi, e) << 32) | rdlane_u32(g.lo, e);
-                        const int64_t pos = ((int64_t)rdlane_u32(g.other, e) << 6) + lane;
-                        const int32_t at = pos < N ? map[pos] : 0;
-                        const int r = ex + lanes_below(em);
-                        if (((em >> lane) & 1ull) != 0 && r >= b0 && r < b0 + kCellBatch) hit_s[r - b0] = at;
+                for (int e = 0; e < ne; e += kCellLoads) {
+                    int32_t at[kCellLoads];
+#pragma unroll
+                    for (int u = 0; u < kCellLoads; ++u) {
+                        const int eu = e + u < ne ? e + u : ne - 1;         // wave-uniform
+                        const int64_t pos = ((int64_t)rdlane_u32(g.other, eu) << 6) + lane;
+                        at[u] = pos < N ? map[pos] : 0x7FFFFFFF;
                     }
-                    const int fresh = gsum - b0 < kCellBatch ? gsum - b0 : kCellBatch;
-                    // the same wave reads back what it wrote: the LDS keeps a wave's operations in order
-                    int32_t v[8];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        v[i] = lane + 64 * i < kept ? out_s[lane + 64 * i] : 0x7FFFFFFF;
-                        v[4 + i] = lane + 64 * i < fresh ? hit_s[lane + 64 * i] : 0x7FFFFFFF;
+                    for (int u = 0; u < kCellLoads; ++u) {
+                        if (e + u < ne) {                                   // wave-uniform
+                            const uint64_t em = ((uint64_t)rdlane_u32(g.hi, e + u) << 32) | rdlane_u32(g.lo, e + u);
+                            const bool hit = ((em >> lane) & 1ull) != 0 && at[u] < bound;
+                            const uint64_t bm = __builtin_amdgcn_ballot_w64(hit);
+                            if (bm != 0) {
+                                if (hit) hit_s[fresh + lanes_below(bm)] = at[u];
+                                fresh += __builtin_popcountll(bm);
+                                if (fresh > kCellBatch - 64) take_lowest();
+                            }
+                        }
                     }
-                    const int want = kept + fresh < k ? kept + fresh : k;
-                    for (int t = 0; t < want; ++t) {
-                        int32_t mn = v[0];
-#pragma unroll
-                        for (int i = 1; i < 8; ++i) mn = min(mn, v[i]);
-#pragma unroll
-                        for (int sft = 32; sft > 0; sft >>= 1) mn = min(mn, __shfl_xor(mn, sft, 64));
-                        mn = __builtin_amdgcn_readfirstlane(mn);
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) v[i] = v[i] == mn ? 0x7FFFFFFF : v[i];
-                        if (lane == 0) out_s[t] = mn;
-                    }
-                    kept = want;
                 }
             }
+            if (fresh > 0) take_lowest();
             nh = kept;
         } else if (E <= 64) {
             BqEntry me;
