@@ -243,10 +243,9 @@ fp_status fp_ball_query(const float* xyz, int32_t B, int32_t N,
 /*
  * Ball query through a uniform grid: the result of fp_ball_query without a cache, byte for
  * byte, for any centre set, from the 27 grid cells around a centre instead of all N points
- * (cells as wide as the radius; the hits are put back in index order, which is the order the
- * scan over all points finds them in).  A centre whose ball holds more than 2048 points is
- * scanned in index order over all points, which ends after k hits.  The grid is built in the
- * workspace by every call.
+ * (cells as wide as the radius; of the hits the k lowest indices are kept, in ascending order,
+ * which is what the scan over all points finds first).  The grid is built in the workspace by
+ * every call.
  */
 size_t fp_ball_query_grid_workspace_bytes(int32_t B, int32_t N);
 fp_status fp_ball_query_grid(const float* xyz, int32_t B, int32_t N, const int32_t* center_idx,

@@ -420,14 +420,16 @@ __global__ __launch_bounds__(1024) void grid_scan_kernel(const ExclGrid* __restr
     if (tid == 0 && base + kCellTile >= ncells) st[ncells] = carry + total;      // the cloud's last tile
 }
 
-// the two launches of the scan
+// the two launches of the scan; a grid of one tile per cloud has no tiles in front of any and
+// takes the second only
 static void launch_cell_scan(const ExclGrid* gp, int32_t* cnt, int32_t* st, int32_t* tile_sum, int B, int maxcells,
                              hipStream_t stream)
 {
     const int tiles = (maxcells + kCellTile - 1) / kCellTile;
     const dim3 grid((unsigned)tiles, (unsigned)B);
-    hipLaunchKernelGGL(grid_tile_sum_kernel, grid, dim3(1024), 0, stream, gp, (const int32_t*)cnt, tile_sum, maxcells,
-                       tiles);
+    if (tiles > 1)
+        hipLaunchKernelGGL(grid_tile_sum_kernel, grid, dim3(1024), 0, stream, gp, (const int32_t*)cnt, tile_sum,
+                           maxcells, tiles);
     hipLaunchKernelGGL(grid_scan_kernel, grid, dim3(1024), 0, stream, gp, cnt, st, (const int32_t*)tile_sum, maxcells,
                        tiles);
 }
@@ -874,15 +876,20 @@ __global__ __launch_bounds__(kHeavyWaves * 64) void excl_fill_heavy_kernel(
 
 // Ball query over the uniform grid: the result of the brute-force scan (first k hits by
 // ascending index, strict < on squared binary32 distances, unused slots repeat the first hit)
-// from the 27 cells around the centre.  One wave per centre collects the hits in LDS and orders
-// them by index; a ball with more hits than the buffer holds is scanned in index order over all
-// points instead, which ends after k hits -- and such a ball has them early.
+// from the 27 cells around the centre.  One wave per centre walks the cells and keeps the k lowest
+// indices among the hits (in keep, ascending): once it has k of them the largest is a bound, and
+// only hits with an index below it are collected; when the collection fills, and at the end, the
+// k lowest of kept and collected values are taken one at a time (a point is in the ball once, so
+// the values differ).  A ball of any size is answered from its 27 cells.
+constexpr int kGridBatch = 256;        // hits collected between two selections of the k lowest
+
 __global__ __launch_bounds__(kWaves * 64) void bq_grid_kernel(
     const float* __restrict__ xyz, int N, const int32_t* __restrict__ center_idx, int M, float r2, int k,
     int32_t* __restrict__ out_idx, int32_t* __restrict__ out_cnt, const ExclGrid* __restrict__ gp,
     const int32_t* __restrict__ cell_start, const float4* __restrict__ sorted, int maxcells)
 {
-    __shared__ uint32_t sortbuf[kWaves][kSortCap];
+    __shared__ int32_t keepbuf[kWaves][256];
+    __shared__ int32_t hitbuf[kWaves][kGridBatch];
     const int b = (int)blockIdx.y;
     const int lane = (int)threadIdx.x & 63;
     const int w = uni((int)threadIdx.x >> 6);
@@ -898,45 +905,53 @@ __global__ __launch_bounds__(kWaves * 64) void bq_grid_kernel(
     const ExclGrid g = gp[b];
     const float* __restrict__ cloud = xyz + (int64_t)b * N * 3;
     const float px = cloud[(int64_t)c * 3 + 0], py = cloud[(int64_t)c * 3 + 1], pz = cloud[(int64_t)c * 3 + 2];
-    uint32_t* buf = sortbuf[w];
+    int32_t* keep = keepbuf[w];
+    int32_t* hits = hitbuf[w];
     int cx, cy, cz;
     cell_of(g, px, py, pz, cx, cy, cz);
-    int got = 0;
-    // the walk ends as soon as the ball is known to hold more points than the buffer
-    const int enough = kSortCap;
+    int kept = 0, fresh = 0;
+    int32_t bound = 0x7FFFFFFF;
+    auto take_lowest = [&]() {
+        // the same wave reads back what it wrote: the LDS keeps a wave's operations in order
+        int32_t v[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[i] = lane + 64 * i < kept ? keep[lane + 64 * i] : 0x7FFFFFFF;
+            v[4 + i] = lane + 64 * i < fresh ? hits[lane + 64 * i] : 0x7FFFFFFF;
+        }
+        const int want = kept + fresh < k ? kept + fresh : k;
+        int32_t mn = 0x7FFFFFFF;
+        for (int t = 0; t < want; ++t) {
+            mn = v[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) mn = min(mn, v[i]);
+#pragma unroll
+            for (int sft = 32; sft > 0; sft >>= 1) mn = min(mn, __shfl_xor(mn, sft, 64));
+            mn = uni(mn);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = v[i] == mn ? 0x7FFFFFFF : v[i];
+            if (lane == 0) keep[t] = mn;
+        }
+        kept = want;
+        fresh = 0;
+        bound = kept == k ? mn : 0x7FFFFFFF;
+    };
     for_neighbours(g, cell_start + (int64_t)b * (maxcells + 1), sorted + (int64_t)b * N, cx, cy, cz, lane,
                    [&](const float4& r, bool valid) {
-                       const bool hit = valid && dist2(px, py, pz, r.x, r.y, r.z) < r2;
+                       const int32_t j = __float_as_int(r.w);
+                       const bool hit = valid && dist2(px, py, pz, r.x, r.y, r.z) < r2 && j < bound;
                        const uint64_t mk = __builtin_amdgcn_ballot_w64(hit);
-                       const int at = got + lanes_below(mk);
-                       if (hit && at < kSortCap) buf[at] = (uint32_t)__float_as_int(r.w);
-                       got += __builtin_popcountll(mk);
-                       return got <= enough;
+                       if (mk != 0) {
+                           if (hit) hits[fresh + lanes_below(mk)] = j;
+                           fresh += __builtin_popcountll(mk);
+                           if (fresh > kGridBatch - 64) take_lowest();
+                       }
+                       return true;
                    });
-    if (got <= enough) {
-        wave_order(buf, got, lane);
-        const int cnt = got < k ? got : k;
-        const int first = cnt > 0 ? (int)buf[0] : -1;
-        for (int t = lane; t < k; t += 64) row[t] = t < cnt ? (int)buf[t] : first;
-        if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = cnt;
-    } else {
-        int cnt = 0, first = -1;
-        for (int j0 = 0; j0 < N && cnt < k; j0 += 64) {
-            const int j = j0 + lane;
-            const int jj = j < N ? j : c;
-            const bool hit = j < N && dist2(px, py, pz, cloud[(int64_t)jj * 3 + 0], cloud[(int64_t)jj * 3 + 1],
-                                            cloud[(int64_t)jj * 3 + 2]) < r2;
-            const uint64_t mk = __builtin_amdgcn_ballot_w64(hit);
-            if (mk == 0) continue;
-            if (first < 0) first = j0 + __builtin_ctzll(mk);
-            const int at = cnt + lanes_below(mk);
-            if (hit && at < k) row[at] = j;
-            cnt += __builtin_popcountll(mk);
-        }
-        cnt = cnt < k ? cnt : k;
-        for (int t = cnt + lane; t < k; t += 64) row[t] = first;
-        if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = cnt;
-    }
+    if (fresh > 0) take_lowest();
+    const int first = kept > 0 ? keep[0] : -1;
+    for (int t = lane; t < k; t += 64) row[t] = t < kept ? keep[t] : first;
+    if (lane == 0 && out_cnt) out_cnt[(int64_t)b * M + q] = kept;
 }
 
 // k nearest samples through a grid over the SAMPLES (records carry the sample's position in the
