@@ -57,13 +57,13 @@ GRAPH = "four streams, step replayed as one HIP graph"
 # bench_C2_hbm_traffic.md), keyed by workload and kernel.  None where no counter run is recorded.  The
 # samplers keep the cloud in registers: what they move beyond reading it once is the polling of the
 # words exchanged between the workgroups of a cloud.
-TRAFFIC_BYTES = {"C2": {"fps_exact": 451515, "mdps_sample+record": 2381384, "ball_query_cached": 1960176,
-                        "ball_query_brute": 2003558},
+TRAFFIC_BYTES = {"C2": {"fps_exact": 451516, "mdps_sample+record": 2381385, "ball_query_cached": 1948916,
+                        "ball_query_brute": 2003560},
                  # (C4, C5: the step's recorder is the cell-ordered one, its reader the one for cell-ordered records)
-                 "C4": {"fps_exact": 90513941, "mdps_sample+record": 249870127, "ball_query_cached": 59836625,
-                        "ball_query_brute": 90814037},
-                 "C5": {"fps_exact": 166428283, "mdps_sample+record": 264025455, "ball_query_cached": 29160476,
-                        "ball_query_brute": 204116251}}
+                 "C4": {"fps_exact": 90863873, "mdps_sample+record": 249594631, "ball_query_cached": 59671830,
+                        "ball_query_brute": 90794163},
+                 "C5": {"fps_exact": 167422090, "mdps_sample+record": 263389850, "ball_query_cached": 29253696,
+                        "ball_query_brute": 204122600}}
 
 
 PRUNED_RECORD_FROM = 1 << 14
