@@ -377,7 +377,7 @@ struct RowWords {
 // registers, and the compiler then moves every running distance of the thread from one register to
 // another once per pick.  (The pick's coordinates pass through an empty asm statement there, so that
 // the second evaluation is not merged with the first.)
-template <int P, bool BQ, bool DENSE, int P0>
+template <int P, bool BQ, bool DENSE, int P0, bool REC>
 __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float cy, float cz, float bq_r2,
                                             int s, RowWords<P, BQ>& rw)
 {
@@ -390,9 +390,9 @@ __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float c
             const int p = P0 + u;
             tb[u] = __float_as_uint(dist2(cx, cy, cz, pt.x[p], pt.y[p], pt.z[p]));
             pt.d[p] = __uint_as_float(min(__float_as_uint(pt.d[p]), tb[u]));
-            if (BQ) tmin = min(tmin, tb[u]);
+            if (BQ && REC) tmin = min(tmin, tb[u]);
         }
-        if (BQ) {
+        if (BQ && REC) {
             const uint32_t r2b = __float_as_uint(bq_r2);
             if (__builtin_amdgcn_ballot_w64(tmin < r2b) != 0) {
                 if constexpr (DENSE) {
@@ -411,15 +411,17 @@ __device__ __forceinline__ void fold_groups(Points<P, BQ>& pt, float cx, float c
                 }
             }
         }
-        fold_groups<P, BQ, DENSE, P0 + GRP>(pt, cx, cy, cz, bq_r2, s, rw);
+        fold_groups<P, BQ, DENSE, P0 + GRP, REC>(pt, cx, cy, cz, bq_r2, s, rw);
     }
 }
 
-template <int P, bool BQ, bool DENSE = true>
+// REC false: a pick of a recording kernel whose ball is known to miss every point of the wave
+// (cell-ordered variant: the ball does not reach the wave's box) -- the update alone.
+template <int P, bool BQ, bool DENSE = true, bool REC = true>
 __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, float cz,
                                      const SamplerArgs& a, const Where& wh, int s, RowWords<P, BQ>& rw)
 {
-    fold_groups<P, BQ, DENSE, 0>(pt, cx, cy, cz, a.bq_r2, s, rw);
+    fold_groups<P, BQ, DENSE, 0, REC>(pt, cx, cy, cz, a.bq_r2, s, rw);
 }
 
 // Hands the words of `count` picks (sample positions base, base+1, ...; count <= 64; or, with
@@ -432,6 +434,8 @@ __device__ __forceinline__ void fold(Points<P, BQ>& pt, float cx, float cy, floa
 // here (except for its very first entry of a cloud).  After every call lane 0 notes how much of the
 // chunk is in use.  When no chunk is left the cloud's overflow flag is raised and the wave records
 // nothing more: readers then treat the cloud as not recorded.
+// (Kept in one piece: split into helpers for the chunk bookkeeping the index-ordered recorder of the
+// million-point workload ran 3 % slower.)
 template <int P, bool BQ>
 __device__ __forceinline__ void flush_rows(const RowWords<P, BQ>& rw, const SamplerArgs& a, const Where& wh,
                                            Points<P, BQ>& pt, int base, int count, int my_offset = -1)
@@ -697,17 +701,17 @@ __device__ __noinline__ double pow_int_base(int64_t x, double e)
     return acc * __longlong_as_double((long long)(1023 + (int)q) << 52);
 }
 
-// Cell-ordered variant: which of the first `count` entries of `list` can lower a distance of
-// this wave (one entry per lane), and the wave's bound brought up to date.
+// Cell-ordered variant: which of the first `count` entries of `list` (one entry per lane) this
+// wave has to fold -- those that can lower one of its distances and, in a recording kernel, those
+// whose ball can reach into the wave's box.  `ball` gets the latter: only they need the radius test.
 template <int P, bool BQ>
 __device__ __forceinline__ uint64_t near_mask(const Points<P, BQ>& pt, const Cand* list, int count, int lane,
-                                              float bq_r2)
+                                              float bq_r2, uint64_t& ball)
 {
     const Cand c = list[lane < count ? lane : 0];
-    const float bd = box_dist2<P, BQ>(pt, c.x, c.y, c.z);
-    // a recording kernel also needs the picks whose ball can reach into the box
-    const uint32_t reach = BQ ? max(pt.ub, __float_as_uint(bq_r2)) : pt.ub;
-    return __builtin_amdgcn_ballot_w64(lane < count && __float_as_uint(bd) < reach);
+    const uint32_t bd = __float_as_uint(box_dist2<P, BQ>(pt, c.x, c.y, c.z));
+    ball = BQ ? __builtin_amdgcn_ballot_w64(lane < count && bd < __float_as_uint(bq_r2)) : 0ull;
+    return __builtin_amdgcn_ballot_w64(lane < count && bd < pt.ub) | ball;
 }
 template <int P, bool BQ>
 __device__ __forceinline__ void refresh_bound(Points<P, BQ>& pt)
@@ -773,18 +777,29 @@ __device__ __forceinline__ void fold_pending(Points<P, BQ>& pt, Shared<T>& sh, c
 {
     if (npend <= 0 || wh.ctrl) return;
     RowWords<P, BQ> rw;
-    rw.clear(wh);
     if constexpr (PERM) {
-        uint64_t near = near_mask<P, BQ>(pt, sh.pend, npend, wh.lane, a.bq_r2);
-        while (near != 0) {
-            const int s = first_lane(near);
-            near &= near - 1;
+        uint64_t ball;
+        uint64_t plain = near_mask<P, BQ>(pt, sh.pend, npend, wh.lane, a.bq_r2, ball) & ~ball;
+        rw.row = wh.rows;
+        while (plain != 0) {
+            const int s = first_lane(plain);
+            plain &= plain - 1;
             const Cand cur = sh.pend[s];
-            fold<P, BQ>(pt, cur.x, cur.y, cur.z, a, wh, s, rw);
+            fold<P, BQ, true, false>(pt, cur.x, cur.y, cur.z, a, wh, s, rw);
         }
-        flush_rows<P, BQ>(rw, a, wh, pt, base, npend);
+        if (ball != 0) {                                // uniform
+            rw.clear(wh);
+            while (ball != 0) {
+                const int s = first_lane(ball);
+                ball &= ball - 1;
+                const Cand cur = sh.pend[s];
+                fold<P, BQ>(pt, cur.x, cur.y, cur.z, a, wh, s, rw);
+            }
+            flush_rows<P, BQ>(rw, a, wh, pt, base, npend);
+        }
         return;
     }
+    rw.clear(wh);
     Cand nxt = sh.pend[0];
     for (int s = 0; s < npend; ++s) {                   // npend <= kCand
         const Cand cur = nxt;
@@ -805,13 +820,18 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
 {
     int s = 0;
     RowWords<P, BQ> rw;
-    rw.clear(wh);
-    uint64_t near[NQ];                              // one bit per candidate (word q: candidates 64 q ...)
+    uint64_t near[NQ], ball[NQ];                    // one bit per candidate (word q: candidates 64 q ...)
+    uint64_t anyball = 0;
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
-        near[q] = ~0ull;
-        if constexpr (PERM) near[q] = near_mask<P, BQ>(pt, sh.cand + 64 * q, total - 64 * q, wh.lane, a.bq_r2);
+        near[q] = ball[q] = ~0ull;
+        if constexpr (PERM) near[q] = near_mask<P, BQ>(pt, sh.cand + 64 * q, total - 64 * q, wh.lane, a.bq_r2, ball[q]);
+        anyball |= ball[q];
     }
+    // a cell-ordered wave records only when the ball of some candidate reaches its box
+    const bool records = BQ && anyball != 0;
+    rw.row = wh.rows;
+    if (records) rw.clear(wh);
     uint32_t slot = lds_observe(&sh.live[0]);
     // Lane s of `rw` holds the words of a pick, so a recording wave takes a round of more than 64
     // candidates in parts of up to 64 picks and hands a part's words over before the next; that
@@ -823,7 +843,7 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
 #pragma unroll 1
     for (int part = 0; part < kParts && !ended; ++part) {
         const int stop = kParts > 1 ? 64 * (part + 1) : 0x7FFFFFFF;
-        if (part >= 1) rw.clear(wh);
+        if (part >= 1 && records) rw.clear(wh);
         for (;;) {
             // wait for slot s of this round (requested before the previous pick was folded); nothing
             // but the slot changes in the inner loop, so the distances and row words stay where they
@@ -840,18 +860,24 @@ __device__ __forceinline__ void follow_picks(Points<P, BQ>& pt, Shared<T>& sh, c
             if (s == stop) break;                   // the slot stays in hand for the next part
             const uint32_t cl = slot & kLiveMask;
             slot = lds_observe(&sh.live[s + 1]);
-            uint64_t nword = near[0];
+            uint64_t nword = near[0], bword = ball[0];
 #pragma unroll
-            for (int q = 1; q < NQ; ++q) nword = (cl >> 6) == (uint32_t)q ? near[q] : nword;
+            for (int q = 1; q < NQ; ++q) {
+                nword = (cl >> 6) == (uint32_t)q ? near[q] : nword;
+                bword = (cl >> 6) == (uint32_t)q ? ball[q] : bword;
+            }
             if (!PERM || ((nword >> (cl & 63u)) & 1ull) != 0) {
                 const Cand c = sh.cand[cl];
                 // narrow rounds are those of clouds held by one or a few workgroups
-                fold<P, BQ, NQ == 1>(pt, c.x, c.y, c.z, a, wh, kParts > 1 ? (s & 63) : s, rw);
+                if (!(PERM && BQ) || ((bword >> (cl & 63u)) & 1ull) != 0)
+                    fold<P, BQ, NQ == 1>(pt, c.x, c.y, c.z, a, wh, kParts > 1 ? (s & 63) : s, rw);
+                else
+                    fold<P, BQ, NQ == 1, false>(pt, c.x, c.y, c.z, a, wh, 0, rw);
             }
             ++s;
         }
         // the words of this part's picks (the one place where they are handed over: the code is long)
-        flush_rows<P, BQ>(rw, a, wh, pt, base + handed, s - handed);
+        if (records) flush_rows<P, BQ>(rw, a, wh, pt, base + handed, s - handed);
         handed = s;
     }
 }
@@ -954,10 +980,14 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
                                                uint32_t win_lo = 0, uint32_t win_len = 0)
 {
     constexpr int NW = T / 64;
+    // lane and thread number as values the compiler knows nothing about, so that the addresses below
+    // are formed here instead of being carried through the kernel (see settle_relations)
+    int lane = wh.lane, tid = wh.tid;
+    asm volatile("" : "+v"(lane), "+v"(tid));
     // 1. how many of this wave's points pass
 #ifdef FASTPOINT_PHASE_CLOCKS
     long long sc_t = wall_clock64();
-#define SCAN_MARK(k) do { if (!STRICT && wh.tid == 0) { const long long now__ = wall_clock64(); sh.scan_clk[k] += now__ - sc_t; sc_t = now__; } } while (0)
+#define SCAN_MARK(k) do { if (!STRICT && tid == 0) { const long long now__ = wall_clock64(); sh.scan_clk[k] += now__ - sc_t; sc_t = now__; } } while (0)
 #else
 #define SCAN_MARK(k) do { } while (0)
 #endif
@@ -967,7 +997,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         const bool av = passes<P, BQ, STRICT, WIN, RK>(pt, wh.rk, p, thr, win_lo, win_len);
         cntw += __builtin_popcountll(__builtin_amdgcn_ballot_w64(av));
     }
-    if (wh.lane == 0 && !wh.ctrl) sh.wcnt[wh.w] = cntw;     // the control wave has none (cntw == 0)
+    if (lane == 0 && !wh.ctrl) sh.wcnt[wh.w] = cntw;     // the control wave has none (cntw == 0)
     __syncthreads();
     int off = 0, tot = 0;
 #pragma unroll
@@ -989,7 +1019,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
                 const int rank = base + lanes_below(mk);
                 if (av && rank < CAP) {
                     Cand cd;
-                    cd.idx = PERM ? pt.oi[p] : (uint32_t)(((wh.gw * P + p) << 6) | wh.lane);
+                    cd.idx = PERM ? pt.oi[p] : (uint32_t)(((wh.gw * P + p) << 6) | lane);
                     cd.x = pt.x[p];
                     cd.y = pt.y[p];
                     cd.z = pt.z[p];
@@ -1016,7 +1046,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     uint64_t* cd = a.ll_cd + ((int64_t)(wh.grp * 2 + par) * wh.G) * (kCandMax * kCandWords);
     static_assert(PUB <= CAP && PUB <= kCandMax, "a workgroup's list in the exchange buffer holds kCandMax entries");
     const int publish = tot < PUB ? tot : PUB;     // (PUB < CAP: a workgroup hands on at most PUB of its own)
-    for (int e = wh.tid; e < publish * kCandWords; e += T + kCtrlThreads) {
+    for (int e = tid; e < publish * kCandWords; e += T + kCtrlThreads) {
         const int r = e / kCandWords, k = e - r * kCandWords;
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&sh.cand[r]);
         ll_store(cd + ((int64_t)wh.g * PUB + r) * kCandWords + k, src[k], seq);
@@ -1024,7 +1054,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     // (the counts of the cloud's workgroups lie side by side: a wave that waits for 64 of them touches
     // eight lines of memory, not 64)
     uint64_t* ct = a.ll_ct + (int64_t)(wh.grp * 2 + par) * wh.G;
-    if (wh.tid == 0) ll_store(ct + wh.g, (uint32_t)tot, seq);
+    if (tid == 0) ll_store(ct + wh.g, (uint32_t)tot, seq);
     __syncthreads();          // sh.cand is about to be overwritten
     SCAN_MARK(1);
     // More than 64 workgroups: thread t waits for the count of workgroup t, so that all waits
@@ -1032,10 +1062,10 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     // themselves (one count each), which saves the barrier.
     const bool spread = wh.G > 64;
     if (spread) {
-        if (wh.tid < wh.G) {
+        if (tid < wh.G) {
             uint32_t val[1];
-            const bool got = ll_wait<1>(ct + wh.tid, seq, val, a.wait_ticks);
-            sh.gpre[wh.tid + 1] = got ? (int)val[0] : -1;
+            const bool got = ll_wait<1>(ct + tid, seq, val, a.wait_ticks);
+            sh.gpre[tid + 1] = got ? (int)val[0] : -1;
         }
         __syncthreads();
         SCAN_MARK(2);
@@ -1046,7 +1076,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         int sum = 0, usum = 0;
         bool bad = false;
         for (int k = 0; k < per; ++k) {
-            const int t = wh.lane * per + k;
+            const int t = lane * per + k;
             if (t < wh.G) {
                 int v;
                 if (spread) {
@@ -1067,16 +1097,16 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         int incl = sum;
         for (int s = 1; s < 64; s <<= 1) {
             const int up = __shfl_up(incl, s, 64);
-            if (wh.lane >= s) incl += up;
+            if (lane >= s) incl += up;
         }
         const int excl = incl - sum;
         for (int k = 0; k < per; ++k) {
-            const int t = wh.lane * per + k;
+            const int t = lane * per + k;
             if (t < wh.G) sh.gpre[t + 1] += excl;
         }
         for (int s = 32; s > 0; s >>= 1) usum += __shfl_xor(usum, s, 64);
         const bool anybad = __builtin_amdgcn_ballot_w64(bad) != 0;
-        if (wh.lane == 0) {
+        if (lane == 0) {
             sh.gpre[0] = 0;
             sh.ctrl[1] = usum;
             if (anybad) sh.ctrl[2] = 1;
@@ -1095,7 +1125,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
         uint64_t got[NE];
 #pragma unroll
         for (int u = 0; u < NE; ++u) {
-            const int e = wh.tid + u * (T + kCtrlThreads);
+            const int e = tid + u * (T + kCtrlThreads);
             src[u] = nullptr;
             if (e < total * kCandWords) {
                 const int r = e / kCandWords, k = e - r * kCandWords;
@@ -1113,7 +1143,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
 #pragma unroll
         for (int u = 0; u < NE; ++u) {
             if (src[u]) {
-                const int e = wh.tid + u * (T + kCtrlThreads);
+                const int e = tid + u * (T + kCtrlThreads);
                 uint32_t val[1];
                 val[0] = (uint32_t)got[u];
                 if ((uint32_t)(got[u] >> 32) != seq && !ll_wait<1>(src[u], seq, val, a.wait_ticks)) sh.ctrl[2] = 1;
@@ -1358,10 +1388,14 @@ __device__ __forceinline__ void build_relations(Shared<T>& sh, const Where& wh, 
     constexpr int NWALL = T / 64 + 1;              // the control wave takes its share
     total = uni(total);
     const int nq = (total + 63) >> 6;              // uniform
+    // lane and thread number as values the compiler knows nothing about, so that the addresses below
+    // are formed here instead of being carried through the kernel (see settle_relations)
+    int lane = wh.lane, tid = wh.tid;
+    asm volatile("" : "+v"(lane), "+v"(tid));
     Cand me[kWinWords];
 #pragma unroll
     for (int q = 0; q < kWinWords; ++q) {
-        const int c = wh.lane + 64 * q;
+        const int c = lane + 64 * q;
         me[q] = sh.cand[c < total ? c : 0];
     }
     // With several workgroups every one of them works out the sets of the candidates g, g + G, ...
@@ -1377,19 +1411,19 @@ __device__ __forceinline__ void build_relations(Shared<T>& sh, const Where& wh, 
         for (int q = 0; q < kWinWords; ++q) {
             uint64_t before = 0, blockers = 0;
             if (q < nq) {
-                const bool earlier = wh.lane + 64 * q < total && (BYD ? me[q].d : me[q].idx) < kj;
+                const bool earlier = lane + 64 * q < total && (BYD ? me[q].d : me[q].idx) < kj;
                 const float t = dist2(pj.x, pj.y, pj.z, me[q].x, me[q].y, me[q].z);
                 before = __builtin_amdgcn_ballot_w64(earlier);
                 blockers = __builtin_amdgcn_ballot_w64(earlier && t < r2);
             }
-            set_lane(pay, wh.lane, 2 * q, (uint32_t)before);
-            set_lane(pay, wh.lane, 2 * q + 1, (uint32_t)(before >> 32));
-            set_lane(pay, wh.lane, 2 * kWinWords + 2 * q, (uint32_t)blockers);
-            set_lane(pay, wh.lane, 2 * kWinWords + 2 * q + 1, (uint32_t)(blockers >> 32));
+            set_lane(pay, lane, 2 * q, (uint32_t)before);
+            set_lane(pay, lane, 2 * q + 1, (uint32_t)(before >> 32));
+            set_lane(pay, lane, 2 * kWinWords + 2 * q, (uint32_t)blockers);
+            set_lane(pay, lane, 2 * kWinWords + 2 * q + 1, (uint32_t)(blockers >> 32));
         }
-        if (wh.lane < kRelWords) {
-            if (wh.G == 1) reinterpret_cast<uint32_t*>(&sh.rel[j][0])[wh.lane] = pay;
-            else ll_store(buf + (int64_t)j * kRelWords + wh.lane, pay, seq);
+        if (lane < kRelWords) {
+            if (wh.G == 1) reinterpret_cast<uint32_t*>(&sh.rel[j][0])[lane] = pay;
+            else ll_store(buf + (int64_t)j * kRelWords + lane, pay, seq);
         }
     }
     if (wh.G == 1) return;
@@ -1397,12 +1431,12 @@ __device__ __forceinline__ void build_relations(Shared<T>& sh, const Where& wh, 
     uint64_t got[NE];
 #pragma unroll
     for (int u = 0; u < NE; ++u) {
-        const int e = wh.tid + u * (T + kCtrlThreads);
+        const int e = tid + u * (T + kCtrlThreads);
         got[u] = e < total * kRelWords ? ll_load(buf + e) : 0;
     }
 #pragma unroll
     for (int u = 0; u < NE; ++u) {
-        const int e = wh.tid + u * (T + kCtrlThreads);
+        const int e = tid + u * (T + kCtrlThreads);
         if (e < total * kRelWords) {
             uint32_t val[1];
             val[0] = (uint32_t)got[u];
@@ -1418,12 +1452,17 @@ __device__ __forceinline__ void settle_relations(Shared<T>& sh, const Where& wh,
 {
     total = uni(total);
     limit = uni(limit);
+    // The lane number as a value the compiler knows nothing about: the LDS addresses below are then
+    // formed here.  Formed once per kernel they stay alive through all of it, end up in scratch memory,
+    // and every use in this function waits for a reload.
+    int lane = wh.lane;
+    asm volatile("" : "+v"(lane));
     const int nq = (total + 63) >> 6;              // uniform
     uint64_t blockers[kWinWords][kWinWords];
     uint64_t und[kWinWords], acc[kWinWords], rej[kWinWords];
 #pragma unroll
     for (int q = 0; q < kWinWords; ++q) {
-        const int c = wh.lane + 64 * q;
+        const int c = lane + 64 * q;
         const bool has = c < total;
         und[q] = __builtin_amdgcn_ballot_w64(has);
         acc[q] = 0;
@@ -1442,7 +1481,7 @@ __device__ __forceinline__ void settle_relations(Shared<T>& sh, const Where& wh,
                     open |= blockers[q][w] & ~rej[w];
                     hit |= blockers[q][w] & acc[w];
                 }
-                const bool mine = ((und[q] >> wh.lane) & 1ull) != 0;
+                const bool mine = ((und[q] >> lane) & 1ull) != 0;
                 const uint64_t na = __builtin_amdgcn_ballot_w64(mine && open == 0);
                 const uint64_t nr = __builtin_amdgcn_ballot_w64(mine && hit != 0);
                 acc[q] |= na;
@@ -1459,8 +1498,8 @@ __device__ __forceinline__ void settle_relations(Shared<T>& sh, const Where& wh,
     const int nacc = count < limit ? count : limit;
 #pragma unroll
     for (int q = 0; q < kWinWords; ++q) {
-        const int c = wh.lane + 64 * q;
-        const bool mine = ((acc[q] >> wh.lane) & 1ull) != 0;
+        const int c = lane + 64 * q;
+        const bool mine = ((acc[q] >> lane) & 1ull) != 0;
         int place = 0;
 #pragma unroll
         for (int w = 0; w < kWinWords; ++w)
@@ -1471,15 +1510,16 @@ __device__ __forceinline__ void settle_relations(Shared<T>& sh, const Where& wh,
             sh.place[c] = (uint16_t)place;
         }
         const uint64_t took = __builtin_amdgcn_ballot_w64(keep);
-        if (wh.lane == 0) sh.took[q] = took;
+        if (lane == 0) sh.took[q] = took;
     }
-    if (wh.lane == 0) sh.ctrl[0] = nacc;
+    if (lane == 0) sh.ctrl[0] = nacc;
 }
 
 // The point waves' side: which candidates are near the wave's box (while the control wave settles
 // the round), then -- after the barrier -- the fold of the accepted ones among them.
 struct NearWords {
-    uint64_t w[kWinWords];
+    uint64_t w[kWinWords];      // candidates to fold
+    uint64_t b[kWinWords];      // of those, the ones whose ball reaches the wave's box (recording kernels)
 };
 template <int T, int P, bool BQ>
 __device__ __forceinline__ NearWords near_candidates(const Points<P, BQ>& pt, const Shared<T>& sh,
@@ -1487,7 +1527,8 @@ __device__ __forceinline__ NearWords near_candidates(const Points<P, BQ>& pt, co
 {
     NearWords nw;
 #pragma unroll
-    for (int q = 0; q < kWinWords; ++q) nw.w[q] = near_mask<P, BQ>(pt, sh.cand + 64 * q, total - 64 * q, wh.lane, bq_r2);
+    for (int q = 0; q < kWinWords; ++q)
+        nw.w[q] = near_mask<P, BQ>(pt, sh.cand + 64 * q, total - 64 * q, wh.lane, bq_r2, nw.b[q]);
     return nw;
 }
 template <int T, int P, bool BQ>
@@ -1496,35 +1537,58 @@ __device__ __forceinline__ void fold_accepted(Points<P, BQ>& pt, Shared<T>& sh, 
 {
     RowWords<P, BQ> rw;
     rw.row = wh.rows;
-    uint64_t m[kWinWords];
+    uint64_t m[kWinWords], mb[kWinWords];
     uint64_t left = 0;
+#ifdef FASTPOINT_PHASE_CLOCKS
+    long long fa_t = wall_clock64();
+#define FOLD_MARK(k) do { if (wh.tid == 0) { const long long now__ = wall_clock64(); sh.scan_clk[k] += now__ - fa_t; fa_t = now__; } } while (0)
+#else
+#define FOLD_MARK(k) do { } while (0)
+#endif
 #pragma unroll
     for (int q = 0; q < kWinWords; ++q) {
-        m[q] = nw.w[q] & sh.took[q];
-        left |= m[q];
+        const uint64_t t = nw.w[q] & sh.took[q];
+        mb[q] = BQ ? t & nw.b[q] : 0ull;
+        m[q] = t & ~mb[q];
+        left |= mb[q];
     }
-    // a recording wave takes its picks up to 64 at a time: lane t of the row buffer holds the words of
-    // the t-th of them and the place of that pick among the round's picks
-#pragma unroll 1
-    while (left != 0) {
-        if constexpr (BQ) rw.clear(wh);
-        int s = 0;
-        int my_place = 0;
-        left = 0;
+    // the accepted candidates that need no radius test
 #pragma unroll
-        for (int q = 0; q < kWinWords; ++q) {
-            while (m[q] != 0 && (!BQ || s < 64)) {
-                const int cl = 64 * q + first_lane(m[q]);
-                const Cand c = sh.cand[cl];
-                m[q] &= m[q] - 1;
-                if constexpr (BQ)
-                    if (wh.lane == s) my_place = (int)sh.place[cl];
-                fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, BQ ? s : 0, rw);
-                ++s;
-            }
-            left |= m[q];
+    for (int q = 0; q < kWinWords; ++q) {
+        while (m[q] != 0) {
+            const Cand c = sh.cand[64 * q + first_lane(m[q])];
+            m[q] &= m[q] - 1;
+            fold<P, BQ, true, false>(pt, c.x, c.y, c.z, a, wh, 0, rw);
         }
-        flush_rows<P, BQ>(rw, a, wh, pt, base, s, my_place);
+    }
+    FOLD_MARK(5);
+    if constexpr (BQ) {
+        // a recording wave takes the others up to 64 at a time: lane t of the row buffer holds the words
+        // of the t-th of them and the place of that pick among the round's picks.  (Appending a pick's
+        // words to the list one by one as they are formed saves the row buffer but costs more wherever
+        // balls hold many blocks: measured.)
+#pragma unroll 1
+        while (left != 0) {
+            rw.clear(wh);
+            int s = 0;
+            int my_place = 0;
+            left = 0;
+#pragma unroll
+            for (int q = 0; q < kWinWords; ++q) {
+                while (mb[q] != 0 && s < 64) {
+                    const int cl = 64 * q + first_lane(mb[q]);
+                    const Cand c = sh.cand[cl];
+                    mb[q] &= mb[q] - 1;
+                    if (wh.lane == s) my_place = (int)sh.place[cl];
+                    fold<P, BQ>(pt, c.x, c.y, c.z, a, wh, s, rw);
+                    ++s;
+                }
+                left |= mb[q];
+            }
+            FOLD_MARK(6);
+            flush_rows<P, BQ>(rw, a, wh, pt, base, s, my_place);
+            FOLD_MARK(7);
+        }
     }
 }
 
