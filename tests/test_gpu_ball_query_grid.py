@@ -59,7 +59,7 @@ def test_uniform_cube(fp, N, M, radius, k):
 
 
 def test_dense_and_sparse_balls_in_one_call(fp):
-    # balls below and above the number of hits one wave orders in LDS
+    # balls of a few hits and of thousands (several selections of the k lowest per centre)
     rng = np.random.Generator(np.random.PCG64(5))
     cloud = np.concatenate([rng.normal(0, 0.01, (3500, 3)), rng.uniform(-1, 1, (2500, 3))]).astype(np.float32)
     cloud = cloud[rng.permutation(6000)]
