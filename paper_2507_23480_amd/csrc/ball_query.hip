@@ -42,6 +42,7 @@ __device__ __forceinline__ int lanes_below(uint64_t mask)
 }
 
 constexpr int kChunk = 16;      // points tested per pass of the brute-force inner loop
+typedef float Quad __attribute__((ext_vector_type(4), aligned(4)));   // four coordinates, wherever they lie
 
 // Last step of both ball-query kernels.  Each of the S waves of a workgroup has listed, per
 // centre, the first hits of its part of the index range (hits [S][64][kp], counts [S][64], in
@@ -118,21 +119,42 @@ __global__ __launch_bounds__(S * 64) void bq_brute_kernel(const float* __restric
     int j0 = j_begin;
     for (; j0 < nfull; j0 += kChunk) {
         if (__builtin_amdgcn_ballot_w64(okc && cnt < k) == 0) break;
-        uint64_t m[kChunk];
+        // The test t < r2 of dist2's t = (dx dx + dy dy) + dz dz, decided after the second term where it
+        // can be: the partial sums only grow (every term is >= 0 and rounding is monotone), so a point
+        // whose dx dx + dy dy is not below r2 for any of the wave's 64 centres is done after six
+        // operations instead of nine -- nearly every point of a large cloud.  The sums are those of
+        // dist2, term by term, so a decision that is reached is the same.  (Deciding after dx dx already
+        // was slower: with 64 unrelated centres in a wave half of the points pass that test for one of
+        // them, and a branch per point costs more than the three operations it saves.)
+        float t2[kChunk];
+        uint64_t m2[kChunk];
         uint64_t any = 0;
         const float* __restrict__ pb = cloud + (int64_t)j0 * 3;   // uniform address: scalar loads
+        // the chunk's 48 coordinates as twelve 16-byte scalar loads: every one of them holds an x or a
+        // y, so none of them moves into the branch below (where a wave would wait for it)
+        Quad qd[3 * kChunk / 4];
+#pragma unroll
+        for (int v = 0; v < 3 * kChunk / 4; ++v) qd[v] = reinterpret_cast<const Quad*>(pb)[v];
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) {
-            const float t = dist2(cx, cy, cz, pb[3 * u + 0], pb[3 * u + 1], pb[3 * u + 2]);
-            m[u] = __builtin_amdgcn_ballot_w64(t < r2);
-            any |= m[u];
+            const float dx = cx - qd[(3 * u) / 4][(3 * u) % 4];
+            const float dy = cy - qd[(3 * u + 1) / 4][(3 * u + 1) % 4];
+            float t = dx * dx;
+            t = t + dy * dy;
+            t2[u] = t;
+            m2[u] = __builtin_amdgcn_ballot_w64(t < r2);
+            any |= m2[u];
         }
         if (any != 0) {
 #pragma unroll
             for (int u = 0; u < kChunk; ++u) {
-                if (((m[u] >> lane) & 1ull) && cnt < k) {
-                    myrow[cnt] = j0 + u;
-                    ++cnt;
+                if (m2[u] != 0) {                                 // uniform
+                    const float dz = cz - qd[(3 * u + 2) / 4][(3 * u + 2) % 4];
+                    const float t3 = t2[u] + dz * dz;
+                    if (t3 < r2 && cnt < k) {
+                        myrow[cnt] = j0 + u;
+                        ++cnt;
+                    }
                 }
             }
         }
