@@ -284,7 +284,9 @@ def quality_and_rooflines(torch, fp, ctx, kernel_ms):
         if "ball_query_brute" in ms:
             a = pairs * OPS_PER_PAIR_TEST / (ms["ball_query_brute"] * 1e-3) / 1e12
             roof["ball_query_brute"] = {"bound": "alu", "achieved": a, "peak": ALU_PEAK_TOPS,
-                                        "unit": "TFLOP/s", "frac": a / ALU_PEAK_TOPS}
+                                        "unit": "TFLOP/s", "frac": a / ALU_PEAK_TOPS,
+                                        "note": "pair tests priced at the 9 operations of the full test / time: "
+                                                "most pairs are decided after 6"}
         if "ball_query_cached" in ms:
             # algorithmic bytes: the recorded entries of the centres' rows (12 bytes each) and their
             # offsets read, the result written
