@@ -980,10 +980,12 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
                                                uint32_t win_lo = 0, uint32_t win_len = 0)
 {
     constexpr int NW = T / 64;
-    // lane and thread number as values the compiler knows nothing about, so that the addresses below
-    // are formed here instead of being carried through the kernel (see settle_relations)
+    // Cell-ordered kernels (they sit at the register limit): lane and thread number as values the
+    // compiler knows nothing about, so that the addresses below are formed here instead of being
+    // carried through the kernel (see settle_relations).  The others have the registers, and there
+    // the known values save instructions.
     int lane = wh.lane, tid = wh.tid;
-    asm volatile("" : "+v"(lane), "+v"(tid));
+    if constexpr (PERM) asm volatile("" : "+v"(lane), "+v"(tid));
     // 1. how many of this wave's points pass
 #ifdef FASTPOINT_PHASE_CLOCKS
     long long sc_t = wall_clock64();
