@@ -57,13 +57,13 @@ GRAPH = "four streams, step replayed as one HIP graph"
 # bench_C2_hbm_traffic.md), keyed by workload and kernel.  None where no counter run is recorded.  The
 # samplers keep the cloud in registers: what they move beyond reading it once is the polling of the
 # words exchanged between the workgroups of a cloud.
-TRAFFIC_BYTES = {"C2": {"fps_exact": 451516, "mdps_sample+record": 2381385, "ball_query_cached": 1948916,
-                        "ball_query_brute": 2003560},
+TRAFFIC_BYTES = {"C2": {"fps_exact": 432063, "mdps_sample+record": 2349390, "ball_query_cached": 1948915,
+                        "ball_query_brute": 2004583},
                  # (C4, C5: the step's recorder is the cell-ordered one, its reader the one for cell-ordered records)
-                 "C4": {"fps_exact": 90863873, "mdps_sample+record": 249594631, "ball_query_cached": 59671830,
-                        "ball_query_brute": 90794163},
-                 "C5": {"fps_exact": 167422090, "mdps_sample+record": 263389850, "ball_query_cached": 29253696,
-                        "ball_query_brute": 204122600}}
+                 "C4": {"fps_exact": 90578153, "mdps_sample+record": 234271499, "ball_query_cached": 59653829,
+                        "ball_query_brute": 90649025},
+                 "C5": {"fps_exact": 167753556, "mdps_sample+record": 238113396, "ball_query_cached": 29244884,
+                        "ball_query_brute": 204119016}}
 
 
 PRUNED_RECORD_FROM = 1 << 14
