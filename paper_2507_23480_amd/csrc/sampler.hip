@@ -125,6 +125,18 @@ __device__ __forceinline__ uint32_t wave_max_scalar(uint32_t v)
     v = row_max_u32(v);
     return smax(smax(rdlane(v, 0), rdlane(v, 16)), smax(rdlane(v, 32), rdlane(v, 48)));
 }
+// inclusive prefix sum over the lanes of a wave: inside a row of 16 lanes by shifts of 1, 2, 4, 8
+// (a lane whose source lies outside its row adds 0), then the totals of the rows in front
+__device__ __forceinline__ int wave_incl_sum(int v, int lane)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);    // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);    // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);    // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);    // row_shr:8
+    const int r0 = (int)rdlane((uint32_t)v, 15), r1 = (int)rdlane((uint32_t)v, 31), r2 = (int)rdlane((uint32_t)v, 47);
+    const int row = lane >> 4;
+    return v + (row > 0 ? r0 : 0) + (row > 1 ? r1 : 0) + (row > 2 ? r2 : 0);
+}
 __device__ __forceinline__ int first_lane(uint64_t mask) { return __builtin_ctzll(mask); }
 __device__ __forceinline__ int lanes_below(uint64_t mask)
 {
@@ -263,6 +275,7 @@ struct Shared {
     float mlp_val[32];         // ... the curve there
     double mlp_a[128], mlp_b[128];   // ... activations of successive layers
     int32_t gpre[kMaxGroup + 1];
+    int32_t gtot[8];          // scan_candidates: totals of the (up to four) waves that add up the workgroups' counts
     int32_t ctrl[4];      // [0] accepted picks of the round, [1] points passing in the cloud,
                           // [2] failure, [3] distance bits of the last accepted pick
     // picks of the round being resolved, in acceptance order
@@ -1059,59 +1072,50 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     if (tid == 0) ll_store(ct + wh.g, (uint32_t)tot, seq);
     __syncthreads();          // sh.cand is about to be overwritten
     SCAN_MARK(1);
-    // More than 64 workgroups: thread t waits for the count of workgroup t, so that all waits
-    // are in flight together, and hands it over in LDS.  Up to 64: the lanes of wave 0 wait
-    // themselves (one count each), which saves the barrier.
-    const bool spread = wh.G > 64;
-    if (spread) {
-        if (tid < wh.G) {
-            uint32_t val[1];
-            const bool got = ll_wait<1>(ct + tid, seq, val, a.wait_ticks);
-            sh.gpre[tid + 1] = got ? (int)val[0] : -1;
+    // Thread t waits for the count of workgroup t, so that all waits are in flight together.  The
+    // prefix sums over the workgroups (gpre[t]: entries listed by the workgroups in front of t, a
+    // workgroup lists at most PUB) are formed by the waves that hold the counts: inside a wave by lane
+    // shifts, across the (at most four) waves through their totals in LDS.  Up to 64 workgroups wave 0
+    // does it alone, which saves a barrier.
+    int v = 0;
+    bool bad = false;
+    if (tid < wh.G) {
+        uint32_t val[1];
+        if (ll_wait<1>(ct + tid, seq, val, a.wait_ticks)) v = (int)val[0];
+        else bad = true;
+    }
+    const int c = v < PUB ? v : PUB;
+    const int nwv = (wh.G + 63) >> 6;                  // waves that hold counts (uniform)
+    static_assert(kMaxGroup <= 256, "the totals of four waves");
+    int incl = 0, uincl = 0;
+    if (wh.w < nwv) {                                  // wave-uniform
+        incl = wave_incl_sum(c, lane);
+        uincl = wave_incl_sum(v, lane);
+        if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) sh.ctrl[2] = 1;
+    }
+    if (nwv > 1) {
+        if (wh.w < nwv && lane == 63) {
+            sh.gtot[wh.w] = incl;
+            sh.gtot[4 + wh.w] = uincl;
         }
         __syncthreads();
         SCAN_MARK(2);
     }
-    if (wh.w == 0) {
-        // lane t adds up the counts of workgroups [t*per, (t+1)*per)
-        const int per = (wh.G + 63) / 64;
-        int sum = 0, usum = 0;
-        bool bad = false;
-        for (int k = 0; k < per; ++k) {
-            const int t = lane * per + k;
-            if (t < wh.G) {
-                int v;
-                if (spread) {
-                    v = sh.gpre[t + 1];
-                } else {
-                    uint32_t val[1];
-                    v = ll_wait<1>(ct + t, seq, val, a.wait_ticks) ? (int)val[0] : -1;
+    if (wh.w < nwv) {
+        int base = 0, ubase = 0;
+        if (nwv > 1) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                if (k < wh.w) {
+                    base += sh.gtot[k];
+                    ubase += sh.gtot[4 + k];
                 }
-                if (v < 0) {
-                    bad = true;
-                } else {
-                    usum += v;
-                    sum += v < PUB ? v : PUB;
-                }
-                sh.gpre[t + 1] = sum;      // inclusive inside the lane, fixed below
             }
         }
-        int incl = sum;
-        for (int s = 1; s < 64; s <<= 1) {
-            const int up = __shfl_up(incl, s, 64);
-            if (lane >= s) incl += up;
-        }
-        const int excl = incl - sum;
-        for (int k = 0; k < per; ++k) {
-            const int t = lane * per + k;
-            if (t < wh.G) sh.gpre[t + 1] += excl;
-        }
-        for (int s = 32; s > 0; s >>= 1) usum += __shfl_xor(usum, s, 64);
-        const bool anybad = __builtin_amdgcn_ballot_w64(bad) != 0;
-        if (lane == 0) {
-            sh.gpre[0] = 0;
-            sh.ctrl[1] = usum;
-            if (anybad) sh.ctrl[2] = 1;
+        if (tid < wh.G) sh.gpre[tid] = base + incl - c;
+        if (tid == wh.G - 1) {
+            sh.gpre[wh.G] = base + incl;
+            sh.ctrl[1] = ubase + uincl;
         }
     }
     __syncthreads();
