@@ -275,6 +275,7 @@ struct Shared {
     float mlp_val[32];         // ... the curve there
     double mlp_a[128], mlp_b[128];   // ... activations of successive layers
     int32_t gpre[kMaxGroup + 1];
+    uint16_t own[kCandWin];   // scan_candidates: the workgroup that lists the cloud's r-th candidate
     int32_t gtot[8];          // scan_candidates: totals of the (up to four) waves that add up the workgroups' counts
     int32_t ctrl[4];      // [0] accepted picks of the round, [1] points passing in the cloud,
                           // [2] failure, [3] distance bits of the last accepted pick
@@ -1060,6 +1061,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
     const int par = (int)(seq & 1u);
     uint64_t* cd = a.ll_cd + ((int64_t)(wh.grp * 2 + par) * wh.G) * (kCandMax * kCandWords);
     static_assert(PUB <= CAP && PUB <= kCandMax, "a workgroup's list in the exchange buffer holds kCandMax entries");
+    static_assert(CAP <= kCandWin, "sh.own holds one entry per candidate of a round");
     const int publish = tot < PUB ? tot : PUB;     // (PUB < CAP: a workgroup hands on at most PUB of its own)
     for (int e = tid; e < publish * kCandWords; e += T + kCtrlThreads) {
         const int r = e / kCandWords, k = e - r * kCandWords;
@@ -1112,7 +1114,12 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
                 }
             }
         }
-        if (tid < wh.G) sh.gpre[tid] = base + incl - c;
+        if (tid < wh.G) {
+            // which workgroup lists the cloud's r-th candidate, for the first CAP of them
+            const int first = base + incl - c;
+            sh.gpre[tid] = first;
+            for (int r = first; r < first + c && r < CAP; ++r) sh.own[r] = (uint16_t)tid;
+        }
         if (tid == wh.G - 1) {
             sh.gpre[wh.G] = base + incl;
             sh.ctrl[1] = ubase + uincl;
@@ -1135,12 +1142,7 @@ __device__ __forceinline__ int scan_candidates(const Points<P, BQ>& pt, Shared<T
             src[u] = nullptr;
             if (e < total * kCandWords) {
                 const int r = e / kCandWords, k = e - r * kCandWords;
-                int lo = 0, hi = wh.G;         // workgroup whose range holds rank r
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (sh.gpre[mid] <= r) lo = mid;
-                    else hi = mid;
-                }
+                const int lo = (int)sh.own[r];  // workgroup whose range holds rank r
                 src[u] = cd + ((int64_t)lo * PUB + (r - sh.gpre[lo])) * kCandWords + k;
             }
         }
