@@ -57,13 +57,13 @@ GRAPH = "four streams, step replayed as one HIP graph"
 # bench_C2_hbm_traffic.md), keyed by workload and kernel.  None where no counter run is recorded.  The
 # samplers keep the cloud in registers: what they move beyond reading it once is the polling of the
 # words exchanged between the workgroups of a cloud.
-TRAFFIC_BYTES = {"C2": {"fps_exact": 432063, "mdps_sample+record": 2349390, "ball_query_cached": 1948915,
-                        "ball_query_brute": 2004583},
+TRAFFIC_BYTES = {"C2": {"fps_exact": 443324, "mdps_sample+record": 2366792, "ball_query_cached": 1948912,
+                        "ball_query_brute": 2004579},
                  # (C4, C5: the step's recorder is the cell-ordered one, its reader the one for cell-ordered records)
-                 "C4": {"fps_exact": 90578153, "mdps_sample+record": 234271499, "ball_query_cached": 59653829,
-                        "ball_query_brute": 90649025},
-                 "C5": {"fps_exact": 167753556, "mdps_sample+record": 238113396, "ball_query_cached": 29244884,
-                        "ball_query_brute": 204119016}}
+                 "C4": {"fps_exact": 91991845, "mdps_sample+record": 235600836, "ball_query_cached": 59647997,
+                        "ball_query_brute": 90648748},
+                 "C5": {"fps_exact": 169143207, "mdps_sample+record": 229052944, "ball_query_cached": 29249249,
+                        "ball_query_brute": 204118632}}
 
 
 PRUNED_RECORD_FROM = 1 << 14
