@@ -289,8 +289,10 @@ struct Shared {
     float4 acc[kCandMax];
     // cell order: rel[j] = for candidate j of a window round, which candidates come before it in the
     // order of the sampling rule (words 0..3) and which of those lie closer to it than R_l (words 4..7);
-    // took = the accepted candidates of the round, one bit each
-    uint64_t rel[kCandWin][8];
+    // took = the accepted candidates of the round, one bit each.  A row is nine words long, the last
+    // unused: lane l of the control wave reads word w of candidate l (+ 64 q), and with rows of 64 bytes
+    // the 64 lanes would meet in two pairs of LDS banks; with 72 bytes they spread over all of them.
+    uint64_t rel[kCandWin][9];
     uint64_t took[kCandWin / 64];
     uint16_t place[kCandWin];  // ... and of each accepted one its place among the round's picks
     uint32_t progress;
@@ -1449,7 +1451,7 @@ __device__ __forceinline__ void build_relations(Shared<T>& sh, const Where& wh, 
             uint32_t val[1];
             val[0] = (uint32_t)got[u];
             if ((uint32_t)(got[u] >> 32) != seq && !ll_wait<1>(buf + e, seq, val, a.wait_ticks)) sh.ctrl[2] = 1;
-            reinterpret_cast<uint32_t*>(&sh.rel[0][0])[e] = val[0];
+            reinterpret_cast<uint32_t*>(&sh.rel[e / kRelWords][0])[e % kRelWords] = val[0];
         }
     }
 }
