@@ -235,6 +235,36 @@ def test_recording_with_sixteen_points_per_thread(fp):
         assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
 
 
+@pytest.mark.parametrize("G", [65, 100, 130, 192, 200])
+def test_clouds_over_two_to_four_waves_of_workgroup_counts(fp, G):
+    """The candidate exchange adds up the workgroups' counts in as many waves as hold them (64 counts
+    each): workgroup counts that need two, three and four of them, every sampler, a few hundred
+    points per workgroup so that most rounds take candidates from many workgroups."""
+    N, n = 48000, 1500
+    say("exchange over", G, "workgroups")
+    cloud = inputs.uniform_cube(900 + G, N)
+    x = dev(cloud[None])
+    prm = dict(exponent=0.8, bias=1.04)
+    fp.set_wg_per_cloud(G)
+    try:
+        assert fp.plan(1, N)[0] == G
+        idx = fp.fps_exact(x, n)
+        pidx = fp.fps_exact_pruned(x, n)
+        midx = fp.mdps_sample(x, n, fp.MdpsParams(**prm))
+        mpidx = fp.mdps_sample_pruned(x, n, fp.MdpsParams(**prm))
+        m1idx = fp.mdps_sample(x, n, fp.MdpsParams(scan_order=1, **prm))
+        mp1idx = fp.mdps_sample_pruned(x, n, fp.MdpsParams(scan_order=1, **prm))
+        torch.cuda.synchronize()
+    finally:
+        fp.set_wg_per_cloud(0)
+    want = ref.fps_exact(cloud, n)[0]
+    assert np.array_equal(idx.cpu().numpy()[0], want) and np.array_equal(pidx.cpu().numpy()[0], want)
+    want = ref.mdps_sample(cloud, n, ref.MdpsParams(**prm))[0]
+    assert np.array_equal(midx.cpu().numpy()[0], want) and np.array_equal(mpidx.cpu().numpy()[0], want)
+    want = ref.mdps_sample(cloud, n, ref.MdpsParams(scan_order=1, **prm))[0]
+    assert np.array_equal(m1idx.cpu().numpy()[0], want) and np.array_equal(mp1idx.cpu().numpy()[0], want)
+
+
 def test_plain_fp32_rate_probe(fp):
     """The measurement aid runs and lands near 256 compute units x 64 lanes x the clock."""
     rate = fp.probe_fp32_rate(torch.device("cuda:0"), blocks=4096, iterations=2048)
