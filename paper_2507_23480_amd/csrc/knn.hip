@@ -119,20 +119,44 @@ struct Nearest {
 
 // one sample against the two points of a thread; `s` comes from a wave-uniform LDS address
 // (a broadcast read)
-template <int K>
+template <int K, bool EARLY>
 __device__ __forceinline__ void visit_sample(Nearest<K> (&nb)[2], const float (&px)[2], const float (&py)[2],
                                              const float (&pz)[2], const float4 s, int q)
 {
-    const float d0 = dist2(px[0], py[0], pz[0], s.x, s.y, s.z);
-    const float d1 = dist2(px[1], py[1], pz[1], s.x, s.y, s.z);
-    // after the first few samples a wave rarely has a lane whose list changes
+    if constexpr (!EARLY) {
+        // the first samples: most of them enter some lane's list
+        const float d0 = dist2(px[0], py[0], pz[0], s.x, s.y, s.z);
+        const float d1 = dist2(px[1], py[1], pz[1], s.x, s.y, s.z);
+        if (__builtin_amdgcn_ballot_w64(d0 < nb[0].d[K - 1] || d1 < nb[1].d[K - 1]) != 0) {
+            nb[0].insert(d0, q);
+            nb[1].insert(d1, q);
+        }
+        return;
+    }
+    // After the first samples a wave rarely has a lane whose list changes, and that is mostly known
+    // after two of dist2's three terms: its sum (dx dx + dy dy) + dz dz only grows term by term (every
+    // term is >= 0, rounding is monotone), so a sample whose first two terms already reach the K-th
+    // distance kept by every lane cannot enter a list.  The third term is added in dist2's order, so
+    // a distance that is formed has the same bits.
+    const float ax = px[0] - s.x, ay = py[0] - s.y;
+    const float bx = px[1] - s.x, by = py[1] - s.y;
+    float d0 = ax * ax;
+    d0 = d0 + ay * ay;
+    float d1 = bx * bx;
+    d1 = d1 + by * by;
     if (__builtin_amdgcn_ballot_w64(d0 < nb[0].d[K - 1] || d1 < nb[1].d[K - 1]) != 0) {
-        nb[0].insert(d0, q);
-        nb[1].insert(d1, q);
+        const float az = pz[0] - s.z, bz = pz[1] - s.z;
+        d0 = d0 + az * az;
+        d1 = d1 + bz * bz;
+        if (__builtin_amdgcn_ballot_w64(d0 < nb[0].d[K - 1] || d1 < nb[1].d[K - 1]) != 0) {
+            nb[0].insert(d0, q);
+            nb[1].insert(d1, q);
+        }
     }
 }
 
 constexpr int kTile = 256;          // samples staged in LDS per pass
+constexpr int kFullTests = 1024;    // samples at the head of the list whose distances are formed in full at once
 constexpr int kPointsPerWg = 512;   // two points per thread
 constexpr int kWaveListMax = 4096;  // deferred points per cloud up to which each gets a whole wave
 
@@ -198,12 +222,20 @@ __global__ __launch_bounds__(256) void knn_brute_kernel(const float* __restrict_
         }
         __syncthreads();
         const int cnt = n - q0 < kTile ? n - q0 : kTile;
-        if (cnt == kTile) {
+        if (q0 < kFullTests) {                          // (uniform)
+            if (cnt == kTile) {
 #pragma unroll 4
-            for (int t = 0; t < kTile; ++t) visit_sample<K>(nb, px, py, pz, smp[t], q0 + t);
+                for (int t = 0; t < kTile; ++t) visit_sample<K, false>(nb, px, py, pz, smp[t], q0 + t);
+            } else {
+#pragma unroll 1
+                for (int t = 0; t < cnt; ++t) visit_sample<K, false>(nb, px, py, pz, smp[t], q0 + t);
+            }
+        } else if (cnt == kTile) {
+#pragma unroll 4
+            for (int t = 0; t < kTile; ++t) visit_sample<K, true>(nb, px, py, pz, smp[t], q0 + t);
         } else {
 #pragma unroll 1
-            for (int t = 0; t < cnt; ++t) visit_sample<K>(nb, px, py, pz, smp[t], q0 + t);
+            for (int t = 0; t < cnt; ++t) visit_sample<K, true>(nb, px, py, pz, smp[t], q0 + t);
         }
     }
 #pragma unroll
