@@ -57,13 +57,13 @@ GRAPH = "four streams, step replayed as one HIP graph"
 # bench_C2_hbm_traffic.md), keyed by workload and kernel.  None where no counter run is recorded.  The
 # samplers keep the cloud in registers: what they move beyond reading it once is the polling of the
 # words exchanged between the workgroups of a cloud.
-TRAFFIC_BYTES = {"C2": {"fps_exact": 427966, "mdps_sample+record": 2364745, "ball_query_cached": 1948913,
-                        "ball_query_brute": 2004581},
+TRAFFIC_BYTES = {"C2": {"fps_exact": 427967, "mdps_sample+record": 2364746, "ball_query_cached": 1948914,
+                        "ball_query_brute": 2004582},
                  # (C4, C5: the step's recorder is the cell-ordered one, its reader the one for cell-ordered records)
-                 "C4": {"fps_exact": 91711130, "mdps_sample+record": 236154909, "ball_query_cached": 59638959,
-                        "ball_query_brute": 90647909},
-                 "C5": {"fps_exact": 168607343, "mdps_sample+record": 232584251, "ball_query_cached": 29243809,
-                        "ball_query_brute": 204121217}}
+                 "C4": {"fps_exact": 91435788, "mdps_sample+record": 235871565, "ball_query_cached": 59670967,
+                        "ball_query_brute": 90643229},
+                 "C5": {"fps_exact": 167284349, "mdps_sample+record": 230724683, "ball_query_cached": 29243835,
+                        "ball_query_brute": 204117378}}
 
 
 PRUNED_RECORD_FROM = 1 << 14
